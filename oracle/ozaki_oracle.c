@@ -1,0 +1,321 @@
+/*
+ * CPU oracle for the Ozaki-scheme DGEMM on an INT8 -> INT32 integer matrix unit.
+ *
+ * THIS IS TEST INFRASTRUCTURE. It is a plain, slow, step-by-step restatement of the
+ * method ("Matrix multiplication by the Ozaki scheme on IMMU" and its "SplitInt"
+ * splitting algorithm, Section 3.1 of the paper) that exists only so that the GPU
+ * library can be checked against it. Nothing in the product path may call it, and it
+ * shares no code, header, table or helper with the HIP kernels.
+ *
+ * Conventions (each function cites the passage it follows):
+ *   - matrices are row-major doubles with a leading dimension;
+ *   - W = 7 magnitude bits per slice (Table 2, INT8-INT32: l_in = 7; Eq. (5) BPS);
+ *   - slices are stored as M = A or B^T ("SplitInt" header), i.e. both operands are
+ *     "rows of length k": SA[p][i][l] and SB[q][j][l], slice index first, 0-based in
+ *     memory (slice p of the paper is index p-1);
+ *   - exponents are plain integers E with e = 2^E (the paper's exponent offset vector).
+ *
+ * No blocking, no fusion, no reordering beyond what is stated in each comment.
+ * Compile with -ffp-contract=off (no fused multiply-add may be formed by the compiler;
+ * the only FMA used is the explicit fma() of the double-double reference).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define OZ_W 7 /* magnitude bits kept per INT8 slice */
+
+int oz_oracle_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ---------------------------------------------------------------------------------
+ * Closed forms of Section 3.2.
+ * ------------------------------------------------------------------------------- */
+
+/* Eq. (4): alpha = floor((l_acc - log2 k) / 2). */
+int oz_alpha(int l_acc, double k) { return (int)floor(((double)l_acc - log2(k)) / 2.0); }
+
+/* Eq. (5): BPS = min(alpha, l_in). */
+int oz_bps(int l_in, int l_acc, double k) {
+    int a = oz_alpha(l_acc, k);
+    return a < l_in ? a : l_in;
+}
+
+/* Number of slice products kept: the pairs with i + j <= s + 1, (s + 1) s / 2 of them
+ * (Section 3.2.4, and the double loop of the IMMU algorithm). Counted, not computed
+ * from the formula, so that the formula can be tested against it. */
+int oz_num_pairs(int s) {
+    int c = 0;
+    for (int i = 1; i <= s; ++i)
+        for (int j = 1; j <= s - i + 1; ++j) ++c;
+    return c;
+}
+
+/* ---------------------------------------------------------------------------------
+ * SplitInt, line 2: one exponent per row of M.
+ *
+ * The paper takes the smallest power of two not below the row maximum. Reading used
+ * here: E is the frexp exponent of mu = max_l |M_il|, i.e. mu = f * 2^E with
+ * 0.5 <= f < 1, so |x| * 2^-E < 1 for every element of the row (at an exact power of
+ * two this is one more than the ceiling of log2, which keeps the first chunk below
+ * 128). A zero row gets E = 0.
+ * ------------------------------------------------------------------------------- */
+static int row_exponent(const double *row, int64_t len, int64_t stride) {
+    double mu = 0.0;
+    for (int64_t l = 0; l < len; ++l) {
+        double a = fabs(row[l * stride]);
+        if (a > mu) mu = a;
+    }
+    if (mu == 0.0) return 0;
+    int E;
+    (void)frexp(mu, &E);
+    return E;
+}
+
+/* SplitInt, lines 3-5, for one element: the magnitude r = |x| 2^-E in [0,1) is cut
+ * into consecutive 7-bit chunks below the row's leading place (truncation: the chunk
+ * is floor of the shifted remainder), and each chunk carries the sign of x. */
+static void split_element(double x, int E, int s, int8_t *out, int64_t slice_stride) {
+    double r = ldexp(fabs(x), -E);
+    int neg = signbit(x) != 0;
+    for (int p = 0; p < s; ++p) {
+        r = r * 128.0;         /* exact: power-of-two scaling, r stays below 128 */
+        double q = floor(r);   /* 0 .. 127 */
+        r = r - q;             /* exact: only leading bits are removed */
+        int v = (int)q;
+        out[(int64_t)p * slice_stride] = (int8_t)(neg ? -v : v);
+    }
+}
+
+/* Split the rows of A (m x k, row-major, lda): exponents EA[m], slices SA[s][m][k]. */
+void oz_split_rows(int64_t m, int64_t k, const double *A, int64_t lda, int s, int32_t *EA,
+                   int8_t *SA) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i) {
+        int E = row_exponent(A + i * lda, k, 1);
+        EA[i] = E;
+        for (int64_t l = 0; l < k; ++l)
+            split_element(A[i * lda + l], E, s, SA + i * k + l, m * k);
+    }
+}
+
+/* Split the columns of B (k x n, row-major, ldb), i.e. the rows of M = B^T:
+ * exponents EB[n], slices SB[s][n][k] (column j of B becomes row j of the slice). */
+void oz_split_cols(int64_t k, int64_t n, const double *B, int64_t ldb, int s, int32_t *EB,
+                   int8_t *SB) {
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n; ++j) {
+        int E = row_exponent(B + j, k, ldb);
+        EB[j] = E;
+        for (int64_t l = 0; l < k; ++l)
+            split_element(B[l * ldb + j], E, s, SB + j * k + l, n * k);
+    }
+}
+
+/* ---------------------------------------------------------------------------------
+ * Line 6 of the IMMU algorithm: C_tmp = A^(p) . B^(q), exactly, for one pair and for
+ * the k-range [k0, k0 + klen). P is m x n INT64, row-major, ld = n.
+ * This is the definition (a triple loop); INT64 cannot overflow for any admissible k.
+ * ------------------------------------------------------------------------------- */
+void oz_pair_product(int64_t m, int64_t n, int64_t k, const int8_t *SAp, const int8_t *SBq,
+                     int64_t k0, int64_t klen, int64_t *P) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            int64_t acc = 0;
+            const int8_t *a = SAp + i * k + k0;
+            const int8_t *b = SBq + j * k + k0;
+            for (int64_t l = 0; l < klen; ++l) acc += (int64_t)a[l] * (int64_t)b[l];
+            P[i * n + j] = acc;
+        }
+}
+
+/* Sum of the products of one anti-diagonal d = p + q (2 <= d <= s + 1), in INT64:
+ * S_d = sum_{p=1}^{d-1} A^(p) . B^(d-p). All pairs of a diagonal share the scale
+ * 2^(-7 d) of line 7, and integer addition is exact, so summing them before the
+ * conversion to FP64 changes no mathematics. S is [s][m][n], S[d-2] = S_d. */
+void oz_diagonal_sums(int64_t m, int64_t n, int64_t k, int s, const int8_t *SA,
+                      const int8_t *SB, int64_t *S) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t j = 0; j < n; ++j)
+            for (int d = 2; d <= s + 1; ++d) {
+                int64_t acc = 0;
+                for (int p = 1; p <= d - 1; ++p) {
+                    int q = d - p;
+                    const int8_t *a = SA + ((int64_t)(p - 1) * m + i) * k;
+                    const int8_t *b = SB + ((int64_t)(q - 1) * n + j) * k;
+                    for (int64_t l = 0; l < k; ++l) acc += (int64_t)a[l] * (int64_t)b[l];
+                }
+                S[((int64_t)(d - 2) * m + i) * n + j] = acc;
+            }
+}
+
+/* ---------------------------------------------------------------------------------
+ * Line 7 of the IMMU algorithm: C = sum over the kept products of
+ * C_tmp (.) 2^(-(i+j) W) e_A e_B^T, in FP64.
+ *
+ * Fixed order used as the definition of the result: the per-diagonal integer sums
+ * are converted (exactly: |S_d| < 2^53) and added least significant diagonal first,
+ *     acc = 0;  for d = s+1 down to 2:  acc = RN(acc + S_d * 2^(-7 d))
+ * and the row/column scale 2^(EA_i + EB_j) is applied once at the end by ldexp
+ * (identical to scaling every term unless the result leaves the normal range).
+ * ------------------------------------------------------------------------------- */
+void oz_accumulate(int64_t m, int64_t n, int s, const int64_t *S, const int32_t *EA,
+                   const int32_t *EB, double *C, int64_t ldc) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            double acc = 0.0;
+            for (int d = s + 1; d >= 2; --d) {
+                double t = ldexp((double)S[((int64_t)(d - 2) * m + i) * n + j], -OZ_W * d);
+                acc = acc + t;
+            }
+            C[i * ldc + j] = ldexp(acc, EA[i] + EB[j]);
+        }
+}
+
+/* The whole method: split A, split B, integer products, FP64 sum. Returns 0, or 1
+ * when memory for the slices could not be obtained. */
+int oz_dgemm(int64_t m, int64_t n, int64_t k, const double *A, int64_t lda, const double *B,
+             int64_t ldb, double *C, int64_t ldc, int s) {
+    if (m == 0 || n == 0) return 0;
+    int32_t *EA = malloc(sizeof(int32_t) * (size_t)m);
+    int32_t *EB = malloc(sizeof(int32_t) * (size_t)n);
+    int8_t *SA = malloc((size_t)s * (size_t)m * (size_t)(k ? k : 1));
+    int8_t *SB = malloc((size_t)s * (size_t)n * (size_t)(k ? k : 1));
+    int64_t *S = malloc(sizeof(int64_t) * (size_t)s * (size_t)m * (size_t)n);
+    int rc = 1;
+    if (EA && EB && SA && SB && S) {
+        oz_split_rows(m, k, A, lda, s, EA, SA);
+        oz_split_cols(k, n, B, ldb, s, EB, SB);
+        oz_diagonal_sums(m, n, k, s, SA, SB, S);
+        oz_accumulate(m, n, s, S, EA, EB, C, ldc);
+        rc = 0;
+    }
+    free(EA); free(EB); free(SA); free(SB); free(S);
+    return rc;
+}
+
+/* Cross-check only: the literal loop order of the IMMU algorithm (i outer, j inner,
+ * one FP64 update of C per pair, every term scaled by 2^(-(i+j) W) e_A e_B^T).
+ * It differs from oz_dgemm only in the order and number of FP64 roundings. */
+int oz_dgemm_pairwise_order(int64_t m, int64_t n, int64_t k, const double *A, int64_t lda,
+                            const double *B, int64_t ldb, double *C, int64_t ldc, int s) {
+    if (m == 0 || n == 0) return 0;
+    int32_t *EA = malloc(sizeof(int32_t) * (size_t)m);
+    int32_t *EB = malloc(sizeof(int32_t) * (size_t)n);
+    int8_t *SA = malloc((size_t)s * (size_t)m * (size_t)(k ? k : 1));
+    int8_t *SB = malloc((size_t)s * (size_t)n * (size_t)(k ? k : 1));
+    int64_t *P = malloc(sizeof(int64_t) * (size_t)m * (size_t)n);
+    int rc = 1;
+    if (EA && EB && SA && SB && P) {
+        oz_split_rows(m, k, A, lda, s, EA, SA);
+        oz_split_cols(k, n, B, ldb, s, EB, SB);
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t j = 0; j < n; ++j) C[i * ldc + j] = 0.0;
+        for (int i = 1; i <= s; ++i)
+            for (int j = 1; j <= s - i + 1; ++j) {
+                oz_pair_product(m, n, k, SA + (int64_t)(i - 1) * m * k,
+                                SB + (int64_t)(j - 1) * n * k, 0, k, P);
+                for (int64_t r = 0; r < m; ++r)
+                    for (int64_t c = 0; c < n; ++c) {
+                        double t = ldexp((double)P[r * n + c], -OZ_W * (i + j) + EA[r] + EB[c]);
+                        C[r * ldc + c] = C[r * ldc + c] + t;
+                    }
+            }
+        rc = 0;
+    }
+    free(EA); free(EB); free(SA); free(SB); free(P);
+    return rc;
+}
+
+/* ---------------------------------------------------------------------------------
+ * Complex product by separating real and imaginary parts during the split
+ * (Section 4.4, first extension). A, B, C hold interleaved (re, im) doubles; ld counts
+ * complex elements. Four real Ozaki products G(X, Y), each plane split with its own
+ * exponents:  Cr = RN(G(Ar,Br) - G(Ai,Bi)),  Ci = RN(G(Ar,Bi) + G(Ai,Br)).
+ * ------------------------------------------------------------------------------- */
+int oz_zgemm(int64_t m, int64_t n, int64_t k, const double *A, int64_t lda, const double *B,
+             int64_t ldb, double *C, int64_t ldc, int s) {
+    if (m == 0 || n == 0) return 0;
+    size_t ak = (size_t)m * (size_t)(k ? k : 1), bk = (size_t)(k ? k : 1) * (size_t)n;
+    double *Ar = malloc(sizeof(double) * ak), *Ai = malloc(sizeof(double) * ak);
+    double *Br = malloc(sizeof(double) * bk), *Bi = malloc(sizeof(double) * bk);
+    double *G[4];
+    for (int t = 0; t < 4; ++t) G[t] = malloc(sizeof(double) * (size_t)m * (size_t)n);
+    int rc = 1;
+    if (Ar && Ai && Br && Bi && G[0] && G[1] && G[2] && G[3]) {
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t l = 0; l < k; ++l) {
+                Ar[i * k + l] = A[2 * (i * lda + l)];
+                Ai[i * k + l] = A[2 * (i * lda + l) + 1];
+            }
+        for (int64_t l = 0; l < k; ++l)
+            for (int64_t j = 0; j < n; ++j) {
+                Br[l * n + j] = B[2 * (l * ldb + j)];
+                Bi[l * n + j] = B[2 * (l * ldb + j) + 1];
+            }
+        rc = oz_dgemm(m, n, k, Ar, k, Br, n, G[0], n, s) |
+             oz_dgemm(m, n, k, Ai, k, Bi, n, G[1], n, s) |
+             oz_dgemm(m, n, k, Ar, k, Bi, n, G[2], n, s) |
+             oz_dgemm(m, n, k, Ai, k, Br, n, G[3], n, s);
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t j = 0; j < n; ++j) {
+                C[2 * (i * ldc + j)] = G[0][i * n + j] - G[1][i * n + j];
+                C[2 * (i * ldc + j) + 1] = G[2][i * n + j] + G[3][i * n + j];
+            }
+    }
+    free(Ar); free(Ai); free(Br); free(Bi);
+    for (int t = 0; t < 4; ++t) free(G[t]);
+    return rc;
+}
+
+/* ---------------------------------------------------------------------------------
+ * Reference the accuracy is measured against (Section 4.2, Eq. (7)): the product in
+ * double-double arithmetic. Each a*b is taken exactly as (p, e) with an explicit fma
+ * (TwoProd), added into the (hi, lo) pair with Knuth's TwoSum, and renormalised.
+ * Outputs hi and lo with hi + lo the double-double value. Also |A||B| in FP64.
+ * ------------------------------------------------------------------------------- */
+void oz_dd_gemm(int64_t m, int64_t n, int64_t k, const double *A, int64_t lda, const double *B,
+                int64_t ldb, double *Chi, double *Clo) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            double hi = 0.0, lo = 0.0;
+            for (int64_t l = 0; l < k; ++l) {
+                double a = A[i * lda + l], b = B[l * ldb + j];
+                double p = a * b;
+                double e = fma(a, b, -p);      /* a*b = p + e exactly */
+                double sum = hi + p;           /* TwoSum(hi, p) */
+                double bb = sum - hi;
+                double err = (hi - (sum - bb)) + (p - bb);
+                lo = lo + (err + e);
+                hi = sum + lo;                 /* FastTwoSum(sum, lo) */
+                lo = lo - (hi - sum);
+            }
+            Chi[i * n + j] = hi;
+            Clo[i * n + j] = lo;
+        }
+}
+
+void oz_abs_gemm(int64_t m, int64_t n, int64_t k, const double *A, int64_t lda, const double *B,
+                 int64_t ldb, double *G) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            double acc = 0.0;
+            for (int64_t l = 0; l < k; ++l) acc = acc + fabs(A[i * lda + l]) * fabs(B[l * ldb + j]);
+            G[i * n + j] = acc;
+        }
+}
