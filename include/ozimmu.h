@@ -1,0 +1,136 @@
+/*
+ * ozimmu -- FP64 matrix product by the Ozaki scheme on the INT8 -> INT32 matrix cores of
+ * one MI355X (gfx950). C ABI: plain pointers and sizes, no framework types.
+ *
+ * What is computed (Section 3.1 of the paper, "Matrix multiplication by the Ozaki scheme
+ * on IMMU" and "SplitInt"):
+ *   1. every row of A and every column of B gets one power-of-two exponent, and its
+ *      elements are cut into num_slices signed 7-bit chunks below that exponent;
+ *   2. the slice pairs (p, q) with p + q <= num_slices + 1 are multiplied as INT8 matrices
+ *      with exact INT32 accumulation (blocked so that no INT32 sum can overflow);
+ *   3. the integer products are scaled by 2^(-7 (p + q)) e_A e_B^T and summed in FP64.
+ * Order of the FP64 sum (fixed, part of the contract): the products of one anti-diagonal
+ * d = p + q are first added as integers (exact), then
+ *     acc = 0;  for d = num_slices + 1 down to 2:  acc = RN(acc + S_d 2^(-7 d));
+ *     C_ij = acc * 2^(EA_i + EB_j)      (one ldexp).
+ *
+ * General rules for every entry point
+ *   - All matrix pointers are DEVICE pointers owned by the caller; all matrices are
+ *     row-major; leading dimensions count elements (complex: complex elements).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). All work is
+ *     enqueued on it; no entry point synchronises, allocates or frees device memory, or
+ *     keeps state between calls. Calls that share a workspace must be stream-ordered.
+ *   - Arguments are validated on the host before anything is launched; on an argument
+ *     error nothing is enqueued and outputs are untouched.
+ *   - Inputs must be finite; the result for NaN/Inf inputs is unspecified. -0.0 is zero.
+ *   - Return value: OZIMMU_OK or an error code; ozimmu_status_string() names it.
+ */
+#ifndef OZIMMU_H
+#define OZIMMU_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    OZIMMU_OK = 0,
+    OZIMMU_ERR_BAD_DIM = 1,        /* negative size, or a k-range that breaks the block rules */
+    OZIMMU_ERR_BAD_LD = 2,         /* leading dimension smaller than the row length */
+    OZIMMU_ERR_BAD_SLICES = 3,     /* num_slices outside [1, OZIMMU_MAX_SLICES], or bad (p, q) */
+    OZIMMU_ERR_NULL = 4,           /* null pointer where data is required */
+    OZIMMU_ERR_WORKSPACE = 5,      /* workspace null, misaligned or too small */
+    OZIMMU_ERR_HIP = 6,            /* a HIP call or kernel launch failed */
+    OZIMMU_ERR_NOT_IMPLEMENTED = 7
+} ozimmu_status_t;
+
+#define OZIMMU_MAX_SLICES 16
+#define OZIMMU_SLICE_BITS 7          /* Table 2: INT8-INT32 keeps 7 magnitude bits per slice */
+#define OZIMMU_ROW_ALIGN 256         /* slice rows are padded to a multiple of this */
+#define OZIMMU_K_ALIGN 128           /* slice row length is padded to a multiple of this */
+#define OZIMMU_INT32_BLOCK 131072    /* at most 2^17 INT8 products go into one INT32 sum:
+                                        2^17 * 127^2 < 2^31 (the exact limit is 133144) */
+#define OZIMMU_WORKSPACE_ALIGN 256
+
+const char* ozimmu_status_string(ozimmu_status_t status);
+
+/*
+ * Padded slice geometry. A slice tensor for `rows` rows of length k is stored as
+ *     int8 slices[num_slices][rows_padded][k_padded]      (k contiguous)
+ * with rows_padded = roundup(rows, OZIMMU_ROW_ALIGN), k_padded = roundup(k, OZIMMU_K_ALIGN),
+ * zero-filled outside [0,rows) x [0,k). Both A (rows = m) and B^T (rows = n) use it, so that
+ * both operands of a slice product are "rows of length k" (SplitInt header: M = A or B^T).
+ */
+ozimmu_status_t ozimmu_slice_geometry(int64_t rows, int64_t k, int64_t* rows_padded,
+                                      int64_t* k_padded);
+
+/*
+ * SplitInt on the rows of A (m x k, lda >= k).
+ *   exps   [out] int32[m]: EA_i with 2^(EA_i - 1) <= max_l |A_il| < 2^(EA_i); 0 for a zero row.
+ *   slices [out] padded slice tensor (see above), slices[p-1][i][l] = sign(A_il) * chunk p
+ *                of |A_il| 2^(-EA_i), each chunk in [0, 127] (truncation, no rounding).
+ * split_cols does the same for the columns of B (k x n, ldb >= n), i.e. for M = B^T:
+ * exps int32[n], slices[q-1][j][l] from B_lj. `col_scratch` is device memory of at least
+ * 8 * n bytes (column maxima), 8-byte aligned.
+ */
+ozimmu_status_t ozimmu_split_rows(int64_t m, int64_t k, const double* A, int64_t lda,
+                                  int num_slices, int8_t* slices, int32_t* exps, void* stream);
+ozimmu_status_t ozimmu_split_cols(int64_t k, int64_t n, const double* B, int64_t ldb,
+                                  int num_slices, int8_t* slices, int32_t* exps,
+                                  void* col_scratch, void* stream);
+
+/*
+ * One slice product on the matrix cores (line 6 of the IMMU algorithm), exposed so that
+ * the raw INT32 accumulators can be checked:
+ *     P[i][j] = sum_{l = k0}^{k0 + klen - 1} SA[p-1][i][l] * SB[q-1][j][l]     (INT32, exact)
+ * SA, SB: padded slice tensors for m and n rows of length k holding at least p resp. q
+ * slices. P: int32, m x n, row-major, ldp >= n. Rules: 1 <= p, q <= OZIMMU_MAX_SLICES;
+ * k0 a multiple of OZIMMU_K_ALIGN; klen <= OZIMMU_INT32_BLOCK; klen a multiple of
+ * OZIMMU_K_ALIGN unless k0 + klen == k. klen == 0 gives P = 0.
+ */
+ozimmu_status_t ozimmu_slice_gemm(int64_t m, int64_t n, int64_t k, const int8_t* SA,
+                                  const int8_t* SB, int p, int q, int64_t k0, int64_t klen,
+                                  int32_t* P, int64_t ldp, void* stream);
+
+/*
+ * Workspace size for ozimmu_dgemm / ozimmu_zgemm (slices of A and B, exponents, and the
+ * per-diagonal integer sums that do not stay in registers).
+ */
+ozimmu_status_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_slices,
+                                       int is_complex, size_t* bytes);
+
+/*
+ * C = A . B (overwrite; the paper's problem statement has no alpha, beta or transposes).
+ *   A: m x k, lda >= k.  B: k x n, ldb >= n.  C: m x n, ldc >= n, must not alias A or B.
+ *   workspace: device memory, OZIMMU_WORKSPACE_ALIGN-aligned, at least
+ *   ozimmu_workspace_bytes(...) bytes; contents are scratch.
+ * m == 0 or n == 0: nothing to do. k == 0: C is set to +0.0.
+ * ozimmu_zgemm: A, B, C hold interleaved (re, im) doubles (Section 4.4: the real and
+ * imaginary parts are separated while splitting; four real products, each plane with its own
+ * exponents; Cr = RN(G(Ar,Br) - G(Ai,Bi)), Ci = RN(G(Ar,Bi) + G(Ai,Br))).
+ */
+ozimmu_status_t ozimmu_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                             const double* B, int64_t ldb, double* C, int64_t ldc,
+                             int num_slices, void* workspace, size_t workspace_bytes,
+                             void* stream);
+ozimmu_status_t ozimmu_zgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                             const double* B, int64_t ldb, double* C, int64_t ldc,
+                             int num_slices, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/*
+ * The stages of ozimmu_dgemm run one at a time, for per-stage timing and profiling
+ * (the time breakdown of Section 4.3): stage 0 = split A, 1 = split B, 2 = slice products
+ * with the fused FP64 sum. Stages must be run in order with the same arguments.
+ */
+ozimmu_status_t ozimmu_dgemm_stage(int stage, int64_t m, int64_t n, int64_t k, const double* A,
+                                   int64_t lda, const double* B, int64_t ldb, double* C,
+                                   int64_t ldc, int num_slices, void* workspace,
+                                   size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OZIMMU_H */

@@ -1,0 +1,270 @@
+// C ABI of libozimmu: argument validation, workspace carving and kernel sequencing.
+// Everything that computes is in split.hip and gemm.hip.
+#include <cstdint>
+#include <cstring>
+
+#include "ozimmu_internal.h"
+
+using namespace ozimmu;
+
+namespace {
+
+constexpr int64_t kMaxDim = (int64_t)1 << 24;  // tile counts and byte offsets inside a tile row stay in 32 bits
+
+inline size_t align_up(size_t x) { return (x + OZIMMU_WORKSPACE_ALIGN - 1) / OZIMMU_WORKSPACE_ALIGN * OZIMMU_WORKSPACE_ALIGN; }
+
+bool dims_ok(int64_t a, int64_t b, int64_t c) {
+    return a >= 0 && b >= 0 && c >= 0 && a <= kMaxDim && b <= kMaxDim && c <= kMaxDim;
+}
+
+// A diagonal d = p + q holds d - 1 pairs; the longest one (d = s + 1) sums s * k_pad products
+// per output element. If that exceeds the INT32 block the kernel keeps INT64 sums (k-blocking).
+bool needs_wide(int s, int64_t k_pad) { return (int64_t)s * k_pad > OZIMMU_INT32_BLOCK; }
+
+struct Layout {
+    int64_t m_pad, n_pad, k_pad;
+    int tiles_m, tiles_n;
+    bool wide;
+    size_t sa_bytes, sb_bytes;      // one plane
+    size_t off_sa[2], off_sb[2];    // planes (real GEMM uses plane 0)
+    size_t off_ea[2], off_eb[2];
+    size_t off_colmax, off_d;
+    size_t total;
+};
+
+Layout make_layout(int64_t m, int64_t n, int64_t k, int s, bool cplx) {
+    Layout L{};
+    L.m_pad = round_up(m, kTile);
+    L.n_pad = round_up(n, kTile);
+    L.k_pad = round_up(k, kChunk);
+    L.tiles_m = (int)(L.m_pad / kTile);
+    L.tiles_n = (int)(L.n_pad / kTile);
+    L.wide = needs_wide(s, L.k_pad);
+    L.sa_bytes = (size_t)s * L.m_pad * L.k_pad;
+    L.sb_bytes = (size_t)s * L.n_pad * L.k_pad;
+    const int planes = cplx ? 2 : 1;
+    size_t off = 0;
+    for (int p = 0; p < planes; ++p) { L.off_sa[p] = off; off = align_up(off + L.sa_bytes); }
+    for (int p = 0; p < planes; ++p) { L.off_sb[p] = off; off = align_up(off + L.sb_bytes); }
+    for (int p = 0; p < planes; ++p) { L.off_ea[p] = off; off = align_up(off + sizeof(int32_t) * L.m_pad); }
+    for (int p = 0; p < planes; ++p) { L.off_eb[p] = off; off = align_up(off + sizeof(int32_t) * L.n_pad); }
+    L.off_colmax = off;
+    off = align_up(off + sizeof(unsigned long long) * L.n_pad);
+    L.off_d = off;
+    off = align_up(off + (size_t)s * L.tiles_m * L.tiles_n * kTileElems * (L.wide ? 8 : 4));
+    L.total = off;
+    return L;
+}
+
+ozimmu_status_t hip_status(hipError_t e) { return e == hipSuccess ? OZIMMU_OK : OZIMMU_ERR_HIP; }
+
+ozimmu_status_t check_gemm_args(int64_t m, int64_t n, int64_t k, const void* A, int64_t lda, const void* B,
+                                int64_t ldb, const void* C, int64_t ldc, int s, const void* ws, size_t ws_bytes,
+                                bool cplx, Layout* L) {
+    if (!dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
+    if (s < 1 || s > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
+    if (m == 0 || n == 0) return OZIMMU_OK;
+    if (lda < k || ldb < n || ldc < n) return OZIMMU_ERR_BAD_LD;
+    if (!C || (k > 0 && (!A || !B))) return OZIMMU_ERR_NULL;
+    *L = make_layout(m, n, k, s, cplx);
+    if (k > 0) {
+        if (!ws || (reinterpret_cast<uintptr_t>(ws) % OZIMMU_WORKSPACE_ALIGN) != 0 || ws_bytes < L->total)
+            return OZIMMU_ERR_WORKSPACE;
+    }
+    return OZIMMU_OK;
+}
+
+// One real Ozaki product from already split operands: G = sum over diagonals, written to C with
+// the given column stride and combine mode.
+hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned char* ws, int plane_a, int plane_b,
+                       double* C, int64_t ldc, int c_inc, int c_mode, hipStream_t st) {
+    GemmArgs g{};
+    g.SA = reinterpret_cast<const int8_t*>(ws + L.off_sa[plane_a]);
+    g.SB = reinterpret_cast<const int8_t*>(ws + L.off_sb[plane_b]);
+    g.a_slice_stride = L.m_pad * L.k_pad;
+    g.b_slice_stride = L.n_pad * L.k_pad;
+    g.k_pad = (int)L.k_pad;
+    g.tiles_m = L.tiles_m;
+    g.tiles_n = L.tiles_n;
+    g.m = (int)m;
+    g.n = (int)n;
+    g.num_slices = s;
+    g.pair_p = g.pair_q = 0;
+    g.kc_begin = 0;
+    g.kc_end = (int)(L.k_pad / kChunk);
+    g.D = ws + L.off_d;
+    g.P = nullptr;
+    g.ldp = 0;
+    g.C = C;
+    g.ldc = ldc;
+    g.c_inc = c_inc;
+    g.c_mode = c_mode;
+    g.EA = reinterpret_cast<const int32_t*>(ws + L.off_ea[plane_a]);
+    g.EB = reinterpret_cast<const int32_t*>(ws + L.off_eb[plane_b]);
+    return launch_slice_gemm(g, L.wide, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ozimmu_status_string(ozimmu_status_t status) {
+    switch (status) {
+        case OZIMMU_OK: return "ok";
+        case OZIMMU_ERR_BAD_DIM: return "bad dimension or k-range";
+        case OZIMMU_ERR_BAD_LD: return "leading dimension too small";
+        case OZIMMU_ERR_BAD_SLICES: return "bad slice count or slice index";
+        case OZIMMU_ERR_NULL: return "null pointer";
+        case OZIMMU_ERR_WORKSPACE: return "workspace null, misaligned or too small";
+        case OZIMMU_ERR_HIP: return "HIP error";
+        case OZIMMU_ERR_NOT_IMPLEMENTED: return "not implemented";
+    }
+    return "unknown status";
+}
+
+ozimmu_status_t ozimmu_slice_geometry(int64_t rows, int64_t k, int64_t* rows_padded, int64_t* k_padded) {
+    if (rows < 0 || k < 0 || rows > kMaxDim || k > kMaxDim) return OZIMMU_ERR_BAD_DIM;
+    if (!rows_padded || !k_padded) return OZIMMU_ERR_NULL;
+    *rows_padded = round_up(rows, kTile);
+    *k_padded = round_up(k, kChunk);
+    return OZIMMU_OK;
+}
+
+ozimmu_status_t ozimmu_split_rows(int64_t m, int64_t k, const double* A, int64_t lda, int num_slices,
+                                  int8_t* slices, int32_t* exps, void* stream) {
+    if (!dims_ok(m, k, 0)) return OZIMMU_ERR_BAD_DIM;
+    if (num_slices < 1 || num_slices > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
+    if (m == 0) return OZIMMU_OK;
+    if (lda < k) return OZIMMU_ERR_BAD_LD;
+    if (!exps || (k > 0 && (!A || !slices))) return OZIMMU_ERR_NULL;
+    return hip_status(launch_split_rows(A, lda, 1, m, k, num_slices, slices, round_up(m, kTile),
+                                        round_up(k, kChunk), exps, static_cast<hipStream_t>(stream)));
+}
+
+ozimmu_status_t ozimmu_split_cols(int64_t k, int64_t n, const double* B, int64_t ldb, int num_slices,
+                                  int8_t* slices, int32_t* exps, void* col_scratch, void* stream) {
+    if (!dims_ok(n, k, 0)) return OZIMMU_ERR_BAD_DIM;
+    if (num_slices < 1 || num_slices > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
+    if (n == 0) return OZIMMU_OK;
+    if (ldb < n) return OZIMMU_ERR_BAD_LD;
+    if (!exps || !col_scratch || (k > 0 && (!B || !slices))) return OZIMMU_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(col_scratch) % 8 != 0) return OZIMMU_ERR_WORKSPACE;
+    return hip_status(launch_split_cols(B, ldb, 1, k, n, num_slices, slices, round_up(n, kTile),
+                                        round_up(k, kChunk), exps,
+                                        static_cast<unsigned long long*>(col_scratch),
+                                        static_cast<hipStream_t>(stream)));
+}
+
+ozimmu_status_t ozimmu_slice_gemm(int64_t m, int64_t n, int64_t k, const int8_t* SA, const int8_t* SB, int p,
+                                  int q, int64_t k0, int64_t klen, int32_t* P, int64_t ldp, void* stream) {
+    if (!dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
+    if (p < 1 || q < 1 || p > OZIMMU_MAX_SLICES || q > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
+    if (k0 < 0 || klen < 0 || k0 + klen > k || klen > OZIMMU_INT32_BLOCK || k0 % kChunk != 0)
+        return OZIMMU_ERR_BAD_DIM;
+    if (klen % kChunk != 0 && k0 + klen != k) return OZIMMU_ERR_BAD_DIM;
+    if (m == 0 || n == 0) return OZIMMU_OK;
+    if (ldp < n) return OZIMMU_ERR_BAD_LD;
+    if (!P || (klen > 0 && (!SA || !SB))) return OZIMMU_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (klen == 0) return hip_status(launch_fill_i32(P, ldp, m, n, 0, st));
+    const int64_t m_pad = round_up(m, kTile), n_pad = round_up(n, kTile), k_pad = round_up(k, kChunk);
+    GemmArgs g{};
+    g.SA = SA;
+    g.SB = SB;
+    g.a_slice_stride = m_pad * k_pad;
+    g.b_slice_stride = n_pad * k_pad;
+    g.k_pad = (int)k_pad;
+    g.tiles_m = (int)(m_pad / kTile);
+    g.tiles_n = (int)(n_pad / kTile);
+    g.m = (int)m;
+    g.n = (int)n;
+    g.num_slices = 0;
+    g.pair_p = p;
+    g.pair_q = q;
+    g.kc_begin = (int)(k0 / kChunk);
+    g.kc_end = (int)(round_up(k0 + klen, kChunk) / kChunk);
+    g.P = P;
+    g.ldp = ldp;
+    return hip_status(launch_slice_gemm(g, false, st));
+}
+
+ozimmu_status_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_slices, int is_complex,
+                                       size_t* bytes) {
+    if (!dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
+    if (num_slices < 1 || num_slices > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
+    if (!bytes) return OZIMMU_ERR_NULL;
+    *bytes = make_layout(m, n, k, num_slices, is_complex != 0).total;
+    return OZIMMU_OK;
+}
+
+ozimmu_status_t ozimmu_dgemm_stage(int stage, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                                   const double* B, int64_t ldb, double* C, int64_t ldc, int num_slices,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+    Layout L{};
+    ozimmu_status_t rc = check_gemm_args(m, n, k, A, lda, B, ldb, C, ldc, num_slices, workspace, workspace_bytes,
+                                         false, &L);
+    if (rc != OZIMMU_OK || m == 0 || n == 0) return rc;
+    if (stage < 0 || stage > 2) return OZIMMU_ERR_BAD_DIM;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (k == 0) return stage == 2 ? hip_status(launch_fill_f64(C, ldc, 1, m, n, 0.0, st)) : OZIMMU_OK;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    switch (stage) {
+        case 0:
+            return hip_status(launch_split_rows(A, lda, 1, m, k, num_slices,
+                                                reinterpret_cast<int8_t*>(ws + L.off_sa[0]), L.m_pad, L.k_pad,
+                                                reinterpret_cast<int32_t*>(ws + L.off_ea[0]), st));
+        case 1:
+            return hip_status(launch_split_cols(B, ldb, 1, k, n, num_slices,
+                                                reinterpret_cast<int8_t*>(ws + L.off_sb[0]), L.n_pad, L.k_pad,
+                                                reinterpret_cast<int32_t*>(ws + L.off_eb[0]),
+                                                reinterpret_cast<unsigned long long*>(ws + L.off_colmax), st));
+        default:
+            return hip_status(run_product(L, m, n, num_slices, ws, 0, 0, C, ldc, 1, 0, st));
+    }
+}
+
+ozimmu_status_t ozimmu_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
+                             int64_t ldb, double* C, int64_t ldc, int num_slices, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    for (int stage = 0; stage < 3; ++stage) {
+        ozimmu_status_t rc = ozimmu_dgemm_stage(stage, m, n, k, A, lda, B, ldb, C, ldc, num_slices, workspace,
+                                                workspace_bytes, stream);
+        if (rc != OZIMMU_OK) return rc;
+    }
+    return OZIMMU_OK;
+}
+
+ozimmu_status_t ozimmu_zgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
+                             int64_t ldb, double* C, int64_t ldc, int num_slices, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    Layout L{};
+    ozimmu_status_t rc = check_gemm_args(m, n, k, A, lda, B, ldb, C, ldc, num_slices, workspace, workspace_bytes,
+                                         true, &L);
+    if (rc != OZIMMU_OK || m == 0 || n == 0) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (k == 0) {
+        hipError_t e = launch_fill_f64(C, 2 * ldc, 2, m, n, 0.0, st);
+        if (e == hipSuccess) e = launch_fill_f64(C + 1, 2 * ldc, 2, m, n, 0.0, st);
+        return hip_status(e);
+    }
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    const int s = num_slices;
+    hipError_t e = hipSuccess;
+    // the real and imaginary planes are separated while splitting (element stride 2)
+    for (int pl = 0; pl < 2 && e == hipSuccess; ++pl)
+        e = launch_split_rows(A + pl, lda, 2, m, k, s, reinterpret_cast<int8_t*>(ws + L.off_sa[pl]), L.m_pad,
+                              L.k_pad, reinterpret_cast<int32_t*>(ws + L.off_ea[pl]), st);
+    for (int pl = 0; pl < 2 && e == hipSuccess; ++pl)
+        e = launch_split_cols(B + pl, ldb, 2, k, n, s, reinterpret_cast<int8_t*>(ws + L.off_sb[pl]), L.n_pad,
+                              L.k_pad, reinterpret_cast<int32_t*>(ws + L.off_eb[pl]),
+                              reinterpret_cast<unsigned long long*>(ws + L.off_colmax), st);
+    // Cr = G(Ar,Br) - G(Ai,Bi);  Ci = G(Ar,Bi) + G(Ai,Br): the second product of each part is
+    // combined with the first by one rounded FP64 operation in the kernel's epilogue.
+    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 0, C, 2 * ldc, 2, 0, st);
+    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 1, C, 2 * ldc, 2, 2, st);
+    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, C + 1, 2 * ldc, 2, 0, st);
+    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 0, C + 1, 2 * ldc, 2, 1, st);
+    return hip_status(e);
+}
+
+}  // extern "C"

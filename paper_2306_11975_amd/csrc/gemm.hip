@@ -1,0 +1,364 @@
+// Slice products on the CDNA4 INT8 matrix cores with the FP64 sum fused in
+// (lines 4-9 of the IMMU algorithm, Section 3.1).
+//
+// One workgroup (4 wavefronts) owns a 256 x 256 tile of C for the whole computation. It walks
+// the anti-diagonals d = s+1 .. 2 and, inside a diagonal, the pairs (p, d-p) and the k-chunks,
+// accumulating everything that shares the scale 2^(-7d) into the same INT32 registers
+// (integer addition is exact, so a diagonal is one long INT8 dot product of length (d-1) k).
+// A finished diagonal leaves the registers as one coalesced INT32 store into the workspace; the
+// last diagonal stays in registers and the epilogue adds the diagonals in the fixed order
+// least-significant first, applies 2^(EA_i + EB_j) and writes C. When a diagonal is longer
+// than 2^17 products (INT32 could overflow), the registers are flushed into INT64 sums in the
+// workspace every 2^17 products instead (k-blocking, cf. Section 2.4 on splitting long k).
+//
+// Data path per k-chunk of 128: global -> VGPR -> LDS (XOR-swizzled 16-byte columns, so the
+// 16-byte LDS reads of eight consecutive rows hit distinct bank groups) -> v_mfma_i32_32x32x32_i8.
+// Each wavefront computes 128 x 128 outputs as 4 x 4 MFMA tiles (256 accumulator registers).
+#include "ozimmu_internal.h"
+
+namespace ozimmu {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef long long v2l __attribute__((ext_vector_type(2)));
+
+constexpr int kStageBytes = 2 * kTile * kChunk;      // A tile + B tile of one k-chunk
+constexpr int kLdsBytes = 2 * kStageBytes;           // double buffered
+constexpr int kBlockLen = OZIMMU_INT32_BLOCK;
+
+// Workgroup -> tile. Hardware deals workgroups round-robin over the 8 XCDs (each with its own
+// L2); give every XCD a contiguous run of tiles, ordered in column panels 4 tiles tall so that
+// the 32 workgroups resident on an XCD share A and B panels through that L2.
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
+    const int total = tiles_m * tiles_n;
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int q = total >> 3, r = total & 7;
+    const int logical = xcd * q + (xcd < r ? xcd : r) + slot;
+    constexpr int GM = 4;
+    const int per_group = GM * tiles_n;
+    const int group = logical / per_group;
+    const int first_m = group * GM;
+    const int rows = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+    const int in_group = logical - group * per_group;
+    tm = first_m + in_group % rows;
+    tn = in_group / rows;
+}
+
+// A zero the optimiser cannot see through. Address arithmetic of the code that runs after the
+// k-walk is made to depend on it, so that it is computed there and not hoisted above the walk,
+// where it would occupy registers the matrix-core loop needs.
+__device__ __forceinline__ unsigned opaque_zero() {
+    unsigned z;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+    return z;
+}
+
+// The 256 accumulators live in the accumulation half of the register file for the whole k-walk.
+// Initialising and reading them through these two helpers pins that choice, so that no copies
+// between the two halves of the file are made around the loop.
+__device__ __forceinline__ int acc_zero() {
+    int a;
+    asm("v_accvgpr_write_b32 %0, 0" : "=a"(a));
+    return a;
+}
+__device__ __forceinline__ int acc_read(int a) {
+    int v;
+    asm("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
+}
+
+struct Job {  // one k-chunk of one slice pair
+    int d, p, kc;
+};
+
+template <bool WIDE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void slice_gemm_kernel(const GemmArgs g) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
+    const int tile_id = tm * g.tiles_n + tn;
+    const int num_tiles = g.tiles_m * g.tiles_n;
+
+    const bool pair_mode = g.pair_p > 0;
+    const int d_first = pair_mode ? g.pair_p + g.pair_q : g.num_slices + 1;
+    const int d_last = pair_mode ? d_first : 2;
+
+    // global -> LDS staging: 8 x 16 B of the A tile and 8 x 16 B of the B tile per thread.
+    // Addresses are a wave-uniform 64-bit base plus a 32-bit lane offset (scalar-base addressing).
+    const int ld_row = tid >> 3;                 // + 32 * i
+    const int ld_col = tid & 7;                  // 16-byte column inside the 128-byte chunk row
+    const unsigned ld_lane_off = (unsigned)ld_row * (unsigned)g.k_pad + (unsigned)ld_col * 16u;
+    const int8_t* a_tile = g.SA + (int64_t)tm * kTile * g.k_pad;
+    const int8_t* b_tile = g.SB + (int64_t)tn * kTile * g.k_pad;
+    const int st_off = ld_row * kChunk + ((ld_col ^ (ld_row & 7)) << 4);
+
+    // LDS -> MFMA operands: lane reads row (lane % 32) of a 32-row block, 16-byte column 2 kk + lane / 32
+    const int rd_row = lane & 31;
+    const int rd_half = lane >> 5;
+    const int a_rd = (wm * 128 + rd_row) * kChunk;
+    const int b_rd = kTile * kChunk + (wn * 128 + rd_row) * kChunk;
+    const int rd_sw = lane & 7;
+
+    v4i stage_a[8], stage_b[8];
+    const unsigned lane_off16 = (unsigned)tid * 16u;
+
+    auto gload = [&](const Job& jb) {
+        const int8_t* pa = a_tile + (int64_t)(jb.p - 1) * g.a_slice_stride + (int64_t)jb.kc * kChunk;
+        const int8_t* pb = b_tile + (int64_t)(jb.d - jb.p - 1) * g.b_slice_stride + (int64_t)jb.kc * kChunk;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            stage_a[i] = *reinterpret_cast<const v4i*>(pa + (int64_t)i * 32 * g.k_pad + ld_lane_off);
+            stage_b[i] = *reinterpret_cast<const v4i*>(pb + (int64_t)i * 32 * g.k_pad + ld_lane_off);
+        }
+    };
+    auto lstore = [&](int buf) {
+        unsigned char* base = lds + buf * kStageBytes + st_off;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            *reinterpret_cast<v4i*>(base + i * 32 * kChunk) = stage_a[i];
+            *reinterpret_cast<v4i*>(base + kTile * kChunk + i * 32 * kChunk) = stage_b[i];
+        }
+    };
+    auto compute = [&](v16i (&acc)[4][4], int buf) {
+        const unsigned char* base = lds + buf * kStageBytes;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int col = (((kk << 1) | rd_half) ^ rd_sw) << 4;
+            v4i a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                a[i] = *reinterpret_cast<const v4i*>(base + a_rd + i * 32 * kChunk + col);
+                b[i] = *reinterpret_cast<const v4i*>(base + b_rd + i * 32 * kChunk + col);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    };
+    auto advance = [&](Job& jb) -> bool {  // false when the walk is over
+        if (++jb.kc < g.kc_end) return true;
+        jb.kc = g.kc_begin;
+        if (!pair_mode && ++jb.p < jb.d) return true;
+        --jb.d;
+        jb.p = 1;
+        return jb.d >= d_last;
+    };
+
+    // INT32 registers -> workspace (narrow: plain store of a finished diagonal)
+    auto store_diag32 = [&](v16i (&acc)[4][4], int d) {
+        unsigned char* base = reinterpret_cast<unsigned char*>(g.D) +
+                              ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * 4);
+        const unsigned off = lane_off16 + opaque_zero();
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    v4i v = {acc_read(acc[i][j][4 * r4]), acc_read(acc[i][j][4 * r4 + 1]), acc_read(acc[i][j][4 * r4 + 2]),
+                             acc_read(acc[i][j][4 * r4 + 3])};
+                    *reinterpret_cast<v4i*>(base + ((i * 4 + j) * 4 + r4) * 4096 + off) = v;
+                    __builtin_amdgcn_sched_barrier(0);  // keep register pressure flat
+                }
+    };
+    // INT32 registers -> INT64 sums (wide: k-blocking)
+    auto flush_diag64 = [&](v16i (&acc)[4][4], int d, bool first) {
+        unsigned char* base = reinterpret_cast<unsigned char*>(g.D) +
+                              ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * 8);
+        const unsigned off = lane_off16 + opaque_zero();
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r2 = 0; r2 < 8; ++r2) {
+                    v2l v = {(long long)acc_read(acc[i][j][2 * r2]), (long long)acc_read(acc[i][j][2 * r2 + 1])};
+                    v2l* q = reinterpret_cast<v2l*>(base + ((i * 4 + j) * 8 + r2) * 4096 + off);
+                    if (!first) v += *q;
+                    *q = v;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+    };
+    auto zero_acc = [&](v16i (&acc)[4][4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = acc_zero();
+    };
+
+    // accumulator layout of the 32x32 MFMA: lane holds column (lane % 32); register r holds
+    // row 8 (r / 4) + 4 (lane / 32) + r % 4.
+    const int row0 = tm * kTile + wm * 128 + 4 * rd_half;
+    const int col0 = tn * kTile + wn * 128 + rd_row;
+    const int s = g.num_slices;
+
+    // Pair mode: raw INT32 tile -> row-major P. The tile is staged through LDS (free once the
+    // k-walk is over) in two halves of 128 rows so that the bounds-checked stores are a rolled
+    // loop along rows of P.
+    auto write_pair = [&](v16i (&acc)[4][4]) {
+        int* tile = reinterpret_cast<int*>(lds);  // [128][256] INT32 = 128 KiB
+        const unsigned tbase = (unsigned)(4 * rd_half * kTile + wn * 128 + rd_row) + opaque_zero();
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            if (wm == half) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                        {
+                            tile[tbase + (i * 32 + 8 * (r >> 2) + (r & 3)) * kTile + j * 32] = acc_read(acc[i][j][r]);
+                            if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+                        }
+            }
+            __syncthreads();
+#pragma unroll 1
+            for (int rr = 0; rr < 128; ++rr) {
+                const int row = tm * kTile + half * 128 + rr;
+                const int col = tn * kTile + tid;
+                if (row < g.m && col < g.n) g.P[(int64_t)row * g.ldp + col] = tile[rr * kTile + tid];
+            }
+            __syncthreads();
+        }
+    };
+    auto write_c = [&](int row, int col, int eb, double sum) {
+        if (row < g.m && col < g.n) {
+            const double val = ldexp(sum, g.EA[row] + eb);
+            double* c = g.C + (int64_t)row * g.ldc + (int64_t)col * g.c_inc;
+            if (g.c_mode == 0) *c = val;
+            else if (g.c_mode == 1) *c = *c + val;
+            else *c = *c - val;
+        }
+    };
+    // Fixed-order FP64 sum: the diagonals come back from the workspace (each thread reads what
+    // it wrote itself, so no synchronisation is needed), least significant first.
+    auto final_narrow = [&]() {
+#pragma unroll 1
+        for (int ij = 0; ij < 16; ++ij) {
+            const int i = ij >> 2, j = ij & 3;
+            const int col = col0 + j * 32;
+            const int eb = col < g.n ? g.EB[col] : 0;
+#pragma unroll 1
+            for (int r4 = 0; r4 < 4; ++r4) {
+                double sum[4] = {0.0, 0.0, 0.0, 0.0};
+                for (int d = s + 1; d >= 2; --d) {
+                    const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * d) << 52);
+                    const unsigned char* src = reinterpret_cast<const unsigned char*>(g.D) +
+                                               ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * 4);
+                    v4i v = *reinterpret_cast<const v4i*>(src + (ij * 4 + r4) * 4096 + lane_off16);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) sum[u] = sum[u] + (double)v[u] * sc;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) write_c(row0 + i * 32 + 8 * r4 + u, col, eb, sum[u]);
+            }
+        }
+    };
+    auto final_wide = [&]() {
+#pragma unroll 1
+        for (int ij = 0; ij < 16; ++ij) {
+            const int i = ij >> 2, j = ij & 3;
+            const int col = col0 + j * 32;
+            const int eb = col < g.n ? g.EB[col] : 0;
+#pragma unroll 1
+            for (int r2 = 0; r2 < 8; ++r2) {
+                double sum[2] = {0.0, 0.0};
+                for (int d = s + 1; d >= 2; --d) {
+                    const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * d) << 52);
+                    const unsigned char* src = reinterpret_cast<const unsigned char*>(g.D) +
+                                               ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * 8);
+                    v2l v = *reinterpret_cast<const v2l*>(src + (ij * 8 + r2) * 4096 + lane_off16);
+                    sum[0] = sum[0] + (double)v[0] * sc;
+                    sum[1] = sum[1] + (double)v[1] * sc;
+                }
+                const int r = 2 * r2;
+                write_c(row0 + i * 32 + 8 * (r >> 2) + (r & 3), col, eb, sum[0]);
+                write_c(row0 + i * 32 + 8 * (r >> 2) + (r & 3) + 1, col, eb, sum[1]);
+            }
+        }
+    };
+
+    Job cur = {d_first, pair_mode ? g.pair_p : 1, g.kc_begin};
+    gload(cur);
+    lstore(0);
+    __syncthreads();
+
+    // The walk over (diagonal, pair, k-chunk) is one software pipeline: while chunk t is in the
+    // matrix cores, chunk t+1 (possibly of the next pair or diagonal) travels global -> LDS.
+    const int nkc = g.kc_end - g.kc_begin;
+    int buf = 0;
+    bool more = true;
+    auto run_chunks = [&](v16i (&acc)[4][4], int count) {
+        int t = 0;
+        do {
+            Job nxt = cur;
+            more = advance(nxt);
+            if (more) gload(nxt);
+            compute(acc, buf);
+            if (more) lstore(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
+            cur = nxt;
+        } while (++t < count);
+    };
+
+    for (int d = d_first; d >= d_last; --d) {
+        int jobs = pair_mode ? nkc : (d - 1) * nkc;
+        if (WIDE) {
+            // at most 2^17 products per output element may share one INT32 sum
+            bool fresh = true;
+            do {
+                const int run = jobs > kBlockLen / kChunk ? kBlockLen / kChunk : jobs;
+                jobs -= run;
+                v16i acc[4][4];
+                zero_acc(acc);
+                run_chunks(acc, run);
+                flush_diag64(acc, d, fresh);
+                fresh = false;
+            } while (jobs > 0);
+        } else {
+            v16i acc[4][4];
+            zero_acc(acc);
+            run_chunks(acc, jobs);
+            if (pair_mode) write_pair(acc);
+            else store_diag32(acc, d);
+        }
+    }
+    if (WIDE) final_wide();
+    else if (!pair_mode) final_narrow();
+}
+
+}  // namespace
+
+hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st) {
+    const int blocks = args.tiles_m * args.tiles_n;
+    if (blocks == 0) return hipSuccess;
+    hipError_t e;
+    if (wide) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&slice_gemm_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        slice_gemm_kernel<true><<<dim3(blocks), dim3(256), kLdsBytes, st>>>(args);
+    } else {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&slice_gemm_kernel<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        slice_gemm_kernel<false><<<dim3(blocks), dim3(256), kLdsBytes, st>>>(args);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace ozimmu

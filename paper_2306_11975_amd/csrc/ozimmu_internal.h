@@ -1,0 +1,50 @@
+// Internal declarations shared by the translation units of libozimmu (HIP, gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ozimmu.h"
+
+namespace ozimmu {
+
+constexpr int kTile = 256;          // macro tile edge in rows of A / rows of B^T (= OZIMMU_ROW_ALIGN)
+constexpr int kChunk = 128;         // k-extent of one LDS stage in bytes (= OZIMMU_K_ALIGN)
+constexpr int kTileElems = kTile * kTile;
+
+static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Arguments of the slice-product kernel. One launch covers every macro tile of C.
+struct GemmArgs {
+    const int8_t* SA;      // padded slices of A:   [slice][m_pad][k_pad]
+    const int8_t* SB;      // padded slices of B^T: [slice][n_pad][k_pad]
+    int64_t a_slice_stride;  // bytes between consecutive slices of A
+    int64_t b_slice_stride;
+    int k_pad;             // bytes per slice row
+    int tiles_m, tiles_n;
+    int m, n;              // true extent of C
+    int num_slices;        // full mode: diagonals num_slices+1 .. 2
+    int pair_p, pair_q;    // pair mode (pair_p > 0): only this pair, raw INT32 out
+    int kc_begin, kc_end;  // k-range in chunks of kChunk
+    void* D;               // per-diagonal integer sums that leave the registers (INT32 or INT64)
+    int32_t* P;            // pair mode output, row-major
+    int64_t ldp;
+    double* C;             // full mode output
+    int64_t ldc;           // in doubles
+    int c_inc;             // distance in doubles between consecutive columns (2 for a complex plane)
+    int c_mode;            // 0: C = G, 1: C = C + G, 2: C = C - G
+    const int32_t* EA;
+    const int32_t* EB;
+};
+
+hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k, int s,
+                             int8_t* S, int64_t m_pad, int64_t k_pad, int32_t* E, hipStream_t st);
+hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n, int s,
+                             int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
+                             unsigned long long* colmax, hipStream_t st);
+hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st);
+hipError_t launch_fill_f64(double* C, int64_t ldc, int c_inc, int64_t m, int64_t n, double v,
+                           hipStream_t st);
+hipError_t launch_fill_i32(int32_t* P, int64_t ldp, int64_t m, int64_t n, int32_t v, hipStream_t st);
+
+}  // namespace ozimmu

@@ -1,0 +1,156 @@
+"""Thin binding over the C ABI of libozimmu (include/ozimmu.h): argument marshalling only.
+
+Every function has the name of the C entry point it calls; tensors are torch CUDA tensors used
+purely as device memory, and the stream is torch's current HIP stream unless one is given.
+There is no fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+_LIB_PATH = Path(__file__).resolve().parent / "libozimmu.so"
+
+OK = 0
+MAX_SLICES = 16
+ROW_ALIGN = 256
+K_ALIGN = 128
+INT32_BLOCK = 131072
+WORKSPACE_ALIGN = 256
+
+EXPORTS = (
+    "ozimmu_status_string", "ozimmu_slice_geometry", "ozimmu_split_rows", "ozimmu_split_cols",
+    "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_stage",
+)
+
+
+class OzimmuError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"ozimmu error {code}: {what}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libozimmu.so (built by ``python -m paper_2306_11975_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2306_11975_amd.build` "
+                               "(there is no CPU fallback)")
+        L = ctypes.CDLL(str(_LIB_PATH))
+        i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+        L.ozimmu_status_string.restype = ctypes.c_char_p
+        L.ozimmu_status_string.argtypes = [i32]
+        L.ozimmu_slice_geometry.restype = i32
+        L.ozimmu_slice_geometry.argtypes = [i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.ozimmu_split_rows.restype = i32
+        L.ozimmu_split_rows.argtypes = [i64, i64, vp, i64, i32, vp, vp, vp]
+        L.ozimmu_split_cols.restype = i32
+        L.ozimmu_split_cols.argtypes = [i64, i64, vp, i64, i32, vp, vp, vp, vp]
+        L.ozimmu_slice_gemm.restype = i32
+        L.ozimmu_slice_gemm.argtypes = [i64, i64, i64, vp, vp, i32, i32, i64, i64, vp, i64, vp]
+        L.ozimmu_workspace_bytes.restype = i32
+        L.ozimmu_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ctypes.POINTER(sz)]
+        for name in ("ozimmu_dgemm", "ozimmu_zgemm"):
+            f = getattr(L, name)
+            f.restype = i32
+            f.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
+        L.ozimmu_dgemm_stage.restype = i32
+        L.ozimmu_dgemm_stage.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().ozimmu_status_string(int(code)).decode()
+
+
+def _check(code: int) -> None:
+    if code != OK:
+        raise OzimmuError(code, status_string(code))
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _stream(stream) -> int:
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream
+
+
+def slice_geometry(rows: int, k: int):
+    rp, kp = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().ozimmu_slice_geometry(rows, k, ctypes.byref(rp), ctypes.byref(kp)))
+    return rp.value, kp.value
+
+
+def workspace_bytes(m: int, n: int, k: int, num_slices: int, is_complex: bool = False) -> int:
+    out = ctypes.c_size_t()
+    _check(lib().ozimmu_workspace_bytes(m, n, k, num_slices, int(is_complex), ctypes.byref(out)))
+    return out.value
+
+
+def split_rows(A, num_slices: int, slices, exps, stream=None) -> None:
+    """A: (m, k) float64 device tensor with unit column stride; slices: int8 device buffer of
+    num_slices * rows_padded * k_padded bytes; exps: int32 device tensor of m entries."""
+    m, k = A.shape
+    _check(lib().ozimmu_split_rows(m, k, _ptr(A), A.stride(0) if m > 1 else max(k, 1), num_slices,
+                                   _ptr(slices), _ptr(exps), _stream(stream)))
+
+
+def split_cols(B, num_slices: int, slices, exps, col_scratch, stream=None) -> None:
+    k, n = B.shape
+    _check(lib().ozimmu_split_cols(k, n, _ptr(B), B.stride(0) if k > 1 else max(n, 1), num_slices,
+                                   _ptr(slices), _ptr(exps), _ptr(col_scratch), _stream(stream)))
+
+
+def slice_gemm(m: int, n: int, k: int, SA, SB, p: int, q: int, k0: int, klen: int, P, stream=None) -> None:
+    _check(lib().ozimmu_slice_gemm(m, n, k, _ptr(SA), _ptr(SB), p, q, k0, klen, _ptr(P),
+                                   P.stride(0) if m > 1 else max(n, 1), _stream(stream)))
+
+
+def _ld(t, cols):
+    return t.stride(0) if t.shape[0] > 1 else max(cols, 1)
+
+
+def dgemm(A, B, C, num_slices: int, workspace, stream=None) -> None:
+    """C = A . B by the Ozaki scheme on the INT8 matrix cores (A: m x k, B: k x n, C: m x n,
+    float64 device tensors with unit column stride; workspace: uint8 device tensor)."""
+    m, k = A.shape
+    n = B.shape[1]
+    _check(lib().ozimmu_dgemm(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C), _ld(C, n), num_slices,
+                              _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+
+
+def dgemm_stage(stage: int, A, B, C, num_slices: int, workspace, stream=None) -> None:
+    m, k = A.shape
+    n = B.shape[1]
+    _check(lib().ozimmu_dgemm_stage(stage, m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C), _ld(C, n),
+                                    num_slices, _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                    _stream(stream)))
+
+
+def zgemm(A, B, C, num_slices: int, workspace, stream=None) -> None:
+    """Complex128 device tensors (interleaved re, im), otherwise as dgemm."""
+    m, k = A.shape
+    n = B.shape[1]
+    _check(lib().ozimmu_zgemm(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C), _ld(C, n), num_slices,
+                              _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+
+
+def alloc_workspace(m: int, n: int, k: int, num_slices: int, is_complex: bool = False, device="cuda"):
+    """Convenience for callers that use torch for device memory: a uint8 tensor of the right size
+    (torch's caching allocator returns 512-byte aligned blocks)."""
+    import torch
+
+    nbytes = max(workspace_bytes(m, n, k, num_slices, is_complex), WORKSPACE_ALIGN)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    assert ws.data_ptr() % WORKSPACE_ALIGN == 0
+    return ws

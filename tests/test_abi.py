@@ -1,0 +1,91 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares,
+and rejects bad arguments on the host before anything is launched (no GPU needed)."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2306_11975_amd import ozimmu
+
+HEADER = Path(__file__).resolve().parents[1] / "include" / "ozimmu.h"
+
+
+def declared_functions():
+    text = HEADER.read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ozimmu_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree_and_library_exports_everything():
+    names = declared_functions()
+    assert set(names) == set(ozimmu.EXPORTS)
+    L = ozimmu.lib()
+    for name in names:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings():
+    assert ozimmu.status_string(0) == "ok"
+    seen = {ozimmu.status_string(c) for c in range(8)}
+    assert len(seen) == 8
+    assert ozimmu.status_string(99) == "unknown status"
+
+
+def test_geometry_and_workspace_size():
+    assert ozimmu.slice_geometry(1, 1) == (256, 128)
+    assert ozimmu.slice_geometry(256, 128) == (256, 128)
+    assert ozimmu.slice_geometry(257, 129) == (512, 256)
+    assert ozimmu.slice_geometry(0, 0) == (0, 0)
+    s, m, n, k = 8, 8192, 8192, 8192
+    ws = ozimmu.workspace_bytes(m, n, k, s)
+    # slices of A and B, exponents, column maxima and s INT32 diagonal buffers
+    lower = s * m * k * 2 + s * m * n * 4
+    assert lower <= ws <= lower + 4 * (m + n) + 8 * n + 16 * 256
+    # long k: a diagonal no longer fits one INT32 block, the diagonal sums are INT64
+    ws_wide = ozimmu.workspace_bytes(4096, 4096, 131072, 8)
+    assert ws_wide >= 8 * 4096 * 131072 * 2 + 8 * 4096 * 4096 * 8
+    assert ozimmu.workspace_bytes(64, 64, 64, 3, True) > ozimmu.workspace_bytes(64, 64, 64, 3, False)
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    L = ozimmu.lib()
+    out = ctypes.c_size_t()
+    assert L.ozimmu_workspace_bytes(-1, 1, 1, 3, 0, ctypes.byref(out)) == 1
+    assert L.ozimmu_workspace_bytes(1, 1, 1, 0, 0, ctypes.byref(out)) == 3
+    assert L.ozimmu_workspace_bytes(1, 1, 1, 17, 0, ctypes.byref(out)) == 3
+    assert L.ozimmu_workspace_bytes(1, 1, 1, 3, 0, None) == 4
+    fake = ctypes.c_void_p(256)  # never dereferenced: validation fails first
+    # negative dimension, bad slice count, small leading dimensions, null pointers, workspace
+    assert L.ozimmu_dgemm(-1, 4, 4, fake, 4, fake, 4, fake, 4, 3, fake, 1 << 30, None) == 1
+    assert L.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 0, fake, 1 << 30, None) == 3
+    assert L.ozimmu_dgemm(4, 4, 4, fake, 3, fake, 4, fake, 4, 3, fake, 1 << 30, None) == 2
+    assert L.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 3, fake, 4, 3, fake, 1 << 30, None) == 2
+    assert L.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 3, 3, fake, 1 << 30, None) == 2
+    assert L.ozimmu_dgemm(4, 4, 4, None, 4, fake, 4, fake, 4, 3, fake, 1 << 30, None) == 4
+    assert L.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, None, 4, 3, fake, 1 << 30, None) == 4
+    assert L.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 3, None, 1 << 30, None) == 5
+    assert L.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 3, ctypes.c_void_p(264), 1 << 30, None) == 5
+    assert L.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 3, fake, 16, None) == 5
+    assert L.ozimmu_zgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 3, fake, 16, None) == 5
+    # empty products are no-ops
+    assert L.ozimmu_dgemm(0, 4, 4, None, 4, None, 4, None, 4, 3, None, 0, None) == 0
+    assert L.ozimmu_dgemm(4, 0, 4, None, 4, None, 0, None, 0, 3, None, 0, None) == 0
+    # staged entry points
+    assert L.ozimmu_split_rows(4, 4, fake, 3, 3, fake, fake, None) == 2
+    assert L.ozimmu_split_rows(4, 4, fake, 4, 3, fake, None, None) == 4
+    assert L.ozimmu_split_cols(4, 4, fake, 4, 3, fake, fake, None, None) == 4
+    assert L.ozimmu_split_cols(4, 4, fake, 4, 3, fake, fake, ctypes.c_void_p(12), None) == 5
+    assert L.ozimmu_slice_gemm(4, 4, 256, fake, fake, 0, 1, 0, 128, fake, 4, None) == 3
+    assert L.ozimmu_slice_gemm(4, 4, 256, fake, fake, 1, 1, 64, 128, fake, 4, None) == 1   # k0 not aligned
+    assert L.ozimmu_slice_gemm(4, 4, 256, fake, fake, 1, 1, 0, 100, fake, 4, None) == 1    # ragged inside
+    assert L.ozimmu_slice_gemm(4, 4, 256, fake, fake, 1, 1, 128, 256, fake, 4, None) == 1  # beyond k
+    assert L.ozimmu_slice_gemm(4, 4, 1 << 18, fake, fake, 1, 1, 0, (1 << 17) + 128, fake, 4, None) == 1
+    assert L.ozimmu_slice_gemm(4, 4, 256, fake, fake, 1, 1, 0, 128, fake, 3, None) == 2
+    assert L.ozimmu_dgemm_stage(3, 4, 4, 4, fake, 4, fake, 4, fake, 4, 3, fake, 1 << 30, None) == 1
+
+
+def test_binding_raises_typed_error():
+    with pytest.raises(ozimmu.OzimmuError) as e:
+        ozimmu.workspace_bytes(1, 1, 1, 0)
+    assert e.value.code == 3
