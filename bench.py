@@ -58,7 +58,7 @@ def main():
     ap.add_argument("--size", type=int, default=8192, help="m = n = k")
     ap.add_argument("--slices", type=int, default=8, help="number of INT8 slices s")
     ap.add_argument("--phi", type=float, default=1.0)
-    ap.add_argument("--cpu-rows", type=int, default=16, help="rows of A in the CPU oracle sample (0: skip)")
+    ap.add_argument("--cpu-rows", type=int, default=256, help="rows of A in the CPU oracle sample (0: skip)")
     ap.add_argument("--no-context", action="store_true", help="skip the native FP64 DGEMM context timing")
     args = ap.parse_args()
 

@@ -35,7 +35,7 @@ def build(force: bool = False) -> Path:
     _LIB.parent.mkdir(exist_ok=True)
     tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
     cmd = ["gcc", "-std=c99", "-O2", "-ftree-vectorize", "-ffp-contract=off", "-fno-fast-math",
-           "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", str(_SRC), "-o", str(tmp), "-lm"]
+           "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-Wno-maybe-uninitialized", str(_SRC), "-o", str(tmp), "-lm"]
     subprocess.run(cmd, check=True)
     os.replace(tmp, _LIB)
     return _LIB
