@@ -50,6 +50,7 @@ typedef enum {
 #define OZIMMU_SLICE_BITS 7          /* Table 2: INT8-INT32 keeps 7 magnitude bits per slice */
 #define OZIMMU_ROW_ALIGN 256         /* slice rows are padded to a multiple of this */
 #define OZIMMU_K_ALIGN 128           /* slice row length is padded to a multiple of this */
+#define OZIMMU_K_STEP 64             /* k-extent of one contiguous block of a slice tensor */
 #define OZIMMU_INT32_BLOCK 131072    /* at most 2^17 INT8 products go into one INT32 sum:
                                         2^17 * 127^2 < 2^31 (the exact limit is 133144) */
 #define OZIMMU_WORKSPACE_ALIGN 256
@@ -57,22 +58,32 @@ typedef enum {
 const char* ozimmu_status_string(ozimmu_status_t status);
 
 /*
- * Padded slice geometry. A slice tensor for `rows` rows of length k is stored as
- *     int8 slices[num_slices][rows_padded][k_padded]      (k contiguous)
- * with rows_padded = roundup(rows, OZIMMU_ROW_ALIGN), k_padded = roundup(k, OZIMMU_K_ALIGN),
- * zero-filled outside [0,rows) x [0,k). Both A (rows = m) and B^T (rows = n) use it, so that
- * both operands of a slice product are "rows of length k" (SplitInt header: M = A or B^T).
+ * Slice tensors. The slices of `rows` rows of length k (A: rows = m; B^T: rows = n, so that both
+ * operands of a slice product are "rows of length k", SplitInt header: M = A or B^T) are padded
+ * to rows_padded = roundup(rows, OZIMMU_ROW_ALIGN) and k_padded = roundup(k, OZIMMU_K_ALIGN),
+ * zero-filled outside [0,rows) x [0,k), and stored tiled, in exactly the order in which the
+ * slice-product kernel copies them into LDS: a block of OZIMMU_ROW_ALIGN rows x
+ * OZIMMU_K_STEP bytes is contiguous (16 KiB), and inside a row of a block the four 16-byte
+ * columns are XOR-swizzled with bits 2..3 of the row. Element (slice s, row r, position l),
+ * with rr = r % 256, c = (l % 64) / 16, lives at byte offset
+ *     s * rows_padded * k_padded
+ *   + ((r / 256) * (k_padded / 64) + l / 64) * 16384
+ *   + rr * 64 + ((c ^ ((rr / 4) % 4)) * 16) + l % 16
+ * (ozimmu_slice_offset computes it). Size: num_slices * rows_padded * k_padded bytes.
  */
 ozimmu_status_t ozimmu_slice_geometry(int64_t rows, int64_t k, int64_t* rows_padded,
                                       int64_t* k_padded);
+/* Byte offset of element (slice, row, l) in a slice tensor of the given padded geometry
+ * (host-side index arithmetic only); -1 if an index is out of range. */
+int64_t ozimmu_slice_offset(int64_t rows_padded, int64_t k_padded, int slice, int64_t row, int64_t l);
 
 /*
  * SplitInt on the rows of A (m x k, lda >= k).
  *   exps   [out] int32[m]: EA_i with 2^(EA_i - 1) <= max_l |A_il| < 2^(EA_i); 0 for a zero row.
- *   slices [out] padded slice tensor (see above), slices[p-1][i][l] = sign(A_il) * chunk p
- *                of |A_il| 2^(-EA_i), each chunk in [0, 127] (truncation, no rounding).
+ *   slices [out] slice tensor (layout above): element (p-1, i, l) = sign(A_il) * chunk p of
+ *                |A_il| 2^(-EA_i), each chunk in [0, 127] (truncation, no rounding).
  * split_cols does the same for the columns of B (k x n, ldb >= n), i.e. for M = B^T:
- * exps int32[n], slices[q-1][j][l] from B_lj. `col_scratch` is device memory of at least
+ * exps int32[n], element (q-1, j, l) from B_lj. `col_scratch` is device memory of at least
  * 8 * n bytes (column maxima), 8-byte aligned.
  */
 ozimmu_status_t ozimmu_split_rows(int64_t m, int64_t k, const double* A, int64_t lda,
@@ -84,8 +95,8 @@ ozimmu_status_t ozimmu_split_cols(int64_t k, int64_t n, const double* B, int64_t
 /*
  * One slice product on the matrix cores (line 6 of the IMMU algorithm), exposed so that
  * the raw INT32 accumulators can be checked:
- *     P[i][j] = sum_{l = k0}^{k0 + klen - 1} SA[p-1][i][l] * SB[q-1][j][l]     (INT32, exact)
- * SA, SB: padded slice tensors for m and n rows of length k holding at least p resp. q
+ *     P[i][j] = sum_{l = k0}^{k0 + klen - 1} SA(p-1, i, l) * SB(q-1, j, l)     (INT32, exact)
+ * SA, SB: slice tensors for m and n rows of length k holding at least p resp. q
  * slices. P: int32, m x n, row-major, ldp >= n. Rules: 1 <= p, q <= OZIMMU_MAX_SLICES;
  * k0 a multiple of OZIMMU_K_ALIGN; klen <= OZIMMU_INT32_BLOCK; klen a multiple of
  * OZIMMU_K_ALIGN unless k0 + klen == k. klen == 0 gives P = 0.

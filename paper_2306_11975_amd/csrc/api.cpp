@@ -130,6 +130,13 @@ ozimmu_status_t ozimmu_slice_geometry(int64_t rows, int64_t k, int64_t* rows_pad
     return OZIMMU_OK;
 }
 
+int64_t ozimmu_slice_offset(int64_t rows_padded, int64_t k_padded, int slice, int64_t row, int64_t l) {
+    if (slice < 0 || row < 0 || l < 0 || row >= rows_padded || l >= k_padded) return -1;
+    const int64_t rr = row % kTile, c = (l % kStep) / 16;
+    return (int64_t)slice * rows_padded * k_padded + ((row / kTile) * (k_padded / kStep) + l / kStep) * (kTile * kStep) +
+           rr * kStep + ((c ^ ((rr >> 2) & 3)) << 4) + l % 16;
+}
+
 ozimmu_status_t ozimmu_split_rows(int64_t m, int64_t k, const double* A, int64_t lda, int num_slices,
                                   int8_t* slices, int32_t* exps, void* stream) {
     if (!dims_ok(m, k, 0)) return OZIMMU_ERR_BAD_DIM;

@@ -2,18 +2,26 @@
 // (lines 4-9 of the IMMU algorithm, Section 3.1).
 //
 // One workgroup (4 wavefronts) owns a 256 x 256 tile of C for the whole computation. It walks
-// the anti-diagonals d = s+1 .. 2 and, inside a diagonal, the pairs (p, d-p) and the k-chunks,
+// the anti-diagonals d = s+1 .. 2 and, inside a diagonal, the pairs (p, d-p) and the k-steps,
 // accumulating everything that shares the scale 2^(-7d) into the same INT32 registers
 // (integer addition is exact, so a diagonal is one long INT8 dot product of length (d-1) k).
-// A finished diagonal leaves the registers as one coalesced INT32 store into the workspace; the
-// last diagonal stays in registers and the epilogue adds the diagonals in the fixed order
+// A finished diagonal leaves the registers as one coalesced INT32 store into the workspace; at
+// the end every thread reads its own values back, adds the diagonals in the fixed order
 // least-significant first, applies 2^(EA_i + EB_j) and writes C. When a diagonal is longer
 // than 2^17 products (INT32 could overflow), the registers are flushed into INT64 sums in the
 // workspace every 2^17 products instead (k-blocking, cf. Section 2.4 on splitting long k).
 //
-// Data path per k-chunk of 128: global -> VGPR -> LDS (XOR-swizzled 16-byte columns, so the
-// 16-byte LDS reads of eight consecutive rows hit distinct bank groups) -> v_mfma_i32_32x32x32_i8.
+// Data path: the walk over (diagonal, pair, k) is cut into steps of 64 along k. A step moves
+// global -> LDS directly (global_load_lds_dwordx4, no staging registers; the slice tensors are
+// stored as ready-made LDS images, so every load is a linear run of full 128-byte lines, which
+// keeps the number of requests the vector L1 must track per byte at its minimum) into one of
+// kStages LDS buffers, kStages - 1 steps ahead of the matrix cores, so that an L2 miss has
+// several step times to arrive; LDS -> registers with 16-byte reads, XOR-swizzled so that the
+// 16 lanes the LDS serves per clock hit 16 distinct bank groups; registers ->
+// v_mfma_i32_32x32x32_i8.
 // Each wavefront computes 128 x 128 outputs as 4 x 4 MFMA tiles (256 accumulator registers).
+// The operand fragments are double buffered in registers: while the 16 MFMAs of one 32-wide
+// k-slab run, the fragments of the next slab are read, with one workgroup barrier per step.
 #include "ozimmu_internal.h"
 
 namespace ozimmu {
@@ -23,9 +31,19 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef long long v2l __attribute__((ext_vector_type(2)));
 
-constexpr int kStageBytes = 2 * kTile * kChunk;      // A tile + B tile of one k-chunk
-constexpr int kLdsBytes = 2 * kStageBytes;           // double buffered
-constexpr int kBlockLen = OZIMMU_INT32_BLOCK;
+constexpr int kStepsPerChunk = kChunk / kStep;        // the API counts k in chunks of kChunk
+#ifndef OZ_STAGES
+#define OZ_STAGES 4
+#endif
+constexpr int kStages = OZ_STAGES;                    // LDS buffers
+constexpr int kTileBytes = kBlockBytes;               // one operand tile of one step: 16 KiB
+constexpr int kStageBytes = 2 * kTileBytes;           // A tile + B tile
+constexpr int kLdsBytes = kStages * kStageBytes;
+constexpr int kPairLdsBytes = 128 * kTile * 4;        // staging of the raw INT32 tile in pair mode
+constexpr int kLdsAlloc = kLdsBytes > kPairLdsBytes ? kLdsBytes : kPairLdsBytes;
+constexpr int kBlockSteps = OZIMMU_INT32_BLOCK / kStep;
+constexpr int kLoadsPerStep = 8;                      // direct loads per wavefront and step
+static_assert(kStages >= 3 && kStages <= 5, "vmcnt immediates below assume 3..5 stages");
 
 // Workgroup -> tile. Hardware deals workgroups round-robin over the 8 XCDs (each with its own
 // L2); give every XCD a contiguous run of tiles, ordered in column panels 4 tiles tall so that
@@ -68,8 +86,31 @@ __device__ __forceinline__ int acc_read(int a) {
     return v;
 }
 
-struct Job {  // one k-chunk of one slice pair
-    int d, p, kc;
+// One wavefront-wide direct load: lane i fetches 16 bytes from gbase + voff_i and the hardware
+// writes them to LDS at lds_addr + 16 i (M0 carries the LDS base). Issued as inline assembly so
+// that its completion is awaited only by the explicit vmcnt before the step barrier and not
+// before every LDS read in between.
+__device__ __forceinline__ void dma_load16(const void* gbase, unsigned voff, unsigned lds_addr) {
+    asm volatile(
+        "s_mov_b32 m0, %2\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %0"
+        :
+        : "s"(gbase), "v"(voff), "s"(lds_addr)
+        : "memory");  // M0 is written here; nothing else in this kernel uses it
+}
+
+// Wait until at most (kStages - 2) steps of this wave's direct loads are outstanding (they return
+// in order, so the oldest step has landed) and until its own LDS reads are done, then meet the
+// other waves.
+__device__ __forceinline__ void publish_barrier() {
+    if (kStages == 3) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else if (kStages == 4) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(24) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+struct Job {  // one k-step of one slice pair
+    int d, p, ks;
 };
 
 template <bool WIDE>
@@ -79,7 +120,7 @@ void slice_gemm_kernel(const GemmArgs g) {
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
     const int wm = wave >> 1, wn = wave & 1;
 
     int tm, tn;
@@ -90,68 +131,79 @@ void slice_gemm_kernel(const GemmArgs g) {
     const bool pair_mode = g.pair_p > 0;
     const int d_first = pair_mode ? g.pair_p + g.pair_q : g.num_slices + 1;
     const int d_last = pair_mode ? d_first : 2;
+    const int ks_begin = g.kc_begin * kStepsPerChunk, ks_end = g.kc_end * kStepsPerChunk;
 
-    // global -> LDS staging: 8 x 16 B of the A tile and 8 x 16 B of the B tile per thread.
-    // Addresses are a wave-uniform 64-bit base plus a 32-bit lane offset (scalar-base addressing).
-    const int ld_row = tid >> 3;                 // + 32 * i
-    const int ld_col = tid & 7;                  // 16-byte column inside the 128-byte chunk row
-    const unsigned ld_lane_off = (unsigned)ld_row * (unsigned)g.k_pad + (unsigned)ld_col * 16u;
-    const int8_t* a_tile = g.SA + (int64_t)tm * kTile * g.k_pad;
-    const int8_t* b_tile = g.SB + (int64_t)tn * kTile * g.k_pad;
-    const int st_off = ld_row * kChunk + ((ld_col ^ (ld_row & 7)) << 4);
+    // global -> LDS. The slice tensors are stored in blocks of 256 rows x 64 bytes that already
+    // are the LDS image of one operand tile of one step (16-byte columns swizzled with bits 2..3
+    // of the row: the LDS of gfx950 serves 16 lanes x 16 bytes per clock from 64 banks, and with
+    // this swizzle the 16 rows a ds_read_b128 reads together fall into 16 distinct bank groups).
+    // A wave-wide direct load copies 1 KiB; wave w copies bytes [4096 w, 4096 w + 4096) of the A
+    // block and of the B block (4 loads each), every load a run of eight full 128-byte lines.
+    const unsigned ld_lane_off = (unsigned)lane * 16u;
+    const int64_t steps_total = g.k_pad / kStep;
+    const int8_t* a_tile = g.SA + (int64_t)tm * steps_total * kBlockBytes + wave * 4096;
+    const int8_t* b_tile = g.SB + (int64_t)tn * steps_total * kBlockBytes + wave * 4096;
+    const unsigned lds_base = (unsigned)(unsigned long)(__attribute__((address_space(3))) unsigned char*)lds;
+    const unsigned ld_lds_off = lds_base + (unsigned)wave * 4096u;
 
     // LDS -> MFMA operands: lane reads row (lane % 32) of a 32-row block, 16-byte column 2 kk + lane / 32
     const int rd_row = lane & 31;
     const int rd_half = lane >> 5;
-    const int a_rd = (wm * 128 + rd_row) * kChunk;
-    const int b_rd = kTile * kChunk + (wn * 128 + rd_row) * kChunk;
-    const int rd_sw = lane & 7;
+    const int a_rd = (wm * 128 + rd_row) * kStep;
+    const int b_rd = kTileBytes + (wn * 128 + rd_row) * kStep;
+    const int rd_sw = (lane >> 2) & 3;
 
-    v4i stage_a[8], stage_b[8];
     const unsigned lane_off16 = (unsigned)tid * 16u;
 
-    auto gload = [&](const Job& jb) {
-        const int8_t* pa = a_tile + (int64_t)(jb.p - 1) * g.a_slice_stride + (int64_t)jb.kc * kChunk;
-        const int8_t* pb = b_tile + (int64_t)(jb.d - jb.p - 1) * g.b_slice_stride + (int64_t)jb.kc * kChunk;
+    auto issue_loads = [&](const Job& jb, int buf) {
+        const int8_t* pa = a_tile + (int64_t)(jb.p - 1) * g.a_slice_stride + (int64_t)jb.ks * kBlockBytes;
+        const int8_t* pb = b_tile + (int64_t)(jb.d - jb.p - 1) * g.b_slice_stride + (int64_t)jb.ks * kBlockBytes;
+        const unsigned la = ld_lds_off + (unsigned)buf * kStageBytes;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            stage_a[i] = *reinterpret_cast<const v4i*>(pa + (int64_t)i * 32 * g.k_pad + ld_lane_off);
-            stage_b[i] = *reinterpret_cast<const v4i*>(pb + (int64_t)i * 32 * g.k_pad + ld_lane_off);
+        for (int i = 0; i < kLoadsPerStep / 2; ++i) {
+            dma_load16(pa + i * 1024, ld_lane_off, la + i * 1024);
+            dma_load16(pb + i * 1024, ld_lane_off, la + kTileBytes + i * 1024);
         }
     };
-    auto lstore = [&](int buf) {
-        unsigned char* base = lds + buf * kStageBytes + st_off;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            *reinterpret_cast<v4i*>(base + i * 32 * kChunk) = stage_a[i];
-            *reinterpret_cast<v4i*>(base + kTile * kChunk + i * 32 * kChunk) = stage_b[i];
-        }
-    };
-    auto compute = [&](v16i (&acc)[4][4], int buf) {
+    auto read_frags = [&](v4i (&a)[4], v4i (&b)[4], int buf, int kk) {
         const unsigned char* base = lds + buf * kStageBytes;
+        const int col = (((kk << 1) | rd_half) ^ rd_sw) << 4;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int col = (((kk << 1) | rd_half) ^ rd_sw) << 4;
-            v4i a[4], b[4];
+        for (int i = 0; i < 4; ++i) {
+            a[i] = *reinterpret_cast<const v4i*>(base + a_rd + i * 32 * kStep + col);
+            b[i] = *reinterpret_cast<const v4i*>(base + b_rd + i * 32 * kStep + col);
+        }
+    };
+    auto mfma16 = [&](v16i (&acc)[4][4], const v4i (&a)[4], const v4i (&b)[4]) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                a[i] = *reinterpret_cast<const v4i*>(base + a_rd + i * 32 * kChunk + col);
-                b[i] = *reinterpret_cast<const v4i*>(base + b_rd + i * 32 * kChunk + col);
-            }
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+    };
+    // 8 LDS reads spread over 16 MFMAs
+    auto interleave = [&]() {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int x = 0; x < 8; ++x) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 DS read
         }
     };
     auto advance = [&](Job& jb) -> bool {  // false when the walk is over
-        if (++jb.kc < g.kc_end) return true;
-        jb.kc = g.kc_begin;
+        if (++jb.ks < ks_end) return true;
+        jb.ks = ks_begin;
         if (!pair_mode && ++jb.p < jb.d) return true;
         --jb.d;
         jb.p = 1;
         return jb.d >= d_last;
+    };
+    // At the end of the walk the iterator stops advancing and the last step is simply loaded
+    // again into a buffer nobody reads any more: the number of loads in flight stays the same in
+    // every step, which is what the vmcnt in publish_barrier() counts on, and the loop body needs
+    // no branch around the loads.
+    auto advance_clamped = [&](Job& jb) {
+        Job cand = jb;
+        if (advance(cand)) jb = cand;
     };
 
     // INT32 registers -> workspace (narrow: plain store of a finished diagonal)
@@ -210,6 +262,7 @@ void slice_gemm_kernel(const GemmArgs g) {
     auto write_pair = [&](v16i (&acc)[4][4]) {
         int* tile = reinterpret_cast<int*>(lds);  // [128][256] INT32 = 128 KiB
         const unsigned tbase = (unsigned)(4 * rd_half * kTile + wn * 128 + rd_row) + opaque_zero();
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");  // no direct load may still land here
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             if (wm == half) {
@@ -218,8 +271,7 @@ void slice_gemm_kernel(const GemmArgs g) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                        {
+                        for (int r = 0; r < 16; ++r) {
                             tile[tbase + (i * 32 + 8 * (r >> 2) + (r & 3)) * kTile + j * 32] = acc_read(acc[i][j][r]);
                             if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
                         }
@@ -291,52 +343,66 @@ void slice_gemm_kernel(const GemmArgs g) {
         }
     };
 
-    Job cur = {d_first, pair_mode ? g.pair_p : 1, g.kc_begin};
-    gload(cur);
-    lstore(0);
-    __syncthreads();
+    // Pipeline prologue: steps 0 .. kStages-1 are requested, step 0 is awaited and published.
+    Job nxt = {d_first, pair_mode ? g.pair_p : 1, ks_begin};   // last step requested
+    issue_loads(nxt, 0);
+#pragma unroll
+    for (int b = 1; b < kStages; ++b) {
+        advance_clamped(nxt);
+        issue_loads(nxt, b);
+    }
+    if (kStages == 3) asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+    else if (kStages == 4) asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(32)\n\ts_barrier" ::: "memory");
+    v4i fa0[4], fb0[4], fa1[4], fb1[4];
+    read_frags(fa0, fb0, 0, 0);
 
-    // The walk over (diagonal, pair, k-chunk) is one software pipeline: while chunk t is in the
-    // matrix cores, chunk t+1 (possibly of the next pair or diagonal) travels global -> LDS.
-    const int nkc = g.kc_end - g.kc_begin;
-    int buf = 0;
-    bool more = true;
-    auto run_chunks = [&](v16i (&acc)[4][4], int count) {
+    const int nks = ks_end - ks_begin;
+    int buf = 0;   // LDS buffer of the step in the matrix cores
+    auto run_steps = [&](v16i (&acc)[4][4], int count) {
         int t = 0;
         do {
-            Job nxt = cur;
-            more = advance(nxt);
-            if (more) gload(nxt);
-            compute(acc, buf);
-            if (more) lstore(buf ^ 1);
-            __syncthreads();
-            buf ^= 1;
-            cur = nxt;
+            read_frags(fa1, fb1, buf, 1);
+            mfma16(acc, fa0, fb0);
+            interleave();
+            // Every wave has read its last fragments of this buffer and its direct loads of the
+            // next step have landed: publish, then refill the released buffer with the step that
+            // is kStages ahead.
+            publish_barrier();
+            advance_clamped(nxt);
+            issue_loads(nxt, buf);
+            buf = buf + 1 == kStages ? 0 : buf + 1;
+            read_frags(fa0, fb0, buf, 0);
+            mfma16(acc, fa1, fb1);
+            interleave();
         } while (++t < count);
     };
 
     for (int d = d_first; d >= d_last; --d) {
-        int jobs = pair_mode ? nkc : (d - 1) * nkc;
+        int jobs = pair_mode ? nks : (d - 1) * nks;
         if (WIDE) {
             // at most 2^17 products per output element may share one INT32 sum
             bool fresh = true;
             do {
-                const int run = jobs > kBlockLen / kChunk ? kBlockLen / kChunk : jobs;
+                const int run = jobs > kBlockSteps ? kBlockSteps : jobs;
                 jobs -= run;
                 v16i acc[4][4];
                 zero_acc(acc);
-                run_chunks(acc, run);
+                run_steps(acc, run);
                 flush_diag64(acc, d, fresh);
                 fresh = false;
             } while (jobs > 0);
         } else {
             v16i acc[4][4];
             zero_acc(acc);
-            run_chunks(acc, jobs);
+            run_steps(acc, jobs);
             if (pair_mode) write_pair(acc);
             else store_diag32(acc, d);
         }
     }
+    // direct loads of the clamped tail may still be in flight: they must land before this
+    // workgroup's LDS can be handed to another one
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (WIDE) final_wide();
     else if (!pair_mode) final_narrow();
 }
@@ -349,14 +415,14 @@ hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st) {
     hipError_t e;
     if (wide) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&slice_gemm_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsAlloc);
         if (e != hipSuccess) return e;
-        slice_gemm_kernel<true><<<dim3(blocks), dim3(256), kLdsBytes, st>>>(args);
+        slice_gemm_kernel<true><<<dim3(blocks), dim3(256), kLdsAlloc, st>>>(args);
     } else {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&slice_gemm_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsAlloc);
         if (e != hipSuccess) return e;
-        slice_gemm_kernel<false><<<dim3(blocks), dim3(256), kLdsBytes, st>>>(args);
+        slice_gemm_kernel<false><<<dim3(blocks), dim3(256), kLdsAlloc, st>>>(args);
     }
     return hipGetLastError();
 }

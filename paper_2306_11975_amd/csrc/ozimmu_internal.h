@@ -9,18 +9,20 @@
 namespace ozimmu {
 
 constexpr int kTile = 256;          // macro tile edge in rows of A / rows of B^T (= OZIMMU_ROW_ALIGN)
-constexpr int kChunk = 128;         // k-extent of one LDS stage in bytes (= OZIMMU_K_ALIGN)
+constexpr int kChunk = 128;         // granularity of k in the API (= OZIMMU_K_ALIGN)
+constexpr int kStep = 64;           // k-extent of one contiguous slice block and of one pipeline step (= OZIMMU_K_STEP)
+constexpr int kBlockBytes = kTile * kStep;  // one block of a slice tensor: 256 rows x 64 bytes
 constexpr int kTileElems = kTile * kTile;
 
 static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 // Arguments of the slice-product kernel. One launch covers every macro tile of C.
 struct GemmArgs {
-    const int8_t* SA;      // padded slices of A:   [slice][m_pad][k_pad]
-    const int8_t* SB;      // padded slices of B^T: [slice][n_pad][k_pad]
+    const int8_t* SA;      // slice tensor of A   (tiled layout, see ozimmu.h)
+    const int8_t* SB;      // slice tensor of B^T
     int64_t a_slice_stride;  // bytes between consecutive slices of A
     int64_t b_slice_stride;
-    int k_pad;             // bytes per slice row
+    int k_pad;             // padded row length
     int tiles_m, tiles_n;
     int m, n;              // true extent of C
     int num_slices;        // full mode: diagonals num_slices+1 .. 2

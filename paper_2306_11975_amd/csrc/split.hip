@@ -2,9 +2,9 @@
 //
 // One power-of-two exponent per row of M = A or B^T (line 2 of SplitInt), then every element
 // is cut by bit operations (Section 4.1) into signed 7-bit chunks of its significand, placed
-// relative to the row exponent (lines 3-5). Output: padded INT8 slice tensors
-// [slice][rows_padded][k_padded], k contiguous, zero outside the matrix, which is the layout the
-// slice-product kernel streams into LDS without bounds checks.
+// relative to the row exponent (lines 3-5). Output: padded INT8 slice tensors, zero outside the
+// matrix, in the tiled and column-swizzled block layout that the slice-product kernel copies
+// linearly into LDS (blocks of 256 rows x 64 bytes; the layout is defined with the C ABI).
 //
 // Both kernels are HBM-bound: 8 B read per element (16 B for B, whose column maxima need a
 // pass of their own) and num_slices bytes written.
@@ -51,6 +51,14 @@ __device__ __forceinline__ int chunk(const Prepared& x, int p) {
     return x.neg ? -(int)c : (int)c;
 }
 
+// Byte offset, inside one slice, of the 4-byte word that holds positions l0 .. l0+3 (l0 % 4 == 0)
+// of padded row r: blocks of 256 rows x 64 bytes, 16-byte columns swizzled with bits 2..3 of the row.
+__device__ __forceinline__ int64_t word_offset(int64_t r, int64_t l0, int64_t k_pad) {
+    const int64_t rr = r & (kTile - 1);
+    const int64_t c = (l0 & (kStep - 1)) >> 4;
+    return ((r / kTile) * (k_pad / kStep) + l0 / kStep) * kBlockBytes + rr * kStep + ((c ^ ((rr >> 2) & 3)) << 4) + (l0 & 15);
+}
+
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -71,12 +79,13 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const double* __restric
     const int row = blockIdx.x;
     const int tid = threadIdx.x;
     const int64_t slice_stride = m_pad * k_pad;
-    uint32_t* out_row = reinterpret_cast<uint32_t*>(S + (int64_t)row * k_pad);
     const int64_t words = k_pad / 4;
 
     if (row >= m) {  // padding rows: zeros in every slice
-        for (int p = 0; p < s; ++p)
-            for (int64_t w = tid; w < words; w += 256) out_row[p * (slice_stride / 4) + w] = 0u;
+        for (int64_t w = tid; w < words; w += 256) {
+            const int64_t off = word_offset(row, w * 4, k_pad);
+            for (int p = 0; p < s; ++p) *reinterpret_cast<uint32_t*>(S + p * slice_stride + off) = 0u;
+        }
         return;
     }
 
@@ -104,11 +113,12 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const double* __restric
             unsigned long long b = (l0 + u < k) ? src[(l0 + u) * inc] : 0ull;
             x[u] = prepare(b, E);
         }
+        const int64_t off = word_offset(row, l0, k_pad);
         for (int p = 1; p <= s; ++p) {
             uint32_t packed = 0;
 #pragma unroll
             for (int u = 0; u < 4; ++u) packed |= ((uint32_t)chunk(x[u], p) & 0xffu) << (8 * u);
-            out_row[(int64_t)(p - 1) * (slice_stride / 4) + w] = packed;
+            *reinterpret_cast<uint32_t*>(S + (int64_t)(p - 1) * slice_stride + off) = packed;
         }
     }
 }
@@ -184,15 +194,24 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
             }
         }
         __syncthreads();
-        // 64 rows x 32 words per slice; lanes run along l
+        // Write-out: per slice the tile is 2 k-steps x 64 rows x four 16-byte columns; in the
+        // block layout 16 consecutive rows of one k-step are 1 KiB contiguous, so consecutive
+        // lanes store consecutive 16-byte columns.
         for (int pp = 0; pp < np; ++pp) {
-            uint32_t* dst = reinterpret_cast<uint32_t*>(S + (int64_t)(p0 + pp - 1) * slice_stride);
+            int8_t* dst = S + (int64_t)(p0 + pp - 1) * slice_stride;
 #pragma unroll
-            for (int it = 0; it < (kColTileJ * 32) / 256; ++it) {
-                const int idx = it * 256 + tid;
-                const int r = idx >> 5, w = idx & 31;
+            for (int it = 0; it < 2; ++it) {
+                const int unit = it * 256 + tid;       // 0..511
+                const int ks2 = unit >> 8;              // k-step inside the tile
+                const int r = (unit >> 2) & 63;         // row inside the tile
+                const int pc = unit & 3;                // physical 16-byte column
                 const int64_t jr = (int64_t)blockIdx.x * kColTileJ + r;
-                dst[(jr * k_pad + lbase) / 4 + w] = tile[pp][r][w];
+                const int rr = (int)(jr & (kTile - 1));
+                const int c = pc ^ ((rr >> 2) & 3);     // logical column stored there
+                const int w0 = ks2 * 16 + c * 4;        // first word of that column in the LDS row
+                uint4 v = {tile[pp][r][w0], tile[pp][r][w0 + 1], tile[pp][r][w0 + 2], tile[pp][r][w0 + 3]};
+                const int64_t off = ((jr / kTile) * (k_pad / kStep) + (lbase / kStep + ks2)) * kBlockBytes + rr * kStep + pc * 16;
+                *reinterpret_cast<uint4*>(dst + off) = v;
             }
         }
         __syncthreads();

@@ -15,11 +15,12 @@ OK = 0
 MAX_SLICES = 16
 ROW_ALIGN = 256
 K_ALIGN = 128
+K_STEP = 64
 INT32_BLOCK = 131072
 WORKSPACE_ALIGN = 256
 
 EXPORTS = (
-    "ozimmu_status_string", "ozimmu_slice_geometry", "ozimmu_split_rows", "ozimmu_split_cols",
+    "ozimmu_status_string", "ozimmu_slice_geometry", "ozimmu_slice_offset", "ozimmu_split_rows", "ozimmu_split_cols",
     "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_stage",
 )
 
@@ -46,6 +47,8 @@ def lib() -> ctypes.CDLL:
         L.ozimmu_status_string.argtypes = [i32]
         L.ozimmu_slice_geometry.restype = i32
         L.ozimmu_slice_geometry.argtypes = [i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.ozimmu_slice_offset.restype = i64
+        L.ozimmu_slice_offset.argtypes = [i64, i64, i32, i64, i64]
         L.ozimmu_split_rows.restype = i32
         L.ozimmu_split_rows.argtypes = [i64, i64, vp, i64, i32, vp, vp, vp]
         L.ozimmu_split_cols.restype = i32
@@ -89,6 +92,35 @@ def slice_geometry(rows: int, k: int):
     rp, kp = ctypes.c_int64(), ctypes.c_int64()
     _check(lib().ozimmu_slice_geometry(rows, k, ctypes.byref(rp), ctypes.byref(kp)))
     return rp.value, kp.value
+
+
+def slice_offset(rows_padded: int, k_padded: int, slice_: int, row: int, l: int) -> int:
+    return int(lib().ozimmu_slice_offset(rows_padded, k_padded, slice_, row, l))
+
+
+def unpack_slices(raw, num_slices: int, rows: int, k: int):
+    """Re-order the bytes of a slice tensor (as the library stores it, any 1-D or N-D int8 numpy
+    array of num_slices * rows_padded * k_padded elements) into a plain [slice][row][l] numpy
+    array of the padded shape. Pure index permutation: the block geometry is queried from the
+    library through ozimmu_slice_offset, no arithmetic of the method happens here."""
+    import numpy as np
+
+    rp, kp = slice_geometry(rows, k)
+    flat = np.ascontiguousarray(raw).reshape(-1)
+    assert flat.size == num_slices * rp * kp
+    if flat.size == 0:
+        return flat.reshape(num_slices, rp, kp)
+    # offsets are separable: offset(s, r, l) = s * rp * kp + f(r, 0) + g(r % 256, l)
+    row_part = np.array([slice_offset(rp, kp, 0, r, 0) for r in range(0, rp, ROW_ALIGN)], dtype=np.int64)
+    in_block = np.array([[slice_offset(rp, kp, 0, rr, l) for l in range(K_STEP)] for rr in range(ROW_ALIGN)],
+                        dtype=np.int64)                      # [256][64], block 0
+    step_part = np.array([slice_offset(rp, kp, 0, 0, l) for l in range(0, kp, K_STEP)], dtype=np.int64)
+    idx = (row_part[:, None, None, None] + in_block[None, :, None, :] + step_part[None, None, :, None])
+    idx = idx.reshape(rp, kp)                                # [row][l]
+    out = np.empty((num_slices, rp, kp), dtype=flat.dtype)
+    for s_ in range(num_slices):
+        out[s_] = flat[s_ * rp * kp + idx]
+    return out
 
 
 def workspace_bytes(m: int, n: int, k: int, num_slices: int, is_complex: bool = False) -> int:

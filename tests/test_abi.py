@@ -48,6 +48,25 @@ def test_geometry_and_workspace_size():
     assert ozimmu.workspace_bytes(64, 64, 64, 3, True) > ozimmu.workspace_bytes(64, 64, 64, 3, False)
 
 
+def test_slice_offset_is_a_bijection_with_contiguous_blocks():
+    import numpy as np
+
+    rp, kp = ozimmu.slice_geometry(300, 200)   # 512 x 256
+    offs = np.array([[ozimmu.slice_offset(rp, kp, 0, r, l) for l in range(kp)] for r in range(rp)])
+    assert sorted(offs.reshape(-1).tolist()) == list(range(rp * kp))
+    # a block of 256 rows x 64 positions is one contiguous 16 KiB run; 16 bytes stay together
+    blk = offs[256:512, 64:128]
+    assert blk.min() == (1 * (kp // 64) + 1) * 16384 and blk.max() == blk.min() + 16383
+    assert (np.diff(offs[:, :16], axis=1) == 1).all()
+    assert ozimmu.slice_offset(rp, kp, 2, 0, 0) == 2 * rp * kp
+    assert ozimmu.slice_offset(rp, kp, 0, rp, 0) == -1 and ozimmu.slice_offset(rp, kp, 0, 0, kp) == -1
+    # unpack_slices inverts it
+    raw = np.zeros(2 * rp * kp, dtype=np.int8)
+    raw[ozimmu.slice_offset(rp, kp, 1, 299, 199)] = 5
+    un = ozimmu.unpack_slices(raw, 2, 300, 200)
+    assert un[1, 299, 199] == 5 and np.count_nonzero(un) == 1
+
+
 def test_argument_errors_are_reported_before_any_launch():
     L = ozimmu.lib()
     out = ctypes.c_size_t()

@@ -32,7 +32,7 @@ def gpu_split_rows(A, s):
     E = torch.full((max(m, 1),), -12345, dtype=torch.int32, device=DEV)
     ozimmu.split_rows(dev(A), s, S, E)
     torch.cuda.synchronize()
-    return E.cpu().numpy()[:m], S.cpu().numpy(), S
+    return E.cpu().numpy()[:m], ozimmu.unpack_slices(S.cpu().numpy(), s, m, k), S
 
 
 def gpu_split_cols(B, s):
@@ -43,7 +43,7 @@ def gpu_split_cols(B, s):
     scratch = torch.empty(max(npad, 1), dtype=torch.int64, device=DEV)
     ozimmu.split_cols(dev(B), s, S, E, scratch)
     torch.cuda.synchronize()
-    return E.cpu().numpy()[:n], S.cpu().numpy(), S
+    return E.cpu().numpy()[:n], ozimmu.unpack_slices(S.cpu().numpy(), s, n, k), S
 
 
 def gpu_dgemm(A, B, s, ldc_extra=0):
@@ -108,13 +108,15 @@ def test_split_respects_leading_dimension():
     E = torch.zeros(50, dtype=torch.int32, device=DEV)
     ozimmu.split_rows(t, s, S, E)
     Eo, So = oracle.split_rows(view, s)
-    assert np.array_equal(E.cpu().numpy(), Eo) and np.array_equal(S.cpu().numpy()[:, :50, :140], So)
+    assert np.array_equal(E.cpu().numpy(), Eo)
+    assert np.array_equal(ozimmu.unpack_slices(S.cpu().numpy(), s, 50, 140)[:, :50, :140], So)
     npad, kp = ozimmu.slice_geometry(140, 50)
     S = torch.zeros((s, npad, kp), dtype=torch.int8, device=DEV)
     E = torch.zeros(140, dtype=torch.int32, device=DEV)
     ozimmu.split_cols(t, s, S, E, torch.empty(npad, dtype=torch.int64, device=DEV))
     Eo, So = oracle.split_cols(view, s)
-    assert np.array_equal(E.cpu().numpy(), Eo) and np.array_equal(S.cpu().numpy()[:, :140, :50], So)
+    assert np.array_equal(E.cpu().numpy(), Eo)
+    assert np.array_equal(ozimmu.unpack_slices(S.cpu().numpy(), s, 140, 50)[:, :140, :50], So)
 
 
 # ------------------------------------------------------------------ INT32 slice products
