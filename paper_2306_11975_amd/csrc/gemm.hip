@@ -109,6 +109,13 @@ __device__ __forceinline__ void publish_barrier() {
     else asm volatile("s_waitcnt vmcnt(24) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+#ifdef OZ_TRACE
+__device__ long long oz_trace[8192];
+#define OZ_T(i) do { if (trace_on && trace_n < 2040) { oz_trace[trace_n * 4 + (i)] = clock64(); } } while (0)
+#else
+#define OZ_T(i) do { } while (0)
+#endif
+
 struct Job {  // one k-step of one slice pair
     int d, p, ks;
 };
@@ -155,39 +162,43 @@ void slice_gemm_kernel(const GemmArgs g) {
 
     const unsigned lane_off16 = (unsigned)tid * 16u;
 
-    auto issue_loads = [&](const Job& jb, int buf) {
-        const int8_t* pa = a_tile + (int64_t)(jb.p - 1) * g.a_slice_stride + (int64_t)jb.ks * kBlockBytes;
-        const int8_t* pb = b_tile + (int64_t)(jb.d - jb.p - 1) * g.b_slice_stride + (int64_t)jb.ks * kBlockBytes;
-        const unsigned la = ld_lds_off + (unsigned)buf * kStageBytes;
+    // One direct load of a step: `which` = 0..3 copies KiB `which` of this wave's share of the A
+    // block, 4..7 the same of the B block.
+    auto issue_load = [&](const Job& jb, int buf, int which) {
+        const int i = which & 3;
+        if (which < 4) {
+            const int8_t* pa = a_tile + (int64_t)(jb.p - 1) * g.a_slice_stride + (int64_t)jb.ks * kBlockBytes;
+            dma_load16(pa + i * 1024, ld_lane_off, ld_lds_off + (unsigned)buf * kStageBytes + i * 1024);
+        } else {
+            const int8_t* pb = b_tile + (int64_t)(jb.d - jb.p - 1) * g.b_slice_stride + (int64_t)jb.ks * kBlockBytes;
+            dma_load16(pb + i * 1024, ld_lane_off, ld_lds_off + (unsigned)buf * kStageBytes + kTileBytes + i * 1024);
+        }
+    };
+    auto issue_loads = [&](const Job& jb, int buf, int first, int last) {
 #pragma unroll
-        for (int i = 0; i < kLoadsPerStep / 2; ++i) {
-            dma_load16(pa + i * 1024, ld_lane_off, la + i * 1024);
-            dma_load16(pb + i * 1024, ld_lane_off, la + kTileBytes + i * 1024);
+        for (int w = first; w < last; ++w) issue_load(jb, buf, w);
+    };
+    // Fragment reads of one 32-wide k-slab, two per call, in the order the next slab's MFMAs
+    // need them: B fragments 0..3 first, then A fragments 0..3.
+    auto read_two = [&](v4i (&a)[4], v4i (&b)[4], int buf, int kk, int part) {
+        const unsigned char* base = lds + buf * kStageBytes;
+        const int col = (((kk << 1) | rd_half) ^ rd_sw) << 4;
+        if (part < 2) {
+            b[2 * part] = *reinterpret_cast<const v4i*>(base + b_rd + (2 * part) * 32 * kStep + col);
+            b[2 * part + 1] = *reinterpret_cast<const v4i*>(base + b_rd + (2 * part + 1) * 32 * kStep + col);
+        } else {
+            a[2 * part - 4] = *reinterpret_cast<const v4i*>(base + a_rd + (2 * part - 4) * 32 * kStep + col);
+            a[2 * part - 3] = *reinterpret_cast<const v4i*>(base + a_rd + (2 * part - 3) * 32 * kStep + col);
         }
     };
     auto read_frags = [&](v4i (&a)[4], v4i (&b)[4], int buf, int kk) {
-        const unsigned char* base = lds + buf * kStageBytes;
-        const int col = (((kk << 1) | rd_half) ^ rd_sw) << 4;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            a[i] = *reinterpret_cast<const v4i*>(base + a_rd + i * 32 * kStep + col);
-            b[i] = *reinterpret_cast<const v4i*>(base + b_rd + i * 32 * kStep + col);
-        }
+        for (int part = 0; part < 4; ++part) read_two(a, b, buf, kk, part);
     };
-    auto mfma16 = [&](v16i (&acc)[4][4], const v4i (&a)[4], const v4i (&b)[4]) {
+    auto mfma_row = [&](v16i (&acc)[4][4], const v4i (&a)[4], const v4i (&b)[4], int i) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
-    };
-    // 8 LDS reads spread over 16 MFMAs
-    auto interleave = [&]() {
-#pragma unroll
-        for (int x = 0; x < 8; ++x) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 DS read
-        }
+        for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
     };
     auto advance = [&](Job& jb) -> bool {  // false when the walk is over
         if (++jb.ks < ks_end) return true;
@@ -343,38 +354,65 @@ void slice_gemm_kernel(const GemmArgs g) {
         }
     };
 
-    // Pipeline prologue: steps 0 .. kStages-1 are requested, step 0 is awaited and published.
+    // Pipeline prologue: steps 0 .. kStages-2 are requested in full and the A half of step
+    // kStages-1; step 0 is awaited and published.
     Job nxt = {d_first, pair_mode ? g.pair_p : 1, ks_begin};   // last step requested
-    issue_loads(nxt, 0);
+    issue_loads(nxt, 0, 0, 8);
 #pragma unroll
     for (int b = 1; b < kStages; ++b) {
         advance_clamped(nxt);
-        issue_loads(nxt, b);
+        issue_loads(nxt, b, 0, b == kStages - 1 ? 4 : 8);
     }
-    if (kStages == 3) asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
-    else if (kStages == 4) asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(32)\n\ts_barrier" ::: "memory");
+    if (kStages == 3) asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
+    else if (kStages == 4) asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(28)\n\ts_barrier" ::: "memory");
     v4i fa0[4], fb0[4], fa1[4], fb1[4];
     read_frags(fa0, fb0, 0, 0);
 
     const int nks = ks_end - ks_begin;
-    int buf = 0;   // LDS buffer of the step in the matrix cores
+    int buf = 0;                // LDS buffer of the step in the matrix cores
+    int prev = kStages - 1;     // the buffer released at the previous barrier
+#ifdef OZ_TRACE
+    const bool trace_on = blockIdx.x == 8 && tid == 0;
+    int trace_n = 0;
+#endif
+    // One step = 32 MFMAs in 8 blocks of 4. Every block also reads two fragments of the next
+    // slab and issues ONE direct load: the texture-address unit takes about 18 cycles per
+    // wave-wide 1 KiB load and a wave stalls at issue while it is busy, so the 32 loads a step
+    // needs from the four waves are spread evenly over the step instead of being issued in a
+    // burst after the barrier. The B half of a step's loads is therefore issued one phase
+    // later than its A half, into the buffer released at the previous barrier.
     auto run_steps = [&](v16i (&acc)[4][4], int count) {
         int t = 0;
         do {
-            read_frags(fa1, fb1, buf, 1);
-            mfma16(acc, fa0, fb0);
-            interleave();
+            OZ_T(0);
+#pragma unroll
+            for (int blk = 0; blk < 4; ++blk) {
+                read_two(fa1, fb1, buf, 1, blk);
+                mfma_row(acc, fa0, fb0, blk);
+                issue_load(nxt, prev, 4 + blk);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            OZ_T(1);
             // Every wave has read its last fragments of this buffer and its direct loads of the
-            // next step have landed: publish, then refill the released buffer with the step that
-            // is kStages ahead.
+            // next step have landed: publish, then start refilling the released buffer with the
+            // step that is kStages ahead.
             publish_barrier();
+            OZ_T(2);
             advance_clamped(nxt);
-            issue_loads(nxt, buf);
+            prev = buf;
             buf = buf + 1 == kStages ? 0 : buf + 1;
-            read_frags(fa0, fb0, buf, 0);
-            mfma16(acc, fa1, fb1);
-            interleave();
+#pragma unroll
+            for (int blk = 0; blk < 4; ++blk) {
+                read_two(fa0, fb0, buf, 0, blk);
+                mfma_row(acc, fa1, fb1, blk);
+                issue_load(nxt, prev, blk);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            OZ_T(3);
+#ifdef OZ_TRACE
+            ++trace_n;
+#endif
         } while (++t < count);
     };
 
@@ -408,6 +446,12 @@ void slice_gemm_kernel(const GemmArgs g) {
 }
 
 }  // namespace
+
+#ifdef OZ_TRACE
+extern "C" int ozimmu_debug_trace(long long* host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(oz_trace), sizeof(long long) * n);
+}
+#endif
 
 hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st) {
     const int blocks = args.tiles_m * args.tiles_n;
