@@ -1,7 +1,7 @@
 // Slice products on the CDNA4 INT8 matrix cores with the FP64 sum fused in
 // (lines 4-9 of the IMMU algorithm, Section 3.1).
 //
-// One workgroup (4 wavefronts) owns a 256 x 256 tile of C for the whole computation. It walks
+// One workgroup (8 wavefronts, two per SIMD) owns a 256 x 256 tile of C for the whole computation. It walks
 // the anti-diagonals d = s+1 .. 2 and, inside a diagonal, the pairs (p, d-p) and the k-steps,
 // accumulating everything that shares the scale 2^(-7d) into the same INT32 registers
 // (integer addition is exact, so a diagonal is one long INT8 dot product of length (d-1) k).
@@ -19,9 +19,11 @@
 // several step times to arrive; LDS -> registers with 16-byte reads, XOR-swizzled so that the
 // 16 lanes the LDS serves per clock hit 16 distinct bank groups; registers ->
 // v_mfma_i32_32x32x32_i8.
-// Each wavefront computes 128 x 128 outputs as 4 x 4 MFMA tiles (256 accumulator registers).
-// The operand fragments are double buffered in registers: while the 16 MFMAs of one 32-wide
-// k-slab run, the fragments of the next slab are read, with one workgroup barrier per step.
+// Each wavefront computes 128 x 64 outputs as 4 x 2 MFMA tiles (128 accumulator registers), so
+// that two wavefronts fit on a SIMD: whenever one of them waits (at the barrier, for LDS, or at
+// the issue of a direct load while the texture-address unit is busy) the other one keeps the
+// matrix core fed. The operand fragments are double buffered in registers: while the MFMAs of
+// one 32-wide k-slab run, the fragments of the next slab are read; one barrier per step.
 #include "ozimmu_internal.h"
 
 namespace ozimmu {
@@ -42,8 +44,20 @@ constexpr int kLdsBytes = kStages * kStageBytes;
 constexpr int kPairLdsBytes = 128 * kTile * 4;        // staging of the raw INT32 tile in pair mode
 constexpr int kLdsAlloc = kLdsBytes > kPairLdsBytes ? kLdsBytes : kPairLdsBytes;
 constexpr int kBlockSteps = OZIMMU_INT32_BLOCK / kStep;
-constexpr int kLoadsPerStep = 8;                      // direct loads per wavefront and step
-static_assert(kStages >= 3 && kStages <= 5, "vmcnt immediates below assume 3..5 stages");
+#ifndef OZ_WAVES_N
+#define OZ_WAVES_N 4
+#endif
+constexpr int kWavesM = 2, kWavesN = OZ_WAVES_N;      // wavefront grid inside the workgroup
+constexpr int kWaves = kWavesM * kWavesN;
+constexpr int kThreads = 64 * kWaves;
+constexpr int kTM = kTile / kWavesM / 32;             // 32x32 MFMA tiles per wavefront along m (4)
+constexpr int kTN = kTile / kWavesN / 32;             // ... along n (2)
+constexpr int kWaveShare = kBlockBytes / kWaves;      // bytes of each operand block a wavefront copies per step
+constexpr int kLoadsPerOperand = kWaveShare / 1024;   // wave-wide 1 KiB direct loads per operand and step
+constexpr int kLoadsPerStep = 2 * kLoadsPerOperand;   // direct loads per wavefront and step
+constexpr int kGroups = kTM * kTN * 4;                // 16-byte groups of accumulators per thread
+static_assert(kStages >= 3 && kStages <= 5, "LDS budget");
+static_assert(kTM % kLoadsPerOperand == 0, "one load per kTM / kLoadsPerOperand MFMA rows");
 
 // Workgroup -> tile. Hardware deals workgroups round-robin over the 8 XCDs (each with its own
 // L2); give every XCD a contiguous run of tiles, ordered in column panels 4 tiles tall so that
@@ -100,13 +114,11 @@ __device__ __forceinline__ void dma_load16(const void* gbase, unsigned voff, uns
         : "memory");  // M0 is written here; nothing else in this kernel uses it
 }
 
-// Wait until at most (kStages - 2) steps of this wave's direct loads are outstanding (they return
-// in order, so the oldest step has landed) and until its own LDS reads are done, then meet the
-// other waves.
-__device__ __forceinline__ void publish_barrier() {
-    if (kStages == 3) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else if (kStages == 4) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(24) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+// Wait until at most N of this wave's direct loads are outstanding (they return in order, so
+// everything older has landed) and until its own LDS reads are done, then meet the other waves.
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(N) : "memory");
 }
 
 #ifdef OZ_TRACE
@@ -121,14 +133,14 @@ struct Job {  // one k-step of one slice pair
 };
 
 template <bool WIDE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWaves / 4, kWaves / 4)))
 void slice_gemm_kernel(const GemmArgs g) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / kWavesN, wn = wave % kWavesN;
 
     int tm, tn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
@@ -144,29 +156,29 @@ void slice_gemm_kernel(const GemmArgs g) {
     // are the LDS image of one operand tile of one step (16-byte columns swizzled with bits 2..3
     // of the row: the LDS of gfx950 serves 16 lanes x 16 bytes per clock from 64 banks, and with
     // this swizzle the 16 rows a ds_read_b128 reads together fall into 16 distinct bank groups).
-    // A wave-wide direct load copies 1 KiB; wave w copies bytes [4096 w, 4096 w + 4096) of the A
-    // block and of the B block (4 loads each), every load a run of eight full 128-byte lines.
+    // A wave-wide direct load copies 1 KiB; wave w copies bytes [kWaveShare w, kWaveShare (w+1))
+    // of the A block and of the B block, every load a run of eight full 128-byte lines.
     const unsigned ld_lane_off = (unsigned)lane * 16u;
     const int64_t steps_total = g.k_pad / kStep;
-    const int8_t* a_tile = g.SA + (int64_t)tm * steps_total * kBlockBytes + wave * 4096;
-    const int8_t* b_tile = g.SB + (int64_t)tn * steps_total * kBlockBytes + wave * 4096;
+    const int8_t* a_tile = g.SA + (int64_t)tm * steps_total * kBlockBytes + wave * kWaveShare;
+    const int8_t* b_tile = g.SB + (int64_t)tn * steps_total * kBlockBytes + wave * kWaveShare;
     const unsigned lds_base = (unsigned)(unsigned long)(__attribute__((address_space(3))) unsigned char*)lds;
-    const unsigned ld_lds_off = lds_base + (unsigned)wave * 4096u;
+    const unsigned ld_lds_off = lds_base + (unsigned)wave * (unsigned)kWaveShare;
 
     // LDS -> MFMA operands: lane reads row (lane % 32) of a 32-row block, 16-byte column 2 kk + lane / 32
     const int rd_row = lane & 31;
     const int rd_half = lane >> 5;
     const int a_rd = (wm * 128 + rd_row) * kStep;
-    const int b_rd = kTileBytes + (wn * 128 + rd_row) * kStep;
+    const int b_rd = kTileBytes + (wn * 32 * kTN + rd_row) * kStep;
     const int rd_sw = (lane >> 2) & 3;
 
     const unsigned lane_off16 = (unsigned)tid * 16u;
 
-    // One direct load of a step: `which` = 0..3 copies KiB `which` of this wave's share of the A
-    // block, 4..7 the same of the B block.
+    // One direct load of a step: `which` < kLoadsPerOperand copies KiB `which` of this wave's
+    // share of the A block, the others the same of the B block.
     auto issue_load = [&](const Job& jb, int buf, int which) {
-        const int i = which & 3;
-        if (which < 4) {
+        const int i = which % kLoadsPerOperand;
+        if (which < kLoadsPerOperand) {
             const int8_t* pa = a_tile + (int64_t)(jb.p - 1) * g.a_slice_stride + (int64_t)jb.ks * kBlockBytes;
             dma_load16(pa + i * 1024, ld_lane_off, ld_lds_off + (unsigned)buf * kStageBytes + i * 1024);
         } else {
@@ -178,27 +190,33 @@ void slice_gemm_kernel(const GemmArgs g) {
 #pragma unroll
         for (int w = first; w < last; ++w) issue_load(jb, buf, w);
     };
-    // Fragment reads of one 32-wide k-slab, two per call, in the order the next slab's MFMAs
-    // need them: B fragments 0..3 first, then A fragments 0..3.
-    auto read_two = [&](v4i (&a)[4], v4i (&b)[4], int buf, int kk, int part) {
+    // Fragment read number f of one 32-wide k-slab, in the order the slab's MFMAs need them:
+    // B fragments 0..kTN-1 first, then A fragments 0..kTM-1.
+    auto read_one = [&](v4i (&a)[kTM], v4i (&b)[kTN], int buf, int kk, int f) {
         const unsigned char* base = lds + buf * kStageBytes;
         const int col = (((kk << 1) | rd_half) ^ rd_sw) << 4;
-        if (part < 2) {
-            b[2 * part] = *reinterpret_cast<const v4i*>(base + b_rd + (2 * part) * 32 * kStep + col);
-            b[2 * part + 1] = *reinterpret_cast<const v4i*>(base + b_rd + (2 * part + 1) * 32 * kStep + col);
-        } else {
-            a[2 * part - 4] = *reinterpret_cast<const v4i*>(base + a_rd + (2 * part - 4) * 32 * kStep + col);
-            a[2 * part - 3] = *reinterpret_cast<const v4i*>(base + a_rd + (2 * part - 3) * 32 * kStep + col);
-        }
+        if (f < kTN) b[f] = *reinterpret_cast<const v4i*>(base + b_rd + f * 32 * kStep + col);
+        else a[f - kTN] = *reinterpret_cast<const v4i*>(base + a_rd + (f - kTN) * 32 * kStep + col);
     };
-    auto read_frags = [&](v4i (&a)[4], v4i (&b)[4], int buf, int kk) {
+    auto read_frags = [&](v4i (&a)[kTM], v4i (&b)[kTN], int buf, int kk) {
 #pragma unroll
-        for (int part = 0; part < 4; ++part) read_two(a, b, buf, kk, part);
+        for (int f = 0; f < kTM + kTN; ++f) read_one(a, b, buf, kk, f);
     };
-    auto mfma_row = [&](v16i (&acc)[4][4], const v4i (&a)[4], const v4i (&b)[4], int i) {
+    // One MFMA row of the register tile (kTN MFMAs) plus its share of the next slab's fragment
+    // reads and, every kTM / kLoadsPerOperand rows, one direct load of the step that is being
+    // prefetched: the texture-address unit takes about 18 cycles per wave-wide 1 KiB load and a
+    // wave stalls at issue while it is busy, so the loads are spread evenly over the step
+    // instead of being issued in a burst after the barrier.
+    constexpr int kReadsPerRow = (kTM + kTN + kTM - 1) / kTM;
+    auto mfma_row = [&](v16i (&acc)[kTM][kTN], const v4i (&a)[kTM], const v4i (&b)[kTN], int i, v4i (&na)[kTM],
+                        v4i (&nb)[kTN], int nbuf, int nkk, const Job& jb, int lbuf, int load_base) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int f = i * kReadsPerRow; f < (i + 1) * kReadsPerRow && f < kTM + kTN; ++f) read_one(na, nb, nbuf, nkk, f);
+#pragma unroll
+        for (int j = 0; j < kTN; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+        if (i % (kTM / kLoadsPerOperand) == 0) issue_load(jb, lbuf, load_base + i / (kTM / kLoadsPerOperand));
+        __builtin_amdgcn_sched_barrier(0);
     };
     auto advance = [&](Job& jb) -> bool {  // false when the walk is over
         if (++jb.ks < ks_end) return true;
@@ -218,45 +236,45 @@ void slice_gemm_kernel(const GemmArgs g) {
     };
 
     // INT32 registers -> workspace (narrow: plain store of a finished diagonal)
-    auto store_diag32 = [&](v16i (&acc)[4][4], int d) {
+    auto store_diag32 = [&](v16i (&acc)[kTM][kTN], int d) {
         unsigned char* base = reinterpret_cast<unsigned char*>(g.D) +
                               ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * 4);
         const unsigned off = lane_off16 + opaque_zero();
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < kTM; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < kTN; ++j)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     v4i v = {acc_read(acc[i][j][4 * r4]), acc_read(acc[i][j][4 * r4 + 1]), acc_read(acc[i][j][4 * r4 + 2]),
                              acc_read(acc[i][j][4 * r4 + 3])};
-                    *reinterpret_cast<v4i*>(base + ((i * 4 + j) * 4 + r4) * 4096 + off) = v;
+                    *reinterpret_cast<v4i*>(base + ((i * kTN + j) * 4 + r4) * (kThreads * 16) + off) = v;
                     __builtin_amdgcn_sched_barrier(0);  // keep register pressure flat
                 }
     };
     // INT32 registers -> INT64 sums (wide: k-blocking)
-    auto flush_diag64 = [&](v16i (&acc)[4][4], int d, bool first) {
+    auto flush_diag64 = [&](v16i (&acc)[kTM][kTN], int d, bool first) {
         unsigned char* base = reinterpret_cast<unsigned char*>(g.D) +
                               ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * 8);
         const unsigned off = lane_off16 + opaque_zero();
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < kTM; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < kTN; ++j)
 #pragma unroll
                 for (int r2 = 0; r2 < 8; ++r2) {
                     v2l v = {(long long)acc_read(acc[i][j][2 * r2]), (long long)acc_read(acc[i][j][2 * r2 + 1])};
-                    v2l* q = reinterpret_cast<v2l*>(base + ((i * 4 + j) * 8 + r2) * 4096 + off);
+                    v2l* q = reinterpret_cast<v2l*>(base + ((i * kTN + j) * 8 + r2) * (kThreads * 16) + off);
                     if (!first) v += *q;
                     *q = v;
                     __builtin_amdgcn_sched_barrier(0);
                 }
     };
-    auto zero_acc = [&](v16i (&acc)[4][4]) {
+    auto zero_acc = [&](v16i (&acc)[kTM][kTN]) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < kTM; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < kTN; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = acc_zero();
     };
@@ -264,23 +282,23 @@ void slice_gemm_kernel(const GemmArgs g) {
     // accumulator layout of the 32x32 MFMA: lane holds column (lane % 32); register r holds
     // row 8 (r / 4) + 4 (lane / 32) + r % 4.
     const int row0 = tm * kTile + wm * 128 + 4 * rd_half;
-    const int col0 = tn * kTile + wn * 128 + rd_row;
+    const int col0 = tn * kTile + wn * 32 * kTN + rd_row;
     const int s = g.num_slices;
 
     // Pair mode: raw INT32 tile -> row-major P. The tile is staged through LDS (free once the
     // k-walk is over) in two halves of 128 rows so that the bounds-checked stores are a rolled
     // loop along rows of P.
-    auto write_pair = [&](v16i (&acc)[4][4]) {
+    auto write_pair = [&](v16i (&acc)[kTM][kTN]) {
         int* tile = reinterpret_cast<int*>(lds);  // [128][256] INT32 = 128 KiB
-        const unsigned tbase = (unsigned)(4 * rd_half * kTile + wn * 128 + rd_row) + opaque_zero();
+        const unsigned tbase = (unsigned)(4 * rd_half * kTile + wn * 32 * kTN + rd_row) + opaque_zero();
         asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");  // no direct load may still land here
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             if (wm == half) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < kTM; ++i)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
+                    for (int j = 0; j < kTN; ++j)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             tile[tbase + (i * 32 + 8 * (r >> 2) + (r & 3)) * kTile + j * 32] = acc_read(acc[i][j][r]);
@@ -289,10 +307,10 @@ void slice_gemm_kernel(const GemmArgs g) {
             }
             __syncthreads();
 #pragma unroll 1
-            for (int rr = 0; rr < 128; ++rr) {
+            for (int rr = tid / kTile; rr < 128; rr += kThreads / kTile) {
                 const int row = tm * kTile + half * 128 + rr;
-                const int col = tn * kTile + tid;
-                if (row < g.m && col < g.n) g.P[(int64_t)row * g.ldp + col] = tile[rr * kTile + tid];
+                const int col = tn * kTile + (tid % kTile);
+                if (row < g.m && col < g.n) g.P[(int64_t)row * g.ldp + col] = tile[rr * kTile + (tid % kTile)];
             }
             __syncthreads();
         }
@@ -310,8 +328,8 @@ void slice_gemm_kernel(const GemmArgs g) {
     // it wrote itself, so no synchronisation is needed), least significant first.
     auto final_narrow = [&]() {
 #pragma unroll 1
-        for (int ij = 0; ij < 16; ++ij) {
-            const int i = ij >> 2, j = ij & 3;
+        for (int ij = 0; ij < kTM * kTN; ++ij) {
+            const int i = ij / kTN, j = ij % kTN;
             const int col = col0 + j * 32;
             const int eb = col < g.n ? g.EB[col] : 0;
 #pragma unroll 1
@@ -321,7 +339,7 @@ void slice_gemm_kernel(const GemmArgs g) {
                     const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * d) << 52);
                     const unsigned char* src = reinterpret_cast<const unsigned char*>(g.D) +
                                                ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * 4);
-                    v4i v = *reinterpret_cast<const v4i*>(src + (ij * 4 + r4) * 4096 + lane_off16);
+                    v4i v = *reinterpret_cast<const v4i*>(src + (ij * 4 + r4) * (kThreads * 16) + lane_off16);
 #pragma unroll
                     for (int u = 0; u < 4; ++u) sum[u] = sum[u] + (double)v[u] * sc;
                 }
@@ -332,8 +350,8 @@ void slice_gemm_kernel(const GemmArgs g) {
     };
     auto final_wide = [&]() {
 #pragma unroll 1
-        for (int ij = 0; ij < 16; ++ij) {
-            const int i = ij >> 2, j = ij & 3;
+        for (int ij = 0; ij < kTM * kTN; ++ij) {
+            const int i = ij / kTN, j = ij % kTN;
             const int col = col0 + j * 32;
             const int eb = col < g.n ? g.EB[col] : 0;
 #pragma unroll 1
@@ -343,7 +361,7 @@ void slice_gemm_kernel(const GemmArgs g) {
                     const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * d) << 52);
                     const unsigned char* src = reinterpret_cast<const unsigned char*>(g.D) +
                                                ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * 8);
-                    v2l v = *reinterpret_cast<const v2l*>(src + (ij * 8 + r2) * 4096 + lane_off16);
+                    v2l v = *reinterpret_cast<const v2l*>(src + (ij * 8 + r2) * (kThreads * 16) + lane_off16);
                     sum[0] = sum[0] + (double)v[0] * sc;
                     sum[1] = sum[1] + (double)v[1] * sc;
                 }
@@ -357,16 +375,14 @@ void slice_gemm_kernel(const GemmArgs g) {
     // Pipeline prologue: steps 0 .. kStages-2 are requested in full and the A half of step
     // kStages-1; step 0 is awaited and published.
     Job nxt = {d_first, pair_mode ? g.pair_p : 1, ks_begin};   // last step requested
-    issue_loads(nxt, 0, 0, 8);
+    issue_loads(nxt, 0, 0, kLoadsPerStep);
 #pragma unroll
     for (int b = 1; b < kStages; ++b) {
         advance_clamped(nxt);
-        issue_loads(nxt, b, 0, b == kStages - 1 ? 4 : 8);
+        issue_loads(nxt, b, 0, b == kStages - 1 ? kLoadsPerOperand : kLoadsPerStep);
     }
-    if (kStages == 3) asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
-    else if (kStages == 4) asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(28)\n\ts_barrier" ::: "memory");
-    v4i fa0[4], fb0[4], fa1[4], fb1[4];
+    wait_loads_and_barrier<(kStages - 2) * kLoadsPerStep + kLoadsPerOperand>();
+    v4i fa0[kTM], fb0[kTN], fa1[kTM], fb1[kTN];
     read_frags(fa0, fb0, 0, 0);
 
     const int nks = ks_end - ks_begin;
@@ -376,39 +392,24 @@ void slice_gemm_kernel(const GemmArgs g) {
     const bool trace_on = blockIdx.x == 8 && tid == 0;
     int trace_n = 0;
 #endif
-    // One step = 32 MFMAs in 8 blocks of 4. Every block also reads two fragments of the next
-    // slab and issues ONE direct load: the texture-address unit takes about 18 cycles per
-    // wave-wide 1 KiB load and a wave stalls at issue while it is busy, so the 32 loads a step
-    // needs from the four waves are spread evenly over the step instead of being issued in a
-    // burst after the barrier. The B half of a step's loads is therefore issued one phase
-    // later than its A half, into the buffer released at the previous barrier.
-    auto run_steps = [&](v16i (&acc)[4][4], int count) {
+    // One step = two k-slabs. During the first slab the B half of the prefetched step's loads is
+    // issued (into the buffer released at the previous barrier), then every wave has read its
+    // last fragments of the current buffer and its loads of the next step have landed: barrier.
+    // During the second slab the A half of the following step goes into the buffer just released.
+    auto run_steps = [&](v16i (&acc)[kTM][kTN], int count) {
         int t = 0;
         do {
             OZ_T(0);
 #pragma unroll
-            for (int blk = 0; blk < 4; ++blk) {
-                read_two(fa1, fb1, buf, 1, blk);
-                mfma_row(acc, fa0, fb0, blk);
-                issue_load(nxt, prev, 4 + blk);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            for (int i = 0; i < kTM; ++i) mfma_row(acc, fa0, fb0, i, fa1, fb1, buf, 1, nxt, prev, kLoadsPerOperand);
             OZ_T(1);
-            // Every wave has read its last fragments of this buffer and its direct loads of the
-            // next step have landed: publish, then start refilling the released buffer with the
-            // step that is kStages ahead.
-            publish_barrier();
+            wait_loads_and_barrier<(kStages - 2) * kLoadsPerStep>();
             OZ_T(2);
             advance_clamped(nxt);
             prev = buf;
             buf = buf + 1 == kStages ? 0 : buf + 1;
 #pragma unroll
-            for (int blk = 0; blk < 4; ++blk) {
-                read_two(fa0, fb0, buf, 0, blk);
-                mfma_row(acc, fa1, fb1, blk);
-                issue_load(nxt, prev, blk);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            for (int i = 0; i < kTM; ++i) mfma_row(acc, fa1, fb1, i, fa0, fb0, buf, 0, nxt, prev, 0);
             OZ_T(3);
 #ifdef OZ_TRACE
             ++trace_n;
@@ -424,14 +425,14 @@ void slice_gemm_kernel(const GemmArgs g) {
             do {
                 const int run = jobs > kBlockSteps ? kBlockSteps : jobs;
                 jobs -= run;
-                v16i acc[4][4];
+                v16i acc[kTM][kTN];
                 zero_acc(acc);
                 run_steps(acc, run);
                 flush_diag64(acc, d, fresh);
                 fresh = false;
             } while (jobs > 0);
         } else {
-            v16i acc[4][4];
+            v16i acc[kTM][kTN];
             zero_acc(acc);
             run_steps(acc, jobs);
             if (pair_mode) write_pair(acc);
@@ -461,12 +462,12 @@ hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&slice_gemm_kernel<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsAlloc);
         if (e != hipSuccess) return e;
-        slice_gemm_kernel<true><<<dim3(blocks), dim3(256), kLdsAlloc, st>>>(args);
+        slice_gemm_kernel<true><<<dim3(blocks), dim3(kThreads), kLdsAlloc, st>>>(args);
     } else {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&slice_gemm_kernel<false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsAlloc);
         if (e != hipSuccess) return e;
-        slice_gemm_kernel<false><<<dim3(blocks), dim3(256), kLdsAlloc, st>>>(args);
+        slice_gemm_kernel<false><<<dim3(blocks), dim3(kThreads), kLdsAlloc, st>>>(args);
     }
     return hipGetLastError();
 }
