@@ -21,6 +21,19 @@ if ROOT not in sys.path:
 
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense INT8, published
 HBM_PEAK_GBS = 8000.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "slice_gemm_m8192_pmc.md")
+
+
+def measured_traffic(m, s):
+    """HBM bytes per launch of the slice-product kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration); None if not recorded."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            if line.startswith(f"traffic_bytes_per_launch m={m} s={s}:"):
+                return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(A_rows, B_host, s, m_full):
@@ -145,7 +158,7 @@ def main():
             "peak": INT8_MFMA_PEAK_TOPS,
             "unit": "TOP/s",
             "frac": achieved_tops / INT8_MFMA_PEAK_TOPS,
-            "traffic": None,
+            "traffic": measured_traffic(m, s),
             "algorithmic_ops_per_launch": int8_ops,
             "avg_launch_ms": gemm_ms,
         },
@@ -156,6 +169,15 @@ def main():
     }
 
     if not args.no_context:
+        # context only: what the matrix cores sustain in a register-only issue loop on this chip,
+        # with all-zero operands and with operands distributed like the slices
+        z_tops, z_mhz = ozimmu.probe_int8_mfma(0)
+        r_tops, r_mhz = ozimmu.probe_int8_mfma(2)
+        out["context_int8_mfma_issue_loop"] = {
+            "zero_operands": {"TOPs": z_tops, "shader_MHz": z_mhz},
+            "random_7bit_operands": {"TOPs": r_tops, "shader_MHz": r_mhz},
+            "kernel_vs_random_7bit_loop": achieved_tops / r_tops if r_tops > 0 else None,
+        }
         # context only: the vendor FP64 GEMM on the same GPU
         for _ in range(2):
             torch.matmul(A, B)
@@ -168,6 +190,14 @@ def main():
         c1 = time.perf_counter()
         out["context_native_fp64_dgemm_TFLOPs"] = 2.0 * m * n * k / ((c1 - c0) / reps) / 1e12
         del R
+
+    # plain copy of known size (1 GiB read, 1 GiB written): the calibration point for the
+    # FETCH_SIZE / WRITE_SIZE counters when this command runs under rocprofv3 --pmc
+    cal_src = torch.empty(1 << 27, dtype=torch.float64, device="cuda").fill_(1.0)
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
 
     if args.cpu_rows > 0:
         rng = np.random.default_rng(7)

@@ -141,6 +141,21 @@ ozimmu_status_t ozimmu_dgemm_stage(int stage, int64_t m, int64_t n, int64_t k, c
                                    int64_t ldc, int num_slices, void* workspace,
                                    size_t workspace_bytes, void* stream);
 
+/*
+ * Device characterisation (measurement utilities for the benchmark, not part of the product
+ * path; unlike every entry point above they allocate a few KiB for the duration of the call and
+ * synchronise the device).
+ *   ozimmu_probe_int8_mfma: sustained rate of a register-only v_mfma_i32_32x32x32_i8 issue loop on
+ *     all compute units, in 10^12 INT8 operations per second, and the shader clock it ran at.
+ *     pattern 0: all-zero operands; 1: random bytes; 2: random signed 7-bit magnitudes (the value
+ *     distribution of the slices of Section 3.1). The reachable matrix-core rate depends on it.
+ *   ozimmu_probe_lds_read: wave-wide 16-byte LDS read throughput in bytes per ns and compute unit.
+ *     pattern 0: linear; 1: 64-byte rows without column swizzle; 2: the slice-tensor block layout.
+ */
+ozimmu_status_t ozimmu_probe_int8_mfma(int pattern, int iters, double* tera_ops_per_s,
+                                       double* shader_mhz);
+ozimmu_status_t ozimmu_probe_lds_read(int pattern, int iters, double* bytes_per_ns_per_cu);
+
 #ifdef __cplusplus
 }
 #endif

@@ -34,20 +34,14 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef long long v2l __attribute__((ext_vector_type(2)));
 
 constexpr int kStepsPerChunk = kChunk / kStep;        // the API counts k in chunks of kChunk
-#ifndef OZ_STAGES
-#define OZ_STAGES 4
-#endif
-constexpr int kStages = OZ_STAGES;                    // LDS buffers
+constexpr int kStages = 4;                            // LDS buffers (3 are as fast at 8192^3; 4 leave slack for L2 misses)
 constexpr int kTileBytes = kBlockBytes;               // one operand tile of one step: 16 KiB
 constexpr int kStageBytes = 2 * kTileBytes;           // A tile + B tile
 constexpr int kLdsBytes = kStages * kStageBytes;
 constexpr int kPairLdsBytes = 128 * kTile * 4;        // staging of the raw INT32 tile in pair mode
 constexpr int kLdsAlloc = kLdsBytes > kPairLdsBytes ? kLdsBytes : kPairLdsBytes;
 constexpr int kBlockSteps = OZIMMU_INT32_BLOCK / kStep;
-#ifndef OZ_WAVES_N
-#define OZ_WAVES_N 4
-#endif
-constexpr int kWavesM = 2, kWavesN = OZ_WAVES_N;      // wavefront grid inside the workgroup
+constexpr int kWavesM = 2, kWavesN = 4;               // wavefront grid inside the workgroup
 constexpr int kWaves = kWavesM * kWavesN;
 constexpr int kThreads = 64 * kWaves;
 constexpr int kTM = kTile / kWavesM / 32;             // 32x32 MFMA tiles per wavefront along m (4)
@@ -121,15 +115,10 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(N) : "memory");
 }
 
-#ifdef OZ_TRACE
-__device__ long long oz_trace[8192];
-#define OZ_T(i) do { if (trace_on && trace_n < 2040) { oz_trace[trace_n * 4 + (i)] = clock64(); } } while (0)
-#else
-#define OZ_T(i) do { } while (0)
-#endif
-
-struct Job {  // one k-step of one slice pair
+struct Job {  // one k-step of one slice pair, with this wave's source addresses for it
     int d, p, ks;
+    const int8_t* pa;
+    const int8_t* pb;
 };
 
 template <bool WIDE>
@@ -178,13 +167,10 @@ void slice_gemm_kernel(const GemmArgs g) {
     // share of the A block, the others the same of the B block.
     auto issue_load = [&](const Job& jb, int buf, int which) {
         const int i = which % kLoadsPerOperand;
-        if (which < kLoadsPerOperand) {
-            const int8_t* pa = a_tile + (int64_t)(jb.p - 1) * g.a_slice_stride + (int64_t)jb.ks * kBlockBytes;
-            dma_load16(pa + i * 1024, ld_lane_off, ld_lds_off + (unsigned)buf * kStageBytes + i * 1024);
-        } else {
-            const int8_t* pb = b_tile + (int64_t)(jb.d - jb.p - 1) * g.b_slice_stride + (int64_t)jb.ks * kBlockBytes;
-            dma_load16(pb + i * 1024, ld_lane_off, ld_lds_off + (unsigned)buf * kStageBytes + kTileBytes + i * 1024);
-        }
+        if (which < kLoadsPerOperand)
+            dma_load16(jb.pa + i * 1024, ld_lane_off, ld_lds_off + (unsigned)buf * kStageBytes + i * 1024);
+        else
+            dma_load16(jb.pb + i * 1024, ld_lane_off, ld_lds_off + (unsigned)buf * kStageBytes + kTileBytes + i * 1024);
     };
     auto issue_loads = [&](const Job& jb, int buf, int first, int last) {
 #pragma unroll
@@ -218,17 +204,28 @@ void slice_gemm_kernel(const GemmArgs g) {
         if (i % (kTM / kLoadsPerOperand) == 0) issue_load(jb, lbuf, load_base + i / (kTM / kLoadsPerOperand));
         __builtin_amdgcn_sched_barrier(0);
     };
+    auto locate = [&](Job& jb) {  // source addresses of the first step of pair (jb.p, jb.d - jb.p)
+        jb.pa = a_tile + (int64_t)(jb.p - 1) * g.a_slice_stride + (int64_t)jb.ks * kBlockBytes;
+        jb.pb = b_tile + (int64_t)(jb.d - jb.p - 1) * g.b_slice_stride + (int64_t)jb.ks * kBlockBytes;
+    };
     auto advance = [&](Job& jb) -> bool {  // false when the walk is over
-        if (++jb.ks < ks_end) return true;
+        if (++jb.ks < ks_end) {   // next step of the same pair: the next block of both tensors
+            jb.pa += kBlockBytes;
+            jb.pb += kBlockBytes;
+            return true;
+        }
         jb.ks = ks_begin;
-        if (!pair_mode && ++jb.p < jb.d) return true;
-        --jb.d;
-        jb.p = 1;
-        return jb.d >= d_last;
+        if (pair_mode || ++jb.p >= jb.d) {
+            --jb.d;
+            jb.p = 1;
+            if (jb.d < d_last) return false;
+        }
+        locate(jb);
+        return true;
     };
     // At the end of the walk the iterator stops advancing and the last step is simply loaded
     // again into a buffer nobody reads any more: the number of loads in flight stays the same in
-    // every step, which is what the vmcnt in publish_barrier() counts on, and the loop body needs
+    // every step, which is what the vmcnt of the step barrier counts on, and the loop body needs
     // no branch around the loads.
     auto advance_clamped = [&](Job& jb) {
         Job cand = jb;
@@ -332,20 +329,25 @@ void slice_gemm_kernel(const GemmArgs g) {
             const int i = ij / kTN, j = ij % kTN;
             const int col = col0 + j * 32;
             const int eb = col < g.n ? g.EB[col] : 0;
-#pragma unroll 1
-            for (int r4 = 0; r4 < 4; ++r4) {
-                double sum[4] = {0.0, 0.0, 0.0, 0.0};
-                for (int d = s + 1; d >= 2; --d) {
-                    const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * d) << 52);
-                    const unsigned char* src = reinterpret_cast<const unsigned char*>(g.D) +
-                                               ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * 4);
+            double sum[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) sum[u] = 0.0;
+            // all 16 accumulators of one MFMA tile at once: four independent 16-byte loads per
+            // diagonal, several diagonals in flight
+#pragma unroll 4
+            for (int d = s + 1; d >= 2; --d) {
+                const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * d) << 52);
+                const unsigned char* src = reinterpret_cast<const unsigned char*>(g.D) +
+                                           ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * 4);
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
                     v4i v = *reinterpret_cast<const v4i*>(src + (ij * 4 + r4) * (kThreads * 16) + lane_off16);
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) sum[u] = sum[u] + (double)v[u] * sc;
+                    for (int u = 0; u < 4; ++u) sum[4 * r4 + u] = sum[4 * r4 + u] + (double)v[u] * sc;
                 }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) write_c(row0 + i * 32 + 8 * r4 + u, col, eb, sum[u]);
             }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) write_c(row0 + i * 32 + 8 * (u >> 2) + (u & 3), col, eb, sum[u]);
         }
     };
     auto final_wide = [&]() {
@@ -374,7 +376,8 @@ void slice_gemm_kernel(const GemmArgs g) {
 
     // Pipeline prologue: steps 0 .. kStages-2 are requested in full and the A half of step
     // kStages-1; step 0 is awaited and published.
-    Job nxt = {d_first, pair_mode ? g.pair_p : 1, ks_begin};   // last step requested
+    Job nxt = {d_first, pair_mode ? g.pair_p : 1, ks_begin, nullptr, nullptr};   // last step requested
+    locate(nxt);
     issue_loads(nxt, 0, 0, kLoadsPerStep);
 #pragma unroll
     for (int b = 1; b < kStages; ++b) {
@@ -388,10 +391,6 @@ void slice_gemm_kernel(const GemmArgs g) {
     const int nks = ks_end - ks_begin;
     int buf = 0;                // LDS buffer of the step in the matrix cores
     int prev = kStages - 1;     // the buffer released at the previous barrier
-#ifdef OZ_TRACE
-    const bool trace_on = blockIdx.x == 8 && tid == 0;
-    int trace_n = 0;
-#endif
     // One step = two k-slabs. During the first slab the B half of the prefetched step's loads is
     // issued (into the buffer released at the previous barrier), then every wave has read its
     // last fragments of the current buffer and its loads of the next step have landed: barrier.
@@ -399,21 +398,14 @@ void slice_gemm_kernel(const GemmArgs g) {
     auto run_steps = [&](v16i (&acc)[kTM][kTN], int count) {
         int t = 0;
         do {
-            OZ_T(0);
 #pragma unroll
             for (int i = 0; i < kTM; ++i) mfma_row(acc, fa0, fb0, i, fa1, fb1, buf, 1, nxt, prev, kLoadsPerOperand);
-            OZ_T(1);
             wait_loads_and_barrier<(kStages - 2) * kLoadsPerStep>();
-            OZ_T(2);
             advance_clamped(nxt);
             prev = buf;
             buf = buf + 1 == kStages ? 0 : buf + 1;
 #pragma unroll
             for (int i = 0; i < kTM; ++i) mfma_row(acc, fa1, fb1, i, fa0, fb0, buf, 0, nxt, prev, 0);
-            OZ_T(3);
-#ifdef OZ_TRACE
-            ++trace_n;
-#endif
         } while (++t < count);
     };
 
@@ -448,11 +440,6 @@ void slice_gemm_kernel(const GemmArgs g) {
 
 }  // namespace
 
-#ifdef OZ_TRACE
-extern "C" int ozimmu_debug_trace(long long* host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(oz_trace), sizeof(long long) * n);
-}
-#endif
 
 hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st) {
     const int blocks = args.tiles_m * args.tiles_n;

@@ -22,6 +22,7 @@ WORKSPACE_ALIGN = 256
 EXPORTS = (
     "ozimmu_status_string", "ozimmu_slice_geometry", "ozimmu_slice_offset", "ozimmu_split_rows", "ozimmu_split_cols",
     "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_stage",
+    "ozimmu_probe_int8_mfma", "ozimmu_probe_lds_read",
 )
 
 
@@ -63,6 +64,11 @@ def lib() -> ctypes.CDLL:
             f.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
         L.ozimmu_dgemm_stage.restype = i32
         L.ozimmu_dgemm_stage.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
+        dp = ctypes.POINTER(ctypes.c_double)
+        L.ozimmu_probe_int8_mfma.restype = i32
+        L.ozimmu_probe_int8_mfma.argtypes = [i32, i32, dp, dp]
+        L.ozimmu_probe_lds_read.restype = i32
+        L.ozimmu_probe_lds_read.argtypes = [i32, i32, dp]
         _lib = L
     return _lib
 
@@ -175,6 +181,20 @@ def zgemm(A, B, C, num_slices: int, workspace, stream=None) -> None:
     n = B.shape[1]
     _check(lib().ozimmu_zgemm(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C), _ld(C, n), num_slices,
                               _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+
+
+def probe_int8_mfma(pattern: int, iters: int = 200000):
+    """(10^12 INT8 ops/s, shader MHz) of a register-only MFMA issue loop; see ozimmu.h."""
+    tops, mhz = ctypes.c_double(), ctypes.c_double()
+    _check(lib().ozimmu_probe_int8_mfma(pattern, iters, ctypes.byref(tops), ctypes.byref(mhz)))
+    return tops.value, mhz.value
+
+
+def probe_lds_read(pattern: int, iters: int = 20000) -> float:
+    """LDS 16-byte read throughput in bytes per ns and compute unit; see ozimmu.h."""
+    out = ctypes.c_double()
+    _check(lib().ozimmu_probe_lds_read(pattern, iters, ctypes.byref(out)))
+    return out.value
 
 
 def alloc_workspace(m: int, n: int, k: int, num_slices: int, is_complex: bool = False, device="cuda"):
