@@ -51,6 +51,7 @@ typedef enum {
 #define OZIMMU_ROW_ALIGN 256         /* slice rows are padded to a multiple of this */
 #define OZIMMU_K_ALIGN 128           /* slice row length is padded to a multiple of this */
 #define OZIMMU_K_STEP 64             /* k-extent of one contiguous block of a slice tensor */
+#define OZIMMU_MAX_DIM 4194304       /* largest m, n or k accepted (2^22); beyond: OZIMMU_ERR_BAD_DIM */
 #define OZIMMU_INT32_BLOCK 131072    /* at most 2^17 INT8 products go into one INT32 sum:
                                         2^17 * 127^2 < 2^31 (the exact limit is 133144) */
 #define OZIMMU_WORKSPACE_ALIGN 256

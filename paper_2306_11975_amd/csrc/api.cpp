@@ -9,7 +9,7 @@ using namespace ozimmu;
 
 namespace {
 
-constexpr int64_t kMaxDim = (int64_t)1 << 24;  // tile counts and byte offsets inside a tile row stay in 32 bits
+constexpr int64_t kMaxDim = OZIMMU_MAX_DIM;  // every launch grid (k / 128 blocks in grid.y at most) stays legal
 
 inline size_t align_up(size_t x) { return (x + OZIMMU_WORKSPACE_ALIGN - 1) / OZIMMU_WORKSPACE_ALIGN * OZIMMU_WORKSPACE_ALIGN; }
 

@@ -220,14 +220,20 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
 
 __global__ __launch_bounds__(256) void fill_f64_kernel(double* C, int64_t ldc, int c_inc, int64_t m,
                                                        int64_t n, double v) {
-    int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx < m * n) C[(idx / n) * ldc + (idx % n) * c_inc] = v;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < m * n; idx += (int64_t)gridDim.x * 256)
+        C[(idx / n) * ldc + (idx % n) * c_inc] = v;
 }
 
 __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* P, int64_t ldp, int64_t m, int64_t n,
                                                        int32_t v) {
-    int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx < m * n) P[(idx / n) * ldp + (idx % n)] = v;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < m * n; idx += (int64_t)gridDim.x * 256)
+        P[(idx / n) * ldp + (idx % n)] = v;
+}
+
+// Grid of a grid-stride fill: enough blocks to cover the range, capped so the count fits any grid limit.
+unsigned fill_blocks(int64_t elems) {
+    const int64_t b = (elems + 255) / 256;
+    return (unsigned)(b < (1 << 20) ? b : (1 << 20));
 }
 
 }  // namespace
@@ -266,13 +272,13 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
 hipError_t launch_fill_f64(double* C, int64_t ldc, int c_inc, int64_t m, int64_t n, double v,
                            hipStream_t st) {
     if (m * n == 0) return hipSuccess;
-    fill_f64_kernel<<<dim3((unsigned)((m * n + 255) / 256)), dim3(256), 0, st>>>(C, ldc, c_inc, m, n, v);
+    fill_f64_kernel<<<dim3(fill_blocks(m * n)), dim3(256), 0, st>>>(C, ldc, c_inc, m, n, v);
     return hipGetLastError();
 }
 
 hipError_t launch_fill_i32(int32_t* P, int64_t ldp, int64_t m, int64_t n, int32_t v, hipStream_t st) {
     if (m * n == 0) return hipSuccess;
-    fill_i32_kernel<<<dim3((unsigned)((m * n + 255) / 256)), dim3(256), 0, st>>>(P, ldp, m, n, v);
+    fill_i32_kernel<<<dim3(fill_blocks(m * n)), dim3(256), 0, st>>>(P, ldp, m, n, v);
     return hipGetLastError();
 }
 

@@ -87,6 +87,9 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 3, ctypes.c_void_p(264), 1 << 30, None) == 5
     assert L.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 3, fake, 16, None) == 5
     assert L.ozimmu_zgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 3, fake, 16, None) == 5
+    # dimensions beyond OZIMMU_MAX_DIM (2^22) are refused
+    assert L.ozimmu_dgemm((1 << 22) + 1, 4, 4, fake, 4, fake, 4, fake, 4, 3, fake, 1 << 30, None) == 1
+    assert L.ozimmu_workspace_bytes(4, 4, (1 << 22) + 1, 3, 0, ctypes.byref(out)) == 1
     # empty products are no-ops
     assert L.ozimmu_dgemm(0, 4, 4, None, 4, None, 4, None, 4, 3, None, 0, None) == 0
     assert L.ozimmu_dgemm(4, 0, 4, None, 4, None, 0, None, 0, 3, None, 0, None) == 0
