@@ -1,0 +1,99 @@
+"""Parity at the full size of the large workloads, in the launch configuration the benchmark times.
+
+An entry C_ij depends only on row i of A and column j of B, so the oracle run on a few rows of A
+against all of B reproduces exactly those rows of the full result: the sampled rows (tile edges of
+the 256-row macro tiles plus random ones) must be bit-exact. Inputs are generated on the device
+from a seed and the sampled rows copied back for the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2306_11975_amd import ozimmu
+from paper_2306_11975_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def bits(x):
+    return np.ascontiguousarray(x).view(np.uint64)
+
+
+def sample_rows(m, extra, seed):
+    edges = [0, 1, 127, 128, 255, 256, m // 2 - 1, m // 2, m - 257, m - 256, m - 1]
+    rng = np.random.default_rng(seed)
+    rows = set(int(r) for r in edges if 0 <= r < m) | set(int(r) for r in rng.choice(m, size=extra, replace=False))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+@pytest.fixture(scope="module")
+def config3():
+    m = n = k = 8192
+    A = wl.phi_matrix_device(m, k, 1.0, 1003)
+    B = wl.phi_matrix_device(k, n, 1.0, 2003)
+    rows = sample_rows(m, 13, seed=3)
+    A_rows = A[torch.from_numpy(rows).cuda()].cpu().numpy()
+    B_host = B.cpu().numpy()
+    yield A, B, rows, A_rows, B_host
+    del A, B
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("s", [6, 8, 10])
+def test_config3_8192_cubed_sampled_rows_bit_exact(config3, s):
+    A, B, rows, A_rows, B_host = config3
+    m, k = A.shape
+    n = B.shape[1]
+    C = torch.full((m, n), float("nan"), dtype=torch.float64, device="cuda")
+    ws = ozimmu.alloc_workspace(m, n, k, s)
+    ozimmu.dgemm(A, B, C, s, ws)
+    torch.cuda.synchronize()
+    assert not torch.isnan(C).any()
+    got = C[torch.from_numpy(rows).cuda()].cpu().numpy()
+    want = oracle.dgemm(A_rows, B_host, s)
+    assert np.array_equal(bits(got), bits(want))
+    # sampled accuracy against the double-double product, scaled by (|A||B|): below 2^-50 once s is large
+    if s == 10:
+        hi, lo = oracle.dd_gemm(A_rows, B_host)
+        scale = oracle.abs_gemm(A_rows, B_host)
+        assert np.max(np.abs((got - hi) - lo) / scale) <= 2.0 ** -50
+
+
+def test_config4_long_k_wide_exponents_sampled_rows_bit_exact():
+    """m = n = 4096, k = 131072, phi = 2, s = 8: every diagonal spans several INT32 blocks (INT64 sums)."""
+    m, n, k, s = 4096, 4096, 131072, 8
+    A = wl.phi_matrix_device(m, k, 2.0, 1004)
+    B = wl.phi_matrix_device(k, n, 2.0, 2004)
+    C = torch.full((m, n), float("nan"), dtype=torch.float64, device="cuda")
+    ws = ozimmu.alloc_workspace(m, n, k, s)
+    ozimmu.dgemm(A, B, C, s, ws)
+    torch.cuda.synchronize()
+    assert not torch.isnan(C).any()
+    rows = np.array([0, 255, 256, 2047, 3840, 4095], dtype=np.int64)
+    A_rows = A[torch.from_numpy(rows).cuda()].cpu().numpy()
+    got = C[torch.from_numpy(rows).cuda()].cpu().numpy()
+    del A, C, ws
+    B_host = B.cpu().numpy()
+    del B
+    torch.cuda.empty_cache()
+    want = oracle.dgemm(A_rows, B_host, s)
+    assert np.array_equal(bits(got), bits(want))
+
+
+def test_config5_complex_small_k_sampled_rows_bit_exact():
+    """Complex m = n = 4096, k = 256, s = 7: Gaussian A, unit-norm columns of B."""
+    m, n, k, s = 4096, 4096, 256, 7
+    A = wl.gaussian_complex_device(m, k, 1005)
+    B = wl.unit_column_complex_device(k, n, 2005)
+    C = torch.full((m, n), complex(float("nan"), float("nan")), dtype=torch.complex128, device="cuda")
+    ws = ozimmu.alloc_workspace(m, n, k, s, is_complex=True)
+    ozimmu.zgemm(A, B, C, s, ws)
+    torch.cuda.synchronize()
+    assert not torch.isnan(torch.view_as_real(C)).any()
+    rows = sample_rows(m, 117, seed=5)
+    idx = torch.from_numpy(rows).cuda()
+    got = C[idx].cpu().numpy()
+    want = oracle.zgemm(A[idx].cpu().numpy(), B.cpu().numpy(), s)
+    assert np.array_equal(bits(got.real.copy()), bits(want.real.copy()))
+    assert np.array_equal(bits(got.imag.copy()), bits(want.imag.copy()))
