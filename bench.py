@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--phi", type=float, default=1.0)
     ap.add_argument("--cpu-rows", type=int, default=256, help="rows of A in the CPU oracle sample (0: skip)")
     ap.add_argument("--no-context", action="store_true", help="skip the native FP64 DGEMM context timing")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="diagnostic: all-zero A and B (same instruction stream, no operand bits toggling): "
+                         "shows how much of the kernel time is the data-dependent matrix-core clock")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -96,6 +99,9 @@ def main():
     pairs = s * (s + 1) // 2
     A = wl.phi_matrix_device(m, k, args.phi, 1003)
     B = wl.phi_matrix_device(k, n, args.phi, 2003)
+    if args.zero_operands:
+        A.zero_()
+        B.zero_()
     C = torch.empty((m, n), dtype=torch.float64, device="cuda")
     ws = ozimmu.alloc_workspace(m, n, k, s)
     stream = torch.cuda.current_stream()
@@ -148,7 +154,8 @@ def main():
         "vs_baseline": None,
         "dtype": "int8 slices, int32 accumulation, f64 sum",
         "data": "synthetic",
-        "config": {"workload": f"real FP64 GEMM m=n=k={m}, entries (U(0,1)-0.5)*exp({args.phi}*N(0,1)), "
+        "config": {"workload": ("DIAGNOSTIC all-zero operands, " if args.zero_operands else "") +
+                               f"real FP64 GEMM m=n=k={m}, entries (U(0,1)-0.5)*exp({args.phi}*N(0,1)), "
                                f"num_slices={s} ({pairs} INT8 slice products)",
                    "m": m, "n": n, "k": k, "num_slices": s, "phi": args.phi},
         "roofline": {
