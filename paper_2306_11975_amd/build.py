@@ -13,7 +13,7 @@ INCLUDE = PKG.parent / "include"
 OBJ = PKG / "_build"
 LIB = PKG / "libozimmu.so"
 
-SOURCES = ["split.hip", "gemm.hip", "probes.hip", "api.cpp"]
+SOURCES = ["split.hip", "gemm.hip", "gemm_fused.hip", "probes.hip", "api.cpp"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", f"-I{INCLUDE}", f"-I{CSRC}"]
 # device code: gfx950 only; packed-FP32 instruction selection is switched off on the test machines
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -77,7 +77,8 @@ ozimmu_status_t check_gemm_args(int64_t m, int64_t n, int64_t k, const void* A, 
 // One real Ozaki product from already split operands: G = sum over diagonals, written to C with
 // the given column stride and combine mode.
 hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned char* ws, int plane_a, int plane_b,
-                       double* C, int64_t ldc, int c_inc, int c_mode, hipStream_t st) {
+                       double* C, int64_t ldc, int c_inc, int c_mode, hipStream_t st, int dual = 0,
+                       int plane_a2 = 0, int plane_b2 = 0) {
     GemmArgs g{};
     g.SA = reinterpret_cast<const int8_t*>(ws + L.off_sa[plane_a]);
     g.SB = reinterpret_cast<const int8_t*>(ws + L.off_sb[plane_b]);
@@ -101,6 +102,15 @@ hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned ch
     g.c_mode = c_mode;
     g.EA = reinterpret_cast<const int32_t*>(ws + L.off_ea[plane_a]);
     g.EB = reinterpret_cast<const int32_t*>(ws + L.off_eb[plane_b]);
+    g.dual = dual;
+    if (dual) {  // only the register-resident kernel combines two products
+        g.SA2 = reinterpret_cast<const int8_t*>(ws + L.off_sa[plane_a2]);
+        g.SB2 = reinterpret_cast<const int8_t*>(ws + L.off_sb[plane_b2]);
+        g.EA2 = reinterpret_cast<const int32_t*>(ws + L.off_ea[plane_a2]);
+        g.EB2 = reinterpret_cast<const int32_t*>(ws + L.off_eb[plane_b2]);
+        if (!fused_gemm_applies(g, L.wide)) return hipErrorInvalidValue;
+    }
+    if (fused_gemm_applies(g, L.wide)) return launch_fused_gemm(g, st);
     return launch_slice_gemm(g, L.wide, st);
 }
 
@@ -267,10 +277,16 @@ ozimmu_status_t ozimmu_zgemm(int64_t m, int64_t n, int64_t k, const double* A, i
                               reinterpret_cast<unsigned long long*>(ws + L.off_colmax), st);
     // Cr = G(Ar,Br) - G(Ai,Bi);  Ci = G(Ar,Bi) + G(Ai,Br): the second product of each part is
     // combined with the first by one rounded FP64 operation in the kernel's epilogue.
-    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 0, C, 2 * ldc, 2, 0, st);
-    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 1, C, 2 * ldc, 2, 2, st);
-    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, C + 1, 2 * ldc, 2, 0, st);
-    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 0, C + 1, 2 * ldc, 2, 1, st);
+    if (!L.wide && L.k_pad <= kFusedMaxK) {
+        // short k: both products of a part in one launch, the first one never leaves the registers
+        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 0, C, 2 * ldc, 2, 0, st, 2, 1, 1);
+        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, C + 1, 2 * ldc, 2, 0, st, 1, 1, 0);
+    } else {
+        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 0, C, 2 * ldc, 2, 0, st);
+        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 1, C, 2 * ldc, 2, 2, st);
+        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, C + 1, 2 * ldc, 2, 0, st);
+        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 0, C + 1, 2 * ldc, 2, 1, st);
+    }
     return hip_status(e);
 }
 

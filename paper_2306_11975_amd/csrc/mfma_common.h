@@ -1,0 +1,76 @@
+// Device helpers shared by the slice-product kernels (gfx950 only).
+#pragma once
+
+#include "ozimmu_internal.h"
+
+namespace ozimmu {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef long long v2l __attribute__((ext_vector_type(2)));
+
+// Workgroup -> tile. Hardware deals workgroups round-robin over the 8 XCDs (each with its own
+// L2); give every XCD a contiguous run of tiles, ordered in column panels 4 tiles tall so that
+// the 32 workgroups resident on an XCD share A and B panels through that L2.
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
+    const int total = tiles_m * tiles_n;
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int q = total >> 3, r = total & 7;
+    const int logical = xcd * q + (xcd < r ? xcd : r) + slot;
+    constexpr int GM = 4;
+    const int per_group = GM * tiles_n;
+    const int group = logical / per_group;
+    const int first_m = group * GM;
+    const int rows = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+    const int in_group = logical - group * per_group;
+    tm = first_m + in_group % rows;
+    tn = in_group / rows;
+}
+
+// A zero the optimiser cannot see through. Address arithmetic of the code that runs after the
+// k-walk is made to depend on it, so that it is computed there and not hoisted above the walk,
+// where it would occupy registers the matrix-core loop needs.
+__device__ __forceinline__ unsigned opaque_zero() {
+    unsigned z;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+    return z;
+}
+
+// The accumulators live in the accumulation half of the register file for the whole k-walk.
+// Initialising and reading them through these two helpers pins that choice, so that no copies
+// between the two halves of the file are made around the loop.
+__device__ __forceinline__ int acc_zero() {
+    int a;
+    asm("v_accvgpr_write_b32 %0, 0" : "=a"(a));
+    return a;
+}
+__device__ __forceinline__ int acc_read(int a) {
+    int v;
+    asm("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
+}
+
+// One wavefront-wide direct load: lane i fetches 16 bytes from gbase + voff_i and the hardware
+// writes them to LDS at lds_addr + 16 i (M0 carries the LDS base). Issued as inline assembly so
+// that its completion is awaited only by the explicit vmcnt before the step barrier and not
+// before every LDS read in between.
+__device__ __forceinline__ void dma_load16(const void* gbase, unsigned voff, unsigned lds_addr) {
+    asm volatile(
+        "s_mov_b32 m0, %2\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %0"
+        :
+        : "s"(gbase), "v"(voff), "s"(lds_addr)
+        : "memory");  // M0 is written here; nothing else in this kernel uses it
+}
+
+// Wait until at most N of this wave's direct loads are outstanding (they return in order, so
+// everything older has landed) and until its own LDS reads are done, then meet the other waves.
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(N) : "memory");
+}
+
+}  // namespace
+}  // namespace ozimmu

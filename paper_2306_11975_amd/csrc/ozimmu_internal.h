@@ -37,6 +37,13 @@ struct GemmArgs {
     int c_mode;            // 0: C = G, 1: C = C + G, 2: C = C - G
     const int32_t* EA;
     const int32_t* EB;
+    // second product of the register-resident kernel (dual != 0): C = G(SA,SB) + G(SA2,SB2) if
+    // dual == 1, C = G(SA,SB) - G(SA2,SB2) if dual == 2, each G scaled by its own exponents
+    int dual;
+    const int8_t* SA2;
+    const int8_t* SB2;
+    const int32_t* EA2;
+    const int32_t* EB2;
 };
 
 hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k, int s,
@@ -45,6 +52,10 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
                              int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
                              unsigned long long* colmax, hipStream_t st);
 hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st);
+// Variant for short inner dimensions that keeps the FP64 sum in registers (no use of args.D).
+constexpr int kFusedMaxK = 1024;
+bool fused_gemm_applies(const GemmArgs& args, bool wide);
+hipError_t launch_fused_gemm(const GemmArgs& args, hipStream_t st);
 hipError_t launch_fill_f64(double* C, int64_t ldc, int c_inc, int64_t m, int64_t n, double v,
                            hipStream_t st);
 hipError_t launch_fill_i32(int32_t* P, int64_t ldp, int64_t m, int64_t n, int32_t v, hipStream_t st);

@@ -132,14 +132,14 @@ __global__ __launch_bounds__(256) void fill_u64_kernel(unsigned long long* p, in
 
 // Column maxima of |B|: a lane owns a column (loads are contiguous across lanes), a workgroup
 // owns a band of rows, bands are combined with a 64-bit atomic maximum on the bit patterns.
-constexpr int kColBand = 256;
+constexpr int kColBand = 256;   // rows per band when the matrix is tall enough to fill the chip
 __global__ __launch_bounds__(256) void col_max_kernel(const double* __restrict__ B, int64_t ldb,
-                                                      int inc, int64_t k, int64_t n,
+                                                      int inc, int64_t k, int64_t n, int band,
                                                       unsigned long long* __restrict__ colmax) {
     const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= n) return;
-    const int64_t l0 = (int64_t)blockIdx.y * kColBand;
-    const int64_t l1 = l0 + kColBand < k ? l0 + kColBand : k;
+    const int64_t l0 = (int64_t)blockIdx.y * band;
+    const int64_t l1 = l0 + band < k ? l0 + band : k;
     const unsigned long long* src = reinterpret_cast<const unsigned long long*>(B);
     unsigned long long mx = 0;
     for (int64_t l = l0; l < l1; ++l) {
@@ -254,8 +254,13 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (k > 0 && n > 0) {
-        col_max_kernel<<<dim3((unsigned)((n + 255) / 256), (unsigned)((k + kColBand - 1) / kColBand)),
-                         dim3(256), 0, st>>>(B, ldb, inc, k, n, colmax);
+        // short matrices: thinner bands, so that a few thousand workgroups exist
+        const int64_t bx = (n + 255) / 256;
+        const int64_t want_y = (2048 + bx - 1) / bx;
+        int64_t band = (k + want_y - 1) / want_y;
+        band = band < 8 ? 8 : (band > kColBand ? kColBand : band);
+        col_max_kernel<<<dim3((unsigned)bx, (unsigned)((k + band - 1) / band)), dim3(256), 0, st>>>(
+            B, ldb, inc, k, n, (int)band, colmax);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

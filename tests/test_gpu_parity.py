@@ -178,7 +178,11 @@ def test_config1_64_cubed_bit_exact(s):
 
 @pytest.mark.parametrize("m,n,k,s,phi,seed", [(300, 270, 517, 8, 1.0, 2), (257, 513, 130, 13, 2.0, 3),
                                               (1, 1, 1, 1, 1.0, 4), (255, 256, 128, 16, 0.5, 5),
-                                              (520, 100, 2000, 2, 4.0, 6)])
+                                              (520, 100, 2000, 2, 4.0, 6),
+                                              # around the switch between the kernel that keeps the FP64
+                                              # sum in registers (padded k <= 1024) and the general one
+                                              (300, 270, 1024, 8, 1.0, 7), (300, 270, 1025, 8, 1.0, 8),
+                                              (513, 385, 1300, 7, 2.0, 9), (129, 640, 3000, 11, 1.0, 10)])
 def test_dgemm_ragged_shapes_bit_exact(m, n, k, s, phi, seed):
     A, B = wl.phi_pair(m, n, k, phi, seed)
     assert np.array_equal(bits(gpu_dgemm(A, B, s, ldc_extra=5)), bits(oracle.dgemm(A, B, s)))
