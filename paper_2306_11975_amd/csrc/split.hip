@@ -24,31 +24,59 @@ __device__ __forceinline__ int exponent_of_max(unsigned long long maxbits) {
     return (64 - __clzll((long long)maxbits)) - 1074;  // subnormal maximum
 }
 
-// An element prepared for chunk extraction: |x| = M * 2^(-g) * 2^E with M < 2^53.
-struct Prepared {
-    unsigned long long M;
-    int g;      // chunk p = floor(M * 2^(7p - g)) mod 128
-    int neg;
+// |x| 2^(-E) < 1 as a binary fraction of up to 128 bits: bit 63 of hi has weight 1/2. Slice p is
+// the p-th group of 7 bits after the binary point (truncation: the bits are simply cut), so once
+// the significand sits at its place every slice is a bit field at a fixed position. The one
+// shift whose amount varies from element to element is paid once, not once per slice.
+struct Fixed {
+    unsigned long long hi, lo;
 };
 
-__device__ __forceinline__ Prepared prepare(unsigned long long bits, int E) {
-    Prepared r;
-    int e = (int)((bits >> 52) & 0x7ff);
-    unsigned long long mant = bits & kMantMask;
-    r.M = e ? (mant | (1ull << 52)) : mant;
-    r.g = E + 1075 - (e ? e : 1);
-    r.neg = (int)(bits >> 63);
-    return r;
+template <bool WIDE>   // WIDE: more than 9 slices, i.e. more than the 63 bits the upper half can serve
+__device__ __forceinline__ Fixed to_fixed(unsigned long long bits, int E) {
+    const unsigned e = (unsigned)(bits >> 52) & 0x7ffu;
+    const unsigned long long mant = bits & kMantMask;
+    // significand with its leading bit at bit 63 (subnormal: no implicit bit, exponent field 1)
+    const unsigned long long T = (e ? (mant | (1ull << 52)) : mant) << 11;
+    // right shift that puts the binary point of |x| 2^(-E) just above bit 63. Never negative for
+    // normal numbers (|x| < 2^E); in a subnormal row the significands have leading zeros of
+    // their own and the shift of the largest ones goes the other way (by at most 52).
+    const int z = E + 1022 - (int)(e ? e : 1u);
+    Fixed f;
+    f.hi = z < 0 ? T << (-z) : z < 64 ? T >> z : 0ull;
+    f.lo = 0ull;
+    if (WIDE) f.lo = z <= 0 ? 0ull : z < 64 ? T << (64 - z) : z < 128 ? T >> (z - 64) : 0ull;
+    return f;
 }
 
-__device__ __forceinline__ int chunk(const Prepared& x, int p) {
-    int nsh = x.g - OZIMMU_SLICE_BITS * p;  // right shift that brings chunk p to the low 7 bits
-    unsigned int c;
-    if (nsh >= 64) c = 0;
-    else if (nsh >= 0) c = (unsigned int)(x.M >> nsh) & 127u;
-    else if (nsh > -OZIMMU_SLICE_BITS) c = (unsigned int)(x.M << (-nsh)) & 127u;
-    else c = 0;
-    return x.neg ? -(int)c : (int)c;
+// Magnitude of slice p (1-based). With p a constant after unrolling this is one bit-field
+// extract of a 32-bit half, or a funnel shift when the field straddles two words.
+__device__ __forceinline__ unsigned field(const Fixed& f, int p) {
+    const int o = OZIMMU_SLICE_BITS * (p - 1);   // bits of the fraction ahead of the field
+    if (o + OZIMMU_SLICE_BITS <= 64) return (unsigned)(f.hi >> (64 - OZIMMU_SLICE_BITS - o)) & 127u;
+    if (o >= 64) return (unsigned)(f.lo >> (128 - OZIMMU_SLICE_BITS - o)) & 127u;
+    return ((unsigned)(f.hi << (o + OZIMMU_SLICE_BITS - 64)) & 127u) | (unsigned)(f.lo >> (128 - OZIMMU_SLICE_BITS - o));
+}
+
+// Signs of four consecutive elements as byte masks, and the byte-wise negation of the packed
+// magnitudes c (each 0..127) where the sign is set: per byte (c ^ 0xff) + 1 without a carry into
+// the next byte, i.e. the low seven bits are added on their own and the top bit is put back.
+struct SignMask {
+    uint32_t m7, m1, m80;
+};
+__device__ __forceinline__ SignMask sign_mask(unsigned long long b0, unsigned long long b1,
+                                              unsigned long long b2, unsigned long long b3) {
+    const uint32_t m = ((uint32_t)(b0 >> 63) * 0xffu) | ((uint32_t)(b1 >> 63) * 0xff00u) |
+                       ((uint32_t)(b2 >> 63) * 0xff0000u) | ((uint32_t)(b3 >> 63) * 0xff000000u);
+    return {m & 0x7f7f7f7fu, m & 0x01010101u, m & 0x80808080u};
+}
+__device__ __forceinline__ uint32_t apply_sign(uint32_t packed, const SignMask& sm) {
+    return ((packed ^ sm.m7) + sm.m1) ^ sm.m80;
+}
+template <bool WIDE>
+__device__ __forceinline__ uint32_t packed_slice(const Fixed (&x)[4], const SignMask& sm, int p) {
+    const uint32_t c = field(x[0], p) | (field(x[1], p) << 8) | (field(x[2], p) << 16) | (field(x[3], p) << 24);
+    return apply_sign(c, sm);
 }
 
 // Byte offset, inside one slice, of the 4-byte word that holds positions l0 .. l0+3 (l0 % 4 == 0)
@@ -69,9 +97,38 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
 }
 
 // ------------------------------------------------------------------------------ rows of A
-// One workgroup per padded row. Pass 1: maximum of |x| bit patterns (monotone in |x|), wave
-// reduction then LDS. Pass 2: the row is read again (it was just streamed through L2) and
-// four consecutive elements per lane are packed into one 32-bit store per slice.
+// One workgroup per padded row; a thread owns words of four consecutive elements (one 32-bit
+// store per slice). Pass 1: maximum of the |x| bit patterns (monotone in |x|), wave reduction
+// then LDS. Pass 2: emission. A row of up to 8192 elements stays in registers between the two
+// passes (CACHED), so A is read from memory once; longer rows are read twice.
+constexpr int kRowCacheWords = 8;   // words of 4 elements per thread that fit the register cache
+
+template <bool VEC>   // VEC: unit stride and 16-byte aligned rows, two 16-byte loads per word
+__device__ __forceinline__ void load_word(const unsigned long long* src, int64_t l0, int64_t k, int inc,
+                                          unsigned long long (&b)[4]) {
+    if (VEC && l0 + 4 <= k) {
+        const ulonglong2 v0 = *reinterpret_cast<const ulonglong2*>(src + l0);
+        const ulonglong2 v1 = *reinterpret_cast<const ulonglong2*>(src + l0 + 2);
+        b[0] = v0.x; b[1] = v0.y; b[2] = v1.x; b[3] = v1.y;
+    } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) b[u] = (l0 + u < k) ? src[(l0 + u) * inc] : 0ull;
+    }
+}
+
+template <bool WIDE>
+__device__ __forceinline__ void emit_word(const unsigned long long (&b)[4], int E, int s, int8_t* dst,
+                                          int64_t slice_stride) {
+    Fixed x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) x[u] = to_fixed<WIDE>(b[u], E);
+    const SignMask sm = sign_mask(b[0], b[1], b[2], b[3]);
+#pragma unroll
+    for (int p = 1; p <= (WIDE ? OZIMMU_MAX_SLICES : 9); ++p)   // unrolled: p is a constant in field()
+        if (p <= s) *reinterpret_cast<uint32_t*>(dst + (int64_t)(p - 1) * slice_stride) = packed_slice<WIDE>(x, sm, p);
+}
+
+template <bool WIDE, bool CACHED, bool VEC>
 __global__ __launch_bounds__(256) void split_rows_kernel(const double* __restrict__ A, int64_t lda,
                                                          int inc, int m, int64_t k, int s,
                                                          int8_t* __restrict__ S, int64_t m_pad,
@@ -89,11 +146,31 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const double* __restric
         return;
     }
 
-    const unsigned long long* src = reinterpret_cast<const unsigned long long*>(A) + (int64_t)row * lda * 1;
+    const unsigned long long* src = reinterpret_cast<const unsigned long long*>(A) + (int64_t)row * lda;
+    unsigned long long cache[CACHED ? kRowCacheWords : 1][4];
     unsigned long long mx = 0;
-    for (int64_t l = tid; l < k; l += 256) {
-        unsigned long long b = src[l * inc] & kAbsMask;
-        mx = b > mx ? b : mx;
+    if (CACHED) {
+#pragma unroll
+        for (int j = 0; j < kRowCacheWords; ++j) {
+            const int64_t w = tid + 256 * j;
+            if (w < words) load_word<VEC>(src, w * 4, k, inc, cache[j]);
+            else cache[j][0] = cache[j][1] = cache[j][2] = cache[j][3] = 0ull;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const unsigned long long a = cache[j][u] & kAbsMask;
+                mx = a > mx ? a : mx;
+            }
+        }
+    } else {
+        for (int64_t w = tid; w < words; w += 256) {
+            unsigned long long b[4];
+            load_word<VEC>(src, w * 4, k, inc, b);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const unsigned long long a = b[u] & kAbsMask;
+                mx = a > mx ? a : mx;
+            }
+        }
     }
     mx = wave_max_u64(mx);
     __shared__ unsigned long long wmax[4];
@@ -105,20 +182,17 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const double* __restric
     const int E = exponent_of_max(mx);
     if (tid == 0) Eout[row] = E;
 
-    for (int64_t w = tid; w < words; w += 256) {
-        const int64_t l0 = w * 4;
-        Prepared x[4];
+    if (CACHED) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            unsigned long long b = (l0 + u < k) ? src[(l0 + u) * inc] : 0ull;
-            x[u] = prepare(b, E);
+        for (int j = 0; j < kRowCacheWords; ++j) {
+            const int64_t w = tid + 256 * j;
+            if (w < words) emit_word<WIDE>(cache[j], E, s, S + word_offset(row, w * 4, k_pad), slice_stride);
         }
-        const int64_t off = word_offset(row, l0, k_pad);
-        for (int p = 1; p <= s; ++p) {
-            uint32_t packed = 0;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) packed |= ((uint32_t)chunk(x[u], p) & 0xffu) << (8 * u);
-            *reinterpret_cast<uint32_t*>(S + (int64_t)(p - 1) * slice_stride + off) = packed;
+    } else {
+        for (int64_t w = tid; w < words; w += 256) {
+            unsigned long long b[4];
+            load_word<VEC>(src, w * 4, k, inc, b);
+            emit_word<WIDE>(b, E, s, S + word_offset(row, w * 4, k_pad), slice_stride);
         }
     }
 }
@@ -158,8 +232,10 @@ __global__ __launch_bounds__(256) void col_exponent_kernel(const unsigned long l
 // Slice emission for B^T: a workgroup takes a 128 (l) x 64 (j) tile of B. Lane (jj, lg) reads
 // 32 elements of column jj (contiguous across lanes for each l), packs four consecutive l per
 // slice into one word and transposes through LDS so that the global stores run along l.
-constexpr int kColTileL = 128, kColTileJ = 64, kColGroup = 7;
+constexpr int kColTileL = 128, kColTileJ = 64;
+constexpr int kColGroup = 4;   // slices transposed through LDS at a time: 34 KiB, four workgroups per CU
 constexpr int kColLdsStride = kColTileL / 4 + 1;  // words per LDS row (+1: conflict-free columns)
+template <bool WIDE>
 __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restrict__ B, int64_t ldb,
                                                          int inc, int64_t k, int64_t n, int s,
                                                          int8_t* __restrict__ S, int64_t n_pad,
@@ -174,23 +250,28 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
     const unsigned long long* src = reinterpret_cast<const unsigned long long*>(B);
     const int E = (j < n) ? exponent_of_max(colmax[j]) : 0;
 
-    Prepared x[32];
+    Fixed x[8][4];
+    SignMask sm[8];
 #pragma unroll
-    for (int u = 0; u < 32; ++u) {
-        const int64_t l = lbase + lg * 32 + u;
-        unsigned long long b = (j < n && l < k) ? src[(l * ldb + j) * inc] : 0ull;
-        x[u] = prepare(b, E);
+    for (int u4 = 0; u4 < 8; ++u4) {
+        unsigned long long b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t l = lbase + lg * 32 + u4 * 4 + u;
+            b[u] = (j < n && l < k) ? src[(l * ldb + j) * inc] : 0ull;
+            x[u4][u] = to_fixed<WIDE>(b[u], E);
+        }
+        sm[u4] = sign_mask(b[0], b[1], b[2], b[3]);
     }
-    for (int p0 = 1; p0 <= s; p0 += kColGroup) {
+#pragma unroll
+    for (int p0 = 1; p0 <= (WIDE ? OZIMMU_MAX_SLICES : 9); p0 += kColGroup) {   // unrolled: slice numbers are constants
+        if (p0 > s) continue;   // uniform
         const int np = (s - p0 + 1) < kColGroup ? (s - p0 + 1) : kColGroup;
-        for (int pp = 0; pp < np; ++pp) {
 #pragma unroll
-            for (int u4 = 0; u4 < 8; ++u4) {
-                uint32_t packed = 0;
+        for (int pp = 0; pp < kColGroup; ++pp) {
+            if (pp < np && p0 + pp <= OZIMMU_MAX_SLICES) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    packed |= ((uint32_t)chunk(x[u4 * 4 + u], p0 + pp) & 0xffu) << (8 * u);
-                tile[pp][jj][lg * 8 + u4] = packed;
+                for (int u4 = 0; u4 < 8; ++u4) tile[pp][jj][lg * 8 + u4] = packed_slice<WIDE>(x[u4], sm[u4], p0 + pp);
             }
         }
         __syncthreads();
@@ -241,8 +322,19 @@ unsigned fill_blocks(int64_t elems) {
 hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k, int s,
                              int8_t* S, int64_t m_pad, int64_t k_pad, int32_t* E, hipStream_t st) {
     if (m_pad == 0) return hipSuccess;
-    split_rows_kernel<<<dim3((unsigned)m_pad), dim3(256), 0, st>>>(A, lda * inc, inc, (int)m, k, s, S,
-                                                                   m_pad, k_pad, E);
+    const bool wide = s > 9;
+    const bool cached = k_pad <= 4 * 256 * kRowCacheWords;
+    const bool vec = inc == 1 && lda % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
+    const dim3 grid((unsigned)m_pad), block(256);
+#define OZ_ROWS(W, C, V) split_rows_kernel<W, C, V><<<grid, block, 0, st>>>(A, lda * inc, inc, (int)m, k, s, S, m_pad, k_pad, E)
+    if (wide) {
+        if (cached) { if (vec) OZ_ROWS(true, true, true); else OZ_ROWS(true, true, false); }
+        else        { if (vec) OZ_ROWS(true, false, true); else OZ_ROWS(true, false, false); }
+    } else {
+        if (cached) { if (vec) OZ_ROWS(false, true, true); else OZ_ROWS(false, true, false); }
+        else        { if (vec) OZ_ROWS(false, false, true); else OZ_ROWS(false, false, false); }
+    }
+#undef OZ_ROWS
     return hipGetLastError();
 }
 
@@ -269,8 +361,9 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    split_cols_kernel<<<dim3((unsigned)(n_pad / kColTileJ), (unsigned)(k_pad / kColTileL)), dim3(256),
-                        0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax);
+    const dim3 grid((unsigned)(n_pad / kColTileJ), (unsigned)(k_pad / kColTileL));
+    if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax);
+    else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax);
     return hipGetLastError();
 }
 
