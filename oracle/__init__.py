@@ -9,8 +9,11 @@ Pins (see tests/test_oracle_*.py): closed forms of Section 3.2, exact reconstruc
 truncation bounds of the slices, brute force on raw bit patterns with Python integers,
 exact-rational products on tiny inputs, the INT32 overflow bound, and the integer-matrix
 special case in which the result must equal a plain integer matrix product.
-Unpinned: the paper's error curves and its Table 3 figures (plots and circuit
-configurations are not available in text form) -- parity unpinned for those.
+The automatic slice count (Section 4.4) is pinned by a bit-position brute force on raw
+patterns, the single-binade closed form, exact reconstruction at threshold 0 and monotonicity.
+Unpinned: the paper's error curves and its Table 3 figures, and the slice counts its
+automatic mode picked for its circuits (plots and circuit configurations are not available
+in text form) -- parity unpinned for those.
 """
 from __future__ import annotations
 
@@ -72,6 +75,10 @@ def _load():
             f.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32]
         lib.oz_dd_gemm.restype = None
         lib.oz_dd_gemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp]
+        lib.oz_auto_loss_sums.restype = None
+        lib.oz_auto_loss_sums.argtypes = [i64, i64, vp, i64, i64, i32, i32, vp]
+        lib.oz_auto_num_slices.restype = i32
+        lib.oz_auto_num_slices.argtypes = [i32, i32, vp, vp, dbl]
         lib.oz_abs_gemm.restype = None
         lib.oz_abs_gemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp]
         _lib = lib
@@ -220,3 +227,30 @@ def abs_gemm(A, B) -> np.ndarray:
     G = np.zeros((m, n), dtype=np.float64)
     _load().oz_abs_gemm(m, n, k, _p(A), k, _p(B), n, _p(G))
     return G
+
+
+def auto_loss_sums(M, by_columns: bool, s_max: int = 16) -> np.ndarray:
+    """Section 4.4 (INT8-AUTO): sum over the elements of the real matrix M of the mantissa bits
+    lost with s = 1 .. s_max slices, exponents per row (A) or per column (B). uint64[s_max]."""
+    M = _f64(M)
+    rows, cols = M.shape
+    out = np.zeros(s_max, dtype=np.uint64)
+    _load().oz_auto_loss_sums(rows, cols, _p(M), cols, 1, int(bool(by_columns)), s_max, _p(out))
+    return out
+
+
+def auto_num_slices(A, B, T: float, s_max: int = 16):
+    """Section 4.4 (INT8-AUTO): the smallest number of slices whose average mantissa loss is <= T
+    for every input plane. A (m x k) and B (k x n) real or complex. Returns (s, sums[planes][s_max])."""
+    A = np.asarray(A)
+    B = np.asarray(B)
+    planes = []
+    for M, by_cols in ((A, False), (B, True)):
+        if np.iscomplexobj(M):
+            planes += [(np.ascontiguousarray(M.real), by_cols), (np.ascontiguousarray(M.imag), by_cols)]
+        else:
+            planes.append((M, by_cols))
+    sums = np.stack([auto_loss_sums(M, bc, s_max) for M, bc in planes])
+    counts = np.array([M.size for M, _ in planes], dtype=np.int64)
+    s = int(_load().oz_auto_num_slices(len(planes), s_max, _p(np.ascontiguousarray(sums)), _p(counts), float(T)))
+    return s, sums

@@ -15,6 +15,9 @@
  *     memory (slice p of the paper is index p-1);
  *   - exponents are plain integers E with e = 2^E (the paper's exponent offset vector).
  *
+ * Parity unpinned: the paper's error curves, its Table 3 figures and the slice counts
+ * its automatic mode picked for its circuits (only in figures that are not available).
+ *
  * No blocking, no fusion, no reordering beyond what is stated in each comment.
  * Compile with -ffp-contract=off (no fused multiply-add may be formed by the compiler;
  * the only FMA used is the explicit fma() of the double-double reference).
@@ -318,4 +321,63 @@ void oz_abs_gemm(int64_t m, int64_t n, int64_t k, const double *A, int64_t lda, 
             for (int64_t l = 0; l < k; ++l) acc = acc + fabs(A[i * lda + l]) * fabs(B[l * ldb + j]);
             G[i * n + j] = acc;
         }
+}
+
+/* ---------------------------------------------------------------------------------
+ * Automatic choice of the number of slices (Section 4.4, "INT8-AUTO"): every element
+ * of both inputs is inspected and the smallest number of slices is taken for which
+ * the average number of mantissa bits lost in the splitting is at most a threshold T
+ * (T = 0: the split loses nothing).
+ *
+ * Reading used here (the paper gives no formula). An element x != 0 of a row with
+ * exponent E has its leading bit at fraction position z + 1 after the binary point of
+ * |x| 2^-E (z = E - frexp exponent of x) and its lowest stored mantissa bit at
+ * position z + L, where L = 53 for a normal number and the number of stored
+ * significant bits for a subnormal one. s slices keep positions 1 .. 7 s, so
+ *     lost(x, s) = number of the L mantissa positions beyond 7 s
+ *                = min(L, max(0, z + L - 7 s)),
+ * counted by position, whatever the value of the bits there. Zeros lose nothing but
+ * count in the average. The average is taken per input matrix (per real plane of a
+ * complex one) over all its elements, and every matrix must meet the threshold.
+ * ------------------------------------------------------------------------------- */
+
+/* loss_sums[s - 1] = sum over the elements of M of lost(x, s), s = 1 .. s_max, for the
+ * rows of M (by_columns = 0: rows x cols with leading dimension ld and element stride
+ * inc) or its columns (by_columns = 1: the exponent is per column). */
+void oz_auto_loss_sums(int64_t rows, int64_t cols, const double *M, int64_t ld, int64_t inc,
+                       int by_columns, int s_max, uint64_t *loss_sums) {
+    for (int s = 1; s <= s_max; ++s) loss_sums[s - 1] = 0;
+    int64_t outer = by_columns ? cols : rows, inner = by_columns ? rows : cols;
+    for (int64_t o = 0; o < outer; ++o) {
+        const double *vec = by_columns ? M + o * inc : M + o * ld * 1;
+        int64_t stride = by_columns ? ld : inc;
+        int E = row_exponent(vec, inner, stride);
+        for (int64_t l = 0; l < inner; ++l) {
+            double x = vec[l * stride];
+            if (x == 0.0) continue;
+            int ex;
+            (void)frexp(fabs(x), &ex);
+            int z = E - ex;
+            int L = ex + 1074 < 53 ? ex + 1074 : 53; /* subnormals store fewer bits */
+            for (int s = 1; s <= s_max; ++s) {
+                int beyond = z + L - OZ_W * s;
+                if (beyond < 0) beyond = 0;
+                if (beyond > L) beyond = L;
+                loss_sums[s - 1] += (uint64_t)beyond;
+            }
+        }
+    }
+}
+
+/* The smallest s in 1 .. s_max for which every plane's average loss is <= T; s_max if
+ * none is. sums is [planes][s_max], counts[planes] the number of elements of each
+ * plane. The comparison is sum <= T * count in double precision. */
+int oz_auto_num_slices(int planes, int s_max, const uint64_t *sums, const int64_t *counts, double T) {
+    for (int s = 1; s <= s_max; ++s) {
+        int ok = 1;
+        for (int p = 0; p < planes; ++p)
+            if (!((double)sums[(int64_t)p * s_max + (s - 1)] <= T * (double)counts[p])) ok = 0;
+        if (ok) return s;
+    }
+    return s_max;
 }

@@ -452,3 +452,93 @@ def test_degenerate_shapes():
     assert C.shape == (3, 2) and not C.any() and not np.signbit(C).any()
     C = oracle.dgemm(np.array([[1.5, -1.5]]), np.array([[2.0], [2.0]]), 6)
     assert C[0, 0] == 0.0 and not np.signbit(C[0, 0])
+
+
+# ------------------------------------------------------------------ INT8-AUTO (Section 4.4)
+def brute_loss_sums(M, by_columns, s_max=16):
+    """Lost mantissa bits per slice count from the raw bit patterns: every stored bit of the
+    significand is placed at its position after the binary point of |x| 2^-E and counted if it
+    lies beyond the 7 s positions that s slices keep."""
+    M = np.asarray(M, dtype=np.float64)
+    vecs = M.T if by_columns else M
+    sums = [0] * s_max
+    for vec in vecs:
+        E = brute_exponent(vec)
+        for x in vec:
+            _, Mi, ex = decompose(float(x))
+            if Mi == 0:
+                continue
+            nbits = 53 if Mi >> 52 else Mi.bit_length()     # stored significant bits
+            # bit i of Mi has weight 2^(ex + i); its position after the binary point is E - ex - i
+            positions = [E - ex - i for i in range(Mi.bit_length() - nbits, Mi.bit_length())]
+            assert min(positions) >= 1
+            for s in range(1, s_max + 1):
+                sums[s - 1] += sum(1 for q in positions if q > W * s)
+    return np.array(sums, dtype=np.uint64)
+
+
+def test_auto_loss_sums_match_bit_position_brute_force():
+    A, B = wl.phi_pair(9, 11, 13, 2.0, seed=21)
+    assert np.array_equal(oracle.auto_loss_sums(A, False), brute_loss_sums(A, False))
+    assert np.array_equal(oracle.auto_loss_sums(B, True), brute_loss_sums(B, True))
+    M = wl.adversarial_matrix(12, 17, seed=5)    # zeros, powers of two, subnormals, huge and tiny rows
+    assert np.array_equal(oracle.auto_loss_sums(M, False), brute_loss_sums(M, False))
+    assert np.array_equal(oracle.auto_loss_sums(M, True), brute_loss_sums(M, True))
+
+
+def test_auto_single_binade_closed_form():
+    """All entries in [1, 2): no leading zeros anywhere, every element loses max(0, 53 - 7 s) bits,
+    so the choice is ceil((53 - T) / 7) whatever the shape."""
+    rng = np.random.default_rng(3)
+    A = 1.0 + rng.random((20, 30))
+    B = -(1.0 + rng.random((30, 10)))
+    sums = oracle.auto_loss_sums(A, False)
+    assert [int(v) for v in sums] == [A.size * max(0, 53 - 7 * s) for s in range(1, 17)]
+    for T, want in ((0, 8), (3, 8), (4, 7), (10.99, 7), (11, 6), (25, 4), (46, 1), (60, 1)):
+        assert oracle.auto_num_slices(A, B, T)[0] == want, T
+    assert oracle.auto_num_slices(A, B, 0, s_max=6)[0] == 6      # nothing qualifies: the maximum is returned
+
+
+def test_auto_threshold_zero_means_exact_split_and_is_minimal():
+    A, B = wl.phi_pair(15, 12, 20, 1.5, seed=8)
+    s, sums = oracle.auto_num_slices(A, B, 0.0)
+    assert (sums[:, s - 1] == 0).all() and (sums[:, s - 2] > 0).any()
+    EA, SA = oracle.split_rows(A, s)
+    EB, SB = oracle.split_cols(B, s)
+    for (E, S, M) in ((EA, SA, A), (EB, SB, B.T)):
+        for i in range(M.shape[0]):
+            for l in range(M.shape[1]):
+                rec = sum(Fraction(int(S[p, i, l])) * Fraction(2) ** (int(E[i]) - W * (p + 1)) for p in range(s))
+                assert rec == Fraction(float(M[i, l]))
+
+
+def test_auto_monotone_and_scale_invariant():
+    A, B = wl.phi_pair(30, 25, 40, 2.0, seed=4)
+    picks = [oracle.auto_num_slices(A, B, T)[0] for T in (0, 0.25, 0.5, 1, 2, 4, 8, 16, 32, 53)]
+    assert picks == sorted(picks, reverse=True) and picks[-1] == 1
+    sums = oracle.auto_loss_sums(A, False)
+    assert all(int(sums[i]) >= int(sums[i + 1]) for i in range(15))
+    assert all(int(sums[i]) - int(sums[i + 1]) <= 7 * A.size for i in range(15))
+    A2 = A * np.ldexp(1.0, np.arange(30) % 9 - 4)[:, None]       # rows scaled by powers of two
+    assert np.array_equal(oracle.auto_loss_sums(A2, False), sums)
+    # a complex input is judged plane by plane
+    Z = A + 1j * A[::-1]
+    s_c, sums_c = oracle.auto_num_slices(Z, B, 1.0)
+    assert sums_c.shape == (3, 16)
+    assert s_c == max(oracle.auto_num_slices(A, B, 1.0)[0], oracle.auto_num_slices(A[::-1].copy(), B, 1.0)[0])
+
+
+def test_auto_on_random_unitary_gate_is_in_the_range_the_paper_reports():
+    """Section 4.4 reports 12-13 slices at T = 0 and 8-9 at T = 1 for its random-unitary circuits.
+    Those circuits are defined in a figure that is not available, so this is a plausibility check
+    on the same kind of input (Haar-like unitary from the QR of a complex Gaussian matrix applied to
+    a normalised random state reshaped to 2^(N-d) x 2^d), not a like-for-like pin."""
+    rng = np.random.default_rng(5)
+    d, N = 7, 16
+    G = rng.standard_normal((2 ** d, 2 ** d)) + 1j * rng.standard_normal((2 ** d, 2 ** d))
+    Q, _ = np.linalg.qr(G)
+    psi = rng.standard_normal(2 ** N) + 1j * rng.standard_normal(2 ** N)
+    psi /= np.linalg.norm(psi)
+    A = psi.reshape(2 ** (N - d), 2 ** d)
+    assert oracle.auto_num_slices(A, Q, 0.0)[0] in (11, 12, 13)
+    assert oracle.auto_num_slices(A, Q, 1.0)[0] in (8, 9)
