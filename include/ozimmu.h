@@ -143,6 +143,34 @@ ozimmu_status_t ozimmu_dgemm_stage(int stage, int64_t m, int64_t n, int64_t k, c
                                    size_t workspace_bytes, void* stream);
 
 /*
+ * Automatic choice of the number of slices (Section 4.4, "INT8-AUTO": all elements of the inputs
+ * are inspected and the number of slices is taken so that the average mantissa loss of the split
+ * stays within a threshold; threshold 0 means a lossless split).
+ *
+ * Definition used (the paper gives no formula): an element x != 0 whose row (A) or column (B) has
+ * exponent E has its leading bit z + 1 places after the binary point of |x| 2^-E and stores L
+ * significant bits (53; fewer if subnormal); s slices keep 7 s places, so the element loses
+ * min(L, max(0, z + L - 7 s)) bits, counted by position. Zeros lose nothing and count in the
+ * average. The average is taken per input matrix (per real plane if is_complex) over all its
+ * elements. *num_slices = the smallest s in 1 .. max_slices for which every plane's sum of lost
+ * bits is <= threshold * (number of elements), compared in double precision; max_slices if none.
+ *
+ * A, B: device pointers, row-major as for ozimmu_dgemm / ozimmu_zgemm (interleaved complex if
+ * is_complex). scratch: device memory, 256-byte aligned, at least ozimmu_auto_scratch_bytes(n).
+ * num_slices: HOST pointer. loss_sums: optional HOST array of planes * 16 uint64 (planes = 2, or
+ * 4 if is_complex: A re, A im, B re, B im / A, B), receives the sums of lost bits for
+ * s = 1 .. 16. Unlike the other entry points this one returns a result to the host: it
+ * enqueues its kernels on `stream`, copies 512 bytes back and waits for the stream
+ * (it cannot be captured into a graph). Errors as for ozimmu_dgemm; a negative or NaN threshold
+ * or max_slices outside 1 .. 16 give OZIMMU_ERR_BAD_SLICES.
+ */
+ozimmu_status_t ozimmu_auto_scratch_bytes(int64_t n, size_t* bytes);
+ozimmu_status_t ozimmu_auto_num_slices(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                                       const double* B, int64_t ldb, int is_complex, double threshold,
+                                       int max_slices, void* scratch, size_t scratch_bytes,
+                                       int* num_slices, uint64_t* loss_sums, void* stream);
+
+/*
  * Device characterisation (measurement utilities for the benchmark, not part of the product
  * path; unlike every entry point above they allocate a few KiB for the duration of the call and
  * synchronise the device).

@@ -290,4 +290,54 @@ ozimmu_status_t ozimmu_zgemm(int64_t m, int64_t n, int64_t k, const double* A, i
     return hip_status(e);
 }
 
+ozimmu_status_t ozimmu_auto_scratch_bytes(int64_t n, size_t* bytes) {
+    if (n < 0 || n > kMaxDim) return OZIMMU_ERR_BAD_DIM;
+    if (!bytes) return OZIMMU_ERR_NULL;
+    *bytes = 512 + sizeof(unsigned long long) * (size_t)round_up(n, kTile);
+    return OZIMMU_OK;
+}
+
+ozimmu_status_t ozimmu_auto_num_slices(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                                       const double* B, int64_t ldb, int is_complex, double threshold,
+                                       int max_slices, void* scratch, size_t scratch_bytes,
+                                       int* num_slices, uint64_t* loss_sums, void* stream) {
+    if (!dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
+    if (max_slices < 1 || max_slices > OZIMMU_MAX_SLICES || !(threshold >= 0.0)) return OZIMMU_ERR_BAD_SLICES;
+    if (!num_slices) return OZIMMU_ERR_NULL;
+    if ((m > 0 && lda < k) || (k > 0 && ldb < n)) return OZIMMU_ERR_BAD_LD;
+    if ((m > 0 && k > 0 && !A) || (k > 0 && n > 0 && !B)) return OZIMMU_ERR_NULL;
+    size_t need = 0;
+    ozimmu_auto_scratch_bytes(n, &need);
+    if (!scratch || (reinterpret_cast<uintptr_t>(scratch) % OZIMMU_WORKSPACE_ALIGN) != 0 || scratch_bytes < need)
+        return OZIMMU_ERR_WORKSPACE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned long long* sums = static_cast<unsigned long long*>(scratch);          // [4][16]
+    unsigned long long* colmax = sums + 4 * OZIMMU_MAX_SLICES;
+    const int parts = is_complex ? 2 : 1, inc = is_complex ? 2 : 1;
+    hipError_t e = launch_fill_u64(sums, 4 * OZIMMU_MAX_SLICES, 0ull, st);
+    for (int pl = 0; pl < parts && e == hipSuccess; ++pl)
+        e = launch_loss_scan_rows(A + pl, lda, inc, m, k, sums + pl * OZIMMU_MAX_SLICES, st);
+    for (int pl = 0; pl < parts && e == hipSuccess; ++pl)
+        e = launch_loss_scan_cols(B + pl, ldb, inc, k, n, colmax, sums + (parts + pl) * OZIMMU_MAX_SLICES, st);
+    unsigned long long host[4 * OZIMMU_MAX_SLICES];
+    if (e == hipSuccess) e = hipMemcpyAsync(host, sums, sizeof(host), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return OZIMMU_ERR_HIP;
+
+    const int planes = 2 * parts;
+    const double count_a = (double)m * (double)k, count_b = (double)k * (double)n;
+    int pick = max_slices;
+    for (int s = 1; s <= max_slices; ++s) {
+        bool ok = true;
+        for (int p = 0; p < planes; ++p)
+            ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < parts ? count_a : count_b);
+        if (ok) { pick = s; break; }
+    }
+    *num_slices = pick;
+    if (loss_sums)
+        for (int i = 0; i < planes * OZIMMU_MAX_SLICES; ++i) loss_sums[i] = host[i];
+    return OZIMMU_OK;
+}
+
 }  // extern "C"

@@ -56,6 +56,12 @@ hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st);
 constexpr int kFusedMaxK = 1024;
 bool fused_gemm_applies(const GemmArgs& args, bool wide);
 hipError_t launch_fused_gemm(const GemmArgs& args, hipStream_t st);
+// Slice-count scan: adds, for s = 1 .. 16, the mantissa bits s slices would lose into sums[s - 1].
+hipError_t launch_loss_scan_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k,
+                                 unsigned long long* sums, hipStream_t st);
+hipError_t launch_loss_scan_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n,
+                                 unsigned long long* colmax, unsigned long long* sums, hipStream_t st);
+hipError_t launch_fill_u64(unsigned long long* p, int64_t count, unsigned long long v, hipStream_t st);
 hipError_t launch_fill_f64(double* C, int64_t ldc, int c_inc, int64_t m, int64_t n, double v,
                            hipStream_t st);
 hipError_t launch_fill_i32(int32_t* P, int64_t ldp, int64_t m, int64_t n, int32_t v, hipStream_t st);

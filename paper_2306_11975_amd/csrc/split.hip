@@ -299,6 +299,135 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
     }
 }
 
+// ------------------------------------------------------------------------------ slice-count scan
+// Automatic choice of the number of slices (Section 4.4, "INT8-AUTO"): every element is
+// inspected and, for each candidate s = 1 .. 16, the mantissa bits that s slices would cut off
+// are added up. An element whose leading bit sits z places below the binary point of
+// |x| 2^(-E) and that stores L significant bits (53, fewer for a subnormal) has its lowest bit
+// at position v = z + L; s slices keep positions 1 .. 7 s, so it loses min(L, max(0, v - 7 s))
+// bits. The host divides the sums by the element counts and picks the smallest s whose average
+// is within the threshold.
+struct LossAcc {
+    uint32_t lost[OZIMMU_MAX_SLICES];
+};
+__device__ __forceinline__ void loss_clear(LossAcc& a) {
+#pragma unroll
+    for (int s = 0; s < OZIMMU_MAX_SLICES; ++s) a.lost[s] = 0u;
+}
+__device__ __forceinline__ void loss_add(LossAcc& a, unsigned long long bits, int E) {
+    const unsigned long long mag = bits & kAbsMask;
+    if (mag == 0) return;
+    const int e = (int)(mag >> 52);
+    int L = 53, z = E + 1022 - e;
+    if (e == 0) {                       // subnormal: leading bit b of the stored field
+        const int b = 63 - __clzll((long long)mag);
+        L = b + 1;
+        z = E + 1073 - b;
+    }
+    const int v = z + L;
+#pragma unroll
+    for (int s = 1; s <= OZIMMU_MAX_SLICES; ++s) {
+        int beyond = v - OZIMMU_SLICE_BITS * s;
+        beyond = beyond < 0 ? 0 : (beyond > L ? L : beyond);
+        a.lost[s - 1] += (uint32_t)beyond;
+    }
+}
+// Workgroup-wide sum of the per-thread counters, then one 64-bit atomic per slice count.
+__device__ __forceinline__ void loss_flush(const LossAcc& a, uint32_t* lds16, unsigned long long* sums) {
+    if (threadIdx.x < OZIMMU_MAX_SLICES) lds16[threadIdx.x] = 0u;
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < OZIMMU_MAX_SLICES; ++s) {
+        uint32_t v = a.lost[s];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+        if ((threadIdx.x & 63) == 0 && v) atomicAdd(&lds16[s], v);
+    }
+    __syncthreads();
+    if (threadIdx.x < OZIMMU_MAX_SLICES && lds16[threadIdx.x])
+        atomicAdd(&sums[threadIdx.x], (unsigned long long)lds16[threadIdx.x]);
+}
+
+// Rows of A: one workgroup per row, maximum first (the row stays in registers if it is short
+// enough), then the loss counters.
+template <bool CACHED, bool VEC>
+__global__ __launch_bounds__(256) void loss_rows_kernel(const double* __restrict__ A, int64_t lda, int inc,
+                                                        int64_t k, unsigned long long* __restrict__ sums) {
+    const int tid = threadIdx.x;
+    const int64_t words = (k + 3) / 4;
+    const unsigned long long* src = reinterpret_cast<const unsigned long long*>(A) + (int64_t)blockIdx.x * lda;
+    unsigned long long cache[CACHED ? kRowCacheWords : 1][4];
+    unsigned long long mx = 0;
+    if (CACHED) {
+#pragma unroll
+        for (int j = 0; j < kRowCacheWords; ++j) {
+            const int64_t w = tid + 256 * j;
+            if (w < words) load_word<VEC>(src, w * 4, k, inc, cache[j]);
+            else cache[j][0] = cache[j][1] = cache[j][2] = cache[j][3] = 0ull;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const unsigned long long a = cache[j][u] & kAbsMask;
+                mx = a > mx ? a : mx;
+            }
+        }
+    } else {
+        for (int64_t w = tid; w < words; w += 256) {
+            unsigned long long b[4];
+            load_word<VEC>(src, w * 4, k, inc, b);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const unsigned long long a = b[u] & kAbsMask;
+                mx = a > mx ? a : mx;
+            }
+        }
+    }
+    mx = wave_max_u64(mx);
+    __shared__ unsigned long long wmax[4];
+    __shared__ uint32_t lds16[OZIMMU_MAX_SLICES];
+    if ((tid & 63) == 0) wmax[tid >> 6] = mx;
+    __syncthreads();
+    mx = wmax[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) mx = wmax[w] > mx ? wmax[w] : mx;
+    const int E = exponent_of_max(mx);
+
+    LossAcc acc;
+    loss_clear(acc);
+    if (CACHED) {
+#pragma unroll
+        for (int j = 0; j < kRowCacheWords; ++j)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) loss_add(acc, cache[j][u], E);   // words beyond the row hold zeros
+    } else {
+        for (int64_t w = tid; w < words; w += 256) {
+            unsigned long long b[4];
+            load_word<VEC>(src, w * 4, k, inc, b);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) loss_add(acc, b[u], E);
+        }
+    }
+    loss_flush(acc, lds16, sums);
+}
+
+// Columns of B: as the column-maximum pass, a lane owns a column and a workgroup a band of rows.
+__global__ __launch_bounds__(256) void loss_cols_kernel(const double* __restrict__ B, int64_t ldb, int inc,
+                                                        int64_t k, int64_t n, int band,
+                                                        const unsigned long long* __restrict__ colmax,
+                                                        unsigned long long* __restrict__ sums) {
+    __shared__ uint32_t lds16[OZIMMU_MAX_SLICES];
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    LossAcc acc;
+    loss_clear(acc);
+    if (j < n) {
+        const int E = exponent_of_max(colmax[j]);
+        const int64_t l0 = (int64_t)blockIdx.y * band;
+        const int64_t l1 = l0 + band < k ? l0 + band : k;
+        const unsigned long long* src = reinterpret_cast<const unsigned long long*>(B);
+        for (int64_t l = l0; l < l1; ++l) loss_add(acc, src[(l * ldb + j) * inc], E);
+    }
+    loss_flush(acc, lds16, sums);
+}
+
 __global__ __launch_bounds__(256) void fill_f64_kernel(double* C, int64_t ldc, int c_inc, int64_t m,
                                                        int64_t n, double v) {
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < m * n; idx += (int64_t)gridDim.x * 256)
@@ -318,6 +447,15 @@ unsigned fill_blocks(int64_t elems) {
 }
 
 }  // namespace
+
+// Band height of the column passes: 256 rows, thinner when the matrix is short so that a few
+// thousand workgroups exist.
+static int column_band(int64_t k, int64_t n) {
+    const int64_t bx = (n + 255) / 256;
+    const int64_t want_y = (2048 + bx - 1) / bx;
+    int64_t band = (k + want_y - 1) / want_y;
+    return (int)(band < 8 ? 8 : (band > kColBand ? kColBand : band));
+}
 
 hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k, int s,
                              int8_t* S, int64_t m_pad, int64_t k_pad, int32_t* E, hipStream_t st) {
@@ -346,13 +484,10 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (k > 0 && n > 0) {
-        // short matrices: thinner bands, so that a few thousand workgroups exist
         const int64_t bx = (n + 255) / 256;
-        const int64_t want_y = (2048 + bx - 1) / bx;
-        int64_t band = (k + want_y - 1) / want_y;
-        band = band < 8 ? 8 : (band > kColBand ? kColBand : band);
+        const int band = column_band(k, n);
         col_max_kernel<<<dim3((unsigned)bx, (unsigned)((k + band - 1) / band)), dim3(256), 0, st>>>(
-            B, ldb, inc, k, n, (int)band, colmax);
+            B, ldb, inc, k, n, band, colmax);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -364,6 +499,44 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
     const dim3 grid((unsigned)(n_pad / kColTileJ), (unsigned)(k_pad / kColTileL));
     if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax);
     else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax);
+    return hipGetLastError();
+}
+
+hipError_t launch_loss_scan_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k,
+                                 unsigned long long* sums, hipStream_t st) {
+    if (m == 0 || k == 0) return hipSuccess;
+    const bool cached = k <= 4 * 256 * kRowCacheWords;
+    const bool vec = inc == 1 && lda % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
+    const dim3 grid((unsigned)m), block(256);
+    if (cached) {
+        if (vec) loss_rows_kernel<true, true><<<grid, block, 0, st>>>(A, lda * inc, inc, k, sums);
+        else loss_rows_kernel<true, false><<<grid, block, 0, st>>>(A, lda * inc, inc, k, sums);
+    } else {
+        if (vec) loss_rows_kernel<false, true><<<grid, block, 0, st>>>(A, lda * inc, inc, k, sums);
+        else loss_rows_kernel<false, false><<<grid, block, 0, st>>>(A, lda * inc, inc, k, sums);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_loss_scan_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n,
+                                 unsigned long long* colmax, unsigned long long* sums, hipStream_t st) {
+    if (k == 0 || n == 0) return hipSuccess;
+    const int64_t bx = (n + 255) / 256;
+    fill_u64_kernel<<<dim3((unsigned)bx), dim3(256), 0, st>>>(colmax, n, 0ull);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int band = column_band(k, n);
+    const dim3 grid((unsigned)bx, (unsigned)((k + band - 1) / band));
+    col_max_kernel<<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, band, colmax);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    loss_cols_kernel<<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, band, colmax, sums);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_u64(unsigned long long* p, int64_t count, unsigned long long v, hipStream_t st) {
+    if (count == 0) return hipSuccess;
+    fill_u64_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(p, count, v);
     return hipGetLastError();
 }
 

@@ -22,6 +22,7 @@ WORKSPACE_ALIGN = 256
 EXPORTS = (
     "ozimmu_status_string", "ozimmu_slice_geometry", "ozimmu_slice_offset", "ozimmu_split_rows", "ozimmu_split_cols",
     "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_stage",
+    "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices",
     "ozimmu_probe_int8_mfma", "ozimmu_probe_lds_read",
 )
 
@@ -64,6 +65,11 @@ def lib() -> ctypes.CDLL:
             f.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
         L.ozimmu_dgemm_stage.restype = i32
         L.ozimmu_dgemm_stage.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
+        L.ozimmu_auto_scratch_bytes.restype = i32
+        L.ozimmu_auto_scratch_bytes.argtypes = [i64, ctypes.POINTER(sz)]
+        L.ozimmu_auto_num_slices.restype = i32
+        L.ozimmu_auto_num_slices.argtypes = [i64, i64, i64, vp, i64, vp, i64, i32, ctypes.c_double, i32, vp, sz,
+                                             ctypes.POINTER(i32), vp, vp]
         dp = ctypes.POINTER(ctypes.c_double)
         L.ozimmu_probe_int8_mfma.restype = i32
         L.ozimmu_probe_int8_mfma.argtypes = [i32, i32, dp, dp]
@@ -181,6 +187,34 @@ def zgemm(A, B, C, num_slices: int, workspace, stream=None) -> None:
     n = B.shape[1]
     _check(lib().ozimmu_zgemm(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C), _ld(C, n), num_slices,
                               _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+
+
+def auto_scratch_bytes(n: int) -> int:
+    out = ctypes.c_size_t()
+    _check(lib().ozimmu_auto_scratch_bytes(n, ctypes.byref(out)))
+    return out.value
+
+
+def auto_num_slices(A, B, threshold: float, max_slices: int = MAX_SLICES, scratch=None, stream=None):
+    """Number of slices whose average mantissa loss is within `threshold` (see ozimmu.h) for the
+    float64 or complex128 device tensors A (m x k) and B (k x n). Returns (s, sums) with sums a
+    numpy uint64 array [planes][16]. Waits for the stream."""
+    import numpy as np
+    import torch
+
+    m, k = A.shape
+    n = B.shape[1]
+    cplx = A.is_complex()
+    assert cplx == B.is_complex()
+    if scratch is None:
+        scratch = torch.empty(max(auto_scratch_bytes(n), WORKSPACE_ALIGN), dtype=torch.uint8, device=A.device)
+    planes = 4 if cplx else 2
+    sums = np.zeros((planes, MAX_SLICES), dtype=np.uint64)
+    s = ctypes.c_int()
+    _check(lib().ozimmu_auto_num_slices(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), int(cplx), float(threshold),
+                                        int(max_slices), _ptr(scratch), scratch.numel(), ctypes.byref(s),
+                                        sums.ctypes.data, _stream(stream)))
+    return s.value, sums
 
 
 def probe_int8_mfma(pattern: int, iters: int = 200000):

@@ -107,6 +107,27 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.ozimmu_dgemm_stage(3, 4, 4, 4, fake, 4, fake, 4, fake, 4, 3, fake, 1 << 30, None) == 1
 
 
+def test_auto_slice_count_argument_errors():
+    L = ozimmu.lib()
+    out = ctypes.c_size_t()
+    assert L.ozimmu_auto_scratch_bytes(1000, ctypes.byref(out)) == 0 and out.value == 512 + 8 * 1024
+    assert L.ozimmu_auto_scratch_bytes(-1, ctypes.byref(out)) == 1
+    fake = ctypes.c_void_p(256)
+    s = ctypes.c_int(-7)
+    args = lambda **kw: [kw.get("m", 4), 4, 4, fake, kw.get("lda", 4), fake, 4, 0, kw.get("T", 1.0), kw.get("smax", 16),
+                         kw.get("scratch", fake), kw.get("sb", 1 << 20), kw.get("out", ctypes.byref(s)), None, None]
+    assert L.ozimmu_auto_num_slices(*args(m=-1)) == 1
+    assert L.ozimmu_auto_num_slices(*args(lda=3)) == 2
+    assert L.ozimmu_auto_num_slices(*args(smax=0)) == 3
+    assert L.ozimmu_auto_num_slices(*args(smax=17)) == 3
+    assert L.ozimmu_auto_num_slices(*args(T=-0.5)) == 3
+    assert L.ozimmu_auto_num_slices(*args(T=float("nan"))) == 3
+    assert L.ozimmu_auto_num_slices(*args(out=None)) == 4
+    assert L.ozimmu_auto_num_slices(*args(scratch=None)) == 5
+    assert L.ozimmu_auto_num_slices(*args(sb=100)) == 5
+    assert s.value == -7   # untouched on error
+
+
 def test_binding_raises_typed_error():
     with pytest.raises(ozimmu.OzimmuError) as e:
         ozimmu.workspace_bytes(1, 1, 1, 0)

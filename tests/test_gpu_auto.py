@@ -1,0 +1,81 @@
+"""Automatic choice of the number of slices (Section 4.4) on the GPU against the oracle: the sums
+of lost mantissa bits per slice count are integers and must be identical, and so must the choice
+(both sides decide sum <= T * count in double precision)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2306_11975_amd import ozimmu
+from paper_2306_11975_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check(A, B, thresholds=(0.0, 0.5, 1.0, 3.0, 20.0), dA=None, dB=None):
+    dA = dev(A) if dA is None else dA
+    dB = dev(B) if dB is None else dB
+    for T in thresholds:
+        s_want, sums_want = oracle.auto_num_slices(A, B, T)
+        s_got, sums_got = ozimmu.auto_num_slices(dA, dB, T)
+        assert np.array_equal(sums_got, sums_want)
+        assert s_got == s_want, T
+    return ozimmu.auto_num_slices(dA, dB, 0.0)[0]
+
+
+@pytest.mark.parametrize("m,n,k,phi,seed", [(64, 64, 64, 0.5, 1), (300, 270, 517, 2.0, 2), (257, 513, 130, 1.0, 3),
+                                            (1, 1, 1, 1.0, 4), (7, 1000, 9000, 1.0, 5)])
+def test_auto_matches_oracle(m, n, k, phi, seed):
+    A, B = wl.phi_pair(m, n, k, phi, seed)
+    check(A, B)
+
+
+def test_auto_adversarial_values_and_strides():
+    M = wl.adversarial_matrix(40, 333, seed=9)       # zero row/column, powers of two, subnormals, huge rows
+    check(M, np.ascontiguousarray(M.T))
+    big = wl.phi_matrix(50, 200, 1.0, seed=3)
+    A = big[:, 11:151]                                # odd offset: rows are not 16-byte aligned
+    B = wl.phi_matrix(140, 90, 2.0, seed=4)
+    dbig = dev(big)
+    check(np.ascontiguousarray(A), B, dA=dbig[:, 11:151])
+
+
+def test_auto_single_binade_and_limits():
+    rng = np.random.default_rng(3)
+    A = 1.0 + rng.random((100, 300))
+    B = 1.0 + rng.random((300, 50))
+    dA, dB = dev(A), dev(B)
+    assert ozimmu.auto_num_slices(dA, dB, 0.0)[0] == 8
+    assert ozimmu.auto_num_slices(dA, dB, 4.0)[0] == 7
+    assert ozimmu.auto_num_slices(dA, dB, 0.0, max_slices=6)[0] == 6
+    # the chosen count makes the GPU product exact here: integers below 2^20 times 2^-20
+    Ai = np.round(A * 2 ** 20) / 2 ** 20
+    Bi = np.round(B * 2 ** 20) / 2 ** 20
+    s = ozimmu.auto_num_slices(dev(Ai), dev(Bi), 0.0)[0]
+    C = torch.empty((100, 50), dtype=torch.float64, device="cuda")
+    ozimmu.dgemm(dev(Ai), dev(Bi), C, s, ozimmu.alloc_workspace(100, 50, 300, s))
+    torch.cuda.synchronize()
+    assert np.array_equal(C.cpu().numpy(), oracle.dgemm(Ai, Bi, s))
+    # degenerate shapes pick one slice
+    e = torch.empty((0, 5), dtype=torch.float64, device="cuda")
+    assert ozimmu.auto_num_slices(e, torch.empty((5, 3), dtype=torch.float64, device="cuda"), 0.0)[0] >= 1
+    assert ozimmu.auto_num_slices(torch.empty((3, 0), dtype=torch.float64, device="cuda"),
+                                  torch.empty((0, 3), dtype=torch.float64, device="cuda"), 0.0)[0] == 1
+
+
+def test_auto_complex_planes():
+    A = wl.gaussian_complex(130, 256, seed=1)
+    B = wl.unit_column_complex(256, 70, seed=2)
+    check(A, B, thresholds=(0.0, 1.0))
+
+
+def test_auto_full_size_matches_oracle():
+    """m = n = k = 4096, phi = 1: the launch configuration of the large workloads (rows kept in
+    registers, 256-row bands for the columns)."""
+    A = wl.phi_matrix_device(4096, 4096, 1.0, 1003)
+    B = wl.phi_matrix_device(4096, 4096, 1.0, 2003)
+    check(A.cpu().numpy(), B.cpu().numpy(), thresholds=(0.0, 1.0), dA=A, dB=B)
