@@ -79,6 +79,8 @@ def _load():
         lib.oz_auto_loss_sums.argtypes = [i64, i64, vp, i64, i64, i32, i32, vp]
         lib.oz_auto_num_slices.restype = i32
         lib.oz_auto_num_slices.argtypes = [i32, i32, vp, vp, dbl]
+        lib.oz_dgemm_blas.restype = i32
+        lib.oz_dgemm_blas.argtypes = [i32, i32, i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, i32]
         lib.oz_abs_gemm.restype = None
         lib.oz_abs_gemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp]
         _lib = lib
@@ -254,3 +256,19 @@ def auto_num_slices(A, B, T: float, s_max: int = 16):
     counts = np.array([M.size for M, _ in planes], dtype=np.int64)
     s = int(_load().oz_auto_num_slices(len(planes), s_max, _p(np.ascontiguousarray(sums)), _p(counts), float(T)))
     return s, sums
+
+
+def dgemm_blas(transa: bool, transb: bool, alpha: float, A, B, beta: float, C, s: int) -> np.ndarray:
+    """BLAS-style call: returns alpha op(A) op(B) + beta C for 2-D arrays given as mathematical
+    matrices (A is m x k, or k x m if transa; B likewise; C is m x n). They are handed to the C
+    routine in column-major storage."""
+    Af = np.asfortranarray(np.asarray(A, dtype=np.float64))
+    Bf = np.asfortranarray(np.asarray(B, dtype=np.float64))
+    Cf = np.array(C, dtype=np.float64, order="F", copy=True)
+    m, n = Cf.shape
+    k = Af.shape[0] if transa else Af.shape[1]
+    rc = _load().oz_dgemm_blas(int(transa), int(transb), m, n, k, float(alpha), _p(Af), max(Af.shape[0], 1), _p(Bf),
+                               max(Bf.shape[0], 1), float(beta), _p(Cf), max(m, 1), int(s))
+    if rc:
+        raise MemoryError
+    return Cf

@@ -381,3 +381,45 @@ int oz_auto_num_slices(int planes, int s_max, const uint64_t *sums, const int64_
     }
     return s_max;
 }
+
+/* ---------------------------------------------------------------------------------
+ * BLAS-style call (Section 4.4: the method stands in for the vendor DGEMM routine):
+ * column-major storage, C <- alpha op(A) op(B) + beta C with op(X) = X or X^T.
+ *
+ * op(A) (m x k) and op(B) (k x n) are first written out as plain row-major matrices,
+ * G = their Ozaki product as above (exponents per row of op(A) and per column of
+ * op(B)), and then, element by element,
+ *     C = RN(alpha G)                        if beta == 0 (C is not read),
+ *     C = RN( RN(alpha G) + RN(beta C) )     otherwise;
+ * if alpha == 0 or k == 0 the product is not formed: C = +0 if beta == 0, else RN(beta C).
+ * (The paper does not discuss alpha and beta; this is the reference BLAS order of operations.)
+ * ------------------------------------------------------------------------------- */
+int oz_dgemm_blas(int transa, int transb, int64_t m, int64_t n, int64_t k, double alpha,
+                  const double *A, int64_t lda, const double *B, int64_t ldb, double beta, double *C,
+                  int64_t ldc, int s) {
+    if (m == 0 || n == 0) return 0;
+    if (alpha == 0.0 || k == 0) {
+        for (int64_t j = 0; j < n; ++j)
+            for (int64_t i = 0; i < m; ++i) C[i + j * ldc] = beta == 0.0 ? 0.0 : beta * C[i + j * ldc];
+        return 0;
+    }
+    double *opA = (double *)malloc(sizeof(double) * (size_t)(m * k));
+    double *opB = (double *)malloc(sizeof(double) * (size_t)(k * n));
+    double *G = (double *)malloc(sizeof(double) * (size_t)(m * n));
+    if (!opA || !opB || !G) { free(opA); free(opB); free(G); return 1; }
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t l = 0; l < k; ++l) opA[i * k + l] = transa ? A[l + i * lda] : A[i + l * lda];
+    for (int64_t l = 0; l < k; ++l)
+        for (int64_t j = 0; j < n; ++j) opB[l * n + j] = transb ? B[j + l * ldb] : B[l + j * ldb];
+    int rc = oz_dgemm(m, n, k, opA, k, opB, n, G, n, s);
+    if (rc == 0) {
+        for (int64_t j = 0; j < n; ++j)
+            for (int64_t i = 0; i < m; ++i) {
+                double v = alpha * G[i * n + j];
+                if (beta != 0.0) v = v + beta * C[i + j * ldc];
+                C[i + j * ldc] = v;
+            }
+    }
+    free(opA); free(opB); free(G);
+    return rc;
+}

@@ -542,3 +542,44 @@ def test_auto_on_random_unitary_gate_is_in_the_range_the_paper_reports():
     A = psi.reshape(2 ** (N - d), 2 ** d)
     assert oracle.auto_num_slices(A, Q, 0.0)[0] in (11, 12, 13)
     assert oracle.auto_num_slices(A, Q, 1.0)[0] in (8, 9)
+
+
+# ------------------------------------------------------------------ BLAS-style call (Section 4.4)
+@pytest.mark.parametrize("ta,tb", [(False, False), (True, False), (False, True), (True, True)])
+def test_blas_call_reduces_to_plain_integer_arithmetic(ta, tb):
+    """Integer matrices |x| <= 127 live in slice 1, so G is the exact integer product for any s, and
+    with integer alpha, beta and C every operation of the update is exact: the whole call must equal
+    numpy's integer arithmetic. A transposed operand, a wrong leading dimension or swapped m/n fails."""
+    rng = np.random.default_rng(17)
+    m, n, k = 5, 7, 9
+    opA = rng.integers(-127, 128, size=(m, k))
+    opB = rng.integers(-127, 128, size=(k, n))
+    C0 = rng.integers(-1000, 1000, size=(m, n))
+    A = opA.T if ta else opA
+    B = opB.T if tb else opB
+    for alpha, beta in ((1, 0), (3, 0), (1, 1), (-2, 5), (0, 4), (0, 0)):
+        got = oracle.dgemm_blas(ta, tb, alpha, A.astype(float), B.astype(float), beta, C0.astype(float), 3)
+        want = alpha * (opA @ opB) + beta * C0
+        assert np.array_equal(got, want.astype(float)), (alpha, beta)
+    # beta = 0 must not read C (BLAS convention): NaN there does not propagate
+    got = oracle.dgemm_blas(ta, tb, 1.0, A.astype(float), B.astype(float), 0.0, np.full((m, n), np.nan), 2)
+    assert np.array_equal(got, (opA @ opB).astype(float))
+
+
+def test_blas_call_rounding_order_against_exact_rationals():
+    """General values: G from the plain routine (pinned above), then the update replayed in exact
+    rationals with the three roundings made explicit."""
+    A, B = wl.phi_pair(4, 5, 6, 1.0, seed=31)
+    rng = np.random.default_rng(2)
+    C0 = rng.standard_normal((4, 5))
+    alpha, beta = 1.7, -0.3
+    G = oracle.dgemm(A, B, 9)
+    got = oracle.dgemm_blas(False, False, alpha, A, B, beta, C0, 9)
+    for i in range(4):
+        for j in range(5):
+            t1 = float(Fraction(alpha) * Fraction(float(G[i, j])))      # float(Fraction) rounds to nearest even
+            t2 = float(Fraction(beta) * Fraction(float(C0[i, j])))
+            assert got[i, j] == float(Fraction(t1) + Fraction(t2))
+    # transposed inputs give the same bits as the plain call on the transposed data
+    got_t = oracle.dgemm_blas(True, True, alpha, A.T.copy(), B.T.copy(), beta, C0, 9)
+    assert np.array_equal(got_t.view(np.uint64), got.view(np.uint64))
