@@ -143,6 +143,22 @@ ozimmu_status_t ozimmu_dgemm_stage(int stage, int64_t m, int64_t n, int64_t k, c
                                    size_t workspace_bytes, void* stream);
 
 /*
+ * BLAS-style call (Section 4.4: the library stands in for the vendor DGEMM): COLUMN-MAJOR storage,
+ * C <- alpha op(A) op(B) + beta C, op(X) = X ('N') or X^T ('T', 'C'); op(A) is m x k, op(B) is
+ * k x n, C is m x n; leading dimensions as in the reference BLAS. G = the Ozaki product of op(A) and
+ * op(B) as in ozimmu_dgemm (exponents per row of op(A) and per column of op(B)); then per element
+ * C = RN(alpha G) if beta == 0 (C is not read), else C = RN(RN(alpha G) + RN(beta C)); if
+ * alpha == 0 or k == 0 the product is not formed (A, B, workspace may be null): C = +0 or
+ * RN(beta C). alpha and beta are host scalars. Workspace: ozimmu_workspace_bytes(n, m, k, ...)
+ * (note the order: the operands swap roles internally). Errors: an unknown transpose letter gives
+ * OZIMMU_ERR_BAD_DIM, the rest as for ozimmu_dgemm.
+ */
+ozimmu_status_t ozimmu_dgemm_blas(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha,
+                                  const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
+                                  double* C, int64_t ldc, int num_slices, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
+/*
  * Automatic choice of the number of slices (Section 4.4, "INT8-AUTO": all elements of the inputs
  * are inspected and the number of slices is taken so that the average mantissa loss of the split
  * stays within a threshold; threshold 0 means a lossless split).

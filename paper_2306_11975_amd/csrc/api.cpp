@@ -3,6 +3,8 @@
 #include <cstdint>
 #include <cstring>
 
+#include <algorithm>
+
 #include "ozimmu_internal.h"
 
 using namespace ozimmu;
@@ -49,7 +51,7 @@ Layout make_layout(int64_t m, int64_t n, int64_t k, int s, bool cplx) {
     for (int p = 0; p < planes; ++p) { L.off_ea[p] = off; off = align_up(off + sizeof(int32_t) * L.m_pad); }
     for (int p = 0; p < planes; ++p) { L.off_eb[p] = off; off = align_up(off + sizeof(int32_t) * L.n_pad); }
     L.off_colmax = off;
-    off = align_up(off + sizeof(unsigned long long) * L.n_pad);
+    off = align_up(off + sizeof(unsigned long long) * (L.n_pad > L.m_pad ? L.n_pad : L.m_pad));  // either operand may be split by columns
     L.off_d = off;
     off = align_up(off + (size_t)s * L.tiles_m * L.tiles_n * kTileElems * (L.wide ? 8 : 4));
     L.total = off;
@@ -78,7 +80,7 @@ ozimmu_status_t check_gemm_args(int64_t m, int64_t n, int64_t k, const void* A, 
 // the given column stride and combine mode.
 hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned char* ws, int plane_a, int plane_b,
                        double* C, int64_t ldc, int c_inc, int c_mode, hipStream_t st, int dual = 0,
-                       int plane_a2 = 0, int plane_b2 = 0) {
+                       int plane_a2 = 0, int plane_b2 = 0, double alpha = 1.0, double beta = 0.0) {
     GemmArgs g{};
     g.SA = reinterpret_cast<const int8_t*>(ws + L.off_sa[plane_a]);
     g.SB = reinterpret_cast<const int8_t*>(ws + L.off_sb[plane_b]);
@@ -100,6 +102,8 @@ hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned ch
     g.ldc = ldc;
     g.c_inc = c_inc;
     g.c_mode = c_mode;
+    g.alpha = alpha;
+    g.beta = beta;
     g.EA = reinterpret_cast<const int32_t*>(ws + L.off_ea[plane_a]);
     g.EB = reinterpret_cast<const int32_t*>(ws + L.off_eb[plane_b]);
     g.dual = dual;
@@ -338,6 +342,48 @@ ozimmu_status_t ozimmu_auto_num_slices(int64_t m, int64_t n, int64_t k, const do
     if (loss_sums)
         for (int i = 0; i < planes * OZIMMU_MAX_SLICES; ++i) loss_sums[i] = host[i];
     return OZIMMU_OK;
+}
+
+ozimmu_status_t ozimmu_dgemm_blas(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha,
+                                  const double* A, int64_t lda, const double* B, int64_t ldb, double beta, double* C,
+                                  int64_t ldc, int num_slices, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+    auto parse = [](char c, bool* t) {
+        if (c == 'N' || c == 'n') { *t = false; return true; }
+        if (c == 'T' || c == 't' || c == 'C' || c == 'c') { *t = true; return true; }
+        return false;
+    };
+    bool ta = false, tb = false;
+    if (!parse(transa, &ta) || !parse(transb, &tb) || !dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
+    if (num_slices < 1 || num_slices > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
+    const int64_t one = 1;
+    if (lda < std::max(one, ta ? k : m) || ldb < std::max(one, tb ? n : k) || ldc < std::max(one, m))
+        return OZIMMU_ERR_BAD_LD;
+    if (m == 0 || n == 0) return OZIMMU_OK;
+    if (!C) return OZIMMU_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // Column-major C (m x n) is the row-major n x m array C^T = op(B)^T op(A)^T: the operands swap
+    // roles, and an operand is split along whichever of its two storage directions runs along k.
+    if (k == 0 || alpha == 0.0) return hip_status(launch_scale_f64(C, ldc, n, m, beta, st));
+    if (!A || !B) return OZIMMU_ERR_NULL;
+    const Layout L = make_layout(n, m, k, num_slices, false);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % OZIMMU_WORKSPACE_ALIGN) != 0 || workspace_bytes < L.total)
+        return OZIMMU_ERR_WORKSPACE;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    int8_t* SR = reinterpret_cast<int8_t*>(ws + L.off_sa[0]);      // slices of op(B)^T: n rows of length k
+    int8_t* SC = reinterpret_cast<int8_t*>(ws + L.off_sb[0]);      // slices of op(A): m rows of length k
+    int32_t* ER = reinterpret_cast<int32_t*>(ws + L.off_ea[0]);
+    int32_t* EC = reinterpret_cast<int32_t*>(ws + L.off_eb[0]);
+    unsigned long long* colmax = reinterpret_cast<unsigned long long*>(ws + L.off_colmax);
+    hipError_t e;
+    if (!tb) e = launch_split_rows(B, ldb, 1, n, k, num_slices, SR, L.m_pad, L.k_pad, ER, st);   // B: k x n, column j contiguous
+    else e = launch_split_cols(B, ldb, 1, k, n, num_slices, SR, L.m_pad, L.k_pad, ER, colmax, st);  // B: n x k
+    if (e == hipSuccess) {
+        if (!ta) e = launch_split_cols(A, lda, 1, k, m, num_slices, SC, L.n_pad, L.k_pad, EC, colmax, st);  // A: m x k
+        else e = launch_split_rows(A, lda, 1, m, k, num_slices, SC, L.n_pad, L.k_pad, EC, st);              // A: k x m
+    }
+    if (e == hipSuccess) e = run_product(L, n, m, num_slices, ws, 0, 0, C, ldc, 1, 3, st, 0, 0, 0, alpha, beta);
+    return hip_status(e);
 }
 
 }  // extern "C"

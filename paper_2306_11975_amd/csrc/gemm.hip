@@ -254,7 +254,12 @@ void slice_gemm_kernel(const GemmArgs g) {
             double* c = g.C + (int64_t)row * g.ldc + (int64_t)col * g.c_inc;
             if (g.c_mode == 0) *c = val;
             else if (g.c_mode == 1) *c = *c + val;
-            else *c = *c - val;
+            else if (g.c_mode == 2) *c = *c - val;
+            else {   // BLAS update: RN(alpha G), then RN(RN(alpha G) + RN(beta C)); C is not read if beta == 0
+                double v = g.alpha * val;
+                if (g.beta != 0.0) v = v + g.beta * *c;
+                *c = v;
+            }
         }
     };
     // Fixed-order FP64 sum: the diagonals come back from the workspace (each thread reads what

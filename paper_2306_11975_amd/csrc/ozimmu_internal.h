@@ -34,7 +34,8 @@ struct GemmArgs {
     double* C;             // full mode output
     int64_t ldc;           // in doubles
     int c_inc;             // distance in doubles between consecutive columns (2 for a complex plane)
-    int c_mode;            // 0: C = G, 1: C = C + G, 2: C = C - G
+    int c_mode;            // 0: C = G, 1: C = C + G, 2: C = C - G, 3: C = alpha G (+ beta C if beta != 0)
+    double alpha, beta;    // c_mode 3 only
     const int32_t* EA;
     const int32_t* EB;
     // second product of the register-resident kernel (dual != 0): C = G(SA,SB) + G(SA2,SB2) if
@@ -61,6 +62,8 @@ hipError_t launch_loss_scan_rows(const double* A, int64_t lda, int inc, int64_t 
                                  unsigned long long* sums, hipStream_t st);
 hipError_t launch_loss_scan_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n,
                                  unsigned long long* colmax, unsigned long long* sums, hipStream_t st);
+// C = beta C (C = +0 if beta == 0, without reading C) on an m x n row-major array.
+hipError_t launch_scale_f64(double* C, int64_t ldc, int64_t m, int64_t n, double beta, hipStream_t st);
 hipError_t launch_fill_u64(unsigned long long* p, int64_t count, unsigned long long v, hipStream_t st);
 hipError_t launch_fill_f64(double* C, int64_t ldc, int c_inc, int64_t m, int64_t n, double v,
                            hipStream_t st);

@@ -440,6 +440,13 @@ __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* P, int64_t ldp, 
         P[(idx / n) * ldp + (idx % n)] = v;
 }
 
+__global__ __launch_bounds__(256) void scale_f64_kernel(double* C, int64_t ldc, int64_t m, int64_t n, double beta) {
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < m * n; idx += (int64_t)gridDim.x * 256) {
+        double* c = C + (idx / n) * ldc + (idx % n);
+        *c = beta == 0.0 ? 0.0 : beta * *c;
+    }
+}
+
 // Grid of a grid-stride fill: enough blocks to cover the range, capped so the count fits any grid limit.
 unsigned fill_blocks(int64_t elems) {
     const int64_t b = (elems + 255) / 256;
@@ -531,6 +538,12 @@ hipError_t launch_loss_scan_cols(const double* B, int64_t ldb, int inc, int64_t 
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     loss_cols_kernel<<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, band, colmax, sums);
+    return hipGetLastError();
+}
+
+hipError_t launch_scale_f64(double* C, int64_t ldc, int64_t m, int64_t n, double beta, hipStream_t st) {
+    if (m * n == 0) return hipSuccess;
+    scale_f64_kernel<<<dim3(fill_blocks(m * n)), dim3(256), 0, st>>>(C, ldc, m, n, beta);
     return hipGetLastError();
 }
 

@@ -107,6 +107,28 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.ozimmu_dgemm_stage(3, 4, 4, 4, fake, 4, fake, 4, fake, 4, 3, fake, 1 << 30, None) == 1
 
 
+def test_blas_call_argument_errors():
+    L = ozimmu.lib()
+    fake = ctypes.c_void_p(256)
+    f = L.ozimmu_dgemm_blas
+    ok = [b"N", b"N", 4, 5, 6, 1.0, fake, 4, fake, 6, 0.0, fake, 4, 3, fake, 1 << 30, None]
+    def call(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return f(*a)
+    assert call(_0=b"X") == 1 and call(_1=b"?") == 1 and call(_2=-1) == 1
+    assert call(_13=0) == 3 and call(_13=17) == 3
+    assert call(_7=3) == 2            # lda < m for 'N'
+    assert call(_0=b"T", _7=5) == 2   # lda < k for 'T'
+    assert call(_9=5) == 2            # ldb < k for 'N'
+    assert call(_1=b"T", _9=4) == 2   # ldb < n for 'T'
+    assert call(_12=3) == 2           # ldc < m
+    assert call(_11=None) == 4 and call(_6=None) == 4
+    assert call(_14=None) == 5 and call(_15=16) == 5
+    assert call(_2=0) == 0            # empty result: no-op
+
+
 def test_auto_slice_count_argument_errors():
     L = ozimmu.lib()
     out = ctypes.c_size_t()

@@ -1,0 +1,75 @@
+"""BLAS-style entry point (column-major, transposes, alpha/beta; Section 4.4) against the oracle,
+bit for bit: the Ozaki product is the same fixed-order computation and the update has a fixed order
+of roundings."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2306_11975_amd import ozimmu
+from paper_2306_11975_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def bits(x):
+    return np.ascontiguousarray(x).view(np.uint64)
+
+
+def col_major_on_device(M, ld):
+    """Mathematical matrix M (r x c) -> device buffer holding it column-major with leading dimension ld
+    (padding rows poisoned)."""
+    r, c = M.shape
+    buf = np.full((max(c, 1), ld), 7.25e300)
+    buf[:c, :r] = M.T
+    return torch.from_numpy(buf).cuda()
+
+
+def run(ta, tb, m, n, k, alpha, beta, s, phi=1.0, seed=1, pad=(0, 0, 0), c_nan=False):
+    opA, opB = wl.phi_pair(m, n, k, phi, seed)
+    A = opA.T.copy() if ta else opA
+    B = opB.T.copy() if tb else opB
+    rng = np.random.default_rng(seed + 100)
+    C0 = np.full((m, n), np.nan) if c_nan else rng.standard_normal((m, n))
+    lda, ldb, ldc = max(A.shape[0], 1) + pad[0], max(B.shape[0], 1) + pad[1], max(m, 1) + pad[2]
+    dA, dB, dC = col_major_on_device(A, lda), col_major_on_device(B, ldb), col_major_on_device(C0, ldc)
+    ws = ozimmu.alloc_workspace(n, m, k, s)
+    ozimmu.dgemm_blas("T" if ta else "N", "T" if tb else "N", m, n, k, alpha, dA, lda, dB, ldb, beta, dC, ldc, s, ws)
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy()
+    got = out[:n, :m].T
+    want = oracle.dgemm_blas(ta, tb, alpha, A, B, beta, C0, s)
+    assert np.array_equal(bits(got), bits(want))
+    assert (out[:, m:] == 7.25e300).all(), "padding of C must be untouched"
+
+
+@pytest.mark.parametrize("ta", [False, True])
+@pytest.mark.parametrize("tb", [False, True])
+def test_blas_transposes_and_scalars_bit_exact(ta, tb):
+    for alpha, beta in ((1.0, 0.0), (1.7, -0.3), (-2.0, 1.0), (0.5, 0.0)):
+        run(ta, tb, 130, 70, 300, alpha, beta, 8, pad=(3, 5, 2))
+
+
+@pytest.mark.parametrize("m,n,k,s", [(300, 270, 1300, 7), (33, 520, 2049, 5), (257, 64, 64, 13), (40, 50, 70000, 2)])
+def test_blas_shapes_across_the_kernels(m, n, k, s):
+    """Short k (sum kept in registers), long k (diagonal buffers) and INT64 k-blocking."""
+    run(True, False, m, n, k, 1.25, 0.75, s, phi=2.0, seed=3, pad=(1, 0, 7))
+    run(False, True, m, n, k, 1.0, 0.0, s, phi=0.5, seed=4)
+
+
+def test_blas_beta_zero_does_not_read_c_and_degenerate_cases():
+    run(False, False, 64, 48, 100, 2.0, 0.0, 6, c_nan=True)
+    run(True, True, 64, 48, 2000, 1.0, 0.0, 6, c_nan=True)
+    # alpha == 0 and k == 0: only the scaling of C remains
+    for k, alpha in ((0, 1.0), (50, 0.0)):
+        m, n = 37, 21
+        C0 = np.random.default_rng(5).standard_normal((m, n))
+        for beta in (0.0, -1.5):
+            dC = col_major_on_device(C0, m + 2)
+            dA = torch.zeros(max(m * max(k, 1), 1), dtype=torch.float64, device="cuda")
+            ozimmu.dgemm_blas("N", "N", m, n, k, alpha, dA, m, dA, max(k, 1), beta, dC, m + 2, 4, None)
+            torch.cuda.synchronize()
+            got = dC.cpu().numpy()[:n, :m].T
+            want = np.zeros((m, n)) if beta == 0.0 else beta * C0
+            assert np.array_equal(bits(got), bits(want))
+            assert not np.signbit(got).any() or beta != 0.0
