@@ -583,3 +583,42 @@ def test_blas_call_rounding_order_against_exact_rationals():
     # transposed inputs give the same bits as the plain call on the transposed data
     got_t = oracle.dgemm_blas(True, True, alpha, A.T.copy(), B.T.copy(), beta, C0, 9)
     assert np.array_equal(got_t.view(np.uint64), got.view(np.uint64))
+
+
+# ------------------------------------------------------------------ accuracy trends of Section 4.2
+def avg_rel_error(C, hi, lo):
+    """Eq. (7), averaged: |C - C_dd| / |C_dd| with the double-double reference (hi + lo)."""
+    return float(np.mean(np.abs((C - hi) - lo) / np.abs(hi)))
+
+
+def test_accuracy_trends_the_paper_reports_for_the_exponent_range():
+    """Section 4.2 (exponent distribution range): with phi = 0.1 nine slices already beat plain FP64
+    DGEMM; with 11 and 13 slices the error is below or about at the level of DGEMM up to phi = 4."""
+    n = 192
+    for phi, s, factor in ((0.1, 9, 1.0), (1.0, 11, 1.0), (2.0, 13, 1.0), (4.0, 13, 4.0)):
+        A = wl.phi_matrix(n, n, phi, seed=41)
+        B = wl.phi_matrix(n, n, phi, seed=42)
+        hi, lo = oracle.dd_gemm(A, B)
+        e_oz = avg_rel_error(oracle.dgemm(A, B, s), hi, lo)
+        e_fp = avg_rel_error(A @ B, hi, lo)
+        assert e_oz <= factor * e_fp, (phi, s, e_oz, e_fp)
+    # and too few slices for a wide range are worse than DGEMM (the disadvantage of Section 3.3)
+    A = wl.phi_matrix(n, n, 4.0, seed=41)
+    B = wl.phi_matrix(n, n, 4.0, seed=42)
+    hi, lo = oracle.dd_gemm(A, B)
+    assert avg_rel_error(oracle.dgemm(A, B, 9), hi, lo) > avg_rel_error(A @ B, hi, lo)
+
+
+def test_zero_cancellation_product_is_more_accurate_than_fp64_gemm():
+    """Section 4.2 (zero-cancellation): A ~ N(0,1) times its computed inverse; the reference is the
+    double-double product, not the identity. The scheme resolves the cancelling leading digits
+    exactly, so with enough slices its error is below that of FP64 DGEMM."""
+    n = 160
+    rng = np.random.default_rng(43)
+    A = rng.standard_normal((n, n))
+    X = np.linalg.solve(A, np.eye(n))
+    hi, lo = oracle.dd_gemm(A, X)
+    e_fp = avg_rel_error(A @ X, hi, lo)
+    errs = {s: avg_rel_error(oracle.dgemm(A, X, s), hi, lo) for s in (8, 10, 12, 13)}
+    assert errs[12] < e_fp and errs[13] < e_fp
+    assert errs[13] <= errs[12] <= errs[10] <= errs[8]
