@@ -387,13 +387,11 @@ hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st) {
     if (blocks == 0) return hipSuccess;
     hipError_t e;
     if (wide) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&slice_gemm_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsAlloc);
+        e = allow_dynamic_lds<&slice_gemm_kernel<true>>(kLdsAlloc);
         if (e != hipSuccess) return e;
         slice_gemm_kernel<true><<<dim3(blocks), dim3(kThreads), kLdsAlloc, st>>>(args);
     } else {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&slice_gemm_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsAlloc);
+        e = allow_dynamic_lds<&slice_gemm_kernel<false>>(kLdsAlloc);
         if (e != hipSuccess) return e;
         slice_gemm_kernel<false><<<dim3(blocks), dim3(kThreads), kLdsAlloc, st>>>(args);
     }

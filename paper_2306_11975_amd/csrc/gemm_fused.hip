@@ -279,8 +279,7 @@ hipError_t launch_shape(const GemmArgs& args, hipStream_t st) {
     const int blocks = args.tiles_m * (kTile / Sh::kRows) * args.tiles_n * (kTile / Sh::kCols);
     if (blocks == 0) return hipSuccess;
     auto kernel = &fused_gemm_kernel<WM, WN, TM, TN, DUAL>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Sh::kLds);
+    hipError_t e = allow_dynamic_lds<&fused_gemm_kernel<WM, WN, TM, TN, DUAL>>(Sh::kLds);
     if (e != hipSuccess) return e;
     kernel<<<dim3(blocks), dim3(512), Sh::kLds, st>>>(args);
     return hipGetLastError();

@@ -72,5 +72,21 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(N) : "memory");
 }
 
+// Raise a kernel's dynamic LDS limit once per device instead of before every launch (the call
+// is a host-side driver round trip, and it keeps the launch path free of anything but the launch).
+// One instantiation, hence one set of flags, per kernel. Two host threads racing here both make
+// the (idempotent) driver call.
+template <auto kernel>
+inline hipError_t allow_dynamic_lds(int bytes) {
+    static bool done[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;
+    return e;
+}
+
 }  // namespace
 }  // namespace ozimmu

@@ -103,6 +103,12 @@ def _stream(stream) -> int:
     return stream.cuda_stream
 
 
+def _ld(t, cols):
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("expected a 2-D row-major tensor (unit stride along the second dimension)")
+    return t.stride(0) if t.shape[0] > 1 else max(cols, 1)
+
+
 def slice_geometry(rows: int, k: int):
     rp, kp = ctypes.c_int64(), ctypes.c_int64()
     _check(lib().ozimmu_slice_geometry(rows, k, ctypes.byref(rp), ctypes.byref(kp)))
@@ -148,23 +154,19 @@ def split_rows(A, num_slices: int, slices, exps, stream=None) -> None:
     """A: (m, k) float64 device tensor with unit column stride; slices: int8 device buffer of
     num_slices * rows_padded * k_padded bytes; exps: int32 device tensor of m entries."""
     m, k = A.shape
-    _check(lib().ozimmu_split_rows(m, k, _ptr(A), A.stride(0) if m > 1 else max(k, 1), num_slices,
+    _check(lib().ozimmu_split_rows(m, k, _ptr(A), _ld(A, k), num_slices,
                                    _ptr(slices), _ptr(exps), _stream(stream)))
 
 
 def split_cols(B, num_slices: int, slices, exps, col_scratch, stream=None) -> None:
     k, n = B.shape
-    _check(lib().ozimmu_split_cols(k, n, _ptr(B), B.stride(0) if k > 1 else max(n, 1), num_slices,
+    _check(lib().ozimmu_split_cols(k, n, _ptr(B), _ld(B, n), num_slices,
                                    _ptr(slices), _ptr(exps), _ptr(col_scratch), _stream(stream)))
 
 
 def slice_gemm(m: int, n: int, k: int, SA, SB, p: int, q: int, k0: int, klen: int, P, stream=None) -> None:
     _check(lib().ozimmu_slice_gemm(m, n, k, _ptr(SA), _ptr(SB), p, q, k0, klen, _ptr(P),
-                                   P.stride(0) if m > 1 else max(n, 1), _stream(stream)))
-
-
-def _ld(t, cols):
-    return t.stride(0) if t.shape[0] > 1 else max(cols, 1)
+                                   _ld(P, n), _stream(stream)))
 
 
 def dgemm(A, B, C, num_slices: int, workspace, stream=None) -> None:

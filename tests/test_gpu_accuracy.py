@@ -20,7 +20,7 @@ def test_zero_cancellation_beats_native_fp64_gemm():
     g = torch.Generator(device="cuda")
     g.manual_seed(43)
     A = torch.randn((n, n), generator=g, device="cuda", dtype=torch.float64)
-    X = torch.linalg.solve(A, torch.eye(n, dtype=torch.float64, device="cuda"))
+    X = torch.linalg.solve(A, torch.eye(n, dtype=torch.float64, device="cuda")).contiguous()
     Ah, Xh = A.cpu().numpy(), X.cpu().numpy()
     hi, lo = oracle.dd_gemm(Ah, Xh)
     e_native = avg_rel_error(torch.matmul(A, X).cpu().numpy(), hi, lo)
