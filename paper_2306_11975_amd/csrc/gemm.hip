@@ -47,9 +47,59 @@ constexpr int kTN = kTile / kWavesN / 32;             // ... along n (2)
 constexpr int kWaveShare = kBlockBytes / kWaves;      // bytes of each operand block a wavefront copies per step
 constexpr int kLoadsPerOperand = kWaveShare / 1024;   // wave-wide 1 KiB direct loads per operand and step
 constexpr int kLoadsPerStep = 2 * kLoadsPerOperand;   // direct loads per wavefront and step
+constexpr int kResidentTiles = 256;                   // workgroups the chip runs at a time (one per CU)
 constexpr int kGroups = kTM * kTN * 4;                // 16-byte groups of accumulators per thread
 static_assert(kStages >= 3 && kStages <= 5, "LDS budget");
 static_assert(kTM % kLoadsPerOperand == 0, "one load per kTM / kLoadsPerOperand MFMA rows");
+
+// One element of the result: C (op)= 2^(EA_i + EB_j) * sum, with the combine mode of the call.
+__device__ __forceinline__ void write_c_element(const GemmArgs& g, int row, int col, int eb, double sum) {
+    if (row < g.m && col < g.n) {
+        const double val = ldexp(sum, g.EA[row] + eb);
+        double* c = g.C + (int64_t)row * g.ldc + (int64_t)col * g.c_inc;
+        if (g.c_mode == 0) *c = val;
+        else if (g.c_mode == 1) *c = *c + val;
+        else if (g.c_mode == 2) *c = *c - val;
+        else {   // BLAS update: RN(alpha G), then RN(RN(alpha G) + RN(beta C)); C is not read if beta == 0
+            double v = g.alpha * val;
+            if (g.beta != 0.0) v = v + g.beta * *c;
+            *c = v;
+        }
+    }
+}
+
+// Fixed-order FP64 sum of one macro tile: the INT32 diagonal sums come back from the workspace in
+// the order the accumulator registers were stored (thread t of the 512 reads what thread t wrote),
+// least significant diagonal first.
+__device__ __forceinline__ void final_sum_narrow(const GemmArgs& g, int tile_id, int num_tiles, int row0, int col0,
+                                                 unsigned lane_off16) {
+    const int s = g.num_slices;
+#pragma unroll 1
+    for (int ij = 0; ij < kTM * kTN; ++ij) {
+        const int i = ij / kTN, j = ij % kTN;
+        const int col = col0 + j * 32;
+        const int eb = col < g.n ? g.EB[col] : 0;
+        double sum[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) sum[u] = 0.0;
+        // all 16 accumulators of one MFMA tile at once: four independent 16-byte loads per
+        // diagonal, several diagonals in flight
+#pragma unroll 4
+        for (int d = s + 1; d >= 2; --d) {
+            const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * d) << 52);
+            const unsigned char* src = reinterpret_cast<const unsigned char*>(g.D) +
+                                       ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * 4);
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                v4i v = *reinterpret_cast<const v4i*>(src + (ij * 4 + r4) * (kThreads * 16) + lane_off16);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) sum[4 * r4 + u] = sum[4 * r4 + u] + (double)v[u] * sc;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) write_c_element(g, row0 + i * 32 + 8 * (u >> 2) + (u & 3), col, eb, sum[u]);
+    }
+}
 
 struct Job {  // one k-step of one slice pair, with this wave's source addresses for it
     int d, p, ks;
@@ -67,14 +117,38 @@ void slice_gemm_kernel(const GemmArgs g) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
     const int wm = wave / kWavesN, wn = wave % kWavesN;
 
-    int tm, tn;
-    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
+    // Small problems have fewer macro tiles than the chip has CUs; then several workgroups share a
+    // tile, each taking a subset of its diagonals (diag_mask), and a second kernel adds them up.
+    // In that case the grid is 8 XCDs x groups x (largest tile run of an XCD): an XCD first walks
+    // its run of tiles for group 0, then for group 1, ..., so that the workgroups resident on it at
+    // any time still work on neighbouring tiles and the same slice pairs; surplus workgroups
+    // leave at once.
+    const int groups = g.split_groups > 1 ? g.split_groups : 1;
+    int tm, tn, group = 0;
+    if (groups > 1) {
+        const int slot = (int)blockIdx.x >> 3;
+        const int per_xcd = (g.tiles_m * g.tiles_n + 7) >> 3;
+        group = slot / per_xcd;
+        const int tile_slot = slot - group * per_xcd;
+        int first, count;
+        xcd_tile_range((int)blockIdx.x & 7, g.tiles_m * g.tiles_n, first, count);
+        if (tile_slot >= count) return;
+        tile_of_logical(first + tile_slot, g.tiles_m, g.tiles_n, tm, tn);
+    } else {
+        tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
+    }
     const int tile_id = tm * g.tiles_n + tn;
     const int num_tiles = g.tiles_m * g.tiles_n;
 
+    // The diagonals this workgroup walks, as a bit mask (bit d = diagonal d), highest first.
     const bool pair_mode = g.pair_p > 0;
-    const int d_first = pair_mode ? g.pair_p + g.pair_q : g.num_slices + 1;
-    const int d_last = pair_mode ? d_first : 2;
+    const unsigned diag_mask = pair_mode ? 1u << (g.pair_p + g.pair_q)
+                               : groups > 1 ? g.diag_mask[group] : (1u << (g.num_slices + 2)) - 4u;
+    auto next_diag = [&](int d) -> int {   // the next lower diagonal in the mask, 0 if none
+        const unsigned below = diag_mask & ((1u << d) - 1u);
+        return below ? 31 - __builtin_clz(below) : 0;
+    };
+    const int d_first = 31 - __builtin_clz(diag_mask);
     const int ks_begin = g.kc_begin * kStepsPerChunk, ks_end = g.kc_end * kStepsPerChunk;
 
     // global -> LDS. The slice tensors are stored in blocks of 256 rows x 64 bytes that already
@@ -152,9 +226,9 @@ void slice_gemm_kernel(const GemmArgs g) {
         }
         jb.ks = ks_begin;
         if (pair_mode || ++jb.p >= jb.d) {
-            --jb.d;
+            jb.d = next_diag(jb.d);
             jb.p = 1;
-            if (jb.d < d_last) return false;
+            if (jb.d == 0) return false;
         }
         locate(jb);
         return true;
@@ -248,49 +322,8 @@ void slice_gemm_kernel(const GemmArgs g) {
             __syncthreads();
         }
     };
-    auto write_c = [&](int row, int col, int eb, double sum) {
-        if (row < g.m && col < g.n) {
-            const double val = ldexp(sum, g.EA[row] + eb);
-            double* c = g.C + (int64_t)row * g.ldc + (int64_t)col * g.c_inc;
-            if (g.c_mode == 0) *c = val;
-            else if (g.c_mode == 1) *c = *c + val;
-            else if (g.c_mode == 2) *c = *c - val;
-            else {   // BLAS update: RN(alpha G), then RN(RN(alpha G) + RN(beta C)); C is not read if beta == 0
-                double v = g.alpha * val;
-                if (g.beta != 0.0) v = v + g.beta * *c;
-                *c = v;
-            }
-        }
-    };
-    // Fixed-order FP64 sum: the diagonals come back from the workspace (each thread reads what
-    // it wrote itself, so no synchronisation is needed), least significant first.
-    auto final_narrow = [&]() {
-#pragma unroll 1
-        for (int ij = 0; ij < kTM * kTN; ++ij) {
-            const int i = ij / kTN, j = ij % kTN;
-            const int col = col0 + j * 32;
-            const int eb = col < g.n ? g.EB[col] : 0;
-            double sum[16];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) sum[u] = 0.0;
-            // all 16 accumulators of one MFMA tile at once: four independent 16-byte loads per
-            // diagonal, several diagonals in flight
-#pragma unroll 4
-            for (int d = s + 1; d >= 2; --d) {
-                const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * d) << 52);
-                const unsigned char* src = reinterpret_cast<const unsigned char*>(g.D) +
-                                           ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * 4);
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    v4i v = *reinterpret_cast<const v4i*>(src + (ij * 4 + r4) * (kThreads * 16) + lane_off16);
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) sum[4 * r4 + u] = sum[4 * r4 + u] + (double)v[u] * sc;
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 16; ++u) write_c(row0 + i * 32 + 8 * (u >> 2) + (u & 3), col, eb, sum[u]);
-        }
-    };
+    auto write_c = [&](int row, int col, int eb, double sum) { write_c_element(g, row, col, eb, sum); };
+    auto final_narrow = [&]() { final_sum_narrow(g, tile_id, num_tiles, row0, col0, lane_off16); };
     auto final_wide = [&]() {
 #pragma unroll 1
         for (int ij = 0; ij < kTM * kTN; ++ij) {
@@ -350,7 +383,7 @@ void slice_gemm_kernel(const GemmArgs g) {
         } while (++t < count);
     };
 
-    for (int d = d_first; d >= d_last; --d) {
+    for (int d = d_first; d != 0; d = next_diag(d)) {
         int jobs = pair_mode ? nks : (d - 1) * nks;
         if (WIDE) {
             // at most 2^17 products per output element may share one INT32 sum
@@ -376,7 +409,38 @@ void slice_gemm_kernel(const GemmArgs g) {
     // workgroup's LDS can be handed to another one
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (WIDE) final_wide();
-    else if (!pair_mode) final_narrow();
+    else if (!pair_mode && groups == 1) final_narrow();
+}
+
+// FP64 sum of the stored diagonals as a kernel of its own, for launches in which several
+// workgroups shared a macro tile: same thread-to-element mapping as the product kernel.
+__global__ __launch_bounds__(kThreads) void diag_sum_kernel(const GemmArgs g) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / kWavesN, wn = wave % kWavesN;
+    int tm, tn;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
+    const int row0 = tm * kTile + wm * 128 + 4 * (lane >> 5);
+    const int col0 = tn * kTile + wn * 32 * kTN + (lane & 31);
+    final_sum_narrow(g, tm * g.tiles_n + tn, g.tiles_m * g.tiles_n, row0, col0, (unsigned)tid * 16u);
+}
+
+// Diagonal d costs d - 1 slice products: longest first onto the least loaded group. Returns the
+// largest load.
+int balance_diagonals(int s, int groups, unsigned* masks) {
+    int load[OZIMMU_MAX_SLICES] = {};
+    for (int gidx = 0; gidx < groups; ++gidx) masks[gidx] = 0u;
+    for (int d = s + 1; d >= 2; --d) {
+        int best = 0;
+        for (int gidx = 1; gidx < groups; ++gidx)
+            if (load[gidx] < load[best]) best = gidx;
+        masks[best] |= 1u << d;
+        load[best] += d - 1;
+    }
+    int worst = 0;
+    for (int gidx = 0; gidx < groups; ++gidx) worst = load[gidx] > worst ? load[gidx] : worst;
+    return worst;
 }
 
 }  // namespace
@@ -393,7 +457,35 @@ hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st) {
     } else {
         e = allow_dynamic_lds<&slice_gemm_kernel<false>>(kLdsAlloc);
         if (e != hipSuccess) return e;
-        slice_gemm_kernel<false><<<dim3(blocks), dim3(kThreads), kLdsAlloc, st>>>(args);
+        // The chip runs kResidentTiles workgroups at a time. If the tile count is small, or not
+        // close to a multiple of that, several workgroups share a tile, each taking a balanced
+        // subset of its diagonals: pick the group count with the fewest slice products on the
+        // critical path (rounds of workgroups x products of the most loaded group); ties go to
+        // the smaller count. More than (s + 1) / 2 groups cannot be balanced (the longest
+        // diagonal alone has s of the s (s + 1) / 2 products).
+        const int s = args.num_slices;
+        int groups = 1;
+        if (args.pair_p == 0) {
+            long best_cost = 0;
+            unsigned scratch_masks[OZIMMU_MAX_SLICES];
+            for (int cand = 1; cand <= (s + 1) / 2; ++cand) {
+                const long rounds = ((long)((blocks + 7) / 8) * 8 * cand + kResidentTiles - 1) / kResidentTiles;
+                const long cost = rounds * balance_diagonals(s, cand, scratch_masks) + (cand > 1 ? 1 : 0);
+                if (cand == 1 || cost < best_cost) { best_cost = cost; groups = cand; }
+            }
+        }
+        if (args.pair_p == 0 && groups >= 2) {
+            GemmArgs split = args;
+            split.split_groups = groups;
+            balance_diagonals(s, groups, split.diag_mask);
+            const int per_xcd = (blocks + 7) / 8;   // the largest run of tiles an XCD owns
+            slice_gemm_kernel<false><<<dim3(8 * per_xcd * groups), dim3(kThreads), kLdsAlloc, st>>>(split);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            diag_sum_kernel<<<dim3(blocks), dim3(kThreads), 0, st>>>(split);
+        } else {
+            slice_gemm_kernel<false><<<dim3(blocks), dim3(kThreads), kLdsAlloc, st>>>(args);
+        }
     }
     return hipGetLastError();
 }

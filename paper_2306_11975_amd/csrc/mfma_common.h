@@ -13,11 +13,7 @@ typedef long long v2l __attribute__((ext_vector_type(2)));
 // Workgroup -> tile. Hardware deals workgroups round-robin over the 8 XCDs (each with its own
 // L2); give every XCD a contiguous run of tiles, ordered in column panels 4 tiles tall so that
 // the 32 workgroups resident on an XCD share A and B panels through that L2.
-__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
-    const int total = tiles_m * tiles_n;
-    const int xcd = bid & 7, slot = bid >> 3;
-    const int q = total >> 3, r = total & 7;
-    const int logical = xcd * q + (xcd < r ? xcd : r) + slot;
+__device__ __forceinline__ void tile_of_logical(int logical, int tiles_m, int tiles_n, int& tm, int& tn) {
     constexpr int GM = 4;
     const int per_group = GM * tiles_n;
     const int group = logical / per_group;
@@ -26,6 +22,17 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
     const int in_group = logical - group * per_group;
     tm = first_m + in_group % rows;
     tn = in_group / rows;
+}
+// XCD x owns the logical tiles [first, first + count): the total is dealt out in eight nearly equal runs.
+__device__ __forceinline__ void xcd_tile_range(int xcd, int total, int& first, int& count) {
+    const int q = total >> 3, r = total & 7;
+    first = xcd * q + (xcd < r ? xcd : r);
+    count = q + (xcd < r ? 1 : 0);
+}
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
+    int first, count;
+    xcd_tile_range(bid & 7, tiles_m * tiles_n, first, count);
+    tile_of_logical(first + (bid >> 3), tiles_m, tiles_n, tm, tn);
 }
 
 // A zero the optimiser cannot see through. Address arithmetic of the code that runs after the

@@ -38,6 +38,10 @@ struct GemmArgs {
     double alpha, beta;    // c_mode 3 only
     const int32_t* EA;
     const int32_t* EB;
+    // several workgroups per macro tile (small problems): workgroup group g of a tile walks the
+    // diagonals in diag_mask[g] (bit d = diagonal d) and a second kernel forms the FP64 sum
+    int split_groups;               // 0 or 1: off
+    unsigned diag_mask[OZIMMU_MAX_SLICES];
     // second product of the register-resident kernel (dual != 0): C = G(SA,SB) + G(SA2,SB2) if
     // dual == 1, C = G(SA,SB) - G(SA2,SB2) if dual == 2, each G scaled by its own exponents
     int dual;
