@@ -294,6 +294,8 @@ bool fused_gemm_applies(const GemmArgs& args, bool wide) {
 
 hipError_t launch_fused_gemm(const GemmArgs& args, hipStream_t st) {
     if (args.dual) return launch_shape<2, 4, 2, 1, true>(args, st);
+    // few tiles: the smaller tile shape puts twice as many workgroups on the chip
+    if (args.tiles_m * args.tiles_n * 2 <= 128) return launch_shape<2, 4, 2, 1, false>(args, st);
     return launch_shape<4, 2, 2, 2, false>(args, st);
 }
 
