@@ -93,7 +93,7 @@ __device__ __forceinline__ void final_sum_narrow(const GemmArgs& g, int tile_id,
             for (int r4 = 0; r4 < 4; ++r4) {
                 v4i v = *reinterpret_cast<const v4i*>(src + (ij * 4 + r4) * (kThreads * 16) + lane_off16);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) sum[4 * r4 + u] = sum[4 * r4 + u] + (double)v[u] * sc;
+                for (int u = 0; u < 4; ++u) sum[4 * r4 + u] = fma((double)v[u], sc, sum[4 * r4 + u]);   // exact product: rounds like the add
             }
         }
 #pragma unroll

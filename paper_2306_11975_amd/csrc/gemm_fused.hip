@@ -217,13 +217,14 @@ void fused_gemm_kernel(const GemmArgs g) {
                 buf = nbuf;
             }
             // fold the finished diagonal: exact conversion, exact power-of-two scale, one rounded add
+            // (the product inside the fused multiply-add is exact, so it rounds exactly like the add)
             const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * d) << 52);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int u = 0; u < 16; ++u) sum[i][j][u] = sum[i][j][u] + (double)acc_read(acc[i][j][u]) * sc;
+                    for (int u = 0; u < 16; ++u) sum[i][j][u] = fma((double)acc_read(acc[i][j][u]), sc, sum[i][j][u]);
         }
         if (DUAL && prod == 0) {
 #pragma unroll
