@@ -79,6 +79,10 @@ def _load():
         lib.oz_auto_loss_sums.argtypes = [i64, i64, vp, i64, i64, i32, i32, vp]
         lib.oz_auto_num_slices.restype = i32
         lib.oz_auto_num_slices.argtypes = [i32, i32, vp, vp, dbl]
+        lib.oz_accumulate_dd.restype = None
+        lib.oz_accumulate_dd.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, i64]
+        lib.oz_dgemm_dd.restype = i32
+        lib.oz_dgemm_dd.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, i32]
         lib.oz_dgemm_blas.restype = i32
         lib.oz_dgemm_blas.argtypes = [i32, i32, i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, i32]
         lib.oz_abs_gemm.restype = None
@@ -272,3 +276,28 @@ def dgemm_blas(transa: bool, transb: bool, alpha: float, A, B, beta: float, C, s
     if rc:
         raise MemoryError
     return Cf
+
+
+def accumulate_dd(S, EA, EB):
+    """Double-double summing-up of the scaled diagonal sums: returns (hi, lo)."""
+    S = np.ascontiguousarray(S, dtype=np.int64)
+    EA = np.ascontiguousarray(EA, dtype=np.int32)
+    EB = np.ascontiguousarray(EB, dtype=np.int32)
+    s, m, n = S.shape
+    hi = np.zeros((m, n), dtype=np.float64)
+    lo = np.zeros((m, n), dtype=np.float64)
+    _load().oz_accumulate_dd(m, n, s, _p(S), _p(EA), _p(EB), _p(hi), _p(lo), n)
+    return hi, lo
+
+
+def dgemm_dd(A, B, s: int):
+    """The Ozaki product with the double-double summing-up: returns (hi, lo), C = hi + lo."""
+    A = _f64(A)
+    B = _f64(B)
+    m, k = A.shape
+    n = B.shape[1]
+    hi = np.zeros((m, n), dtype=np.float64)
+    lo = np.zeros((m, n), dtype=np.float64)
+    if _load().oz_dgemm_dd(m, n, k, _p(A), max(k, 1), _p(B), max(n, 1), _p(hi), _p(lo), max(n, 1), int(s)):
+        raise MemoryError
+    return hi, lo

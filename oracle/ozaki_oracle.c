@@ -423,3 +423,60 @@ int oz_dgemm_blas(int transa, int transb, int64_t m, int64_t n, int64_t k, doubl
     free(opA); free(opB); free(G);
     return rc;
 }
+
+/* ---------------------------------------------------------------------------------
+ * Summing-up in higher precision (Section 2.3.4, first advantage: the precision of the
+ * scheme can be raised above FP64 by more slices and a more accurate summing-up of the
+ * products). Here the per-diagonal integer sums are added in double-double arithmetic
+ * and the result is returned as an unevaluated pair (hi, lo), C = hi + lo.
+ *
+ * Steps per element, least significant diagonal first (t = S_d 2^(-7 d) is exact):
+ *     (h, l) = (0, 0)
+ *     for d = s+1 down to 2:
+ *         sh = RN(h + t);  bb = RN(sh - h)                    -- TwoSum of h and t:
+ *         e  = RN( RN(h - RN(sh - bb)) + RN(t - bb) )         -- h + t = sh + e exactly
+ *         l2 = RN(l + e)
+ *         h  = RN(sh + l2);  l = RN(l2 - RN(h - sh))          -- FastTwoSum renormalisation
+ *     hi = ldexp(h, EA_i + EB_j),  lo = ldexp(l, EA_i + EB_j)
+ * ------------------------------------------------------------------------------- */
+void oz_accumulate_dd(int64_t m, int64_t n, int s, const int64_t *S, const int32_t *EA,
+                      const int32_t *EB, double *Chi, double *Clo, int64_t ldc) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            double h = 0.0, l = 0.0;
+            for (int d = s + 1; d >= 2; --d) {
+                double t = ldexp((double)S[((int64_t)(d - 2) * m + i) * n + j], -OZ_W * d);
+                double sh = h + t;
+                double bb = sh - h;
+                double e = (h - (sh - bb)) + (t - bb);
+                double l2 = l + e;
+                double hn = sh + l2;
+                l = l2 - (hn - sh);
+                h = hn;
+            }
+            Chi[i * ldc + j] = ldexp(h, EA[i] + EB[j]);
+            Clo[i * ldc + j] = ldexp(l, EA[i] + EB[j]);
+        }
+}
+
+/* The whole method with the double-double summing-up. */
+int oz_dgemm_dd(int64_t m, int64_t n, int64_t k, const double *A, int64_t lda, const double *B,
+                int64_t ldb, double *Chi, double *Clo, int64_t ldc, int s) {
+    if (m == 0 || n == 0) return 0;
+    int32_t *EA = malloc(sizeof(int32_t) * (size_t)m);
+    int32_t *EB = malloc(sizeof(int32_t) * (size_t)n);
+    int8_t *SA = malloc((size_t)s * (size_t)m * (size_t)(k ? k : 1));
+    int8_t *SB = malloc((size_t)s * (size_t)n * (size_t)(k ? k : 1));
+    int64_t *S = malloc(sizeof(int64_t) * (size_t)s * (size_t)m * (size_t)n);
+    int rc = 1;
+    if (EA && EB && SA && SB && S) {
+        oz_split_rows(m, k, A, lda, s, EA, SA);
+        oz_split_cols(k, n, B, ldb, s, EB, SB);
+        oz_diagonal_sums(m, n, k, s, SA, SB, S);
+        oz_accumulate_dd(m, n, s, S, EA, EB, Chi, Clo, ldc);
+        rc = 0;
+    }
+    free(EA); free(EB); free(SA); free(SB); free(S);
+    return rc;
+}

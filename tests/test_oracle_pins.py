@@ -622,3 +622,51 @@ def test_zero_cancellation_product_is_more_accurate_than_fp64_gemm():
     errs = {s: avg_rel_error(oracle.dgemm(A, X, s), hi, lo) for s in (8, 10, 12, 13)}
     assert errs[12] < e_fp and errs[13] < e_fp
     assert errs[13] <= errs[12] <= errs[10] <= errs[8]
+
+
+# ------------------------------------------------------------------ double-double summing-up (Section 2.3.4)
+def test_dd_summing_up_against_exact_rational_sum():
+    """The pair (hi, lo) must represent the exact sum of the scaled integer diagonal sums to about
+    2^-104 (double-double addition), and hi must be that sum rounded to nearest."""
+    rng = np.random.default_rng(61)
+    s, m, n = 14, 6, 5
+    S = rng.integers(-(1 << 40), 1 << 40, size=(s, m, n))
+    S[3] = 0
+    S[:, 0, 0] = 0                                 # an exactly zero element
+    S[:, 1, 1] = [(-1) ** d * (1 << 45) for d in range(s)]   # heavy cancellation between diagonals
+    EA = rng.integers(-30, 30, size=m)
+    EB = rng.integers(-30, 30, size=n)
+    hi, lo = oracle.accumulate_dd(S, EA, EB)
+    for i in range(m):
+        for j in range(n):
+            exact = sum(Fraction(int(S[d - 2, i, j])) * Fraction(2) ** (-W * d) for d in range(2, s + 2))
+            exact *= Fraction(2) ** int(EA[i] + EB[j])
+            got = Fraction(float(hi[i, j])) + Fraction(float(lo[i, j]))
+            assert abs(got - exact) <= abs(exact) * Fraction(2) ** -100
+            assert hi[i, j] == float(exact)        # float(Fraction) is correctly rounded
+            if exact == 0:
+                assert hi[i, j] == 0.0 and lo[i, j] == 0.0
+    # with few diagonals the exact sum fits 106 bits and the pair is exact
+    hi2, lo2 = oracle.accumulate_dd(S[:5], EA, EB)
+    for i in range(m):
+        for j in range(n):
+            exact = sum(Fraction(int(S[d - 2, i, j])) * Fraction(2) ** (-W * d) for d in range(2, 7))
+            exact *= Fraction(2) ** int(EA[i] + EB[j])
+            assert Fraction(float(hi2[i, j])) + Fraction(float(lo2[i, j])) == exact
+
+
+def test_dd_product_is_more_accurate_than_fp64_allows():
+    """With 14 slices the kept products carry about 2^-80 of |A||B|; the FP64 summing-up throws that
+    away (2^-53), the double-double one keeps it: the advantage 'precision higher than FP64'."""
+    A, B = wl.phi_pair(24, 20, 200, 0.5, seed=62)
+    ref = exact_product(A, B)
+    G = oracle.abs_gemm(A, B)
+    hi, lo = oracle.dgemm_dd(A, B, 14)
+    C64 = oracle.dgemm(A, B, 14)
+    worst_dd = max(abs(Fraction(float(hi[i, j])) + Fraction(float(lo[i, j])) - ref[i][j]) / Fraction(float(G[i, j]))
+                   for i in range(24) for j in range(20))
+    worst_64 = max(abs(Fraction(float(C64[i, j])) - ref[i][j]) / Fraction(float(G[i, j]))
+                   for i in range(24) for j in range(20))
+    assert worst_dd <= Fraction(2) ** -75
+    assert worst_64 >= Fraction(2) ** -60          # FP64 cannot do better than about half an ulp
+    assert np.array_equal(hi, C64) or np.max(np.abs(hi - C64) / G) <= 2.0 ** -52
