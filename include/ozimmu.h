@@ -143,6 +143,19 @@ ozimmu_status_t ozimmu_dgemm_stage(int stage, int64_t m, int64_t n, int64_t k, c
                                    size_t workspace_bytes, void* stream);
 
 /*
+ * Product with the summing-up in double-double (Section 2.3.4, first advantage of the scheme: its
+ * precision can be raised above FP64 by more slices and a more accurate summing-up). Same splits and
+ * slice products as ozimmu_dgemm; the diagonal sums are then added, least significant first, in
+ * double-double arithmetic (TwoSum of the running high part and the exact term S_d 2^(-7d), error added
+ * to the low part, FastTwoSum renormalisation after every term) and both parts are scaled by
+ * 2^(EA_i + EB_j): C = C_hi + C_lo as an unevaluated sum, C_hi being the FP64-rounded value. C_hi and
+ * C_lo are m x n row-major with the same leading dimension ldc. Workspace and errors as ozimmu_dgemm.
+ */
+ozimmu_status_t ozimmu_dgemm_dd(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                                const double* B, int64_t ldb, double* C_hi, double* C_lo, int64_t ldc,
+                                int num_slices, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * BLAS-style call (Section 4.4: the library stands in for the vendor DGEMM): COLUMN-MAJOR storage,
  * C <- alpha op(A) op(B) + beta C, op(X) = X ('N') or X^T ('T', 'C'); op(A) is m x k, op(B) is
  * k x n, C is m x n; leading dimensions as in the reference BLAS. G = the Ozaki product of op(A) and

@@ -106,6 +106,8 @@ hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned ch
     g.beta = beta;
     g.EA = reinterpret_cast<const int32_t*>(ws + L.off_ea[plane_a]);
     g.EB = reinterpret_cast<const int32_t*>(ws + L.off_eb[plane_b]);
+    g.skip_final = 0;
+    g.C_lo = nullptr;
     g.dual = dual;
     if (dual) {  // only the register-resident kernel combines two products
         g.SA2 = reinterpret_cast<const int8_t*>(ws + L.off_sa[plane_a2]);
@@ -383,6 +385,51 @@ ozimmu_status_t ozimmu_dgemm_blas(char transa, char transb, int64_t m, int64_t n
         else e = launch_split_rows(A, lda, 1, m, k, num_slices, SC, L.n_pad, L.k_pad, EC, st);              // A: k x m
     }
     if (e == hipSuccess) e = run_product(L, n, m, num_slices, ws, 0, 0, C, ldc, 1, 3, st, 0, 0, 0, alpha, beta);
+    return hip_status(e);
+}
+
+ozimmu_status_t ozimmu_dgemm_dd(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
+                                int64_t ldb, double* C_hi, double* C_lo, int64_t ldc, int num_slices,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    Layout L{};
+    ozimmu_status_t rc = check_gemm_args(m, n, k, A, lda, B, ldb, C_hi, ldc, num_slices, workspace, workspace_bytes,
+                                         false, &L);
+    if (rc != OZIMMU_OK || m == 0 || n == 0) return rc;
+    if (!C_lo) return OZIMMU_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (k == 0) {
+        hipError_t e0 = launch_fill_f64(C_hi, ldc, 1, m, n, 0.0, st);
+        if (e0 == hipSuccess) e0 = launch_fill_f64(C_lo, ldc, 1, m, n, 0.0, st);
+        return hip_status(e0);
+    }
+    for (int stage = 0; stage < 2; ++stage) {   // the two splits are those of ozimmu_dgemm
+        rc = ozimmu_dgemm_stage(stage, m, n, k, A, lda, B, ldb, C_hi, ldc, num_slices, workspace, workspace_bytes, stream);
+        if (rc != OZIMMU_OK) return rc;
+    }
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    GemmArgs g{};
+    g.SA = reinterpret_cast<const int8_t*>(ws + L.off_sa[0]);
+    g.SB = reinterpret_cast<const int8_t*>(ws + L.off_sb[0]);
+    g.a_slice_stride = L.m_pad * L.k_pad;
+    g.b_slice_stride = L.n_pad * L.k_pad;
+    g.k_pad = (int)L.k_pad;
+    g.tiles_m = L.tiles_m;
+    g.tiles_n = L.tiles_n;
+    g.m = (int)m;
+    g.n = (int)n;
+    g.num_slices = num_slices;
+    g.kc_begin = 0;
+    g.kc_end = (int)(L.k_pad / kChunk);
+    g.D = ws + L.off_d;
+    g.C = C_hi;
+    g.C_lo = C_lo;
+    g.ldc = ldc;
+    g.c_inc = 1;
+    g.EA = reinterpret_cast<const int32_t*>(ws + L.off_ea[0]);
+    g.EB = reinterpret_cast<const int32_t*>(ws + L.off_eb[0]);
+    g.skip_final = 1;   // every diagonal sum stays in the workspace; the summing-up is a kernel of its own
+    hipError_t e = launch_slice_gemm(g, L.wide, st);
+    if (e == hipSuccess) e = launch_diag_sum_dd(g, L.wide, st);
     return hip_status(e);
 }
 

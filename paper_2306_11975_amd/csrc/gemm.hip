@@ -408,6 +408,7 @@ void slice_gemm_kernel(const GemmArgs g) {
     // direct loads of the clamped tail may still be in flight: they must land before this
     // workgroup's LDS can be handed to another one
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (g.skip_final) return;   // uniform: the sums stay in the workspace for a kernel of their own
     if (WIDE) final_wide();
     else if (!pair_mode && groups == 1) final_narrow();
 }
@@ -424,6 +425,74 @@ __global__ __launch_bounds__(kThreads) void diag_sum_kernel(const GemmArgs g) {
     const int row0 = tm * kTile + wm * 128 + 4 * (lane >> 5);
     const int col0 = tn * kTile + wn * 32 * kTN + (lane & 31);
     final_sum_narrow(g, tm * g.tiles_n + tn, g.tiles_m * g.tiles_n, row0, col0, (unsigned)tid * 16u);
+}
+
+// Double-double sum of the stored diagonal sums (INT32, or INT64 if WIDE), least significant first:
+// TwoSum of the running high part and the exact term, error into the low part, FastTwoSum to
+// renormalise (Section 2.3.4: summing-up in higher precision). Same thread-to-element mapping as the
+// stores of the product kernel.
+__device__ __forceinline__ void dd_add(double& h, double& l, double t) {
+    const double sh = h + t;
+    const double bb = sh - h;
+    const double e = (h - (sh - bb)) + (t - bb);
+    const double l2 = l + e;
+    const double hn = sh + l2;
+    l = l2 - (hn - sh);
+    h = hn;
+}
+template <bool WIDE>
+__global__ __launch_bounds__(kThreads) void diag_sum_dd_kernel(const GemmArgs g) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / kWavesN, wn = wave % kWavesN;
+    int tm, tn;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
+    const int tile_id = tm * g.tiles_n + tn, num_tiles = g.tiles_m * g.tiles_n;
+    const int row0 = tm * kTile + wm * 128 + 4 * (lane >> 5);
+    const int col0 = tn * kTile + wn * 32 * kTN + (lane & 31);
+    const int s = g.num_slices;
+    const unsigned lane_off16 = (unsigned)tid * 16u;
+    constexpr int kPer = WIDE ? 2 : 4;            // values per 16-byte group
+    constexpr int kGroupsPerTile = 16 / kPer;     // 16-byte groups per MFMA tile and thread
+#pragma unroll 1
+    for (int ij = 0; ij < kTM * kTN; ++ij) {
+        const int i = ij / kTN, j = ij % kTN;
+        const int col = col0 + j * 32;
+        if (col >= g.n) continue;
+        const int eb = g.EB[col];
+#pragma unroll 1
+        for (int q = 0; q < kGroupsPerTile; ++q) {
+            double h[kPer], l[kPer];
+#pragma unroll
+            for (int u = 0; u < kPer; ++u) h[u] = l[u] = 0.0;
+            for (int d = s + 1; d >= 2; --d) {
+                const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * d) << 52);
+                const unsigned char* src = reinterpret_cast<const unsigned char*>(g.D) +
+                                           ((int64_t)(d - 2) * num_tiles + tile_id) * (int64_t)(kTileElems * (WIDE ? 8 : 4)) +
+                                           (ij * kGroupsPerTile + q) * (kThreads * 16) + lane_off16;
+                if (WIDE) {
+                    const v2l v = *reinterpret_cast<const v2l*>(src);
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) dd_add(h[u], l[u], (double)v[u] * sc);
+                } else {
+                    const v4i v = *reinterpret_cast<const v4i*>(src);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) dd_add(h[u], l[u], (double)v[u] * sc);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kPer; ++u) {
+                const int r = q * kPer + u;       // accumulator register index 0 .. 15
+                const int row = row0 + i * 32 + 8 * (r >> 2) + (r & 3);
+                if (row < g.m) {
+                    const int e = g.EA[row] + eb;
+                    g.C[(int64_t)row * g.ldc + col] = ldexp(h[u], e);
+                    g.C_lo[(int64_t)row * g.ldc + col] = ldexp(l[u], e);
+                }
+            }
+        }
+    }
 }
 
 // Diagonal d costs d - 1 slice products: longest first onto the least loaded group. Returns the
@@ -454,6 +523,10 @@ hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st) {
         e = allow_dynamic_lds<&slice_gemm_kernel<true>>(kLdsAlloc);
         if (e != hipSuccess) return e;
         slice_gemm_kernel<true><<<dim3(blocks), dim3(kThreads), kLdsAlloc, st>>>(args);
+    } else if (args.skip_final) {
+        e = allow_dynamic_lds<&slice_gemm_kernel<false>>(kLdsAlloc);
+        if (e != hipSuccess) return e;
+        slice_gemm_kernel<false><<<dim3(blocks), dim3(kThreads), kLdsAlloc, st>>>(args);
     } else {
         e = allow_dynamic_lds<&slice_gemm_kernel<false>>(kLdsAlloc);
         if (e != hipSuccess) return e;
@@ -487,6 +560,14 @@ hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st) {
             slice_gemm_kernel<false><<<dim3(blocks), dim3(kThreads), kLdsAlloc, st>>>(args);
         }
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_diag_sum_dd(const GemmArgs& args, bool wide, hipStream_t st) {
+    const int blocks = args.tiles_m * args.tiles_n;
+    if (blocks == 0) return hipSuccess;
+    if (wide) diag_sum_dd_kernel<true><<<dim3(blocks), dim3(kThreads), 0, st>>>(args);
+    else diag_sum_dd_kernel<false><<<dim3(blocks), dim3(kThreads), 0, st>>>(args);
     return hipGetLastError();
 }
 

@@ -40,6 +40,8 @@ struct GemmArgs {
     const int32_t* EB;
     // several workgroups per macro tile (small problems): workgroup group g of a tile walks the
     // diagonals in diag_mask[g] (bit d = diagonal d) and a second kernel forms the FP64 sum
+    int skip_final;                 // leave every diagonal sum in D and write no C (a separate kernel sums)
+    double* C_lo;                   // low parts of a double-double result (sum kernel only)
     int split_groups;               // 0 or 1: off
     unsigned diag_mask[OZIMMU_MAX_SLICES];
     // second product of the register-resident kernel (dual != 0): C = G(SA,SB) + G(SA2,SB2) if
@@ -57,6 +59,8 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
                              int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
                              unsigned long long* colmax, hipStream_t st);
 hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st);
+// Double-double sum of the diagonal sums left in D by a launch with skip_final (C = high, C_lo = low parts).
+hipError_t launch_diag_sum_dd(const GemmArgs& args, bool wide, hipStream_t st);
 // Variant for short inner dimensions that keeps the FP64 sum in registers (no use of args.D).
 constexpr int kFusedMaxK = 1024;
 bool fused_gemm_applies(const GemmArgs& args, bool wide);

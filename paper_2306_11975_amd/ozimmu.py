@@ -22,7 +22,7 @@ WORKSPACE_ALIGN = 256
 EXPORTS = (
     "ozimmu_status_string", "ozimmu_slice_geometry", "ozimmu_slice_offset", "ozimmu_split_rows", "ozimmu_split_cols",
     "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_stage",
-    "ozimmu_dgemm_blas", "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices",
+    "ozimmu_dgemm_dd", "ozimmu_dgemm_blas", "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices",
     "ozimmu_probe_int8_mfma", "ozimmu_probe_lds_read",
 )
 
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
             f.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
         L.ozimmu_dgemm_stage.restype = i32
         L.ozimmu_dgemm_stage.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
+        L.ozimmu_dgemm_dd.restype = i32
+        L.ozimmu_dgemm_dd.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, i32, vp, sz, vp]
         L.ozimmu_dgemm_blas.restype = i32
         L.ozimmu_dgemm_blas.argtypes = [ctypes.c_char, ctypes.c_char, i64, i64, i64, ctypes.c_double, vp, i64, vp, i64,
                                         ctypes.c_double, vp, i64, i32, vp, sz, vp]
@@ -192,6 +194,18 @@ def zgemm(A, B, C, num_slices: int, workspace, stream=None) -> None:
     n = B.shape[1]
     _check(lib().ozimmu_zgemm(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C), _ld(C, n), num_slices,
                               _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+
+
+def dgemm_dd(A, B, C_hi, C_lo, num_slices: int, workspace, stream=None) -> None:
+    """C_hi + C_lo = A . B with the diagonal sums added in double-double (see ozimmu.h)."""
+    m, k = A.shape
+    n = B.shape[1]
+    ldc = _ld(C_hi, n)
+    if _ld(C_lo, n) != ldc:
+        raise ValueError("C_hi and C_lo must have the same leading dimension")
+    _check(lib().ozimmu_dgemm_dd(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C_hi), _ptr(C_lo), ldc,
+                                 num_slices, _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                 _stream(stream)))
 
 
 def dgemm_blas(transa: str, transb: str, m: int, n: int, k: int, alpha: float, A, lda: int, B, ldb: int,
