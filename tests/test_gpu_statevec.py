@@ -1,0 +1,68 @@
+"""End-to-end use the paper describes (Section 4.4): a state-vector simulation of a brickwork circuit of
+random d-qubit unitaries, each gate applied as a complex product of the reshaped state (2^(N-d) x 2^d)
+with the 2^d x 2^d gate matrix, the number of slices chosen automatically before every product.
+The circuits of the paper are defined in a figure that is not available; this is the same kind of
+computation on a seeded synthetic circuit, checked against the vendor complex GEMM and unitarity."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2306_11975_amd import ozimmu
+
+pytestmark = pytest.mark.gpu
+
+
+def random_unitary(dim, gen):
+    g = torch.complex(torch.randn((dim, dim), generator=gen, dtype=torch.float64),
+                      torch.randn((dim, dim), generator=gen, dtype=torch.float64))
+    q, r = torch.linalg.qr(g)
+    return q * (torch.diagonal(r) / torch.diagonal(r).abs())   # Haar-distributed
+
+
+def apply_gate(state, U, first_qubit, d, N, product):
+    """state: 2^N amplitudes; the gate acts on qubits first_qubit .. first_qubit + d - 1."""
+    psi = state.reshape([2] * N)
+    axes = list(range(first_qubit, first_qubit + d))
+    rest = [a for a in range(N) if a not in axes]
+    M = psi.permute(rest + axes).reshape(2 ** (N - d), 2 ** d).contiguous()
+    out = product(M, U.T.contiguous())                          # row vector convention: psi' = psi U^T
+    inv = np.argsort(rest + axes).tolist()
+    return out.reshape([2] * N).permute(inv).reshape(-1).contiguous()
+
+
+@pytest.mark.parametrize("threshold,max_rel", [(0.0, 5e-14), (1.0, 5e-13)])
+def test_brickwork_random_unitary_circuit(threshold, max_rel):
+    N, d, layers = 16, 6, 4
+    gen = torch.Generator().manual_seed(11)
+    picked = []
+
+    def ozaki(M, V):
+        m, k = M.shape
+        n = V.shape[1]
+        s, _ = ozimmu.auto_num_slices(M, V, threshold)
+        picked.append(s)
+        C = torch.empty((m, n), dtype=torch.complex128, device="cuda")
+        ozimmu.zgemm(M, V, C, s, ozimmu.alloc_workspace(m, n, k, s, is_complex=True))
+        return C
+
+    state0 = torch.zeros(2 ** N, dtype=torch.complex128, device="cuda")
+    state0[0] = 1.0
+    a, b = state0.clone(), state0.clone()
+    for layer in range(layers):
+        offset = (d // 2) * (layer % 2)
+        for first in range(offset, N - d + 1, d):
+            U = random_unitary(2 ** d, gen).cuda()
+            a = apply_gate(a, U, first, d, N, ozaki)
+            b = apply_gate(b, U, first, d, N, torch.matmul)
+    torch.cuda.synchronize()
+    a, b = a.cpu().numpy(), b.cpu().numpy()
+    assert abs(np.linalg.norm(a) - 1.0) <= 1e-12
+    assert np.max(np.abs(a - b)) <= max_rel * np.max(np.abs(b)) * 50
+    # amplitude of |00...0>, the quantity the paper compares
+    assert abs(a[0] - b[0]) <= max_rel * 50 * abs(b[0]) + 1e-16
+    # a lossless split needs more slices than one that may drop a bit on average
+    assert min(picked) >= 1 and max(picked) <= 16
+    if threshold == 0.0:
+        assert max(picked) >= 9
+    else:
+        assert max(picked) <= 10
