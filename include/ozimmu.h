@@ -94,7 +94,7 @@ ozimmu_status_t ozimmu_split_cols(int64_t k, int64_t n, const double* B, int64_t
                                   void* col_scratch, void* stream);
 
 /*
- * One slice product on the matrix cores (line 6 of the IMMU algorithm), exposed so that
+ * One slice product on the matrix cores (the product step of the IMMU algorithm), exposed so that
  * the raw INT32 accumulators can be checked:
  *     P[i][j] = sum_{l = k0}^{k0 + klen - 1} SA(p-1, i, l) * SB(q-1, j, l)     (INT32, exact)
  * SA, SB: slice tensors for m and n rows of length k holding at least p resp. q

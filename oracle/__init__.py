@@ -168,7 +168,7 @@ def diagonal_sums(SA, SB) -> np.ndarray:
 
 
 def accumulate(S, EA, EB) -> np.ndarray:
-    """Fixed-order FP64 sum of the scaled diagonal sums (line 7 of the IMMU algorithm)."""
+    """Fixed-order FP64 sum of the scaled diagonal sums (summing-up step of the IMMU algorithm)."""
     S = np.ascontiguousarray(S, dtype=np.int64)
     EA = np.ascontiguousarray(EA, dtype=np.int32)
     EB = np.ascontiguousarray(EB, dtype=np.int32)

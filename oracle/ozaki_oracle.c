@@ -65,7 +65,7 @@ int oz_num_pairs(int s) {
 }
 
 /* ---------------------------------------------------------------------------------
- * SplitInt, line 2: one exponent per row of M.
+ * SplitInt, exponent step: one exponent per row of M.
  *
  * The paper takes the smallest power of two not below the row maximum. Reading used
  * here: E is the frexp exponent of mu = max_l |M_il|, i.e. mu = f * 2^E with
@@ -85,7 +85,7 @@ static int row_exponent(const double *row, int64_t len, int64_t stride) {
     return E;
 }
 
-/* SplitInt, lines 3-5, for one element: the magnitude r = |x| 2^-E in [0,1) is cut
+/* SplitInt, slice-extraction loop, for one element: the magnitude r = |x| 2^-E in [0,1) is cut
  * into consecutive 7-bit chunks below the row's leading place (truncation: the chunk
  * is floor of the shifted remainder), and each chunk carries the sign of x. */
 static void split_element(double x, int E, int s, int8_t *out, int64_t slice_stride) {
@@ -126,7 +126,7 @@ void oz_split_cols(int64_t k, int64_t n, const double *B, int64_t ldb, int s, in
 }
 
 /* ---------------------------------------------------------------------------------
- * Line 6 of the IMMU algorithm: C_tmp = A^(p) . B^(q), exactly, for one pair and for
+ * Product step of the IMMU algorithm: C_tmp = A^(p) . B^(q), exactly, for one pair and for
  * the k-range [k0, k0 + klen). P is m x n INT64, row-major, ld = n.
  * This is the definition (a triple loop); INT64 cannot overflow for any admissible k.
  * ------------------------------------------------------------------------------- */
@@ -145,7 +145,7 @@ void oz_pair_product(int64_t m, int64_t n, int64_t k, const int8_t *SAp, const i
 
 /* Sum of the products of one anti-diagonal d = p + q (2 <= d <= s + 1), in INT64:
  * S_d = sum_{p=1}^{d-1} A^(p) . B^(d-p). All pairs of a diagonal share the scale
- * 2^(-7 d) of line 7, and integer addition is exact, so summing them before the
+ * 2^(-7 d) of the summing-up step, and integer addition is exact, so summing them before the
  * conversion to FP64 changes no mathematics. S is [s][m][n], S[d-2] = S_d. */
 void oz_diagonal_sums(int64_t m, int64_t n, int64_t k, int s, const int8_t *SA,
                       const int8_t *SB, int64_t *S) {
@@ -165,7 +165,7 @@ void oz_diagonal_sums(int64_t m, int64_t n, int64_t k, int s, const int8_t *SA,
 }
 
 /* ---------------------------------------------------------------------------------
- * Line 7 of the IMMU algorithm: C = sum over the kept products of
+ * Summing-up step of the IMMU algorithm: C = sum over the kept products of
  * C_tmp (.) 2^(-(i+j) W) e_A e_B^T, in FP64.
  *
  * Fixed order used as the definition of the result: the per-diagonal integer sums

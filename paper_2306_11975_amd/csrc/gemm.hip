@@ -1,5 +1,5 @@
 // Slice products on the CDNA4 INT8 matrix cores with the FP64 sum fused in
-// (lines 4-9 of the IMMU algorithm, Section 3.1).
+// (the pair loop of the IMMU algorithm with its product and summing-up steps, Section 3.1).
 //
 // One workgroup (8 wavefronts, two per SIMD) owns a 256 x 256 tile of C for the whole computation. It walks
 // the anti-diagonals d = s+1 .. 2 and, inside a diagonal, the pairs (p, d-p) and the k-steps,

@@ -1,8 +1,8 @@
 // SplitInt (Section 3.1, splitting algorithm for integer arithmetic) on gfx950.
 //
-// One power-of-two exponent per row of M = A or B^T (line 2 of SplitInt), then every element
+// One power-of-two exponent per row of M = A or B^T (exponent step of SplitInt), then every element
 // is cut by bit operations (Section 4.1) into signed 7-bit chunks of its significand, placed
-// relative to the row exponent (lines 3-5). Output: padded INT8 slice tensors, zero outside the
+// relative to the row exponent (its slice-extraction loop). Output: padded INT8 slice tensors, zero outside the
 // matrix, in the tiled and column-swizzled block layout that the slice-product kernel copies
 // linearly into LDS (blocks of 256 rows x 64 bytes; the layout is defined with the C ABI).
 //
