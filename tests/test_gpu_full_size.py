@@ -97,3 +97,20 @@ def test_config5_complex_small_k_sampled_rows_bit_exact():
     want = oracle.zgemm(A[idx].cpu().numpy(), B.cpu().numpy(), s)
     assert np.array_equal(bits(got.real.copy()), bits(want.real.copy()))
     assert np.array_equal(bits(got.imag.copy()), bits(want.imag.copy()))
+
+
+@pytest.mark.parametrize("size,s", [(2048, 8), (3072, 7), (6144, 8)])
+def test_tile_counts_that_do_not_fill_the_chip_sampled_rows_bit_exact(size, s):
+    """64, 144 and 576 macro tiles on 256 CUs: several workgroups share a tile (each a subset of its
+    diagonals) and a second kernel forms the sum; the result must not change by a bit."""
+    m = n = k = size
+    A = wl.phi_matrix_device(m, k, 1.0, 1006)
+    B = wl.phi_matrix_device(k, n, 1.0, 2006)
+    C = torch.full((m, n), float("nan"), dtype=torch.float64, device="cuda")
+    ozimmu.dgemm(A, B, C, s, ozimmu.alloc_workspace(m, n, k, s))
+    torch.cuda.synchronize()
+    assert not torch.isnan(C).any()
+    rows = sample_rows(m, 9, seed=size)
+    idx = torch.from_numpy(rows).cuda()
+    want = oracle.dgemm(A[idx].cpu().numpy(), B.cpu().numpy(), s)
+    assert np.array_equal(bits(C[idx].cpu().numpy()), bits(want))
