@@ -268,7 +268,9 @@ def test_two_runs_identical_and_stream_argument():
 
 
 # ------------------------------------------------------------------ complex
-@pytest.mark.parametrize("m,n,k,s", [(64, 64, 64, 7), (130, 70, 256, 7), (33, 300, 100, 11)])
+@pytest.mark.parametrize("m,n,k,s", [(64, 64, 64, 7), (130, 70, 256, 7), (33, 300, 100, 11),
+                                     # beyond the short-k kernel: four launches of the general kernel, INT32 and INT64 sums
+                                     (70, 50, 1300, 6), (300, 260, 1100, 9), (20, 30, 70000, 2)])
 def test_zgemm_bit_exact(m, n, k, s):
     A = wl.gaussian_complex(m, k, seed=1)
     B = wl.unit_column_complex(k, n, seed=2)
