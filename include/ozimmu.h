@@ -19,7 +19,12 @@
  *     row-major; leading dimensions count elements (complex: complex elements).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). All work is
  *     enqueued on it; no entry point synchronises, allocates or frees device memory, or
- *     keeps state between calls. Calls that share a workspace must be stream-ordered.
+ *     keeps state between calls (exceptions, stated where they are declared:
+ *     ozimmu_auto_num_slices returns a value to the host and waits for the stream; the
+ *     ozimmu_probe_* utilities). Calls that share a workspace must be stream-ordered.
+ *   - Only kernels are enqueued (no memsets or copies), so the calls can be captured into
+ *     a HIP graph. The first launch of a kernel on a device raises that kernel's dynamic
+ *     LDS limit (a host-side driver call, once): make one ordinary call before capturing.
  *   - Arguments are validated on the host before anything is launched; on an argument
  *     error nothing is enqueued and outputs are untouched.
  *   - Inputs must be finite; the result for NaN/Inf inputs is unspecified. -0.0 is zero.
