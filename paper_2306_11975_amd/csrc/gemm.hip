@@ -48,7 +48,6 @@ constexpr int kWaveShare = kBlockBytes / kWaves;      // bytes of each operand b
 constexpr int kLoadsPerOperand = kWaveShare / 1024;   // wave-wide 1 KiB direct loads per operand and step
 constexpr int kLoadsPerStep = 2 * kLoadsPerOperand;   // direct loads per wavefront and step
 constexpr int kResidentTiles = 256;                   // workgroups the chip runs at a time (one per CU)
-constexpr int kGroups = kTM * kTN * 4;                // 16-byte groups of accumulators per thread
 static_assert(kStages >= 3 && kStages <= 5, "LDS budget");
 static_assert(kTM % kLoadsPerOperand == 0, "one load per kTM / kLoadsPerOperand MFMA rows");
 
