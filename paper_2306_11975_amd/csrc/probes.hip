@@ -135,10 +135,10 @@ ozimmu_status_t ozimmu_probe_int8_mfma(int pattern, int iters, double* tera_ops_
         *tera_ops_per_s = (double)cus * 4.0 * iters * 16.0 * 65536.0 / (ms * 1e-3) / 1e12;
         *shader_mhz = clocks[1] > 0 ? (double)clocks[0] / (double)clocks[1] * 100.0 : 0.0;  // wall clock: 100 MHz
     }
-    if (e0) hipEventDestroy(e0);
-    if (e1) hipEventDestroy(e1);
-    if (sink) hipFree(sink);
-    if (clocks) hipHostFree(clocks);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (sink) (void)hipFree(sink);
+    if (clocks) (void)hipHostFree(clocks);
     return ok ? OZIMMU_OK : OZIMMU_ERR_HIP;
 }
 
@@ -163,9 +163,9 @@ ozimmu_status_t ozimmu_probe_lds_read(int pattern, int iters, double* bytes_per_
              hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
     }
     if (ok && ms > 0.f) *bytes_per_ns_per_cu = (double)iters * 8.0 * 16.0 * 1024.0 / (ms * 1e6);
-    if (e0) hipEventDestroy(e0);
-    if (e1) hipEventDestroy(e1);
-    if (sink) hipFree(sink);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (sink) (void)hipFree(sink);
     return ok ? OZIMMU_OK : OZIMMU_ERR_HIP;
 }
 
