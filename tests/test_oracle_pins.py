@@ -672,3 +672,20 @@ def test_dd_product_is_more_accurate_than_fp64_allows():
     assert worst_dd <= Fraction(2) ** -75
     assert worst_64 >= Fraction(2) ** -60          # FP64 cannot do better than about half an ulp
     assert np.array_equal(hi, C64) or np.max(np.abs(hi - C64) / G) <= 2.0 ** -52
+
+
+# ------------------------------------------------------------------ structural invariants of the method
+def test_transpose_symmetry_and_power_of_two_scaling_are_exact():
+    """(A B)^T = B^T A^T holds bit for bit in the scheme: the slices of a row do not depend on which
+    operand the row belongs to, the integer diagonal sums are symmetric under swapping the roles, and the
+    FP64 order is per element. Likewise scaling rows of A and columns of B by powers of two only moves
+    the exponents: the result is scaled exactly (no rounding changes), unlike a re-association in FP64."""
+    A, B = wl.phi_pair(13, 11, 37, 2.0, seed=71)
+    for s in (3, 8, 13):
+        C = oracle.dgemm(A, B, s)
+        Ct = oracle.dgemm(np.ascontiguousarray(B.T), np.ascontiguousarray(A.T), s)
+        assert np.array_equal(C.T.copy().view(np.uint64), Ct.view(np.uint64))
+        ra = np.ldexp(1.0, (np.arange(13) % 7) - 3)
+        cb = np.ldexp(1.0, (np.arange(11) % 5) - 2)
+        Cs = oracle.dgemm(A * ra[:, None], B * cb[None, :], s)
+        assert np.array_equal(Cs.view(np.uint64), (C * ra[:, None] * cb[None, :]).view(np.uint64))
