@@ -12,6 +12,7 @@ CSRC = PKG / "csrc"
 INCLUDE = PKG.parent / "include"
 OBJ = PKG / "_build"
 LIB = PKG / "libozimmu.so"
+EXAMPLE = PKG / "example_dgemm"       # stand-alone C++ user of the C ABI (csrc/example_dgemm.cpp)
 
 SOURCES = ["split.hip", "gemm.hip", "gemm_fused.hip", "probes.hip", "api.cpp"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", f"-I{INCLUDE}", f"-I{CSRC}"]
@@ -51,6 +52,11 @@ def build(verbose: bool = True) -> Path:
     cmd = [hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", *map(str, objs), "-o", str(tmp)]
     subprocess.run(cmd, check=True)
     os.replace(tmp, LIB)
+    # the stand-alone example links against the library it was just built next to
+    tmp_ex = EXAMPLE.with_suffix(f".tmp{os.getpid()}")
+    subprocess.run([hipcc(), "-O2", "-std=c++17", f"-I{INCLUDE}", str(CSRC / "example_dgemm.cpp"), f"-L{PKG}", "-lozimmu",
+                    "-Wl,-rpath,$ORIGIN", "-o", str(tmp_ex)], check=True)
+    os.replace(tmp_ex, EXAMPLE)
     if verbose:
         print(f"built {LIB}")
     return LIB

@@ -314,3 +314,17 @@ def test_dgemm_captured_in_a_graph_replays_correctly():
         got = C.cpu().numpy()
         assert np.array_equal(bits(got), bits(oracle.dgemm(Ah, Bh, s))), seed
         assert np.array_equal(bits(got), bits(gpu_dgemm(Ah, Bh, s))), seed
+
+
+def test_standalone_cpp_example_runs():
+    """The C ABI without Python or a framework: a small HIP host program (built with the library) picks
+    the lossless slice count, multiplies and checks itself against a plain FP64 loop."""
+    import subprocess
+    from pathlib import Path
+
+    exe = Path(ozimmu.__file__).resolve().parent / "example_dgemm"
+    if not exe.exists():
+        pytest.skip("example_dgemm has not been built (python -m paper_2306_11975_amd.build)")
+    res = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "lossless split" in res.stdout
