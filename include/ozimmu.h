@@ -148,6 +148,17 @@ ozimmu_status_t ozimmu_dgemm_stage(int stage, int64_t m, int64_t n, int64_t k, c
                                    size_t workspace_bytes, void* stream);
 
 /*
+ * Which kernel ozimmu_dgemm uses for a shape, on the host only (nothing is launched; for tests and
+ * for callers who want to know): *kernel = 0 the general slice-product kernel (INT32 diagonal sums),
+ * 1 the register-resident kernel for short k, 2 the general kernel with INT64 diagonal sums
+ * (k-blocking). *groups = number of workgroups that share one 256 x 256 tile (each takes the
+ * diagonals whose bits are set in diag_masks[group], bit d = diagonal d; optional array of
+ * OZIMMU_MAX_SLICES entries): 1 unless the tile count does not fill the chip.
+ */
+ozimmu_status_t ozimmu_launch_plan(int64_t m, int64_t n, int64_t k, int num_slices, int* kernel, int* groups,
+                                   uint32_t* diag_masks);
+
+/*
  * Product with the summing-up in double-double (Section 2.3.4, first advantage of the scheme: its
  * precision can be raised above FP64 by more slices and a more accurate summing-up). Same splits and
  * slice products as ozimmu_dgemm; the diagonal sums are then added, least significant first, in

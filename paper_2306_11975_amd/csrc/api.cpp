@@ -433,4 +433,27 @@ ozimmu_status_t ozimmu_dgemm_dd(int64_t m, int64_t n, int64_t k, const double* A
     return hip_status(e);
 }
 
+ozimmu_status_t ozimmu_launch_plan(int64_t m, int64_t n, int64_t k, int num_slices, int* kernel, int* groups,
+                                   uint32_t* diag_masks) {
+    if (!dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
+    if (num_slices < 1 || num_slices > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
+    if (!kernel || !groups) return OZIMMU_ERR_NULL;
+    const Layout L = make_layout(m, n, k, num_slices, false);
+    unsigned masks[OZIMMU_MAX_SLICES] = {};
+    *groups = 1;
+    if (L.wide) {
+        *kernel = 2;
+        masks[0] = (1u << (num_slices + 2)) - 4u;
+    } else if (L.k_pad <= kFusedMaxK) {
+        *kernel = 1;
+        masks[0] = (1u << (num_slices + 2)) - 4u;
+    } else {
+        *kernel = 0;
+        *groups = plan_tile_sharing(L.tiles_m * L.tiles_n, num_slices, masks);
+    }
+    if (diag_masks)
+        for (int i = 0; i < OZIMMU_MAX_SLICES; ++i) diag_masks[i] = i < *groups ? masks[i] : 0u;
+    return OZIMMU_OK;
+}
+
 }  // extern "C"

@@ -513,6 +513,24 @@ int balance_diagonals(int s, int groups, unsigned* masks) {
 
 }  // namespace
 
+// The chip runs kResidentTiles workgroups at a time. If the tile count is small, or not close to a
+// multiple of that, several workgroups share a tile, each taking a balanced subset of its
+// diagonals: the group count with the fewest slice products on the critical path (rounds of
+// workgroups x products of the most loaded group) is taken; ties go to the smaller count. More
+// than (s + 1) / 2 groups cannot be balanced (the longest diagonal alone has s of the
+// s (s + 1) / 2 products). Returns the group count and fills masks[group] (bit d = diagonal d).
+int plan_tile_sharing(int tiles, int s, unsigned* masks) {
+    int groups = 1;
+    long best_cost = 0;
+    unsigned scratch_masks[OZIMMU_MAX_SLICES];
+    for (int cand = 1; cand <= (s + 1) / 2; ++cand) {
+        const long rounds = ((long)((tiles + 7) / 8) * 8 * cand + kResidentTiles - 1) / kResidentTiles;
+        const long cost = rounds * balance_diagonals(s, cand, scratch_masks) + (cand > 1 ? 1 : 0);
+        if (cand == 1 || cost < best_cost) { best_cost = cost; groups = cand; }
+    }
+    balance_diagonals(s, groups, masks);
+    return groups;
+}
 
 hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st) {
     const int blocks = args.tiles_m * args.tiles_n;
@@ -529,27 +547,13 @@ hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st) {
     } else {
         e = allow_dynamic_lds<&slice_gemm_kernel<false>>(kLdsAlloc);
         if (e != hipSuccess) return e;
-        // The chip runs kResidentTiles workgroups at a time. If the tile count is small, or not
-        // close to a multiple of that, several workgroups share a tile, each taking a balanced
-        // subset of its diagonals: pick the group count with the fewest slice products on the
-        // critical path (rounds of workgroups x products of the most loaded group); ties go to
-        // the smaller count. More than (s + 1) / 2 groups cannot be balanced (the longest
-        // diagonal alone has s of the s (s + 1) / 2 products).
         const int s = args.num_slices;
-        int groups = 1;
-        if (args.pair_p == 0) {
-            long best_cost = 0;
-            unsigned scratch_masks[OZIMMU_MAX_SLICES];
-            for (int cand = 1; cand <= (s + 1) / 2; ++cand) {
-                const long rounds = ((long)((blocks + 7) / 8) * 8 * cand + kResidentTiles - 1) / kResidentTiles;
-                const long cost = rounds * balance_diagonals(s, cand, scratch_masks) + (cand > 1 ? 1 : 0);
-                if (cand == 1 || cost < best_cost) { best_cost = cost; groups = cand; }
-            }
-        }
+        unsigned masks[OZIMMU_MAX_SLICES];
+        const int groups = args.pair_p == 0 ? plan_tile_sharing(blocks, s, masks) : 1;
         if (args.pair_p == 0 && groups >= 2) {
             GemmArgs split = args;
             split.split_groups = groups;
-            balance_diagonals(s, groups, split.diag_mask);
+            for (int gidx = 0; gidx < groups; ++gidx) split.diag_mask[gidx] = masks[gidx];
             const int per_xcd = (blocks + 7) / 8;   // the largest run of tiles an XCD owns
             slice_gemm_kernel<false><<<dim3(8 * per_xcd * groups), dim3(kThreads), kLdsAlloc, st>>>(split);
             e = hipGetLastError();

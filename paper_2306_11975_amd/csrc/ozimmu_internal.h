@@ -59,6 +59,8 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
                              int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
                              unsigned long long* colmax, hipStream_t st);
 hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st);
+// How many workgroups share a macro tile for a given tile count and slice count, and which diagonals each takes.
+int plan_tile_sharing(int tiles, int s, unsigned* masks);
 // Double-double sum of the diagonal sums left in D by a launch with skip_final (C = high, C_lo = low parts).
 hipError_t launch_diag_sum_dd(const GemmArgs& args, bool wide, hipStream_t st);
 // Variant for short inner dimensions that keeps the FP64 sum in registers (no use of args.D).

@@ -22,7 +22,7 @@ WORKSPACE_ALIGN = 256
 EXPORTS = (
     "ozimmu_status_string", "ozimmu_slice_geometry", "ozimmu_slice_offset", "ozimmu_split_rows", "ozimmu_split_cols",
     "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_stage",
-    "ozimmu_dgemm_dd", "ozimmu_dgemm_blas", "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices",
+    "ozimmu_launch_plan", "ozimmu_dgemm_dd", "ozimmu_dgemm_blas", "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices",
     "ozimmu_probe_int8_mfma", "ozimmu_probe_lds_read",
 )
 
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
             f.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
         L.ozimmu_dgemm_stage.restype = i32
         L.ozimmu_dgemm_stage.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
+        L.ozimmu_launch_plan.restype = i32
+        L.ozimmu_launch_plan.argtypes = [i64, i64, i64, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
         L.ozimmu_dgemm_dd.restype = i32
         L.ozimmu_dgemm_dd.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, i32, vp, sz, vp]
         L.ozimmu_dgemm_blas.restype = i32
@@ -194,6 +196,14 @@ def zgemm(A, B, C, num_slices: int, workspace, stream=None) -> None:
     n = B.shape[1]
     _check(lib().ozimmu_zgemm(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C), _ld(C, n), num_slices,
                               _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+
+
+def launch_plan(m: int, n: int, k: int, num_slices: int):
+    """(kernel, groups, masks): which kernel ozimmu_dgemm uses and how diagonals are shared (see ozimmu.h)."""
+    kernel, groups = ctypes.c_int(), ctypes.c_int()
+    masks = (ctypes.c_uint32 * MAX_SLICES)()
+    _check(lib().ozimmu_launch_plan(m, n, k, num_slices, ctypes.byref(kernel), ctypes.byref(groups), masks))
+    return kernel.value, groups.value, list(masks)[: groups.value]
 
 
 def dgemm_dd(A, B, C_hi, C_lo, num_slices: int, workspace, stream=None) -> None:

@@ -107,6 +107,38 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.ozimmu_dgemm_stage(3, 4, 4, 4, fake, 4, fake, 4, fake, 4, 3, fake, 1 << 30, None) == 1
 
 
+def test_launch_plan_host_logic():
+    # the headline shape: 1024 tiles = 4 full rounds of the 256 CUs, one workgroup per tile
+    assert ozimmu.launch_plan(8192, 8192, 8192, 8) == (0, 1, [(1 << 10) - 4])
+    # short k: register-resident kernel; long diagonals: INT64 sums
+    assert ozimmu.launch_plan(4096, 4096, 256, 7)[0] == 1
+    assert ozimmu.launch_plan(4096, 4096, 131072, 8)[0] == 2
+    assert ozimmu.launch_plan(64, 64, 16384, 8)[0] == 0 and ozimmu.launch_plan(64, 64, 16385, 8)[0] == 2
+    # tile counts that do not fill the chip: diagonals shared out, every diagonal exactly once, loads balanced
+    for (size, s) in ((2048, 8), (3072, 7), (6144, 8), (1536, 13), (2048, 2), (2048, 16)):
+        kernel, groups, masks = ozimmu.launch_plan(size, size, size, s)
+        assert kernel == 0 and 1 <= groups <= (s + 1) // 2 and len(masks) == groups
+        seen = 0
+        loads = []
+        for mk in masks:
+            assert mk and not (seen & mk)
+            seen |= mk
+            loads.append(sum(d - 1 for d in range(2, s + 2) if mk >> d & 1))
+        assert seen == (1 << (s + 2)) - 4
+        assert max(loads) - min(loads) <= s            # longest-first assignment
+        tiles = (size // 256) ** 2
+        rounds = lambda g: -(-((tiles + 7) // 8 * 8 * g) // 256)
+        assert rounds(groups) * max(loads) <= rounds(1) * (s * (s + 1) // 2)
+    assert ozimmu.launch_plan(2048, 2048, 2048, 8)[1] == 4
+    assert ozimmu.launch_plan(6144, 6144, 6144, 8)[1] == 4
+    assert ozimmu.launch_plan(2048, 2048, 2048, 2)[1] == 1
+    L = ozimmu.lib()
+    kern, grp = ctypes.c_int(), ctypes.c_int()
+    assert L.ozimmu_launch_plan(-1, 1, 1, 3, ctypes.byref(kern), ctypes.byref(grp), None) == 1
+    assert L.ozimmu_launch_plan(1, 1, 1, 0, ctypes.byref(kern), ctypes.byref(grp), None) == 3
+    assert L.ozimmu_launch_plan(1, 1, 1, 3, None, ctypes.byref(grp), None) == 4
+
+
 def test_blas_call_argument_errors():
     L = ozimmu.lib()
     fake = ctypes.c_void_p(256)
