@@ -20,10 +20,9 @@
 // 16 lanes the LDS serves per clock hit 16 distinct bank groups; registers ->
 // v_mfma_i32_32x32x32_i8.
 // Each wavefront computes 128 x 64 outputs as 4 x 2 MFMA tiles (128 accumulator registers), so
-// that two wavefronts fit on a SIMD: whenever one of them waits (at the barrier, for LDS, or at
-// the issue of a direct load while the texture-address unit is busy) the other one keeps the
-// matrix core fed. The operand fragments are double buffered in registers: while the MFMAs of
-// one 32-wide k-slab run, the fragments of the next slab are read; one barrier per step.
+// that two wavefronts fit on a SIMD. The two take turns: one issues the MFMAs of a 32-wide
+// k-slab from fragments it holds in registers while the other reads its next fragments and
+// issues its direct loads (four phases and four barriers per step, see the main loop).
 #include "ozimmu_internal.h"
 
 #include "mfma_common.h"
@@ -197,22 +196,6 @@ void slice_gemm_kernel(const GemmArgs g) {
 #pragma unroll
         for (int f = 0; f < kTM + kTN; ++f) read_one(a, b, buf, kk, f);
     };
-    // One MFMA row of the register tile (kTN MFMAs) plus its share of the next slab's fragment
-    // reads and, every kTM / kLoadsPerOperand rows, one direct load of the step that is being
-    // prefetched: the texture-address unit takes about 18 cycles per wave-wide 1 KiB load and a
-    // wave stalls at issue while it is busy, so the loads are spread evenly over the step
-    // instead of being issued in a burst after the barrier.
-    constexpr int kReadsPerRow = (kTM + kTN + kTM - 1) / kTM;
-    auto mfma_row = [&](v16i (&acc)[kTM][kTN], const v4i (&a)[kTM], const v4i (&b)[kTN], int i, v4i (&na)[kTM],
-                        v4i (&nb)[kTN], int nbuf, int nkk, const Job& jb, int lbuf, int load_base) {
-#pragma unroll
-        for (int f = i * kReadsPerRow; f < (i + 1) * kReadsPerRow && f < kTM + kTN; ++f) read_one(na, nb, nbuf, nkk, f);
-#pragma unroll
-        for (int j = 0; j < kTN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
-        if (i % (kTM / kLoadsPerOperand) == 0) issue_load(jb, lbuf, load_base + i / (kTM / kLoadsPerOperand));
-        __builtin_amdgcn_sched_barrier(0);
-    };
     auto locate = [&](Job& jb) {  // source addresses of the first step of pair (jb.p, jb.d - jb.p)
         jb.pa = a_tile + (int64_t)(jb.p - 1) * g.a_slice_stride + (int64_t)jb.ks * kBlockBytes;
         jb.pb = b_tile + (int64_t)(jb.d - jb.p - 1) * g.b_slice_stride + (int64_t)jb.ks * kBlockBytes;
@@ -364,22 +347,58 @@ void slice_gemm_kernel(const GemmArgs g) {
     const int nks = ks_end - ks_begin;
     int buf = 0;                // LDS buffer of the step in the matrix cores
     int prev = kStages - 1;     // the buffer released at the previous barrier
-    // One step = two k-slabs. During the first slab the B half of the prefetched step's loads is
-    // issued (into the buffer released at the previous barrier), then every wave has read its
-    // last fragments of the current buffer and its loads of the next step have landed: barrier.
-    // During the second slab the A half of the following step goes into the buffer just released.
+    // One step = two k-slabs = four phases. The two halves of the workgroup (wavefronts 0-3 and 4-7,
+    // one of each on every SIMD) take turns: while one half issues the 8 MFMAs of a slab from
+    // fragments it already holds, the other half reads its next fragments from LDS and issues its
+    // share of the direct loads; a barrier ends every phase and the second half runs one phase
+    // behind the first. The matrix cores of a SIMD thus always have a wavefront that does nothing
+    // but issue MFMAs, and LDS latency, load issue (the texture-address unit takes about 18 cycles
+    // per wave-wide load and a wavefront stalls at issue while it is busy) and barrier waits fall
+    // on the wavefront that has no MFMA to issue anyway. Per step and wavefront:
+    //   MFMA slab 0 | read slab-1 fragments, B half of the loads 3 steps ahead (into the buffer
+    //   released a step ago), wait for the loads of the next step | MFMA slab 1 | read the next
+    //   step's slab-0 fragments, A half of the loads 4 steps ahead (into the buffer just left).
+    // A buffer is overwritten only after both halves have read it: the lagging half reads its
+    // slab-1 fragments one phase after the leading half, and the loads into that buffer are
+    // issued a phase later still.
+    const bool lag = wave >= kWaves / 2;
+    auto phase_barrier = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_barrier" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto mfma_phase = [&](v16i (&acc)[kTM][kTN], const v4i (&a)[kTM], const v4i (&b)[kTN]) {
+        __builtin_amdgcn_s_setprio(1);   // the wavefront with MFMAs to issue goes first on its SIMD
+#pragma unroll
+        for (int i = 0; i < kTM; ++i)
+#pragma unroll
+            for (int j = 0; j < kTN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_s_setprio(0);
+    };
     auto run_steps = [&](v16i (&acc)[kTM][kTN], int count) {
+        if (lag) phase_barrier();        // fall one phase behind ...
         int t = 0;
         do {
-#pragma unroll
-            for (int i = 0; i < kTM; ++i) mfma_row(acc, fa0, fb0, i, fa1, fb1, buf, 1, nxt, prev, kLoadsPerOperand);
+            mfma_phase(acc, fa0, fb0);
+            phase_barrier();
+            read_frags(fa1, fb1, buf, 1);
+            issue_loads(nxt, prev, kLoadsPerOperand, kLoadsPerStep);
+            __builtin_amdgcn_sched_barrier(0);
             wait_loads_and_barrier<(kStages - 2) * kLoadsPerStep>();
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_phase(acc, fa1, fb1);
+            phase_barrier();
             advance_clamped(nxt);
             prev = buf;
             buf = buf + 1 == kStages ? 0 : buf + 1;
-#pragma unroll
-            for (int i = 0; i < kTM; ++i) mfma_row(acc, fa1, fb1, i, fa0, fb0, buf, 0, nxt, prev, 0);
+            read_frags(fa0, fb0, buf, 0);
+            issue_loads(nxt, prev, 0, kLoadsPerOperand);
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
         } while (++t < count);
+        if (!lag) phase_barrier();       // ... and let it catch up: what follows is done by all together
     };
 
     for (int d = d_first; d != 0; d = next_diag(d)) {
