@@ -85,6 +85,8 @@ def _load():
         lib.oz_dgemm_dd.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, i32]
         lib.oz_dgemm_blas.restype = i32
         lib.oz_dgemm_blas.argtypes = [i32, i32, i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, i32]
+        lib.oz_zgemm_blas.restype = i32
+        lib.oz_zgemm_blas.argtypes = [i32, i32, i64, i64, i64, vp, vp, i64, vp, i64, vp, vp, i64, i32]
         lib.oz_abs_gemm.restype = None
         lib.oz_abs_gemm.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp]
         _lib = lib
@@ -273,6 +275,26 @@ def dgemm_blas(transa: bool, transb: bool, alpha: float, A, B, beta: float, C, s
     k = Af.shape[0] if transa else Af.shape[1]
     rc = _load().oz_dgemm_blas(int(transa), int(transb), m, n, k, float(alpha), _p(Af), max(Af.shape[0], 1), _p(Bf),
                                max(Bf.shape[0], 1), float(beta), _p(Cf), max(m, 1), int(s))
+    if rc:
+        raise MemoryError
+    return Cf
+
+
+def zgemm_blas(transa: str, transb: str, alpha: complex, A, B, beta: complex, C, s: int) -> np.ndarray:
+    """Complex BLAS-style call: returns alpha op(A) op(B) + beta C; transa / transb are 'N', 'T' or 'C'
+    (conjugate transpose). A, B, C are 2-D complex arrays as stored (A is m x k for 'N', k x m otherwise;
+    B likewise; C is m x n). They are handed to the C routine in column-major storage."""
+    code = {"N": 0, "T": 1, "C": 2}
+    ta, tb = code[transa.upper()], code[transb.upper()]
+    Af = np.asfortranarray(np.asarray(A, dtype=np.complex128))
+    Bf = np.asfortranarray(np.asarray(B, dtype=np.complex128))
+    Cf = np.array(C, dtype=np.complex128, order="F", copy=True)
+    m, n = Cf.shape
+    k = Af.shape[0] if ta else Af.shape[1]
+    al = np.array([complex(alpha).real, complex(alpha).imag], dtype=np.float64)
+    be = np.array([complex(beta).real, complex(beta).imag], dtype=np.float64)
+    rc = _load().oz_zgemm_blas(ta, tb, m, n, k, _p(al), _p(Af), max(Af.shape[0], 1), _p(Bf), max(Bf.shape[0], 1),
+                               _p(be), _p(Cf), max(m, 1), int(s))
     if rc:
         raise MemoryError
     return Cf

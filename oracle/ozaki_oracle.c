@@ -425,6 +425,78 @@ int oz_dgemm_blas(int transa, int transb, int64_t m, int64_t n, int64_t k, doubl
 }
 
 /* ---------------------------------------------------------------------------------
+ * BLAS-style complex call (Section 4.4: complex GEMM by separated real and imaginary
+ * parts, standing in for the vendor ZGEMM routine): column-major storage of
+ * interleaved (re, im) doubles, leading dimensions in complex elements,
+ * C <- alpha op(A) op(B) + beta C with op(X) = X (0), X^T (1) or X^H (2).
+ *
+ * op(A) (m x k) and op(B) (k x n) are written out as plain row-major complex matrices,
+ * a conjugation negating the imaginary part (exact). G = their complex Ozaki product as
+ * in oz_zgemm (four real products, one rounded combination per part). Then per element,
+ * with alpha = (ar, ai), beta = (br, bi), every operation a rounded FP64 one:
+ *     t = ( RN(RN(ar Gr) - RN(ai Gi)),  RN(RN(ar Gi) + RN(ai Gr)) )
+ *     C = t                                                   if beta == 0 (C is not read),
+ *     u = ( RN(RN(br Cr) - RN(bi Ci)),  RN(RN(br Ci) + RN(bi Cr)) )
+ *     C = ( RN(tr + ur), RN(ti + ui) )                        otherwise;
+ * if alpha == 0 or k == 0 the product is not formed: C = +0 if beta == 0, else u.
+ * (The paper does not discuss alpha, beta or transposes; the order above is the plain
+ * textbook complex multiply-add.)
+ * ------------------------------------------------------------------------------- */
+int oz_zgemm_blas(int transa, int transb, int64_t m, int64_t n, int64_t k, const double *alpha,
+                  const double *A, int64_t lda, const double *B, int64_t ldb, const double *beta,
+                  double *C, int64_t ldc, int s) {
+    if (m == 0 || n == 0) return 0;
+    const double ar = alpha[0], ai = alpha[1], br = beta[0], bi = beta[1];
+    const int beta_zero = br == 0.0 && bi == 0.0;
+    const int no_product = (ar == 0.0 && ai == 0.0) || k == 0;
+    double *opA = NULL, *opB = NULL, *G = NULL;
+    int rc = 0;
+    if (!no_product) {
+        opA = (double *)malloc(sizeof(double) * 2 * (size_t)(m * k));
+        opB = (double *)malloc(sizeof(double) * 2 * (size_t)(k * n));
+        G = (double *)malloc(sizeof(double) * 2 * (size_t)(m * n));
+        if (!opA || !opB || !G) { free(opA); free(opB); free(G); return 1; }
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t l = 0; l < k; ++l) {
+                const double *src = A + 2 * (transa ? l + i * lda : i + l * lda);
+                opA[2 * (i * k + l)] = src[0];
+                opA[2 * (i * k + l) + 1] = transa == 2 ? -src[1] : src[1];
+            }
+        for (int64_t l = 0; l < k; ++l)
+            for (int64_t j = 0; j < n; ++j) {
+                const double *src = B + 2 * (transb ? j + l * ldb : l + j * ldb);
+                opB[2 * (l * n + j)] = src[0];
+                opB[2 * (l * n + j) + 1] = transb == 2 ? -src[1] : src[1];
+            }
+        rc = oz_zgemm(m, n, k, opA, k, opB, n, G, n, s);
+    }
+    if (rc == 0) {
+        for (int64_t j = 0; j < n; ++j)
+            for (int64_t i = 0; i < m; ++i) {
+                double *c = C + 2 * (i + j * ldc);
+                double tr = 0.0, ti = 0.0;
+                if (!no_product) {
+                    const double gr = G[2 * (i * n + j)], gi = G[2 * (i * n + j) + 1];
+                    const double x0 = ar * gr, x1 = ai * gi, y0 = ar * gi, y1 = ai * gr;
+                    tr = x0 - x1;
+                    ti = y0 + y1;
+                }
+                if (beta_zero) {
+                    c[0] = tr;
+                    c[1] = ti;
+                } else {
+                    const double x0 = br * c[0], x1 = bi * c[1], y0 = br * c[1], y1 = bi * c[0];
+                    const double ur = x0 - x1, ui = y0 + y1;
+                    c[0] = no_product ? ur : tr + ur;
+                    c[1] = no_product ? ui : ti + ui;
+                }
+            }
+    }
+    free(opA); free(opB); free(G);
+    return rc;
+}
+
+/* ---------------------------------------------------------------------------------
  * Summing-up in higher precision (Section 2.3.4, first advantage: the precision of the
  * scheme can be raised above FP64 by more slices and a more accurate summing-up of the
  * products). Here the per-diagonal integer sums are added in double-double arithmetic

@@ -587,6 +587,68 @@ def test_blas_call_rounding_order_against_exact_rationals():
     assert np.array_equal(got_t.view(np.uint64), got.view(np.uint64))
 
 
+@pytest.mark.parametrize("ta", ["N", "T", "C"])
+@pytest.mark.parametrize("tb", ["N", "T", "C"])
+def test_complex_blas_call_reduces_to_gaussian_integer_arithmetic(ta, tb):
+    """Gaussian-integer matrices with parts |x| <= 127 live in slice 1 of each plane, so the four real
+    products are exact integers for any s; with Gaussian-integer alpha, beta and C every operation of
+    the update is exact and the call must equal Python's exact complex integer arithmetic. A wrong
+    sign of a conjugation, a swapped plane or a transposed operand fails."""
+    rng = np.random.default_rng(23)
+    m, n, k = 4, 6, 5
+
+    def gauss(shape, lim):
+        return rng.integers(-lim, lim + 1, size=shape) + 1j * rng.integers(-lim, lim + 1, size=shape)
+
+    opA, opB, C0 = gauss((m, k), 127), gauss((k, n), 127), gauss((m, n), 500)
+    A = {"N": opA, "T": opA.T, "C": opA.conj().T}[ta]
+    B = {"N": opB, "T": opB.T, "C": opB.conj().T}[tb]
+    for alpha, beta in ((1, 0), (2 - 3j, 0), (1, 1), (-1 + 2j, 3 - 1j), (0, 2j), (0, 0), (1j, 1j)):
+        got = oracle.zgemm_blas(ta, tb, alpha, A, B, beta, C0, 3)
+        want = alpha * (opA @ opB) + beta * C0      # all parts are integers far below 2^53: exact in complex128
+        assert np.array_equal(got, want), (alpha, beta)
+    got = oracle.zgemm_blas(ta, tb, 1.0, A, B, 0.0, np.full((m, n), np.nan + 1j * np.nan), 2)
+    assert np.array_equal(got, opA @ opB)
+
+
+def test_complex_blas_call_rounding_order_against_exact_rationals():
+    """General values: G from the plain complex routine (pinned elsewhere), then the update replayed in
+    exact rationals with every rounding of the stated order made explicit."""
+    rng = np.random.default_rng(5)
+    m, n, k = 3, 4, 6
+    A = rng.standard_normal((m, k)) + 1j * rng.standard_normal((m, k))
+    B = rng.standard_normal((k, n)) + 1j * rng.standard_normal((k, n))
+    C0 = rng.standard_normal((m, n)) + 1j * rng.standard_normal((m, n))
+    alpha, beta = 1.3 - 0.4j, -0.2 + 0.9j
+    G = oracle.zgemm(A, B, 9)
+    got = oracle.zgemm_blas("N", "N", alpha, A, B, beta, C0, 9)
+
+    def rn(x):
+        return float(x)                          # float(Fraction) rounds to nearest even
+
+    def cmul(a, z):
+        F = Fraction
+        re = rn(F(rn(F(a.real) * F(z.real))) - F(rn(F(a.imag) * F(z.imag))))
+        im = rn(F(rn(F(a.real) * F(z.imag))) + F(rn(F(a.imag) * F(z.real))))
+        return re, im
+
+    for i in range(m):
+        for j in range(n):
+            tr, ti = cmul(alpha, complex(G[i, j]))
+            ur, ui = cmul(beta, complex(C0[i, j]))
+            assert got[i, j].real == rn(Fraction(tr) + Fraction(ur))
+            assert got[i, j].imag == rn(Fraction(ti) + Fraction(ui))
+    # beta == 0: t alone; alpha == 1 leaves G's bits untouched
+    def bits(z):
+        return np.ascontiguousarray(z).view(np.uint64)
+
+    assert np.array_equal(bits(oracle.zgemm_blas("N", "N", 1.0, A, B, 0.0, C0, 9)), bits(G))
+    # the product is odd in each operand plane, so a conjugate transpose equals the plain call on
+    # the explicitly conjugated and transposed data
+    got_c = oracle.zgemm_blas("C", "T", alpha, A.conj().T.copy(), B.T.copy(), beta, C0, 9)
+    assert np.array_equal(bits(got_c), bits(got))
+
+
 # ------------------------------------------------------------------ accuracy trends of Section 4.2
 def avg_rel_error(C, hi, lo):
     """Eq. (7), averaged: |C - C_dd| / |C_dd| with the double-double reference (hi + lo)."""
