@@ -188,6 +188,30 @@ ozimmu_status_t ozimmu_dgemm_blas(char transa, char transb, int64_t m, int64_t n
                                   size_t workspace_bytes, void* stream);
 
 /*
+ * Complex BLAS-style call (Section 4.4: complex GEMM from separated real and imaginary parts,
+ * standing in for the vendor ZGEMM): COLUMN-MAJOR storage of interleaved (re, im) doubles, leading
+ * dimensions in complex elements, C <- alpha op(A) op(B) + beta C, op(X) = X ('N'), X^T ('T') or
+ * X^H ('C'); op(A) is m x k, op(B) is k x n, C is m x n. alpha and beta point to two host doubles
+ * (re, im) each. G = the complex Ozaki product of op(A) and op(B) as in ozimmu_zgemm, the imaginary
+ * plane of a conjugated operand being negated while it is split (exact). Then per element, every
+ * operation one rounded FP64 operation:
+ *     t = ( RN(RN(ar Gr) - RN(ai Gi)),  RN(RN(ar Gi) + RN(ai Gr)) )
+ *     C = t                                         if beta == 0 (C is not read),
+ *     u = beta C formed like t,  C = ( RN(tr + ur), RN(ti + ui) )   otherwise;
+ * if alpha == 0 or k == 0 the product is not formed (A, B, workspace may be null): C = +0 or u.
+ * With alpha == 1 and beta == 0 the product is written straight into C; with beta != 0 it is held in
+ * the workspace until the update (16 m n bytes more). Workspace:
+ * ozimmu_zgemm_blas_workspace_bytes(m, n, k, num_slices, beta_is_zero, &bytes). Errors as for
+ * ozimmu_dgemm_blas; null alpha or beta gives OZIMMU_ERR_NULL.
+ */
+ozimmu_status_t ozimmu_zgemm_blas_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_slices,
+                                                  int beta_is_zero, size_t* bytes);
+ozimmu_status_t ozimmu_zgemm_blas(char transa, char transb, int64_t m, int64_t n, int64_t k,
+                                  const double* alpha, const double* A, int64_t lda, const double* B,
+                                  int64_t ldb, const double* beta, double* C, int64_t ldc, int num_slices,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Automatic choice of the number of slices (Section 4.4, "INT8-AUTO": all elements of the inputs
  * are inspected and the number of slices is taken so that the average mantissa loss of the split
  * stays within a threshold; threshold 0 means a lossless split).

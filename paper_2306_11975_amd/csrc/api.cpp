@@ -120,6 +120,35 @@ hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned ch
     return launch_slice_gemm(g, L.wide, st);
 }
 
+// The four real products of a complex one from the split planes (0 = real, 1 = imaginary):
+// Cr = G(Ar,Br) - G(Ai,Bi);  Ci = G(Ar,Bi) + G(Ai,Br): the second product of each part is
+// combined with the first by one rounded FP64 operation in the kernel's epilogue.
+hipError_t run_complex_products(const Layout& L, int64_t m, int64_t n, int s, unsigned char* ws, double* C,
+                                int64_t ldc, hipStream_t st) {
+    hipError_t e = hipSuccess;
+    if (!L.wide && L.k_pad <= kFusedMaxK) {
+        // short k: both products of a part in one launch, the first one never leaves the registers
+        e = run_product(L, m, n, s, ws, 0, 0, C, 2 * ldc, 2, 0, st, 2, 1, 1);
+        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, C + 1, 2 * ldc, 2, 0, st, 1, 1, 0);
+    } else {
+        e = run_product(L, m, n, s, ws, 0, 0, C, 2 * ldc, 2, 0, st);
+        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 1, C, 2 * ldc, 2, 2, st);
+        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, C + 1, 2 * ldc, 2, 0, st);
+        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 0, C + 1, 2 * ldc, 2, 1, st);
+    }
+    return e;
+}
+
+// 'N' -> 0, 'T' -> 1, 'C' -> 2, anything else -> -1
+int parse_trans(char c) {
+    switch (c) {
+        case 'N': case 'n': return 0;
+        case 'T': case 't': return 1;
+        case 'C': case 'c': return 2;
+    }
+    return -1;
+}
+
 }  // namespace
 
 extern "C" {
@@ -281,18 +310,7 @@ ozimmu_status_t ozimmu_zgemm(int64_t m, int64_t n, int64_t k, const double* A, i
         e = launch_split_cols(B + pl, ldb, 2, k, n, s, reinterpret_cast<int8_t*>(ws + L.off_sb[pl]), L.n_pad,
                               L.k_pad, reinterpret_cast<int32_t*>(ws + L.off_eb[pl]),
                               reinterpret_cast<unsigned long long*>(ws + L.off_colmax), st);
-    // Cr = G(Ar,Br) - G(Ai,Bi);  Ci = G(Ar,Bi) + G(Ai,Br): the second product of each part is
-    // combined with the first by one rounded FP64 operation in the kernel's epilogue.
-    if (!L.wide && L.k_pad <= kFusedMaxK) {
-        // short k: both products of a part in one launch, the first one never leaves the registers
-        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 0, C, 2 * ldc, 2, 0, st, 2, 1, 1);
-        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, C + 1, 2 * ldc, 2, 0, st, 1, 1, 0);
-    } else {
-        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 0, C, 2 * ldc, 2, 0, st);
-        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 1, C, 2 * ldc, 2, 2, st);
-        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, C + 1, 2 * ldc, 2, 0, st);
-        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 0, C + 1, 2 * ldc, 2, 1, st);
-    }
+    if (e == hipSuccess) e = run_complex_products(L, m, n, s, ws, C, ldc, st);
     return hip_status(e);
 }
 
@@ -350,13 +368,9 @@ ozimmu_status_t ozimmu_dgemm_blas(char transa, char transb, int64_t m, int64_t n
                                   const double* A, int64_t lda, const double* B, int64_t ldb, double beta, double* C,
                                   int64_t ldc, int num_slices, void* workspace, size_t workspace_bytes,
                                   void* stream) {
-    auto parse = [](char c, bool* t) {
-        if (c == 'N' || c == 'n') { *t = false; return true; }
-        if (c == 'T' || c == 't' || c == 'C' || c == 'c') { *t = true; return true; }
-        return false;
-    };
-    bool ta = false, tb = false;
-    if (!parse(transa, &ta) || !parse(transb, &tb) || !dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
+    const int pa = parse_trans(transa), pb = parse_trans(transb);
+    if (pa < 0 || pb < 0 || !dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
+    const bool ta = pa != 0, tb = pb != 0;
     if (num_slices < 1 || num_slices > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
     const int64_t one = 1;
     if (lda < std::max(one, ta ? k : m) || ldb < std::max(one, tb ? n : k) || ldc < std::max(one, m))
@@ -385,6 +399,69 @@ ozimmu_status_t ozimmu_dgemm_blas(char transa, char transb, int64_t m, int64_t n
         else e = launch_split_rows(A, lda, 1, m, k, num_slices, SC, L.n_pad, L.k_pad, EC, st);              // A: k x m
     }
     if (e == hipSuccess) e = run_product(L, n, m, num_slices, ws, 0, 0, C, ldc, 1, 3, st, 0, 0, 0, alpha, beta);
+    return hip_status(e);
+}
+
+ozimmu_status_t ozimmu_zgemm_blas_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_slices, int beta_is_zero,
+                                                  size_t* bytes) {
+    if (!dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
+    if (num_slices < 1 || num_slices > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
+    if (!bytes) return OZIMMU_ERR_NULL;
+    size_t total = make_layout(n, m, k, num_slices, true).total;
+    if (!beta_is_zero) total = align_up(total + 2 * sizeof(double) * (size_t)m * (size_t)n);   // the product before the update
+    *bytes = total;
+    return OZIMMU_OK;
+}
+
+ozimmu_status_t ozimmu_zgemm_blas(char transa, char transb, int64_t m, int64_t n, int64_t k, const double* alpha,
+                                  const double* A, int64_t lda, const double* B, int64_t ldb, const double* beta,
+                                  double* C, int64_t ldc, int num_slices, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+    const int ta = parse_trans(transa), tb = parse_trans(transb);
+    if (ta < 0 || tb < 0 || !dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
+    if (num_slices < 1 || num_slices > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
+    const int64_t one = 1;
+    if (lda < std::max(one, ta ? k : m) || ldb < std::max(one, tb ? n : k) || ldc < std::max(one, m))
+        return OZIMMU_ERR_BAD_LD;
+    if (!alpha || !beta) return OZIMMU_ERR_NULL;
+    if (m == 0 || n == 0) return OZIMMU_OK;
+    if (!C) return OZIMMU_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const double ar = alpha[0], ai = alpha[1], br = beta[0], bi = beta[1];
+    const bool beta_zero = br == 0.0 && bi == 0.0;
+    // As in ozimmu_dgemm_blas the column-major m x n result is the row-major n x m array
+    // C^T = op(B)^T op(A)^T (a complex product commutes element by element, so the parts are the same).
+    if (k == 0 || (ar == 0.0 && ai == 0.0)) return hip_status(launch_zaxpby(nullptr, 0, C, ldc, n, m, 0.0, 0.0, br, bi, st));
+    if (!A || !B) return OZIMMU_ERR_NULL;
+    size_t need = 0;
+    ozimmu_zgemm_blas_workspace_bytes(m, n, k, num_slices, beta_zero, &need);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % OZIMMU_WORKSPACE_ALIGN) != 0 || workspace_bytes < need)
+        return OZIMMU_ERR_WORKSPACE;
+    const Layout L = make_layout(n, m, k, num_slices, true);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    unsigned long long* colmax = reinterpret_cast<unsigned long long*>(ws + L.off_colmax);
+    hipError_t e = hipSuccess;
+    // planes: real, then imaginary (negated while splitting if the operand is conjugated)
+    for (int pl = 0; pl < 2 && e == hipSuccess; ++pl) {
+        int8_t* SR = reinterpret_cast<int8_t*>(ws + L.off_sa[pl]);      // op(B)^T: n rows of length k
+        int32_t* ER = reinterpret_cast<int32_t*>(ws + L.off_ea[pl]);
+        const bool neg = pl == 1 && tb == 2;
+        if (!tb) e = launch_split_rows(B + pl, ldb, 2, n, k, num_slices, SR, L.m_pad, L.k_pad, ER, st, neg);
+        else e = launch_split_cols(B + pl, ldb, 2, k, n, num_slices, SR, L.m_pad, L.k_pad, ER, colmax, st, neg);
+    }
+    for (int pl = 0; pl < 2 && e == hipSuccess; ++pl) {
+        int8_t* SC = reinterpret_cast<int8_t*>(ws + L.off_sb[pl]);      // op(A): m rows of length k
+        int32_t* EC = reinterpret_cast<int32_t*>(ws + L.off_eb[pl]);
+        const bool neg = pl == 1 && ta == 2;
+        if (!ta) e = launch_split_cols(A + pl, lda, 2, k, m, num_slices, SC, L.n_pad, L.k_pad, EC, colmax, st, neg);
+        else e = launch_split_rows(A + pl, lda, 2, m, k, num_slices, SC, L.n_pad, L.k_pad, EC, st, neg);
+    }
+    const bool alpha_one = ar == 1.0 && ai == 0.0;
+    // The product goes straight into C when C's old values are not needed, else beside the slices.
+    double* G = beta_zero ? C : reinterpret_cast<double*>(ws + align_up(L.total));
+    const int64_t ldg = beta_zero ? ldc : m;
+    if (e == hipSuccess) e = run_complex_products(L, n, m, num_slices, ws, G, ldg, st);
+    if (e == hipSuccess && !(beta_zero && alpha_one)) e = launch_zaxpby(G, ldg, C, ldc, n, m, ar, ai, br, bi, st);
     return hip_status(e);
 }
 

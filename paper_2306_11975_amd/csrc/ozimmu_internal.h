@@ -53,11 +53,14 @@ struct GemmArgs {
     const int32_t* EB2;
 };
 
+// negate: emit the slices of -A (-B) instead: same exponents, every slice with the opposite sign
+// (how a conjugated operand's imaginary plane is split)
 hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k, int s,
-                             int8_t* S, int64_t m_pad, int64_t k_pad, int32_t* E, hipStream_t st);
+                             int8_t* S, int64_t m_pad, int64_t k_pad, int32_t* E, hipStream_t st,
+                             bool negate = false);
 hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n, int s,
                              int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
-                             unsigned long long* colmax, hipStream_t st);
+                             unsigned long long* colmax, hipStream_t st, bool negate = false);
 hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st);
 // How many workgroups share a macro tile for a given tile count and slice count, and which diagonals each takes.
 int plan_tile_sharing(int tiles, int s, unsigned* masks);
@@ -74,6 +77,12 @@ hipError_t launch_loss_scan_cols(const double* B, int64_t ldb, int inc, int64_t 
                                  unsigned long long* colmax, unsigned long long* sums, hipStream_t st);
 // C = beta C (C = +0 if beta == 0, without reading C) on an m x n row-major array.
 hipError_t launch_scale_f64(double* C, int64_t ldc, int64_t m, int64_t n, double beta, hipStream_t st);
+// Complex update on rows x cols row-major arrays of interleaved (re, im) doubles, leading
+// dimensions in complex elements: t = alpha T (T == nullptr: no product term), u = beta C
+// (beta == 0: C is not read), C = t + u, each complex product as RN(RN(ar xr) - RN(ai xi)),
+// RN(RN(ar xi) + RN(ai xr)). T may be C itself.
+hipError_t launch_zaxpby(const double* T, int64_t ldt, double* C, int64_t ldc, int64_t rows, int64_t cols,
+                         double ar, double ai, double br, double bi, hipStream_t st);
 hipError_t launch_fill_u64(unsigned long long* p, int64_t count, unsigned long long v, hipStream_t st);
 hipError_t launch_fill_f64(double* C, int64_t ldc, int c_inc, int64_t m, int64_t n, double v,
                            hipStream_t st);

@@ -118,11 +118,11 @@ __device__ __forceinline__ void load_word(const unsigned long long* src, int64_t
 
 template <bool WIDE>
 __device__ __forceinline__ void emit_word(const unsigned long long (&b)[4], int E, int s, int8_t* dst,
-                                          int64_t slice_stride) {
+                                          int64_t slice_stride, unsigned long long flip) {
     Fixed x[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) x[u] = to_fixed<WIDE>(b[u], E);
-    const SignMask sm = sign_mask(b[0], b[1], b[2], b[3]);
+    const SignMask sm = sign_mask(b[0] ^ flip, b[1] ^ flip, b[2] ^ flip, b[3] ^ flip);
 #pragma unroll
     for (int p = 1; p <= (WIDE ? OZIMMU_MAX_SLICES : 9); ++p)   // unrolled: p is a constant in field()
         if (p <= s) *reinterpret_cast<uint32_t*>(dst + (int64_t)(p - 1) * slice_stride) = packed_slice<WIDE>(x, sm, p);
@@ -132,7 +132,8 @@ template <bool WIDE, bool CACHED, bool VEC>
 __global__ __launch_bounds__(256) void split_rows_kernel(const double* __restrict__ A, int64_t lda,
                                                          int inc, int m, int64_t k, int s,
                                                          int8_t* __restrict__ S, int64_t m_pad,
-                                                         int64_t k_pad, int32_t* __restrict__ Eout) {
+                                                         int64_t k_pad, int32_t* __restrict__ Eout,
+                                                         unsigned long long flip) {   // sign bit, or 0: slices of -A
     const int row = blockIdx.x;
     const int tid = threadIdx.x;
     const int64_t slice_stride = m_pad * k_pad;
@@ -186,13 +187,13 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const double* __restric
 #pragma unroll
         for (int j = 0; j < kRowCacheWords; ++j) {
             const int64_t w = tid + 256 * j;
-            if (w < words) emit_word<WIDE>(cache[j], E, s, S + word_offset(row, w * 4, k_pad), slice_stride);
+            if (w < words) emit_word<WIDE>(cache[j], E, s, S + word_offset(row, w * 4, k_pad), slice_stride, flip);
         }
     } else {
         for (int64_t w = tid; w < words; w += 256) {
             unsigned long long b[4];
             load_word<VEC>(src, w * 4, k, inc, b);
-            emit_word<WIDE>(b, E, s, S + word_offset(row, w * 4, k_pad), slice_stride);
+            emit_word<WIDE>(b, E, s, S + word_offset(row, w * 4, k_pad), slice_stride, flip);
         }
     }
 }
@@ -240,7 +241,8 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
                                                          int inc, int64_t k, int64_t n, int s,
                                                          int8_t* __restrict__ S, int64_t n_pad,
                                                          int64_t k_pad,
-                                                         const unsigned long long* __restrict__ colmax) {
+                                                         const unsigned long long* __restrict__ colmax,
+                                                         unsigned long long flip) {   // sign bit, or 0: slices of -B
     __shared__ uint32_t tile[kColGroup][kColTileJ][kColLdsStride];
     const int tid = threadIdx.x;
     const int jj = tid & 63, lg = tid >> 6;
@@ -261,7 +263,7 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
             b[u] = (j < n && l < k) ? src[(l * ldb + j) * inc] : 0ull;
             x[u4][u] = to_fixed<WIDE>(b[u], E);
         }
-        sm[u4] = sign_mask(b[0], b[1], b[2], b[3]);
+        sm[u4] = sign_mask(b[0] ^ flip, b[1] ^ flip, b[2] ^ flip, b[3] ^ flip);
     }
 #pragma unroll
     for (int p0 = 1; p0 <= (WIDE ? OZIMMU_MAX_SLICES : 9); p0 += kColGroup) {   // unrolled: slice numbers are constants
@@ -447,6 +449,30 @@ __global__ __launch_bounds__(256) void scale_f64_kernel(double* C, int64_t ldc, 
     }
 }
 
+__global__ __launch_bounds__(256) void zaxpby_kernel(const double* T, int64_t ldt, double* C, int64_t ldc,
+                                                     int64_t rows, int64_t cols, double ar, double ai, double br,
+                                                     double bi) {
+    const bool beta_zero = br == 0.0 && bi == 0.0;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < rows * cols; idx += (int64_t)gridDim.x * 256) {
+        const int64_t r = idx / cols, c = idx % cols;
+        double* dst = C + 2 * (r * ldc + c);
+        double tr = 0.0, ti = 0.0;
+        if (T) {
+            const double gr = T[2 * (r * ldt + c)], gi = T[2 * (r * ldt + c) + 1];
+            tr = ar * gr - ai * gi;
+            ti = ar * gi + ai * gr;
+        }
+        if (!beta_zero) {
+            const double cr = dst[0], ci = dst[1];
+            const double ur = br * cr - bi * ci, ui = br * ci + bi * cr;
+            tr = T ? tr + ur : ur;
+            ti = T ? ti + ui : ui;
+        }
+        dst[0] = tr;
+        dst[1] = ti;
+    }
+}
+
 // Grid of a grid-stride fill: enough blocks to cover the range, capped so the count fits any grid limit.
 unsigned fill_blocks(int64_t elems) {
     const int64_t b = (elems + 255) / 256;
@@ -465,13 +491,14 @@ static int column_band(int64_t k, int64_t n) {
 }
 
 hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k, int s,
-                             int8_t* S, int64_t m_pad, int64_t k_pad, int32_t* E, hipStream_t st) {
+                             int8_t* S, int64_t m_pad, int64_t k_pad, int32_t* E, hipStream_t st, bool negate) {
     if (m_pad == 0) return hipSuccess;
+    const unsigned long long flip = negate ? 1ull << 63 : 0ull;
     const bool wide = s > 9;
     const bool cached = k_pad <= 4 * 256 * kRowCacheWords;
     const bool vec = inc == 1 && lda % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
     const dim3 grid((unsigned)m_pad), block(256);
-#define OZ_ROWS(W, C, V) split_rows_kernel<W, C, V><<<grid, block, 0, st>>>(A, lda * inc, inc, (int)m, k, s, S, m_pad, k_pad, E)
+#define OZ_ROWS(W, C, V) split_rows_kernel<W, C, V><<<grid, block, 0, st>>>(A, lda * inc, inc, (int)m, k, s, S, m_pad, k_pad, E, flip)
     if (wide) {
         if (cached) { if (vec) OZ_ROWS(true, true, true); else OZ_ROWS(true, true, false); }
         else        { if (vec) OZ_ROWS(true, false, true); else OZ_ROWS(true, false, false); }
@@ -485,8 +512,9 @@ hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, i
 
 hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n, int s,
                              int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
-                             unsigned long long* colmax, hipStream_t st) {
+                             unsigned long long* colmax, hipStream_t st, bool negate) {
     if (n_pad == 0) return hipSuccess;
+    const unsigned long long flip = negate ? 1ull << 63 : 0ull;
     fill_u64_kernel<<<dim3((unsigned)((n_pad + 255) / 256)), dim3(256), 0, st>>>(colmax, n_pad, 0ull);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -504,8 +532,8 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
         if (e != hipSuccess) return e;
     }
     const dim3 grid((unsigned)(n_pad / kColTileJ), (unsigned)(k_pad / kColTileL));
-    if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax);
-    else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax);
+    if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, flip);
+    else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, flip);
     return hipGetLastError();
 }
 
@@ -544,6 +572,13 @@ hipError_t launch_loss_scan_cols(const double* B, int64_t ldb, int inc, int64_t 
 hipError_t launch_scale_f64(double* C, int64_t ldc, int64_t m, int64_t n, double beta, hipStream_t st) {
     if (m * n == 0) return hipSuccess;
     scale_f64_kernel<<<dim3(fill_blocks(m * n)), dim3(256), 0, st>>>(C, ldc, m, n, beta);
+    return hipGetLastError();
+}
+
+hipError_t launch_zaxpby(const double* T, int64_t ldt, double* C, int64_t ldc, int64_t rows, int64_t cols,
+                         double ar, double ai, double br, double bi, hipStream_t st) {
+    if (rows == 0 || cols == 0) return hipSuccess;
+    zaxpby_kernel<<<dim3(fill_blocks(rows * cols)), dim3(256), 0, st>>>(T, ldt, C, ldc, rows, cols, ar, ai, br, bi);
     return hipGetLastError();
 }
 

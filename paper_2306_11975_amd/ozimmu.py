@@ -22,7 +22,8 @@ WORKSPACE_ALIGN = 256
 EXPORTS = (
     "ozimmu_status_string", "ozimmu_slice_geometry", "ozimmu_slice_offset", "ozimmu_split_rows", "ozimmu_split_cols",
     "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_stage",
-    "ozimmu_launch_plan", "ozimmu_dgemm_dd", "ozimmu_dgemm_blas", "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices",
+    "ozimmu_launch_plan", "ozimmu_dgemm_dd", "ozimmu_dgemm_blas", "ozimmu_zgemm_blas_workspace_bytes", "ozimmu_zgemm_blas",
+    "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices",
     "ozimmu_probe_int8_mfma", "ozimmu_probe_lds_read",
 )
 
@@ -72,6 +73,11 @@ def lib() -> ctypes.CDLL:
         L.ozimmu_dgemm_blas.restype = i32
         L.ozimmu_dgemm_blas.argtypes = [ctypes.c_char, ctypes.c_char, i64, i64, i64, ctypes.c_double, vp, i64, vp, i64,
                                         ctypes.c_double, vp, i64, i32, vp, sz, vp]
+        L.ozimmu_zgemm_blas_workspace_bytes.restype = i32
+        L.ozimmu_zgemm_blas_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ctypes.POINTER(sz)]
+        L.ozimmu_zgemm_blas.restype = i32
+        L.ozimmu_zgemm_blas.argtypes = [ctypes.c_char, ctypes.c_char, i64, i64, i64, vp, vp, i64, vp, i64, vp, vp, i64,
+                                        i32, vp, sz, vp]
         L.ozimmu_auto_scratch_bytes.restype = i32
         L.ozimmu_auto_scratch_bytes.argtypes = [i64, ctypes.POINTER(sz)]
         L.ozimmu_auto_num_slices.restype = i32
@@ -224,6 +230,23 @@ def dgemm_blas(transa: str, transb: str, m: int, n: int, k: int, alpha: float, A
     column-major storage with the given leading dimensions (see ozimmu.h)."""
     _check(lib().ozimmu_dgemm_blas(transa.encode()[:1], transb.encode()[:1], m, n, k, float(alpha), _ptr(A), lda,
                                    _ptr(B), ldb, float(beta), _ptr(C), ldc, num_slices, _ptr(workspace),
+                                   0 if workspace is None else workspace.numel(), _stream(stream)))
+
+
+def zgemm_blas_workspace_bytes(m: int, n: int, k: int, num_slices: int, beta_is_zero: bool) -> int:
+    out = ctypes.c_size_t()
+    _check(lib().ozimmu_zgemm_blas_workspace_bytes(m, n, k, num_slices, int(bool(beta_is_zero)), ctypes.byref(out)))
+    return out.value
+
+
+def zgemm_blas(transa: str, transb: str, m: int, n: int, k: int, alpha: complex, A, lda: int, B, ldb: int,
+               beta: complex, C, ldc: int, num_slices: int, workspace, stream=None) -> None:
+    """Column-major complex C = alpha op(A) op(B) + beta C; A, B, C are complex128 device tensors used as
+    raw column-major storage with the given leading dimensions in complex elements (see ozimmu.h)."""
+    al = (ctypes.c_double * 2)(complex(alpha).real, complex(alpha).imag)
+    be = (ctypes.c_double * 2)(complex(beta).real, complex(beta).imag)
+    _check(lib().ozimmu_zgemm_blas(transa.encode()[:1], transb.encode()[:1], m, n, k, ctypes.addressof(al), _ptr(A), lda,
+                                   _ptr(B), ldb, ctypes.addressof(be), _ptr(C), ldc, num_slices, _ptr(workspace),
                                    0 if workspace is None else workspace.numel(), _stream(stream)))
 
 

@@ -73,3 +73,62 @@ def test_blas_beta_zero_does_not_read_c_and_degenerate_cases():
             want = np.zeros((m, n)) if beta == 0.0 else beta * C0
             assert np.array_equal(bits(got), bits(want))
             assert not np.signbit(got).any() or beta != 0.0
+
+
+# ------------------------------------------------------------------ complex call
+def zcol_major_on_device(M, ld):
+    r, c = M.shape
+    buf = np.full((max(c, 1), ld), 7.25e300 + 3.5e299j, dtype=np.complex128)
+    buf[:c, :r] = M.T
+    return torch.from_numpy(buf).cuda()
+
+
+def zrun(ta, tb, m, n, k, alpha, beta, s, seed=1, pad=(0, 0, 0), c_nan=False, scale_cols=True):
+    rng = np.random.default_rng(seed)
+    opA = rng.standard_normal((m, k)) * np.exp(rng.standard_normal((m, k))) + 1j * rng.standard_normal((m, k))
+    opB = rng.standard_normal((k, n)) + 1j * rng.standard_normal((k, n)) * np.exp(0.5 * rng.standard_normal((k, n)))
+    A = {"N": opA, "T": opA.T.copy(), "C": opA.conj().T.copy()}[ta]
+    B = {"N": opB, "T": opB.T.copy(), "C": opB.conj().T.copy()}[tb]
+    C0 = np.full((m, n), np.nan + 1j * np.nan) if c_nan else rng.standard_normal((m, n)) + 1j * rng.standard_normal((m, n))
+    lda, ldb, ldc = max(A.shape[0], 1) + pad[0], max(B.shape[0], 1) + pad[1], max(m, 1) + pad[2]
+    dA, dB, dC = zcol_major_on_device(A, lda), zcol_major_on_device(B, ldb), zcol_major_on_device(C0, ldc)
+    ws = torch.empty(ozimmu.zgemm_blas_workspace_bytes(m, n, k, s, beta == 0), dtype=torch.uint8, device="cuda")
+    ozimmu.zgemm_blas(ta, tb, m, n, k, alpha, dA, lda, dB, ldb, beta, dC, ldc, s, ws)
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy()
+    got = out[:n, :m].T
+    want = oracle.zgemm_blas(ta, tb, alpha, A, B, beta, C0, s)
+    assert np.array_equal(bits(got), bits(want)), (ta, tb, alpha, beta)
+    assert (out[:, m:] == 7.25e300 + 3.5e299j).all(), "padding of C must be untouched"
+
+
+@pytest.mark.parametrize("ta", ["N", "T", "C"])
+@pytest.mark.parametrize("tb", ["N", "T", "C"])
+def test_complex_blas_transposes_and_scalars_bit_exact(ta, tb):
+    for alpha, beta in ((1.0, 0.0), (1.3 - 0.4j, -0.2 + 0.9j), (-2.0, 1.0), (0.5j, 0.0)):
+        zrun(ta, tb, 130, 70, 300, alpha, beta, 8, pad=(3, 5, 2))
+
+
+@pytest.mark.parametrize("m,n,k,s", [(300, 270, 1300, 7), (33, 520, 2049, 5), (257, 64, 64, 13), (40, 50, 70000, 2)])
+def test_complex_blas_shapes_across_the_kernels(m, n, k, s):
+    """Short k (both products of a part in one launch), long k (four launches) and INT64 k-blocking."""
+    zrun("C", "N", m, n, k, 1.25 + 0.5j, 0.75j, s, seed=3, pad=(1, 0, 7))
+    zrun("N", "C", m, n, k, 1.0, 0.0, s, seed=4)
+
+
+def test_complex_blas_beta_zero_does_not_read_c_and_degenerate_cases():
+    zrun("N", "N", 64, 48, 100, 2.0 - 1j, 0.0, 6, c_nan=True)
+    zrun("C", "C", 64, 48, 2000, 1.0, 0.0, 6, c_nan=True)
+    for k, alpha in ((0, 1.0), (50, 0.0)):
+        m, n = 37, 21
+        rng = np.random.default_rng(5)
+        C0 = rng.standard_normal((m, n)) + 1j * rng.standard_normal((m, n))
+        for beta in (0.0, -1.5 + 0.25j):
+            dC = zcol_major_on_device(C0, m + 2)
+            dA = torch.zeros(max(m * max(k, 1), 1), dtype=torch.complex128, device="cuda")
+            ozimmu.zgemm_blas("N", "N", m, n, k, alpha, dA, m, dA, max(k, 1), beta, dC, m + 2, 4, None)
+            torch.cuda.synchronize()
+            got = dC.cpu().numpy()[:n, :m].T
+            want = oracle.zgemm_blas("N", "N", alpha, np.zeros((m, k), dtype=complex), np.zeros((k, n), dtype=complex),
+                                     beta, C0, 4)
+            assert np.array_equal(bits(got), bits(want))
