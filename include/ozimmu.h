@@ -240,6 +240,18 @@ ozimmu_status_t ozimmu_auto_num_slices(int64_t m, int64_t n, int64_t k, const do
                                        int* num_slices, uint64_t* loss_sums, void* stream);
 
 /*
+ * The same choice for the operands of a BLAS-style call (ozimmu_dgemm_blas / ozimmu_zgemm_blas):
+ * column-major A and B with transposes as there; the exponents go with the rows of op(A) and the
+ * columns of op(B). scratch: at least ozimmu_auto_scratch_bytes(max(m, n)). Everything else as
+ * ozimmu_auto_num_slices.
+ */
+ozimmu_status_t ozimmu_auto_num_slices_blas(char transa, char transb, int64_t m, int64_t n, int64_t k,
+                                            const double* A, int64_t lda, const double* B, int64_t ldb,
+                                            int is_complex, double threshold, int max_slices, void* scratch,
+                                            size_t scratch_bytes, int* num_slices, uint64_t* loss_sums,
+                                            void* stream);
+
+/*
  * Device characterisation (measurement utilities for the benchmark, not part of the product
  * path; unlike every entry point above they allocate a few KiB for the duration of the call and
  * synchronise the device).

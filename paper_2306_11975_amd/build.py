@@ -13,6 +13,8 @@ INCLUDE = PKG.parent / "include"
 OBJ = PKG / "_build"
 LIB = PKG / "libozimmu.so"
 EXAMPLE = PKG / "example_dgemm"       # stand-alone C++ user of the C ABI (csrc/example_dgemm.cpp)
+PRELOAD = PKG / "libozimmu_preload.so"  # interposer for the vendor DGEMM/ZGEMM symbols (csrc/preload.cpp)
+BLAS_CLIENT = PKG / "blas_client"     # plain rocBLAS/hipBLAS program the interposer is tried on (csrc/blas_client.cpp)
 
 SOURCES = ["split.hip", "gemm.hip", "gemm_fused.hip", "probes.hip", "api.cpp"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", f"-I{INCLUDE}", f"-I{CSRC}"]
@@ -57,6 +59,15 @@ def build(verbose: bool = True) -> Path:
     subprocess.run([hipcc(), "-O2", "-std=c++17", f"-I{INCLUDE}", str(CSRC / "example_dgemm.cpp"), f"-L{PKG}", "-lozimmu",
                     "-Wl,-rpath,$ORIGIN", "-o", str(tmp_ex)], check=True)
     os.replace(tmp_ex, EXAMPLE)
+    # the interposer needs libozimmu and the HIP runtime only: the vendor BLAS is whatever the host program loads
+    tmp_pre = PRELOAD.with_suffix(f".tmp{os.getpid()}.so")
+    subprocess.run([hipcc(), *COMMON, "-shared", str(CSRC / "preload.cpp"), f"-L{PKG}", "-lozimmu", "-ldl",
+                    "-Wl,-rpath,$ORIGIN", "-o", str(tmp_pre)], check=True)
+    os.replace(tmp_pre, PRELOAD)
+    tmp_cl = BLAS_CLIENT.with_suffix(f".tmp{os.getpid()}")
+    subprocess.run([hipcc(), "-O2", "-std=c++17", str(CSRC / "blas_client.cpp"), "-lrocblas", "-lhipblas",
+                    "-o", str(tmp_cl)], check=True)
+    os.replace(tmp_cl, BLAS_CLIENT)
     if verbose:
         print(f"built {LIB}")
     return LIB

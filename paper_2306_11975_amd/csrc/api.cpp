@@ -149,6 +149,58 @@ int parse_trans(char c) {
     return -1;
 }
 
+// One operand of the automatic slice-count choice: a row-major rows x cols array whose groups
+// (the vectors that share an exponent) are its rows, or its columns if by_cols.
+struct ScanOperand {
+    const double* ptr;
+    int64_t ld, rows, cols;
+    bool by_cols;
+};
+
+ozimmu_status_t auto_select(const ScanOperand& a, const ScanOperand& b, int64_t scratch_cols, int is_complex,
+                            double threshold, int max_slices, void* scratch, size_t scratch_bytes, int* num_slices,
+                            uint64_t* loss_sums, void* stream) {
+    if (max_slices < 1 || max_slices > OZIMMU_MAX_SLICES || !(threshold >= 0.0)) return OZIMMU_ERR_BAD_SLICES;
+    if (!num_slices) return OZIMMU_ERR_NULL;
+    if ((a.rows > 0 && a.cols > 0 && !a.ptr) || (b.rows > 0 && b.cols > 0 && !b.ptr)) return OZIMMU_ERR_NULL;
+    size_t need = 0;
+    ozimmu_auto_scratch_bytes(scratch_cols, &need);
+    if (!scratch || (reinterpret_cast<uintptr_t>(scratch) % OZIMMU_WORKSPACE_ALIGN) != 0 || scratch_bytes < need)
+        return OZIMMU_ERR_WORKSPACE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned long long* sums = static_cast<unsigned long long*>(scratch);          // [4][16]
+    unsigned long long* colmax = sums + 4 * OZIMMU_MAX_SLICES;
+    const int parts = is_complex ? 2 : 1, inc = is_complex ? 2 : 1;
+    hipError_t e = launch_fill_u64(sums, 4 * OZIMMU_MAX_SLICES, 0ull, st);
+    const ScanOperand* ops[2] = {&a, &b};
+    for (int o = 0; o < 2; ++o)
+        for (int pl = 0; pl < parts && e == hipSuccess; ++pl) {
+            const ScanOperand& x = *ops[o];
+            unsigned long long* dst = sums + (o * parts + pl) * OZIMMU_MAX_SLICES;
+            if (x.by_cols) e = launch_loss_scan_cols(x.ptr + pl, x.ld, inc, x.rows, x.cols, colmax, dst, st);
+            else e = launch_loss_scan_rows(x.ptr + pl, x.ld, inc, x.rows, x.cols, dst, st);
+        }
+    unsigned long long host[4 * OZIMMU_MAX_SLICES];
+    if (e == hipSuccess) e = hipMemcpyAsync(host, sums, sizeof(host), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return OZIMMU_ERR_HIP;
+
+    const int planes = 2 * parts;
+    const double count_a = (double)a.rows * (double)a.cols, count_b = (double)b.rows * (double)b.cols;
+    int pick = max_slices;
+    for (int s = 1; s <= max_slices; ++s) {
+        bool ok = true;
+        for (int p = 0; p < planes; ++p)
+            ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < parts ? count_a : count_b);
+        if (ok) { pick = s; break; }
+    }
+    *num_slices = pick;
+    if (loss_sums)
+        for (int i = 0; i < planes * OZIMMU_MAX_SLICES; ++i) loss_sums[i] = host[i];
+    return OZIMMU_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -326,42 +378,29 @@ ozimmu_status_t ozimmu_auto_num_slices(int64_t m, int64_t n, int64_t k, const do
                                        int max_slices, void* scratch, size_t scratch_bytes,
                                        int* num_slices, uint64_t* loss_sums, void* stream) {
     if (!dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
-    if (max_slices < 1 || max_slices > OZIMMU_MAX_SLICES || !(threshold >= 0.0)) return OZIMMU_ERR_BAD_SLICES;
-    if (!num_slices) return OZIMMU_ERR_NULL;
     if ((m > 0 && lda < k) || (k > 0 && ldb < n)) return OZIMMU_ERR_BAD_LD;
-    if ((m > 0 && k > 0 && !A) || (k > 0 && n > 0 && !B)) return OZIMMU_ERR_NULL;
-    size_t need = 0;
-    ozimmu_auto_scratch_bytes(n, &need);
-    if (!scratch || (reinterpret_cast<uintptr_t>(scratch) % OZIMMU_WORKSPACE_ALIGN) != 0 || scratch_bytes < need)
-        return OZIMMU_ERR_WORKSPACE;
+    // row-major A (m x k): rows as stored; row-major B (k x n): columns of the stored array
+    const ScanOperand a{A, lda, m, k, false}, b{B, ldb, k, n, true};
+    return auto_select(a, b, n, is_complex, threshold, max_slices, scratch, scratch_bytes, num_slices, loss_sums,
+                       stream);
+}
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    unsigned long long* sums = static_cast<unsigned long long*>(scratch);          // [4][16]
-    unsigned long long* colmax = sums + 4 * OZIMMU_MAX_SLICES;
-    const int parts = is_complex ? 2 : 1, inc = is_complex ? 2 : 1;
-    hipError_t e = launch_fill_u64(sums, 4 * OZIMMU_MAX_SLICES, 0ull, st);
-    for (int pl = 0; pl < parts && e == hipSuccess; ++pl)
-        e = launch_loss_scan_rows(A + pl, lda, inc, m, k, sums + pl * OZIMMU_MAX_SLICES, st);
-    for (int pl = 0; pl < parts && e == hipSuccess; ++pl)
-        e = launch_loss_scan_cols(B + pl, ldb, inc, k, n, colmax, sums + (parts + pl) * OZIMMU_MAX_SLICES, st);
-    unsigned long long host[4 * OZIMMU_MAX_SLICES];
-    if (e == hipSuccess) e = hipMemcpyAsync(host, sums, sizeof(host), hipMemcpyDeviceToHost, st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess) return OZIMMU_ERR_HIP;
-
-    const int planes = 2 * parts;
-    const double count_a = (double)m * (double)k, count_b = (double)k * (double)n;
-    int pick = max_slices;
-    for (int s = 1; s <= max_slices; ++s) {
-        bool ok = true;
-        for (int p = 0; p < planes; ++p)
-            ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < parts ? count_a : count_b);
-        if (ok) { pick = s; break; }
-    }
-    *num_slices = pick;
-    if (loss_sums)
-        for (int i = 0; i < planes * OZIMMU_MAX_SLICES; ++i) loss_sums[i] = host[i];
-    return OZIMMU_OK;
+ozimmu_status_t ozimmu_auto_num_slices_blas(char transa, char transb, int64_t m, int64_t n, int64_t k,
+                                            const double* A, int64_t lda, const double* B, int64_t ldb,
+                                            int is_complex, double threshold, int max_slices, void* scratch,
+                                            size_t scratch_bytes, int* num_slices, uint64_t* loss_sums,
+                                            void* stream) {
+    const int ta = parse_trans(transa), tb = parse_trans(transb);
+    if (ta < 0 || tb < 0 || !dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
+    const int64_t one = 1;
+    if (lda < std::max(one, ta ? k : m) || ldb < std::max(one, tb ? n : k)) return OZIMMU_ERR_BAD_LD;
+    // A column-major r x c array is the row-major c x r array with the same leading dimension.
+    // Exponents go with the rows of op(A) and the columns of op(B): those are rows of the stored
+    // row-major array when the operand is transposed (A) or not transposed (B).
+    const ScanOperand a = ta ? ScanOperand{A, lda, m, k, false} : ScanOperand{A, lda, k, m, true};
+    const ScanOperand b = tb ? ScanOperand{B, ldb, k, n, true} : ScanOperand{B, ldb, n, k, false};
+    return auto_select(a, b, std::max(m, n), is_complex, threshold, max_slices, scratch, scratch_bytes, num_slices,
+                       loss_sums, stream);
 }
 
 ozimmu_status_t ozimmu_dgemm_blas(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha,

@@ -1,0 +1,319 @@
+// libozimmu_preload.so: stands in for the vendor's double-precision GEMM entry points
+// (Section 4.4, third extension: the vendor DGEMM/ZGEMM calls of an unmodified program are
+// intercepted through the dynamic loader's preload list and computed by the Ozaki scheme with an
+// automatically chosen number of slices).
+//
+//   LD_PRELOAD=/path/to/libozimmu_preload.so  program ...
+//
+// Intercepted: rocblas_dgemm, rocblas_zgemm, hipblasDgemm, hipblasZgemm and their _64 forms. A call
+// is computed here when the handle is in host pointer mode (alpha and beta readable on the host) and
+// the library accepts the arguments; every other call, and every call in vendor mode, goes on to the
+// vendor's routine found with dlsym(RTLD_NEXT, ...), which then also reports argument errors.
+//
+// Environment (read once, at the first intercepted call):
+//   OZIMMU_MODE       "auto" (default): slice count chosen per call from the operands;
+//                     "3" .. "16": that many slices; "vendor": pass everything through.
+//   OZIMMU_THRESHOLD  admitted average mantissa loss in bits for "auto" (default 0: lossless split).
+//   OZIMMU_MIN_WORK   calls with m*n*k below this go to the vendor (default 0: none do).
+//   OZIMMU_VERBOSE    "1": one line per intercepted call on stderr.
+//
+// Unlike libozimmu itself this layer owns device memory: one workspace per device, grown on demand
+// with hipMalloc (after a device synchronisation when an older, smaller one is replaced) and kept
+// until the process ends. Calls are serialised by a lock while they are enqueued, and a call on a
+// different stream than the previous one first waits (on the device) for that one's work, so the
+// shared workspace is never used by two products at once. In "auto" mode each call waits for its
+// stream once (the slice count comes back to the host).
+#include <dlfcn.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+
+#include <hip/hip_runtime.h>
+#include <hipblas/hipblas.h>
+#include <rocblas/rocblas.h>
+
+#include "ozimmu.h"
+
+namespace {
+
+struct Config {
+    int slices = 0;          // 0: automatic; > 0: fixed; -1: vendor
+    double threshold = 0.0;
+    double min_work = 0.0;
+    bool verbose = false;
+};
+
+const Config& config() {
+    static Config cfg;
+    static std::once_flag once;
+    std::call_once(once, [] {
+        if (const char* v = std::getenv("OZIMMU_MODE")) {
+            if (!std::strcmp(v, "vendor")) cfg.slices = -1;
+            else if (!std::strcmp(v, "auto") || !*v) cfg.slices = 0;
+            else {
+                char* end = nullptr;
+                const long s = std::strtol(v, &end, 10);
+                if (*end == 0 && s >= 3 && s <= OZIMMU_MAX_SLICES) cfg.slices = (int)s;
+                else {
+                    std::fprintf(stderr, "[ozimmu] OZIMMU_MODE=%s not understood (auto, vendor, 3..%d): using auto\n", v,
+                                 OZIMMU_MAX_SLICES);
+                }
+            }
+        }
+        if (const char* v = std::getenv("OZIMMU_THRESHOLD")) {
+            const double t = std::atof(v);
+            if (t >= 0.0) cfg.threshold = t;
+        }
+        if (const char* v = std::getenv("OZIMMU_MIN_WORK")) cfg.min_work = std::atof(v);
+        if (const char* v = std::getenv("OZIMMU_VERBOSE")) cfg.verbose = std::atoi(v) != 0;
+    });
+    return cfg;
+}
+
+template <class F>
+F vendor(const char* name) {
+    F f = reinterpret_cast<F>(dlsym(RTLD_NEXT, name));
+    if (!f) {
+        std::fprintf(stderr, "[ozimmu] %s: the vendor library is not loaded after this one\n", name);
+        std::abort();
+    }
+    return f;
+}
+
+template <class F>
+F helper(const char* name) { return reinterpret_cast<F>(dlsym(RTLD_DEFAULT, name)); }
+
+// ---- per-device workspace -------------------------------------------------------------------
+constexpr int kMaxDevices = 64;
+struct DeviceState {
+    void* buffer = nullptr;
+    size_t bytes = 0;
+    hipEvent_t done = nullptr;
+    hipStream_t last_stream = nullptr;
+    bool used = false;
+};
+DeviceState g_state[kMaxDevices];
+std::mutex g_lock;
+
+size_t align_up(size_t x) { return (x + OZIMMU_WORKSPACE_ALIGN - 1) / OZIMMU_WORKSPACE_ALIGN * OZIMMU_WORKSPACE_ALIGN; }
+
+// At least `bytes` of device memory on the current device; earlier contents are not kept.
+void* reserve(DeviceState& d, size_t bytes) {
+    if (d.bytes >= bytes) return d.buffer;
+    if (d.buffer) {
+        if (hipDeviceSynchronize() != hipSuccess) return nullptr;
+        (void)hipFree(d.buffer);
+        d.buffer = nullptr;
+        d.bytes = 0;
+    }
+    const size_t want = align_up(bytes + bytes / 8);
+    if (hipMalloc(&d.buffer, want) != hipSuccess) {
+        (void)hipGetLastError();
+        d.buffer = nullptr;
+        return nullptr;
+    }
+    d.bytes = want;
+    return d.buffer;
+}
+
+struct Call {
+    const char* name;
+    bool cplx;
+    char ta, tb;
+    int64_t m, n, k;
+    const double* alpha;   // host: 1 or 2 doubles
+    const double* A;
+    int64_t lda;
+    const double* B;
+    int64_t ldb;
+    const double* beta;
+    double* C;
+    int64_t ldc;
+};
+
+// Computes the call with the Ozaki scheme; false if it has to go to the vendor instead.
+bool compute(const Call& c, hipStream_t stream) {
+    const Config& cfg = config();
+    if (cfg.slices < 0 || !c.alpha || !c.beta) return false;
+    if (c.m <= 0 || c.n <= 0 || c.k < 0) return false;   // empty or invalid: nothing to gain
+    if ((double)c.m * (double)c.n * (double)c.k < cfg.min_work) return false;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+
+    std::lock_guard<std::mutex> guard(g_lock);
+    DeviceState& d = g_state[dev];
+    if (!d.done && hipEventCreateWithFlags(&d.done, hipEventDisableTiming) != hipSuccess) return false;
+    if (d.used && d.last_stream != stream && hipStreamWaitEvent(stream, d.done, 0) != hipSuccess) return false;
+
+    const bool alpha_zero = c.alpha[0] == 0.0 && (!c.cplx || c.alpha[1] == 0.0);
+    const bool beta_zero = c.beta[0] == 0.0 && (!c.cplx || c.beta[1] == 0.0);
+    const bool product = c.k > 0 && !alpha_zero;
+    int s = cfg.slices > 0 ? cfg.slices : 1;
+    size_t scan_bytes = 0;
+    if (product && cfg.slices == 0) {
+        if (ozimmu_auto_scratch_bytes(std::max(c.m, c.n), &scan_bytes) != OZIMMU_OK) return false;
+        scan_bytes = align_up(scan_bytes);
+        void* scratch = reserve(d, scan_bytes);
+        if (!scratch) return false;
+        if (ozimmu_auto_num_slices_blas(c.ta, c.tb, c.m, c.n, c.k, c.A, c.lda, c.B, c.ldb, c.cplx, cfg.threshold,
+                                        OZIMMU_MAX_SLICES, scratch, scan_bytes, &s, nullptr, stream) != OZIMMU_OK)
+            return false;
+    }
+    size_t ws_bytes = 0;
+    void* ws = nullptr;
+    if (product) {
+        const ozimmu_status_t rc = c.cplx ? ozimmu_zgemm_blas_workspace_bytes(c.m, c.n, c.k, s, beta_zero, &ws_bytes)
+                                          : ozimmu_workspace_bytes(c.n, c.m, c.k, s, 0, &ws_bytes);
+        if (rc != OZIMMU_OK) return false;
+        ws = reserve(d, ws_bytes);
+        if (!ws) return false;
+    }
+    ozimmu_status_t rc;
+    if (c.cplx)
+        rc = ozimmu_zgemm_blas(c.ta, c.tb, c.m, c.n, c.k, c.alpha, c.A, c.lda, c.B, c.ldb, c.beta, c.C, c.ldc, s, ws,
+                               ws_bytes, stream);
+    else
+        rc = ozimmu_dgemm_blas(c.ta, c.tb, c.m, c.n, c.k, c.alpha[0], c.A, c.lda, c.B, c.ldb, c.beta[0], c.C, c.ldc, s, ws,
+                               ws_bytes, stream);
+    if (rc != OZIMMU_OK) return false;   // nothing has been written to C: the vendor routine redoes the call
+    d.used = true;
+    d.last_stream = stream;
+    (void)hipEventRecord(d.done, stream);
+    if (cfg.verbose)
+        std::fprintf(stderr, "[ozimmu] %s %c%c m=%lld n=%lld k=%lld slices=%d%s\n", c.name, c.ta, c.tb, (long long)c.m,
+                     (long long)c.n, (long long)c.k, s, cfg.slices == 0 && product ? " (auto)" : "");
+    return true;
+}
+
+void note_passthrough(const char* name) {
+    if (config().verbose) std::fprintf(stderr, "[ozimmu] %s -> vendor\n", name);
+}
+
+char op_letter(int op) { return op == 111 ? 'N' : op == 112 ? 'T' : op == 113 ? 'C' : '?'; }   // the BLAS operation codes both libraries use
+
+// ---- rocBLAS ----------------------------------------------------------------------------------
+bool rocblas_context(rocblas_handle handle, hipStream_t* stream) {
+    using get_stream_t = rocblas_status (*)(rocblas_handle, hipStream_t*);
+    using get_mode_t = rocblas_status (*)(rocblas_handle, rocblas_pointer_mode*);
+    static const get_stream_t get_stream = helper<get_stream_t>("rocblas_get_stream");
+    static const get_mode_t get_mode = helper<get_mode_t>("rocblas_get_pointer_mode");
+    rocblas_pointer_mode mode;
+    return handle && get_stream && get_mode && get_mode(handle, &mode) == rocblas_status_success &&
+           mode == rocblas_pointer_mode_host && get_stream(handle, stream) == rocblas_status_success;
+}
+
+template <class Int, class T, class F>
+rocblas_status rocblas_entry(const char* name, bool cplx, rocblas_handle handle, rocblas_operation ta, rocblas_operation tb,
+                             Int m, Int n, Int k, const T* alpha, const T* A, Int lda, const T* B, Int ldb, const T* beta,
+                             T* C, Int ldc) {
+    hipStream_t stream = nullptr;
+    if (config().slices >= 0 && rocblas_context(handle, &stream)) {
+        const Call c{name, cplx, op_letter((int)ta), op_letter((int)tb), (int64_t)m, (int64_t)n, (int64_t)k,
+                     reinterpret_cast<const double*>(alpha), reinterpret_cast<const double*>(A), (int64_t)lda,
+                     reinterpret_cast<const double*>(B), (int64_t)ldb, reinterpret_cast<const double*>(beta),
+                     reinterpret_cast<double*>(C), (int64_t)ldc};
+        if (compute(c, stream)) return rocblas_status_success;
+    }
+    note_passthrough(name);
+    static const F next = vendor<F>(name);
+    return next(handle, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+}
+
+// ---- hipBLAS ----------------------------------------------------------------------------------
+bool hipblas_context(hipblasHandle_t handle, hipStream_t* stream) {
+    using get_stream_t = hipblasStatus_t (*)(hipblasHandle_t, hipStream_t*);
+    using get_mode_t = hipblasStatus_t (*)(hipblasHandle_t, hipblasPointerMode_t*);
+    static const get_stream_t get_stream = helper<get_stream_t>("hipblasGetStream");
+    static const get_mode_t get_mode = helper<get_mode_t>("hipblasGetPointerMode");
+    hipblasPointerMode_t mode;
+    return handle && get_stream && get_mode && get_mode(handle, &mode) == HIPBLAS_STATUS_SUCCESS &&
+           mode == HIPBLAS_POINTER_MODE_HOST && get_stream(handle, stream) == HIPBLAS_STATUS_SUCCESS;
+}
+
+template <class Int, class T, class F>
+hipblasStatus_t hipblas_entry(const char* name, bool cplx, hipblasHandle_t handle, hipblasOperation_t ta,
+                              hipblasOperation_t tb, Int m, Int n, Int k, const T* alpha, const T* A, Int lda, const T* B,
+                              Int ldb, const T* beta, T* C, Int ldc) {
+    hipStream_t stream = nullptr;
+    if (config().slices >= 0 && hipblas_context(handle, &stream)) {
+        const Call c{name, cplx, op_letter((int)ta), op_letter((int)tb), (int64_t)m, (int64_t)n, (int64_t)k,
+                     reinterpret_cast<const double*>(alpha), reinterpret_cast<const double*>(A), (int64_t)lda,
+                     reinterpret_cast<const double*>(B), (int64_t)ldb, reinterpret_cast<const double*>(beta),
+                     reinterpret_cast<double*>(C), (int64_t)ldc};
+        if (compute(c, stream)) return HIPBLAS_STATUS_SUCCESS;
+    }
+    note_passthrough(name);
+    static const F next = vendor<F>(name);
+    return next(handle, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+}
+
+}  // namespace
+
+extern "C" {
+
+rocblas_status rocblas_dgemm(rocblas_handle handle, rocblas_operation transA, rocblas_operation transB, rocblas_int m,
+                             rocblas_int n, rocblas_int k, const double* alpha, const double* A, rocblas_int lda,
+                             const double* B, rocblas_int ldb, const double* beta, double* C, rocblas_int ldc) {
+    return rocblas_entry<rocblas_int, double, decltype(&rocblas_dgemm)>("rocblas_dgemm", false, handle, transA, transB, m, n,
+                                                                        k, alpha, A, lda, B, ldb, beta, C, ldc);
+}
+
+rocblas_status rocblas_dgemm_64(rocblas_handle handle, rocblas_operation transA, rocblas_operation transB, int64_t m,
+                                int64_t n, int64_t k, const double* alpha, const double* A, int64_t lda, const double* B,
+                                int64_t ldb, const double* beta, double* C, int64_t ldc) {
+    return rocblas_entry<int64_t, double, decltype(&rocblas_dgemm_64)>("rocblas_dgemm_64", false, handle, transA, transB, m,
+                                                                       n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+}
+
+rocblas_status rocblas_zgemm(rocblas_handle handle, rocblas_operation transA, rocblas_operation transB, rocblas_int m,
+                             rocblas_int n, rocblas_int k, const rocblas_double_complex* alpha,
+                             const rocblas_double_complex* A, rocblas_int lda, const rocblas_double_complex* B,
+                             rocblas_int ldb, const rocblas_double_complex* beta, rocblas_double_complex* C,
+                             rocblas_int ldc) {
+    return rocblas_entry<rocblas_int, rocblas_double_complex, decltype(&rocblas_zgemm)>(
+        "rocblas_zgemm", true, handle, transA, transB, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+}
+
+rocblas_status rocblas_zgemm_64(rocblas_handle handle, rocblas_operation transA, rocblas_operation transB, int64_t m,
+                                int64_t n, int64_t k, const rocblas_double_complex* alpha, const rocblas_double_complex* A,
+                                int64_t lda, const rocblas_double_complex* B, int64_t ldb,
+                                const rocblas_double_complex* beta, rocblas_double_complex* C, int64_t ldc) {
+    return rocblas_entry<int64_t, rocblas_double_complex, decltype(&rocblas_zgemm_64)>(
+        "rocblas_zgemm_64", true, handle, transA, transB, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+}
+
+hipblasStatus_t hipblasDgemm(hipblasHandle_t handle, hipblasOperation_t transA, hipblasOperation_t transB, int m, int n,
+                             int k, const double* alpha, const double* AP, int lda, const double* BP, int ldb,
+                             const double* beta, double* CP, int ldc) {
+    return hipblas_entry<int, double, decltype(&hipblasDgemm)>("hipblasDgemm", false, handle, transA, transB, m, n, k, alpha,
+                                                               AP, lda, BP, ldb, beta, CP, ldc);
+}
+
+hipblasStatus_t hipblasDgemm_64(hipblasHandle_t handle, hipblasOperation_t transA, hipblasOperation_t transB, int64_t m,
+                                int64_t n, int64_t k, const double* alpha, const double* AP, int64_t lda, const double* BP,
+                                int64_t ldb, const double* beta, double* CP, int64_t ldc) {
+    return hipblas_entry<int64_t, double, decltype(&hipblasDgemm_64)>("hipblasDgemm_64", false, handle, transA, transB, m, n,
+                                                                      k, alpha, AP, lda, BP, ldb, beta, CP, ldc);
+}
+
+hipblasStatus_t hipblasZgemm(hipblasHandle_t handle, hipblasOperation_t transA, hipblasOperation_t transB, int m, int n,
+                             int k, const hipDoubleComplex* alpha, const hipDoubleComplex* AP, int lda,
+                             const hipDoubleComplex* BP, int ldb, const hipDoubleComplex* beta, hipDoubleComplex* CP,
+                             int ldc) {
+    return hipblas_entry<int, hipDoubleComplex, decltype(&hipblasZgemm)>("hipblasZgemm", true, handle, transA, transB, m, n,
+                                                                         k, alpha, AP, lda, BP, ldb, beta, CP, ldc);
+}
+
+hipblasStatus_t hipblasZgemm_64(hipblasHandle_t handle, hipblasOperation_t transA, hipblasOperation_t transB, int64_t m,
+                                int64_t n, int64_t k, const hipDoubleComplex* alpha, const hipDoubleComplex* AP,
+                                int64_t lda, const hipDoubleComplex* BP, int64_t ldb, const hipDoubleComplex* beta,
+                                hipDoubleComplex* CP, int64_t ldc) {
+    return hipblas_entry<int64_t, hipDoubleComplex, decltype(&hipblasZgemm_64)>(
+        "hipblasZgemm_64", true, handle, transA, transB, m, n, k, alpha, AP, lda, BP, ldb, beta, CP, ldc);
+}
+
+}  // extern "C"

@@ -11,7 +11,7 @@ from pathlib import Path
 
 _LIB_PATH = Path(__file__).resolve().parent / "libozimmu.so"
 
-OK = 0
+OK, ERR_BAD_DIM, ERR_BAD_LD, ERR_BAD_SLICES, ERR_NULL, ERR_WORKSPACE, ERR_HIP, ERR_NOT_IMPLEMENTED = range(8)
 MAX_SLICES = 16
 ROW_ALIGN = 256
 K_ALIGN = 128
@@ -23,7 +23,7 @@ EXPORTS = (
     "ozimmu_status_string", "ozimmu_slice_geometry", "ozimmu_slice_offset", "ozimmu_split_rows", "ozimmu_split_cols",
     "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_stage",
     "ozimmu_launch_plan", "ozimmu_dgemm_dd", "ozimmu_dgemm_blas", "ozimmu_zgemm_blas_workspace_bytes", "ozimmu_zgemm_blas",
-    "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices",
+    "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices", "ozimmu_auto_num_slices_blas",
     "ozimmu_probe_int8_mfma", "ozimmu_probe_lds_read",
 )
 
@@ -83,6 +83,9 @@ def lib() -> ctypes.CDLL:
         L.ozimmu_auto_num_slices.restype = i32
         L.ozimmu_auto_num_slices.argtypes = [i64, i64, i64, vp, i64, vp, i64, i32, ctypes.c_double, i32, vp, sz,
                                              ctypes.POINTER(i32), vp, vp]
+        L.ozimmu_auto_num_slices_blas.restype = i32
+        L.ozimmu_auto_num_slices_blas.argtypes = [ctypes.c_char, ctypes.c_char, i64, i64, i64, vp, i64, vp, i64, i32,
+                                                  ctypes.c_double, i32, vp, sz, ctypes.POINTER(i32), vp, vp]
         dp = ctypes.POINTER(ctypes.c_double)
         L.ozimmu_probe_int8_mfma.restype = i32
         L.ozimmu_probe_int8_mfma.argtypes = [i32, i32, dp, dp]
@@ -275,6 +278,24 @@ def auto_num_slices(A, B, threshold: float, max_slices: int = MAX_SLICES, scratc
     _check(lib().ozimmu_auto_num_slices(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), int(cplx), float(threshold),
                                         int(max_slices), _ptr(scratch), scratch.numel(), ctypes.byref(s),
                                         sums.ctypes.data, _stream(stream)))
+    return s.value, sums
+
+
+def auto_num_slices_blas(transa: str, transb: str, m: int, n: int, k: int, A, lda: int, B, ldb: int, is_complex: bool,
+                         threshold: float, max_slices: int = MAX_SLICES, scratch=None, stream=None):
+    """The same choice for column-major operands with transposes (see ozimmu.h); A and B are device
+    tensors used as raw storage. Returns (s, sums). Waits for the stream."""
+    import numpy as np
+    import torch
+
+    if scratch is None:
+        scratch = torch.empty(max(auto_scratch_bytes(max(m, n)), WORKSPACE_ALIGN), dtype=torch.uint8, device=A.device)
+    planes = 4 if is_complex else 2
+    sums = np.zeros((planes, MAX_SLICES), dtype=np.uint64)
+    s = ctypes.c_int()
+    _check(lib().ozimmu_auto_num_slices_blas(transa.encode()[:1], transb.encode()[:1], m, n, k, _ptr(A), lda, _ptr(B), ldb,
+                                             int(bool(is_complex)), float(threshold), int(max_slices), _ptr(scratch),
+                                             scratch.numel(), ctypes.byref(s), sums.ctypes.data, _stream(stream)))
     return s.value, sums
 
 

@@ -186,3 +186,37 @@ def test_binding_raises_typed_error():
     with pytest.raises(ozimmu.OzimmuError) as e:
         ozimmu.workspace_bytes(1, 1, 1, 0)
     assert e.value.code == 3
+
+
+def test_interposer_exports_the_vendor_gemm_symbols_and_blas_argument_errors():
+    """libozimmu_preload.so must define exactly the vendor entry points it stands in for (so the dynamic
+    loader binds a program's calls to it); host-side argument checks of the complex BLAS-style call."""
+    pre = Path(ozimmu.__file__).resolve().parent / "libozimmu_preload.so"
+    if not pre.exists():
+        pytest.skip("libozimmu_preload.so has not been built (python -m paper_2306_11975_amd.build)")
+    P = ctypes.CDLL(str(pre))
+    for name in ("rocblas_dgemm", "rocblas_zgemm", "rocblas_dgemm_64", "rocblas_zgemm_64", "hipblasDgemm",
+                 "hipblasZgemm", "hipblasDgemm_64", "hipblasZgemm_64"):
+        assert getattr(P, name) is not None
+
+    L = ozimmu.lib()
+    two = (ctypes.c_double * 2)(1.0, 0.0)
+    al, junk = ctypes.addressof(two), 4096   # junk: a non-null pointer that no check dereferences
+
+    def z(ta, tb, m, n, k, lda, ldb, ldc, s=4, alpha=al, beta=al, C=junk, ws=None, ws_bytes=0):
+        return L.ozimmu_zgemm_blas(ta, tb, m, n, k, alpha, junk, lda, junk, ldb, beta, C, ldc, s, ws, ws_bytes, None)
+
+    assert z(b"X", b"N", 4, 4, 4, 4, 4, 4) == ozimmu.ERR_BAD_DIM
+    assert z(b"N", b"N", -1, 4, 4, 4, 4, 4) == ozimmu.ERR_BAD_DIM
+    assert z(b"N", b"N", 4, 4, 4, 4, 4, 4, s=0) == ozimmu.ERR_BAD_SLICES
+    assert z(b"N", b"N", 5, 4, 3, 4, 3, 5) == ozimmu.ERR_BAD_LD        # lda < m
+    assert z(b"C", b"N", 5, 4, 3, 2, 3, 5) == ozimmu.ERR_BAD_LD        # lda < k for a transposed A
+    assert z(b"N", b"T", 5, 4, 3, 5, 3, 5) == ozimmu.ERR_BAD_LD        # ldb < n for a transposed B
+    assert z(b"N", b"N", 5, 4, 3, 5, 3, 4) == ozimmu.ERR_BAD_LD        # ldc < m
+    assert z(b"N", b"N", 5, 4, 3, 5, 3, 5, alpha=None) == ozimmu.ERR_NULL
+    assert z(b"N", b"N", 5, 4, 3, 5, 3, 5, C=None) == ozimmu.ERR_NULL
+    assert z(b"N", b"N", 0, 4, 3, 1, 3, 1, C=None) == ozimmu.OK        # empty result: nothing to do
+    assert z(b"N", b"N", 5, 4, 3, 5, 3, 5) == ozimmu.ERR_WORKSPACE     # product needed, no workspace
+    with_c = ozimmu.zgemm_blas_workspace_bytes(300, 200, 100, 8, False)
+    without = ozimmu.zgemm_blas_workspace_bytes(300, 200, 100, 8, True)
+    assert with_c - without >= 16 * 300 * 200 and without >= ozimmu.workspace_bytes(200, 300, 100, 8, True)

@@ -79,3 +79,31 @@ def test_auto_full_size_matches_oracle():
     A = wl.phi_matrix_device(4096, 4096, 1.0, 1003)
     B = wl.phi_matrix_device(4096, 4096, 1.0, 2003)
     check(A.cpu().numpy(), B.cpu().numpy(), thresholds=(0.0, 1.0), dA=A, dB=B)
+
+
+@pytest.mark.parametrize("ta", ["N", "T", "C"])
+@pytest.mark.parametrize("tb", ["N", "T"])
+@pytest.mark.parametrize("cplx", [False, True])
+def test_auto_for_column_major_operands_with_transposes(ta, tb, cplx):
+    """The BLAS-style variant must see the same groups (rows of op(A), columns of op(B)) whichever way
+    the operands are stored: sums and choice equal the oracle's on op(A), op(B)."""
+    m, n, k = 70, 300, 190
+    opA, opB = wl.phi_pair(m, n, k, 2.0, seed=21)
+    if cplx:
+        oA2, oB2 = wl.phi_pair(m, n, k, 0.5, seed=22)
+        opA, opB = opA + 1j * oA2, opB + 1j * oB2
+    A = {"N": opA, "T": opA.T, "C": opA.conj().T}[ta]
+    B = {"N": opB, "T": opB.T, "C": opB.conj().T}[tb]
+    lda, ldb = A.shape[0] + 3, B.shape[0] + 1
+
+    def col_major(M, ld):
+        buf = np.full((M.shape[1], ld), 1e300, dtype=M.dtype)   # padding rows would dominate every exponent if read
+        buf[:, :M.shape[0]] = M.T
+        return torch.from_numpy(buf).cuda()
+
+    dA, dB = col_major(A, lda), col_major(B, ldb)
+    for T in (0.0, 1.0, 6.0):
+        s_want, sums_want = oracle.auto_num_slices(opA, opB, T)
+        s_got, sums_got = ozimmu.auto_num_slices_blas(ta, tb, m, n, k, dA, lda, dB, ldb, cplx, T)
+        assert np.array_equal(sums_got, sums_want)
+        assert s_got == s_want

@@ -1,0 +1,126 @@
+"""Interception of the vendor DGEMM/ZGEMM calls (Section 4.4, third extension): an unmodified rocBLAS /
+hipBLAS program is started with libozimmu_preload.so first in the loader's preload list; its result
+must then be the Ozaki result, bit for bit the oracle's, and the vendor's own result when the
+interposer is told to pass calls through. The program is a child process: it reads the problem from a
+file and writes C back (csrc/blas_client.cpp)."""
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2306_11975_amd import ozimmu
+from paper_2306_11975_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+PKG = Path(ozimmu.__file__).resolve().parent
+CLIENT, PRELOAD = PKG / "blas_client", PKG / "libozimmu_preload.so"
+CODE = {"N": 0, "T": 1, "C": 2}
+
+
+def bits(x):
+    return np.ascontiguousarray(x).view(np.uint64)
+
+
+def run_client(tmp_path, api, ta, tb, alpha, beta, A, B, C0, mode, repeats=1, streams=1, extra_env=None):
+    """A, B, C0 as stored (column-major semantics are produced here). Returns (C, stderr)."""
+    if not CLIENT.exists() or not PRELOAD.exists():
+        pytest.skip("blas_client / libozimmu_preload.so have not been built (python -m paper_2306_11975_amd.build)")
+    cplx = np.iscomplexobj(C0)
+    dt = np.complex128 if cplx else np.float64
+    m, n = C0.shape
+    k = A.shape[0] if CODE[ta] else A.shape[1]
+    prob, res = tmp_path / "problem.bin", tmp_path / "result.bin"
+    with open(prob, "wb") as f:
+        np.array([api, int(cplx), CODE[ta], CODE[tb], m, n, k, repeats, streams], dtype=np.int64).tofile(f)
+        np.array([complex(alpha).real, complex(alpha).imag, complex(beta).real, complex(beta).imag]).tofile(f)
+        for M in (A, B, C0):
+            np.asfortranarray(M.astype(dt)).T.tofile(f)     # column-major bytes
+    env = dict(os.environ)
+    if mode is not None:
+        # first in the list; whatever the environment already preloads stays in place behind it
+        env["LD_PRELOAD"] = str(PRELOAD) + (":" + env["LD_PRELOAD"] if env.get("LD_PRELOAD") else "")
+        env["OZIMMU_MODE"] = mode
+        env["OZIMMU_VERBOSE"] = "1"
+    env.update(extra_env or {})
+    if res.exists():
+        res.unlink()
+    print(f"blas_client api={api} {ta}{tb} m={m} n={n} k={k} mode={mode}", flush=True)
+    p = subprocess.run([str(CLIENT), str(prob), str(res)], env=env, capture_output=True, text=True, timeout=100)
+    assert p.returncode == 0, p.stderr
+    C = np.fromfile(res, dtype=dt).reshape(n, m).T
+    return C, p.stderr
+
+
+def real_problem(ta, tb, m, n, k, seed):
+    opA, opB = wl.phi_pair(m, n, k, 1.0, seed)
+    A = opA.T.copy() if ta != "N" else opA
+    B = opB.T.copy() if tb != "N" else opB
+    C0 = np.random.default_rng(seed + 7).standard_normal((m, n))
+    return opA, opB, A, B, C0
+
+
+@pytest.mark.parametrize("api", [0, 1])
+def test_intercepted_dgemm_is_the_ozaki_result(tmp_path, api):
+    name = ("rocblas_dgemm", "hipblasDgemm")[api]
+    opA, opB, A, B, C0 = real_problem("T", "N", 150, 90, 260, seed=5)
+    alpha, beta = 1.5, -0.25
+    got, log = run_client(tmp_path, api, "T", "N", alpha, beta, A, B, C0, mode="9")
+    want = oracle.dgemm_blas(True, False, alpha, A, B, beta, C0, 9)
+    assert np.array_equal(bits(got), bits(want))
+    assert f"[ozimmu] {name} TN m=150 n=90 k=260 slices=9" in log
+
+    # automatic slice count, lossless split: the count the oracle picks for op(A), op(B)
+    s_auto = oracle.auto_num_slices(opA, opB, 0.0)[0]
+    got, log = run_client(tmp_path, api, "T", "N", 1.0, 0.0, A, B, C0, mode="auto")
+    assert f"slices={s_auto} (auto)" in log
+    assert np.array_equal(bits(got), bits(oracle.dgemm_blas(True, False, 1.0, A, B, 0.0, C0, s_auto)))
+    # ... and with one bit of average loss admitted
+    s_t1 = oracle.auto_num_slices(opA, opB, 1.0)[0]
+    assert s_t1 < s_auto
+    got, log = run_client(tmp_path, api, "T", "N", 1.0, 0.0, A, B, C0, mode="auto", extra_env={"OZIMMU_THRESHOLD": "1"})
+    assert f"slices={s_t1} (auto)" in log
+    assert np.array_equal(bits(got), bits(oracle.dgemm_blas(True, False, 1.0, A, B, 0.0, C0, s_t1)))
+
+
+def test_vendor_mode_and_no_preload_give_the_vendor_result(tmp_path):
+    opA, opB, A, B, C0 = real_problem("N", "T", 64, 130, 200, seed=6)
+    plain, _ = run_client(tmp_path, 0, "N", "T", 2.0, 1.0, A, B, C0, mode=None)
+    through, log = run_client(tmp_path, 0, "N", "T", 2.0, 1.0, A, B, C0, mode="vendor")
+    assert np.array_equal(bits(plain), bits(through))
+    assert "rocblas_dgemm -> vendor" in log and "slices=" not in log
+    ref = 2.0 * (opA @ opB) + C0
+    assert np.allclose(plain, ref, rtol=1e-11, atol=1e-11)
+    # small calls can be left to the vendor
+    small, log = run_client(tmp_path, 0, "N", "T", 2.0, 1.0, A, B, C0, mode="8", extra_env={"OZIMMU_MIN_WORK": "1e9"})
+    assert "-> vendor" in log and np.array_equal(bits(small), bits(plain))
+
+
+@pytest.mark.parametrize("api", [0, 1])
+def test_intercepted_zgemm_is_the_ozaki_result(tmp_path, api):
+    rng = np.random.default_rng(11)
+    m, n, k = 100, 140, 300
+    opA = rng.standard_normal((m, k)) + 1j * rng.standard_normal((m, k))
+    opB = rng.standard_normal((k, n)) + 1j * rng.standard_normal((k, n))
+    C0 = rng.standard_normal((m, n)) + 1j * rng.standard_normal((m, n))
+    A, B = opA.conj().T.copy(), opB
+    alpha, beta = 0.5 - 1.25j, 0.75 + 0.5j
+    got, log = run_client(tmp_path, api, "C", "N", alpha, beta, A, B, C0, mode="7")
+    assert np.array_equal(bits(got), bits(oracle.zgemm_blas("C", "N", alpha, A, B, beta, C0, 7)))
+    assert ("rocblas_zgemm", "hipblasZgemm")[api] + " CN" in log
+    s_auto = oracle.auto_num_slices(opA, opB, 0.0)[0]
+    got, log = run_client(tmp_path, api, "C", "N", 1.0, 0.0, A, B, C0, mode="auto")
+    assert f"slices={s_auto} (auto)" in log
+    assert np.array_equal(bits(got), bits(oracle.zgemm_blas("C", "N", 1.0, A, B, 0.0, C0, s_auto)))
+
+
+def test_repeated_calls_on_several_streams_share_the_workspace_safely(tmp_path):
+    """Six calls round-robin over three streams: the interposer orders them on the device (they share one
+    workspace), so the result is that of a single call."""
+    opA, opB, A, B, C0 = real_problem("N", "N", 520, 300, 1100, seed=8)
+    got, log = run_client(tmp_path, 0, "N", "N", 1.0, 0.0, A, B, C0, mode="6", repeats=6, streams=3)
+    assert log.count("slices=6") == 6
+    assert np.array_equal(bits(got), bits(oracle.dgemm_blas(False, False, 1.0, A, B, 0.0, C0, 6)))
