@@ -5,10 +5,12 @@
 //
 //   LD_PRELOAD=/path/to/libozimmu_preload.so  program ...
 //
-// Intercepted: rocblas_dgemm, rocblas_zgemm, hipblasDgemm, hipblasZgemm and their _64 forms. A call
+// Intercepted: rocblas_dgemm, rocblas_zgemm, hipblasDgemm, hipblasZgemm, their _64 forms and their
+// strided-batched forms (computed member by member). A call
 // is computed here when the handle is in host pointer mode (alpha and beta readable on the host) and
 // the library accepts the arguments; every other call, and every call in vendor mode, goes on to the
-// vendor's routine found with dlsym(RTLD_NEXT, ...), which then also reports argument errors.
+// vendor's routine (found behind this library in the global scope, or in the loaded vendor library
+// if the host keeps it in a local scope), which then also reports argument errors.
 //
 // Environment (read once, at the first intercepted call):
 //   OZIMMU_MODE       "auto" (default): slice count chosen per call from the operands;
@@ -24,6 +26,7 @@
 // shared workspace is never used by two products at once. In "auto" mode each call waits for its
 // stream once (the slice count comes back to the host).
 #include <dlfcn.h>
+#include <link.h>
 
 #include <algorithm>
 #include <cstdint>
@@ -74,18 +77,34 @@ const Config& config() {
     return cfg;
 }
 
-template <class F>
-F vendor(const char* name) {
-    F f = reinterpret_cast<F>(dlsym(RTLD_NEXT, name));
-    if (!f) {
-        std::fprintf(stderr, "[ozimmu] %s: the vendor library is not loaded after this one\n", name);
-        std::abort();
+// A symbol of the vendor library this interposer stands in front of. A program linked against the
+// vendor library has it in the global scope behind this one (RTLD_NEXT finds it); a host that loaded
+// it into a local scope (a Python extension module, a plugin) has not, so the loaded objects are
+// searched for the library by name and the symbol is taken from that object. nullptr if absent.
+struct FindObject {
+    const char* part;
+    void* handle;
+};
+int find_object(struct dl_phdr_info* info, size_t, void* data) {
+    FindObject* f = static_cast<FindObject*>(data);
+    if (info->dlpi_name && std::strstr(info->dlpi_name, f->part) && !std::strstr(info->dlpi_name, "ozimmu")) {
+        f->handle = dlopen(info->dlpi_name, RTLD_NOLOAD | RTLD_LAZY);   // already loaded: only a handle to it
+        return f->handle != nullptr;
     }
+    return 0;
+}
+void* vendor_symbol(const char* library_part, const char* name) {
+    if (void* f = dlsym(RTLD_NEXT, name)) return f;
+    FindObject probe{library_part, nullptr};
+    dl_iterate_phdr(find_object, &probe);
+    return probe.handle ? dlsym(probe.handle, name) : nullptr;
+}
+template <class F>
+F vendor(const char* library_part, const char* name) {
+    F f = reinterpret_cast<F>(vendor_symbol(library_part, name));
+    if (!f) std::fprintf(stderr, "[ozimmu] %s: no vendor library with this symbol is loaded\n", name);
     return f;
 }
-
-template <class F>
-F helper(const char* name) { return reinterpret_cast<F>(dlsym(RTLD_DEFAULT, name)); }
 
 // ---- per-device workspace -------------------------------------------------------------------
 constexpr int kMaxDevices = 64;
@@ -199,8 +218,8 @@ char op_letter(int op) { return op == 111 ? 'N' : op == 112 ? 'T' : op == 113 ? 
 bool rocblas_context(rocblas_handle handle, hipStream_t* stream) {
     using get_stream_t = rocblas_status (*)(rocblas_handle, hipStream_t*);
     using get_mode_t = rocblas_status (*)(rocblas_handle, rocblas_pointer_mode*);
-    static const get_stream_t get_stream = helper<get_stream_t>("rocblas_get_stream");
-    static const get_mode_t get_mode = helper<get_mode_t>("rocblas_get_pointer_mode");
+    static const get_stream_t get_stream = reinterpret_cast<get_stream_t>(vendor_symbol("librocblas.so", "rocblas_get_stream"));
+    static const get_mode_t get_mode = reinterpret_cast<get_mode_t>(vendor_symbol("librocblas.so", "rocblas_get_pointer_mode"));
     rocblas_pointer_mode mode;
     return handle && get_stream && get_mode && get_mode(handle, &mode) == rocblas_status_success &&
            mode == rocblas_pointer_mode_host && get_stream(handle, stream) == rocblas_status_success;
@@ -219,7 +238,8 @@ rocblas_status rocblas_entry(const char* name, bool cplx, rocblas_handle handle,
         if (compute(c, stream)) return rocblas_status_success;
     }
     note_passthrough(name);
-    static const F next = vendor<F>(name);
+    static const F next = vendor<F>("librocblas.so", name);
+    if (!next) return rocblas_status_internal_error;
     return next(handle, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
 }
 
@@ -227,8 +247,8 @@ rocblas_status rocblas_entry(const char* name, bool cplx, rocblas_handle handle,
 bool hipblas_context(hipblasHandle_t handle, hipStream_t* stream) {
     using get_stream_t = hipblasStatus_t (*)(hipblasHandle_t, hipStream_t*);
     using get_mode_t = hipblasStatus_t (*)(hipblasHandle_t, hipblasPointerMode_t*);
-    static const get_stream_t get_stream = helper<get_stream_t>("hipblasGetStream");
-    static const get_mode_t get_mode = helper<get_mode_t>("hipblasGetPointerMode");
+    static const get_stream_t get_stream = reinterpret_cast<get_stream_t>(vendor_symbol("libhipblas.so", "hipblasGetStream"));
+    static const get_mode_t get_mode = reinterpret_cast<get_mode_t>(vendor_symbol("libhipblas.so", "hipblasGetPointerMode"));
     hipblasPointerMode_t mode;
     return handle && get_stream && get_mode && get_mode(handle, &mode) == HIPBLAS_STATUS_SUCCESS &&
            mode == HIPBLAS_POINTER_MODE_HOST && get_stream(handle, stream) == HIPBLAS_STATUS_SUCCESS;
@@ -247,8 +267,70 @@ hipblasStatus_t hipblas_entry(const char* name, bool cplx, hipblasHandle_t handl
         if (compute(c, stream)) return HIPBLAS_STATUS_SUCCESS;
     }
     note_passthrough(name);
-    static const F next = vendor<F>(name);
+    static const F next = vendor<F>("libhipblas.so", name);
+    if (!next) return HIPBLAS_STATUS_INTERNAL_ERROR;
     return next(handle, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc);
+}
+
+// Strided-batched forms: the members are computed one after the other with the same workspace. If a
+// member cannot be computed the whole call goes to the vendor; that is only safe while C is unchanged,
+// i.e. at the first member or with beta == 0 (C is then overwritten anyway).
+template <class Stride>
+int compute_batched(Call c, hipStream_t stream, Stride sa, Stride sb, Stride sc, int64_t batch) {   // 1 done, 0 vendor, -1 error
+    if (batch <= 0) return 0;
+    const int w = c.cplx ? 2 : 1;
+    const bool beta_zero = c.beta && c.beta[0] == 0.0 && (!c.cplx || c.beta[1] == 0.0);
+    const double *A0 = c.A, *B0 = c.B;
+    double* C0 = c.C;
+    for (int64_t i = 0; i < batch; ++i) {
+        c.A = A0 + (int64_t)sa * i * w;
+        c.B = B0 + (int64_t)sb * i * w;
+        c.C = C0 + (int64_t)sc * i * w;
+        if (!compute(c, stream)) return (i == 0 || beta_zero) ? 0 : -1;
+    }
+    return 1;
+}
+
+template <class Int, class Stride, class T, class F>
+rocblas_status rocblas_batched_entry(const char* name, bool cplx, rocblas_handle handle, rocblas_operation ta,
+                                     rocblas_operation tb, Int m, Int n, Int k, const T* alpha, const T* A, Int lda,
+                                     Stride sa, const T* B, Int ldb, Stride sb, const T* beta, T* C, Int ldc, Stride sc,
+                                     Int batch) {
+    hipStream_t stream = nullptr;
+    if (config().slices >= 0 && rocblas_context(handle, &stream)) {
+        const Call c{name, cplx, op_letter((int)ta), op_letter((int)tb), (int64_t)m, (int64_t)n, (int64_t)k,
+                     reinterpret_cast<const double*>(alpha), reinterpret_cast<const double*>(A), (int64_t)lda,
+                     reinterpret_cast<const double*>(B), (int64_t)ldb, reinterpret_cast<const double*>(beta),
+                     reinterpret_cast<double*>(C), (int64_t)ldc};
+        const int rc = compute_batched(c, stream, sa, sb, sc, (int64_t)batch);
+        if (rc > 0) return rocblas_status_success;
+        if (rc < 0) return rocblas_status_internal_error;
+    }
+    note_passthrough(name);
+    static const F next = vendor<F>("librocblas.so", name);
+    if (!next) return rocblas_status_internal_error;
+    return next(handle, ta, tb, m, n, k, alpha, A, lda, sa, B, ldb, sb, beta, C, ldc, sc, batch);
+}
+
+template <class Int, class Stride, class T, class F>
+hipblasStatus_t hipblas_batched_entry(const char* name, bool cplx, hipblasHandle_t handle, hipblasOperation_t ta,
+                                      hipblasOperation_t tb, Int m, Int n, Int k, const T* alpha, const T* A, Int lda,
+                                      Stride sa, const T* B, Int ldb, Stride sb, const T* beta, T* C, Int ldc, Stride sc,
+                                      Int batch) {
+    hipStream_t stream = nullptr;
+    if (config().slices >= 0 && hipblas_context(handle, &stream)) {
+        const Call c{name, cplx, op_letter((int)ta), op_letter((int)tb), (int64_t)m, (int64_t)n, (int64_t)k,
+                     reinterpret_cast<const double*>(alpha), reinterpret_cast<const double*>(A), (int64_t)lda,
+                     reinterpret_cast<const double*>(B), (int64_t)ldb, reinterpret_cast<const double*>(beta),
+                     reinterpret_cast<double*>(C), (int64_t)ldc};
+        const int rc = compute_batched(c, stream, sa, sb, sc, (int64_t)batch);
+        if (rc > 0) return HIPBLAS_STATUS_SUCCESS;
+        if (rc < 0) return HIPBLAS_STATUS_INTERNAL_ERROR;
+    }
+    note_passthrough(name);
+    static const F next = vendor<F>("libhipblas.so", name);
+    if (!next) return HIPBLAS_STATUS_INTERNAL_ERROR;
+    return next(handle, ta, tb, m, n, k, alpha, A, lda, sa, B, ldb, sb, beta, C, ldc, sc, batch);
 }
 
 }  // namespace
@@ -314,6 +396,48 @@ hipblasStatus_t hipblasZgemm_64(hipblasHandle_t handle, hipblasOperation_t trans
                                 hipDoubleComplex* CP, int64_t ldc) {
     return hipblas_entry<int64_t, hipDoubleComplex, decltype(&hipblasZgemm_64)>(
         "hipblasZgemm_64", true, handle, transA, transB, m, n, k, alpha, AP, lda, BP, ldb, beta, CP, ldc);
+}
+
+rocblas_status rocblas_dgemm_strided_batched(rocblas_handle handle, rocblas_operation transA, rocblas_operation transB,
+                                             rocblas_int m, rocblas_int n, rocblas_int k, const double* alpha,
+                                             const double* A, rocblas_int lda, rocblas_stride stride_a, const double* B,
+                                             rocblas_int ldb, rocblas_stride stride_b, const double* beta, double* C,
+                                             rocblas_int ldc, rocblas_stride stride_c, rocblas_int batch_count) {
+    return rocblas_batched_entry<rocblas_int, rocblas_stride, double, decltype(&rocblas_dgemm_strided_batched)>(
+        "rocblas_dgemm_strided_batched", false, handle, transA, transB, m, n, k, alpha, A, lda, stride_a, B, ldb, stride_b,
+        beta, C, ldc, stride_c, batch_count);
+}
+
+rocblas_status rocblas_zgemm_strided_batched(rocblas_handle handle, rocblas_operation transA, rocblas_operation transB,
+                                             rocblas_int m, rocblas_int n, rocblas_int k,
+                                             const rocblas_double_complex* alpha, const rocblas_double_complex* A,
+                                             rocblas_int lda, rocblas_stride stride_a, const rocblas_double_complex* B,
+                                             rocblas_int ldb, rocblas_stride stride_b, const rocblas_double_complex* beta,
+                                             rocblas_double_complex* C, rocblas_int ldc, rocblas_stride stride_c,
+                                             rocblas_int batch_count) {
+    return rocblas_batched_entry<rocblas_int, rocblas_stride, rocblas_double_complex,
+                                 decltype(&rocblas_zgemm_strided_batched)>(
+        "rocblas_zgemm_strided_batched", true, handle, transA, transB, m, n, k, alpha, A, lda, stride_a, B, ldb, stride_b,
+        beta, C, ldc, stride_c, batch_count);
+}
+
+hipblasStatus_t hipblasDgemmStridedBatched(hipblasHandle_t handle, hipblasOperation_t transA, hipblasOperation_t transB,
+                                           int m, int n, int k, const double* alpha, const double* AP, int lda,
+                                           long long strideA, const double* BP, int ldb, long long strideB,
+                                           const double* beta, double* CP, int ldc, long long strideC, int batchCount) {
+    return hipblas_batched_entry<int, long long, double, decltype(&hipblasDgemmStridedBatched)>(
+        "hipblasDgemmStridedBatched", false, handle, transA, transB, m, n, k, alpha, AP, lda, strideA, BP, ldb, strideB,
+        beta, CP, ldc, strideC, batchCount);
+}
+
+hipblasStatus_t hipblasZgemmStridedBatched(hipblasHandle_t handle, hipblasOperation_t transA, hipblasOperation_t transB,
+                                           int m, int n, int k, const hipDoubleComplex* alpha, const hipDoubleComplex* AP,
+                                           int lda, long long strideA, const hipDoubleComplex* BP, int ldb,
+                                           long long strideB, const hipDoubleComplex* beta, hipDoubleComplex* CP, int ldc,
+                                           long long strideC, int batchCount) {
+    return hipblas_batched_entry<int, long long, hipDoubleComplex, decltype(&hipblasZgemmStridedBatched)>(
+        "hipblasZgemmStridedBatched", true, handle, transA, transB, m, n, k, alpha, AP, lda, strideA, BP, ldb, strideB,
+        beta, CP, ldc, strideC, batchCount);
 }
 
 }  // extern "C"

@@ -196,7 +196,8 @@ def test_interposer_exports_the_vendor_gemm_symbols_and_blas_argument_errors():
         pytest.skip("libozimmu_preload.so has not been built (python -m paper_2306_11975_amd.build)")
     P = ctypes.CDLL(str(pre))
     for name in ("rocblas_dgemm", "rocblas_zgemm", "rocblas_dgemm_64", "rocblas_zgemm_64", "hipblasDgemm",
-                 "hipblasZgemm", "hipblasDgemm_64", "hipblasZgemm_64"):
+                 "hipblasZgemm", "hipblasDgemm_64", "hipblasZgemm_64", "rocblas_dgemm_strided_batched",
+                 "rocblas_zgemm_strided_batched", "hipblasDgemmStridedBatched", "hipblasZgemmStridedBatched"):
         assert getattr(P, name) is not None
 
     L = ozimmu.lib()

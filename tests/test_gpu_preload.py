@@ -124,3 +124,56 @@ def test_repeated_calls_on_several_streams_share_the_workspace_safely(tmp_path):
     got, log = run_client(tmp_path, 0, "N", "N", 1.0, 0.0, A, B, C0, mode="6", repeats=6, streams=3)
     assert log.count("slices=6") == 6
     assert np.array_equal(bits(got), bits(oracle.dgemm_blas(False, False, 1.0, A, B, 0.0, C0, 6)))
+
+
+TORCH_CHILD = r'''
+import sys
+import numpy as np
+import torch
+d = np.load(sys.argv[1])
+dev = lambda a: torch.from_numpy(a).cuda()
+A, B, M, Za, Zb = (dev(d[k]) for k in ("A", "B", "M", "Za", "Zb"))
+out = {}
+out["mm"] = torch.mm(A, B)
+out["mm_t"] = torch.mm(B.t(), A.t())
+out["addmm"] = torch.addmm(M, A, B, beta=0.5, alpha=-1.75)
+out["zmm"] = Za @ Zb
+out["zmm_h"] = Zb.conj().t() @ Za.conj().t()
+out["bmm"] = torch.bmm(torch.stack([A, 2 * A, -A]), torch.stack([B, B, 3 * B]))
+torch.cuda.synchronize()
+np.savez(sys.argv[2], **{k: v.cpu().numpy() for k, v in out.items()})
+'''
+
+
+def test_pytorch_fp64_matmul_is_intercepted(tmp_path):
+    """PyTorch's FP64 and complex128 matmul on the GPU reach the vendor library through hipblasDgemm /
+    hipblasZgemm (and the strided-batched form for bmm), loaded into a local scope by the extension
+    module: started under the preload list an unmodified script computes the Ozaki products."""
+    import sys
+
+    if not PRELOAD.exists():
+        pytest.skip("libozimmu_preload.so has not been built (python -m paper_2306_11975_amd.build)")
+    rng = np.random.default_rng(31)
+    A, B = wl.phi_pair(200, 150, 330, 1.0, seed=12)
+    M = rng.standard_normal((200, 150))
+    Za = rng.standard_normal((70, 90)) + 1j * rng.standard_normal((70, 90))
+    Zb = rng.standard_normal((90, 40)) + 1j * rng.standard_normal((90, 40))
+    np.savez(tmp_path / "in.npz", A=A, B=B, M=M, Za=Za, Zb=Zb)
+    env = dict(os.environ)
+    env["LD_PRELOAD"] = str(PRELOAD) + (":" + env["LD_PRELOAD"] if env.get("LD_PRELOAD") else "")
+    env.update(OZIMMU_MODE="8", OZIMMU_VERBOSE="1")
+    print("python child under the preload list", flush=True)
+    p = subprocess.run([sys.executable, "-c", TORCH_CHILD, str(tmp_path / "in.npz"), str(tmp_path / "out.npz")], env=env,
+                       capture_output=True, text=True, timeout=110)
+    assert p.returncode == 0, p.stderr[-2000:]
+    got = np.load(tmp_path / "out.npz")
+    assert p.stderr.count("hipblasDgemm ") >= 3 and p.stderr.count("hipblasZgemm ") >= 2, p.stderr[-2000:]
+    assert "hipblasDgemmStridedBatched" in p.stderr and "-> vendor" not in p.stderr
+    s = 8
+    assert np.array_equal(bits(got["mm"]), bits(oracle.dgemm(A, B, s)))
+    assert np.array_equal(bits(got["mm_t"]), bits(oracle.dgemm(B.T.copy(), A.T.copy(), s)))
+    assert np.array_equal(bits(got["addmm"]), bits(oracle.dgemm_blas(False, False, -1.75, A, B, 0.5, M, s)))
+    assert np.array_equal(bits(got["zmm"]), bits(oracle.zgemm(Za, Zb, s)))
+    assert np.array_equal(bits(got["zmm_h"]), bits(oracle.zgemm(Zb.conj().T.copy(), Za.conj().T.copy(), s)))
+    for i, (fa, fb) in enumerate(((1, 1), (2, 1), (-1, 3))):
+        assert np.array_equal(bits(got["bmm"][i]), bits(oracle.dgemm(fa * A, fb * B, s)))
