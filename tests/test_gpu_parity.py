@@ -188,6 +188,27 @@ def test_dgemm_ragged_shapes_bit_exact(m, n, k, s, phi, seed):
     assert np.array_equal(bits(gpu_dgemm(A, B, s, ldc_extra=5)), bits(oracle.dgemm(A, B, s)))
 
 
+def random_shapes(count, seed, budget=1.5e9):
+    """Seeded shapes and slice counts, ragged on purpose, with the oracle's work (pairs * m * n * k) bounded."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        s = int(rng.integers(1, 17))
+        m, n = int(rng.integers(1, 700)), int(rng.integers(1, 700))
+        k = int(rng.choice([rng.integers(1, 200), rng.integers(200, 1100), rng.integers(1100, 6000)]))
+        if s * (s + 1) // 2 * m * n * k <= budget:
+            out.append((m, n, k, s, float(rng.choice([0.5, 1.0, 2.0, 4.0]))))
+    return out
+
+
+@pytest.mark.parametrize("case", range(20))
+def test_dgemm_seeded_random_shapes_bit_exact(case):
+    m, n, k, s, phi = random_shapes(20, seed=2024)[case]
+    print(f"m={m} n={n} k={k} s={s} phi={phi}", flush=True)
+    A, B = wl.phi_pair(m, n, k, phi, seed=100 + case)
+    assert np.array_equal(bits(gpu_dgemm(A, B, s, ldc_extra=case % 3)), bits(oracle.dgemm(A, B, s)))
+
+
 @pytest.mark.parametrize("phi", [0.5, 1.0, 2.0])
 def test_config2_1024_cubed_bit_exact_and_accuracy(phi):
     A, B = wl.phi_pair(1024, 1024, 1024, phi, seed=2)
