@@ -221,3 +221,16 @@ def test_interposer_exports_the_vendor_gemm_symbols_and_blas_argument_errors():
     with_c = ozimmu.zgemm_blas_workspace_bytes(300, 200, 100, 8, False)
     without = ozimmu.zgemm_blas_workspace_bytes(300, 200, 100, 8, True)
     assert with_c - without >= 16 * 300 * 200 and without >= ozimmu.workspace_bytes(200, 300, 100, 8, True)
+
+
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 with no C++ or HIP types in it."""
+    import shutil
+    import subprocess
+
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", str(HEADER)],
+                         capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
