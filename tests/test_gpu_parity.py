@@ -209,6 +209,15 @@ def test_dgemm_seeded_random_shapes_bit_exact(case):
     assert np.array_equal(bits(gpu_dgemm(A, B, s, ldc_extra=case % 3)), bits(oracle.dgemm(A, B, s)))
 
 
+@pytest.mark.parametrize("m,n,k,s", [(300000, 2, 3, 8), (2, 300000, 3, 8), (3, 2, 200000, 8), (70000, 3, 1500, 4),
+                                     (1, 1, 140000, 16)])
+def test_dgemm_extreme_aspect_ratios_bit_exact(m, n, k, s):
+    """Thousands of tiles along one dimension and a single ragged one along the other; very long k with a
+    handful of outputs (INT64 diagonal sums)."""
+    A, B = wl.phi_pair(m, n, k, 1.0, seed=41)
+    assert np.array_equal(bits(gpu_dgemm(A, B, s)), bits(oracle.dgemm(A, B, s)))
+
+
 @pytest.mark.parametrize("phi", [0.5, 1.0, 2.0])
 def test_config2_1024_cubed_bit_exact_and_accuracy(phi):
     A, B = wl.phi_pair(1024, 1024, 1024, phi, seed=2)
