@@ -218,6 +218,15 @@ def test_dgemm_extreme_aspect_ratios_bit_exact(m, n, k, s):
     assert np.array_equal(bits(gpu_dgemm(A, B, s)), bits(oracle.dgemm(A, B, s)))
 
 
+@pytest.mark.parametrize("m,n,k", [(4194304, 1, 1), (1, 4194304, 2), (1, 2, 4194304)])
+def test_dgemm_at_the_largest_accepted_dimension(m, n, k):
+    """OZIMMU_MAX_DIM = 2^22 in each position (16384 tiles along m or n; 65536 k-steps in one INT64-summed walk)."""
+    s = 3
+    print(f"m={m} n={n} k={k}", flush=True)
+    A, B = wl.phi_pair(m, n, k, 1.0, seed=43)
+    assert np.array_equal(bits(gpu_dgemm(A, B, s)), bits(oracle.dgemm(A, B, s)))
+
+
 @pytest.mark.parametrize("phi", [0.5, 1.0, 2.0])
 def test_config2_1024_cubed_bit_exact_and_accuracy(phi):
     A, B = wl.phi_pair(1024, 1024, 1024, phi, seed=2)
