@@ -14,7 +14,7 @@
 //
 // Environment (read once, at the first intercepted call):
 //   OZIMMU_MODE       "auto" (default): slice count chosen per call from the operands;
-//                     "3" .. "16": that many slices; "vendor": pass everything through.
+//                     "1" .. "16": that many slices; "vendor": pass everything through.
 //   OZIMMU_THRESHOLD  admitted average mantissa loss in bits for "auto" (default 0: lossless split).
 //   OZIMMU_MIN_WORK   calls with m*n*k below this go to the vendor (default 0: none do).
 //   OZIMMU_VERBOSE    "1": one line per intercepted call on stderr.
@@ -60,9 +60,9 @@ const Config& config() {
             else {
                 char* end = nullptr;
                 const long s = std::strtol(v, &end, 10);
-                if (*end == 0 && s >= 3 && s <= OZIMMU_MAX_SLICES) cfg.slices = (int)s;
+                if (*end == 0 && s >= 1 && s <= OZIMMU_MAX_SLICES) cfg.slices = (int)s;
                 else {
-                    std::fprintf(stderr, "[ozimmu] OZIMMU_MODE=%s not understood (auto, vendor, 3..%d): using auto\n", v,
+                    std::fprintf(stderr, "[ozimmu] OZIMMU_MODE=%s not understood (auto, vendor, 1..%d): using auto\n", v,
                                  OZIMMU_MAX_SLICES);
                 }
             }
