@@ -177,3 +177,68 @@ def test_pytorch_fp64_matmul_is_intercepted(tmp_path):
     assert np.array_equal(bits(got["zmm_h"]), bits(oracle.zgemm(Zb.conj().T.copy(), Za.conj().T.copy(), s)))
     for i, (fa, fb) in enumerate(((1, 1), (2, 1), (-1, 3))):
         assert np.array_equal(bits(got["bmm"][i]), bits(oracle.dgemm(fa * A, fb * B, s)))
+
+
+SIMULATOR = r'''
+# a plain PyTorch state-vector simulator: brickwork circuit of Haar-random d-qubit gates, every gate one
+# complex128 matmul of the reshaped state with the gate matrix (knows nothing about ozimmu)
+import sys
+import numpy as np
+import torch
+N, d, layers = 16, 6, 4
+gen = torch.Generator().manual_seed(11)
+
+def random_unitary(dim):
+    g = torch.complex(torch.randn((dim, dim), generator=gen, dtype=torch.float64),
+                      torch.randn((dim, dim), generator=gen, dtype=torch.float64))
+    q, r = torch.linalg.qr(g)
+    return q * (torch.diagonal(r) / torch.diagonal(r).abs())
+
+state = torch.zeros(2 ** N, dtype=torch.complex128, device="cuda")
+state[0] = 1.0
+for layer in range(layers):
+    offset = (d // 2) * (layer % 2)
+    for first in range(offset, N - d + 1, d):
+        U = random_unitary(2 ** d).cuda()
+        axes = list(range(first, first + d))
+        rest = [a for a in range(N) if a not in axes]
+        M = state.reshape([2] * N).permute(rest + axes).reshape(2 ** (N - d), 2 ** d).contiguous()
+        out = torch.matmul(M, U.T.contiguous())
+        state = out.reshape([2] * N).permute(np.argsort(rest + axes).tolist()).reshape(-1).contiguous()
+torch.cuda.synchronize()
+np.save(sys.argv[1], state.cpu().numpy())
+'''
+
+
+def test_unmodified_simulator_under_the_preload_list(tmp_path):
+    """The use the paper reports (Section 4.4): a state-vector simulator that calls the vendor ZGEMM is run
+    unchanged, once as it is and once with the interposer in automatic mode at thresholds 0 and 1."""
+    import re
+    import sys
+
+    if not PRELOAD.exists():
+        pytest.skip("libozimmu_preload.so has not been built (python -m paper_2306_11975_amd.build)")
+
+    def run(mode, threshold=None):
+        env = dict(os.environ)
+        if mode is not None:
+            env["LD_PRELOAD"] = str(PRELOAD) + (":" + env["LD_PRELOAD"] if env.get("LD_PRELOAD") else "")
+            env.update(OZIMMU_MODE=mode, OZIMMU_VERBOSE="1")
+            if threshold is not None:
+                env["OZIMMU_THRESHOLD"] = str(threshold)
+        out = tmp_path / f"state_{mode}_{threshold}.npy"
+        print(f"simulator child, mode={mode} threshold={threshold}", flush=True)
+        p = subprocess.run([sys.executable, "-c", SIMULATOR, str(out)], env=env, capture_output=True, text=True, timeout=110)
+        assert p.returncode == 0, p.stderr[-2000:]
+        return np.load(out), p.stderr
+
+    ref, _ = run(None)
+    assert abs(np.linalg.norm(ref) - 1.0) <= 1e-12
+    for threshold, tol, lo, hi in ((0, 5e-14, 9, 16), (1, 5e-13, 3, 10)):
+        got, log = run("auto", threshold)
+        picked = [int(x) for x in re.findall(r"hipblasZgemm \S+ m=\d+ n=\d+ k=\d+ slices=(\d+) \(auto\)", log)]
+        assert len(picked) == 8, log[-1500:]             # 4 layers of 2 gates
+        assert lo <= max(picked) <= hi
+        assert abs(np.linalg.norm(got) - 1.0) <= 1e-12
+        assert np.max(np.abs(got - ref)) <= tol * 50 * np.max(np.abs(ref))
+        assert abs(got[0] - ref[0]) <= tol * 50 * abs(ref[0]) + 1e-16     # the amplitude the paper compares
