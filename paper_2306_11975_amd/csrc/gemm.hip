@@ -15,14 +15,14 @@
 // global -> LDS directly (global_load_lds_dwordx4, no staging registers; the slice tensors are
 // stored as ready-made LDS images, so every load is a linear run of full 128-byte lines, which
 // keeps the number of requests the vector L1 must track per byte at its minimum) into one of
-// kStages LDS buffers, kStages - 1 steps ahead of the matrix cores, so that an L2 miss has
+// kStages LDS buffers, kStages steps ahead of the matrix cores, so that an L2 miss has
 // several step times to arrive; LDS -> registers with 16-byte reads, XOR-swizzled so that the
 // 16 lanes the LDS serves per clock hit 16 distinct bank groups; registers ->
 // v_mfma_i32_32x32x32_i8.
 // Each wavefront computes 128 x 64 outputs as 4 x 2 MFMA tiles (128 accumulator registers), so
-// that two wavefronts fit on a SIMD. The two take turns: one issues the MFMAs of a 32-wide
-// k-slab from fragments it holds in registers while the other reads its next fragments and
-// issues its direct loads (four phases and four barriers per step, see the main loop).
+// that two wavefronts fit on a SIMD. The two take turns: one issues the 16 MFMAs of a step
+// from fragments it holds in registers while the other reads its next fragments and issues
+// its direct loads (two phases and two barriers per step, see the main loop).
 #include "ozimmu_internal.h"
 
 #include "mfma_common.h"
@@ -48,7 +48,6 @@ constexpr int kLoadsPerOperand = kWaveShare / 1024;   // wave-wide 1 KiB direct 
 constexpr int kLoadsPerStep = 2 * kLoadsPerOperand;   // direct loads per wavefront and step
 constexpr int kResidentTiles = 256;                   // workgroups the chip runs at a time (one per CU)
 static_assert(kStages >= 3 && kStages <= 5, "LDS budget");
-static_assert(kTM % kLoadsPerOperand == 0, "one load per kTM / kLoadsPerOperand MFMA rows");
 
 // One element of the result: C (op)= 2^(EA_i + EB_j) * sum, with the combine mode of the call.
 __device__ __forceinline__ void write_c_element(const GemmArgs& g, int row, int col, int eb, double sum) {
@@ -330,73 +329,66 @@ void slice_gemm_kernel(const GemmArgs g) {
         }
     };
 
-    // Pipeline prologue: steps 0 .. kStages-2 are requested in full and the A half of step
-    // kStages-1; step 0 is awaited and published.
+    // Pipeline prologue: steps 0 .. kStages-1 are requested; steps 0 and 1 are awaited and published.
     Job nxt = {d_first, pair_mode ? g.pair_p : 1, ks_begin, nullptr, nullptr};   // last step requested
     locate(nxt);
     issue_loads(nxt, 0, 0, kLoadsPerStep);
 #pragma unroll
     for (int b = 1; b < kStages; ++b) {
         advance_clamped(nxt);
-        issue_loads(nxt, b, 0, b == kStages - 1 ? kLoadsPerOperand : kLoadsPerStep);
+        issue_loads(nxt, b, 0, kLoadsPerStep);
     }
-    wait_loads_and_barrier<(kStages - 2) * kLoadsPerStep + kLoadsPerOperand>();
-    v4i fa0[kTM], fb0[kTN], fa1[kTM], fb1[kTN];
+    wait_loads_and_barrier<(kStages - 2) * kLoadsPerStep>();
+    v4i fa0[kTM], fb0[kTN], fa1[kTM], fb1[kTN];   // fragments of the two 32-wide k-slabs of a step
     read_frags(fa0, fb0, 0, 0);
+    read_frags(fa1, fb1, 0, 1);
 
     const int nks = ks_end - ks_begin;
     int buf = 0;                // LDS buffer of the step in the matrix cores
-    int prev = kStages - 1;     // the buffer released at the previous barrier
-    // One step = two k-slabs = four phases. The two halves of the workgroup (wavefronts 0-3 and 4-7,
-    // one of each on every SIMD) take turns: while one half issues the 8 MFMAs of a slab from
-    // fragments it already holds, the other half reads its next fragments from LDS and issues its
-    // share of the direct loads; a barrier ends every phase and the second half runs one phase
-    // behind the first. The matrix cores of a SIMD thus always have a wavefront that does nothing
-    // but issue MFMAs, and LDS latency, load issue (the texture-address unit takes about 18 cycles
-    // per wave-wide load and a wavefront stalls at issue while it is busy) and barrier waits fall
-    // on the wavefront that has no MFMA to issue anyway. Per step and wavefront:
-    //   MFMA slab 0 | read slab-1 fragments, B half of the loads 3 steps ahead (into the buffer
-    //   released a step ago), wait for the loads of the next step | MFMA slab 1 | read the next
-    //   step's slab-0 fragments, A half of the loads 4 steps ahead (into the buffer just left).
-    // A buffer is overwritten only after both halves have read it: the lagging half reads its
-    // slab-1 fragments one phase after the leading half, and the loads into that buffer are
-    // issued a phase later still.
+    // One step = two phases. The two halves of the workgroup (wavefronts 0-3 and 4-7, one of each
+    // on every SIMD) take turns: while one half issues the 16 MFMAs of a step from fragments it
+    // already holds, the other half reads the fragments of its next step from LDS, issues its share
+    // of the direct loads and waits for older ones; a barrier ends every phase and the second half
+    // runs one phase behind the first. The matrix cores of a SIMD thus always have a wavefront that
+    // does nothing but issue MFMAs, and LDS latency, load issue (the texture-address unit takes
+    // about 18 cycles per wave-wide load and a wavefront stalls at issue while it is busy) and
+    // barrier waits fall on the wavefront that has no MFMA to issue anyway. Memory phase of step u:
+    //   read the fragments of step u+1; request step u+kStages into the buffer of step u (both
+    //   halves read its fragments at least one barrier ago: the leading half two phases, the
+    //   lagging half one phase earlier); wait until this wavefront's loads of step u+2 have landed.
+    // Hence when a half reads the fragments of step u+1, every wavefront has confirmed its loads
+    // of that step at least one barrier earlier (in its memory phase of step u-1, or the prologue).
     const bool lag = wave >= kWaves / 2;
     auto phase_barrier = [&]() {
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_barrier" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto mfma_phase = [&](v16i (&acc)[kTM][kTN], const v4i (&a)[kTM], const v4i (&b)[kTN]) {
-        __builtin_amdgcn_s_setprio(1);   // the wavefront with MFMAs to issue goes first on its SIMD
+    auto mfma_slab = [&](v16i (&acc)[kTM][kTN], const v4i (&a)[kTM], const v4i (&b)[kTN]) {
 #pragma unroll
         for (int i = 0; i < kTM; ++i)
 #pragma unroll
             for (int j = 0; j < kTN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
-        __builtin_amdgcn_s_setprio(0);
     };
     auto run_steps = [&](v16i (&acc)[kTM][kTN], int count) {
         if (lag) phase_barrier();        // fall one phase behind ...
         int t = 0;
         do {
-            mfma_phase(acc, fa0, fb0);
+            __builtin_amdgcn_s_setprio(1);   // the wavefront with MFMAs to issue goes first on its SIMD
+            mfma_slab(acc, fa0, fb0);
+            mfma_slab(acc, fa1, fb1);
+            __builtin_amdgcn_s_setprio(0);
             phase_barrier();
-            read_frags(fa1, fb1, buf, 1);
-            issue_loads(nxt, prev, kLoadsPerOperand, kLoadsPerStep);
+            const int nbuf = buf + 1 == kStages ? 0 : buf + 1;
+            read_frags(fa0, fb0, nbuf, 0);
+            read_frags(fa1, fb1, nbuf, 1);
+            advance_clamped(nxt);
+            issue_loads(nxt, buf, 0, kLoadsPerStep);
             __builtin_amdgcn_sched_barrier(0);
             wait_loads_and_barrier<(kStages - 2) * kLoadsPerStep>();
             __builtin_amdgcn_sched_barrier(0);
-            mfma_phase(acc, fa1, fb1);
-            phase_barrier();
-            advance_clamped(nxt);
-            prev = buf;
-            buf = buf + 1 == kStages ? 0 : buf + 1;
-            read_frags(fa0, fb0, buf, 0);
-            issue_loads(nxt, prev, 0, kLoadsPerOperand);
-            __builtin_amdgcn_sched_barrier(0);
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            __builtin_amdgcn_sched_barrier(0);
+            buf = nbuf;
         } while (++t < count);
         if (!lag) phase_barrier();       // ... and let it catch up: what follows is done by all together
     };
