@@ -1,11 +1,11 @@
 // A plain user of the vendor BLAS that knows nothing about ozimmu: reads one GEMM problem from a
-// file, runs it through rocblas_{d,z}gemm or hipblas{D,Z}gemm on a stream of its own and writes C
+// file, runs it through rocblas_{d,z}gemm, hipblas{D,Z}gemm or the gemm_ex forms on a stream of its own and writes C
 // back. It exists to show (and test) that preloading libozimmu_preload.so redirects such a program.
 //
 //   blas_client <problem file> <result file>
 //
-// Problem file: nine int64 (api: 0 rocBLAS / 1 hipBLAS, complex 0/1, transa, transb as 0 N / 1 T /
-// 2 C, m, n, k, repeats, streams), alpha and beta as two doubles each, then A, B, C column-major
+// Problem file: nine int64 (api: 0 rocBLAS / 1 hipBLAS typed calls, 2 rocblas_gemm_ex / 3 hipblasGemmEx;
+// complex 0/1; transa, transb as 0 N / 1 T / 2 C; m, n, k, repeats, streams), alpha and beta as two doubles each, then A, B, C column-major
 // without padding (lda = rows of A as stored, ...). Complex data interleaved. The call is issued
 // `repeats` times with the same arguments, round-robin over `streams` streams; with beta = 0 the result
 // is that of one call. Result file: C, same layout.
@@ -53,7 +53,7 @@ int main(int argc, char** argv) {
     hipStream_t st[4];
     for (int i = 0; i < streams; ++i) CHECK(hipStreamCreate(&st[i]) == hipSuccess);
 
-    if (api == 0) {
+    if (api == 0 || api == 2) {
         rocblas_handle handle;
         CHECK(rocblas_create_handle(&handle) == rocblas_status_success);
         const rocblas_operation ops[3] = {rocblas_operation_none, rocblas_operation_transpose,
@@ -61,7 +61,12 @@ int main(int argc, char** argv) {
         for (int64_t r = 0; r < repeats; ++r) {
             CHECK(rocblas_set_stream(handle, st[r % streams]) == rocblas_status_success);
             rocblas_status rc;
-            if (cplx)
+            if (api == 2) {
+                const rocblas_datatype ty = cplx ? rocblas_datatype_f64_c : rocblas_datatype_f64_r;
+                rc = rocblas_gemm_ex(handle, ops[ta], ops[tb], (rocblas_int)m, (rocblas_int)n, (rocblas_int)k, alpha, dA, ty,
+                                     (rocblas_int)a_rows, dB, ty, (rocblas_int)b_rows, beta, dC, ty, (rocblas_int)m, dC, ty,
+                                     (rocblas_int)m, ty, rocblas_gemm_algo_standard, 0, 0);
+            } else if (cplx)
                 rc = rocblas_zgemm(handle, ops[ta], ops[tb], (rocblas_int)m, (rocblas_int)n, (rocblas_int)k,
                                    reinterpret_cast<const rocblas_double_complex*>(alpha),
                                    reinterpret_cast<const rocblas_double_complex*>(dA), (rocblas_int)a_rows,
@@ -82,7 +87,11 @@ int main(int argc, char** argv) {
         for (int64_t r = 0; r < repeats; ++r) {
             CHECK(hipblasSetStream(handle, st[r % streams]) == HIPBLAS_STATUS_SUCCESS);
             hipblasStatus_t rc;
-            if (cplx)
+            if (api == 3) {
+                const hipDataType ty = cplx ? HIP_C_64F : HIP_R_64F;
+                rc = hipblasGemmEx(handle, ops[ta], ops[tb], (int)m, (int)n, (int)k, alpha, dA, ty, (int)a_rows, dB, ty,
+                                   (int)b_rows, beta, dC, ty, (int)m, HIPBLAS_COMPUTE_64F, HIPBLAS_GEMM_DEFAULT);
+            } else if (cplx)
                 rc = hipblasZgemm(handle, ops[ta], ops[tb], (int)m, (int)n, (int)k,
                                   reinterpret_cast<const hipDoubleComplex*>(alpha),
                                   reinterpret_cast<const hipDoubleComplex*>(dA), (int)a_rows,

@@ -5,8 +5,9 @@
 //
 //   LD_PRELOAD=/path/to/libozimmu_preload.so  program ...
 //
-// Intercepted: rocblas_dgemm, rocblas_zgemm, hipblasDgemm, hipblasZgemm, their _64 forms and their
-// strided-batched forms (computed member by member). A call
+// Intercepted: rocblas_dgemm, rocblas_zgemm, hipblasDgemm, hipblasZgemm, their _64 forms, their
+// strided-batched forms (computed member by member) and the all-FP64 in-place case of rocblas_gemm_ex /
+// hipblasGemmEx. A call
 // is computed here when the handle is in host pointer mode (alpha and beta readable on the host) and
 // the library accepts the arguments; every other call, and every call in vendor mode, goes on to the
 // vendor's routine (found behind this library in the global scope, or in the loaded vendor library
@@ -438,6 +439,50 @@ hipblasStatus_t hipblasZgemmStridedBatched(hipblasHandle_t handle, hipblasOperat
     return hipblas_batched_entry<int, long long, hipDoubleComplex, decltype(&hipblasZgemmStridedBatched)>(
         "hipblasZgemmStridedBatched", true, handle, transA, transB, m, n, k, alpha, AP, lda, strideA, BP, ldb, strideB,
         beta, CP, ldc, strideC, batchCount);
+}
+
+rocblas_status rocblas_gemm_ex(rocblas_handle handle, rocblas_operation transA, rocblas_operation transB, rocblas_int m,
+                               rocblas_int n, rocblas_int k, const void* alpha, const void* a, rocblas_datatype a_type,
+                               rocblas_int lda, const void* b, rocblas_datatype b_type, rocblas_int ldb, const void* beta,
+                               const void* c, rocblas_datatype c_type, rocblas_int ldc, void* d, rocblas_datatype d_type,
+                               rocblas_int ldd, rocblas_datatype compute_type, rocblas_gemm_algo algo,
+                               int32_t solution_index, uint32_t flags) {
+    // only the all-FP64 (real or complex) in-place form is a DGEMM / ZGEMM; everything else is the vendor's
+    const bool f64 = a_type == b_type && a_type == c_type && a_type == d_type && a_type == compute_type &&
+                     (a_type == rocblas_datatype_f64_r || a_type == rocblas_datatype_f64_c) && c == d && ldc == ldd;
+    hipStream_t stream = nullptr;
+    if (f64 && config().slices >= 0 && rocblas_context(handle, &stream)) {
+        const Call call{"rocblas_gemm_ex", a_type == rocblas_datatype_f64_c, op_letter((int)transA), op_letter((int)transB),
+                        (int64_t)m, (int64_t)n, (int64_t)k, static_cast<const double*>(alpha), static_cast<const double*>(a),
+                        (int64_t)lda, static_cast<const double*>(b), (int64_t)ldb, static_cast<const double*>(beta),
+                        static_cast<double*>(d), (int64_t)ldd};
+        if (compute(call, stream)) return rocblas_status_success;
+    }
+    note_passthrough("rocblas_gemm_ex");
+    static const auto next = vendor<decltype(&rocblas_gemm_ex)>("librocblas.so", "rocblas_gemm_ex");
+    if (!next) return rocblas_status_internal_error;
+    return next(handle, transA, transB, m, n, k, alpha, a, a_type, lda, b, b_type, ldb, beta, c, c_type, ldc, d, d_type, ldd,
+                compute_type, algo, solution_index, flags);
+}
+
+hipblasStatus_t hipblasGemmEx(hipblasHandle_t handle, hipblasOperation_t transA, hipblasOperation_t transB, int m, int n,
+                              int k, const void* alpha, const void* A, hipDataType aType, int lda, const void* B,
+                              hipDataType bType, int ldb, const void* beta, void* C, hipDataType cType, int ldc,
+                              hipblasComputeType_t computeType, hipblasGemmAlgo_t algo) {
+    const bool f64 = aType == bType && aType == cType && (aType == HIP_R_64F || aType == HIP_C_64F) &&
+                     computeType == HIPBLAS_COMPUTE_64F;
+    hipStream_t stream = nullptr;
+    if (f64 && config().slices >= 0 && hipblas_context(handle, &stream)) {
+        const Call call{"hipblasGemmEx", aType == HIP_C_64F, op_letter((int)transA), op_letter((int)transB), (int64_t)m,
+                        (int64_t)n, (int64_t)k, static_cast<const double*>(alpha), static_cast<const double*>(A), (int64_t)lda,
+                        static_cast<const double*>(B), (int64_t)ldb, static_cast<const double*>(beta),
+                        static_cast<double*>(C), (int64_t)ldc};
+        if (compute(call, stream)) return HIPBLAS_STATUS_SUCCESS;
+    }
+    note_passthrough("hipblasGemmEx");
+    static const auto next = vendor<decltype(&hipblasGemmEx)>("libhipblas.so", "hipblasGemmEx");
+    if (!next) return HIPBLAS_STATUS_INTERNAL_ERROR;
+    return next(handle, transA, transB, m, n, k, alpha, A, aType, lda, B, bType, ldb, beta, C, cType, ldc, computeType, algo);
 }
 
 }  // extern "C"

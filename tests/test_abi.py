@@ -197,7 +197,8 @@ def test_interposer_exports_the_vendor_gemm_symbols_and_blas_argument_errors():
     P = ctypes.CDLL(str(pre))
     for name in ("rocblas_dgemm", "rocblas_zgemm", "rocblas_dgemm_64", "rocblas_zgemm_64", "hipblasDgemm",
                  "hipblasZgemm", "hipblasDgemm_64", "hipblasZgemm_64", "rocblas_dgemm_strided_batched",
-                 "rocblas_zgemm_strided_batched", "hipblasDgemmStridedBatched", "hipblasZgemmStridedBatched"):
+                 "rocblas_zgemm_strided_batched", "hipblasDgemmStridedBatched", "hipblasZgemmStridedBatched",
+                 "rocblas_gemm_ex", "hipblasGemmEx"):
         assert getattr(P, name) is not None
 
     L = ozimmu.lib()

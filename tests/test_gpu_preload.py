@@ -117,6 +117,28 @@ def test_intercepted_zgemm_is_the_ozaki_result(tmp_path, api):
     assert np.array_equal(bits(got), bits(oracle.zgemm_blas("C", "N", 1.0, A, B, 0.0, C0, s_auto)))
 
 
+@pytest.mark.parametrize("api,cplx", [(2, False), (2, True), (3, False), (3, True)])
+def test_all_fp64_gemm_ex_calls_are_intercepted_too(tmp_path, api, cplx):
+    name = {2: "rocblas_gemm_ex", 3: "hipblasGemmEx"}[api]
+    rng = np.random.default_rng(17 + api)
+    m, n, k = 90, 120, 200
+    if cplx:
+        opA = rng.standard_normal((m, k)) + 1j * rng.standard_normal((m, k))
+        opB = rng.standard_normal((k, n)) + 1j * rng.standard_normal((k, n))
+        C0 = rng.standard_normal((m, n)) + 1j * rng.standard_normal((m, n))
+        alpha, beta = 1.5 + 0.5j, -0.5j
+        got, log = run_client(tmp_path, api, "N", "C", alpha, beta, opA, opB.conj().T.copy(), C0, mode="8")
+        want = oracle.zgemm_blas("N", "C", alpha, opA, opB.conj().T.copy(), beta, C0, 8)
+    else:
+        opA, opB = wl.phi_pair(m, n, k, 1.0, seed=9)
+        C0 = rng.standard_normal((m, n))
+        alpha, beta = -1.25, 2.0
+        got, log = run_client(tmp_path, api, "N", "T", alpha, beta, opA, opB.T.copy(), C0, mode="8")
+        want = oracle.dgemm_blas(False, True, alpha, opA, opB.T.copy(), beta, C0, 8)
+    assert f"[ozimmu] {name} N" in log and "slices=8" in log
+    assert np.array_equal(bits(got), bits(want))
+
+
 def test_repeated_calls_on_several_streams_share_the_workspace_safely(tmp_path):
     """Six calls round-robin over three streams: the interposer orders them on the device (they share one
     workspace), so the result is that of a single call."""
