@@ -258,7 +258,9 @@ ozimmu_status_t ozimmu_auto_num_slices_blas(char transa, char transb, int64_t m,
  *   ozimmu_probe_int8_mfma: sustained rate of a register-only v_mfma_i32_32x32x32_i8 issue loop on
  *     all compute units, in 10^12 INT8 operations per second, and the shader clock it ran at.
  *     pattern 0: all-zero operands; 1: random bytes; 2: random signed 7-bit magnitudes (the value
- *     distribution of the slices of Section 3.1). The reachable matrix-core rate depends on it.
+ *     distribution of the slices of Section 3.1); 3: random signed 3-bit magnitudes; 4: random 7-bit
+ *     magnitudes without sign; 5: A as 2, every byte of B equal to 1; 6: A as 2, B zero. The
+ *     reachable matrix-core rate depends on the operand data.
  *   ozimmu_probe_lds_read: wave-wide 16-byte LDS read throughput in bytes per ns and compute unit.
  *     pattern 0: linear; 1: 64-byte rows without column swizzle; 2: the slice-tensor block layout.
  */

@@ -18,7 +18,9 @@ __device__ __forceinline__ unsigned mix(unsigned x) {
 
 // Register-only issue loop: 16 independent 32x32x32 INT8 MFMAs per iteration, 4 waves per CU.
 // pattern 0: all-zero operands, 1: random bytes, 2: random 7-bit magnitudes with random sign
-// (sign-magnitude values in [-127, 127], the value distribution of Ozaki slices beyond the first).
+// (sign-magnitude values in [-127, 127], the value distribution of Ozaki slices beyond the first),
+// 3: random signed 3-bit magnitudes, 4: random 7-bit magnitudes without sign, 5: A as 2 and every
+// byte of B equal to 1, 6: A as 2 and B zero.
 __global__ __launch_bounds__(256) void mfma_rate_kernel(int pattern, int iters, int* sink, long long* clocks) {
     const long long c0 = clock64(), w0 = wall_clock64();
     v16i acc[16];
@@ -31,16 +33,20 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int pattern, int iters, 
         for (int c = 0; c < 4; ++c) {
             unsigned ha = mix(threadIdx.x * 64 + i * 8 + c + blockIdx.x * 7919), hb = mix(ha + 12345);
             if (pattern == 0) ha = hb = 0;
-            if (pattern == 2) {
+            if (pattern >= 2) {
+                // bytes as sign-magnitude values: `bits` magnitude bits, sign from bit 7 unless unsigned
+                const int bits = pattern == 3 ? 3 : 7;
+                const bool with_sign = pattern != 4;
                 unsigned va = 0, vb = 0;
                 for (int k = 0; k < 4; ++k) {
-                    int xa = (int)((ha >> (8 * k)) & 127), xb = (int)((hb >> (8 * k)) & 127);
-                    if ((ha >> (8 * k + 7)) & 1) xa = -xa;
-                    if ((hb >> (8 * k + 7)) & 1) xb = -xb;
+                    int xa = (int)((ha >> (8 * k)) & ((1u << bits) - 1u)), xb = (int)((hb >> (8 * k)) & ((1u << bits) - 1u));
+                    if (with_sign && ((ha >> (8 * k + 7)) & 1)) xa = -xa;
+                    if (with_sign && ((hb >> (8 * k + 7)) & 1)) xb = -xb;
                     va |= ((unsigned)xa & 255u) << (8 * k);
                     vb |= ((unsigned)xb & 255u) << (8 * k);
                 }
-                ha = va; hb = vb;
+                ha = va;
+                hb = pattern == 5 ? 0x01010101u : pattern == 6 ? 0u : vb;
             }
             a[i][c] = (int)ha;
             b[i][c] = (int)hb;
@@ -113,7 +119,7 @@ extern "C" {
 // Allocates a few KiB of device and pinned host memory for the duration of the call and
 // synchronises the device: a measurement utility, not a building block.
 ozimmu_status_t ozimmu_probe_int8_mfma(int pattern, int iters, double* tera_ops_per_s, double* shader_mhz) {
-    if (pattern < 0 || pattern > 2 || iters < 1) return OZIMMU_ERR_BAD_DIM;
+    if (pattern < 0 || pattern > 6 || iters < 1) return OZIMMU_ERR_BAD_DIM;
     if (!tera_ops_per_s || !shader_mhz) return OZIMMU_ERR_NULL;
     int cus = 0, dev = 0;
     int* sink = nullptr;
