@@ -98,6 +98,42 @@ def test_split_adversarial_values():
         check_split(Eg, Sg, Eo, So, 40, 333)
 
 
+def random_bit_patterns(shape, seed, exp_lo=0, exp_hi=2046):
+    """Doubles drawn as raw bit patterns: random sign and 52-bit fraction, exponent field uniform in
+    [exp_lo, exp_hi] (0 = subnormals and zeros, 2046 = the largest finite binade)."""
+    rng = np.random.default_rng(seed)
+    frac = rng.integers(0, 1 << 52, size=shape, dtype=np.uint64)
+    expo = rng.integers(exp_lo, exp_hi + 1, size=shape, dtype=np.uint64)
+    sign = rng.integers(0, 2, size=shape, dtype=np.uint64)
+    return ((sign << np.uint64(63)) | (expo << np.uint64(52)) | frac).view(np.float64)
+
+
+@pytest.mark.parametrize("s", [3, 9, 16])
+def test_split_of_random_bit_patterns(s):
+    """Every finite binade, subnormals included, in one matrix: rows whose largest element is near
+    DBL_MAX next to subnormal rows, most elements far below their row's first slice."""
+    M = random_bit_patterns((70, 333), seed=5)
+    M[3, :] = random_bit_patterns((333,), seed=6, exp_lo=0, exp_hi=0)       # a subnormal row
+    M[4, :] = 0.0
+    Eo, So = oracle.split_rows(M, s)
+    Eg, Sg, _ = gpu_split_rows(M, s)
+    check_split(Eg, Sg, Eo, So, 70, 333)
+    Eo, So = oracle.split_cols(np.ascontiguousarray(M.T), s)
+    Eg, Sg, _ = gpu_split_cols(np.ascontiguousarray(M.T), s)
+    check_split(Eg, Sg, Eo, So, 70, 333)
+
+
+def test_dgemm_of_random_bit_patterns_bit_exact():
+    """Exponent fields spread over 600 binades (the result stays finite), and over all binades (the scale
+    2^(EA+EB) overflows for part of the outputs: both sides must then give the same infinities, never NaN)."""
+    for lo, hi, seed in ((723, 1323, 7), (0, 2046, 8)):
+        A = random_bit_patterns((130, 200), seed, lo, hi)
+        B = random_bit_patterns((200, 90), seed + 100, lo, hi)
+        got, want = gpu_dgemm(A, B, 8), oracle.dgemm(A, B, 8)
+        assert not np.isnan(want).any() and np.array_equal(bits(got), bits(want))
+    assert np.isinf(want).any()
+
+
 def test_split_respects_leading_dimension():
     big = wl.phi_matrix(50, 200, 1.0, seed=3)
     view = big[:, 10:150]
