@@ -187,6 +187,25 @@ def test_slices_brute_force_adversarial():
             assert list(S[:, i, l]) == brute_chunks(A[i, l], int(E[i]), s), (i, l)
 
 
+def test_slices_brute_force_on_raw_bit_patterns_of_every_binade():
+    """Doubles drawn as raw 64-bit patterns (exponent field uniform over 0 .. 2046: subnormals to the
+    largest binade; one all-subnormal row), rows and columns, against the Python-integer cut."""
+    rng = np.random.default_rng(12)
+    shape = (9, 21)
+    bits = ((rng.integers(0, 2, size=shape, dtype=np.uint64) << np.uint64(63)) |
+            (rng.integers(0, 2047, size=shape, dtype=np.uint64) << np.uint64(52)) |
+            rng.integers(0, 1 << 52, size=shape, dtype=np.uint64))
+    bits[2, :] &= np.uint64((1 << 52) - 1) | np.uint64(1 << 63)     # subnormal row
+    A = bits.view(np.float64)
+    s = 16
+    E, S = oracle.split_rows(A, s)
+    Ec, Sc = oracle.split_cols(np.ascontiguousarray(A.T), s)
+    assert np.array_equal(E, Ec) and np.array_equal(S, Sc)          # B is split as its transpose
+    for i in range(shape[0]):
+        for l in range(shape[1]):
+            assert list(S[:, i, l]) == brute_chunks(A[i, l], int(E[i]), s), (i, l)
+
+
 def test_slice_prefix_property_and_truncation_residual():
     A = wl.phi_matrix(8, 64, 1.0, seed=9)
     E, S13 = oracle.split_rows(A, 13)
