@@ -48,7 +48,8 @@ typedef enum {
     OZIMMU_ERR_NULL = 4,           /* null pointer where data is required */
     OZIMMU_ERR_WORKSPACE = 5,      /* workspace null, misaligned or too small */
     OZIMMU_ERR_HIP = 6,            /* a HIP call or kernel launch failed */
-    OZIMMU_ERR_NOT_IMPLEMENTED = 7
+    OZIMMU_ERR_NOT_IMPLEMENTED = 7,
+    OZIMMU_ERR_TOO_LARGE = 8       /* the product needs more scratch than ozimmu_dgemm_static holds */
 } ozimmu_status_t;
 
 #define OZIMMU_MAX_SLICES 16
@@ -60,6 +61,7 @@ typedef enum {
 #define OZIMMU_INT32_BLOCK 131072    /* at most 2^17 INT8 products go into one INT32 sum:
                                         2^17 * 127^2 < 2^31 (the exact limit is 133144) */
 #define OZIMMU_WORKSPACE_ALIGN 256
+#define OZIMMU_STATIC_SCRATCH_BYTES 67108864   /* 64 MiB: the built-in scratch of ozimmu_dgemm_static */
 
 const char* ozimmu_status_string(ozimmu_status_t status);
 
@@ -136,6 +138,23 @@ ozimmu_status_t ozimmu_zgemm(int64_t m, int64_t n, int64_t k, const double* A, i
                              const double* B, int64_t ldb, double* C, int64_t ldc,
                              int num_slices, void* workspace, size_t workspace_bytes,
                              void* stream);
+
+/*
+ * ozimmu_dgemm for callers that cannot allocate device memory or carry a workspace around: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments and
+ * result as ozimmu_dgemm (bit for bit) without the workspace: the library's own scratch, a device
+ * array of OZIMMU_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process
+ * ends, takes its place. The call allocates and frees nothing and only enqueues kernels. A product
+ * whose ozimmu_workspace_bytes(m, n, k, num_slices, 0) exceeds OZIMMU_STATIC_SCRATCH_BYTES is
+ * refused with OZIMMU_ERR_TOO_LARGE before anything is enqueued (use ozimmu_dgemm with a
+ * workspace of your own). All calls on one GPU share that GPU's scratch: calls that overlap on one
+ * GPU (different streams without ordering between them, or several host threads) race; calls on one
+ * stream, or ordered by events, are safe. The first call on a device looks the array's address up
+ * (hipGetSymbolAddress, no allocation).
+ */
+ozimmu_status_t ozimmu_dgemm_static(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                                    const double* B, int64_t ldb, double* C, int64_t ldc,
+                                    int num_slices, void* stream);
 
 /*
  * The stages of ozimmu_dgemm run one at a time, for per-stage timing and profiling

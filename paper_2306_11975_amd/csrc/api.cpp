@@ -215,6 +215,7 @@ const char* ozimmu_status_string(ozimmu_status_t status) {
         case OZIMMU_ERR_WORKSPACE: return "workspace null, misaligned or too small";
         case OZIMMU_ERR_HIP: return "HIP error";
         case OZIMMU_ERR_NOT_IMPLEMENTED: return "not implemented";
+        case OZIMMU_ERR_TOO_LARGE: return "product too large for the built-in scratch (use a workspace)";
     }
     return "unknown status";
 }

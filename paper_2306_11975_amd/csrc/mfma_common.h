@@ -69,7 +69,8 @@ __device__ __forceinline__ void dma_load16(const void* gbase, unsigned voff, uns
         "global_load_lds_dwordx4 %1, %0"
         :
         : "s"(gbase), "v"(voff), "s"(lds_addr)
-        : "memory");  // M0 is written here; nothing else in this kernel uses it
+        : "memory");  // M0 is written here (the compiler refuses it as a clobber: reserved register); the build
+                      // checks the generated assembly for any other use of M0 in the kernels
 }
 
 // Wait until at most N of this wave's direct loads are outstanding (they return in order, so

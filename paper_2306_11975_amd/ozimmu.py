@@ -11,17 +11,19 @@ from pathlib import Path
 
 _LIB_PATH = Path(__file__).resolve().parent / "libozimmu.so"
 
-OK, ERR_BAD_DIM, ERR_BAD_LD, ERR_BAD_SLICES, ERR_NULL, ERR_WORKSPACE, ERR_HIP, ERR_NOT_IMPLEMENTED = range(8)
+(OK, ERR_BAD_DIM, ERR_BAD_LD, ERR_BAD_SLICES, ERR_NULL, ERR_WORKSPACE, ERR_HIP, ERR_NOT_IMPLEMENTED,
+ ERR_TOO_LARGE) = range(9)
 MAX_SLICES = 16
 ROW_ALIGN = 256
 K_ALIGN = 128
 K_STEP = 64
 INT32_BLOCK = 131072
 WORKSPACE_ALIGN = 256
+STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = (
     "ozimmu_status_string", "ozimmu_slice_geometry", "ozimmu_slice_offset", "ozimmu_split_rows", "ozimmu_split_cols",
-    "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_stage",
+    "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_static", "ozimmu_dgemm_stage",
     "ozimmu_launch_plan", "ozimmu_dgemm_dd", "ozimmu_dgemm_blas", "ozimmu_zgemm_blas_workspace_bytes", "ozimmu_zgemm_blas",
     "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices", "ozimmu_auto_num_slices_blas",
     "ozimmu_probe_int8_mfma", "ozimmu_probe_lds_read",
@@ -64,6 +66,8 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = i32
             f.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
+        L.ozimmu_dgemm_static.restype = i32
+        L.ozimmu_dgemm_static.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp]
         L.ozimmu_dgemm_stage.restype = i32
         L.ozimmu_dgemm_stage.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
         L.ozimmu_launch_plan.restype = i32
@@ -189,6 +193,14 @@ def dgemm(A, B, C, num_slices: int, workspace, stream=None) -> None:
     n = B.shape[1]
     _check(lib().ozimmu_dgemm(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C), _ld(C, n), num_slices,
                               _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+
+
+def dgemm_static(A, B, C, num_slices: int, stream=None) -> None:
+    """ozimmu_dgemm without a workspace argument: the library's built-in scratch is used (see ozimmu.h)."""
+    m, k = A.shape
+    n = B.shape[1]
+    _check(lib().ozimmu_dgemm_static(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C), _ld(C, n),
+                                     num_slices, _stream(stream)))
 
 
 def dgemm_stage(stage: int, A, B, C, num_slices: int, workspace, stream=None) -> None:

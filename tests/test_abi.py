@@ -27,8 +27,8 @@ def test_header_and_binding_agree_and_library_exports_everything():
 
 def test_status_strings():
     assert ozimmu.status_string(0) == "ok"
-    seen = {ozimmu.status_string(c) for c in range(8)}
-    assert len(seen) == 8
+    seen = {ozimmu.status_string(c) for c in range(9)}
+    assert len(seen) == 9
     assert ozimmu.status_string(99) == "unknown status"
 
 
