@@ -20,8 +20,10 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). All work is
  *     enqueued on it; no entry point synchronises, allocates or frees device memory, or
  *     keeps state between calls (exceptions, stated where they are declared:
- *     ozimmu_auto_num_slices returns a value to the host and waits for the stream; the
- *     ozimmu_probe_* utilities). Calls that share a workspace must be stream-ordered.
+ *     ozimmu_auto_num_slices returns a value to the host and waits for the stream;
+ *     ozimmu_dgemm_static uses the library's own scratch array; the library remembers per
+ *     device that it has raised a kernel's dynamic LDS limit). Calls that share a workspace must
+ *     be stream-ordered.
  *   - Only kernels are enqueued (no memsets or copies), so the calls can be captured into
  *     a HIP graph. The first launch of a kernel on a device raises that kernel's dynamic
  *     LDS limit (a host-side driver call, once): make one ordinary call before capturing.
@@ -54,9 +56,9 @@ typedef enum {
 
 #define OZIMMU_MAX_SLICES 16
 #define OZIMMU_SLICE_BITS 7          /* Table 2: INT8-INT32 keeps 7 magnitude bits per slice */
-#define OZIMMU_ROW_ALIGN 256         /* slice rows are padded to a multiple of this */
-#define OZIMMU_K_ALIGN 128           /* slice row length is padded to a multiple of this */
-#define OZIMMU_K_STEP 64             /* k-extent of one contiguous block of a slice tensor */
+#define OZIMMU_ROW_ALIGN 128         /* slice rows are padded to a multiple of this */
+#define OZIMMU_K_ALIGN 32            /* slice row length is padded to a multiple of this: the k-extent of
+                                        one MFMA operand fragment (32 rows x 32 bytes = 1 KiB) */
 #define OZIMMU_MAX_DIM 4194304       /* largest m, n or k accepted (2^22); beyond: OZIMMU_ERR_BAD_DIM */
 #define OZIMMU_INT32_BLOCK 131072    /* at most 2^17 INT8 products go into one INT32 sum:
                                         2^17 * 127^2 < 2^31 (the exact limit is 133144) */
@@ -69,14 +71,14 @@ const char* ozimmu_status_string(ozimmu_status_t status);
  * Slice tensors. The slices of `rows` rows of length k (A: rows = m; B^T: rows = n, so that both
  * operands of a slice product are "rows of length k", SplitInt header: M = A or B^T) are padded
  * to rows_padded = roundup(rows, OZIMMU_ROW_ALIGN) and k_padded = roundup(k, OZIMMU_K_ALIGN),
- * zero-filled outside [0,rows) x [0,k), and stored tiled, in exactly the order in which the
- * slice-product kernel copies them into LDS: a block of OZIMMU_ROW_ALIGN rows x
- * OZIMMU_K_STEP bytes is contiguous (16 KiB), and inside a row of a block the four 16-byte
- * columns are XOR-swizzled with bits 2..3 of the row. Element (slice s, row r, position l),
- * with rr = r % 256, c = (l % 64) / 16, lives at byte offset
+ * zero-filled outside [0,rows) x [0,k), and stored as the MFMA operand fragments the
+ * slice-product kernel copies unchanged into LDS: a fragment = 32 rows x 32 positions of one slice,
+ * 1 KiB contiguous, fragments ordered [slice][row / 32][l / 32]; inside a fragment row rr = r % 32
+ * occupies bytes [32 rr, 32 rr + 32), its two 16-byte halves swapped when bit 3 of rr is set.
+ * Element (slice s, row r, position l), with rr = r % 32, h = (l % 32) / 16, lives at byte offset
  *     s * rows_padded * k_padded
- *   + ((r / 256) * (k_padded / 64) + l / 64) * 16384
- *   + rr * 64 + ((c ^ ((rr / 4) % 4)) * 16) + l % 16
+ *   + ((r / 32) * (k_padded / 32) + l / 32) * 1024
+ *   + rr * 32 + ((h ^ ((rr / 8) % 2)) * 16) + l % 16
  * (ozimmu_slice_offset computes it). Size: num_slices * rows_padded * k_padded bytes.
  */
 ozimmu_status_t ozimmu_slice_geometry(int64_t rows, int64_t k, int64_t* rows_padded,
@@ -92,7 +94,9 @@ int64_t ozimmu_slice_offset(int64_t rows_padded, int64_t k_padded, int slice, in
  *                |A_il| 2^(-EA_i), each chunk in [0, 127] (truncation, no rounding).
  * split_cols does the same for the columns of B (k x n, ldb >= n), i.e. for M = B^T:
  * exps int32[n], element (q-1, j, l) from B_lj. `col_scratch` is device memory of at least
- * 8 * n bytes (column maxima), 8-byte aligned.
+ * 8 * roundup(n, OZIMMU_ROW_ALIGN) bytes, 8-byte aligned: the column maxima are reduced there with
+ * atomics by one kernel and read by the next (an argument the algorithm itself does not have; it
+ * keeps the library free of allocations).
  */
 ozimmu_status_t ozimmu_split_rows(int64_t m, int64_t k, const double* A, int64_t lda,
                                   int num_slices, int8_t* slices, int32_t* exps, void* stream);
@@ -106,16 +110,18 @@ ozimmu_status_t ozimmu_split_cols(int64_t k, int64_t n, const double* B, int64_t
  *     P[i][j] = sum_{l = k0}^{k0 + klen - 1} SA(p-1, i, l) * SB(q-1, j, l)     (INT32, exact)
  * SA, SB: slice tensors for m and n rows of length k holding at least p resp. q
  * slices. P: int32, m x n, row-major, ldp >= n. Rules: 1 <= p, q <= OZIMMU_MAX_SLICES;
- * k0 a multiple of OZIMMU_K_ALIGN; klen <= OZIMMU_INT32_BLOCK; klen a multiple of
- * OZIMMU_K_ALIGN unless k0 + klen == k. klen == 0 gives P = 0.
+ * klen <= OZIMMU_INT32_BLOCK; the range must consist of whole fragments: k0 a multiple of
+ * OZIMMU_K_ALIGN (32), and klen too unless k0 + klen == k (the kernel has no masking inside a
+ * fragment; beyond k the slices hold zeros). klen == 0 gives P = 0.
  */
 ozimmu_status_t ozimmu_slice_gemm(int64_t m, int64_t n, int64_t k, const int8_t* SA,
                                   const int8_t* SB, int p, int q, int64_t k0, int64_t klen,
                                   int32_t* P, int64_t ldp, void* stream);
 
 /*
- * Workspace size for ozimmu_dgemm / ozimmu_zgemm (slices of A and B, exponents, and the
- * per-diagonal integer sums that do not stay in registers).
+ * Workspace size for ozimmu_dgemm / ozimmu_zgemm: slices of A and B, exponents, column maxima, and
+ * -- only when num_slices * k_padded > OZIMMU_INT32_BLOCK (k-blocking) -- num_slices INT64 sums per
+ * element of C. Otherwise every integer sum stays in registers.
  */
 ozimmu_status_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_slices,
                                        int is_complex, size_t* bytes);
@@ -167,20 +173,25 @@ ozimmu_status_t ozimmu_dgemm_stage(int stage, int64_t m, int64_t n, int64_t k, c
                                    size_t workspace_bytes, void* stream);
 
 /*
- * Which kernel ozimmu_dgemm uses for a shape, on the host only (nothing is launched; for tests and
- * for callers who want to know): *kernel = 0 the general slice-product kernel (INT32 diagonal sums),
- * 1 the register-resident kernel for short k, 2 the general kernel with INT64 diagonal sums
- * (k-blocking). *groups = number of workgroups that share one 256 x 256 tile (each takes the
- * diagonals whose bits are set in diag_masks[group], bit d = diagonal d; optional array of
- * OZIMMU_MAX_SLICES entries): 1 unless the tile count does not fill the chip.
+ * How ozimmu_dgemm runs a shape, on the host only (nothing is launched; for tests and for callers
+ * who want to know): the tile of C one workgroup owns, the number of workgroups, the number of bands
+ * the anti-diagonals are walked in (a wavefront holds the INT32 sums of at most eight diagonals at a
+ * time: 2 bands beyond eight slices), and int32_block_steps = the number of steps of
+ * OZIMMU_K_ALIGN positions after which the INT32 sums are moved into INT64 sums (k-blocking),
+ * 0 if a whole diagonal fits one INT32 sum.
  */
-ozimmu_status_t ozimmu_launch_plan(int64_t m, int64_t n, int64_t k, int num_slices, int* kernel, int* groups,
-                                   uint32_t* diag_masks);
+typedef struct {
+    int tile_rows, tile_cols;
+    int64_t workgroups;
+    int bands;
+    int int32_block_steps;
+} ozimmu_plan_t;
+ozimmu_status_t ozimmu_launch_plan(int64_t m, int64_t n, int64_t k, int num_slices, ozimmu_plan_t* plan);
 
 /*
  * Product with the summing-up in double-double (Section 2.3.4, first advantage of the scheme: its
  * precision can be raised above FP64 by more slices and a more accurate summing-up). Same splits and
- * slice products as ozimmu_dgemm; the diagonal sums are then added, least significant first, in
+ * slice products as ozimmu_dgemm; the diagonal sums are added, least significant first, in
  * double-double arithmetic (TwoSum of the running high part and the exact term S_d 2^(-7d), error added
  * to the low part, FastTwoSum renormalisation after every term) and both parts are scaled by
  * 2^(EA_i + EB_j): C = C_hi + C_lo as an unevaluated sum, C_hi being the FP64-rounded value. C_hi and
@@ -269,23 +280,6 @@ ozimmu_status_t ozimmu_auto_num_slices_blas(char transa, char transb, int64_t m,
                                             int is_complex, double threshold, int max_slices, void* scratch,
                                             size_t scratch_bytes, int* num_slices, uint64_t* loss_sums,
                                             void* stream);
-
-/*
- * Device characterisation (measurement utilities for the benchmark, not part of the product
- * path; unlike every entry point above they allocate a few KiB for the duration of the call and
- * synchronise the device).
- *   ozimmu_probe_int8_mfma: sustained rate of a register-only v_mfma_i32_32x32x32_i8 issue loop on
- *     all compute units, in 10^12 INT8 operations per second, and the shader clock it ran at.
- *     pattern 0: all-zero operands; 1: random bytes; 2: random signed 7-bit magnitudes (the value
- *     distribution of the slices of Section 3.1); 3: random signed 3-bit magnitudes; 4: random 7-bit
- *     magnitudes without sign; 5: A as 2, every byte of B equal to 1; 6: A as 2, B zero. The
- *     reachable matrix-core rate depends on the operand data.
- *   ozimmu_probe_lds_read: wave-wide 16-byte LDS read throughput in bytes per ns and compute unit.
- *     pattern 0: linear; 1: 64-byte rows without column swizzle; 2: the slice-tensor block layout.
- */
-ozimmu_status_t ozimmu_probe_int8_mfma(int pattern, int iters, double* tera_ops_per_s,
-                                       double* shader_mhz);
-ozimmu_status_t ozimmu_probe_lds_read(int pattern, int iters, double* bytes_per_ns_per_cu);
 
 #ifdef __cplusplus
 }

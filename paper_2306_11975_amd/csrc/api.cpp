@@ -20,12 +20,14 @@ bool dims_ok(int64_t a, int64_t b, int64_t c) {
 }
 
 // A diagonal d = p + q holds d - 1 pairs; the longest one (d = s + 1) sums s * k_pad products
-// per output element. If that exceeds the INT32 block the kernel keeps INT64 sums (k-blocking).
+// per output element. If that exceeds the INT32 block the kernel moves its INT32 sums into INT64
+// sums in the workspace every block_steps steps of 32 products per pair (k-blocking).
 bool needs_wide(int s, int64_t k_pad) { return (int64_t)s * k_pad > OZIMMU_INT32_BLOCK; }
+int block_steps_for(int s) { return OZIMMU_INT32_BLOCK / (s * kSlab); }
 
 struct Layout {
     int64_t m_pad, n_pad, k_pad;
-    int tiles_m, tiles_n;
+    int tiles_m, tiles_n, tile_rows, tile_cols;
     bool wide;
     size_t sa_bytes, sb_bytes;      // one plane
     size_t off_sa[2], off_sb[2];    // planes (real GEMM uses plane 0)
@@ -36,11 +38,15 @@ struct Layout {
 
 Layout make_layout(int64_t m, int64_t n, int64_t k, int s, bool cplx) {
     Layout L{};
-    L.m_pad = round_up(m, kTile);
-    L.n_pad = round_up(n, kTile);
-    L.k_pad = round_up(k, kChunk);
-    L.tiles_m = (int)(L.m_pad / kTile);
-    L.tiles_n = (int)(L.n_pad / kTile);
+    L.m_pad = round_up(m, kRowAlign);
+    L.n_pad = round_up(n, kRowAlign);
+    L.k_pad = round_up(k, kSlab);
+    int wm, wn;
+    tile_waves(s, &wm, &wn);
+    L.tile_rows = wm * kFragRows;
+    L.tile_cols = wn * kFragRows;
+    L.tiles_m = (int)((m + L.tile_rows - 1) / L.tile_rows);
+    L.tiles_n = (int)((n + L.tile_cols - 1) / L.tile_cols);
     L.wide = needs_wide(s, L.k_pad);
     L.sa_bytes = (size_t)s * L.m_pad * L.k_pad;
     L.sb_bytes = (size_t)s * L.n_pad * L.k_pad;
@@ -53,7 +59,7 @@ Layout make_layout(int64_t m, int64_t n, int64_t k, int s, bool cplx) {
     L.off_colmax = off;
     off = align_up(off + sizeof(unsigned long long) * (L.n_pad > L.m_pad ? L.n_pad : L.m_pad));  // either operand may be split by columns
     L.off_d = off;
-    off = align_up(off + (size_t)s * L.tiles_m * L.tiles_n * kTileElems * (L.wide ? 8 : 4));
+    if (L.wide) off = align_up(off + (size_t)s * L.tiles_m * L.tiles_n * L.tile_rows * L.tile_cols * sizeof(long long));
     L.total = off;
     return L;
 }
@@ -77,25 +83,24 @@ ozimmu_status_t check_gemm_args(int64_t m, int64_t n, int64_t k, const void* A, 
 }
 
 // One real Ozaki product from already split operands: G = sum over diagonals, written to C with
-// the given column stride and combine mode.
+// the given column stride and combine mode (C_lo != nullptr: double-double sum into C, C_lo).
 hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned char* ws, int plane_a, int plane_b,
-                       double* C, int64_t ldc, int c_inc, int c_mode, hipStream_t st, int dual = 0,
-                       int plane_a2 = 0, int plane_b2 = 0, double alpha = 1.0, double beta = 0.0) {
+                       double* C, int64_t ldc, int c_inc, int c_mode, hipStream_t st, double alpha = 1.0,
+                       double beta = 0.0, double* C_lo = nullptr) {
     GemmArgs g{};
     g.SA = reinterpret_cast<const int8_t*>(ws + L.off_sa[plane_a]);
     g.SB = reinterpret_cast<const int8_t*>(ws + L.off_sb[plane_b]);
     g.a_slice_stride = L.m_pad * L.k_pad;
     g.b_slice_stride = L.n_pad * L.k_pad;
-    g.k_pad = (int)L.k_pad;
+    g.kslabs = (int)(L.k_pad / kSlab);
+    g.t_begin = 0;
+    g.t_end = g.kslabs;
     g.tiles_m = L.tiles_m;
     g.tiles_n = L.tiles_n;
     g.m = (int)m;
     g.n = (int)n;
-    g.num_slices = s;
-    g.pair_p = g.pair_q = 0;
-    g.kc_begin = 0;
-    g.kc_end = (int)(L.k_pad / kChunk);
-    g.D = ws + L.off_d;
+    g.block_steps = L.wide ? block_steps_for(s) : 0;
+    g.D = L.wide ? reinterpret_cast<long long*>(ws + L.off_d) : nullptr;
     g.P = nullptr;
     g.ldp = 0;
     g.C = C;
@@ -104,20 +109,10 @@ hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned ch
     g.c_mode = c_mode;
     g.alpha = alpha;
     g.beta = beta;
+    g.C_lo = C_lo;
     g.EA = reinterpret_cast<const int32_t*>(ws + L.off_ea[plane_a]);
     g.EB = reinterpret_cast<const int32_t*>(ws + L.off_eb[plane_b]);
-    g.skip_final = 0;
-    g.C_lo = nullptr;
-    g.dual = dual;
-    if (dual) {  // only the register-resident kernel combines two products
-        g.SA2 = reinterpret_cast<const int8_t*>(ws + L.off_sa[plane_a2]);
-        g.SB2 = reinterpret_cast<const int8_t*>(ws + L.off_sb[plane_b2]);
-        g.EA2 = reinterpret_cast<const int32_t*>(ws + L.off_ea[plane_a2]);
-        g.EB2 = reinterpret_cast<const int32_t*>(ws + L.off_eb[plane_b2]);
-        if (!fused_gemm_applies(g, L.wide)) return hipErrorInvalidValue;
-    }
-    if (fused_gemm_applies(g, L.wide)) return launch_fused_gemm(g, st);
-    return launch_slice_gemm(g, L.wide, st);
+    return launch_slice_gemm(g, s, C_lo != nullptr, st);
 }
 
 // The four real products of a complex one from the split planes (0 = real, 1 = imaginary):
@@ -125,17 +120,10 @@ hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned ch
 // combined with the first by one rounded FP64 operation in the kernel's epilogue.
 hipError_t run_complex_products(const Layout& L, int64_t m, int64_t n, int s, unsigned char* ws, double* C,
                                 int64_t ldc, hipStream_t st) {
-    hipError_t e = hipSuccess;
-    if (!L.wide && L.k_pad <= kFusedMaxK) {
-        // short k: both products of a part in one launch, the first one never leaves the registers
-        e = run_product(L, m, n, s, ws, 0, 0, C, 2 * ldc, 2, 0, st, 2, 1, 1);
-        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, C + 1, 2 * ldc, 2, 0, st, 1, 1, 0);
-    } else {
-        e = run_product(L, m, n, s, ws, 0, 0, C, 2 * ldc, 2, 0, st);
-        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 1, C, 2 * ldc, 2, 2, st);
-        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, C + 1, 2 * ldc, 2, 0, st);
-        if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 0, C + 1, 2 * ldc, 2, 1, st);
-    }
+    hipError_t e = run_product(L, m, n, s, ws, 0, 0, C, 2 * ldc, 2, 0, st);
+    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 1, C, 2 * ldc, 2, 2, st);
+    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, C + 1, 2 * ldc, 2, 0, st);
+    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 0, C + 1, 2 * ldc, 2, 1, st);
     return e;
 }
 
@@ -223,16 +211,16 @@ const char* ozimmu_status_string(ozimmu_status_t status) {
 ozimmu_status_t ozimmu_slice_geometry(int64_t rows, int64_t k, int64_t* rows_padded, int64_t* k_padded) {
     if (rows < 0 || k < 0 || rows > kMaxDim || k > kMaxDim) return OZIMMU_ERR_BAD_DIM;
     if (!rows_padded || !k_padded) return OZIMMU_ERR_NULL;
-    *rows_padded = round_up(rows, kTile);
-    *k_padded = round_up(k, kChunk);
+    *rows_padded = round_up(rows, kRowAlign);
+    *k_padded = round_up(k, kSlab);
     return OZIMMU_OK;
 }
 
 int64_t ozimmu_slice_offset(int64_t rows_padded, int64_t k_padded, int slice, int64_t row, int64_t l) {
     if (slice < 0 || row < 0 || l < 0 || row >= rows_padded || l >= k_padded) return -1;
-    const int64_t rr = row % kTile, c = (l % kStep) / 16;
-    return (int64_t)slice * rows_padded * k_padded + ((row / kTile) * (k_padded / kStep) + l / kStep) * (kTile * kStep) +
-           rr * kStep + ((c ^ ((rr >> 2) & 3)) << 4) + l % 16;
+    const int64_t rr = row % kFragRows, h = (l % kSlab) / 16;
+    return (int64_t)slice * rows_padded * k_padded + ((row / kFragRows) * (k_padded / kSlab) + l / kSlab) * kFragBytes +
+           rr * kSlab + ((h ^ ((rr >> 3) & 1)) << 4) + l % 16;
 }
 
 ozimmu_status_t ozimmu_split_rows(int64_t m, int64_t k, const double* A, int64_t lda, int num_slices,
@@ -242,8 +230,8 @@ ozimmu_status_t ozimmu_split_rows(int64_t m, int64_t k, const double* A, int64_t
     if (m == 0) return OZIMMU_OK;
     if (lda < k) return OZIMMU_ERR_BAD_LD;
     if (!exps || (k > 0 && (!A || !slices))) return OZIMMU_ERR_NULL;
-    return hip_status(launch_split_rows(A, lda, 1, m, k, num_slices, slices, round_up(m, kTile),
-                                        round_up(k, kChunk), exps, static_cast<hipStream_t>(stream)));
+    return hip_status(launch_split_rows(A, lda, 1, m, k, num_slices, slices, round_up(m, kRowAlign),
+                                        round_up(k, kSlab), exps, static_cast<hipStream_t>(stream)));
 }
 
 ozimmu_status_t ozimmu_split_cols(int64_t k, int64_t n, const double* B, int64_t ldb, int num_slices,
@@ -254,8 +242,8 @@ ozimmu_status_t ozimmu_split_cols(int64_t k, int64_t n, const double* B, int64_t
     if (ldb < n) return OZIMMU_ERR_BAD_LD;
     if (!exps || !col_scratch || (k > 0 && (!B || !slices))) return OZIMMU_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(col_scratch) % 8 != 0) return OZIMMU_ERR_WORKSPACE;
-    return hip_status(launch_split_cols(B, ldb, 1, k, n, num_slices, slices, round_up(n, kTile),
-                                        round_up(k, kChunk), exps,
+    return hip_status(launch_split_cols(B, ldb, 1, k, n, num_slices, slices, round_up(n, kRowAlign),
+                                        round_up(k, kSlab), exps,
                                         static_cast<unsigned long long*>(col_scratch),
                                         static_cast<hipStream_t>(stream)));
 }
@@ -264,33 +252,30 @@ ozimmu_status_t ozimmu_slice_gemm(int64_t m, int64_t n, int64_t k, const int8_t*
                                   int q, int64_t k0, int64_t klen, int32_t* P, int64_t ldp, void* stream) {
     if (!dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
     if (p < 1 || q < 1 || p > OZIMMU_MAX_SLICES || q > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
-    if (k0 < 0 || klen < 0 || k0 + klen > k || klen > OZIMMU_INT32_BLOCK || k0 % kChunk != 0)
+    if (k0 < 0 || klen < 0 || k0 + klen > k || klen > OZIMMU_INT32_BLOCK || k0 % kSlab != 0)
         return OZIMMU_ERR_BAD_DIM;
-    if (klen % kChunk != 0 && k0 + klen != k) return OZIMMU_ERR_BAD_DIM;
+    if (klen % kSlab != 0 && k0 + klen != k) return OZIMMU_ERR_BAD_DIM;
     if (m == 0 || n == 0) return OZIMMU_OK;
     if (ldp < n) return OZIMMU_ERR_BAD_LD;
     if (!P || (klen > 0 && (!SA || !SB))) return OZIMMU_ERR_NULL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (klen == 0) return hip_status(launch_fill_i32(P, ldp, m, n, 0, st));
-    const int64_t m_pad = round_up(m, kTile), n_pad = round_up(n, kTile), k_pad = round_up(k, kChunk);
+    const Layout L = make_layout(m, n, k, 1, false);   // the one-slice problem of slices p and q
     GemmArgs g{};
-    g.SA = SA;
-    g.SB = SB;
-    g.a_slice_stride = m_pad * k_pad;
-    g.b_slice_stride = n_pad * k_pad;
-    g.k_pad = (int)k_pad;
-    g.tiles_m = (int)(m_pad / kTile);
-    g.tiles_n = (int)(n_pad / kTile);
+    g.a_slice_stride = L.m_pad * L.k_pad;
+    g.b_slice_stride = L.n_pad * L.k_pad;
+    g.SA = SA + (int64_t)(p - 1) * g.a_slice_stride;
+    g.SB = SB + (int64_t)(q - 1) * g.b_slice_stride;
+    g.kslabs = (int)(L.k_pad / kSlab);
+    g.t_begin = (int)(k0 / kSlab);
+    g.t_end = (int)(round_up(k0 + klen, kSlab) / kSlab);
+    g.tiles_m = L.tiles_m;
+    g.tiles_n = L.tiles_n;
     g.m = (int)m;
     g.n = (int)n;
-    g.num_slices = 0;
-    g.pair_p = p;
-    g.pair_q = q;
-    g.kc_begin = (int)(k0 / kChunk);
-    g.kc_end = (int)(round_up(k0 + klen, kChunk) / kChunk);
     g.P = P;
     g.ldp = ldp;
-    return hip_status(launch_slice_gemm(g, false, st));
+    return hip_status(launch_slice_gemm(g, 1, false, st));
 }
 
 ozimmu_status_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_slices, int is_complex,
@@ -370,7 +355,7 @@ ozimmu_status_t ozimmu_zgemm(int64_t m, int64_t n, int64_t k, const double* A, i
 ozimmu_status_t ozimmu_auto_scratch_bytes(int64_t n, size_t* bytes) {
     if (n < 0 || n > kMaxDim) return OZIMMU_ERR_BAD_DIM;
     if (!bytes) return OZIMMU_ERR_NULL;
-    *bytes = 512 + sizeof(unsigned long long) * (size_t)round_up(n, kTile);
+    *bytes = 512 + sizeof(unsigned long long) * (size_t)round_up(n, kRowAlign);
     return OZIMMU_OK;
 }
 
@@ -438,7 +423,7 @@ ozimmu_status_t ozimmu_dgemm_blas(char transa, char transb, int64_t m, int64_t n
         if (!ta) e = launch_split_cols(A, lda, 1, k, m, num_slices, SC, L.n_pad, L.k_pad, EC, colmax, st);  // A: m x k
         else e = launch_split_rows(A, lda, 1, m, k, num_slices, SC, L.n_pad, L.k_pad, EC, st);              // A: k x m
     }
-    if (e == hipSuccess) e = run_product(L, n, m, num_slices, ws, 0, 0, C, ldc, 1, 3, st, 0, 0, 0, alpha, beta);
+    if (e == hipSuccess) e = run_product(L, n, m, num_slices, ws, 0, 0, C, ldc, 1, 3, st, alpha, beta);
     return hip_status(e);
 }
 
@@ -524,52 +509,19 @@ ozimmu_status_t ozimmu_dgemm_dd(int64_t m, int64_t n, int64_t k, const double* A
         if (rc != OZIMMU_OK) return rc;
     }
     unsigned char* ws = static_cast<unsigned char*>(workspace);
-    GemmArgs g{};
-    g.SA = reinterpret_cast<const int8_t*>(ws + L.off_sa[0]);
-    g.SB = reinterpret_cast<const int8_t*>(ws + L.off_sb[0]);
-    g.a_slice_stride = L.m_pad * L.k_pad;
-    g.b_slice_stride = L.n_pad * L.k_pad;
-    g.k_pad = (int)L.k_pad;
-    g.tiles_m = L.tiles_m;
-    g.tiles_n = L.tiles_n;
-    g.m = (int)m;
-    g.n = (int)n;
-    g.num_slices = num_slices;
-    g.kc_begin = 0;
-    g.kc_end = (int)(L.k_pad / kChunk);
-    g.D = ws + L.off_d;
-    g.C = C_hi;
-    g.C_lo = C_lo;
-    g.ldc = ldc;
-    g.c_inc = 1;
-    g.EA = reinterpret_cast<const int32_t*>(ws + L.off_ea[0]);
-    g.EB = reinterpret_cast<const int32_t*>(ws + L.off_eb[0]);
-    g.skip_final = 1;   // every diagonal sum stays in the workspace; the summing-up is a kernel of its own
-    hipError_t e = launch_slice_gemm(g, L.wide, st);
-    if (e == hipSuccess) e = launch_diag_sum_dd(g, L.wide, st);
-    return hip_status(e);
+    return hip_status(run_product(L, m, n, num_slices, ws, 0, 0, C_hi, ldc, 1, 0, st, 1.0, 0.0, C_lo));
 }
 
-ozimmu_status_t ozimmu_launch_plan(int64_t m, int64_t n, int64_t k, int num_slices, int* kernel, int* groups,
-                                   uint32_t* diag_masks) {
+ozimmu_status_t ozimmu_launch_plan(int64_t m, int64_t n, int64_t k, int num_slices, ozimmu_plan_t* plan) {
     if (!dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
     if (num_slices < 1 || num_slices > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
-    if (!kernel || !groups) return OZIMMU_ERR_NULL;
+    if (!plan) return OZIMMU_ERR_NULL;
     const Layout L = make_layout(m, n, k, num_slices, false);
-    unsigned masks[OZIMMU_MAX_SLICES] = {};
-    *groups = 1;
-    if (L.wide) {
-        *kernel = 2;
-        masks[0] = (1u << (num_slices + 2)) - 4u;
-    } else if (L.k_pad <= kFusedMaxK) {
-        *kernel = 1;
-        masks[0] = (1u << (num_slices + 2)) - 4u;
-    } else {
-        *kernel = 0;
-        *groups = plan_tile_sharing(L.tiles_m * L.tiles_n, num_slices, masks);
-    }
-    if (diag_masks)
-        for (int i = 0; i < OZIMMU_MAX_SLICES; ++i) diag_masks[i] = i < *groups ? masks[i] : 0u;
+    plan->tile_rows = L.tile_rows;
+    plan->tile_cols = L.tile_cols;
+    plan->workgroups = (int64_t)L.tiles_m * L.tiles_n;
+    plan->bands = num_slices > kBand ? 2 : 1;
+    plan->int32_block_steps = L.wide ? block_steps_for(num_slices) : 0;
     return OZIMMU_OK;
 }
 

@@ -11,10 +11,10 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef long long v2l __attribute__((ext_vector_type(2)));
 
 // Workgroup -> tile. Hardware deals workgroups round-robin over the 8 XCDs (each with its own
-// L2); give every XCD a contiguous run of tiles, ordered in column panels 4 tiles tall so that
-// the 32 workgroups resident on an XCD share A and B panels through that L2.
+// L2); give every XCD a contiguous run of tiles, ordered in column panels 8 tiles tall so that
+// the 32 workgroups resident on an XCD (8 x 4 tiles) share A and B panels through that L2.
 __device__ __forceinline__ void tile_of_logical(int logical, int tiles_m, int tiles_n, int& tm, int& tn) {
-    constexpr int GM = 4;
+    constexpr int GM = 8;
     const int per_group = GM * tiles_n;
     const int group = logical / per_group;
     const int first_m = group * GM;

@@ -8,49 +8,43 @@
 
 namespace ozimmu {
 
-constexpr int kTile = 256;          // macro tile edge in rows of A / rows of B^T (= OZIMMU_ROW_ALIGN)
-constexpr int kChunk = 128;         // granularity of k in the API (= OZIMMU_K_ALIGN)
-constexpr int kStep = 64;           // k-extent of one contiguous slice block and of one pipeline step (= OZIMMU_K_STEP)
-constexpr int kBlockBytes = kTile * kStep;  // one block of a slice tensor: 256 rows x 64 bytes
-constexpr int kTileElems = kTile * kTile;
+constexpr int kRowAlign = OZIMMU_ROW_ALIGN;   // slice rows are padded to a multiple of this (128)
+constexpr int kSlab = OZIMMU_K_ALIGN;         // k-extent of one MFMA operand fragment and of one pipeline step (32)
+constexpr int kFragRows = 32;                 // rows of one fragment
+constexpr int kFragBytes = kFragRows * kSlab; // 1 KiB: what one wave-wide direct load moves and one ds_read_b128 reads
+constexpr int kBand = 8;                      // anti-diagonals whose INT32 sums a wavefront holds at a time
 
 static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
-// Arguments of the slice-product kernel. One launch covers every macro tile of C.
+// Wavefront grid of the product kernel for a slice count: 2 x 4 wavefronts of 32 x 32 outputs (a
+// 64 x 128 tile of C) while two pipeline stages of all slices fit the LDS, 2 x 2 beyond.
+static inline void tile_waves(int s, int* wm, int* wn) {
+    *wm = 2;
+    *wn = s <= 13 ? 4 : 2;
+}
+
+// Arguments of the slice-product kernel. One launch covers every tile of C.
 struct GemmArgs {
-    const int8_t* SA;      // slice tensor of A   (tiled layout, see ozimmu.h)
-    const int8_t* SB;      // slice tensor of B^T
+    const int8_t* SA;        // slice tensor of A   (fragment layout, see ozimmu.h)
+    const int8_t* SB;        // slice tensor of B^T
     int64_t a_slice_stride;  // bytes between consecutive slices of A
     int64_t b_slice_stride;
-    int k_pad;             // padded row length
+    int kslabs;              // padded row length in slabs of 32
+    int t_begin, t_end;      // slab range of the walk along k
     int tiles_m, tiles_n;
-    int m, n;              // true extent of C
-    int num_slices;        // full mode: diagonals num_slices+1 .. 2
-    int pair_p, pair_q;    // pair mode (pair_p > 0): only this pair, raw INT32 out
-    int kc_begin, kc_end;  // k-range in chunks of kChunk
-    void* D;               // per-diagonal integer sums that leave the registers (INT32 or INT64)
-    int32_t* P;            // pair mode output, row-major
+    int m, n;                // true extent of C
+    int block_steps;         // steps after which the INT32 sums are moved into the INT64 sums in D (0: never)
+    long long* D;            // INT64 diagonal sums (k-blocking only)
+    int32_t* P;              // pair mode (P != nullptr): raw INT32 product of the slices SA, SB point at
     int64_t ldp;
-    double* C;             // full mode output
-    int64_t ldc;           // in doubles
-    int c_inc;             // distance in doubles between consecutive columns (2 for a complex plane)
-    int c_mode;            // 0: C = G, 1: C = C + G, 2: C = C - G, 3: C = alpha G (+ beta C if beta != 0)
-    double alpha, beta;    // c_mode 3 only
+    double* C;               // output
+    int64_t ldc;             // in doubles
+    int c_inc;               // distance in doubles between consecutive columns (2 for a complex plane)
+    int c_mode;              // 0: C = G, 1: C = C + G, 2: C = C - G, 3: C = alpha G (+ beta C if beta != 0)
+    double alpha, beta;      // c_mode 3 only
+    double* C_lo;            // low parts of a double-double result (double-double summing-up only)
     const int32_t* EA;
     const int32_t* EB;
-    // several workgroups per macro tile (small problems): workgroup group g of a tile walks the
-    // diagonals in diag_mask[g] (bit d = diagonal d) and a second kernel forms the FP64 sum
-    int skip_final;                 // leave every diagonal sum in D and write no C (a separate kernel sums)
-    double* C_lo;                   // low parts of a double-double result (sum kernel only)
-    int split_groups;               // 0 or 1: off
-    unsigned diag_mask[OZIMMU_MAX_SLICES];
-    // second product of the register-resident kernel (dual != 0): C = G(SA,SB) + G(SA2,SB2) if
-    // dual == 1, C = G(SA,SB) - G(SA2,SB2) if dual == 2, each G scaled by its own exponents
-    int dual;
-    const int8_t* SA2;
-    const int8_t* SB2;
-    const int32_t* EA2;
-    const int32_t* EB2;
 };
 
 // negate: emit the slices of -A (-B) instead: same exponents, every slice with the opposite sign
@@ -61,15 +55,8 @@ hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, i
 hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n, int s,
                              int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
                              unsigned long long* colmax, hipStream_t st, bool negate = false);
-hipError_t launch_slice_gemm(const GemmArgs& args, bool wide, hipStream_t st);
-// How many workgroups share a macro tile for a given tile count and slice count, and which diagonals each takes.
-int plan_tile_sharing(int tiles, int s, unsigned* masks);
-// Double-double sum of the diagonal sums left in D by a launch with skip_final (C = high, C_lo = low parts).
-hipError_t launch_diag_sum_dd(const GemmArgs& args, bool wide, hipStream_t st);
-// Variant for short inner dimensions that keeps the FP64 sum in registers (no use of args.D).
-constexpr int kFusedMaxK = 1024;
-bool fused_gemm_applies(const GemmArgs& args, bool wide);
-hipError_t launch_fused_gemm(const GemmArgs& args, hipStream_t st);
+// Slice products of the pairs p + q <= s + 1 with the FP64 sum (dd: double-double sum into C, C_lo).
+hipError_t launch_slice_gemm(const GemmArgs& args, int s, bool dd, hipStream_t st);
 // Slice-count scan: adds, for s = 1 .. 16, the mantissa bits s slices would lose into sums[s - 1].
 hipError_t launch_loss_scan_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k,
                                  unsigned long long* sums, hipStream_t st);

@@ -3,8 +3,8 @@
 // One power-of-two exponent per row of M = A or B^T (exponent step of SplitInt), then every element
 // is cut by bit operations (Section 4.1) into signed 7-bit chunks of its significand, placed
 // relative to the row exponent (its slice-extraction loop). Output: padded INT8 slice tensors, zero outside the
-// matrix, in the tiled and column-swizzled block layout that the slice-product kernel copies
-// linearly into LDS (blocks of 256 rows x 64 bytes; the layout is defined with the C ABI).
+// matrix, in the fragment layout that the slice-product kernel copies linearly into LDS (fragments of
+// 32 rows x 32 bytes, the MFMA operand of one wavefront; the layout is defined with the C ABI).
 //
 // Both kernels are HBM-bound: 8 B read per element (16 B for B, whose column maxima need a
 // pass of their own) and num_slices bytes written.
@@ -80,11 +80,12 @@ __device__ __forceinline__ uint32_t packed_slice(const Fixed (&x)[4], const Sign
 }
 
 // Byte offset, inside one slice, of the 4-byte word that holds positions l0 .. l0+3 (l0 % 4 == 0)
-// of padded row r: blocks of 256 rows x 64 bytes, 16-byte columns swizzled with bits 2..3 of the row.
+// of padded row r: fragments of 32 rows x 32 bytes, the two 16-byte halves of a row swapped in
+// rows 8..15 and 24..31 of a fragment.
 __device__ __forceinline__ int64_t word_offset(int64_t r, int64_t l0, int64_t k_pad) {
-    const int64_t rr = r & (kTile - 1);
-    const int64_t c = (l0 & (kStep - 1)) >> 4;
-    return ((r / kTile) * (k_pad / kStep) + l0 / kStep) * kBlockBytes + rr * kStep + ((c ^ ((rr >> 2) & 3)) << 4) + (l0 & 15);
+    const int64_t rr = r & (kFragRows - 1);
+    const int64_t h = (l0 & (kSlab - 1)) >> 4;
+    return ((r / kFragRows) * (k_pad / kSlab) + l0 / kSlab) * kFragBytes + rr * kSlab + ((h ^ ((rr >> 3) & 1)) << 4) + (l0 & 15);
 }
 
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
@@ -97,11 +98,16 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
 }
 
 // ------------------------------------------------------------------------------ rows of A
-// One workgroup per padded row; a thread owns words of four consecutive elements (one 32-bit
-// store per slice). Pass 1: maximum of the |x| bit patterns (monotone in |x|), wave reduction
-// then LDS. Pass 2: emission. A row of up to 8192 elements stays in registers between the two
-// passes (CACHED), so A is read from memory once; longer rows are read twice.
+// One workgroup per four consecutive padded rows: a quarter of a wavefront (16 lanes) works on a row,
+// a thread owns words of four consecutive elements (one 32-bit store per slice), a wave-wide load
+// covers 64 consecutive elements of each of the four rows, and a wave-wide store fills, per 32
+// positions of k, the 128 contiguous bytes that four consecutive rows occupy in a fragment: full
+// lines both ways. Pass 1: maximum of the |x| bit patterns (monotone in |x|), shuffles within the
+// 16 lanes, then LDS across the wavefronts. Pass 2: emission. Rows of up to 8192 elements stay in
+// registers between the two passes (CACHED), so A is read from memory once; longer rows are read twice.
 constexpr int kRowCacheWords = 8;   // words of 4 elements per thread that fit the register cache
+constexpr int kRowGroup = 4;        // rows per workgroup
+constexpr int kRowWavesMax = 16;
 
 template <bool VEC>   // VEC: unit stride and 16-byte aligned rows, two 16-byte loads per word
 __device__ __forceinline__ void load_word(const unsigned long long* src, int64_t l0, int64_t k, int inc,
@@ -129,32 +135,29 @@ __device__ __forceinline__ void emit_word(const unsigned long long (&b)[4], int 
 }
 
 template <bool WIDE, bool CACHED, bool VEC>
-__global__ __launch_bounds__(256) void split_rows_kernel(const double* __restrict__ A, int64_t lda,
-                                                         int inc, int m, int64_t k, int s,
-                                                         int8_t* __restrict__ S, int64_t m_pad,
-                                                         int64_t k_pad, int32_t* __restrict__ Eout,
-                                                         unsigned long long flip) {   // sign bit, or 0: slices of -A
-    const int row = blockIdx.x;
+__global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_kernel(const double* __restrict__ A, int64_t lda,
+                                                                       int inc, int m, int64_t k, int s,
+                                                                       int8_t* __restrict__ S, int64_t m_pad,
+                                                                       int64_t k_pad, int32_t* __restrict__ Eout,
+                                                                       unsigned long long flip) {   // sign bit, or 0: slices of -A
     const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const int r4 = lane >> 4, c16 = lane & 15;
+    const int row = blockIdx.x * kRowGroup + r4;
+    const bool live = row < m;                       // padding rows: zeros in every slice
     const int64_t slice_stride = m_pad * k_pad;
-    const int64_t words = k_pad / 4;
+    // chunk c of a row = its elements [64 c, 64 c + 64); the wavefronts take the chunks round-robin
+    const int64_t chunks = (k_pad + 63) / 64;
+    const unsigned long long* src = reinterpret_cast<const unsigned long long*>(A) + (int64_t)(live ? row : 0) * lda;
+    const int64_t k_live = live ? k : 0;             // a padding row reads nothing
 
-    if (row >= m) {  // padding rows: zeros in every slice
-        for (int64_t w = tid; w < words; w += 256) {
-            const int64_t off = word_offset(row, w * 4, k_pad);
-            for (int p = 0; p < s; ++p) *reinterpret_cast<uint32_t*>(S + p * slice_stride + off) = 0u;
-        }
-        return;
-    }
-
-    const unsigned long long* src = reinterpret_cast<const unsigned long long*>(A) + (int64_t)row * lda;
     unsigned long long cache[CACHED ? kRowCacheWords : 1][4];
     unsigned long long mx = 0;
     if (CACHED) {
 #pragma unroll
         for (int j = 0; j < kRowCacheWords; ++j) {
-            const int64_t w = tid + 256 * j;
-            if (w < words) load_word<VEC>(src, w * 4, k, inc, cache[j]);
+            const int64_t l0 = ((int64_t)(wave + nwaves * j) * 16 + c16) * 4;
+            if (l0 < k_live) load_word<VEC>(src, l0, k_live, inc, cache[j]);
             else cache[j][0] = cache[j][1] = cache[j][2] = cache[j][3] = 0ull;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -163,9 +166,10 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const double* __restric
             }
         }
     } else {
-        for (int64_t w = tid; w < words; w += 256) {
+        for (int64_t c = wave; c < chunks; c += nwaves) {
+            const int64_t l0 = (c * 16 + c16) * 4;
             unsigned long long b[4];
-            load_word<VEC>(src, w * 4, k, inc, b);
+            load_word<VEC>(src, l0, k_live, inc, b);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const unsigned long long a = b[u] & kAbsMask;
@@ -173,27 +177,33 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const double* __restric
             }
         }
     }
-    mx = wave_max_u64(mx);
-    __shared__ unsigned long long wmax[4];
-    if ((tid & 63) == 0) wmax[tid >> 6] = mx;
-    __syncthreads();
-    mx = wmax[0];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) mx = wmax[w] > mx ? wmax[w] : mx;
+    for (int off = 8; off >= 1; off >>= 1) {
+        const unsigned long long o = __shfl_xor(mx, off, 64);
+        mx = o > mx ? o : mx;
+    }
+    __shared__ unsigned long long wmax[kRowWavesMax][kRowGroup];
+    if (c16 == 0) wmax[wave][r4] = mx;
+    __syncthreads();
+    mx = wmax[0][r4];
+    for (int w = 1; w < nwaves; ++w) mx = wmax[w][r4] > mx ? wmax[w][r4] : mx;
     const int E = exponent_of_max(mx);
-    if (tid == 0) Eout[row] = E;
+    if (live && wave == 0 && c16 == 0) Eout[row] = E;
 
     if (CACHED) {
 #pragma unroll
         for (int j = 0; j < kRowCacheWords; ++j) {
-            const int64_t w = tid + 256 * j;
-            if (w < words) emit_word<WIDE>(cache[j], E, s, S + word_offset(row, w * 4, k_pad), slice_stride, flip);
+            const int64_t l0 = ((int64_t)(wave + nwaves * j) * 16 + c16) * 4;
+            if (l0 < k_pad) emit_word<WIDE>(cache[j], E, s, S + word_offset(row, l0, k_pad), slice_stride, flip);
         }
     } else {
-        for (int64_t w = tid; w < words; w += 256) {
-            unsigned long long b[4];
-            load_word<VEC>(src, w * 4, k, inc, b);
-            emit_word<WIDE>(b, E, s, S + word_offset(row, w * 4, k_pad), slice_stride, flip);
+        for (int64_t c = wave; c < chunks; c += nwaves) {
+            const int64_t l0 = (c * 16 + c16) * 4;
+            if (l0 < k_pad) {
+                unsigned long long b[4];
+                load_word<VEC>(src, l0, k_live, inc, b);
+                emit_word<WIDE>(b, E, s, S + word_offset(row, l0, k_pad), slice_stride, flip);
+            }
         }
     }
 }
@@ -277,24 +287,26 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
             }
         }
         __syncthreads();
-        // Write-out: per slice the tile is 2 k-steps x 64 rows x four 16-byte columns; in the
-        // block layout 16 consecutive rows of one k-step are 1 KiB contiguous, so consecutive
-        // lanes store consecutive 16-byte columns.
+        // Write-out: per slice the tile is 2 row groups x 4 slabs = 8 fragments of 1 KiB, each
+        // contiguous in the slice tensor: consecutive lanes store consecutive 16-byte units.
         for (int pp = 0; pp < np; ++pp) {
             int8_t* dst = S + (int64_t)(p0 + pp - 1) * slice_stride;
 #pragma unroll
             for (int it = 0; it < 2; ++it) {
                 const int unit = it * 256 + tid;       // 0..511
-                const int ks2 = unit >> 8;              // k-step inside the tile
-                const int r = (unit >> 2) & 63;         // row inside the tile
-                const int pc = unit & 3;                // physical 16-byte column
-                const int64_t jr = (int64_t)blockIdx.x * kColTileJ + r;
-                const int rr = (int)(jr & (kTile - 1));
-                const int c = pc ^ ((rr >> 2) & 3);     // logical column stored there
-                const int w0 = ks2 * 16 + c * 4;        // first word of that column in the LDS row
+                const int f = unit >> 6;                // fragment inside the tile
+                const int ks = f >> 1, rg = f & 1;      // its slab and its row group
+                const int pos = unit & 63;              // 16-byte unit inside the fragment
+                const int rr = pos >> 1;                // fragment row
+                const int h = (pos & 1) ^ ((rr >> 3) & 1);   // which half of the row's 32 positions is stored there
+                const int r = rg * kFragRows + rr;      // row inside the tile (a column of B)
+                const int w0 = ks * 8 + h * 4;          // first word of that half in the LDS row
                 uint4 v = {tile[pp][r][w0], tile[pp][r][w0 + 1], tile[pp][r][w0 + 2], tile[pp][r][w0 + 3]};
-                const int64_t off = ((jr / kTile) * (k_pad / kStep) + (lbase / kStep + ks2)) * kBlockBytes + rr * kStep + pc * 16;
-                *reinterpret_cast<uint4*>(dst + off) = v;
+                const int64_t slab = lbase / kSlab + ks;
+                if (slab < k_pad / kSlab) {
+                    const int64_t off = (((int64_t)blockIdx.x * 2 + rg) * (k_pad / kSlab) + slab) * kFragBytes + pos * 16;
+                    *reinterpret_cast<uint4*>(dst + off) = v;
+                }
             }
         }
         __syncthreads();
@@ -492,12 +504,15 @@ static int column_band(int64_t k, int64_t n) {
 
 hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k, int s,
                              int8_t* S, int64_t m_pad, int64_t k_pad, int32_t* E, hipStream_t st, bool negate) {
-    if (m_pad == 0) return hipSuccess;
+    if (m_pad == 0 || k_pad == 0) return hipSuccess;
     const unsigned long long flip = negate ? 1ull << 63 : 0ull;
     const bool wide = s > 9;
-    const bool cached = k_pad <= 4 * 256 * kRowCacheWords;
+    // a wavefront covers 64 elements of each of its four rows per word it caches
+    const int64_t want = (k_pad + 64 * kRowCacheWords - 1) / (64 * kRowCacheWords);
+    const int nwaves = (int)(want < 1 ? 1 : want > kRowWavesMax ? kRowWavesMax : want);
+    const bool cached = k_pad <= (int64_t)64 * kRowCacheWords * nwaves;
     const bool vec = inc == 1 && lda % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
-    const dim3 grid((unsigned)m_pad), block(256);
+    const dim3 grid((unsigned)(m_pad / kRowGroup)), block(64 * nwaves);
 #define OZ_ROWS(W, C, V) split_rows_kernel<W, C, V><<<grid, block, 0, st>>>(A, lda * inc, inc, (int)m, k, s, S, m_pad, k_pad, E, flip)
     if (wide) {
         if (cached) { if (vec) OZ_ROWS(true, true, true); else OZ_ROWS(true, true, false); }
@@ -531,7 +546,8 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    const dim3 grid((unsigned)(n_pad / kColTileJ), (unsigned)(k_pad / kColTileL));
+    if (k_pad == 0) return hipSuccess;
+    const dim3 grid((unsigned)(n_pad / kColTileJ), (unsigned)((k_pad + kColTileL - 1) / kColTileL));
     if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, flip);
     else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, flip);
     return hipGetLastError();

@@ -14,9 +14,9 @@ _LIB_PATH = Path(__file__).resolve().parent / "libozimmu.so"
 (OK, ERR_BAD_DIM, ERR_BAD_LD, ERR_BAD_SLICES, ERR_NULL, ERR_WORKSPACE, ERR_HIP, ERR_NOT_IMPLEMENTED,
  ERR_TOO_LARGE) = range(9)
 MAX_SLICES = 16
-ROW_ALIGN = 256
-K_ALIGN = 128
-K_STEP = 64
+ROW_ALIGN = 128
+K_ALIGN = 32
+FRAG_ROWS = 32
 INT32_BLOCK = 131072
 WORKSPACE_ALIGN = 256
 STATIC_SCRATCH_BYTES = 64 << 20
@@ -26,14 +26,20 @@ EXPORTS = (
     "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_static", "ozimmu_dgemm_stage",
     "ozimmu_launch_plan", "ozimmu_dgemm_dd", "ozimmu_dgemm_blas", "ozimmu_zgemm_blas_workspace_bytes", "ozimmu_zgemm_blas",
     "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices", "ozimmu_auto_num_slices_blas",
-    "ozimmu_probe_int8_mfma", "ozimmu_probe_lds_read",
 )
+PROBE_EXPORTS = ("ozimmu_probe_int8_mfma",)      # include/ozimmu_probe.h: measurement utility, not the product path
 
 
 class OzimmuError(RuntimeError):
     def __init__(self, code: int, what: str):
         super().__init__(f"ozimmu error {code}: {what}")
         self.code = code
+
+
+class Plan(ctypes.Structure):
+    """ozimmu_plan_t of include/ozimmu.h."""
+    _fields_ = [("tile_rows", ctypes.c_int), ("tile_cols", ctypes.c_int), ("workgroups", ctypes.c_int64),
+                ("bands", ctypes.c_int), ("int32_block_steps", ctypes.c_int)]
 
 
 _lib = None
@@ -71,7 +77,7 @@ def lib() -> ctypes.CDLL:
         L.ozimmu_dgemm_stage.restype = i32
         L.ozimmu_dgemm_stage.argtypes = [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp, sz, vp]
         L.ozimmu_launch_plan.restype = i32
-        L.ozimmu_launch_plan.argtypes = [i64, i64, i64, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
+        L.ozimmu_launch_plan.argtypes = [i64, i64, i64, i32, ctypes.POINTER(Plan)]
         L.ozimmu_dgemm_dd.restype = i32
         L.ozimmu_dgemm_dd.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, i32, vp, sz, vp]
         L.ozimmu_dgemm_blas.restype = i32
@@ -92,9 +98,7 @@ def lib() -> ctypes.CDLL:
                                                   ctypes.c_double, i32, vp, sz, ctypes.POINTER(i32), vp, vp]
         dp = ctypes.POINTER(ctypes.c_double)
         L.ozimmu_probe_int8_mfma.restype = i32
-        L.ozimmu_probe_int8_mfma.argtypes = [i32, i32, dp, dp]
-        L.ozimmu_probe_lds_read.restype = i32
-        L.ozimmu_probe_lds_read.argtypes = [i32, i32, dp]
+        L.ozimmu_probe_int8_mfma.argtypes = [i32, i32, i32, dp, dp]
         _lib = L
     return _lib
 
@@ -148,12 +152,12 @@ def unpack_slices(raw, num_slices: int, rows: int, k: int):
     assert flat.size == num_slices * rp * kp
     if flat.size == 0:
         return flat.reshape(num_slices, rp, kp)
-    # offsets are separable: offset(s, r, l) = s * rp * kp + f(r, 0) + g(r % 256, l)
-    row_part = np.array([slice_offset(rp, kp, 0, r, 0) for r in range(0, rp, ROW_ALIGN)], dtype=np.int64)
-    in_block = np.array([[slice_offset(rp, kp, 0, rr, l) for l in range(K_STEP)] for rr in range(ROW_ALIGN)],
-                        dtype=np.int64)                      # [256][64], block 0
-    step_part = np.array([slice_offset(rp, kp, 0, 0, l) for l in range(0, kp, K_STEP)], dtype=np.int64)
-    idx = (row_part[:, None, None, None] + in_block[None, :, None, :] + step_part[None, None, :, None])
+    # offsets are separable: offset(s, r, l) = s * rp * kp + f(r - r % 32, 0) + g(r % 32, l % 32) + h(0, l - l % 32)
+    row_part = np.array([slice_offset(rp, kp, 0, r, 0) for r in range(0, rp, FRAG_ROWS)], dtype=np.int64)
+    in_frag = np.array([[slice_offset(rp, kp, 0, rr, l) for l in range(K_ALIGN)] for rr in range(FRAG_ROWS)],
+                       dtype=np.int64)                       # [32][32], fragment 0
+    slab_part = np.array([slice_offset(rp, kp, 0, 0, l) for l in range(0, kp, K_ALIGN)], dtype=np.int64)
+    idx = (row_part[:, None, None, None] + in_frag[None, :, None, :] + slab_part[None, None, :, None])
     idx = idx.reshape(rp, kp)                                # [row][l]
     out = np.empty((num_slices, rp, kp), dtype=flat.dtype)
     for s_ in range(num_slices):
@@ -219,12 +223,11 @@ def zgemm(A, B, C, num_slices: int, workspace, stream=None) -> None:
                               _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
 
 
-def launch_plan(m: int, n: int, k: int, num_slices: int):
-    """(kernel, groups, masks): which kernel ozimmu_dgemm uses and how diagonals are shared (see ozimmu.h)."""
-    kernel, groups = ctypes.c_int(), ctypes.c_int()
-    masks = (ctypes.c_uint32 * MAX_SLICES)()
-    _check(lib().ozimmu_launch_plan(m, n, k, num_slices, ctypes.byref(kernel), ctypes.byref(groups), masks))
-    return kernel.value, groups.value, list(masks)[: groups.value]
+def launch_plan(m: int, n: int, k: int, num_slices: int) -> dict:
+    """How ozimmu_dgemm runs a shape (ozimmu_plan_t as a dict; see ozimmu.h)."""
+    plan = Plan()
+    _check(lib().ozimmu_launch_plan(m, n, k, num_slices, ctypes.byref(plan)))
+    return {name: getattr(plan, name) for name, _ in Plan._fields_}
 
 
 def dgemm_dd(A, B, C_hi, C_lo, num_slices: int, workspace, stream=None) -> None:
@@ -311,18 +314,11 @@ def auto_num_slices_blas(transa: str, transb: str, m: int, n: int, k: int, A, ld
     return s.value, sums
 
 
-def probe_int8_mfma(pattern: int, iters: int = 200000):
-    """(10^12 INT8 ops/s, shader MHz) of a register-only MFMA issue loop; see ozimmu.h."""
+def probe_int8_mfma(pattern: int, shape: int = 0, iters: int = 200000):
+    """(10^12 INT8 ops/s, shader MHz) of a register-only MFMA issue loop; see ozimmu_probe.h."""
     tops, mhz = ctypes.c_double(), ctypes.c_double()
-    _check(lib().ozimmu_probe_int8_mfma(pattern, iters, ctypes.byref(tops), ctypes.byref(mhz)))
+    _check(lib().ozimmu_probe_int8_mfma(pattern, shape, iters, ctypes.byref(tops), ctypes.byref(mhz)))
     return tops.value, mhz.value
-
-
-def probe_lds_read(pattern: int, iters: int = 20000) -> float:
-    """LDS 16-byte read throughput in bytes per ns and compute unit; see ozimmu.h."""
-    out = ctypes.c_double()
-    _check(lib().ozimmu_probe_lds_read(pattern, iters, ctypes.byref(out)))
-    return out.value
 
 
 def alloc_workspace(m: int, n: int, k: int, num_slices: int, is_complex: bool = False, device="cuda"):

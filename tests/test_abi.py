@@ -9,10 +9,11 @@ import pytest
 from paper_2306_11975_amd import ozimmu
 
 HEADER = Path(__file__).resolve().parents[1] / "include" / "ozimmu.h"
+PROBE_HEADER = HEADER.with_name("ozimmu_probe.h")
 
 
-def declared_functions():
-    text = HEADER.read_text()
+def declared_functions(header=HEADER):
+    text = header.read_text()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ozimmu_[a-z_0-9]+)\s*\(", text)))
 
@@ -20,8 +21,10 @@ def declared_functions():
 def test_header_and_binding_agree_and_library_exports_everything():
     names = declared_functions()
     assert set(names) == set(ozimmu.EXPORTS)
+    probes = declared_functions(PROBE_HEADER)
+    assert set(probes) == set(ozimmu.PROBE_EXPORTS)
     L = ozimmu.lib()
-    for name in names:
+    for name in names + probes:
         assert getattr(L, name) is not None
 
 
@@ -33,30 +36,33 @@ def test_status_strings():
 
 
 def test_geometry_and_workspace_size():
-    assert ozimmu.slice_geometry(1, 1) == (256, 128)
-    assert ozimmu.slice_geometry(256, 128) == (256, 128)
-    assert ozimmu.slice_geometry(257, 129) == (512, 256)
+    assert ozimmu.slice_geometry(1, 1) == (128, 32)
+    assert ozimmu.slice_geometry(128, 32) == (128, 32)
+    assert ozimmu.slice_geometry(129, 33) == (256, 64)
     assert ozimmu.slice_geometry(0, 0) == (0, 0)
     s, m, n, k = 8, 8192, 8192, 8192
     ws = ozimmu.workspace_bytes(m, n, k, s)
-    # slices of A and B, exponents, column maxima and s INT32 diagonal buffers
-    lower = s * m * k * 2 + s * m * n * 4
+    # slices of A and B, exponents and column maxima: every integer sum stays in registers
+    lower = s * m * k * 2
     assert lower <= ws <= lower + 4 * (m + n) + 8 * n + 16 * 256
-    # long k: a diagonal no longer fits one INT32 block, the diagonal sums are INT64
+    # long k: a diagonal no longer fits one INT32 block, INT64 diagonal sums are kept in the workspace
     ws_wide = ozimmu.workspace_bytes(4096, 4096, 131072, 8)
     assert ws_wide >= 8 * 4096 * 131072 * 2 + 8 * 4096 * 4096 * 8
     assert ozimmu.workspace_bytes(64, 64, 64, 3, True) > ozimmu.workspace_bytes(64, 64, 64, 3, False)
 
 
-def test_slice_offset_is_a_bijection_with_contiguous_blocks():
+def test_slice_offset_is_a_bijection_with_contiguous_fragments():
     import numpy as np
 
-    rp, kp = ozimmu.slice_geometry(300, 200)   # 512 x 256
+    rp, kp = ozimmu.slice_geometry(300, 200)   # 384 x 224
+    assert (rp, kp) == (384, 224)
     offs = np.array([[ozimmu.slice_offset(rp, kp, 0, r, l) for l in range(kp)] for r in range(rp)])
     assert sorted(offs.reshape(-1).tolist()) == list(range(rp * kp))
-    # a block of 256 rows x 64 positions is one contiguous 16 KiB run; 16 bytes stay together
-    blk = offs[256:512, 64:128]
-    assert blk.min() == (1 * (kp // 64) + 1) * 16384 and blk.max() == blk.min() + 16383
+    # a fragment of 32 rows x 32 positions is one contiguous 1 KiB run; a row's 32 positions are 32
+    # contiguous bytes; 16 bytes stay together
+    frag = offs[64:96, 32:64]
+    assert frag.min() == (2 * (kp // 32) + 1) * 1024 and frag.max() == frag.min() + 1023
+    assert all(frag[r].max() - frag[r].min() == 31 and frag[r].min() == frag.min() + 32 * r for r in range(32))
     assert (np.diff(offs[:, :16], axis=1) == 1).all()
     assert ozimmu.slice_offset(rp, kp, 2, 0, 0) == 2 * rp * kp
     assert ozimmu.slice_offset(rp, kp, 0, rp, 0) == -1 and ozimmu.slice_offset(rp, kp, 0, 0, kp) == -1
@@ -99,7 +105,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.ozimmu_split_cols(4, 4, fake, 4, 3, fake, fake, None, None) == 4
     assert L.ozimmu_split_cols(4, 4, fake, 4, 3, fake, fake, ctypes.c_void_p(12), None) == 5
     assert L.ozimmu_slice_gemm(4, 4, 256, fake, fake, 0, 1, 0, 128, fake, 4, None) == 3
-    assert L.ozimmu_slice_gemm(4, 4, 256, fake, fake, 1, 1, 64, 128, fake, 4, None) == 1   # k0 not aligned
+    assert L.ozimmu_slice_gemm(4, 4, 256, fake, fake, 1, 1, 48, 128, fake, 4, None) == 1   # k0 not aligned
     assert L.ozimmu_slice_gemm(4, 4, 256, fake, fake, 1, 1, 0, 100, fake, 4, None) == 1    # ragged inside
     assert L.ozimmu_slice_gemm(4, 4, 256, fake, fake, 1, 1, 128, 256, fake, 4, None) == 1  # beyond k
     assert L.ozimmu_slice_gemm(4, 4, 1 << 18, fake, fake, 1, 1, 0, (1 << 17) + 128, fake, 4, None) == 1
@@ -108,35 +114,24 @@ def test_argument_errors_are_reported_before_any_launch():
 
 
 def test_launch_plan_host_logic():
-    # the headline shape: 1024 tiles = 4 full rounds of the 256 CUs, one workgroup per tile
-    assert ozimmu.launch_plan(8192, 8192, 8192, 8) == (0, 1, [(1 << 10) - 4])
-    # short k: register-resident kernel; long diagonals: INT64 sums
-    assert ozimmu.launch_plan(4096, 4096, 256, 7)[0] == 1
-    assert ozimmu.launch_plan(4096, 4096, 131072, 8)[0] == 2
-    assert ozimmu.launch_plan(64, 64, 16384, 8)[0] == 0 and ozimmu.launch_plan(64, 64, 16385, 8)[0] == 2
-    # tile counts that do not fill the chip: diagonals shared out, every diagonal exactly once, loads balanced
-    for (size, s) in ((2048, 8), (3072, 7), (6144, 8), (1536, 13), (2048, 2), (2048, 16)):
-        kernel, groups, masks = ozimmu.launch_plan(size, size, size, s)
-        assert kernel == 0 and 1 <= groups <= (s + 1) // 2 and len(masks) == groups
-        seen = 0
-        loads = []
-        for mk in masks:
-            assert mk and not (seen & mk)
-            seen |= mk
-            loads.append(sum(d - 1 for d in range(2, s + 2) if mk >> d & 1))
-        assert seen == (1 << (s + 2)) - 4
-        assert max(loads) - min(loads) <= s            # longest-first assignment
-        tiles = (size // 256) ** 2
-        rounds = lambda g: -(-((tiles + 7) // 8 * 8 * g) // 256)
-        assert rounds(groups) * max(loads) <= rounds(1) * (s * (s + 1) // 2)
-    assert ozimmu.launch_plan(2048, 2048, 2048, 8)[1] == 4
-    assert ozimmu.launch_plan(6144, 6144, 6144, 8)[1] == 4
-    assert ozimmu.launch_plan(2048, 2048, 2048, 2)[1] == 1
+    # the headline shape: 64 x 128 tiles, 8192 workgroups = 32 full rounds of the 256 CUs, one band, no k-blocking
+    assert ozimmu.launch_plan(8192, 8192, 8192, 8) == {"tile_rows": 64, "tile_cols": 128, "workgroups": 8192,
+                                                       "bands": 1, "int32_block_steps": 0}
+    assert ozimmu.launch_plan(8192, 8192, 8192, 10)["bands"] == 2
+    assert ozimmu.launch_plan(100, 100, 100, 16) == {"tile_rows": 64, "tile_cols": 64, "workgroups": 4,
+                                                     "bands": 2, "int32_block_steps": 0}
+    # k-blocking starts where the longest diagonal (s pairs) exceeds 2^17 products: steps of 32 positions
+    assert ozimmu.launch_plan(4096, 4096, 131072, 8)["int32_block_steps"] == 512
+    assert ozimmu.launch_plan(64, 64, 16384, 8)["int32_block_steps"] == 0
+    assert ozimmu.launch_plan(64, 64, 16385, 8)["int32_block_steps"] == 512
+    for s in range(1, 17):
+        steps = ozimmu.launch_plan(1, 1, 1 << 22, s)["int32_block_steps"]
+        assert steps * 32 * s <= ozimmu.INT32_BLOCK < (steps + 1) * 32 * s
     L = ozimmu.lib()
-    kern, grp = ctypes.c_int(), ctypes.c_int()
-    assert L.ozimmu_launch_plan(-1, 1, 1, 3, ctypes.byref(kern), ctypes.byref(grp), None) == 1
-    assert L.ozimmu_launch_plan(1, 1, 1, 0, ctypes.byref(kern), ctypes.byref(grp), None) == 3
-    assert L.ozimmu_launch_plan(1, 1, 1, 3, None, ctypes.byref(grp), None) == 4
+    plan = ozimmu.Plan()
+    assert L.ozimmu_launch_plan(-1, 1, 1, 3, ctypes.byref(plan)) == 1
+    assert L.ozimmu_launch_plan(1, 1, 1, 0, ctypes.byref(plan)) == 3
+    assert L.ozimmu_launch_plan(1, 1, 1, 3, None) == 4
 
 
 def test_blas_call_argument_errors():
