@@ -19,11 +19,16 @@
 // workspace (k-blocking) and the FP64 sum is formed from those.
 //
 // Data path of a step: global -> LDS with wave-wide direct loads (global_load_lds_dwordx4, no
-// staging registers; a fragment is 1 KiB contiguous in memory and in LDS), two or three LDS stages;
+// staging registers; a fragment is 1 KiB contiguous in memory and in LDS), two or three LDS stages
+// (as many as fit 160 KiB);
 // LDS -> registers with ds_read_b128 (fragment rows are 32 bytes with the two 16-byte halves
 // swapped in rows 8..15 and 24..31, so that any 16 consecutive lanes cover all 64 banks);
 // registers -> v_mfma_i32_32x32x32_i8.
 #include <type_traits>
+
+#ifndef OZIMMU_TUNE_MAX_STAGES
+#define OZIMMU_TUNE_MAX_STAGES 3
+#endif
 
 #include "ozimmu_internal.h"
 
@@ -33,6 +38,7 @@ namespace ozimmu {
 namespace {
 
 constexpr int kLdsLimit = 160 * 1024;
+constexpr int kMaxStages = OZIMMU_TUNE_MAX_STAGES;   // LDS stages at most (loads are requested kMaxStages - 1 steps ahead)
 
 // One band of a walk: the pairs (p, q), 0-based, with E0 <= p + q <= SB - 1 of an SB-slice problem.
 template <int SB, int WM, int WN>
@@ -42,11 +48,17 @@ struct Band {
     static constexpr int NW = WM * WN;
     static constexpr int NFRAG = SB * (WM + WN);          // fragments per step
     static constexpr int STAGE = NFRAG * kFragBytes;
-    static constexpr int NST = 3 * STAGE <= kLdsLimit ? 3 : 2;
+    // RESIDENT: all 2 SB fragments of a step are held in registers (8 SB of them) and re-read in place
+    // for the next step; beyond 11 slices they no longer fit beside the accumulators and the B
+    // fragments are streamed through three registers instead.
+    static constexpr bool RESIDENT = SB <= 11;
+    static constexpr int FIT = kLdsLimit / STAGE;
+    static constexpr int NST = !RESIDENT ? 2 : FIT > kMaxStages ? kMaxStages : FIT;
     static constexpr int LDS = NST * STAGE;
     static constexpr int NLOAD = (NFRAG + NW - 1) / NW;   // direct loads per wavefront and step
-    static_assert(LDS <= kLdsLimit, "two stages must fit the LDS");
-    static_assert(2 * NLOAD < 64, "vmcnt is a 6-bit counter");
+    static_assert(NST >= 2, "two stages must fit the LDS");
+    static_assert(NST * NLOAD < 64, "vmcnt is a 6-bit counter");
+    static_assert(NLOAD <= SB, "one direct load per MFMA group");
 };
 
 template <int S, int WM, int WN>
@@ -128,11 +140,17 @@ __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g,
     // the last step is requested again (into a stage nobody reads any more)
     unsigned voff = (unsigned)w.lane * 16u + (unsigned)g.t_begin * kFragBytes;
     const unsigned voff_last = (unsigned)w.lane * 16u + (unsigned)(g.t_end - 1) * kFragBytes;
+    // Load jj of the step being requested; the last one moves on to the next step.
+    auto issue_one = [&](int jj, unsigned stage_off) __attribute__((always_inline)) {
+        dma_load16(src[jj], voff, dst[jj] + stage_off);
+        if (jj == NLOAD - 1) {
+            const unsigned nv = voff + kFragBytes;
+            voff = nv < voff_last ? nv : voff_last;
+        }
+    };
     auto issue = [&](unsigned stage_off) __attribute__((always_inline)) {
 #pragma unroll
-        for (int jj = 0; jj < NLOAD; ++jj) dma_load16(src[jj], voff, dst[jj] + stage_off);
-        const unsigned nv = voff + kFragBytes;
-        voff = nv < voff_last ? nv : voff_last;
+        for (int jj = 0; jj < NLOAD; ++jj) issue_one(jj, stage_off);
     };
     const unsigned char* rd_a = w.lds + w.wm * kFragBytes + w.rd_lane;
     const unsigned char* rd_b = w.lds + (SB * WM + w.wn) * kFragBytes + w.rd_lane;
@@ -143,64 +161,84 @@ __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g,
         return *reinterpret_cast<const v4i*>(rd_b + stage_off + q * WN * kFragBytes);
     };
 
-    v4i a[SB], b[2], bn;
     const int steps = g.t_end - g.t_begin;
-    unsigned cur = 0, nxt = B::STAGE, nn = NST == 3 ? 2 * B::STAGE : 0;
-
-    if (NST == 3) {
-        // steps 0 and 1 are requested; step 0 is awaited and published, its fragments are read
-        issue(cur);
-        issue(nxt);
-        wait_loads<NLOAD>();
+    // Group q of a step = the MFMAs of B fragment q with the A fragments p = pmax(q) .. pmin(q),
+    // highest first: a[SB - 1 - q] and b[q] have their last use of the step in group q.
+    if constexpr (B::RESIDENT) {
+        // All 2 SB fragments of a step live in registers; each is re-read from the stage of the next
+        // step as soon as its last MFMA of this step is issued, a whole step before it is needed
+        // again. The stage of step t is therefore read during step t - 1 only, and free from the
+        // barrier of step t on: it takes the loads of step t + NST, which get NST - 1 steps to land.
+        constexpr int AHEAD = NST - 1;
+        v4i a[SB], b[SB];
+        unsigned cur = 0;
+        static_for<0, NST>([&](auto sc) __attribute__((always_inline)) { issue(decltype(sc)::value * B::STAGE); });
+        wait_loads<AHEAD * NLOAD>();    // step 0 has landed
         workgroup_barrier();
-#pragma unroll
-        for (int p = 0; p < SB; ++p) a[p] = read_a(p, cur);
-        bn = read_b(0, cur);
+        static_for<0, SB>([&](auto pc) __attribute__((always_inline)) {
+            constexpr int p = decltype(pc)::value;
+            a[SB - 1 - p] = read_a(SB - 1 - p, cur);
+            b[p] = read_b(p, cur);
+        });
+        for (int t = 0; t < steps; ++t) {
+            const unsigned nxt = cur + B::STAGE < (unsigned)B::LDS ? cur + B::STAGE : 0u;
+            static_for<0, SB>([&](auto qc) __attribute__((always_inline)) {
+                constexpr int q = decltype(qc)::value;
+                constexpr int pmax = SB - 1 - q, pmin = E0 - q > 0 ? E0 - q : 0;
+                static_for<0, pmax - pmin + 1>([&](auto ic) __attribute__((always_inline)) {
+                    constexpr int p = pmax - decltype(ic)::value;
+                    acc[p + q - E0] = mfma(a[p], b[q], acc[p + q - E0]);
+                });
+                if constexpr (q == 0) {
+                    // step t + 1 has landed everywhere (its fragments may be read from here on) and
+                    // every wavefront has read the last fragment of step t: its stage is free
+                    __builtin_amdgcn_sched_barrier(0);
+                    wait_loads<(AHEAD - 1) * NLOAD>();
+                    workgroup_barrier();
+                }
+                // one direct load per group (NLOAD <= SB): a wavefront stalls while its load is issued,
+                // and eight wavefronts that issue all their loads at once queue behind each other
+                if constexpr (q < NLOAD) issue_one(q, cur);
+                b[q] = read_b(q, nxt);
+                a[pmax] = read_a(pmax, nxt);
+                __builtin_amdgcn_sched_barrier(0);   // keep the re-reads where their registers fall free
+            });
+            cur = nxt;
+            after_step(t + 1);
+        }
     } else {
+        // Two stages: the fragments of a step are read at its start, in the order of their first
+        // use and two groups ahead of it (B fragments pass through three rotating registers).
+        v4i a[SB], b[3];
+        unsigned cur = 0, nxt = B::STAGE;
         issue(cur);
-    }
-
-    for (int t = 0; t < steps; ++t) {
-        if (NST == 2) {
+        for (int t = 0; t < steps; ++t) {
             // step t has landed everywhere and nobody reads the other stage any more
             wait_loads<0>();
             workgroup_barrier();
             issue(nxt);
-#pragma unroll
-            for (int p = 0; p < SB; ++p) a[p] = read_a(p, cur);
             b[0] = read_b(0, cur);
-        } else {
-            b[0] = bn;
-        }
-        static_for<0, SB>([&](auto qc) __attribute__((always_inline)) {
-            constexpr int q = decltype(qc)::value;
-            constexpr int pmax = SB - 1 - q, pmin = E0 - q > 0 ? E0 - q : 0;
-            if constexpr (q + 1 < SB) b[(q + 1) & 1] = read_b(q + 1, cur);
-            if constexpr (NST == 3 && q == SB - 1 && (SB > 1)) bn = read_b(0, nxt);
-            static_for<0, pmax - pmin + 1>([&](auto ic) __attribute__((always_inline)) {   // a[0] last: it is the last one to be re-read
-                constexpr int p = pmax - decltype(ic)::value;
-                acc[p + q - E0] = mfma(a[p], b[q & 1], acc[p + q - E0]);
+            static_for<0, SB - E0>([&](auto ic) __attribute__((always_inline)) {
+                a[SB - 1 - decltype(ic)::value] = read_a(SB - 1 - decltype(ic)::value, cur);
             });
-            if constexpr (NST == 3) {
-                if constexpr (q == 0) {
-                    // step t + 1 has landed everywhere (its fragments may be read from here on) and
-                    // every wavefront is past step t - 1, whose stage takes the loads of step t + 2
-                    wait_loads<0>();
-                    workgroup_barrier();
-                    issue(nn);
-                    if constexpr (SB == 1) bn = read_b(0, nxt);
-                }
-                a[pmax] = read_a(pmax, nxt);   // a[pmax] has had its last use in this step
-            }
-        });
-        if (NST == 3) {
-            const unsigned o = cur;
-            cur = nxt; nxt = nn; nn = o;
-        } else {
+            if constexpr (SB > 1) b[1] = read_b(1, cur);
+            if constexpr (E0 >= 1) a[E0 - 1] = read_a(E0 - 1, cur);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<0, SB>([&](auto qc) __attribute__((always_inline)) {
+                constexpr int q = decltype(qc)::value;
+                constexpr int pmax = SB - 1 - q, pmin = E0 - q > 0 ? E0 - q : 0;
+                if constexpr (q + 2 < SB) b[(q + 2) % 3] = read_b(q + 2, cur);
+                if constexpr (E0 - (q + 2) >= 0) a[E0 - (q + 2)] = read_a(E0 - (q + 2), cur);
+                static_for<0, pmax - pmin + 1>([&](auto ic) __attribute__((always_inline)) {
+                    constexpr int p = pmax - decltype(ic)::value;
+                    acc[p + q - E0] = mfma(a[p], b[q % 3], acc[p + q - E0]);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
             const unsigned o = cur;
             cur = nxt; nxt = o;
+            after_step(t + 1);
         }
-        after_step(t + 1);
     }
     // direct loads of the clamped tail may still be in flight: they must land before the LDS is
     // used for anything else or handed to another workgroup
@@ -312,6 +350,9 @@ void product_kernel(const GemmArgs g) {
                 q += diag_stride;
             }
         }
+        // no store of this block may still be in flight when the walk goes back to counting its
+        // direct loads (stores and loads share the counter)
+        wait_loads<0>();
     };
 
     // accumulator layout of the 32x32 MFMA: lane holds column (lane % 32); register u holds
