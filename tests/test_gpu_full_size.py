@@ -1,8 +1,8 @@
 """Parity at the full size of the large workloads, in the launch configuration the benchmark times.
 
 An entry C_ij depends only on row i of A and column j of B, so the oracle run on a few rows of A
-against all of B reproduces exactly those rows of the full result: the sampled rows (tile edges of
-the 256-row macro tiles plus random ones) must be bit-exact. Inputs are generated on the device
+against all of B reproduces exactly those rows of the full result: the sampled rows (one in every
+64-row tile of C, tile edges, and random ones) must be bit-exact. Inputs are generated on the device
 from a seed and the sampled rows copied back for the oracle.
 """
 import numpy as np
@@ -20,10 +20,16 @@ def bits(x):
     return np.ascontiguousarray(x).view(np.uint64)
 
 
-def sample_rows(m, extra, seed):
-    edges = [0, 1, 127, 128, 255, 256, m // 2 - 1, m // 2, m - 257, m - 256, m - 1]
+TILE_ROWS = 64   # rows of C one workgroup owns
+
+
+def sample_rows(m, extra, seed, every_tile=False):
+    edges = [0, 1, 63, 64, 127, 128, 255, 256, m // 2 - 1, m // 2, m - 257, m - 256, m - 65, m - 64, m - 1]
     rng = np.random.default_rng(seed)
     rows = set(int(r) for r in edges if 0 <= r < m) | set(int(r) for r in rng.choice(m, size=extra, replace=False))
+    if every_tile:   # one row at a random position inside every tile row
+        rows |= set(int(t * TILE_ROWS + rng.integers(0, min(TILE_ROWS, m - t * TILE_ROWS)))
+                    for t in range((m + TILE_ROWS - 1) // TILE_ROWS))
     return np.array(sorted(rows), dtype=np.int64)
 
 
@@ -32,7 +38,8 @@ def config3():
     m = n = k = 8192
     A = wl.phi_matrix_device(m, k, 1.0, 1003)
     B = wl.phi_matrix_device(k, n, 1.0, 2003)
-    rows = sample_rows(m, 13, seed=3)
+    rows = sample_rows(m, 13, seed=3, every_tile=True)
+    assert len(set(rows // TILE_ROWS)) == m // TILE_ROWS
     A_rows = A[torch.from_numpy(rows).cuda()].cpu().numpy()
     B_host = B.cpu().numpy()
     yield A, B, rows, A_rows, B_host
@@ -70,7 +77,8 @@ def test_config4_long_k_wide_exponents_sampled_rows_bit_exact():
     ozimmu.dgemm(A, B, C, s, ws)
     torch.cuda.synchronize()
     assert not torch.isnan(C).any()
-    rows = np.array([0, 255, 256, 2047, 3840, 4095], dtype=np.int64)
+    rows = sample_rows(m, 0, seed=4, every_tile=True)
+    assert len(set(rows // TILE_ROWS)) == m // TILE_ROWS
     A_rows = A[torch.from_numpy(rows).cuda()].cpu().numpy()
     got = C[torch.from_numpy(rows).cuda()].cpu().numpy()
     del A, C, ws
@@ -101,8 +109,7 @@ def test_config5_complex_small_k_sampled_rows_bit_exact():
 
 @pytest.mark.parametrize("size,s", [(2048, 8), (3072, 7), (6144, 8)])
 def test_tile_counts_that_do_not_fill_the_chip_sampled_rows_bit_exact(size, s):
-    """64, 144 and 576 macro tiles on 256 CUs: several workgroups share a tile (each a subset of its
-    diagonals) and a second kernel forms the sum; the result must not change by a bit."""
+    """512, 1152 and 4608 tiles on 256 CUs: 2, 4.5 and 18 rounds of workgroups, the last one partial at 3072."""
     m = n = k = size
     A = wl.phi_matrix_device(m, k, 1.0, 1006)
     B = wl.phi_matrix_device(k, n, 1.0, 2006)

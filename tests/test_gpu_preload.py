@@ -218,10 +218,13 @@ def random_unitary(dim):
 
 state = torch.zeros(2 ** N, dtype=torch.complex128, device="cuda")
 state[0] = 1.0
+gates = []
 for layer in range(layers):
     offset = (d // 2) * (layer % 2)
     for first in range(offset, N - d + 1, d):
-        U = random_unitary(2 ** d).cuda()
+        U = random_unitary(2 ** d)
+        gates.append(U.numpy().copy())
+        U = U.cuda()
         axes = list(range(first, first + d))
         rest = [a for a in range(N) if a not in axes]
         M = state.reshape([2] * N).permute(rest + axes).reshape(2 ** (N - d), 2 ** d).contiguous()
@@ -229,7 +232,30 @@ for layer in range(layers):
         state = out.reshape([2] * N).permute(np.argsort(rest + axes).tolist()).reshape(-1).contiguous()
 torch.cuda.synchronize()
 np.save(sys.argv[1], state.cpu().numpy())
+np.save(sys.argv[1] + ".gates.npy", np.stack(gates))      # the circuit, so that a checker can replay it
 '''
+
+
+def replay_with_oracle(gates, threshold, N=16, d=6, layers=4):
+    """The same circuit on the CPU, every gate product by the oracle with the oracle's own automatic
+    slice count. Reshapes and permutations move data without arithmetic, so a simulator whose products
+    are the oracle's ends in exactly this state."""
+    state = np.zeros(2 ** N, dtype=np.complex128)
+    state[0] = 1.0
+    picked, g = [], 0
+    for layer in range(layers):
+        offset = (d // 2) * (layer % 2)
+        for first in range(offset, N - d + 1, d):
+            axes = list(range(first, first + d))
+            rest = [a for a in range(N) if a not in axes]
+            M = np.ascontiguousarray(state.reshape([2] * N).transpose(rest + axes).reshape(2 ** (N - d), 2 ** d))
+            V = np.ascontiguousarray(gates[g].T)
+            g += 1
+            s = oracle.auto_num_slices(M, V, threshold)[0]
+            picked.append(s)
+            out = oracle.zgemm(M, V, s)
+            state = np.ascontiguousarray(out.reshape([2] * N).transpose(np.argsort(rest + axes).tolist()).reshape(-1))
+    return state, picked
 
 
 def test_unmodified_simulator_under_the_preload_list(tmp_path):
@@ -252,15 +278,21 @@ def test_unmodified_simulator_under_the_preload_list(tmp_path):
         print(f"simulator child, mode={mode} threshold={threshold}", flush=True)
         p = subprocess.run([sys.executable, "-c", SIMULATOR, str(out)], env=env, capture_output=True, text=True, timeout=110)
         assert p.returncode == 0, p.stderr[-2000:]
-        return np.load(out), p.stderr
+        return np.load(out), np.load(str(out) + ".gates.npy"), p.stderr
 
-    ref, _ = run(None)
+    ref, ref_gates, _ = run(None)
     assert abs(np.linalg.norm(ref) - 1.0) <= 1e-12
     for threshold, tol, lo, hi in ((0, 5e-14, 9, 16), (1, 5e-13, 3, 10)):
-        got, log = run("auto", threshold)
+        got, gates, log = run("auto", threshold)
         picked = [int(x) for x in re.findall(r"hipblasZgemm \S+ m=\d+ n=\d+ k=\d+ slices=(\d+) \(auto\)", log)]
         assert len(picked) == 8, log[-1500:]             # 4 layers of 2 gates
         assert lo <= max(picked) <= hi
+        # the oracle's replay of the same circuit: same slice count at every gate, same final state bit for bit
+        assert np.array_equal(gates, ref_gates)
+        want, want_picked = replay_with_oracle(gates, float(threshold))
+        assert picked == want_picked
+        assert np.array_equal(bits(got.real.copy()), bits(want.real.copy()))
+        assert np.array_equal(bits(got.imag.copy()), bits(want.imag.copy()))
         assert abs(np.linalg.norm(got) - 1.0) <= 1e-12
         assert np.max(np.abs(got - ref)) <= tol * 50 * np.max(np.abs(ref))
         assert abs(got[0] - ref[0]) <= tol * 50 * abs(ref[0]) + 1e-16     # the amplitude the paper compares

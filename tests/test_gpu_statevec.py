@@ -2,11 +2,13 @@
 random d-qubit unitaries, each gate applied as a complex product of the reshaped state (2^(N-d) x 2^d)
 with the 2^d x 2^d gate matrix, the number of slices chosen automatically before every product.
 The circuits of the paper are defined in a figure that is not available; this is the same kind of
-computation on a seeded synthetic circuit, checked against the vendor complex GEMM and unitarity."""
+computation on a seeded synthetic circuit. Every gate product and every chosen slice count is checked
+bit for bit against the CPU oracle; the vendor complex GEMM and unitarity are extra context."""
 import numpy as np
 import pytest
 import torch
 
+import oracle
 from paper_2306_11975_amd import ozimmu
 
 pytestmark = pytest.mark.gpu
@@ -43,6 +45,12 @@ def test_brickwork_random_unitary_circuit(threshold, max_rel):
         picked.append(s)
         C = torch.empty((m, n), dtype=torch.complex128, device="cuda")
         ozimmu.zgemm(M, V, C, s, ozimmu.alloc_workspace(m, n, k, s, is_complex=True))
+        # the oracle on the same operands: same slice count, same product, bit for bit
+        Mh, Vh = M.cpu().numpy(), V.cpu().numpy()
+        assert s == oracle.auto_num_slices(Mh, Vh, threshold)[0]
+        want, got = oracle.zgemm(Mh, Vh, s), C.cpu().numpy()
+        assert np.array_equal(got.real.copy().view(np.uint64), want.real.copy().view(np.uint64)), len(picked)
+        assert np.array_equal(got.imag.copy().view(np.uint64), want.imag.copy().view(np.uint64)), len(picked)
         return C
 
     state0 = torch.zeros(2 ** N, dtype=torch.complex128, device="cuda")
