@@ -240,11 +240,14 @@ __global__ __launch_bounds__(256) void col_exponent_kernel(const unsigned long l
     if (j < n) E[j] = exponent_of_max(colmax[j]);
 }
 
-// Slice emission for B^T: a workgroup takes a 128 (l) x 64 (j) tile of B. Lane (jj, lg) reads
-// 32 elements of column jj (contiguous across lanes for each l), packs four consecutive l per
-// slice into one word and transposes through LDS so that the global stores run along l.
-constexpr int kColTileL = 128, kColTileJ = 64;
-constexpr int kColGroup = 4;   // slices transposed through LDS at a time: 34 KiB, four workgroups per CU
+// Slice emission for B^T: a workgroup takes a 64 (l) x 64 (j) tile of B. Lane (jj, lg) reads
+// 16 elements of column jj (contiguous across lanes for each l), packs four consecutive l per
+// slice into one word and transposes through LDS so that the global stores run along l. The
+// tile is kept this small for the registers: 16 fixed-point fractions per thread leave room for
+// five or six wavefronts per SIMD, and it is occupancy that keeps the loads of this pass in flight.
+constexpr int kColTileL = 64, kColTileJ = 64;
+constexpr int kColWords = kColTileL / 4 / 4;   // words of four consecutive l per thread
+constexpr int kColGroup = 4;   // slices transposed through LDS at a time
 constexpr int kColLdsStride = kColTileL / 4 + 1;  // words per LDS row (+1: conflict-free columns)
 template <bool WIDE>
 __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restrict__ B, int64_t ldb,
@@ -252,27 +255,31 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
                                                          int8_t* __restrict__ S, int64_t n_pad,
                                                          int64_t k_pad,
                                                          const unsigned long long* __restrict__ colmax,
+                                                         int32_t* __restrict__ Eout, int j_tiles,
                                                          unsigned long long flip) {   // sign bit, or 0: slices of -B
     __shared__ uint32_t tile[kColGroup][kColTileJ][kColLdsStride];
     const int tid = threadIdx.x;
     const int jj = tid & 63, lg = tid >> 6;
-    const int64_t j = (int64_t)blockIdx.x * kColTileJ + jj;
-    const int64_t lbase = (int64_t)blockIdx.y * kColTileL;
+    const int64_t jt = blockIdx.x % j_tiles, lt = blockIdx.x / j_tiles;
+    const int64_t j = jt * kColTileJ + jj;
+    const int64_t lbase = lt * kColTileL;
     const int64_t slice_stride = n_pad * k_pad;
     const unsigned long long* src = reinterpret_cast<const unsigned long long*>(B);
     const int E = (j < n) ? exponent_of_max(colmax[j]) : 0;
+    if (lt == 0 && lg == 0 && j < n) Eout[j] = E;
 
-    Fixed x[8][4];
-    SignMask sm[8];
+    Fixed x[kColWords][4];
+    SignMask sm[kColWords];
 #pragma unroll
-    for (int u4 = 0; u4 < 8; ++u4) {
+    for (int u4 = 0; u4 < kColWords; ++u4) {
         unsigned long long b[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int64_t l = lbase + lg * 32 + u4 * 4 + u;
+            const int64_t l = lbase + lg * (4 * kColWords) + u4 * 4 + u;
             b[u] = (j < n && l < k) ? src[(l * ldb + j) * inc] : 0ull;
-            x[u4][u] = to_fixed<WIDE>(b[u], E);
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u4][u] = to_fixed<WIDE>(b[u], E);
         sm[u4] = sign_mask(b[0] ^ flip, b[1] ^ flip, b[2] ^ flip, b[3] ^ flip);
     }
 #pragma unroll
@@ -283,30 +290,26 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
         for (int pp = 0; pp < kColGroup; ++pp) {
             if (pp < np && p0 + pp <= OZIMMU_MAX_SLICES) {
 #pragma unroll
-                for (int u4 = 0; u4 < 8; ++u4) tile[pp][jj][lg * 8 + u4] = packed_slice<WIDE>(x[u4], sm[u4], p0 + pp);
+                for (int u4 = 0; u4 < kColWords; ++u4) tile[pp][jj][lg * kColWords + u4] = packed_slice<WIDE>(x[u4], sm[u4], p0 + pp);
             }
         }
         __syncthreads();
-        // Write-out: per slice the tile is 2 row groups x 4 slabs = 8 fragments of 1 KiB, each
+        // Write-out: per slice the tile is 2 row groups x 2 slabs = 4 fragments of 1 KiB, each
         // contiguous in the slice tensor: consecutive lanes store consecutive 16-byte units.
         for (int pp = 0; pp < np; ++pp) {
             int8_t* dst = S + (int64_t)(p0 + pp - 1) * slice_stride;
-#pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const int unit = it * 256 + tid;       // 0..511
-                const int f = unit >> 6;                // fragment inside the tile
-                const int ks = f >> 1, rg = f & 1;      // its slab and its row group
-                const int pos = unit & 63;              // 16-byte unit inside the fragment
-                const int rr = pos >> 1;                // fragment row
-                const int h = (pos & 1) ^ ((rr >> 3) & 1);   // which half of the row's 32 positions is stored there
-                const int r = rg * kFragRows + rr;      // row inside the tile (a column of B)
-                const int w0 = ks * 8 + h * 4;          // first word of that half in the LDS row
-                uint4 v = {tile[pp][r][w0], tile[pp][r][w0 + 1], tile[pp][r][w0 + 2], tile[pp][r][w0 + 3]};
-                const int64_t slab = lbase / kSlab + ks;
-                if (slab < k_pad / kSlab) {
-                    const int64_t off = (((int64_t)blockIdx.x * 2 + rg) * (k_pad / kSlab) + slab) * kFragBytes + pos * 16;
-                    *reinterpret_cast<uint4*>(dst + off) = v;
-                }
+            const int f = tid >> 6;                 // fragment inside the tile
+            const int ks = f >> 1, rg = f & 1;      // its slab and its row group
+            const int pos = tid & 63;               // 16-byte unit inside the fragment
+            const int rr = pos >> 1;                // fragment row
+            const int h = (pos & 1) ^ ((rr >> 3) & 1);   // which half of the row's 32 positions is stored there
+            const int r = rg * kFragRows + rr;      // row inside the tile (a column of B)
+            const int w0 = ks * 8 + h * 4;          // first word of that half in the LDS row
+            uint4 v = {tile[pp][r][w0], tile[pp][r][w0 + 1], tile[pp][r][w0 + 2], tile[pp][r][w0 + 3]};
+            const int64_t slab = lbase / kSlab + ks;
+            if (slab < k_pad / kSlab) {
+                const int64_t off = ((jt * 2 + rg) * (k_pad / kSlab) + slab) * kFragBytes + pos * 16;
+                *reinterpret_cast<uint4*>(dst + off) = v;
             }
         }
         __syncthreads();
@@ -541,15 +544,16 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (n > 0) {
-        col_exponent_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(colmax, n, E);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
+    if (k_pad == 0) {   // no slices to write: only the exponents (all zero)
+        if (n > 0) col_exponent_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(colmax, n, E);
+        return hipGetLastError();
     }
-    if (k_pad == 0) return hipSuccess;
-    const dim3 grid((unsigned)(n_pad / kColTileJ), (unsigned)((k_pad + kColTileL - 1) / kColTileL));
-    if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, flip);
-    else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, flip);
+    const int64_t l_tiles = (k_pad + kColTileL - 1) / kColTileL;
+    const int j_tiles = (int)(n_pad / kColTileJ);
+    if (j_tiles * l_tiles > 0x7fffffffll) return hipErrorInvalidValue;   // beyond any grid (and any memory)
+    const dim3 grid((unsigned)(j_tiles * l_tiles));
+    if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, E, j_tiles, flip);
+    else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, E, j_tiles, flip);
     return hipGetLastError();
 }
 
