@@ -6,6 +6,10 @@ over the headline workload: m = n = k = 8192, entries (U(0,1) - 0.5) * exp(1.0 *
 inputs resident in HBM. Prints ONE JSON line: effective FP64 TFLOP/s (2mnk / t), the roofline of
 the dominant kernel (the INT8 MFMA slice-product kernel, timed with events on its own stream
 inside the timed region) and the CPU oracle timed on a bounded sample on this host.
+
+Other workloads: --m/--n/--k/--phi/--slices (real), --complex (ozimmu_zgemm), and
+--statevec N D (Section 4.4: a D-qubit gate applied to an N-qubit state vector, the complex
+product of shape 2^(N-D) x 2^D x 2^D, slice count chosen automatically at --threshold).
 """
 from __future__ import annotations
 
@@ -21,7 +25,7 @@ if ROOT not in sys.path:
 
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense INT8, published
 HBM_PEAK_GBS = 8000.0
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "slice_gemm_m8192_pmc.md")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "product_kernel_m8192_pmc.md")
 
 
 def measured_traffic(m, s):
@@ -63,7 +67,7 @@ def cpu_baseline(A_rows, B_host, s, m_full):
     }
 
 
-def bench_complex(args, m, n, k, s):
+def bench_complex(args, m, n, k, s, statevec=None):
     """Complex product by four real Ozaki products (Section 4.4): one step = ozimmu_zgemm."""
     import numpy as np
     import torch
@@ -71,8 +75,21 @@ def bench_complex(args, m, n, k, s):
     from paper_2306_11975_amd import ozimmu
     from paper_2306_11975_amd import workloads as wl
 
-    A = wl.gaussian_complex_device(m, k, 1005)
-    B = wl.unit_column_complex_device(k, n, 2005)
+    auto_ms = None
+    if statevec:
+        # a normalised Gaussian state reshaped to 2^(N-D) x 2^D, times the transpose of a unitary gate
+        A = wl.gaussian_complex_device(m, k, 1007)
+        A /= torch.linalg.vector_norm(A)
+        B = wl.haar_unitary_device(k, 2007).T.contiguous()
+        s, _ = ozimmu.auto_num_slices(A, B, args.threshold)
+        torch.cuda.synchronize()
+        t_a = time.perf_counter()
+        for _ in range(5):
+            ozimmu.auto_num_slices(A, B, args.threshold)
+        auto_ms = (time.perf_counter() - t_a) / 5 * 1e3
+    else:
+        A = wl.gaussian_complex_device(m, k, 1005)
+        B = wl.unit_column_complex_device(k, n, 2005)
     C = torch.empty((m, n), dtype=torch.complex128, device="cuda")
     ws = ozimmu.alloc_workspace(m, n, k, s, is_complex=True)
     for _ in range(args.warmup):
@@ -90,13 +107,18 @@ def bench_complex(args, m, n, k, s):
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8 slices, int32 accumulation, f64 sum", "data": "synthetic",
-        "config": {"workload": f"complex FP64 GEMM m={m} n={n} k={k}, A re/im N(0,1), columns of B unit 2-norm, "
-                               f"num_slices={s} (4 x {pairs} INT8 slice products)",
+        "config": {"workload": (f"state vector: {statevec[1]}-qubit Haar-like gate on {statevec[0]} qubits = complex FP64 GEMM "
+                                f"m={m} n={n} k={k}, num_slices={s} chosen at threshold {args.threshold} "
+                                f"(4 x {pairs} INT8 slice products)" if statevec else
+                                f"complex FP64 GEMM m={m} n={n} k={k}, A re/im N(0,1), columns of B unit 2-norm, "
+                                f"num_slices={s} (4 x {pairs} INT8 slice products)"),
                    "m": m, "n": n, "k": k, "num_slices": s},
         "roofline": {"kernel": "whole ozimmu_zgemm call (4 splits + slice-product launches)", "bound": "mfma",
                      "achieved": int8_ops / sec / 1e12, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": int8_ops / sec / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": None},
     }
+    if auto_ms is not None:
+        out["auto_num_slices_ms"] = auto_ms
     if not args.no_context:
         for _ in range(2):
             torch.matmul(A, B)
@@ -106,6 +128,7 @@ def bench_complex(args, m, n, k, s):
             torch.matmul(A, B)
         torch.cuda.synchronize()
         out["context_native_zgemm_TFLOPs"] = 8.0 * m * n * k / ((time.perf_counter() - c0) / 5) / 1e12
+        out["context_native_zgemm_ms"] = (time.perf_counter() - c0) / 5 * 1e3
     if args.cpu_rows > 0:
         import oracle
 
@@ -138,6 +161,11 @@ def main():
     ap.add_argument("--complex", action="store_true",
                     help="complex workload instead (ozimmu_zgemm; Gaussian A, unit-norm columns of B), "
                          "e.g. --complex --m 4096 --n 4096 --k 256 --slices 7")
+    ap.add_argument("--statevec", type=int, nargs=2, metavar=("N", "D"), default=None,
+                    help="state-vector workload: a D-qubit gate on an N-qubit state = complex product "
+                         "2^(N-D) x 2^D x 2^D with a Haar-like unitary; the slice count is chosen by "
+                         "ozimmu_auto_num_slices at --threshold (its time is reported, not included)")
+    ap.add_argument("--threshold", type=float, default=1.0, help="--statevec: average mantissa loss allowed (0: lossless)")
     ap.add_argument("--slices", type=int, default=8, help="number of INT8 slices s")
     ap.add_argument("--phi", type=float, default=1.0)
     ap.add_argument("--cpu-rows", type=int, default=256, help="rows of A in the CPU oracle sample (0: skip)")
@@ -168,6 +196,9 @@ def main():
     k = args.k or args.size
     s = args.slices
     pairs = s * (s + 1) // 2
+    if args.statevec:
+        N, D = args.statevec
+        return bench_complex(args, 2 ** (N - D), 2 ** D, 2 ** D, None, statevec=(N, D))
     if args.complex:
         return bench_complex(args, m, n, k, s)
     A = wl.phi_matrix_device(m, k, args.phi, 1003)
@@ -233,7 +264,7 @@ def main():
                                f"num_slices={s} ({pairs} INT8 slice products)",
                    "m": m, "n": n, "k": k, "num_slices": s, "phi": args.phi},
         "roofline": {
-            "kernel": "slice_gemm_kernel (INT8 MFMA slice products + fused FP64 sum)",
+            "kernel": "product_kernel (INT8 MFMA slice products, all diagonals in registers, fused FP64 sum)",
             "bound": "mfma",
             "achieved": achieved_tops,
             "peak": INT8_MFMA_PEAK_TOPS,
@@ -254,10 +285,15 @@ def main():
         # with all-zero operands and with operands distributed like the slices
         z_tops, z_mhz = ozimmu.probe_int8_mfma(0)
         r_tops, r_mhz = ozimmu.probe_int8_mfma(2)
+        z16, z16_mhz = ozimmu.probe_int8_mfma(0, shape=1)
+        r16, r16_mhz = ozimmu.probe_int8_mfma(2, shape=1)
         out["context_int8_mfma_issue_loop"] = {
             "zero_operands": {"TOPs": z_tops, "shader_MHz": z_mhz},
             "random_7bit_operands": {"TOPs": r_tops, "shader_MHz": r_mhz},
             "kernel_vs_random_7bit_loop": achieved_tops / r_tops if r_tops > 0 else None,
+            # the other INT8 MFMA shape of gfx950, for the record (the kernel uses 32x32x32)
+            "mfma_16x16x64": {"zero_operands": {"TOPs": z16, "shader_MHz": z16_mhz},
+                              "random_7bit_operands": {"TOPs": r16, "shader_MHz": r16_mhz}},
         }
         # context only: the vendor's own INT8 -> INT32 GEMM (what torch._int_mm dispatches to) at the same
         # m, n, k on operands distributed like the slices, and on zeros: it shows the same dependence of the

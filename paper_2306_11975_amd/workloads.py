@@ -122,3 +122,16 @@ def gaussian_complex_device(rows: int, cols: int, seed: int, device="cuda"):
     re = torch.randn((rows, cols), generator=g, device=device, dtype=torch.float64)
     im = torch.randn((rows, cols), generator=g, device=device, dtype=torch.float64)
     return torch.complex(re, im)
+
+
+def haar_unitary_device(dim: int, seed: int, device="cuda"):
+    """A Haar-distributed dim x dim unitary (QR of a complex Gaussian matrix with the phases of R's
+    diagonal divided out): the random gates of the circuit workload of Section 4.4."""
+    import torch
+
+    g = torch.Generator().manual_seed(seed)
+    z = torch.complex(torch.randn((dim, dim), generator=g, dtype=torch.float64),
+                      torch.randn((dim, dim), generator=g, dtype=torch.float64))
+    q, r = torch.linalg.qr(z)
+    d = torch.diagonal(r)
+    return (q * (d / d.abs())).to(device)
