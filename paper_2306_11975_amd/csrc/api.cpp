@@ -32,7 +32,7 @@ struct Layout {
     size_t sa_bytes, sb_bytes;      // one plane
     size_t off_sa[2], off_sb[2];    // planes (real GEMM uses plane 0)
     size_t off_ea[2], off_eb[2];
-    size_t off_colmax, off_d;
+    size_t off_colmax, off_d, off_z;
     size_t total;
 };
 
@@ -60,6 +60,8 @@ Layout make_layout(int64_t m, int64_t n, int64_t k, int s, bool cplx) {
     off = align_up(off + sizeof(unsigned long long) * (L.n_pad > L.m_pad ? L.n_pad : L.m_pad));  // either operand may be split by columns
     L.off_d = off;
     if (L.wide) off = align_up(off + (size_t)s * L.tiles_m * L.tiles_n * L.tile_rows * L.tile_cols * sizeof(long long));
+    L.off_z = off;   // complex: the real and imaginary parts of the result as two m x n planes
+    if (cplx) off = align_up(off + (size_t)2 * m * n * sizeof(double));
     L.total = off;
     return L;
 }
@@ -82,11 +84,11 @@ ozimmu_status_t check_gemm_args(int64_t m, int64_t n, int64_t k, const void* A, 
     return OZIMMU_OK;
 }
 
-// One real Ozaki product from already split operands: G = sum over diagonals, written to C with
-// the given column stride and combine mode (C_lo != nullptr: double-double sum into C, C_lo).
+// One real Ozaki product from already split planes: G = sum over diagonals, combined into C as
+// c_mode says (C_lo != nullptr: double-double sum into C, C_lo).
 hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned char* ws, int plane_a, int plane_b,
-                       double* C, int64_t ldc, int c_inc, int c_mode, hipStream_t st, double alpha = 1.0,
-                       double beta = 0.0, double* C_lo = nullptr) {
+                       double* C, int64_t ldc, int c_mode, hipStream_t st, double alpha = 1.0, double beta = 0.0,
+                       double* C_lo = nullptr, const double* Zr = nullptr, double* Cz = nullptr, int64_t ldcz = 0) {
     GemmArgs g{};
     g.SA = reinterpret_cast<const int8_t*>(ws + L.off_sa[plane_a]);
     g.SB = reinterpret_cast<const int8_t*>(ws + L.off_sb[plane_b]);
@@ -101,29 +103,33 @@ hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned ch
     g.n = (int)n;
     g.block_steps = L.wide ? block_steps_for(s) : 0;
     g.D = L.wide ? reinterpret_cast<long long*>(ws + L.off_d) : nullptr;
-    g.P = nullptr;
-    g.ldp = 0;
+    g.EA = reinterpret_cast<const int32_t*>(ws + L.off_ea[plane_a]);
+    g.EB = reinterpret_cast<const int32_t*>(ws + L.off_eb[plane_b]);
     g.C = C;
     g.ldc = ldc;
-    g.c_inc = c_inc;
     g.c_mode = c_mode;
     g.alpha = alpha;
     g.beta = beta;
     g.C_lo = C_lo;
-    g.EA = reinterpret_cast<const int32_t*>(ws + L.off_ea[plane_a]);
-    g.EB = reinterpret_cast<const int32_t*>(ws + L.off_eb[plane_b]);
-    return launch_slice_gemm(g, s, C_lo != nullptr, st);
+    g.Zr = Zr;
+    g.Cz = Cz;
+    g.ldcz = ldcz;
+    return launch_slice_gemm(g, s, C_lo ? 1 : 0, st);
 }
 
 // The four real products of a complex one from the split planes (0 = real, 1 = imaginary):
-// Cr = G(Ar,Br) - G(Ai,Bi);  Ci = G(Ar,Bi) + G(Ai,Br): the second product of each part is
-// combined with the first by one rounded FP64 operation in the kernel's epilogue.
+// Cr = G(Ar,Br) - G(Ai,Bi);  Ci = G(Ar,Bi) + G(Ai,Br). The two parts are formed in two m x n planes of
+// the workspace (contiguous FP64: every update there is a full-line access), the second product of
+// each part combined with the first by one rounded FP64 operation in the kernel's epilogue; the
+// epilogue of the last product writes C, once, as (re, im) pairs.
 hipError_t run_complex_products(const Layout& L, int64_t m, int64_t n, int s, unsigned char* ws, double* C,
                                 int64_t ldc, hipStream_t st) {
-    hipError_t e = run_product(L, m, n, s, ws, 0, 0, C, 2 * ldc, 2, 0, st);
-    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 1, C, 2 * ldc, 2, 2, st);
-    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, C + 1, 2 * ldc, 2, 0, st);
-    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 0, C + 1, 2 * ldc, 2, 1, st);
+    double* Pr = reinterpret_cast<double*>(ws + L.off_z);
+    double* Pi = Pr + (size_t)m * n;
+    hipError_t e = run_product(L, m, n, s, ws, 0, 0, Pr, n, 0, st);
+    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 1, Pr, n, 2, st);
+    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, Pi, n, 0, st);
+    if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 0, Pi, n, 4, st, 1.0, 0.0, nullptr, Pr, C, ldc);
     return e;
 }
 
@@ -275,7 +281,7 @@ ozimmu_status_t ozimmu_slice_gemm(int64_t m, int64_t n, int64_t k, const int8_t*
     g.n = (int)n;
     g.P = P;
     g.ldp = ldp;
-    return hip_status(launch_slice_gemm(g, 1, false, st));
+    return hip_status(launch_slice_gemm(g, 1, 0, st));
 }
 
 ozimmu_status_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_slices, int is_complex,
@@ -309,7 +315,7 @@ ozimmu_status_t ozimmu_dgemm_stage(int stage, int64_t m, int64_t n, int64_t k, c
                                                 reinterpret_cast<int32_t*>(ws + L.off_eb[0]),
                                                 reinterpret_cast<unsigned long long*>(ws + L.off_colmax), st));
         default:
-            return hip_status(run_product(L, m, n, num_slices, ws, 0, 0, C, ldc, 1, 0, st));
+            return hip_status(run_product(L, m, n, num_slices, ws, 0, 0, C, ldc, 0, st));
     }
 }
 
@@ -423,7 +429,7 @@ ozimmu_status_t ozimmu_dgemm_blas(char transa, char transb, int64_t m, int64_t n
         if (!ta) e = launch_split_cols(A, lda, 1, k, m, num_slices, SC, L.n_pad, L.k_pad, EC, colmax, st);  // A: m x k
         else e = launch_split_rows(A, lda, 1, m, k, num_slices, SC, L.n_pad, L.k_pad, EC, st);              // A: k x m
     }
-    if (e == hipSuccess) e = run_product(L, n, m, num_slices, ws, 0, 0, C, ldc, 1, 3, st, alpha, beta);
+    if (e == hipSuccess) e = run_product(L, n, m, num_slices, ws, 0, 0, C, ldc, 3, st, alpha, beta);
     return hip_status(e);
 }
 
@@ -509,7 +515,7 @@ ozimmu_status_t ozimmu_dgemm_dd(int64_t m, int64_t n, int64_t k, const double* A
         if (rc != OZIMMU_OK) return rc;
     }
     unsigned char* ws = static_cast<unsigned char*>(workspace);
-    return hip_status(run_product(L, m, n, num_slices, ws, 0, 0, C_hi, ldc, 1, 0, st, 1.0, 0.0, C_lo));
+    return hip_status(run_product(L, m, n, num_slices, ws, 0, 0, C_hi, ldc, 0, st, 1.0, 0.0, C_lo));
 }
 
 ozimmu_status_t ozimmu_launch_plan(int64_t m, int64_t n, int64_t k, int num_slices, ozimmu_plan_t* plan) {

@@ -63,12 +63,19 @@ __device__ __forceinline__ int acc_read(int a) {
 // that its completion is awaited only by the explicit vmcnt before the step barrier and not
 // before every LDS read in between.
 __device__ __forceinline__ void dma_load16(const void* gbase, unsigned voff, unsigned lds_addr) {
+    // both are wave-uniform by construction; should the register allocator have parked one of them in a
+    // vector register, this brings it back into a scalar one (it costs nothing otherwise)
+    const unsigned long long gb = (unsigned long long)gbase;
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)gb);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(gb >> 32));
+    const void* gs = (const void*)(((unsigned long long)hi << 32) | lo);
+    const unsigned la = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_addr);
     asm volatile(
         "s_mov_b32 m0, %2\n\t"
         "s_nop 0\n\t"
         "global_load_lds_dwordx4 %1, %0"
         :
-        : "s"(gbase), "v"(voff), "s"(lds_addr)
+        : "s"(gs), "v"(voff), "s"(la)
         : "memory");  // M0 is written here (the compiler refuses it as a clobber: reserved register); the build
                       // checks the generated assembly for any other use of M0 in the kernels
 }

@@ -37,10 +37,13 @@ struct GemmArgs {
     long long* D;            // INT64 diagonal sums (k-blocking only)
     int32_t* P;              // pair mode (P != nullptr): raw INT32 product of the slices SA, SB point at
     int64_t ldp;
-    double* C;               // output
+    double* C;               // output, row-major
     int64_t ldc;             // in doubles
-    int c_inc;               // distance in doubles between consecutive columns (2 for a complex plane)
-    int c_mode;              // 0: C = G, 1: C = C + G, 2: C = C - G, 3: C = alpha G (+ beta C if beta != 0)
+    int c_mode;              // 0: C = G, 1: C = C + G, 2: C = C - G, 3: C = alpha G (+ beta C if beta != 0),
+                             // 4: (Zr, C + G) -> Cz as interleaved (re, im) pairs (C is read only)
+    const double* Zr;        // c_mode 4: finished real parts, same shape and leading dimension as C
+    double* Cz;              // c_mode 4: complex output
+    int64_t ldcz;            // c_mode 4: its leading dimension in complex elements
     double alpha, beta;      // c_mode 3 only
     double* C_lo;            // low parts of a double-double result (double-double summing-up only)
     const int32_t* EA;
@@ -55,8 +58,9 @@ hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, i
 hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n, int s,
                              int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
                              unsigned long long* colmax, hipStream_t st, bool negate = false);
-// Slice products of the pairs p + q <= s + 1 with the FP64 sum (dd: double-double sum into C, C_lo).
-hipError_t launch_slice_gemm(const GemmArgs& args, int s, bool dd, hipStream_t st);
+// Slice products of the pairs p + q <= s + 1 with the FP64 sum. mode 0: FP64 sum; 1: double-double sum
+// into C, C_lo.
+hipError_t launch_slice_gemm(const GemmArgs& args, int s, int mode, hipStream_t st);
 // Slice-count scan: adds, for s = 1 .. 16, the mantissa bits s slices would lose into sums[s - 1].
 hipError_t launch_loss_scan_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k,
                                  unsigned long long* sums, hipStream_t st);

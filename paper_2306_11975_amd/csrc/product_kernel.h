@@ -1,0 +1,549 @@
+// Slice products on the CDNA4 INT8 matrix cores with the FP64 sum fused in
+// (the pair loop of the IMMU algorithm with its product and summing-up steps, Section 3.1).
+//
+// Loop nest: "all diagonals resident". A wavefront owns a 32 x 32 patch of C and keeps the exact
+// INT32 sums of up to eight anti-diagonals d = p + q of that patch in its accumulation registers
+// (16 registers per diagonal) for the whole walk along k. A workgroup of 2 x 4 wavefronts owns a
+// 64 x 128 tile. One pipeline step covers 32 positions of k: the 32-row fragments of ALL slices of
+// the tile's rows of A and of B^T (6 s KiB) are brought into LDS once, each wavefront reads its
+// 2 s fragments (one ds_read_b128 each) and issues the s (s + 1) / 2 MFMAs of all pairs
+// p + q <= s + 1, every one into the accumulator of its own diagonal. Integer addition is exact, so
+// all pairs of a diagonal share one INT32 sum; nothing but the slices is read and nothing but C is
+// written: no product and no diagonal sum ever exists in memory. At the end the diagonals are added
+// in the fixed order (least significant first) in FP64, scaled by 2^(EA_i + EB_j), and stored.
+//
+// More than eight slices: the diagonals are walked in two bands, the upper eight first, then the
+// remaining s - 8 (which are exactly the diagonals of the s - 8 slice problem); the FP64 sum of the
+// first band waits in registers. Long k (more than 2^17 products per INT32 sum, cf. Section 2.4 on
+// splitting long k): every block_steps steps the INT32 sums are added into INT64 sums in the
+// workspace (k-blocking) and the FP64 sum is formed from those.
+//
+// Data path of a step: global -> LDS with wave-wide direct loads (global_load_lds_dwordx4, no
+// staging registers; a fragment is 1 KiB contiguous in memory and in LDS), two or three LDS stages
+// (as many as fit 160 KiB);
+// LDS -> registers with ds_read_b128 (fragment rows are 32 bytes with the two 16-byte halves
+// swapped in rows 8..15 and 24..31, so that any 16 consecutive lanes cover all 64 banks);
+// registers -> v_mfma_i32_32x32x32_i8.
+#pragma once
+
+#include <type_traits>
+
+#ifndef OZIMMU_TUNE_MAX_STAGES
+#define OZIMMU_TUNE_MAX_STAGES 3
+#endif
+
+#include "ozimmu_internal.h"
+
+#include "mfma_common.h"
+
+namespace ozimmu {
+namespace {
+
+constexpr int kLdsLimit = 160 * 1024;
+constexpr int kMaxStages = OZIMMU_TUNE_MAX_STAGES;   // LDS stages at most (loads are requested kMaxStages - 1 steps ahead)
+
+// One band of a walk: the pairs (p, q), 0-based, with E0 <= p + q <= SB - 1 of an SB-slice problem.
+template <int SB, int WM, int WN>
+struct Band {
+    static constexpr int ND = SB < kBand ? SB : kBand;    // resident diagonals
+    static constexpr int E0 = SB - ND;                    // lowest one (e = p + q, 0-based; d = e + 2)
+    static constexpr int NW = WM * WN;
+    static constexpr int NFRAG = SB * (WM + WN);          // fragments per step
+    static constexpr int STAGE = NFRAG * kFragBytes;
+    // RESIDENT: all 2 SB fragments of a step are held in registers (8 SB of them) and re-read in place
+    // for the next step; beyond 11 slices they no longer fit beside the accumulators and the B
+    // fragments are streamed through three registers instead.
+    static constexpr bool RESIDENT = SB <= 11;
+    static constexpr int FIT = kLdsLimit / STAGE;
+    static constexpr int NST = !RESIDENT ? 2 : FIT > kMaxStages ? kMaxStages : FIT;
+    static constexpr int LDS = NST * STAGE;
+    static constexpr int NLOAD = (NFRAG + NW - 1) / NW;   // direct loads per wavefront and step
+    static_assert(NST >= 2, "two stages must fit the LDS");
+    static_assert(NST * NLOAD < 64, "vmcnt is a 6-bit counter");
+    static_assert(NLOAD <= SB, "one direct load per MFMA group");
+};
+
+template <int S, int WM, int WN>
+struct Shape {
+    static constexpr int LDS1 = Band<S, WM, WN>::LDS;
+    static constexpr int LDS2 = S > kBand ? Band<(S > kBand ? S - kBand : 1), WM, WN>::LDS : 0;
+    static constexpr int LDS = LDS1 > LDS2 ? LDS1 : LDS2;
+};
+
+// What a wavefront needs to know about its place in the walk.
+struct Walk {
+    unsigned char* lds;      // dynamic LDS segment
+    unsigned lds_base;       // its LDS address
+    unsigned rd_lane;        // byte offset of this lane's 16 bytes inside a fragment
+    int lane, wave, wm, wn;
+    int tm, tn;
+    int tid;
+};
+
+// Compile-time loop: f(integral_constant<int, I>) for I = BEGIN .. END - 1.
+template <int BEGIN, int END, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (BEGIN < END) {
+        f(std::integral_constant<int, BEGIN>{});
+        static_for<BEGIN + 1, END>(f);
+    }
+}
+
+__device__ __forceinline__ v16i mfma(const v4i& a, const v4i& b, const v16i& c) {
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ const int8_t* uniform_ptr(const int8_t* p) {
+    const unsigned long long v = (unsigned long long)p;
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)v);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v >> 32));
+    return (const int8_t*)(((unsigned long long)hi << 32) | lo);
+}
+
+template <int N>
+__device__ __forceinline__ void wait_loads() {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+__device__ __forceinline__ void workgroup_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// The walk of one band over the slabs [g.t_begin, g.t_end), for the products p_begin .. p_end - 1 one
+// after the other: sources(p, sa, sb)
+// names the slice tensors of product p, acc[e - E0] receives the pairs of diagonal e,
+// after_step(steps done in this product) is called after every step (k-blocking hooks in there) and
+// after_product(p) when a product's last step has been issued (it takes the sums and clears acc).
+// In the register-resident schedule the products form one continuous stream of steps: the loads run
+// NST steps ahead of the matrix cores straight across a product boundary, so only the first product
+// of a call pays for filling the pipeline.
+template <int SB, int WM, int WN, class Sources, class AfterStep, class AfterProduct>
+__device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g, const Walk& w, int p_begin, int p_end,
+                                          Sources&& sources, AfterStep&& after_step, AfterProduct&& after_product) {
+    using B = Band<SB, WM, WN>;
+    constexpr int E0 = B::E0, NST = B::NST, NLOAD = B::NLOAD;
+
+    // This wavefront's share of the step's fragments: fragment idx = wave + NW jj. Fragments are
+    // numbered A(p, i) = p WM + i, then B(q, j) = SB WM + q WN + j, and sit in that order in a
+    // stage. A wavefront without a jj-th fragment loads the last one again (same bytes to the same
+    // place), so that every wavefront has the same number of loads in flight.
+    const int8_t* src[NLOAD];
+    unsigned dst[NLOAD];
+    auto set_sources = [&](int prod) __attribute__((always_inline)) {
+        const int8_t *sa, *sb;
+        sources(prod, sa, sb);
+#pragma unroll
+        for (int jj = 0; jj < NLOAD; ++jj) {
+            int idx = w.wave + B::NW * jj;
+            idx = idx < B::NFRAG ? idx : B::NFRAG - 1;
+            const int8_t* s;
+            if (idx < SB * WM) {
+                const int p = idx / WM, i = idx % WM;
+                s = sa + (int64_t)p * g.a_slice_stride + (int64_t)(w.tm * WM + i) * g.kslabs * kFragBytes;
+            } else {
+                const int r = idx - SB * WM;
+                const int q = r / WN, j = r % WN;
+                s = sb + (int64_t)q * g.b_slice_stride + (int64_t)(w.tn * WN + j) * g.kslabs * kFragBytes;
+            }
+            // wave-uniform by construction; say so, so that they live in scalar registers
+            src[jj] = uniform_ptr(s);
+            dst[jj] = (unsigned)__builtin_amdgcn_readfirstlane((int)(w.lds_base + (unsigned)idx * kFragBytes));
+        }
+    };
+    const int steps = g.t_end - g.t_begin;
+    // The request side: product ld_p, step ld_t of it, lane offset voff into its source fragments.
+    // Past the last step of the last product the last step is requested again (into a stage nobody
+    // reads any more), so that the number of loads in flight never changes.
+    const unsigned voff_first = (unsigned)w.lane * 16u + (unsigned)g.t_begin * kFragBytes;
+    unsigned voff = voff_first;
+    int ld_p = p_begin, ld_t = 0, ld_end = p_end;
+    auto issue_one = [&](int jj, unsigned stage_off) __attribute__((always_inline)) {
+        dma_load16(src[jj], voff, dst[jj] + stage_off);
+        if (jj == NLOAD - 1) {   // the step is requested: move on
+            if (++ld_t < steps) {
+                voff += kFragBytes;
+            } else if (ld_p + 1 < ld_end) {
+                ++ld_p;
+                ld_t = 0;
+                set_sources(ld_p);
+                voff = voff_first;
+            } else {
+                --ld_t;
+            }
+        }
+    };
+    auto issue = [&](unsigned stage_off) __attribute__((always_inline)) {
+#pragma unroll
+        for (int jj = 0; jj < NLOAD; ++jj) issue_one(jj, stage_off);
+    };
+    const unsigned char* rd_a = w.lds + w.wm * kFragBytes + w.rd_lane;
+    const unsigned char* rd_b = w.lds + (SB * WM + w.wn) * kFragBytes + w.rd_lane;
+    auto read_a = [&](int p, unsigned stage_off) __attribute__((always_inline)) -> v4i {
+        return *reinterpret_cast<const v4i*>(rd_a + stage_off + p * WM * kFragBytes);
+    };
+    auto read_b = [&](int q, unsigned stage_off) __attribute__((always_inline)) -> v4i {
+        return *reinterpret_cast<const v4i*>(rd_b + stage_off + q * WN * kFragBytes);
+    };
+
+    // Group q of a step = the MFMAs of B fragment q with the A fragments p = pmax(q) .. pmin(q),
+    // highest first: a[SB - 1 - q] and b[q] have their last use of the step in group q.
+    if constexpr (B::RESIDENT) {
+        // All 2 SB fragments of a step live in registers; each is re-read from the stage of the next
+        // step as soon as its last MFMA of this step is issued, a whole step before it is needed
+        // again. The stage of step t is therefore read during step t - 1 only, and free from the
+        // barrier of step t on: it takes the loads of step t + NST, which get NST - 1 steps to land.
+        constexpr int AHEAD = NST - 1;
+        v4i a[SB], b[SB];
+        unsigned cur = 0;
+        set_sources(ld_p);
+        static_for<0, NST>([&](auto sc) __attribute__((always_inline)) { issue(decltype(sc)::value * B::STAGE); });
+        wait_loads<AHEAD * NLOAD>();    // step 0 has landed
+        workgroup_barrier();
+        static_for<0, SB>([&](auto pc) __attribute__((always_inline)) {
+            constexpr int p = decltype(pc)::value;
+            a[SB - 1 - p] = read_a(SB - 1 - p, cur);
+            b[p] = read_b(p, cur);
+        });
+        for (int prod = p_begin; prod < p_end; ++prod) {
+            for (int t = 0; t < steps; ++t) {
+                const unsigned nxt = cur + B::STAGE < (unsigned)B::LDS ? cur + B::STAGE : 0u;
+                static_for<0, SB>([&](auto qc) __attribute__((always_inline)) {
+                    constexpr int q = decltype(qc)::value;
+                    constexpr int pmax = SB - 1 - q, pmin = E0 - q > 0 ? E0 - q : 0;
+                    static_for<0, pmax - pmin + 1>([&](auto ic) __attribute__((always_inline)) {
+                        constexpr int p = pmax - decltype(ic)::value;
+                        acc[p + q - E0] = mfma(a[p], b[q], acc[p + q - E0]);
+                    });
+                    if constexpr (q == 0) {
+                        // step t + 1 has landed everywhere (its fragments may be read from here on) and
+                        // every wavefront has read the last fragment of step t: its stage is free
+                        __builtin_amdgcn_sched_barrier(0);
+                        wait_loads<(AHEAD - 1) * NLOAD>();
+                        workgroup_barrier();
+                    }
+                    // one direct load per group (NLOAD <= SB): a wavefront stalls while its load is issued,
+                    // and eight wavefronts that issue all their loads at once queue behind each other
+                    if constexpr (q < NLOAD) issue_one(q, cur);
+                    b[q] = read_b(q, nxt);
+                    a[pmax] = read_a(pmax, nxt);
+                    __builtin_amdgcn_sched_barrier(0);   // keep the re-reads where their registers fall free
+                });
+                cur = nxt;
+                after_step(t + 1);
+            }
+            after_product(prod);
+        }
+        // direct loads of the repeated last step may still be in flight: they must land before the
+        // LDS is used for anything else or handed to another workgroup
+        wait_loads<0>();
+        workgroup_barrier();
+    } else {
+        // Two stages: the fragments of a step are read at its start, in the order of their first
+        // use and two groups ahead of it (B fragments pass through three rotating registers).
+        // Every product fills the pipeline anew.
+        v4i a[SB], b[3];
+        for (int prod = p_begin; prod < p_end; ++prod) {
+            unsigned cur = 0, nxt = B::STAGE;
+            ld_p = prod;
+            ld_end = prod + 1;
+            ld_t = 0;
+            voff = voff_first;
+            set_sources(prod);
+            issue(cur);
+            for (int t = 0; t < steps; ++t) {
+                // step t has landed everywhere and nobody reads the other stage any more
+                wait_loads<0>();
+                workgroup_barrier();
+                issue(nxt);
+                b[0] = read_b(0, cur);
+                static_for<0, SB - E0>([&](auto ic) __attribute__((always_inline)) {
+                    a[SB - 1 - decltype(ic)::value] = read_a(SB - 1 - decltype(ic)::value, cur);
+                });
+                if constexpr (SB > 1) b[1] = read_b(1, cur);
+                if constexpr (E0 >= 1) a[E0 - 1] = read_a(E0 - 1, cur);
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<0, SB>([&](auto qc) __attribute__((always_inline)) {
+                    constexpr int q = decltype(qc)::value;
+                    constexpr int pmax = SB - 1 - q, pmin = E0 - q > 0 ? E0 - q : 0;
+                    if constexpr (q + 2 < SB) b[(q + 2) % 3] = read_b(q + 2, cur);
+                    if constexpr (E0 - (q + 2) >= 0) a[E0 - (q + 2)] = read_a(E0 - (q + 2), cur);
+                    static_for<0, pmax - pmin + 1>([&](auto ic) __attribute__((always_inline)) {
+                        constexpr int p = pmax - decltype(ic)::value;
+                        acc[p + q - E0] = mfma(a[p], b[q % 3], acc[p + q - E0]);
+                    });
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+                const unsigned o = cur;
+                cur = nxt; nxt = o;
+                after_step(t + 1);
+            }
+            wait_loads<0>();
+            workgroup_barrier();
+            after_product(prod);
+        }
+    }
+}
+
+// acc = RN(acc + S_e 2^(-7 (e + 2))) for the diagonals of a band, least significant first. The
+// product of an integer below 2^31 and a power of two is exact, so the fused operation rounds
+// exactly like the sum it stands for.
+template <int SB>
+__device__ __forceinline__ void fold_band(double (&sum)[16], const v16i (&acc)[kBand]) {
+    constexpr int ND = SB < kBand ? SB : kBand, E0 = SB - ND;
+#pragma unroll
+    for (int e = SB - 1; e >= E0; --e) {
+        const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * (e + 2)) << 52);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) sum[u] = fma((double)acc_read(acc[e - E0][u]), sc, sum[u]);
+    }
+}
+
+// Double-double running sum (Section 2.3.4: summing-up in higher precision): TwoSum of the high
+// part and the exact term, error into the low part, FastTwoSum to renormalise.
+__device__ __forceinline__ void dd_add(double& h, double& l, double t) {
+    const double sh = h + t;
+    const double bb = sh - h;
+    const double e = (h - (sh - bb)) + (t - bb);
+    const double l2 = l + e;
+    const double hn = sh + l2;
+    l = l2 - (hn - sh);
+    h = hn;
+}
+template <int SB>
+__device__ __forceinline__ void fold_band_dd(double (&h)[16], double (&l)[16], const v16i (&acc)[kBand]) {
+    constexpr int ND = SB < kBand ? SB : kBand, E0 = SB - ND;
+#pragma unroll
+    for (int e = SB - 1; e >= E0; --e) {
+        const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * (e + 2)) << 52);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) dd_add(h[u], l[u], (double)acc_read(acc[e - E0][u]) * sc);
+    }
+}
+
+// One element of the result: C (op)= val, with the combine mode of the call.
+__device__ __forceinline__ void write_c_element(const GemmArgs& g, int row, int col, double val) {
+    if (row < g.m && col < g.n) {
+        double* c = g.C + (int64_t)row * g.ldc + col;
+        if (g.c_mode == 0) *c = val;
+        else if (g.c_mode == 1) *c = *c + val;
+        else if (g.c_mode == 2) *c = *c - val;
+        else if (g.c_mode == 3) {   // BLAS update: RN(alpha G), then RN(RN(alpha G) + RN(beta C)); C is not read if beta == 0
+            double v = g.alpha * val;
+            if (g.beta != 0.0) v = v + g.beta * *c;
+            *c = v;
+        } else {   // last of the four real products of a complex one: (re, im) = (Zr, C + val) -> interleaved Cz
+            double2 z;
+            z.x = g.Zr[(int64_t)row * g.ldc + col];
+            z.y = *c + val;
+            *reinterpret_cast<double2*>(g.Cz + 2 * ((int64_t)row * g.ldcz + col)) = z;
+        }
+    }
+}
+
+constexpr int kModeReal = 0, kModeDD = 1;
+
+template <int S, int WM, int WN, int MODE>
+__global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(WM * WN / 4, WM * WN / 4)))
+void product_kernel(const GemmArgs g) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int T = 64 * WM * WN;
+    constexpr int S2 = S > kBand ? S - kBand : 1;   // slice count of the second band (unused if S <= 8)
+    constexpr int NPROD = 1;                              // products walked one after the other by a workgroup
+    constexpr int TR = 32 * WM, TC = 32 * WN;             // tile of C
+
+    Walk w;
+    w.tid = threadIdx.x;
+    w.lane = w.tid & 63;
+    w.wave = __builtin_amdgcn_readfirstlane(w.tid >> 6);   // wave-uniform, kept in a scalar register
+    w.wm = w.wave / WN;
+    w.wn = w.wave % WN;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, w.tm, w.tn);
+    w.lds = lds;
+    w.lds_base = (unsigned)(unsigned long)(__attribute__((address_space(3))) unsigned char*)lds;
+    // MFMA operand: lane holds row (lane % 32), bytes 16 (lane / 32) .. + 16 of the 32-byte fragment row
+    const int rr = w.lane & 31, half = w.lane >> 5;
+    w.rd_lane = (unsigned)(rr * 32 + ((half ^ ((rr >> 3) & 1)) << 4));
+
+    const int tile_id = w.tm * g.tiles_n + w.tn;
+    const int64_t num_tiles = (int64_t)g.tiles_m * g.tiles_n;
+    const bool wide = g.block_steps > 0;
+
+    // The exponents of the tile's rows and columns wait in LDS behind the pipeline stages (rows at
+    // ex, columns at ex + TR): the epilogue must not stall on a round trip to memory. The first
+    // barrier of the walk publishes them.
+    int* ex = reinterpret_cast<int*>(lds + Shape<S, WM, WN>::LDS);
+    if (!g.P) {
+        for (int i = w.tid; i < TR + TC; i += T) {
+            const bool is_a = i < TR;
+            const int pos = is_a ? w.tm * TR + i : w.tn * TC + (i - TR);
+            ex[i] = pos < (is_a ? g.m : g.n) ? (is_a ? g.EA : g.EB)[pos] : 0;
+        }
+    }
+
+    v16i acc[kBand];
+    auto zero_acc = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < kBand; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][r] = acc_zero();
+    };
+    // k-blocking: INT32 sums of the band with lowest diagonal e0 -> INT64 sums in the workspace.
+    // Thread t of the workgroup owns element t of every 16 x (diagonal, tile) run: coalesced, and
+    // nobody else ever touches it.
+    auto flush = [&](int e0, int nd, bool first) __attribute__((always_inline)) {
+        // one running pointer (made opaque so that it is formed here, not ahead of the k-walk)
+        long long* q = g.D + (((int64_t)e0 * num_tiles + tile_id) * 16) * T + w.tid + opaque_zero();
+        const int64_t diag_stride = num_tiles * 16 * T - 16 * T;
+#pragma unroll
+        for (int i = 0; i < kBand; ++i) {
+            if (i < nd) {
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    long long v = (long long)acc_read(acc[i][u]);
+                    if (!first) v += *q;
+                    *q = v;
+                    q += T;
+                    __builtin_amdgcn_sched_barrier(0);   // keep register pressure flat
+                }
+                q += diag_stride;
+            }
+        }
+        // no store of this block may still be in flight when the walk goes back to counting its
+        // direct loads (stores and loads share the counter)
+        wait_loads<0>();
+    };
+
+    // accumulator layout of the 32x32 MFMA: lane holds column (lane % 32); register u holds
+    // row 8 (u / 4) + 4 (lane / 32) + u % 4.
+    const int lrow0_ = w.wm * 32 + 4 * half, lcol_ = w.wn * 32 + rr;   // inside the tile
+    const int row0_ = w.tm * TR + lrow0_, col_ = w.tn * TC + lcol_;
+
+    double sum[16], lo[MODE == kModeDD ? 16 : 1];
+    auto clear_sum = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) sum[u] = 0.0;
+        if constexpr (MODE == kModeDD) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) lo[u] = 0.0;
+        }
+    };
+
+    auto sources = [&](int prod, const int8_t*& sa, const int8_t*& sb) __attribute__((always_inline)) {
+        sa = g.SA;
+        sb = g.SB;
+    };
+    // The sum of product `prod` is complete (in `sum`, or in the INT64 sums of the workspace): scale it,
+    // combine it, store what is final.
+    auto finish_product = [&](int prod) __attribute__((always_inline)) {
+        // Everything this step addresses is formed here, from values made opaque, and not ahead of the
+        // walk, where it would occupy registers the matrix-core loop needs.
+        const int oz = (int)opaque_zero();
+        const int row0 = row0_ + oz, col = col_ + oz, lrow0 = lrow0_ + oz, lcol = lcol_ + oz;
+        if (g.P) {   // pair mode (S == 1): the raw INT32 sums
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int row = row0 + 8 * (u >> 2) + (u & 3);
+                if (row < g.m && col < g.n) g.P[(int64_t)row * g.ldp + col] = acc_read(acc[0][u]);
+            }
+            return;
+        }
+        if (wide) {   // the FP64 sum from the INT64 sums, same order
+            const long long* q = g.D + ((int64_t)tile_id * 16) * T + w.tid + oz;
+            for (int e = S - 1; e >= 0; --e) {
+                const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * (e + 2)) << 52);
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const double term = (double)q[((int64_t)e * num_tiles * 16 + u) * T] * sc;   // exact: |S_e| < 2^53
+                    if constexpr (MODE == kModeDD) dd_add(sum[u], lo[u], term);
+                    else sum[u] = sum[u] + term;
+                }
+            }
+        }
+        const int eb = ex[TR + lcol];
+#pragma unroll
+        for (int u4 = 0; u4 < 4; ++u4) {
+            const v4i ea = *reinterpret_cast<const v4i*>(ex + lrow0 + 8 * u4);   // four consecutive rows
+#pragma unroll
+            for (int uu = 0; uu < 4; ++uu) {
+                const int u = 4 * u4 + uu;
+                const int row = row0 + 8 * u4 + uu;
+                const int e = ea[uu] + eb;
+                const double val = ldexp(sum[u], e);
+                if constexpr (MODE == kModeDD) {
+                    if (row < g.m && col < g.n) {
+                        g.C[(int64_t)row * g.ldc + col] = val;
+                        g.C_lo[(int64_t)row * g.ldc + col] = ldexp(lo[u], e);
+                    }
+                } else {
+                    write_c_element(g, row, col, val);
+                }
+            }
+        }
+    };
+
+    bool first_block = true;
+    int until_flush = g.block_steps;
+    auto run_band = [&](auto sb_tag, int p_begin, int p_end, bool first_band, bool last_band) __attribute__((always_inline)) {
+        constexpr int SB = decltype(sb_tag)::value;
+        using B = Band<SB, WM, WN>;
+        zero_acc();
+        band_walk<SB, WM, WN>(acc, g, w, p_begin, p_end, sources,
+            [&](int done) __attribute__((always_inline)) {
+                if (wide && (--until_flush == 0 || done == g.t_end - g.t_begin)) {
+                    flush(B::E0, B::ND, first_block);
+                    first_block = false;
+                    until_flush = g.block_steps;
+                    zero_acc();
+                }
+            },
+            [&](int prod) __attribute__((always_inline)) {
+                if (first_band) clear_sum();
+                if (!wide && !g.P) {
+                    if constexpr (MODE == kModeDD) fold_band_dd<SB>(sum, lo, acc);
+                    else fold_band<SB>(sum, acc);
+                }
+                if (last_band) finish_product(prod);
+                zero_acc();
+                first_block = true;
+                until_flush = g.block_steps;
+            });
+    };
+    if constexpr (S <= kBand) {
+        run_band(std::integral_constant<int, S>{}, 0, NPROD, true, true);
+    } else {
+        for (int prod = 0; prod < NPROD; ++prod) {
+            run_band(std::integral_constant<int, S>{}, prod, prod + 1, true, false);
+            run_band(std::integral_constant<int, S2>{}, prod, prod + 1, false, true);
+        }
+    }
+}
+
+template <int S, int WM, int WN, int MODE>
+hipError_t launch_one(const GemmArgs& g, hipStream_t st) {
+    constexpr int lds = Shape<S, WM, WN>::LDS + 32 * (WM + WN) * (int)sizeof(int);
+    static_assert(lds <= kLdsLimit, "stages and exponents must fit the LDS");
+    hipError_t e = allow_dynamic_lds<&product_kernel<S, WM, WN, MODE>>(lds);
+    if (e != hipSuccess) return e;
+    product_kernel<S, WM, WN, MODE><<<dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(64 * WM * WN), lds, st>>>(g);
+    return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t launch_for(const GemmArgs& g, int s, hipStream_t st) {
+    switch (s) {
+#define OZ_CASE(S_, WN_) case S_: return launch_one<S_, 2, WN_, MODE>(g, st);
+        OZ_CASE(1, 4) OZ_CASE(2, 4) OZ_CASE(3, 4) OZ_CASE(4, 4) OZ_CASE(5, 4) OZ_CASE(6, 4) OZ_CASE(7, 4) OZ_CASE(8, 4)
+        OZ_CASE(9, 4) OZ_CASE(10, 4) OZ_CASE(11, 4) OZ_CASE(12, 4) OZ_CASE(13, 4) OZ_CASE(14, 2) OZ_CASE(15, 2) OZ_CASE(16, 2)
+#undef OZ_CASE
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+// One translation unit per mode instantiates this for its sixteen slice counts.
+template <int MODE>
+hipError_t launch_product_mode(const GemmArgs& g, int s, hipStream_t st) {
+    return launch_for<MODE>(g, s, st);
+}
+
+}  // namespace ozimmu
