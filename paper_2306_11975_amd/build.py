@@ -29,11 +29,35 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+# translation units whose kernels write M0 in inline assembly (the LDS base of the direct loads)
+USES_M0 = ("gemm_real.hip", "gemm_dd.hip")
+
+
+def _check_m0(src: str) -> None:
+    """The direct global->LDS loads set M0 inside inline assembly, and the compiler does not accept M0 in
+    a clobber list (reserved register). So the generated device assembly is checked instead: apart from
+    those writes no instruction of these kernels may name M0."""
+    import re
+
+    stem = src.rsplit(".", 1)[0]
+    listings = [p for p in OBJ.glob(f"{stem}-hip-amdgcn-amd-amdhsa-gfx950*.s")]
+    if not listings:
+        raise RuntimeError(f"no device assembly listing found for {src} in {OBJ}")
+    ours = re.compile(r"^\s*s_mov_b32\s+m0,\s*(s\d+|vcc_lo|vcc_hi)\s*$")
+    for listing in listings:
+        for n, line in enumerate(listing.read_text().splitlines(), 1):
+            code = line.split(";", 1)[0]
+            if re.search(r"\bm0\b", code) and not ours.match(code):
+                raise RuntimeError(f"{listing.name}:{n}: M0 is used outside the direct-load sequence: {line.strip()}")
+
+
 def _compile(src: str) -> Path:
     obj = OBJ / (src + ".o")
     cmd = [hipcc(), *COMMON]
     if src.endswith(".hip"):
         cmd += DEVICE
+    if src in USES_M0:
+        cmd += ["-save-temps=obj"]       # leaves the device assembly next to the object
     cmd += ["-c", str(CSRC / src), "-o", str(obj)]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
@@ -42,6 +66,8 @@ def _compile(src: str) -> Path:
         raise RuntimeError(f"{' '.join(cmd)}\n{err}")
     if err.strip():
         sys.stderr.write(err + "\n")
+    if src in USES_M0:
+        _check_m0(src)
     return obj
 
 
