@@ -152,8 +152,9 @@ def bench_complex(args, m, n, k, s, statevec=None):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=10,
+                    help="untimed steps first: the launch time of the product kernel settles over the first ten or so launches")
     ap.add_argument("--size", type=int, default=8192, help="m = n = k (the headline workload: 8192)")
     ap.add_argument("--m", type=int, default=0, help="override m (other workloads, e.g. --m 4096 --n 4096 --k 131072 --phi 2)")
     ap.add_argument("--n", type=int, default=0)
