@@ -349,78 +349,91 @@ __device__ __forceinline__ void loss_add(LossAcc& a, unsigned long long bits, in
         a.lost[s - 1] += (uint32_t)beyond;
     }
 }
-// Workgroup-wide sum of the per-thread counters, then one 64-bit atomic per slice count.
-__device__ __forceinline__ void loss_flush(const LossAcc& a, uint32_t* lds16, unsigned long long* sums) {
-    if (threadIdx.x < OZIMMU_MAX_SLICES) lds16[threadIdx.x] = 0u;
+// Workgroup-wide sum of the per-thread counters (64-bit from here on: a workgroup may have scanned
+// many rows), then one 64-bit atomic per slice count.
+__device__ __forceinline__ void loss_flush(const LossAcc& a, unsigned long long* lds16, unsigned long long* sums) {
+    if (threadIdx.x < OZIMMU_MAX_SLICES) lds16[threadIdx.x] = 0ull;
     __syncthreads();
 #pragma unroll
     for (int s = 0; s < OZIMMU_MAX_SLICES; ++s) {
-        uint32_t v = a.lost[s];
+        unsigned long long v = a.lost[s];
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
         if ((threadIdx.x & 63) == 0 && v) atomicAdd(&lds16[s], v);
     }
     __syncthreads();
-    if (threadIdx.x < OZIMMU_MAX_SLICES && lds16[threadIdx.x])
-        atomicAdd(&sums[threadIdx.x], (unsigned long long)lds16[threadIdx.x]);
+    if (threadIdx.x < OZIMMU_MAX_SLICES && lds16[threadIdx.x]) atomicAdd(&sums[threadIdx.x], lds16[threadIdx.x]);
 }
 
-// Rows of A: one workgroup per row, maximum first (the row stays in registers if it is short
-// enough), then the loss counters.
+// Rows of A: as in the row splitter a workgroup takes four rows at a time (a quarter of a wavefront
+// per row, rows of up to 8192 elements cached in registers between the maximum and the scan), but it
+// walks many such groups and flushes its counters once at the end: the sums are 16 atomics on 16
+// addresses per flush, and one flush per row would serialise on them.
 template <bool CACHED, bool VEC>
-__global__ __launch_bounds__(256) void loss_rows_kernel(const double* __restrict__ A, int64_t lda, int inc,
-                                                        int64_t k, unsigned long long* __restrict__ sums) {
+__global__ __launch_bounds__(64 * kRowWavesMax) void loss_rows_kernel(const double* __restrict__ A, int64_t lda, int inc,
+                                                                      int64_t m, int64_t k,
+                                                                      unsigned long long* __restrict__ sums) {
     const int tid = threadIdx.x;
-    const int64_t words = (k + 3) / 4;
-    const unsigned long long* src = reinterpret_cast<const unsigned long long*>(A) + (int64_t)blockIdx.x * lda;
-    unsigned long long cache[CACHED ? kRowCacheWords : 1][4];
-    unsigned long long mx = 0;
-    if (CACHED) {
-#pragma unroll
-        for (int j = 0; j < kRowCacheWords; ++j) {
-            const int64_t w = tid + 256 * j;
-            if (w < words) load_word<VEC>(src, w * 4, k, inc, cache[j]);
-            else cache[j][0] = cache[j][1] = cache[j][2] = cache[j][3] = 0ull;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const unsigned long long a = cache[j][u] & kAbsMask;
-                mx = a > mx ? a : mx;
-            }
-        }
-    } else {
-        for (int64_t w = tid; w < words; w += 256) {
-            unsigned long long b[4];
-            load_word<VEC>(src, w * 4, k, inc, b);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const unsigned long long a = b[u] & kAbsMask;
-                mx = a > mx ? a : mx;
-            }
-        }
-    }
-    mx = wave_max_u64(mx);
-    __shared__ unsigned long long wmax[4];
-    __shared__ uint32_t lds16[OZIMMU_MAX_SLICES];
-    if ((tid & 63) == 0) wmax[tid >> 6] = mx;
-    __syncthreads();
-    mx = wmax[0];
-#pragma unroll
-    for (int w = 1; w < 4; ++w) mx = wmax[w] > mx ? wmax[w] : mx;
-    const int E = exponent_of_max(mx);
-
+    const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const int r4 = lane >> 4, c16 = lane & 15;
+    const int64_t chunks = (k + 63) / 64;
+    __shared__ unsigned long long wmax[kRowWavesMax][kRowGroup];
+    __shared__ unsigned long long lds16[OZIMMU_MAX_SLICES];
     LossAcc acc;
     loss_clear(acc);
-    if (CACHED) {
+    for (int64_t group = blockIdx.x; group * kRowGroup < m; group += gridDim.x) {
+        const int64_t row = group * kRowGroup + r4;
+        const bool live = row < m;
+        const unsigned long long* src = reinterpret_cast<const unsigned long long*>(A) + (live ? row : 0) * lda;
+        const int64_t k_live = live ? k : 0;
+        unsigned long long cache[CACHED ? kRowCacheWords : 1][4];
+        unsigned long long mx = 0;
+        if (CACHED) {
 #pragma unroll
-        for (int j = 0; j < kRowCacheWords; ++j)
+            for (int j = 0; j < kRowCacheWords; ++j) {
+                const int64_t l0 = ((int64_t)(wave + nwaves * j) * 16 + c16) * 4;
+                if (l0 < k_live) load_word<VEC>(src, l0, k_live, inc, cache[j]);
+                else cache[j][0] = cache[j][1] = cache[j][2] = cache[j][3] = 0ull;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) loss_add(acc, cache[j][u], E);   // words beyond the row hold zeros
-    } else {
-        for (int64_t w = tid; w < words; w += 256) {
-            unsigned long long b[4];
-            load_word<VEC>(src, w * 4, k, inc, b);
+                for (int u = 0; u < 4; ++u) {
+                    const unsigned long long a = cache[j][u] & kAbsMask;
+                    mx = a > mx ? a : mx;
+                }
+            }
+        } else {
+            for (int64_t c = wave; c < chunks; c += nwaves) {
+                unsigned long long b[4];
+                load_word<VEC>(src, (c * 16 + c16) * 4, k_live, inc, b);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) loss_add(acc, b[u], E);
+                for (int u = 0; u < 4; ++u) {
+                    const unsigned long long a = b[u] & kAbsMask;
+                    mx = a > mx ? a : mx;
+                }
+            }
+        }
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) {
+            const unsigned long long o = __shfl_xor(mx, off, 64);
+            mx = o > mx ? o : mx;
+        }
+        __syncthreads();   // the maxima of the previous group have been read by everybody
+        if (c16 == 0) wmax[wave][r4] = mx;
+        __syncthreads();
+        mx = wmax[0][r4];
+        for (int w = 1; w < nwaves; ++w) mx = wmax[w][r4] > mx ? wmax[w][r4] : mx;
+        const int E = exponent_of_max(mx);
+        if (CACHED) {
+#pragma unroll
+            for (int j = 0; j < kRowCacheWords; ++j)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) loss_add(acc, cache[j][u], E);   // words beyond the row hold zeros
+        } else {
+            for (int64_t c = wave; c < chunks; c += nwaves) {
+                unsigned long long b[4];
+                load_word<VEC>(src, (c * 16 + c16) * 4, k_live, inc, b);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) loss_add(acc, b[u], E);
+            }
         }
     }
     loss_flush(acc, lds16, sums);
@@ -431,7 +444,7 @@ __global__ __launch_bounds__(256) void loss_cols_kernel(const double* __restrict
                                                         int64_t k, int64_t n, int band,
                                                         const unsigned long long* __restrict__ colmax,
                                                         unsigned long long* __restrict__ sums) {
-    __shared__ uint32_t lds16[OZIMMU_MAX_SLICES];
+    __shared__ unsigned long long lds16[OZIMMU_MAX_SLICES];
     const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     LossAcc acc;
     loss_clear(acc);
@@ -560,15 +573,21 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
 hipError_t launch_loss_scan_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k,
                                  unsigned long long* sums, hipStream_t st) {
     if (m == 0 || k == 0) return hipSuccess;
-    const bool cached = k <= 4 * 256 * kRowCacheWords;
+    const int64_t want = (k + 64 * kRowCacheWords - 1) / (64 * kRowCacheWords);
+    const int nwaves = (int)(want < 1 ? 1 : want > kRowWavesMax ? kRowWavesMax : want);
+    const bool cached = k <= (int64_t)64 * kRowCacheWords * nwaves;
     const bool vec = inc == 1 && lda % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
-    const dim3 grid((unsigned)m), block(256);
+    // enough workgroups to fill the chip several times over, few enough that their final flushes
+    // (16 atomics each) do not queue up
+    const int64_t groups = (m + kRowGroup - 1) / kRowGroup;
+    const int64_t cap = (int64_t)4096 * kRowWavesMax / nwaves;
+    const dim3 grid((unsigned)(groups < cap ? groups : cap)), block(64 * nwaves);
     if (cached) {
-        if (vec) loss_rows_kernel<true, true><<<grid, block, 0, st>>>(A, lda * inc, inc, k, sums);
-        else loss_rows_kernel<true, false><<<grid, block, 0, st>>>(A, lda * inc, inc, k, sums);
+        if (vec) loss_rows_kernel<true, true><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
+        else loss_rows_kernel<true, false><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
     } else {
-        if (vec) loss_rows_kernel<false, true><<<grid, block, 0, st>>>(A, lda * inc, inc, k, sums);
-        else loss_rows_kernel<false, false><<<grid, block, 0, st>>>(A, lda * inc, inc, k, sums);
+        if (vec) loss_rows_kernel<false, true><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
+        else loss_rows_kernel<false, false><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
     }
     return hipGetLastError();
 }
