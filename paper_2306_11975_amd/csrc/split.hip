@@ -324,29 +324,57 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
 // at position v = z + L; s slices keep positions 1 .. 7 s, so it loses min(L, max(0, v - 7 s))
 // bits. The host divides the sums by the element counts and picks the smallest s whose average
 // is within the threshold.
+//
+// With z clamped to [0, 112] (an element that far down loses all L bits for every s <= 16 either
+// way) and v = z + L <= 165, lost(s) = max(0, v - 7 s) - max(0, z - 7 s) = (|v - 7 s| - |z - 7 s| + L) / 2.
+// v and z of four elements fit the four bytes of a register, so one v_sad_u8 per candidate adds
+// |v - 7 s| of all four to a counter (and one more |z - 7 s|): 32 instructions per four elements
+// for the 16 candidates. The halving is done once, when the counters are flushed.
 struct LossAcc {
-    uint32_t lost[OZIMMU_MAX_SLICES];
+    uint32_t sad_v[OZIMMU_MAX_SLICES];   // sum of |v - 7 s|
+    uint32_t sad_z[OZIMMU_MAX_SLICES];   // sum of |z - 7 s|
+    uint32_t bits;                       // sum of L
 };
 __device__ __forceinline__ void loss_clear(LossAcc& a) {
 #pragma unroll
-    for (int s = 0; s < OZIMMU_MAX_SLICES; ++s) a.lost[s] = 0u;
+    for (int s = 0; s < OZIMMU_MAX_SLICES; ++s) a.sad_v[s] = a.sad_z[s] = 0u;
+    a.bits = 0u;
 }
-__device__ __forceinline__ void loss_add(LossAcc& a, unsigned long long bits, int E) {
+// z (clamped) and L of one element; both 0 for a zero.
+__device__ __forceinline__ void loss_position(unsigned long long bits, int E, uint32_t& z, uint32_t& L) {
     const unsigned long long mag = bits & kAbsMask;
-    if (mag == 0) return;
     const int e = (int)(mag >> 52);
-    int L = 53, z = E + 1022 - e;
-    if (e == 0) {                       // subnormal: leading bit b of the stored field
-        const int b = 63 - __clzll((long long)mag);
-        L = b + 1;
-        z = E + 1073 - b;
+    int zz = E + 1022 - e, LL = 53;
+    if (e == 0) {                       // zero, or subnormal with leading bit b of the stored field
+        if (mag == 0) {
+            zz = 0;
+            LL = 0;
+        } else {
+            const int b = 63 - __clzll((long long)mag);
+            LL = b + 1;
+            zz = E + 1073 - b;
+        }
     }
-    const int v = z + L;
+    z = (uint32_t)(zz < 0 ? 0 : zz > OZIMMU_SLICE_BITS * OZIMMU_MAX_SLICES ? OZIMMU_SLICE_BITS * OZIMMU_MAX_SLICES : zz);
+    L = (uint32_t)LL;
+}
+// Four elements that share the exponent E (zeros count nothing: v = z = L = 0).
+__device__ __forceinline__ void loss_add4(LossAcc& a, const unsigned long long b[4], int E) {
+    uint32_t pz = 0, pl = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        uint32_t z, L;
+        loss_position(b[u], E, z, L);
+        pz |= z << (8 * u);
+        pl |= L << (8 * u);
+    }
+    const uint32_t pv = pz + pl;          // bytewise: no byte exceeds 165
+    a.bits = __builtin_amdgcn_sad_u8(pl, 0u, a.bits);
 #pragma unroll
     for (int s = 1; s <= OZIMMU_MAX_SLICES; ++s) {
-        int beyond = v - OZIMMU_SLICE_BITS * s;
-        beyond = beyond < 0 ? 0 : (beyond > L ? L : beyond);
-        a.lost[s - 1] += (uint32_t)beyond;
+        const uint32_t edge = 0x01010101u * (uint32_t)(OZIMMU_SLICE_BITS * s);
+        a.sad_v[s - 1] = __builtin_amdgcn_sad_u8(pv, edge, a.sad_v[s - 1]);
+        a.sad_z[s - 1] = __builtin_amdgcn_sad_u8(pz, edge, a.sad_z[s - 1]);
     }
 }
 // Workgroup-wide sum of the per-thread counters (64-bit from here on: a workgroup may have scanned
@@ -356,7 +384,7 @@ __device__ __forceinline__ void loss_flush(const LossAcc& a, unsigned long long*
     __syncthreads();
 #pragma unroll
     for (int s = 0; s < OZIMMU_MAX_SLICES; ++s) {
-        unsigned long long v = a.lost[s];
+        unsigned long long v = (a.sad_v[s] - a.sad_z[s] + a.bits) >> 1;   // this thread's lost bits: exact, no wrap
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
         if ((threadIdx.x & 63) == 0 && v) atomicAdd(&lds16[s], v);
@@ -365,24 +393,27 @@ __device__ __forceinline__ void loss_flush(const LossAcc& a, unsigned long long*
     if (threadIdx.x < OZIMMU_MAX_SLICES && lds16[threadIdx.x]) atomicAdd(&sums[threadIdx.x], lds16[threadIdx.x]);
 }
 
-// Rows of A: as in the row splitter a workgroup takes four rows at a time (a quarter of a wavefront
-// per row, rows of up to 8192 elements cached in registers between the maximum and the scan), but it
-// walks many such groups and flushes its counters once at the end: the sums are 16 atomics on 16
-// addresses per flush, and one flush per row would serialise on them.
-template <bool CACHED, bool VEC>
-__global__ __launch_bounds__(64 * kRowWavesMax) void loss_rows_kernel(const double* __restrict__ A, int64_t lda, int inc,
-                                                                      int64_t m, int64_t k,
-                                                                      unsigned long long* __restrict__ sums) {
+// Rows of A: ROWS rows at a time per workgroup, 64 / ROWS lanes of every wavefront on each (four
+// rows for short ones as in the row splitter, one for long ones), rows of up to 8192 elements cached
+// in registers between the maximum and the scan. A workgroup walks many such groups and flushes its
+// counters once at the end: the sums are 16 atomics on 16 addresses per flush, and one flush per
+// row would serialise on them.
+constexpr int kLossWavesMax = 4;
+template <int ROWS, bool CACHED, bool VEC>
+__global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_kernel(const double* __restrict__ A, int64_t lda, int inc,
+                                                                       int64_t m, int64_t k,
+                                                                       unsigned long long* __restrict__ sums) {
+    constexpr int LPR = 64 / ROWS;   // lanes per row
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
-    const int r4 = lane >> 4, c16 = lane & 15;
-    const int64_t chunks = (k + 63) / 64;
-    __shared__ unsigned long long wmax[kRowWavesMax][kRowGroup];
+    const int rsub = lane / LPR, c = lane % LPR;
+    const int64_t chunks = (k + 4 * LPR - 1) / (4 * LPR);
+    __shared__ unsigned long long wmax[kLossWavesMax][ROWS];
     __shared__ unsigned long long lds16[OZIMMU_MAX_SLICES];
     LossAcc acc;
     loss_clear(acc);
-    for (int64_t group = blockIdx.x; group * kRowGroup < m; group += gridDim.x) {
-        const int64_t row = group * kRowGroup + r4;
+    for (int64_t group = blockIdx.x; group * ROWS < m; group += gridDim.x) {
+        const int64_t row = group * ROWS + rsub;
         const bool live = row < m;
         const unsigned long long* src = reinterpret_cast<const unsigned long long*>(A) + (live ? row : 0) * lda;
         const int64_t k_live = live ? k : 0;
@@ -391,7 +422,7 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void loss_rows_kernel(const doub
         if (CACHED) {
 #pragma unroll
             for (int j = 0; j < kRowCacheWords; ++j) {
-                const int64_t l0 = ((int64_t)(wave + nwaves * j) * 16 + c16) * 4;
+                const int64_t l0 = ((int64_t)(wave + nwaves * j) * LPR + c) * 4;
                 if (l0 < k_live) load_word<VEC>(src, l0, k_live, inc, cache[j]);
                 else cache[j][0] = cache[j][1] = cache[j][2] = cache[j][3] = 0ull;
 #pragma unroll
@@ -401,9 +432,9 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void loss_rows_kernel(const doub
                 }
             }
         } else {
-            for (int64_t c = wave; c < chunks; c += nwaves) {
+            for (int64_t ch = wave; ch < chunks; ch += nwaves) {
                 unsigned long long b[4];
-                load_word<VEC>(src, (c * 16 + c16) * 4, k_live, inc, b);
+                load_word<VEC>(src, (ch * LPR + c) * 4, k_live, inc, b);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const unsigned long long a = b[u] & kAbsMask;
@@ -412,27 +443,24 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void loss_rows_kernel(const doub
             }
         }
 #pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) {
+        for (int off = LPR / 2; off >= 1; off >>= 1) {
             const unsigned long long o = __shfl_xor(mx, off, 64);
             mx = o > mx ? o : mx;
         }
         __syncthreads();   // the maxima of the previous group have been read by everybody
-        if (c16 == 0) wmax[wave][r4] = mx;
+        if (c == 0) wmax[wave][rsub] = mx;
         __syncthreads();
-        mx = wmax[0][r4];
-        for (int w = 1; w < nwaves; ++w) mx = wmax[w][r4] > mx ? wmax[w][r4] : mx;
+        mx = wmax[0][rsub];
+        for (int w = 1; w < nwaves; ++w) mx = wmax[w][rsub] > mx ? wmax[w][rsub] : mx;
         const int E = exponent_of_max(mx);
         if (CACHED) {
 #pragma unroll
-            for (int j = 0; j < kRowCacheWords; ++j)
-#pragma unroll
-                for (int u = 0; u < 4; ++u) loss_add(acc, cache[j][u], E);   // words beyond the row hold zeros
+            for (int j = 0; j < kRowCacheWords; ++j) loss_add4(acc, cache[j], E);   // words beyond the row hold zeros
         } else {
-            for (int64_t c = wave; c < chunks; c += nwaves) {
+            for (int64_t ch = wave; ch < chunks; ch += nwaves) {
                 unsigned long long b[4];
-                load_word<VEC>(src, (c * 16 + c16) * 4, k_live, inc, b);
-#pragma unroll
-                for (int u = 0; u < 4; ++u) loss_add(acc, b[u], E);
+                load_word<VEC>(src, (ch * LPR + c) * 4, k_live, inc, b);
+                loss_add4(acc, b, E);
             }
         }
     }
@@ -453,7 +481,12 @@ __global__ __launch_bounds__(256) void loss_cols_kernel(const double* __restrict
         const int64_t l0 = (int64_t)blockIdx.y * band;
         const int64_t l1 = l0 + band < k ? l0 + band : k;
         const unsigned long long* src = reinterpret_cast<const unsigned long long*>(B);
-        for (int64_t l = l0; l < l1; ++l) loss_add(acc, src[(l * ldb + j) * inc], E);
+        for (int64_t l = l0; l < l1; l += 4) {   // four elements of the column at a time; zeros past the band
+            unsigned long long b[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) b[u] = l + u < l1 ? src[((l + u) * ldb + j) * inc] : 0ull;
+            loss_add4(acc, b, E);
+        }
     }
     loss_flush(acc, lds16, sums);
 }
@@ -570,26 +603,35 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
     return hipGetLastError();
 }
 
+template <int ROWS>
+static hipError_t launch_loss_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k,
+                                   unsigned long long* sums, hipStream_t st) {
+    // a wavefront covers 4 * (64 / ROWS) elements of each of its rows per word it caches
+    const int64_t per_wave = (int64_t)4 * (64 / ROWS) * kRowCacheWords;
+    const int64_t want = (k + per_wave - 1) / per_wave;
+    const int nwaves = (int)(want < 1 ? 1 : want > kLossWavesMax ? kLossWavesMax : want);
+    const bool cached = k <= per_wave * nwaves;
+    const bool vec = inc == 1 && lda % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
+    // 16 wavefronts per compute unit: enough to keep the memory system busy, and few final flushes
+    const int64_t groups = (m + ROWS - 1) / ROWS;
+    const int64_t cap = (int64_t)256 * 16 / nwaves;
+    const dim3 grid((unsigned)(groups < cap ? groups : cap)), block(64 * nwaves);
+    if (cached) {
+        if (vec) loss_rows_kernel<ROWS, true, true><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
+        else loss_rows_kernel<ROWS, true, false><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
+    } else {
+        if (vec) loss_rows_kernel<ROWS, false, true><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
+        else loss_rows_kernel<ROWS, false, false><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_loss_scan_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k,
                                  unsigned long long* sums, hipStream_t st) {
     if (m == 0 || k == 0) return hipSuccess;
-    const int64_t want = (k + 64 * kRowCacheWords - 1) / (64 * kRowCacheWords);
-    const int nwaves = (int)(want < 1 ? 1 : want > kRowWavesMax ? kRowWavesMax : want);
-    const bool cached = k <= (int64_t)64 * kRowCacheWords * nwaves;
-    const bool vec = inc == 1 && lda % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
-    // enough workgroups to fill the chip several times over, few enough that their final flushes
-    // (16 atomics each) do not queue up
-    const int64_t groups = (m + kRowGroup - 1) / kRowGroup;
-    const int64_t cap = (int64_t)4096 * kRowWavesMax / nwaves;
-    const dim3 grid((unsigned)(groups < cap ? groups : cap)), block(64 * nwaves);
-    if (cached) {
-        if (vec) loss_rows_kernel<true, true><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
-        else loss_rows_kernel<true, false><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
-    } else {
-        if (vec) loss_rows_kernel<false, true><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
-        else loss_rows_kernel<false, false><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
-    }
-    return hipGetLastError();
+    // four rows per wavefront while four wavefronts still hold them in registers (k <= 2048)
+    if (k <= (int64_t)4 * 16 * kRowCacheWords * kLossWavesMax) return launch_loss_rows<4>(A, lda, inc, m, k, sums, st);
+    return launch_loss_rows<1>(A, lda, inc, m, k, sums, st);
 }
 
 hipError_t launch_loss_scan_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n,

@@ -67,6 +67,15 @@ def test_auto_single_binade_and_limits():
                                   torch.empty((0, 3), dtype=torch.float64, device="cuda"), 0.0)[0] == 1
 
 
+@pytest.mark.parametrize("m,k", [(20001, 100), (2500, 3000), (3, 20000)])
+def test_auto_workgroups_that_walk_several_row_groups(m, k):
+    """More row groups than the scan launches workgroups (four short rows per wavefront: 20001 x 100;
+    one long row per workgroup: 2500 x 3000), and rows too long for the register cache (3 x 20000)."""
+    A = wl.phi_matrix(m, k, 1.5, seed=21)
+    B = wl.phi_matrix(k, 5, 1.0, seed=22)
+    check(A, B, thresholds=(0.0, 1.0))
+
+
 def test_auto_complex_planes():
     A = wl.gaussian_complex(130, 256, seed=1)
     B = wl.unit_column_complex(256, 70, seed=2)
