@@ -20,7 +20,11 @@ static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * 
 // 64 x 128 tile of C) while two pipeline stages of all slices fit the LDS, 2 x 2 beyond.
 static inline void tile_waves(int s, int* wm, int* wn) {
     *wm = 2;
+#ifdef OZ_EXP_SMALL
+    *wn = s <= 9 || s > 13 ? 2 : 4;
+#else
     *wn = s <= 13 ? 4 : 2;
+#endif
 }
 
 // Arguments of the slice-product kernel. One launch covers every tile of C.

@@ -54,7 +54,11 @@ struct Band {
     // for the next step; beyond 11 slices they no longer fit beside the accumulators and the B
     // fragments are streamed through three registers instead.
     static constexpr bool RESIDENT = SB <= 11;
+#ifdef OZ_EXP_SMALL
+    static constexpr int FIT = (WN == 2 && SB <= 9 ? 79 * 1024 : kLdsLimit) / STAGE;
+#else
     static constexpr int FIT = kLdsLimit / STAGE;
+#endif
     static constexpr int NST = !RESIDENT ? 2 : FIT > kMaxStages ? kMaxStages : FIT;
     static constexpr int LDS = NST * STAGE;
     static constexpr int NLOAD = (NFRAG + NW - 1) / NW;   // direct loads per wavefront and step
@@ -319,21 +323,28 @@ __device__ __forceinline__ void fold_band_dd(double (&h)[16], double (&l)[16], c
     }
 }
 
-// One element of the result: C (op)= val, with the combine mode of the call.
-__device__ __forceinline__ void write_c_element(const GemmArgs& g, int row, int col, double val) {
+// Whether the combine mode of the call reads the old contents of C.
+__device__ __forceinline__ bool c_mode_reads(const GemmArgs& g) {
+    return g.c_mode == 1 || g.c_mode == 2 || g.c_mode == 4 || (g.c_mode == 3 && g.beta != 0.0);
+}
+
+// One element of the result: C (op)= val, with the combine mode of the call. `old_c` is the element of
+// C (and `old_zr` that of Zr) fetched ahead of time for the modes that read them.
+__device__ __forceinline__ void write_c_element(const GemmArgs& g, int row, int col, double val, double old_c,
+                                                double old_zr) {
     if (row < g.m && col < g.n) {
         double* c = g.C + (int64_t)row * g.ldc + col;
         if (g.c_mode == 0) *c = val;
-        else if (g.c_mode == 1) *c = *c + val;
-        else if (g.c_mode == 2) *c = *c - val;
+        else if (g.c_mode == 1) *c = old_c + val;
+        else if (g.c_mode == 2) *c = old_c - val;
         else if (g.c_mode == 3) {   // BLAS update: RN(alpha G), then RN(RN(alpha G) + RN(beta C)); C is not read if beta == 0
             double v = g.alpha * val;
-            if (g.beta != 0.0) v = v + g.beta * *c;
+            if (g.beta != 0.0) v = v + g.beta * old_c;
             *c = v;
         } else {   // last of the four real products of a complex one: (re, im) = (Zr, C + val) -> interleaved Cz
             double2 z;
-            z.x = g.Zr[(int64_t)row * g.ldc + col];
-            z.y = *c + val;
+            z.x = old_zr;
+            z.y = old_c + val;
             *reinterpret_cast<double2*>(g.Cz + 2 * ((int64_t)row * g.ldcz + col)) = z;
         }
     }
@@ -342,7 +353,11 @@ __device__ __forceinline__ void write_c_element(const GemmArgs& g, int row, int 
 constexpr int kModeReal = 0, kModeDD = 1;
 
 template <int S, int WM, int WN, int MODE>
+#ifdef OZ_EXP_SMALL
+__global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(S <= 9 ? 2 : WM * WN / 4, S <= 9 ? 2 : WM * WN / 4)))
+#else
 __global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(WM * WN / 4, WM * WN / 4)))
+#endif
 void product_kernel(const GemmArgs g) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int T = 64 * WM * WN;
@@ -398,9 +413,10 @@ void product_kernel(const GemmArgs g) {
             if (i < nd) {
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
-                    long long v = (long long)acc_read(acc[i][u]);
-                    if (!first) v += *q;
-                    *q = v;
+                    const long long v = (long long)acc_read(acc[i][u]);
+                    // later blocks add with an atomic that returns nothing: no round trip per element
+                    if (first) *q = v;
+                    else __hip_atomic_fetch_add(q, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     q += T;
                     __builtin_amdgcn_sched_barrier(0);   // keep register pressure flat
                 }
@@ -431,6 +447,27 @@ void product_kernel(const GemmArgs g) {
         sa = g.SA;
         sb = g.SB;
     };
+    // The elements of C that the combine mode reads are requested before the diagonals are folded, so
+    // that they arrive while the fold runs (sixteen dependent round trips to memory otherwise); those of
+    // Zr (complex interleave only) in one batch after it, when the fold's registers are free again.
+    double old_c[MODE == kModeReal ? 16 : 1], old_zr[MODE == kModeReal ? 16 : 1];
+    auto fetch_old = [&](double (&dst)[MODE == kModeReal ? 16 : 1], const double* src, bool wanted) __attribute__((always_inline)) {
+        if constexpr (MODE == kModeReal) {
+            if (!wanted) {
+#pragma unroll
+                for (int u = 0; u < 16; ++u) dst[u] = 0.0;
+                return;
+            }
+            const int oz = (int)opaque_zero();
+            const int row0 = row0_ + oz, col = col_ + oz;
+            const double* c = src + (int64_t)row0 * g.ldc + col;
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int dr = 8 * (u >> 2) + (u & 3);
+                dst[u] = row0 + dr < g.m && col < g.n ? c[(int64_t)dr * g.ldc] : 0.0;
+            }
+        }
+    };
     // The sum of product `prod` is complete (in `sum`, or in the INT64 sums of the workspace): scale it,
     // combine it, store what is final.
     auto finish_product = [&](int prod) __attribute__((always_inline)) {
@@ -452,12 +489,16 @@ void product_kernel(const GemmArgs g) {
                 const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * (e + 2)) << 52);
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
-                    const double term = (double)q[((int64_t)e * num_tiles * 16 + u) * T] * sc;   // exact: |S_e| < 2^53
+                    // read at the L2, where the atomic adds of the blocks were applied
+                    const long long s_e = __hip_atomic_load(q + ((int64_t)e * num_tiles * 16 + u) * T, __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT);
+                    const double term = (double)s_e * sc;   // exact: |S_e| < 2^53
                     if constexpr (MODE == kModeDD) dd_add(sum[u], lo[u], term);
                     else sum[u] = sum[u] + term;
                 }
             }
         }
+        fetch_old(old_zr, g.Zr, g.c_mode == 4);
         const int eb = ex[TR + lcol];
 #pragma unroll
         for (int u4 = 0; u4 < 4; ++u4) {
@@ -474,7 +515,7 @@ void product_kernel(const GemmArgs g) {
                         g.C_lo[(int64_t)row * g.ldc + col] = ldexp(lo[u], e);
                     }
                 } else {
-                    write_c_element(g, row, col, val);
+                    write_c_element(g, row, col, val, old_c[MODE == kModeReal ? u : 0], old_zr[MODE == kModeReal ? u : 0]);
                 }
             }
         }
@@ -497,6 +538,7 @@ void product_kernel(const GemmArgs g) {
             },
             [&](int prod) __attribute__((always_inline)) {
                 if (first_band) clear_sum();
+                if (last_band) fetch_old(old_c, g.C, !g.P && c_mode_reads(g));
                 if (!wide && !g.P) {
                     if constexpr (MODE == kModeDD) fold_band_dd<SB>(sum, lo, acc);
                     else fold_band<SB>(sum, acc);
@@ -530,7 +572,11 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t st) {
 template <int MODE>
 hipError_t launch_for(const GemmArgs& g, int s, hipStream_t st) {
     switch (s) {
+#ifdef OZ_EXP_SMALL
+#define OZ_CASE(S_, WN_) case S_: return launch_one<S_, 2, (S_ <= 9 ? 2 : WN_), MODE>(g, st);
+#else
 #define OZ_CASE(S_, WN_) case S_: return launch_one<S_, 2, WN_, MODE>(g, st);
+#endif
         OZ_CASE(1, 4) OZ_CASE(2, 4) OZ_CASE(3, 4) OZ_CASE(4, 4) OZ_CASE(5, 4) OZ_CASE(6, 4) OZ_CASE(7, 4) OZ_CASE(8, 4)
         OZ_CASE(9, 4) OZ_CASE(10, 4) OZ_CASE(11, 4) OZ_CASE(12, 4) OZ_CASE(13, 4) OZ_CASE(14, 2) OZ_CASE(15, 2) OZ_CASE(16, 2)
 #undef OZ_CASE
