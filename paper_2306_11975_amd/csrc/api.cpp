@@ -88,7 +88,7 @@ ozimmu_status_t check_gemm_args(int64_t m, int64_t n, int64_t k, const void* A, 
 // c_mode says (C_lo != nullptr: double-double sum into C, C_lo).
 hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned char* ws, int plane_a, int plane_b,
                        double* C, int64_t ldc, int c_mode, hipStream_t st, double alpha = 1.0, double beta = 0.0,
-                       double* C_lo = nullptr, const double* Zr = nullptr, double* Cz = nullptr, int64_t ldcz = 0) {
+                       double* C_lo = nullptr, double* Zr = nullptr, double* Cz = nullptr, int64_t ldcz = 0) {
     GemmArgs g{};
     g.SA = reinterpret_cast<const int8_t*>(ws + L.off_sa[plane_a]);
     g.SB = reinterpret_cast<const int8_t*>(ws + L.off_sb[plane_b]);
@@ -126,6 +126,35 @@ hipError_t run_complex_products(const Layout& L, int64_t m, int64_t n, int s, un
                                 int64_t ldc, hipStream_t st) {
     double* Pr = reinterpret_cast<double*>(ws + L.off_z);
     double* Pi = Pr + (size_t)m * n;
+    // one launch: every workgroup walks the four products of its tile one after the other (the walk runs
+    // three steps ahead of the matrix cores: shorter products and k-blocked ones take four launches)
+    if (!L.wide && L.k_pad / kSlab >= 3) {
+        GemmArgs g{};
+        g.SA = reinterpret_cast<const int8_t*>(ws + L.off_sa[0]);
+        g.SA2 = reinterpret_cast<const int8_t*>(ws + L.off_sa[1]);
+        g.SB = reinterpret_cast<const int8_t*>(ws + L.off_sb[0]);
+        g.SB2 = reinterpret_cast<const int8_t*>(ws + L.off_sb[1]);
+        g.EA = reinterpret_cast<const int32_t*>(ws + L.off_ea[0]);
+        g.EA2 = reinterpret_cast<const int32_t*>(ws + L.off_ea[1]);
+        g.EB = reinterpret_cast<const int32_t*>(ws + L.off_eb[0]);
+        g.EB2 = reinterpret_cast<const int32_t*>(ws + L.off_eb[1]);
+        g.a_slice_stride = L.m_pad * L.k_pad;
+        g.b_slice_stride = L.n_pad * L.k_pad;
+        g.kslabs = (int)(L.k_pad / kSlab);
+        g.t_begin = 0;
+        g.t_end = g.kslabs;
+        g.tiles_m = L.tiles_m;
+        g.tiles_n = L.tiles_n;
+        g.m = (int)m;
+        g.n = (int)n;
+        g.Zr = Pr;
+        g.C = Pi;
+        g.ldc = n;
+        g.Cz = C;
+        g.ldcz = ldc;
+        g.alpha = 1.0;
+        return launch_slice_gemm(g, s, 2, st);
+    }
     hipError_t e = run_product(L, m, n, s, ws, 0, 0, Pr, n, 0, st);
     if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 1, Pr, n, 2, st);
     if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, Pi, n, 0, st);

@@ -20,11 +20,7 @@ static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * 
 // 64 x 128 tile of C) while two pipeline stages of all slices fit the LDS, 2 x 2 beyond.
 static inline void tile_waves(int s, int* wm, int* wn) {
     *wm = 2;
-#ifdef OZ_EXP_SMALL
-    *wn = s <= 9 || s > 13 ? 2 : 4;
-#else
     *wn = s <= 13 ? 4 : 2;
-#endif
 }
 
 // Arguments of the slice-product kernel. One launch covers every tile of C.
@@ -45,13 +41,19 @@ struct GemmArgs {
     int64_t ldc;             // in doubles
     int c_mode;              // 0: C = G, 1: C = C + G, 2: C = C - G, 3: C = alpha G (+ beta C if beta != 0),
                              // 4: (Zr, C + G) -> Cz as interleaved (re, im) pairs (C is read only)
-    const double* Zr;        // c_mode 4: finished real parts, same shape and leading dimension as C
+    double* Zr;              // c_mode 4: finished real parts, same shape and leading dimension as C (complex
+                             // mode: the plane the real part is formed in)
     double* Cz;              // c_mode 4: complex output
     int64_t ldcz;            // c_mode 4: its leading dimension in complex elements
     double alpha, beta;      // c_mode 3 only
     double* C_lo;            // low parts of a double-double result (double-double summing-up only)
     const int32_t* EA;
     const int32_t* EB;
+    // complex mode only: the slice tensors and exponents of the imaginary planes (SA, SB, EA, EB: real planes)
+    const int8_t* SA2;
+    const int8_t* SB2;
+    const int32_t* EA2;
+    const int32_t* EB2;
 };
 
 // negate: emit the slices of -A (-B) instead: same exponents, every slice with the opposite sign
@@ -63,7 +65,8 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
                              int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
                              unsigned long long* colmax, hipStream_t st, bool negate = false);
 // Slice products of the pairs p + q <= s + 1 with the FP64 sum. mode 0: FP64 sum; 1: double-double sum
-// into C, C_lo.
+// into C, C_lo; 2: the four real products of a complex one in one launch (no k-blocking: block_steps == 0),
+// real part formed in the plane Zr, imaginary part in the plane C, result interleaved in Cz.
 hipError_t launch_slice_gemm(const GemmArgs& args, int s, int mode, hipStream_t st);
 // Slice-count scan: adds, for s = 1 .. 16, the mantissa bits s slices would lose into sums[s - 1].
 hipError_t launch_loss_scan_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k,

@@ -54,11 +54,7 @@ struct Band {
     // for the next step; beyond 11 slices they no longer fit beside the accumulators and the B
     // fragments are streamed through three registers instead.
     static constexpr bool RESIDENT = SB <= 11;
-#ifdef OZ_EXP_SMALL
-    static constexpr int FIT = (WN == 2 && SB <= 9 ? 79 * 1024 : kLdsLimit) / STAGE;
-#else
     static constexpr int FIT = kLdsLimit / STAGE;
-#endif
     static constexpr int NST = !RESIDENT ? 2 : FIT > kMaxStages ? kMaxStages : FIT;
     static constexpr int LDS = NST * STAGE;
     static constexpr int NLOAD = (NFRAG + NW - 1) / NW;   // direct loads per wavefront and step
@@ -74,6 +70,8 @@ struct Shape {
     static constexpr int LDS = LDS1 > LDS2 ? LDS1 : LDS2;
 };
 
+typedef __attribute__((address_space(3))) long long lds_i64;
+
 // What a wavefront needs to know about its place in the walk.
 struct Walk {
     unsigned char* lds;      // dynamic LDS segment
@@ -82,6 +80,7 @@ struct Walk {
     int lane, wave, wm, wn;
     int tm, tn;
     int tid;
+    lds_i64* switch_table;     // this wavefront's LDS table of source-address changes between products (streams of products only)
 };
 
 // Compile-time loop: f(integral_constant<int, I>) for I = BEGIN .. END - 1.
@@ -113,14 +112,12 @@ __device__ __forceinline__ void workgroup_barrier() {
 }
 
 // The walk of one band over the slabs [g.t_begin, g.t_end), for the products p_begin .. p_end - 1 one
-// after the other: sources(p, sa, sb)
-// names the slice tensors of product p, acc[e - E0] receives the pairs of diagonal e,
-// after_step(steps done in this product) is called after every step (k-blocking hooks in there) and
-// after_product(p) when a product's last step has been issued (it takes the sums and clears acc).
-// In the register-resident schedule the products form one continuous stream of steps: the loads run
-// NST steps ahead of the matrix cores straight across a product boundary, so only the first product
-// of a call pays for filling the pipeline.
-template <int SB, int WM, int WN, class Sources, class AfterStep, class AfterProduct>
+// after the other: sources(p, sa, sb) names the slice tensors of product p, acc[e - E0] receives the
+// pairs of diagonal e, after_step(steps done in this product) is called after every step (k-blocking
+// hooks in there) and after_product(p) when a product's last step has been issued (it takes the sums
+// and clears acc). STREAM (register-resident schedule only, at least NST steps per product): the
+// products form one continuous stream of steps and only the first one pays for filling the pipeline.
+template <int SB, int WM, int WN, bool STREAM, class Sources, class AfterStep, class AfterProduct>
 __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g, const Walk& w, int p_begin, int p_end,
                                           Sources&& sources, AfterStep&& after_step, AfterProduct&& after_product) {
     using B = Band<SB, WM, WN>;
@@ -132,47 +129,43 @@ __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g,
     // place), so that every wavefront has the same number of loads in flight.
     const int8_t* src[NLOAD];
     unsigned dst[NLOAD];
-    auto set_sources = [&](int prod) __attribute__((always_inline)) {
+    auto fragment_index = [&](int jj) __attribute__((always_inline)) -> int {
+        const int idx = w.wave + B::NW * jj;
+        return idx < B::NFRAG ? idx : B::NFRAG - 1;
+    };
+    auto fragment_ptr = [&](int prod, int jj) __attribute__((always_inline)) -> const int8_t* {
         const int8_t *sa, *sb;
         sources(prod, sa, sb);
+        const int idx = fragment_index(jj);
+        if (idx < SB * WM) {
+            const int p = idx / WM, i = idx % WM;
+            return sa + (int64_t)p * g.a_slice_stride + (int64_t)(w.tm * WM + i) * g.kslabs * kFragBytes;
+        }
+        const int r = idx - SB * WM;
+        const int q = r / WN, j = r % WN;
+        return sb + (int64_t)q * g.b_slice_stride + (int64_t)(w.tn * WN + j) * g.kslabs * kFragBytes;
+    };
+    auto set_sources = [&](int prod) __attribute__((always_inline)) {
 #pragma unroll
         for (int jj = 0; jj < NLOAD; ++jj) {
-            int idx = w.wave + B::NW * jj;
-            idx = idx < B::NFRAG ? idx : B::NFRAG - 1;
-            const int8_t* s;
-            if (idx < SB * WM) {
-                const int p = idx / WM, i = idx % WM;
-                s = sa + (int64_t)p * g.a_slice_stride + (int64_t)(w.tm * WM + i) * g.kslabs * kFragBytes;
-            } else {
-                const int r = idx - SB * WM;
-                const int q = r / WN, j = r % WN;
-                s = sb + (int64_t)q * g.b_slice_stride + (int64_t)(w.tn * WN + j) * g.kslabs * kFragBytes;
-            }
             // wave-uniform by construction; say so, so that they live in scalar registers
-            src[jj] = uniform_ptr(s);
-            dst[jj] = (unsigned)__builtin_amdgcn_readfirstlane((int)(w.lds_base + (unsigned)idx * kFragBytes));
+            src[jj] = uniform_ptr(fragment_ptr(prod, jj));
+            dst[jj] = (unsigned)__builtin_amdgcn_readfirstlane((int)(w.lds_base + (unsigned)fragment_index(jj) * kFragBytes));
         }
     };
     const int steps = g.t_end - g.t_begin;
-    // The request side: product ld_p, step ld_t of it, lane offset voff into its source fragments.
-    // Past the last step of the last product the last step is requested again (into a stage nobody
-    // reads any more), so that the number of loads in flight never changes.
+    wait_loads<0>();   // stores of an earlier product's epilogue must not be counted as direct loads
+    // The request side: step ld_t of the product, lane offset voff into its source fragments. Past the
+    // last step of the last product the last step is requested again (into a stage nobody reads any
+    // more), so that the number of loads in flight never changes.
     const unsigned voff_first = (unsigned)w.lane * 16u + (unsigned)g.t_begin * kFragBytes;
     unsigned voff = voff_first;
-    int ld_p = p_begin, ld_t = 0, ld_end = p_end;
+    int ld_t = 0;
     auto issue_one = [&](int jj, unsigned stage_off) __attribute__((always_inline)) {
         dma_load16(src[jj], voff, dst[jj] + stage_off);
         if (jj == NLOAD - 1) {   // the step is requested: move on
-            if (++ld_t < steps) {
-                voff += kFragBytes;
-            } else if (ld_p + 1 < ld_end) {
-                ++ld_p;
-                ld_t = 0;
-                set_sources(ld_p);
-                voff = voff_first;
-            } else {
-                --ld_t;
-            }
+            if (++ld_t < steps) voff += kFragBytes;
+            else --ld_t;
         }
     };
     auto issue = [&](unsigned stage_off) __attribute__((always_inline)) {
@@ -198,48 +191,114 @@ __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g,
         constexpr int AHEAD = NST - 1;
         v4i a[SB], b[SB];
         unsigned cur = 0;
-        set_sources(ld_p);
-        static_for<0, NST>([&](auto sc) __attribute__((always_inline)) { issue(decltype(sc)::value * B::STAGE); });
-        wait_loads<AHEAD * NLOAD>();    // step 0 has landed
-        workgroup_barrier();
-        static_for<0, SB>([&](auto pc) __attribute__((always_inline)) {
-            constexpr int p = decltype(pc)::value;
-            a[SB - 1 - p] = read_a(SB - 1 - p, cur);
-            b[p] = read_b(p, cur);
-        });
-        for (int prod = p_begin; prod < p_end; ++prod) {
-            for (int t = 0; t < steps; ++t) {
-                const unsigned nxt = cur + B::STAGE < (unsigned)B::LDS ? cur + B::STAGE : 0u;
-                static_for<0, SB>([&](auto qc) __attribute__((always_inline)) {
-                    constexpr int q = decltype(qc)::value;
-                    constexpr int pmax = SB - 1 - q, pmin = E0 - q > 0 ? E0 - q : 0;
-                    static_for<0, pmax - pmin + 1>([&](auto ic) __attribute__((always_inline)) {
-                        constexpr int p = pmax - decltype(ic)::value;
-                        acc[p + q - E0] = mfma(a[p], b[q], acc[p + q - E0]);
-                    });
-                    if constexpr (q == 0) {
-                        // step t + 1 has landed everywhere (its fragments may be read from here on) and
-                        // every wavefront has read the last fragment of step t: its stage is free
-                        __builtin_amdgcn_sched_barrier(0);
-                        wait_loads<(AHEAD - 1) * NLOAD>();
-                        workgroup_barrier();
-                    }
-                    // one direct load per group (NLOAD <= SB): a wavefront stalls while its load is issued,
-                    // and eight wavefronts that issue all their loads at once queue behind each other
-                    if constexpr (q < NLOAD) issue_one(q, cur);
-                    b[q] = read_b(q, nxt);
-                    a[pmax] = read_a(pmax, nxt);
-                    __builtin_amdgcn_sched_barrier(0);   // keep the re-reads where their registers fall free
+        auto read_all = [&]() __attribute__((always_inline)) {
+            static_for<0, SB>([&](auto pc) __attribute__((always_inline)) {
+                constexpr int p = decltype(pc)::value;
+                a[SB - 1 - p] = read_a(SB - 1 - p, cur);
+                b[p] = read_b(p, cur);
+            });
+        };
+        // One step; issue_q(jj, stage) requests this wavefront's jj-th fragment of the step NST ahead.
+        auto step = [&](auto&& issue_q) __attribute__((always_inline)) {
+            const unsigned nxt = cur + B::STAGE < (unsigned)B::LDS ? cur + B::STAGE : 0u;
+            static_for<0, SB>([&](auto qc) __attribute__((always_inline)) {
+                constexpr int q = decltype(qc)::value;
+                constexpr int pmax = SB - 1 - q, pmin = E0 - q > 0 ? E0 - q : 0;
+                static_for<0, pmax - pmin + 1>([&](auto ic) __attribute__((always_inline)) {
+                    constexpr int p = pmax - decltype(ic)::value;
+                    acc[p + q - E0] = mfma(a[p], b[q], acc[p + q - E0]);
                 });
-                cur = nxt;
-                after_step(t + 1);
+                if constexpr (q == 0) {
+                    // the next step has landed everywhere (its fragments may be read from here on) and
+                    // every wavefront has read the last fragment of this one: its stage is free
+                    __builtin_amdgcn_sched_barrier(0);
+                    wait_loads<(AHEAD - 1) * NLOAD>();
+                    workgroup_barrier();
+                }
+                // one direct load per group (NLOAD <= SB): a wavefront stalls while its load is issued,
+                // and eight wavefronts that issue all their loads at once queue behind each other
+                if constexpr (q < NLOAD) issue_q(q, cur);
+                b[q] = read_b(q, nxt);
+                a[pmax] = read_a(pmax, nxt);
+                __builtin_amdgcn_sched_barrier(0);   // keep the re-reads where their registers fall free
+            });
+            cur = nxt;
+        };
+        if constexpr (!STREAM) {
+            for (int prod = p_begin; prod < p_end; ++prod) {   // every product fills the pipeline anew
+                cur = 0;
+                ld_t = 0;
+                voff = voff_first;
+                set_sources(prod);
+                static_for<0, NST>([&](auto sc) __attribute__((always_inline)) { issue(decltype(sc)::value * B::STAGE); });
+                wait_loads<AHEAD * NLOAD>();    // step 0 has landed
+                workgroup_barrier();
+                read_all();
+                for (int t = 0; t < steps; ++t) {
+                    step(issue_one);
+                    after_step(t + 1);
+                }
+                after_product(prod);
+                // direct loads of the repeated last step may still be in flight: they must land before the
+                // LDS is used for anything else or handed to another workgroup
+                wait_loads<0>();
+                workgroup_barrier();
             }
-            after_product(prod);
+        } else {
+            // The products form one continuous stream of steps (steps >= NST is the caller's business):
+            // the requests run NST steps ahead of the matrix cores straight across a product boundary,
+            // so only the first product pays for filling the pipeline. While the matrix cores work on
+            // the last NST steps of a product the requests are already in the next one; the step loop
+            // is split there, so that the change of source addresses (amounts worked out before the
+            // walk and kept in LDS) is outside both halves: a scalar load or a second path inside the
+            // loop would turn every wait for LDS reads in it into a wait for all of them.
+            unsigned inc = kFragBytes;
+            auto issue_ahead = [&](int jj, unsigned stage_off) __attribute__((always_inline)) {
+                dma_load16(src[jj], voff, dst[jj] + stage_off);
+                if (jj == NLOAD - 1) voff += inc;
+            };
+            for (int p = p_begin; p + 1 < p_end; ++p) {
+#pragma unroll
+                for (int k = 0; k < NLOAD; ++k)
+                    if (w.lane == 0) w.switch_table[(p - p_begin) * NLOAD + k] = fragment_ptr(p + 1, k) - fragment_ptr(p, k);
+            }
+            set_sources(p_begin);
+            static_for<0, NST>([&](auto sc) __attribute__((always_inline)) {
+#pragma unroll
+                for (int jj = 0; jj < NLOAD; ++jj) issue_ahead(jj, decltype(sc)::value * B::STAGE);
+            });
+            wait_loads<AHEAD * NLOAD>();    // step 0 has landed
+            workgroup_barrier();
+            read_all();
+            for (int prod = p_begin; prod < p_end; ++prod) {
+                for (int t = 0; t < steps - NST; ++t) {
+                    step(issue_ahead);
+                    after_step(t + 1);
+                }
+                if (prod + 1 < p_end) {
+#pragma unroll
+                    for (int k = 0; k < NLOAD; ++k) src[k] = uniform_ptr(src[k] + w.switch_table[(prod - p_begin) * NLOAD + k]);
+                    voff = voff_first;
+                } else {   // nothing follows: the last step again and again
+                    voff -= kFragBytes;
+                    inc = 0;
+                }
+                for (int t = steps - NST; t < steps; ++t) {
+                    step(issue_ahead);
+                    after_step(t + 1);
+                }
+                after_product(prod);
+                // The fragments of the next product's first step were not kept in registers across the
+                // epilogue (it needs them); they are read again from their stage, which the last barrier
+                // has already published. The epilogue's stores share the counter of the direct loads:
+                // loads complete in order among themselves, so a wait for "at most N operations in
+                // flight" still proves that every load older than the N youngest has landed; stores
+                // that are still in flight can only make it wait longer.
+                if (prod + 1 < p_end) read_all();
+            }
+            wait_loads<0>();
+            workgroup_barrier();
         }
-        // direct loads of the repeated last step may still be in flight: they must land before the
-        // LDS is used for anything else or handed to another workgroup
-        wait_loads<0>();
-        workgroup_barrier();
     } else {
         // Two stages: the fragments of a step are read at its start, in the order of their first
         // use and two groups ahead of it (B fragments pass through three rotating registers).
@@ -247,8 +306,6 @@ __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g,
         v4i a[SB], b[3];
         for (int prod = p_begin; prod < p_end; ++prod) {
             unsigned cur = 0, nxt = B::STAGE;
-            ld_p = prod;
-            ld_end = prod + 1;
             ld_t = 0;
             voff = voff_first;
             set_sources(prod);
@@ -323,21 +380,21 @@ __device__ __forceinline__ void fold_band_dd(double (&h)[16], double (&l)[16], c
     }
 }
 
-// Whether the combine mode of the call reads the old contents of C.
-__device__ __forceinline__ bool c_mode_reads(const GemmArgs& g) {
-    return g.c_mode == 1 || g.c_mode == 2 || g.c_mode == 4 || (g.c_mode == 3 && g.beta != 0.0);
+// Whether a combine mode reads the old contents of C.
+__device__ __forceinline__ bool c_mode_reads(const GemmArgs& g, int c_mode) {
+    return c_mode == 1 || c_mode == 2 || c_mode == 4 || (c_mode == 3 && g.beta != 0.0);
 }
 
-// One element of the result: C (op)= val, with the combine mode of the call. `old_c` is the element of
-// C (and `old_zr` that of Zr) fetched ahead of time for the modes that read them.
-__device__ __forceinline__ void write_c_element(const GemmArgs& g, int row, int col, double val, double old_c,
-                                                double old_zr) {
+// One element of the result: C (op)= val with combine mode c_mode. `old_c` is the element of C (and
+// `old_zr` that of Zr) fetched ahead of time for the modes that read them.
+__device__ __forceinline__ void write_c_element(const GemmArgs& g, int c_mode, double* C, int row, int col, double val,
+                                                double old_c, double old_zr) {
     if (row < g.m && col < g.n) {
-        double* c = g.C + (int64_t)row * g.ldc + col;
-        if (g.c_mode == 0) *c = val;
-        else if (g.c_mode == 1) *c = old_c + val;
-        else if (g.c_mode == 2) *c = old_c - val;
-        else if (g.c_mode == 3) {   // BLAS update: RN(alpha G), then RN(RN(alpha G) + RN(beta C)); C is not read if beta == 0
+        double* c = C + (int64_t)row * g.ldc + col;
+        if (c_mode == 0) *c = val;
+        else if (c_mode == 1) *c = old_c + val;
+        else if (c_mode == 2) *c = old_c - val;
+        else if (c_mode == 3) {   // BLAS update: RN(alpha G), then RN(RN(alpha G) + RN(beta C)); C is not read if beta == 0
             double v = g.alpha * val;
             if (g.beta != 0.0) v = v + g.beta * old_c;
             *c = v;
@@ -350,19 +407,20 @@ __device__ __forceinline__ void write_c_element(const GemmArgs& g, int row, int 
     }
 }
 
-constexpr int kModeReal = 0, kModeDD = 1;
+// kModeComplex: the four real products of a complex one, walked one after the other by every workgroup
+// (planes SA/SA2, SB/SB2; real part formed in the plane Zr, imaginary part in C, result interleaved in Cz).
+constexpr int kModeReal = 0, kModeDD = 1, kModeComplex = 2;
 
 template <int S, int WM, int WN, int MODE>
-#ifdef OZ_EXP_SMALL
-__global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(S <= 9 ? 2 : WM * WN / 4, S <= 9 ? 2 : WM * WN / 4)))
-#else
 __global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(WM * WN / 4, WM * WN / 4)))
-#endif
 void product_kernel(const GemmArgs g) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int T = 64 * WM * WN;
     constexpr int S2 = S > kBand ? S - kBand : 1;   // slice count of the second band (unused if S <= 8)
-    constexpr int NPROD = 1;                              // products walked one after the other by a workgroup
+    constexpr bool CPLX = MODE == kModeComplex;
+    constexpr bool PLAIN = MODE != kModeDD;               // FP64 summing-up (real or complex)
+    constexpr int NPROD = CPLX ? 4 : 1;                   // products walked one after the other by a workgroup
+    constexpr int NEX = CPLX ? 2 : 1;                     // exponent sets staged (one per plane)
     constexpr int TR = 32 * WM, TC = 32 * WN;             // tile of C
 
     Walk w;
@@ -380,17 +438,24 @@ void product_kernel(const GemmArgs g) {
 
     const int tile_id = w.tm * g.tiles_n + w.tn;
     const int64_t num_tiles = (int64_t)g.tiles_m * g.tiles_n;
-    const bool wide = g.block_steps > 0;
+    const bool wide = !CPLX && g.block_steps > 0;   // complex calls with k-blocking take four real launches
 
     // The exponents of the tile's rows and columns wait in LDS behind the pipeline stages (rows at
     // ex, columns at ex + TR): the epilogue must not stall on a round trip to memory. The first
     // barrier of the walk publishes them.
-    int* ex = reinterpret_cast<int*>(lds + Shape<S, WM, WN>::LDS);
+    int* ex = reinterpret_cast<int*>(lds + Shape<S, WM, WN>::LDS);   // complex: the imaginary planes' set follows at TR + TC
+    // behind them (complex only): per wavefront, the changes of its source addresses from product to product
+    constexpr int kSwitchEntries = 3 * 8;
+    constexpr int SWITCH_BYTES = CPLX ? WM * WN * kSwitchEntries * 8 : 0;
+    w.switch_table = (lds_i64*)(__attribute__((address_space(3))) unsigned char*)(lds + Shape<S, WM, WN>::LDS + NEX * (TR + TC) * 4) + w.wave * kSwitchEntries;
+    static_assert(!CPLX || Band<(S < kBand ? S : kBand), WM, WN>::NLOAD <= 8, "switch table row");
     if (!g.P) {
-        for (int i = w.tid; i < TR + TC; i += T) {
-            const bool is_a = i < TR;
-            const int pos = is_a ? w.tm * TR + i : w.tn * TC + (i - TR);
-            ex[i] = pos < (is_a ? g.m : g.n) ? (is_a ? g.EA : g.EB)[pos] : 0;
+        for (int i = w.tid; i < NEX * (TR + TC); i += T) {
+            const int plane = i / (TR + TC), ii = i % (TR + TC);
+            const bool is_a = ii < TR;
+            const int pos = is_a ? w.tm * TR + ii : w.tn * TC + (ii - TR);
+            const int32_t* E = is_a ? (plane ? g.EA2 : g.EA) : (plane ? g.EB2 : g.EB);
+            ex[i] = pos < (is_a ? g.m : g.n) ? E[pos] : 0;
         }
     }
 
@@ -444,15 +509,15 @@ void product_kernel(const GemmArgs g) {
     };
 
     auto sources = [&](int prod, const int8_t*& sa, const int8_t*& sb) __attribute__((always_inline)) {
-        sa = g.SA;
-        sb = g.SB;
+        sa = CPLX && (prod & 1) ? g.SA2 : g.SA;
+        sb = CPLX && (prod == 1 || prod == 2) ? g.SB2 : g.SB;
     };
     // The elements of C that the combine mode reads are requested before the diagonals are folded, so
     // that they arrive while the fold runs (sixteen dependent round trips to memory otherwise); those of
     // Zr (complex interleave only) in one batch after it, when the fold's registers are free again.
-    double old_c[MODE == kModeReal ? 16 : 1], old_zr[MODE == kModeReal ? 16 : 1];
-    auto fetch_old = [&](double (&dst)[MODE == kModeReal ? 16 : 1], const double* src, bool wanted) __attribute__((always_inline)) {
-        if constexpr (MODE == kModeReal) {
+    double old_c[PLAIN ? 16 : 1], old_zr[PLAIN ? 16 : 1];
+    auto fetch_old = [&](double (&dst)[PLAIN ? 16 : 1], const double* src, bool wanted) __attribute__((always_inline)) {
+        if constexpr (PLAIN) {
             if (!wanted) {
 #pragma unroll
                 for (int u = 0; u < 16; ++u) dst[u] = 0.0;
@@ -464,9 +529,23 @@ void product_kernel(const GemmArgs g) {
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
                 const int dr = 8 * (u >> 2) + (u & 3);
-                dst[u] = row0 + dr < g.m && col < g.n ? c[(int64_t)dr * g.ldc] : 0.0;
+                const bool in = row0 + dr < g.m && col < g.n;
+                // complex: the planes were written by this lane's own earlier stores (acknowledged by the
+                // L2 since: the walk in between drains the counter they share with the direct loads) and
+                // are read at the L2, not from a line the vector cache may still hold
+                if constexpr (CPLX) dst[u] = in ? __hip_atomic_load(c + (int64_t)dr * g.ldc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+                else dst[u] = in ? c[(int64_t)dr * g.ldc] : 0.0;
             }
         }
+    };
+    // Product prod of a complex call: 0: Ar Br -> Zr, 1: Zr -= Ai Bi, 2: Ar Bi -> C, 3: (Zr, C + Ai Br) -> Cz.
+    auto mode_of = [&](int prod) __attribute__((always_inline)) -> int {
+        if constexpr (CPLX) return prod == 0 ? 0 : prod == 1 ? 2 : prod == 2 ? 0 : 4;
+        else return g.c_mode;
+    };
+    auto plane_of = [&](int prod) __attribute__((always_inline)) -> double* {
+        if constexpr (CPLX) return prod < 2 ? g.Zr : g.C;
+        else return g.C;
     };
     // The sum of product `prod` is complete (in `sum`, or in the INT64 sums of the workspace): scale it,
     // combine it, store what is final.
@@ -498,11 +577,15 @@ void product_kernel(const GemmArgs g) {
                 }
             }
         }
-        fetch_old(old_zr, g.Zr, g.c_mode == 4);
-        const int eb = ex[TR + lcol];
+        const int c_mode = mode_of(prod);
+        double* const plane = plane_of(prod);
+        fetch_old(old_zr, g.Zr, c_mode == 4);
+        const int* exa = ex + (CPLX && (prod & 1) ? TR + TC : 0);
+        const int* exb = ex + (CPLX && (prod == 1 || prod == 2) ? TR + TC : 0) + TR;
+        const int eb = exb[lcol];
 #pragma unroll
         for (int u4 = 0; u4 < 4; ++u4) {
-            const v4i ea = *reinterpret_cast<const v4i*>(ex + lrow0 + 8 * u4);   // four consecutive rows
+            const v4i ea = *reinterpret_cast<const v4i*>(exa + lrow0 + 8 * u4);   // four consecutive rows
 #pragma unroll
             for (int uu = 0; uu < 4; ++uu) {
                 const int u = 4 * u4 + uu;
@@ -515,7 +598,7 @@ void product_kernel(const GemmArgs g) {
                         g.C_lo[(int64_t)row * g.ldc + col] = ldexp(lo[u], e);
                     }
                 } else {
-                    write_c_element(g, row, col, val, old_c[MODE == kModeReal ? u : 0], old_zr[MODE == kModeReal ? u : 0]);
+                    write_c_element(g, c_mode, plane, row, col, val, old_c[PLAIN ? u : 0], old_zr[PLAIN ? u : 0]);
                 }
             }
         }
@@ -527,7 +610,7 @@ void product_kernel(const GemmArgs g) {
         constexpr int SB = decltype(sb_tag)::value;
         using B = Band<SB, WM, WN>;
         zero_acc();
-        band_walk<SB, WM, WN>(acc, g, w, p_begin, p_end, sources,
+        band_walk<SB, WM, WN, (NPROD > 1 && S <= kBand)>(acc, g, w, p_begin, p_end, sources,
             [&](int done) __attribute__((always_inline)) {
                 if (wide && (--until_flush == 0 || done == g.t_end - g.t_begin)) {
                     flush(B::E0, B::ND, first_block);
@@ -538,7 +621,7 @@ void product_kernel(const GemmArgs g) {
             },
             [&](int prod) __attribute__((always_inline)) {
                 if (first_band) clear_sum();
-                if (last_band) fetch_old(old_c, g.C, !g.P && c_mode_reads(g));
+                if (last_band) fetch_old(old_c, plane_of(prod), !g.P && c_mode_reads(g, mode_of(prod)));
                 if (!wide && !g.P) {
                     if constexpr (MODE == kModeDD) fold_band_dd<SB>(sum, lo, acc);
                     else fold_band<SB>(sum, acc);
@@ -561,7 +644,7 @@ void product_kernel(const GemmArgs g) {
 
 template <int S, int WM, int WN, int MODE>
 hipError_t launch_one(const GemmArgs& g, hipStream_t st) {
-    constexpr int lds = Shape<S, WM, WN>::LDS + 32 * (WM + WN) * (int)sizeof(int);
+    constexpr int lds = Shape<S, WM, WN>::LDS + (MODE == kModeComplex ? 2 : 1) * 32 * (WM + WN) * (int)sizeof(int) + (MODE == kModeComplex ? WM * WN * 192 : 0);
     static_assert(lds <= kLdsLimit, "stages and exponents must fit the LDS");
     hipError_t e = allow_dynamic_lds<&product_kernel<S, WM, WN, MODE>>(lds);
     if (e != hipSuccess) return e;
@@ -572,11 +655,7 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t st) {
 template <int MODE>
 hipError_t launch_for(const GemmArgs& g, int s, hipStream_t st) {
     switch (s) {
-#ifdef OZ_EXP_SMALL
-#define OZ_CASE(S_, WN_) case S_: return launch_one<S_, 2, (S_ <= 9 ? 2 : WN_), MODE>(g, st);
-#else
 #define OZ_CASE(S_, WN_) case S_: return launch_one<S_, 2, WN_, MODE>(g, st);
-#endif
         OZ_CASE(1, 4) OZ_CASE(2, 4) OZ_CASE(3, 4) OZ_CASE(4, 4) OZ_CASE(5, 4) OZ_CASE(6, 4) OZ_CASE(7, 4) OZ_CASE(8, 4)
         OZ_CASE(9, 4) OZ_CASE(10, 4) OZ_CASE(11, 4) OZ_CASE(12, 4) OZ_CASE(13, 4) OZ_CASE(14, 2) OZ_CASE(15, 2) OZ_CASE(16, 2)
 #undef OZ_CASE

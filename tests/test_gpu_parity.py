@@ -363,6 +363,24 @@ def test_zgemm_bit_exact(m, n, k, s):
     assert np.array_equal(bits(got.imag.copy()), bits(want.imag.copy()))
 
 
+@pytest.mark.parametrize("s", range(1, 17))
+@pytest.mark.parametrize("k", [96, 200])
+def test_zgemm_one_launch_every_slice_count(s, k):
+    """The four real products walked by one workgroup per tile, for every kernel instantiation: one
+    continuous stream of steps up to eight slices (k = 96: exactly the three steps the walk runs ahead),
+    a pipeline per band beyond; two tile rows and columns with ragged edges."""
+    m, n = 70, 140
+    A = wl.gaussian_complex(m, k, seed=10 + s)
+    B = wl.unit_column_complex(k, n, seed=30 + s)
+    C = torch.full((m, n), complex(float("nan"), float("nan")), dtype=torch.complex128, device=DEV)
+    ozimmu.zgemm(dev(A), dev(B), C, s, ozimmu.alloc_workspace(m, n, k, s, is_complex=True))
+    torch.cuda.synchronize()
+    got = C.cpu().numpy()
+    want = oracle.zgemm(A, B, s)
+    assert np.array_equal(bits(got.real.copy()), bits(want.real.copy()))
+    assert np.array_equal(bits(got.imag.copy()), bits(want.imag.copy()))
+
+
 # ------------------------------------------------------------------ HIP graph capture
 def test_dgemm_captured_in_a_graph_replays_correctly():
     """The library only enqueues kernels on the caller's stream (no memsets, no allocation, no
