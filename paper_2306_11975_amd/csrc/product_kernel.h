@@ -116,7 +116,8 @@ __device__ __forceinline__ void workgroup_barrier() {
 // pairs of diagonal e, after_step(steps done in this product) is called after every step (k-blocking
 // hooks in there) and after_product(p) when a product's last step has been issued (it takes the sums
 // and clears acc). STREAM (register-resident schedule only, at least NST steps per product): the
-// products form one continuous stream of steps and only the first one pays for filling the pipeline.
+// products form one continuous stream of steps and only the first one pays for filling the pipeline;
+// after_product must then wait for every memory operation in flight before it issues its first store.
 template <int SB, int WM, int WN, bool STREAM, class Sources, class AfterStep, class AfterProduct>
 __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g, const Walk& w, int p_begin, int p_end,
                                           Sources&& sources, AfterStep&& after_step, AfterProduct&& after_product) {
@@ -199,7 +200,7 @@ __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g,
             });
         };
         // One step; issue_q(jj, stage) requests this wavefront's jj-th fragment of the step NST ahead.
-        auto step = [&](auto&& issue_q) __attribute__((always_inline)) {
+        auto step = [&](auto&& issue_q, auto await_next) __attribute__((always_inline)) {
             const unsigned nxt = cur + B::STAGE < (unsigned)B::LDS ? cur + B::STAGE : 0u;
             static_for<0, SB>([&](auto qc) __attribute__((always_inline)) {
                 constexpr int q = decltype(qc)::value;
@@ -212,7 +213,7 @@ __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g,
                     // the next step has landed everywhere (its fragments may be read from here on) and
                     // every wavefront has read the last fragment of this one: its stage is free
                     __builtin_amdgcn_sched_barrier(0);
-                    wait_loads<(AHEAD - 1) * NLOAD>();
+                    if constexpr (decltype(await_next)::value) wait_loads<(AHEAD - 1) * NLOAD>();
                     workgroup_barrier();
                 }
                 // one direct load per group (NLOAD <= SB): a wavefront stalls while its load is issued,
@@ -235,7 +236,7 @@ __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g,
                 workgroup_barrier();
                 read_all();
                 for (int t = 0; t < steps; ++t) {
-                    step(issue_one);
+                    step(issue_one, std::true_type{});
                     after_step(t + 1);
                 }
                 after_product(prod);
@@ -271,29 +272,39 @@ __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g,
             workgroup_barrier();
             read_all();
             for (int prod = p_begin; prod < p_end; ++prod) {
-                for (int t = 0; t < steps - NST; ++t) {
-                    step(issue_ahead);
+                // From the second product on, the first AHEAD steps find their successors landed:
+                // after_product waits for everything in flight before its first store, and those
+                // steps were requested before it was called. The counter is not consulted for them
+                // (the stores just issued are in it); from step AHEAD on, "at most N in flight" proves
+                // again that every load older than the N youngest has landed, loads completing in
+                // order among themselves, and stores still in flight can only make that wait longer.
+                // Nothing that shares the counter of the LDS reads may be in flight when the step loops
+                // are entered (a scalar load of a kernel argument that the epilogue wants, say): scalar
+                // loads complete out of order, and with one possibly in flight on entry every wait for a
+                // fragment inside the loops becomes a wait for all of them.
+                __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+                int t = 0;
+                for (; t < steps - NST; ++t) {
+                    step(issue_ahead, std::true_type{});
                     after_step(t + 1);
                 }
                 if (prod + 1 < p_end) {
 #pragma unroll
                     for (int k = 0; k < NLOAD; ++k) src[k] = uniform_ptr(src[k] + w.switch_table[(prod - p_begin) * NLOAD + k]);
-                    voff = voff_first;
+                    // (formed here from the lane number, not kept in a register across the walk)
+                    voff = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) * 16u + (unsigned)g.t_begin * kFragBytes;
                 } else {   // nothing follows: the last step again and again
                     voff -= kFragBytes;
                     inc = 0;
                 }
-                for (int t = steps - NST; t < steps; ++t) {
-                    step(issue_ahead);
+                for (t = steps - NST; t < steps; ++t) {
+                    step(issue_ahead, std::true_type{});
                     after_step(t + 1);
                 }
                 after_product(prod);
                 // The fragments of the next product's first step were not kept in registers across the
                 // epilogue (it needs them); they are read again from their stage, which the last barrier
-                // has already published. The epilogue's stores share the counter of the direct loads:
-                // loads complete in order among themselves, so a wait for "at most N operations in
-                // flight" still proves that every load older than the N youngest has landed; stores
-                // that are still in flight can only make it wait longer.
+                // has already published.
                 if (prod + 1 < p_end) read_all();
             }
             wait_loads<0>();
@@ -515,7 +526,7 @@ void product_kernel(const GemmArgs g) {
     // The elements of C that the combine mode reads are requested before the diagonals are folded, so
     // that they arrive while the fold runs (sixteen dependent round trips to memory otherwise); those of
     // Zr (complex interleave only) in one batch after it, when the fold's registers are free again.
-    double old_c[PLAIN ? 16 : 1], old_zr[PLAIN ? 16 : 1];
+    double old_c[PLAIN ? 16 : 1], old_zr[MODE == kModeReal ? 16 : 1];
     auto fetch_old = [&](double (&dst)[PLAIN ? 16 : 1], const double* src, bool wanted) __attribute__((always_inline)) {
         if constexpr (PLAIN) {
             if (!wanted) {
@@ -579,26 +590,66 @@ void product_kernel(const GemmArgs g) {
         }
         const int c_mode = mode_of(prod);
         double* const plane = plane_of(prod);
-        fetch_old(old_zr, g.Zr, c_mode == 4);
         const int* exa = ex + (CPLX && (prod & 1) ? TR + TC : 0);
         const int* exb = ex + (CPLX && (prod == 1 || prod == 2) ? TR + TC : 0) + TR;
         const int eb = exb[lcol];
+        if constexpr (CPLX) {
+            // Two passes, so that the finished real parts can take the registers of the old values:
+            // first this product's scaled sum combined with the part formed so far, in place ...
 #pragma unroll
-        for (int u4 = 0; u4 < 4; ++u4) {
-            const v4i ea = *reinterpret_cast<const v4i*>(exa + lrow0 + 8 * u4);   // four consecutive rows
+            for (int u4 = 0; u4 < 4; ++u4) {
+                const v4i ea = *reinterpret_cast<const v4i*>(exa + lrow0 + 8 * u4);   // four consecutive rows
 #pragma unroll
-            for (int uu = 0; uu < 4; ++uu) {
-                const int u = 4 * u4 + uu;
-                const int row = row0 + 8 * u4 + uu;
-                const int e = ea[uu] + eb;
-                const double val = ldexp(sum[u], e);
-                if constexpr (MODE == kModeDD) {
-                    if (row < g.m && col < g.n) {
-                        g.C[(int64_t)row * g.ldc + col] = val;
-                        g.C_lo[(int64_t)row * g.ldc + col] = ldexp(lo[u], e);
+                for (int uu = 0; uu < 4; ++uu) {
+                    const int u = 4 * u4 + uu;
+                    const double val = ldexp(sum[u], ea[uu] + eb);
+                    sum[u] = c_mode == 0 ? val : c_mode == 2 ? old_c[u] - val : old_c[u] + val;
+                }
+            }
+            // ... then, for the last product, the real parts, and the stores. Before the first store
+            // everything older has come back: the old values and the direct loads of the next product's
+            // first steps, requested before the fold. The walk relies on it (band_walk, STREAM): stores
+            // and loads share one counter and complete in no fixed order with each other. The loaded
+            // values are also named as used on every path, so that the compiler has no load of its own
+            // left to wait for later, in the walk, where its wait would take the stores and the direct
+            // loads with it.
+            fetch_old(old_c, g.Zr, c_mode == 4);
+            wait_loads<0>();
+#pragma unroll
+            for (int u = 0; u < 16; ++u) asm volatile("" : : "v"(old_c[u]));
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int row = row0 + 8 * (u >> 2) + (u & 3);
+                if (row < g.m && col < g.n) {
+                    if (c_mode == 4) {
+                        double2 z;
+                        z.x = old_c[u];
+                        z.y = sum[u];
+                        *reinterpret_cast<double2*>(g.Cz + 2 * ((int64_t)row * g.ldcz + col)) = z;
+                    } else {
+                        plane[(int64_t)row * g.ldc + col] = sum[u];
                     }
-                } else {
-                    write_c_element(g, c_mode, plane, row, col, val, old_c[PLAIN ? u : 0], old_zr[PLAIN ? u : 0]);
+                }
+            }
+        } else {
+            fetch_old(old_zr, g.Zr, c_mode == 4);
+#pragma unroll
+            for (int u4 = 0; u4 < 4; ++u4) {
+                const v4i ea = *reinterpret_cast<const v4i*>(exa + lrow0 + 8 * u4);   // four consecutive rows
+#pragma unroll
+                for (int uu = 0; uu < 4; ++uu) {
+                    const int u = 4 * u4 + uu;
+                    const int row = row0 + 8 * u4 + uu;
+                    const int e = ea[uu] + eb;
+                    const double val = ldexp(sum[u], e);
+                    if constexpr (MODE == kModeDD) {
+                        if (row < g.m && col < g.n) {
+                            g.C[(int64_t)row * g.ldc + col] = val;
+                            g.C_lo[(int64_t)row * g.ldc + col] = ldexp(lo[u], e);
+                        }
+                    } else {
+                        write_c_element(g, c_mode, plane, row, col, val, old_c[PLAIN ? u : 0], old_zr[PLAIN ? u : 0]);
+                    }
                 }
             }
         }
