@@ -84,6 +84,22 @@ ozimmu_status_t check_gemm_args(int64_t m, int64_t n, int64_t k, const void* A, 
     return OZIMMU_OK;
 }
 
+// Both planes of an interleaved complex operand whose rows run along k (rows x k complex elements, leading
+// dimension ld in complex elements) into the slice tensors and exponents at off_s[0..1], off_e[0..1]:
+// one pass over the data when the rows are short enough to wait in registers, else one strided pass per
+// plane. negate_im: the slices of the conjugated operand.
+hipError_t split_complex_rows(const double* Z, int64_t ld, int64_t rows, int64_t k, int s, unsigned char* ws,
+                              const size_t (&off_s)[2], const size_t (&off_e)[2], int64_t rows_pad, int64_t k_pad,
+                              hipStream_t st, bool negate_im) {
+    int8_t* S[2] = {reinterpret_cast<int8_t*>(ws + off_s[0]), reinterpret_cast<int8_t*>(ws + off_s[1])};
+    int32_t* E[2] = {reinterpret_cast<int32_t*>(ws + off_e[0]), reinterpret_cast<int32_t*>(ws + off_e[1])};
+    if (complex_rows_in_one_pass(Z, k_pad))
+        return launch_split_rows_complex(Z, ld, rows, k, s, S[0], S[1], rows_pad, k_pad, E[0], E[1], st, negate_im);
+    hipError_t e = launch_split_rows(Z, ld, 2, rows, k, s, S[0], rows_pad, k_pad, E[0], st, false);
+    if (e == hipSuccess) e = launch_split_rows(Z + 1, ld, 2, rows, k, s, S[1], rows_pad, k_pad, E[1], st, negate_im);
+    return e;
+}
+
 // One real Ozaki product from already split planes: G = sum over diagonals, combined into C as
 // c_mode says (C_lo != nullptr: double-double sum into C, C_lo).
 hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned char* ws, int plane_a, int plane_b,
@@ -197,13 +213,20 @@ ozimmu_status_t auto_select(const ScanOperand& a, const ScanOperand& b, int64_t 
     const int parts = is_complex ? 2 : 1, inc = is_complex ? 2 : 1;
     hipError_t e = launch_fill_u64(sums, 4 * OZIMMU_MAX_SLICES, 0ull, st);
     const ScanOperand* ops[2] = {&a, &b};
-    for (int o = 0; o < 2; ++o)
+    for (int o = 0; o < 2; ++o) {
+        const ScanOperand& z = *ops[o];
+        if (is_complex && !z.by_cols && complex_scan_in_one_pass(z.ptr, z.cols)) {   // both planes of short rows at once
+            unsigned long long* dst = sums + o * parts * OZIMMU_MAX_SLICES;
+            if (e == hipSuccess) e = launch_loss_scan_rows_complex(z.ptr, z.ld, z.rows, z.cols, dst, dst + OZIMMU_MAX_SLICES, st);
+            continue;
+        }
         for (int pl = 0; pl < parts && e == hipSuccess; ++pl) {
             const ScanOperand& x = *ops[o];
             unsigned long long* dst = sums + (o * parts + pl) * OZIMMU_MAX_SLICES;
             if (x.by_cols) e = launch_loss_scan_cols(x.ptr + pl, x.ld, inc, x.rows, x.cols, colmax, dst, st);
             else e = launch_loss_scan_rows(x.ptr + pl, x.ld, inc, x.rows, x.cols, dst, st);
         }
+    }
     unsigned long long host[4 * OZIMMU_MAX_SLICES];
     if (e == hipSuccess) e = hipMemcpyAsync(host, sums, sizeof(host), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
@@ -376,9 +399,7 @@ ozimmu_status_t ozimmu_zgemm(int64_t m, int64_t n, int64_t k, const double* A, i
     const int s = num_slices;
     hipError_t e = hipSuccess;
     // the real and imaginary planes are separated while splitting (element stride 2)
-    for (int pl = 0; pl < 2 && e == hipSuccess; ++pl)
-        e = launch_split_rows(A + pl, lda, 2, m, k, s, reinterpret_cast<int8_t*>(ws + L.off_sa[pl]), L.m_pad,
-                              L.k_pad, reinterpret_cast<int32_t*>(ws + L.off_ea[pl]), st);
+    e = split_complex_rows(A, lda, m, k, s, ws, L.off_sa, L.off_ea, L.m_pad, L.k_pad, st, false);
     for (int pl = 0; pl < 2 && e == hipSuccess; ++pl)
         e = launch_split_cols(B + pl, ldb, 2, k, n, s, reinterpret_cast<int8_t*>(ws + L.off_sb[pl]), L.n_pad,
                               L.k_pad, reinterpret_cast<int32_t*>(ws + L.off_eb[pl]),
@@ -502,19 +523,15 @@ ozimmu_status_t ozimmu_zgemm_blas(char transa, char transb, int64_t m, int64_t n
     unsigned long long* colmax = reinterpret_cast<unsigned long long*>(ws + L.off_colmax);
     hipError_t e = hipSuccess;
     // planes: real, then imaginary (negated while splitting if the operand is conjugated)
-    for (int pl = 0; pl < 2 && e == hipSuccess; ++pl) {
-        int8_t* SR = reinterpret_cast<int8_t*>(ws + L.off_sa[pl]);      // op(B)^T: n rows of length k
-        int32_t* ER = reinterpret_cast<int32_t*>(ws + L.off_ea[pl]);
-        const bool neg = pl == 1 && tb == 2;
-        if (!tb) e = launch_split_rows(B + pl, ldb, 2, n, k, num_slices, SR, L.m_pad, L.k_pad, ER, st, neg);
-        else e = launch_split_cols(B + pl, ldb, 2, k, n, num_slices, SR, L.m_pad, L.k_pad, ER, colmax, st, neg);
-    }
-    for (int pl = 0; pl < 2 && e == hipSuccess; ++pl) {
-        int8_t* SC = reinterpret_cast<int8_t*>(ws + L.off_sb[pl]);      // op(A): m rows of length k
-        int32_t* EC = reinterpret_cast<int32_t*>(ws + L.off_eb[pl]);
-        const bool neg = pl == 1 && ta == 2;
-        if (!ta) e = launch_split_cols(A + pl, lda, 2, k, m, num_slices, SC, L.n_pad, L.k_pad, EC, colmax, st, neg);
-        else e = launch_split_rows(A + pl, lda, 2, m, k, num_slices, SC, L.n_pad, L.k_pad, EC, st, neg);
+    if (!tb) e = split_complex_rows(B, ldb, n, k, num_slices, ws, L.off_sa, L.off_ea, L.m_pad, L.k_pad, st, false);   // op(B)^T: n rows of length k
+    else for (int pl = 0; pl < 2 && e == hipSuccess; ++pl)
+        e = launch_split_cols(B + pl, ldb, 2, k, n, num_slices, reinterpret_cast<int8_t*>(ws + L.off_sa[pl]), L.m_pad, L.k_pad,
+                              reinterpret_cast<int32_t*>(ws + L.off_ea[pl]), colmax, st, pl == 1 && tb == 2);
+    if (e == hipSuccess) {
+        if (ta) e = split_complex_rows(A, lda, m, k, num_slices, ws, L.off_sb, L.off_eb, L.n_pad, L.k_pad, st, ta == 2);   // op(A): m rows of length k
+        else for (int pl = 0; pl < 2 && e == hipSuccess; ++pl)
+            e = launch_split_cols(A + pl, lda, 2, k, m, num_slices, reinterpret_cast<int8_t*>(ws + L.off_sb[pl]), L.n_pad, L.k_pad,
+                                  reinterpret_cast<int32_t*>(ws + L.off_eb[pl]), colmax, st, false);
     }
     const bool alpha_one = ar == 1.0 && ai == 0.0;
     // The product goes straight into C when C's old values are not needed, else beside the slices.

@@ -64,6 +64,16 @@ hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, i
 hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n, int s,
                              int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
                              unsigned long long* colmax, hipStream_t st, bool negate = false);
+// Rows of an interleaved complex operand (Z: m x k complex elements, leading dimension ldz in complex
+// elements), both planes in one pass; only where complex_rows_in_one_pass / complex_scan_in_one_pass say so
+// (short enough rows, 16-byte aligned), otherwise one strided pass per plane with the functions above / below.
+bool complex_rows_in_one_pass(const double* Z, int64_t k_pad);
+hipError_t launch_split_rows_complex(const double* Z, int64_t ldz, int64_t m, int64_t k, int s, int8_t* S_re,
+                                     int8_t* S_im, int64_t m_pad, int64_t k_pad, int32_t* E_re, int32_t* E_im,
+                                     hipStream_t st, bool negate_im = false);
+bool complex_scan_in_one_pass(const double* Z, int64_t k);
+hipError_t launch_loss_scan_rows_complex(const double* Z, int64_t ldz, int64_t m, int64_t k,
+                                         unsigned long long* sums_re, unsigned long long* sums_im, hipStream_t st);
 // Slice products of the pairs p + q <= s + 1 with the FP64 sum. mode 0: FP64 sum; 1: double-double sum
 // into C, C_lo; 2: the four real products of a complex one in one launch (no k-blocking: block_steps == 0),
 // real part formed in the plane Zr, imaginary part in the plane C, result interleaved in Cz.

@@ -208,6 +208,76 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_kernel(const dou
     }
 }
 
+// Rows of an interleaved complex operand, both planes in one pass: the same mapping as above, a thread's
+// word being four consecutive complex elements (four 16-byte loads), whose real parts go to one set of
+// slices and exponents and whose imaginary parts to the other. Read once (a pass per plane with element
+// stride 2 fetches every line twice). Rows of up to 4096 elements (they stay in registers); longer
+// ones take the two strided passes.
+constexpr int kZRowCacheWords = 4;
+template <bool WIDE>
+__global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_complex_kernel(
+    const double* __restrict__ Z, int64_t ldz, int m, int64_t k, int s, int8_t* __restrict__ S_re,
+    int8_t* __restrict__ S_im, int64_t m_pad, int64_t k_pad, int32_t* __restrict__ E_re, int32_t* __restrict__ E_im,
+    unsigned long long flip_re, unsigned long long flip_im) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const int r4 = lane >> 4, c16 = lane & 15;
+    const int row = blockIdx.x * kRowGroup + r4;
+    const bool live = row < m;
+    const int64_t slice_stride = m_pad * k_pad;
+    const ulonglong2* src = reinterpret_cast<const ulonglong2*>(Z) + (int64_t)(live ? row : 0) * ldz;
+    const int64_t k_live = live ? k : 0;
+
+    unsigned long long re[kZRowCacheWords][4], im[kZRowCacheWords][4];
+    unsigned long long mx_re = 0, mx_im = 0;
+#pragma unroll
+    for (int j = 0; j < kZRowCacheWords; ++j) {
+        const int64_t l0 = ((int64_t)(wave + nwaves * j) * 16 + c16) * 4;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            ulonglong2 v = {0ull, 0ull};
+            if (l0 + u < k_live) v = src[l0 + u];
+            re[j][u] = v.x;
+            im[j][u] = v.y;
+            const unsigned long long a = v.x & kAbsMask, b = v.y & kAbsMask;
+            mx_re = a > mx_re ? a : mx_re;
+            mx_im = b > mx_im ? b : mx_im;
+        }
+    }
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) {
+        const unsigned long long o = __shfl_xor(mx_re, off, 64), q = __shfl_xor(mx_im, off, 64);
+        mx_re = o > mx_re ? o : mx_re;
+        mx_im = q > mx_im ? q : mx_im;
+    }
+    __shared__ unsigned long long wmax[kRowWavesMax][kRowGroup][2];
+    if (c16 == 0) {
+        wmax[wave][r4][0] = mx_re;
+        wmax[wave][r4][1] = mx_im;
+    }
+    __syncthreads();
+    mx_re = wmax[0][r4][0];
+    mx_im = wmax[0][r4][1];
+    for (int w = 1; w < nwaves; ++w) {
+        mx_re = wmax[w][r4][0] > mx_re ? wmax[w][r4][0] : mx_re;
+        mx_im = wmax[w][r4][1] > mx_im ? wmax[w][r4][1] : mx_im;
+    }
+    const int e_re = exponent_of_max(mx_re), e_im = exponent_of_max(mx_im);
+    if (live && wave == 0 && c16 == 0) {
+        E_re[row] = e_re;
+        E_im[row] = e_im;
+    }
+#pragma unroll
+    for (int j = 0; j < kZRowCacheWords; ++j) {
+        const int64_t l0 = ((int64_t)(wave + nwaves * j) * 16 + c16) * 4;
+        if (l0 < k_pad) {
+            const int64_t off = word_offset(row, l0, k_pad);
+            emit_word<WIDE>(re[j], e_re, s, S_re + off, slice_stride, flip_re);
+            emit_word<WIDE>(im[j], e_im, s, S_im + off, slice_stride, flip_im);
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------ columns of B
 __global__ __launch_bounds__(256) void fill_u64_kernel(unsigned long long* p, int64_t n,
                                                        unsigned long long v) {
@@ -467,6 +537,71 @@ __global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_kernel(const dou
     loss_flush(acc, lds16, sums);
 }
 
+// Rows of an interleaved complex operand, both planes in one pass (four short rows per wavefront, rows of up
+// to 1024 elements in registers; anything else takes the two strided passes).
+__global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_complex_kernel(const double* __restrict__ Z, int64_t ldz,
+                                                                               int64_t m, int64_t k,
+                                                                               unsigned long long* __restrict__ sums_re,
+                                                                               unsigned long long* __restrict__ sums_im) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const int r4 = lane >> 4, c16 = lane & 15;
+    __shared__ unsigned long long wmax[kLossWavesMax][kRowGroup][2];
+    __shared__ unsigned long long lds16[OZIMMU_MAX_SLICES];
+    LossAcc acc_re, acc_im;
+    loss_clear(acc_re);
+    loss_clear(acc_im);
+    for (int64_t group = blockIdx.x; group * kRowGroup < m; group += gridDim.x) {
+        const int64_t row = group * kRowGroup + r4;
+        const bool live = row < m;
+        const ulonglong2* src = reinterpret_cast<const ulonglong2*>(Z) + (live ? row : 0) * ldz;
+        const int64_t k_live = live ? k : 0;
+        unsigned long long re[kZRowCacheWords][4], im[kZRowCacheWords][4];
+        unsigned long long mx_re = 0, mx_im = 0;
+#pragma unroll
+        for (int j = 0; j < kZRowCacheWords; ++j) {
+            const int64_t l0 = ((int64_t)(wave + nwaves * j) * 16 + c16) * 4;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                ulonglong2 v = {0ull, 0ull};
+                if (l0 + u < k_live) v = src[l0 + u];
+                re[j][u] = v.x;
+                im[j][u] = v.y;
+                const unsigned long long a = v.x & kAbsMask, b = v.y & kAbsMask;
+                mx_re = a > mx_re ? a : mx_re;
+                mx_im = b > mx_im ? b : mx_im;
+            }
+        }
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) {
+            const unsigned long long o = __shfl_xor(mx_re, off, 64), q = __shfl_xor(mx_im, off, 64);
+            mx_re = o > mx_re ? o : mx_re;
+            mx_im = q > mx_im ? q : mx_im;
+        }
+        __syncthreads();   // the maxima of the previous group have been read by everybody
+        if (c16 == 0) {
+            wmax[wave][r4][0] = mx_re;
+            wmax[wave][r4][1] = mx_im;
+        }
+        __syncthreads();
+        mx_re = wmax[0][r4][0];
+        mx_im = wmax[0][r4][1];
+        for (int w = 1; w < nwaves; ++w) {
+            mx_re = wmax[w][r4][0] > mx_re ? wmax[w][r4][0] : mx_re;
+            mx_im = wmax[w][r4][1] > mx_im ? wmax[w][r4][1] : mx_im;
+        }
+        const int e_re = exponent_of_max(mx_re), e_im = exponent_of_max(mx_im);
+#pragma unroll
+        for (int j = 0; j < kZRowCacheWords; ++j) {   // words beyond the row hold zeros
+            loss_add4(acc_re, re[j], e_re);
+            loss_add4(acc_im, im[j], e_im);
+        }
+    }
+    loss_flush(acc_re, lds16, sums_re);
+    __syncthreads();   // lds16 is reused
+    loss_flush(acc_im, lds16, sums_im);
+}
+
 // Columns of B: as the column-maximum pass, a lane owns a column and a workgroup a band of rows.
 __global__ __launch_bounds__(256) void loss_cols_kernel(const double* __restrict__ B, int64_t ldb, int inc,
                                                         int64_t k, int64_t n, int band,
@@ -571,6 +706,40 @@ hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, i
         else        { if (vec) OZ_ROWS(false, false, true); else OZ_ROWS(false, false, false); }
     }
 #undef OZ_ROWS
+    return hipGetLastError();
+}
+
+bool complex_rows_in_one_pass(const double* Z, int64_t k_pad) {
+    return k_pad <= (int64_t)64 * kZRowCacheWords * kRowWavesMax && reinterpret_cast<uintptr_t>(Z) % 16 == 0;
+}
+
+hipError_t launch_split_rows_complex(const double* Z, int64_t ldz, int64_t m, int64_t k, int s, int8_t* S_re,
+                                     int8_t* S_im, int64_t m_pad, int64_t k_pad, int32_t* E_re, int32_t* E_im,
+                                     hipStream_t st, bool negate_im) {
+    if (m_pad == 0 || k_pad == 0) return hipSuccess;
+    if (!complex_rows_in_one_pass(Z, k_pad)) return hipErrorInvalidValue;
+    const int64_t want = (k_pad + 64 * kZRowCacheWords - 1) / (64 * kZRowCacheWords);
+    const int nwaves = (int)(want < 1 ? 1 : want);
+    const unsigned long long flip_im = negate_im ? 1ull << 63 : 0ull;
+    const dim3 grid((unsigned)(m_pad / kRowGroup)), block(64 * nwaves);
+    if (s > 9) split_rows_complex_kernel<true><<<grid, block, 0, st>>>(Z, ldz, (int)m, k, s, S_re, S_im, m_pad, k_pad, E_re, E_im, 0ull, flip_im);
+    else split_rows_complex_kernel<false><<<grid, block, 0, st>>>(Z, ldz, (int)m, k, s, S_re, S_im, m_pad, k_pad, E_re, E_im, 0ull, flip_im);
+    return hipGetLastError();
+}
+
+bool complex_scan_in_one_pass(const double* Z, int64_t k) {
+    return k <= (int64_t)64 * kZRowCacheWords * kLossWavesMax && reinterpret_cast<uintptr_t>(Z) % 16 == 0;
+}
+
+hipError_t launch_loss_scan_rows_complex(const double* Z, int64_t ldz, int64_t m, int64_t k,
+                                         unsigned long long* sums_re, unsigned long long* sums_im, hipStream_t st) {
+    if (m == 0 || k == 0) return hipSuccess;
+    if (!complex_scan_in_one_pass(Z, k)) return hipErrorInvalidValue;
+    const int64_t want = (k + 64 * kZRowCacheWords - 1) / (64 * kZRowCacheWords);
+    const int nwaves = (int)(want < 1 ? 1 : want);
+    const int64_t groups = (m + kRowGroup - 1) / kRowGroup;
+    const int64_t cap = (int64_t)256 * 16 / nwaves;
+    loss_rows_complex_kernel<<<dim3((unsigned)(groups < cap ? groups : cap)), dim3(64 * nwaves), 0, st>>>(Z, ldz, m, k, sums_re, sums_im);
     return hipGetLastError();
 }
 

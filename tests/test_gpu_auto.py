@@ -82,6 +82,13 @@ def test_auto_complex_planes():
     check(A, B, thresholds=(0.0, 1.0))
 
 
+def test_auto_complex_rows_beyond_the_one_pass_scan():
+    """Interleaved rows of more than 1024 elements are scanned one plane at a time (element stride 2);
+    20000 short rows make the one-pass kernel's workgroups walk several row groups."""
+    check(wl.gaussian_complex(40, 1500, seed=5), wl.unit_column_complex(1500, 33, seed=6), thresholds=(0.0, 1.0))
+    check(wl.gaussian_complex(20000, 70, seed=7), wl.unit_column_complex(70, 9, seed=8), thresholds=(0.0, 1.0))
+
+
 def test_auto_full_size_matches_oracle():
     """m = n = k = 4096, phi = 1: the launch configuration of the large workloads (rows kept in
     registers, 256-row bands for the columns)."""
