@@ -44,6 +44,14 @@ __device__ __forceinline__ unsigned opaque_zero() {
     return z;
 }
 
+// The lane number, formed where it is asked for (not once ahead of the k-walk, where the value would have to
+// be kept, or spilled, across it).
+__device__ __forceinline__ int lane_here() {
+    int l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=&v"(l));
+    return l;
+}
+
 // The accumulators live in the accumulation half of the register file for the whole k-walk.
 // Initialising and reading them through these two helpers pins that choice, so that no copies
 // between the two halves of the file are made around the loop.

@@ -292,7 +292,7 @@ __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g,
 #pragma unroll
                     for (int k = 0; k < NLOAD; ++k) src[k] = uniform_ptr(src[k] + w.switch_table[(prod - p_begin) * NLOAD + k]);
                     // (formed here from the lane number, not kept in a register across the walk)
-                    voff = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) * 16u + (unsigned)g.t_begin * kFragBytes;
+                    voff = (unsigned)lane_here() * 16u + (unsigned)g.t_begin * kFragBytes;
                 } else {   // nothing follows: the last step again and again
                     voff -= kFragBytes;
                     inc = 0;
@@ -366,6 +366,7 @@ __device__ __forceinline__ void fold_band(double (&sum)[16], const v16i (&acc)[k
         const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * (e + 2)) << 52);
 #pragma unroll
         for (int u = 0; u < 16; ++u) sum[u] = fma((double)acc_read(acc[e - E0][u]), sc, sum[u]);
+        __builtin_amdgcn_sched_barrier(0);   // one diagonal's temporaries at a time
     }
 }
 
@@ -482,7 +483,7 @@ void product_kernel(const GemmArgs g) {
     // nobody else ever touches it.
     auto flush = [&](int e0, int nd, bool first) __attribute__((always_inline)) {
         // one running pointer (made opaque so that it is formed here, not ahead of the k-walk)
-        long long* q = g.D + (((int64_t)e0 * num_tiles + tile_id) * 16) * T + w.tid + opaque_zero();
+        long long* q = g.D + (((int64_t)e0 * num_tiles + tile_id) * 16) * T + (w.wave * 64 + lane_here());
         const int64_t diag_stride = num_tiles * 16 * T - 16 * T;
 #pragma unroll
         for (int i = 0; i < kBand; ++i) {
@@ -506,8 +507,19 @@ void product_kernel(const GemmArgs g) {
 
     // accumulator layout of the 32x32 MFMA: lane holds column (lane % 32); register u holds
     // row 8 (u / 4) + 4 (lane / 32) + u % 4.
-    const int lrow0_ = w.wm * 32 + 4 * half, lcol_ = w.wn * 32 + rr;   // inside the tile
-    const int row0_ = w.tm * TR + lrow0_, col_ = w.tn * TC + lcol_;
+    // The coordinates are formed where the epilogue needs them, from the lane number read there: kept
+    // across the walk they would be spilled, and a reload of a spilled register waits for every memory
+    // operation in flight, the direct loads of the next steps included.
+    struct Where { int lrow0, lcol, row0, col; };
+    auto where = [&]() __attribute__((always_inline)) -> Where {
+        const int lane = lane_here();
+        Where p;
+        p.lrow0 = w.wm * 32 + 4 * (lane >> 5);
+        p.lcol = w.wn * 32 + (lane & 31);
+        p.row0 = w.tm * TR + p.lrow0;
+        p.col = w.tn * TC + p.lcol;
+        return p;
+    };
 
     double sum[16], lo[MODE == kModeDD ? 16 : 1];
     auto clear_sum = [&]() __attribute__((always_inline)) {
@@ -534,8 +546,8 @@ void product_kernel(const GemmArgs g) {
                 for (int u = 0; u < 16; ++u) dst[u] = 0.0;
                 return;
             }
-            const int oz = (int)opaque_zero();
-            const int row0 = row0_ + oz, col = col_ + oz;
+            const Where at = where();
+            const int row0 = at.row0, col = at.col;
             const double* c = src + (int64_t)row0 * g.ldc + col;
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
@@ -563,8 +575,9 @@ void product_kernel(const GemmArgs g) {
     auto finish_product = [&](int prod) __attribute__((always_inline)) {
         // Everything this step addresses is formed here, from values made opaque, and not ahead of the
         // walk, where it would occupy registers the matrix-core loop needs.
+        const Where at = where();
         const int oz = (int)opaque_zero();
-        const int row0 = row0_ + oz, col = col_ + oz, lrow0 = lrow0_ + oz, lcol = lcol_ + oz;
+        const int row0 = at.row0, col = at.col, lrow0 = at.lrow0, lcol = at.lcol;
         if (g.P) {   // pair mode (S == 1): the raw INT32 sums
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
@@ -574,7 +587,7 @@ void product_kernel(const GemmArgs g) {
             return;
         }
         if (wide) {   // the FP64 sum from the INT64 sums, same order
-            const long long* q = g.D + ((int64_t)tile_id * 16) * T + w.tid + oz;
+            const long long* q = g.D + ((int64_t)tile_id * 16) * T + (w.wave * 64 + lane_here()) + oz;
             for (int e = S - 1; e >= 0; --e) {
                 const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * (e + 2)) << 52);
 #pragma unroll
@@ -671,12 +684,20 @@ void product_kernel(const GemmArgs g) {
                 }
             },
             [&](int prod) __attribute__((always_inline)) {
+                // nothing of the epilogue is to be scheduled up into the last step, where the fragment
+                // registers are still in use and there is no room for its values
+                __builtin_amdgcn_sched_barrier(0);
                 if (first_band) clear_sum();
-                if (last_band) fetch_old(old_c, plane_of(prod), !g.P && c_mode_reads(g, mode_of(prod)));
+                // The old values are requested before the fold where accumulation registers are to spare
+                // for them; with all eight diagonals resident there are none, and an accumulator would be
+                // spilled to make room (its reload then waits for every memory operation in flight).
+                constexpr bool EARLY = !CPLX || B::ND < kBand;
+                if (last_band && EARLY) fetch_old(old_c, plane_of(prod), !g.P && c_mode_reads(g, mode_of(prod)));
                 if (!wide && !g.P) {
                     if constexpr (MODE == kModeDD) fold_band_dd<SB>(sum, lo, acc);
                     else fold_band<SB>(sum, acc);
                 }
+                if (last_band && !EARLY) fetch_old(old_c, plane_of(prod), !g.P && c_mode_reads(g, mode_of(prod)));
                 if (last_band) finish_product(prod);
                 zero_acc();
                 first_block = true;
