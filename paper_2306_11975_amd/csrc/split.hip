@@ -463,27 +463,28 @@ __device__ __forceinline__ void loss_flush(const LossAcc& a, unsigned long long*
     if (threadIdx.x < OZIMMU_MAX_SLICES && lds16[threadIdx.x]) atomicAdd(&sums[threadIdx.x], lds16[threadIdx.x]);
 }
 
-// Rows of A: ROWS rows at a time per workgroup, 64 / ROWS lanes of every wavefront on each (four
-// rows for short ones as in the row splitter, one for long ones), rows of up to 8192 elements cached
-// in registers between the maximum and the scan. A workgroup walks many such groups and flushes its
-// counters once at the end: the sums are 16 atomics on 16 addresses per flush, and one flush per
-// row would serialise on them.
+// Rows of A: a group of ROWS rows at a time, 64 / ROWS lanes of a wavefront on each (four rows for short
+// ones as in the row splitter, one for long ones), `wpg` wavefronts per group (1, 2 or 4: rows of up to
+// 8192 elements wait in registers between the maximum and the scan). A workgroup is four wavefronts,
+// that is 4 / wpg groups side by side; it walks many of them and flushes its counters once at the end:
+// the sums are 16 atomics on 16 addresses per flush, and thousands of flushes serialise on them.
 constexpr int kLossWavesMax = 4;
 template <int ROWS, bool CACHED, bool VEC>
 __global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_kernel(const double* __restrict__ A, int64_t lda, int inc,
-                                                                       int64_t m, int64_t k,
+                                                                       int64_t m, int64_t k, int wpg,
                                                                        unsigned long long* __restrict__ sums) {
     constexpr int LPR = 64 / ROWS;   // lanes per row
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int sub = wave / wpg, wi = wave % wpg, side = kLossWavesMax / wpg;   // group inside the workgroup, wavefront inside the group
     const int rsub = lane / LPR, c = lane % LPR;
     const int64_t chunks = (k + 4 * LPR - 1) / (4 * LPR);
     __shared__ unsigned long long wmax[kLossWavesMax][ROWS];
     __shared__ unsigned long long lds16[OZIMMU_MAX_SLICES];
     LossAcc acc;
     loss_clear(acc);
-    for (int64_t group = blockIdx.x; group * ROWS < m; group += gridDim.x) {
-        const int64_t row = group * ROWS + rsub;
+    for (int64_t first = (int64_t)blockIdx.x * side; first * ROWS < m; first += (int64_t)gridDim.x * side) {
+        const int64_t row = (first + sub) * ROWS + rsub;
         const bool live = row < m;
         const unsigned long long* src = reinterpret_cast<const unsigned long long*>(A) + (live ? row : 0) * lda;
         const int64_t k_live = live ? k : 0;
@@ -492,7 +493,7 @@ __global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_kernel(const dou
         if (CACHED) {
 #pragma unroll
             for (int j = 0; j < kRowCacheWords; ++j) {
-                const int64_t l0 = ((int64_t)(wave + nwaves * j) * LPR + c) * 4;
+                const int64_t l0 = ((int64_t)(wi + wpg * j) * LPR + c) * 4;
                 if (l0 < k_live) load_word<VEC>(src, l0, k_live, inc, cache[j]);
                 else cache[j][0] = cache[j][1] = cache[j][2] = cache[j][3] = 0ull;
 #pragma unroll
@@ -502,7 +503,7 @@ __global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_kernel(const dou
                 }
             }
         } else {
-            for (int64_t ch = wave; ch < chunks; ch += nwaves) {
+            for (int64_t ch = wi; ch < chunks; ch += wpg) {
                 unsigned long long b[4];
                 load_word<VEC>(src, (ch * LPR + c) * 4, k_live, inc, b);
 #pragma unroll
@@ -517,17 +518,18 @@ __global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_kernel(const dou
             const unsigned long long o = __shfl_xor(mx, off, 64);
             mx = o > mx ? o : mx;
         }
-        __syncthreads();   // the maxima of the previous group have been read by everybody
+        __syncthreads();   // the maxima of the previous groups have been read by everybody
         if (c == 0) wmax[wave][rsub] = mx;
         __syncthreads();
-        mx = wmax[0][rsub];
-        for (int w = 1; w < nwaves; ++w) mx = wmax[w][rsub] > mx ? wmax[w][rsub] : mx;
+        mx = wmax[sub * wpg][rsub];
+        for (int w = 1; w < wpg; ++w) mx = wmax[sub * wpg + w][rsub] > mx ? wmax[sub * wpg + w][rsub] : mx;
         const int E = exponent_of_max(mx);
         if (CACHED) {
 #pragma unroll
-            for (int j = 0; j < kRowCacheWords; ++j) loss_add4(acc, cache[j], E);   // words beyond the row hold zeros
+            for (int j = 0; j < kRowCacheWords; ++j)   // short rows: whole words beyond the row are skipped (same for all lanes)
+                if (ROWS == 1 || (int64_t)(wi + wpg * j) * LPR * 4 < k) loss_add4(acc, cache[j], E);
         } else {
-            for (int64_t ch = wave; ch < chunks; ch += nwaves) {
+            for (int64_t ch = wi; ch < chunks; ch += wpg) {
                 unsigned long long b[4];
                 load_word<VEC>(src, (ch * LPR + c) * 4, k_live, inc, b);
                 loss_add4(acc, b, E);
@@ -538,21 +540,22 @@ __global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_kernel(const dou
 }
 
 // Rows of an interleaved complex operand, both planes in one pass (four short rows per wavefront, rows of up
-// to 1024 elements in registers; anything else takes the two strided passes).
+// to 1024 elements in registers; anything else takes the two strided passes). Workgroup shape as above.
 __global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_complex_kernel(const double* __restrict__ Z, int64_t ldz,
-                                                                               int64_t m, int64_t k,
+                                                                               int64_t m, int64_t k, int wpg,
                                                                                unsigned long long* __restrict__ sums_re,
                                                                                unsigned long long* __restrict__ sums_im) {
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int sub = wave / wpg, wi = wave % wpg, side = kLossWavesMax / wpg;
     const int r4 = lane >> 4, c16 = lane & 15;
     __shared__ unsigned long long wmax[kLossWavesMax][kRowGroup][2];
     __shared__ unsigned long long lds16[OZIMMU_MAX_SLICES];
     LossAcc acc_re, acc_im;
     loss_clear(acc_re);
     loss_clear(acc_im);
-    for (int64_t group = blockIdx.x; group * kRowGroup < m; group += gridDim.x) {
-        const int64_t row = group * kRowGroup + r4;
+    for (int64_t first = (int64_t)blockIdx.x * side; first * kRowGroup < m; first += (int64_t)gridDim.x * side) {
+        const int64_t row = (first + sub) * kRowGroup + r4;
         const bool live = row < m;
         const ulonglong2* src = reinterpret_cast<const ulonglong2*>(Z) + (live ? row : 0) * ldz;
         const int64_t k_live = live ? k : 0;
@@ -560,7 +563,7 @@ __global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_complex_kernel(c
         unsigned long long mx_re = 0, mx_im = 0;
 #pragma unroll
         for (int j = 0; j < kZRowCacheWords; ++j) {
-            const int64_t l0 = ((int64_t)(wave + nwaves * j) * 16 + c16) * 4;
+            const int64_t l0 = ((int64_t)(wi + wpg * j) * 16 + c16) * 4;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 ulonglong2 v = {0ull, 0ull};
@@ -578,23 +581,25 @@ __global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_complex_kernel(c
             mx_re = o > mx_re ? o : mx_re;
             mx_im = q > mx_im ? q : mx_im;
         }
-        __syncthreads();   // the maxima of the previous group have been read by everybody
+        __syncthreads();   // the maxima of the previous groups have been read by everybody
         if (c16 == 0) {
             wmax[wave][r4][0] = mx_re;
             wmax[wave][r4][1] = mx_im;
         }
         __syncthreads();
-        mx_re = wmax[0][r4][0];
-        mx_im = wmax[0][r4][1];
-        for (int w = 1; w < nwaves; ++w) {
-            mx_re = wmax[w][r4][0] > mx_re ? wmax[w][r4][0] : mx_re;
-            mx_im = wmax[w][r4][1] > mx_im ? wmax[w][r4][1] : mx_im;
+        mx_re = wmax[sub * wpg][r4][0];
+        mx_im = wmax[sub * wpg][r4][1];
+        for (int w = 1; w < wpg; ++w) {
+            mx_re = wmax[sub * wpg + w][r4][0] > mx_re ? wmax[sub * wpg + w][r4][0] : mx_re;
+            mx_im = wmax[sub * wpg + w][r4][1] > mx_im ? wmax[sub * wpg + w][r4][1] : mx_im;
         }
         const int e_re = exponent_of_max(mx_re), e_im = exponent_of_max(mx_im);
 #pragma unroll
-        for (int j = 0; j < kZRowCacheWords; ++j) {   // words beyond the row hold zeros
-            loss_add4(acc_re, re[j], e_re);
-            loss_add4(acc_im, im[j], e_im);
+        for (int j = 0; j < kZRowCacheWords; ++j) {   // whole words beyond the row are skipped (same for all lanes)
+            if ((int64_t)(wi + wpg * j) * 64 < k) {
+                loss_add4(acc_re, re[j], e_re);
+                loss_add4(acc_im, im[j], e_im);
+            }
         }
     }
     loss_flush(acc_re, lds16, sums_re);
@@ -731,15 +736,25 @@ bool complex_scan_in_one_pass(const double* Z, int64_t k) {
     return k <= (int64_t)64 * kZRowCacheWords * kLossWavesMax && reinterpret_cast<uintptr_t>(Z) % 16 == 0;
 }
 
+// Wavefronts per row group for rows of k elements when one wavefront covers per_wave of them: 1, 2 or 4.
+static int loss_waves_per_group(int64_t k, int64_t per_wave) {
+    const int64_t want = (k + per_wave - 1) / per_wave;
+    return want <= 1 ? 1 : want <= 2 ? 2 : kLossWavesMax;
+}
+// Workgroups of four wavefronts for `groups` row groups, 4 / wpg of them side by side: as many as fill the chip
+// a few times over, few enough that their final flushes do not queue up.
+static unsigned loss_grid(int64_t groups, int wpg, int64_t cap) {
+    const int64_t side = kLossWavesMax / wpg, wgs = (groups + side - 1) / side;
+    return (unsigned)(wgs < cap ? wgs : cap);
+}
+
 hipError_t launch_loss_scan_rows_complex(const double* Z, int64_t ldz, int64_t m, int64_t k,
                                          unsigned long long* sums_re, unsigned long long* sums_im, hipStream_t st) {
     if (m == 0 || k == 0) return hipSuccess;
     if (!complex_scan_in_one_pass(Z, k)) return hipErrorInvalidValue;
-    const int64_t want = (k + 64 * kZRowCacheWords - 1) / (64 * kZRowCacheWords);
-    const int nwaves = (int)(want < 1 ? 1 : want);
+    const int wpg = loss_waves_per_group(k, 64 * kZRowCacheWords);
     const int64_t groups = (m + kRowGroup - 1) / kRowGroup;
-    const int64_t cap = (int64_t)256 * 16 / nwaves;
-    loss_rows_complex_kernel<<<dim3((unsigned)(groups < cap ? groups : cap)), dim3(64 * nwaves), 0, st>>>(Z, ldz, m, k, sums_re, sums_im);
+    loss_rows_complex_kernel<<<dim3(loss_grid(groups, wpg, 512)), dim3(64 * kLossWavesMax), 0, st>>>(Z, ldz, m, k, wpg, sums_re, sums_im);
     return hipGetLastError();
 }
 
@@ -777,20 +792,16 @@ static hipError_t launch_loss_rows(const double* A, int64_t lda, int inc, int64_
                                    unsigned long long* sums, hipStream_t st) {
     // a wavefront covers 4 * (64 / ROWS) elements of each of its rows per word it caches
     const int64_t per_wave = (int64_t)4 * (64 / ROWS) * kRowCacheWords;
-    const int64_t want = (k + per_wave - 1) / per_wave;
-    const int nwaves = (int)(want < 1 ? 1 : want > kLossWavesMax ? kLossWavesMax : want);
-    const bool cached = k <= per_wave * nwaves;
+    const int wpg = loss_waves_per_group(k, per_wave);
+    const bool cached = k <= per_wave * wpg;
     const bool vec = inc == 1 && lda % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
-    // 16 wavefronts per compute unit: enough to keep the memory system busy, and few final flushes
-    const int64_t groups = (m + ROWS - 1) / ROWS;
-    const int64_t cap = (int64_t)256 * 16 / nwaves;
-    const dim3 grid((unsigned)(groups < cap ? groups : cap)), block(64 * nwaves);
+    const dim3 grid(loss_grid((m + ROWS - 1) / ROWS, wpg, 1024)), block(64 * kLossWavesMax);
     if (cached) {
-        if (vec) loss_rows_kernel<ROWS, true, true><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
-        else loss_rows_kernel<ROWS, true, false><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
+        if (vec) loss_rows_kernel<ROWS, true, true><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, wpg, sums);
+        else loss_rows_kernel<ROWS, true, false><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, wpg, sums);
     } else {
-        if (vec) loss_rows_kernel<ROWS, false, true><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
-        else loss_rows_kernel<ROWS, false, false><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, sums);
+        if (vec) loss_rows_kernel<ROWS, false, true><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, wpg, sums);
+        else loss_rows_kernel<ROWS, false, false><<<grid, block, 0, st>>>(A, lda * inc, inc, m, k, wpg, sums);
     }
     return hipGetLastError();
 }
