@@ -44,6 +44,13 @@ __device__ __forceinline__ unsigned opaque_zero() {
     return z;
 }
 
+// The same in a scalar register, for wave-uniform values that are to be formed after the k-walk.
+__device__ __forceinline__ int opaque_scalar_zero() {
+    int z;
+    asm volatile("s_mov_b32 %0, 0" : "=s"(z));
+    return z;
+}
+
 // The lane number, formed where it is asked for (not once ahead of the k-walk, where the value would have to
 // be kept, or spilled, across it).
 __device__ __forceinline__ int lane_here() {

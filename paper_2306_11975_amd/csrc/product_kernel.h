@@ -539,6 +539,11 @@ void product_kernel(const GemmArgs g) {
     // that they arrive while the fold runs (sixteen dependent round trips to memory otherwise); those of
     // Zr (complex interleave only) in one batch after it, when the fold's registers are free again.
     double old_c[PLAIN ? 16 : 1], old_zr[MODE == kModeReal ? 16 : 1];
+    // whether the whole tile lies inside C (then the epilogue tests nothing per element); formed where it is used
+    auto tile_inside = [&]() __attribute__((always_inline)) -> bool {
+        const int z = opaque_scalar_zero();
+        return (w.tm + 1 + z) * TR <= g.m && (w.tn + 1 + z) * TC <= g.n;
+    };
     auto fetch_old = [&](double (&dst)[PLAIN ? 16 : 1], const double* src, bool wanted) __attribute__((always_inline)) {
         if constexpr (PLAIN) {
             if (!wanted) {
@@ -549,6 +554,12 @@ void product_kernel(const GemmArgs g) {
             const Where at = where();
             const int row0 = at.row0, col = at.col;
             const double* c = src + (int64_t)row0 * g.ldc + col;
+            if (CPLX && tile_inside()) {   // no test per element
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    dst[u] = __hip_atomic_load(c + (int64_t)(8 * (u >> 2) + (u & 3)) * g.ldc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                return;
+            }
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
                 const int dr = 8 * (u >> 2) + (u & 3);
@@ -630,6 +641,23 @@ void product_kernel(const GemmArgs g) {
             wait_loads<0>();
 #pragma unroll
             for (int u = 0; u < 16; ++u) asm volatile("" : : "v"(old_c[u]));
+            if (tile_inside()) {   // no test per element
+                if (c_mode == 4) {
+                    double* z = g.Cz + 2 * ((int64_t)row0 * g.ldcz + col);
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        double2 v;
+                        v.x = old_c[u];
+                        v.y = sum[u];
+                        *reinterpret_cast<double2*>(z + 2 * (int64_t)(8 * (u >> 2) + (u & 3)) * g.ldcz) = v;
+                    }
+                } else {
+                    double* c = plane + (int64_t)row0 * g.ldc + col;
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) c[(int64_t)(8 * (u >> 2) + (u & 3)) * g.ldc] = sum[u];
+                }
+                return;
+            }
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
                 const int row = row0 + 8 * (u >> 2) + (u & 3);
