@@ -89,6 +89,12 @@ def test_auto_complex_rows_beyond_the_one_pass_scan():
     check(wl.gaussian_complex(20000, 70, seed=7), wl.unit_column_complex(70, 9, seed=8), thresholds=(0.0, 1.0))
 
 
+@pytest.mark.parametrize("k", [400, 900, 1024])
+def test_auto_complex_rows_shared_by_two_and_four_wavefronts(k):
+    """One-pass scan of interleaved rows with two (256 < k <= 512) and four (k <= 1024) wavefronts per row group."""
+    check(wl.gaussian_complex(37, k, seed=k), wl.unit_column_complex(k, 21, seed=k + 1), thresholds=(0.0, 1.0))
+
+
 def test_auto_full_size_matches_oracle():
     """m = n = k = 4096, phi = 1: the launch configuration of the large workloads (rows kept in
     registers, 256-row bands for the columns)."""

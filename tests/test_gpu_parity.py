@@ -364,10 +364,11 @@ def test_zgemm_bit_exact(m, n, k, s):
 
 
 @pytest.mark.parametrize("s", range(1, 17))
-@pytest.mark.parametrize("k", [96, 200])
+@pytest.mark.parametrize("k", [96, 128, 200])
 def test_zgemm_one_launch_every_slice_count(s, k):
     """The four real products walked by one workgroup per tile, for every kernel instantiation: one
-    continuous stream of steps up to eight slices (k = 96: exactly the three steps the walk runs ahead),
+    continuous stream of steps up to eight slices (k = 96: exactly the three steps the walk runs ahead, k = 128:
+    one more),
     a pipeline per band beyond; two tile rows and columns with ragged edges."""
     m, n = 70, 140
     A = wl.gaussian_complex(m, k, seed=10 + s)
