@@ -18,6 +18,12 @@
 // splitting long k): every block_steps steps the INT32 sums are added into INT64 sums in the
 // workspace (k-blocking) and the FP64 sum is formed from those.
 //
+// Complex product (kModeComplex, Section 4.4): the workgroup of a tile walks the four real products
+// Ar Br, Ai Bi, Ar Bi, Ai Br one after the other; up to eight slices they form one stream of steps whose
+// loads run ahead across the product boundaries. After each product its diagonals are folded and the
+// result is combined with the part formed so far, which waits in a plane of the workspace (real part:
+// Zr, imaginary part: C) and is read back at the L2; the fourth epilogue writes (re, im) pairs.
+//
 // Data path of a step: global -> LDS with wave-wide direct loads (global_load_lds_dwordx4, no
 // staging registers; a fragment is 1 KiB contiguous in memory and in LDS), two or three LDS stages
 // (as many as fit 160 KiB);
@@ -116,8 +122,11 @@ __device__ __forceinline__ void workgroup_barrier() {
 // pairs of diagonal e, after_step(steps done in this product) is called after every step (k-blocking
 // hooks in there) and after_product(p) when a product's last step has been issued (it takes the sums
 // and clears acc). STREAM (register-resident schedule only, at least NST steps per product): the
-// products form one continuous stream of steps and only the first one pays for filling the pipeline;
-// after_product must then wait for every memory operation in flight before it issues its first store.
+// products form one continuous stream of steps and only the first one pays for filling the pipeline.
+// Stores that after_product issues may still be in flight when the walk resumes: they share the counter
+// of the direct loads, but loads complete in order among themselves, so "at most N operations in flight"
+// still proves that every load older than the N youngest has landed; a store in flight can only make
+// such a wait longer.
 template <int SB, int WM, int WN, bool STREAM, class Sources, class AfterStep, class AfterProduct>
 __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g, const Walk& w, int p_begin, int p_end,
                                           Sources&& sources, AfterStep&& after_step, AfterProduct&& after_product) {
@@ -630,11 +639,10 @@ void product_kernel(const GemmArgs g) {
                     sum[u] = c_mode == 0 ? val : c_mode == 2 ? old_c[u] - val : old_c[u] + val;
                 }
             }
-            // ... then, for the last product, the real parts, and the stores. Before the first store
-            // everything older has come back: the old values and the direct loads of the next product's
-            // first steps, requested before the fold. The walk relies on it (band_walk, STREAM): stores
-            // and loads share one counter and complete in no fixed order with each other. The loaded
-            // values are also named as used on every path, so that the compiler has no load of its own
+            // ... then, for the last product, the real parts, and the stores. Everything older is
+            // awaited before the first store (the old values are needed now anyway; the direct loads of
+            // the next product's first steps were requested before the fold and have landed), and the
+            // loaded values are named as used on every path: the compiler then has no load of its own
             // left to wait for later, in the walk, where its wait would take the stores and the direct
             // loads with it.
             fetch_old(old_c, g.Zr, c_mode == 4);
