@@ -175,7 +175,8 @@ ozimmu_status_t ozimmu_dgemm_stage(int stage, int64_t m, int64_t n, int64_t k, c
 
 /*
  * How ozimmu_dgemm runs a shape, on the host only (nothing is launched; for tests and for callers
- * who want to know): the tile of C one workgroup owns, the number of workgroups, the number of bands
+ * who want to know): the tile of C one workgroup owns (64 x 128; 64 x 64 from fourteen slices on, and up to
+ * nine slices when k <= 512 or fewer than 256 of the larger tiles exist), the number of workgroups, the number of bands
  * the anti-diagonals are walked in (a wavefront holds the INT32 sums of at most eight diagonals at a
  * time: 2 bands beyond eight slices), and int32_block_steps = the number of steps of
  * OZIMMU_K_ALIGN positions after which the INT32 sums are moved into INT64 sums (k-blocking),

@@ -36,18 +36,24 @@ struct Layout {
     size_t total;
 };
 
+// Tile shape and count (the byte offsets of a layout do not depend on them: D exists only with k-blocking,
+// which never takes the small tiles).
+void set_tiles(Layout& L, int64_t m, int64_t n, int s, bool small) {
+    int wm, wn;
+    tile_waves(s, small, &wm, &wn);
+    L.tile_rows = wm * kFragRows;
+    L.tile_cols = wn * kFragRows;
+    L.tiles_m = (int)((m + L.tile_rows - 1) / L.tile_rows);
+    L.tiles_n = (int)((n + L.tile_cols - 1) / L.tile_cols);
+}
+
 Layout make_layout(int64_t m, int64_t n, int64_t k, int s, bool cplx) {
     Layout L{};
     L.m_pad = round_up(m, kRowAlign);
     L.n_pad = round_up(n, kRowAlign);
     L.k_pad = round_up(k, kSlab);
-    int wm, wn;
-    tile_waves(s, &wm, &wn);
-    L.tile_rows = wm * kFragRows;
-    L.tile_cols = wn * kFragRows;
-    L.tiles_m = (int)((m + L.tile_rows - 1) / L.tile_rows);
-    L.tiles_n = (int)((n + L.tile_cols - 1) / L.tile_cols);
     L.wide = needs_wide(s, L.k_pad);
+    set_tiles(L, m, n, s, !cplx && use_small_tiles(m, n, L.k_pad, s, L.wide));
     L.sa_bytes = (size_t)s * L.m_pad * L.k_pad;
     L.sb_bytes = (size_t)s * L.n_pad * L.k_pad;
     const int planes = cplx ? 2 : 1;
@@ -115,6 +121,7 @@ hipError_t run_product(const Layout& L, int64_t m, int64_t n, int s, unsigned ch
     g.t_end = g.kslabs;
     g.tiles_m = L.tiles_m;
     g.tiles_n = L.tiles_n;
+    g.tile_cols = L.tile_cols;
     g.m = (int)m;
     g.n = (int)n;
     g.block_steps = L.wide ? block_steps_for(s) : 0;
@@ -161,6 +168,7 @@ hipError_t run_complex_products(const Layout& L, int64_t m, int64_t n, int s, un
         g.t_end = g.kslabs;
         g.tiles_m = L.tiles_m;
         g.tiles_n = L.tiles_n;
+        g.tile_cols = L.tile_cols;
         g.m = (int)m;
         g.n = (int)n;
         g.Zr = Pr;
@@ -329,6 +337,7 @@ ozimmu_status_t ozimmu_slice_gemm(int64_t m, int64_t n, int64_t k, const int8_t*
     g.t_end = (int)(round_up(k0 + klen, kSlab) / kSlab);
     g.tiles_m = L.tiles_m;
     g.tiles_n = L.tiles_n;
+    g.tile_cols = L.tile_cols;
     g.m = (int)m;
     g.n = (int)n;
     g.P = P;
@@ -561,6 +570,7 @@ ozimmu_status_t ozimmu_dgemm_dd(int64_t m, int64_t n, int64_t k, const double* A
         if (rc != OZIMMU_OK) return rc;
     }
     unsigned char* ws = static_cast<unsigned char*>(workspace);
+    set_tiles(L, m, n, num_slices, false);   // the double-double kernels exist for the large tiles only
     return hip_status(run_product(L, m, n, num_slices, ws, 0, 0, C_hi, ldc, 0, st, 1.0, 0.0, C_lo));
 }
 

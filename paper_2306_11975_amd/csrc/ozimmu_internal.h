@@ -16,11 +16,21 @@ constexpr int kBand = 8;                      // anti-diagonals whose INT32 sums
 
 static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
-// Wavefront grid of the product kernel for a slice count: 2 x 4 wavefronts of 32 x 32 outputs (a
-// 64 x 128 tile of C) while two pipeline stages of all slices fit the LDS, 2 x 2 beyond.
-static inline void tile_waves(int s, int* wm, int* wn) {
+// Wavefront grid of the product kernel: 2 x 4 wavefronts of 32 x 32 outputs (a 64 x 128 tile of C) while two
+// pipeline stages of all slices fit the LDS, 2 x 2 (64 x 64) beyond. `small`: 2 x 2 also for up to nine slices,
+// two such workgroups per compute unit (see use_small_tiles).
+static inline void tile_waves(int s, bool small, int* wm, int* wn) {
     *wm = 2;
-    *wn = s <= 13 ? 4 : 2;
+    *wn = (s > 13 || (small && s <= 9)) ? 2 : 4;
+}
+// Whether a real product of this shape runs on 64 x 64 tiles, two workgroups per compute unit: when the inner
+// dimension is short (a tile is then mostly start-up, fold and stores, and two independent workgroups overlap
+// one's with the other's matrix-core work) or when the 64 x 128 tiling leaves compute units without a tile.
+// Never with k-blocking, so that the workspace layout does not depend on it.
+static inline bool use_small_tiles(int64_t m, int64_t n, int64_t k_pad, int s, bool wide) {
+    if (s > 9 || wide) return false;
+    const int64_t big_tiles = ((m + 63) / 64) * ((n + 127) / 128);
+    return k_pad <= 512 || big_tiles < 256;
 }
 
 // Arguments of the slice-product kernel. One launch covers every tile of C.
@@ -32,6 +42,7 @@ struct GemmArgs {
     int kslabs;              // padded row length in slabs of 32
     int t_begin, t_end;      // slab range of the walk along k
     int tiles_m, tiles_n;
+    int tile_cols;           // 128, or 64 (2 x 2 wavefronts)
     int m, n;                // true extent of C
     int block_steps;         // steps after which the INT32 sums are moved into the INT64 sums in D (0: never)
     long long* D;            // INT64 diagonal sums (k-blocking only)

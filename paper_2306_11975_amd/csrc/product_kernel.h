@@ -60,7 +60,9 @@ struct Band {
     // for the next step; beyond 11 slices they no longer fit beside the accumulators and the B
     // fragments are streamed through three registers instead.
     static constexpr bool RESIDENT = SB <= 11;
-    static constexpr int FIT = kLdsLimit / STAGE;
+    // 2 x 2 wavefronts with up to nine slices: two workgroups share a compute unit (and its LDS)
+    static constexpr bool PAIRED = NW == 4 && SB <= 9;
+    static constexpr int FIT = (PAIRED ? kLdsLimit / 2 - 1024 : kLdsLimit) / STAGE;
     static constexpr int NST = !RESIDENT ? 2 : FIT > kMaxStages ? kMaxStages : FIT;
     static constexpr int LDS = NST * STAGE;
     static constexpr int NLOAD = (NFRAG + NW - 1) / NW;   // direct loads per wavefront and step
@@ -433,7 +435,8 @@ __device__ __forceinline__ void write_c_element(const GemmArgs& g, int c_mode, d
 constexpr int kModeReal = 0, kModeDD = 1, kModeComplex = 2;
 
 template <int S, int WM, int WN, int MODE>
-__global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(WM * WN / 4, WM * WN / 4)))
+__global__ __launch_bounds__(64 * WM * WN)
+__attribute__((amdgpu_waves_per_eu((WM * WN == 4 && S <= 9) ? 2 : WM * WN / 4, (WM * WN == 4 && S <= 9) ? 2 : WM * WN / 4)))
 void product_kernel(const GemmArgs g) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int T = 64 * WM * WN;
@@ -762,6 +765,16 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t st) {
 
 template <int MODE>
 hipError_t launch_for(const GemmArgs& g, int s, hipStream_t st) {
+    if (g.tile_cols == 64 && s <= 9) {   // 64 x 64 tiles, two workgroups per compute unit: real products only
+        if constexpr (MODE == kModeReal) {
+            switch (s) {
+#define OZ_CASE(S_) case S_: return launch_one<S_, 2, 2, MODE>(g, st);
+                OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
+#undef OZ_CASE
+            }
+        }
+        return hipErrorInvalidValue;
+    }
     switch (s) {
 #define OZ_CASE(S_, WN_) case S_: return launch_one<S_, 2, WN_, MODE>(g, st);
         OZ_CASE(1, 4) OZ_CASE(2, 4) OZ_CASE(3, 4) OZ_CASE(4, 4) OZ_CASE(5, 4) OZ_CASE(6, 4) OZ_CASE(7, 4) OZ_CASE(8, 4)

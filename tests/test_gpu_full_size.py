@@ -121,3 +121,29 @@ def test_tile_counts_that_do_not_fill_the_chip_sampled_rows_bit_exact(size, s):
     idx = torch.from_numpy(rows).cuda()
     want = oracle.dgemm(A[idx].cpu().numpy(), B.cpu().numpy(), s)
     assert np.array_equal(bits(C[idx].cpu().numpy()), bits(want))
+
+
+@pytest.mark.parametrize("s", range(1, 10))
+def test_large_tile_kernels_up_to_nine_slices_sampled_rows_bit_exact(s):
+    """Small shapes take 64 x 64 tiles up to nine slices; this one has 256 tiles of 64 x 128 and k > 512, so it
+    runs the 64 x 128 kernels that the small parity cases no longer reach."""
+    m, n, k = 1024, 2048, 544
+    assert ozimmu.launch_plan(m, n, k, s)["tile_cols"] == 128
+    A = wl.phi_matrix_device(m, k, 1.0, 1007)
+    B = wl.phi_matrix_device(k, n, 1.0, 2007)
+    C = torch.full((m, n), float("nan"), dtype=torch.float64, device="cuda")
+    ozimmu.dgemm(A, B, C, s, ozimmu.alloc_workspace(m, n, k, s))
+    torch.cuda.synchronize()
+    assert not torch.isnan(C).any()
+    rows = sample_rows(m, 5, seed=s, every_tile=True)
+    idx = torch.from_numpy(rows).cuda()
+    want = oracle.dgemm(A[idx].cpu().numpy(), B.cpu().numpy(), s)
+    assert np.array_equal(bits(C[idx].cpu().numpy()), bits(want))
+
+
+def test_small_tiles_are_chosen_for_short_k_and_for_grids_that_underfill_the_chip():
+    assert ozimmu.launch_plan(4096, 4096, 256, 7)["tile_cols"] == 64      # short inner dimension
+    assert ozimmu.launch_plan(1024, 1024, 1024, 8)["tile_cols"] == 64     # 128 tiles of 64 x 128 for 256 compute units
+    assert ozimmu.launch_plan(4096, 4096, 4096, 8)["tile_cols"] == 128
+    assert ozimmu.launch_plan(1024, 1024, 1024, 10)["tile_cols"] == 128   # no small kernels beyond nine slices
+    assert ozimmu.launch_plan(64, 64, 200000, 2)["tile_cols"] == 128      # k-blocking keeps the large tiles
