@@ -53,7 +53,10 @@ Layout make_layout(int64_t m, int64_t n, int64_t k, int s, bool cplx) {
     L.n_pad = round_up(n, kRowAlign);
     L.k_pad = round_up(k, kSlab);
     L.wide = needs_wide(s, L.k_pad);
-    set_tiles(L, m, n, s, !cplx && use_small_tiles(m, n, L.k_pad, s, L.wide));
+    // a complex product walks its four real products in one launch of the large-tile kernel from three steps
+    // on; shorter ones take four launches of the real kernel and its tile choice
+    const bool one_launch = cplx && !L.wide && L.k_pad / kSlab >= 3;
+    set_tiles(L, m, n, s, !one_launch && use_small_tiles(m, n, L.k_pad, s, L.wide));
     L.sa_bytes = (size_t)s * L.m_pad * L.k_pad;
     L.sb_bytes = (size_t)s * L.n_pad * L.k_pad;
     const int planes = cplx ? 2 : 1;
@@ -150,7 +153,8 @@ hipError_t run_complex_products(const Layout& L, int64_t m, int64_t n, int s, un
     double* Pr = reinterpret_cast<double*>(ws + L.off_z);
     double* Pi = Pr + (size_t)m * n;
     // one launch: every workgroup walks the four products of its tile one after the other (the walk runs
-    // three steps ahead of the matrix cores: shorter products and k-blocked ones take four launches)
+    // three steps ahead of the matrix cores: shorter products and k-blocked ones take four launches;
+    // make_layout has chosen the tiles accordingly)
     if (!L.wide && L.k_pad / kSlab >= 3) {
         GemmArgs g{};
         g.SA = reinterpret_cast<const int8_t*>(ws + L.off_sa[0]);
