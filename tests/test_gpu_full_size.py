@@ -147,3 +147,21 @@ def test_small_tiles_are_chosen_for_short_k_and_for_grids_that_underfill_the_chi
     assert ozimmu.launch_plan(4096, 4096, 4096, 8)["tile_cols"] == 128
     assert ozimmu.launch_plan(1024, 1024, 1024, 10)["tile_cols"] == 128   # no small kernels beyond nine slices
     assert ozimmu.launch_plan(64, 64, 200000, 2)["tile_cols"] == 128      # k-blocking keeps the large tiles
+
+
+@pytest.mark.parametrize("m,n,k,s,cols", [(1024, 2048, 512, 8, 64), (960, 2048, 600, 5, 64), (1024, 2048, 600, 9, 128),
+                                          (1000, 1000, 1000, 9, 64), (1000, 1000, 1000, 10, 128)])
+def test_both_sides_of_the_tile_choice_sampled_rows_bit_exact(m, n, k, s, cols):
+    """Shapes just on either side of the rule that picks 64 x 64 tiles (k <= 512, or fewer than 256 tiles of
+    64 x 128, up to nine slices), with ragged edges."""
+    assert ozimmu.launch_plan(m, n, k, s)["tile_cols"] == cols
+    A = wl.phi_matrix_device(m, k, 1.0, 1008)
+    B = wl.phi_matrix_device(k, n, 1.0, 2008)
+    C = torch.full((m, n), float("nan"), dtype=torch.float64, device="cuda")
+    ozimmu.dgemm(A, B, C, s, ozimmu.alloc_workspace(m, n, k, s))
+    torch.cuda.synchronize()
+    assert not torch.isnan(C).any()
+    rows = sample_rows(m, 5, seed=s + k, every_tile=True)
+    idx = torch.from_numpy(rows).cuda()
+    want = oracle.dgemm(A[idx].cpu().numpy(), B.cpu().numpy(), s)
+    assert np.array_equal(bits(C[idx].cpu().numpy()), bits(want))
