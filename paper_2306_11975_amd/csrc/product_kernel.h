@@ -283,12 +283,6 @@ __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g,
             workgroup_barrier();
             read_all();
             for (int prod = p_begin; prod < p_end; ++prod) {
-                // From the second product on, the first AHEAD steps find their successors landed:
-                // after_product waits for everything in flight before its first store, and those
-                // steps were requested before it was called. The counter is not consulted for them
-                // (the stores just issued are in it); from step AHEAD on, "at most N in flight" proves
-                // again that every load older than the N youngest has landed, loads completing in
-                // order among themselves, and stores still in flight can only make that wait longer.
                 // Nothing that shares the counter of the LDS reads may be in flight when the step loops
                 // are entered (a scalar load of a kernel argument that the epilogue wants, say): scalar
                 // loads complete out of order, and with one possibly in flight on entry every wait for a
