@@ -1,6 +1,8 @@
 // Device helpers shared by the slice-product kernels (gfx950 only).
 #pragma once
 
+#include <type_traits>
+
 #include "ozimmu_internal.h"
 
 namespace ozimmu {
@@ -73,6 +75,16 @@ __device__ __forceinline__ int acc_read(int a) {
     return v;
 }
 
+// To be called between the last MFMA and the first acc_read of its results. The reads sit in inline assembly,
+// where the compiler does not see them: it neither inserts the wait states that a read of a matrix-core result
+// needs (up to 19 after the issue of an MFMA of sixteen passes) nor keeps other instructions from moving in
+// between. Everything issued so far stays ahead of this point and 32 wait states pass before anything after it.
+__device__ __forceinline__ void mfma_results_ready() {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 // One wavefront-wide direct load: lane i fetches 16 bytes from gbase + voff_i and the hardware
 // writes them to LDS at lds_addr + 16 i (M0 carries the LDS base). Issued as inline assembly so
 // that its completion is awaited only by the explicit vmcnt before the step barrier and not
@@ -100,6 +112,35 @@ __device__ __forceinline__ void dma_load16(const void* gbase, unsigned voff, uns
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(N) : "memory");
+}
+
+// Compile-time loop: f(integral_constant<int, I>) for I = BEGIN .. END - 1.
+template <int BEGIN, int END, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (BEGIN < END) {
+        f(std::integral_constant<int, BEGIN>{});
+        static_for<BEGIN + 1, END>(f);
+    }
+}
+
+__device__ __forceinline__ v16i mfma(const v4i& a, const v4i& b, const v16i& c) {
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+}
+
+// acc = RN(acc + S_e 2^(-7 (e + 2))) for the diagonals of a band, least significant first. The
+// product of an integer below 2^31 and a power of two is exact, so the fused operation rounds
+// exactly like the sum it stands for.
+template <int SB>
+__device__ __forceinline__ void fold_band(double (&sum)[16], const v16i (&acc)[kBand]) {
+    constexpr int ND = SB < kBand ? SB : kBand, E0 = SB - ND;
+    mfma_results_ready();
+#pragma unroll
+    for (int e = SB - 1; e >= E0; --e) {
+        const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * (e + 2)) << 52);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) sum[u] = fma((double)acc_read(acc[e - E0][u]), sc, sum[u]);
+        __builtin_amdgcn_sched_barrier(0);   // one diagonal's temporaries at a time
+    }
 }
 
 // Raise a kernel's dynamic LDS limit once per device instead of before every launch (the call

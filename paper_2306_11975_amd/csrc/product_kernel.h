@@ -32,8 +32,6 @@
 // registers -> v_mfma_i32_32x32x32_i8.
 #pragma once
 
-#include <type_traits>
-
 #ifndef OZIMMU_TUNE_MAX_STAGES
 #define OZIMMU_TUNE_MAX_STAGES 3
 #endif
@@ -90,19 +88,6 @@ struct Walk {
     int tid;
     lds_i64* switch_table;     // this wavefront's LDS table of source-address changes between products (streams of products only)
 };
-
-// Compile-time loop: f(integral_constant<int, I>) for I = BEGIN .. END - 1.
-template <int BEGIN, int END, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-    if constexpr (BEGIN < END) {
-        f(std::integral_constant<int, BEGIN>{});
-        static_for<BEGIN + 1, END>(f);
-    }
-}
-
-__device__ __forceinline__ v16i mfma(const v4i& a, const v4i& b, const v16i& c) {
-    return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
-}
 
 __device__ __forceinline__ const int8_t* uniform_ptr(const int8_t* p) {
     const unsigned long long v = (unsigned long long)p;
@@ -360,21 +345,6 @@ __device__ __forceinline__ void band_walk(v16i (&acc)[kBand], const GemmArgs& g,
     }
 }
 
-// acc = RN(acc + S_e 2^(-7 (e + 2))) for the diagonals of a band, least significant first. The
-// product of an integer below 2^31 and a power of two is exact, so the fused operation rounds
-// exactly like the sum it stands for.
-template <int SB>
-__device__ __forceinline__ void fold_band(double (&sum)[16], const v16i (&acc)[kBand]) {
-    constexpr int ND = SB < kBand ? SB : kBand, E0 = SB - ND;
-#pragma unroll
-    for (int e = SB - 1; e >= E0; --e) {
-        const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * (e + 2)) << 52);
-#pragma unroll
-        for (int u = 0; u < 16; ++u) sum[u] = fma((double)acc_read(acc[e - E0][u]), sc, sum[u]);
-        __builtin_amdgcn_sched_barrier(0);   // one diagonal's temporaries at a time
-    }
-}
-
 // Double-double running sum (Section 2.3.4: summing-up in higher precision): TwoSum of the high
 // part and the exact term, error into the low part, FastTwoSum to renormalise.
 __device__ __forceinline__ void dd_add(double& h, double& l, double t) {
@@ -389,6 +359,7 @@ __device__ __forceinline__ void dd_add(double& h, double& l, double t) {
 template <int SB>
 __device__ __forceinline__ void fold_band_dd(double (&h)[16], double (&l)[16], const v16i (&acc)[kBand]) {
     constexpr int ND = SB < kBand ? SB : kBand, E0 = SB - ND;
+    mfma_results_ready();
 #pragma unroll
     for (int e = SB - 1; e >= E0; --e) {
         const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * (e + 2)) << 52);
@@ -464,7 +435,6 @@ void product_kernel(const GemmArgs g) {
     int* ex = reinterpret_cast<int*>(lds + Shape<S, WM, WN>::LDS);   // complex: the imaginary planes' set follows at TR + TC
     // behind them (complex only): per wavefront, the changes of its source addresses from product to product
     constexpr int kSwitchEntries = 3 * 8;
-    constexpr int SWITCH_BYTES = CPLX ? WM * WN * kSwitchEntries * 8 : 0;
     w.switch_table = (lds_i64*)(__attribute__((address_space(3))) unsigned char*)(lds + Shape<S, WM, WN>::LDS + NEX * (TR + TC) * 4) + w.wave * kSwitchEntries;
     static_assert(!CPLX || Band<(S < kBand ? S : kBand), WM, WN>::NLOAD <= 8, "switch table row");
     if (!g.P) {
@@ -491,6 +461,7 @@ void product_kernel(const GemmArgs g) {
         // one running pointer (made opaque so that it is formed here, not ahead of the k-walk)
         long long* q = g.D + (((int64_t)e0 * num_tiles + tile_id) * 16) * T + (w.wave * 64 + lane_here());
         const int64_t diag_stride = num_tiles * 16 * T - 16 * T;
+        mfma_results_ready();
 #pragma unroll
         for (int i = 0; i < kBand; ++i) {
             if (i < nd) {
@@ -596,6 +567,7 @@ void product_kernel(const GemmArgs g) {
         const int oz = (int)opaque_zero();
         const int row0 = at.row0, col = at.col, lrow0 = at.lrow0, lcol = at.lcol;
         if (g.P) {   // pair mode (S == 1): the raw INT32 sums
+            mfma_results_ready();
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
                 const int row = row0 + 8 * (u >> 2) + (u & 3);

@@ -9,75 +9,10 @@
 // Both kernels are HBM-bound: 8 B read per element (16 B for B, whose column maxima need a
 // pass of their own) and num_slices bytes written.
 #include "ozimmu_internal.h"
+#include "split_common.h"
 
 namespace ozimmu {
 namespace {
-
-constexpr unsigned long long kAbsMask = 0x7fffffffffffffffull;
-constexpr unsigned long long kMantMask = 0x000fffffffffffffull;
-
-// Exponent E with maxabs < 2^E and maxabs >= 2^(E-1); 0 for a zero row.
-__device__ __forceinline__ int exponent_of_max(unsigned long long maxbits) {
-    if (maxbits == 0) return 0;
-    int e = (int)(maxbits >> 52);
-    if (e != 0) return e - 1022;
-    return (64 - __clzll((long long)maxbits)) - 1074;  // subnormal maximum
-}
-
-// |x| 2^(-E) < 1 as a binary fraction of up to 128 bits: bit 63 of hi has weight 1/2. Slice p is
-// the p-th group of 7 bits after the binary point (truncation: the bits are simply cut), so once
-// the significand sits at its place every slice is a bit field at a fixed position. The one
-// shift whose amount varies from element to element is paid once, not once per slice.
-struct Fixed {
-    unsigned long long hi, lo;
-};
-
-template <bool WIDE>   // WIDE: more than 9 slices, i.e. more than the 63 bits the upper half can serve
-__device__ __forceinline__ Fixed to_fixed(unsigned long long bits, int E) {
-    const unsigned e = (unsigned)(bits >> 52) & 0x7ffu;
-    const unsigned long long mant = bits & kMantMask;
-    // significand with its leading bit at bit 63 (subnormal: no implicit bit, exponent field 1)
-    const unsigned long long T = (e ? (mant | (1ull << 52)) : mant) << 11;
-    // right shift that puts the binary point of |x| 2^(-E) just above bit 63. Never negative for
-    // normal numbers (|x| < 2^E); in a subnormal row the significands have leading zeros of
-    // their own and the shift of the largest ones goes the other way (by at most 52).
-    const int z = E + 1022 - (int)(e ? e : 1u);
-    Fixed f;
-    f.hi = z < 0 ? T << (-z) : z < 64 ? T >> z : 0ull;
-    f.lo = 0ull;
-    if (WIDE) f.lo = z <= 0 ? 0ull : z < 64 ? T << (64 - z) : z < 128 ? T >> (z - 64) : 0ull;
-    return f;
-}
-
-// Magnitude of slice p (1-based). With p a constant after unrolling this is one bit-field
-// extract of a 32-bit half, or a funnel shift when the field straddles two words.
-__device__ __forceinline__ unsigned field(const Fixed& f, int p) {
-    const int o = OZIMMU_SLICE_BITS * (p - 1);   // bits of the fraction ahead of the field
-    if (o + OZIMMU_SLICE_BITS <= 64) return (unsigned)(f.hi >> (64 - OZIMMU_SLICE_BITS - o)) & 127u;
-    if (o >= 64) return (unsigned)(f.lo >> (128 - OZIMMU_SLICE_BITS - o)) & 127u;
-    return ((unsigned)(f.hi << (o + OZIMMU_SLICE_BITS - 64)) & 127u) | (unsigned)(f.lo >> (128 - OZIMMU_SLICE_BITS - o));
-}
-
-// Signs of four consecutive elements as byte masks, and the byte-wise negation of the packed
-// magnitudes c (each 0..127) where the sign is set: per byte (c ^ 0xff) + 1 without a carry into
-// the next byte, i.e. the low seven bits are added on their own and the top bit is put back.
-struct SignMask {
-    uint32_t m7, m1, m80;
-};
-__device__ __forceinline__ SignMask sign_mask(unsigned long long b0, unsigned long long b1,
-                                              unsigned long long b2, unsigned long long b3) {
-    const uint32_t m = ((uint32_t)(b0 >> 63) * 0xffu) | ((uint32_t)(b1 >> 63) * 0xff00u) |
-                       ((uint32_t)(b2 >> 63) * 0xff0000u) | ((uint32_t)(b3 >> 63) * 0xff000000u);
-    return {m & 0x7f7f7f7fu, m & 0x01010101u, m & 0x80808080u};
-}
-__device__ __forceinline__ uint32_t apply_sign(uint32_t packed, const SignMask& sm) {
-    return ((packed ^ sm.m7) + sm.m1) ^ sm.m80;
-}
-template <bool WIDE>
-__device__ __forceinline__ uint32_t packed_slice(const Fixed (&x)[4], const SignMask& sm, int p) {
-    const uint32_t c = field(x[0], p) | (field(x[1], p) << 8) | (field(x[2], p) << 16) | (field(x[3], p) << 24);
-    return apply_sign(c, sm);
-}
 
 // Byte offset, inside one slice, of the 4-byte word that holds positions l0 .. l0+3 (l0 % 4 == 0)
 // of padded row r: fragments of 32 rows x 32 bytes, the two 16-byte halves of a row swapped in
@@ -86,15 +21,6 @@ __device__ __forceinline__ int64_t word_offset(int64_t r, int64_t l0, int64_t k_
     const int64_t rr = r & (kFragRows - 1);
     const int64_t h = (l0 & (kSlab - 1)) >> 4;
     return ((r / kFragRows) * (k_pad / kSlab) + l0 / kSlab) * kFragBytes + rr * kSlab + ((h ^ ((rr >> 3) & 1)) << 4) + (l0 & 15);
-}
-
-__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        unsigned long long o = __shfl_xor(v, off, 64);
-        v = o > v ? o : v;
-    }
-    return v;
 }
 
 // ------------------------------------------------------------------------------ rows of A
