@@ -16,7 +16,7 @@ EXAMPLE = PKG / "example_dgemm"       # stand-alone C++ user of the C ABI (csrc/
 PRELOAD = PKG / "libozimmu_preload.so"  # interposer for the vendor DGEMM/ZGEMM symbols (csrc/preload.cpp)
 BLAS_CLIENT = PKG / "blas_client"     # plain rocBLAS/hipBLAS program the interposer is tried on (csrc/blas_client.cpp)
 
-SOURCES = ["split.hip", "gemm.hip", "gemm_real.hip", "gemm_dd.hip", "gemm_complex.hip", "probes.hip", "static_scratch.hip", "api.cpp"]
+SOURCES = ["split.hip", "gemm.hip", "gemm_real.hip", "gemm_dd.hip", "gemm_complex.hip", "gate.hip", "probes.hip", "static_scratch.hip", "api.cpp"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", f"-I{INCLUDE}", f"-I{CSRC}"]
 # device code: gfx950 only; packed-FP32 instruction selection is switched off on the test machines
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

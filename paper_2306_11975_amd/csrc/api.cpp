@@ -190,6 +190,28 @@ hipError_t run_complex_products(const Layout& L, int64_t m, int64_t n, int s, un
     return e;
 }
 
+// The complex product of Z (m x k, split inside the product kernel) with a small B (k x n): see
+// gate_product_applies. The gate's slice tensors take the place of the planes of B's slices in the workspace
+// (the same number of bytes), its exponents that of the first plane's exponents.
+hipError_t run_gate_product(const Layout& L, int64_t m, int64_t n, int64_t k, int s, unsigned char* ws, const double* Z,
+                            int64_t ldz, const double* B, int64_t ldb, double* C, int64_t ldc, hipStream_t st) {
+    int8_t* T = reinterpret_cast<int8_t*>(ws + L.off_sb[0]);
+    int32_t* E = reinterpret_cast<int32_t*>(ws + L.off_eb[0]);
+    hipError_t e = launch_gate_split(B, ldb, k, n, s, T, E, st);
+    if (e != hipSuccess) return e;
+    GateArgs g{};
+    g.Z = Z;
+    g.ldz = ldz;
+    g.m = m;
+    g.k = (int)k;
+    g.n = (int)n;
+    g.T = T;
+    g.E = E;
+    g.Cz = C;
+    g.ldcz = ldc;
+    return launch_gate_product(g, s, st);
+}
+
 // 'N' -> 0, 'T' -> 1, 'C' -> 2, anything else -> -1
 int parse_trans(char c) {
     switch (c) {
@@ -411,6 +433,8 @@ ozimmu_status_t ozimmu_zgemm(int64_t m, int64_t n, int64_t k, const double* A, i
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     const int s = num_slices;
     hipError_t e = hipSuccess;
+    // a small B on a tall A (a gate on a state vector): one kernel that splits A on the fly and reads it once
+    if (gate_product_applies(A, B, C, n, k, s)) return hip_status(run_gate_product(L, m, n, k, s, ws, A, lda, B, ldb, C, ldc, st));
     // the real and imaginary planes are separated while splitting (element stride 2)
     e = split_complex_rows(A, lda, m, k, s, ws, L.off_sa, L.off_ea, L.m_pad, L.k_pad, st, false);
     for (int pl = 0; pl < 2 && e == hipSuccess; ++pl)

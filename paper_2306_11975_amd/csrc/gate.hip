@@ -1,0 +1,320 @@
+// A gate on a state vector (Section 4.4): the complex product of a tall operand Z (m x k, the reshaped state,
+// interleaved re/im) with a small one (B: k x n, the gate), k and n at most 64, up to eight slices, in ONE kernel
+// that reads Z once and writes the result once.
+//
+// With so short an inner dimension the product is bound by the memory traffic of the state and by the vector
+// work around the matrix cores, and splitting the state in a kernel of its own doubles that traffic (slices
+// written, slices read back). Here a workgroup of four wavefronts takes 64 rows of Z: it finds the exponents of
+// their real and imaginary parts and cuts both planes into slices (SplitInt, Section 3.1; the same bit operations as
+// the splitter kernels) straight into LDS, in the fragment layout of the MFMA operand.
+//
+// The gate is split beforehand (gate_split_kernel) into two slice tensors whose 32-row fragments interleave its
+// planes: fragment f of T1 holds columns 16 f .. 16 f + 15 of Br in rows 0..15 and the same columns of Bi in rows
+// 16..31, T2 the other way round. A wavefront owns 32 rows and 16 complex columns at a time: Ar times a T1
+// fragment gives G(Ar,Br) in lanes 0..15 (of each half) and G(Ar,Bi) in lanes 16..31, Ai times the T2 fragment
+// gives G(Ai,Bi) and G(Ai,Br) in the same lanes, so that one rounded FP64 operation per lane forms
+// re = G(Ar,Br) - G(Ai,Bi) or im = G(Ar,Bi) + G(Ai,Br); lanes 16 apart exchange half of their values and every lane
+// stores whole (re, im) pairs. All anti-diagonals of a product are resident in registers, every product is folded
+// in FP64 in the fixed order, least significant first, and scaled by 2^(EA_i + EB_j) (the summing-up step of the
+// algorithm, Section 3.1). Two workgroups share a compute unit, so one loads, splits, folds or stores while the other
+// multiplies.
+//
+// Unlike the large product kernel this one leaves register allocation to the compiler: at two wavefronts per SIMD
+// and with no accumulation-register operand in inline assembly the MFMA results land in ordinary vector registers,
+// where the FP64 fold reads them directly, and a product's first MFMA per diagonal takes the constant 0 as its
+// addend instead of cleared registers.
+#include "mfma_common.h"
+#include "split_common.h"
+
+namespace ozimmu {
+namespace {
+
+constexpr int kGateRows = 64;   // rows of Z per workgroup
+constexpr int kGateCols = 64;   // largest k and n
+
+// ---------------------------------------------------------------------------- the gate -> T1, T2, exponents
+// One workgroup. Thread (c, kq) = (tid % 64, tid / 64) owns column c of B and the positions 16 kq .. 16 kq + 15
+// of k. T: tensor t at t * s * 4 ks KiB, slice q at q * 4 ks KiB, fragment (f, step) at (f ks + step) KiB.
+// E: [t][f][32] exponents of the fragments' rows.
+__global__ __launch_bounds__(256) void gate_split_kernel(const double* __restrict__ B, int64_t ldb, int k, int n, int s,
+                                                         int ks, int8_t* __restrict__ T, int32_t* __restrict__ E) {
+    const int tid = threadIdx.x, c = tid & 63, kq = tid >> 6;
+    const ulonglong2* src = reinterpret_cast<const ulonglong2*>(B);
+    ulonglong2 v[16];
+    unsigned long long mx_re = 0, mx_im = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int l = kq * 16 + i;
+        v[i] = ulonglong2{0ull, 0ull};
+        if (l < k && c < n) v[i] = src[(int64_t)l * ldb + c];
+        const unsigned long long a = v[i].x & kAbsMask, b = v[i].y & kAbsMask;
+        mx_re = a > mx_re ? a : mx_re;
+        mx_im = b > mx_im ? b : mx_im;
+    }
+    __shared__ unsigned long long colmax[4][64][2];
+    colmax[kq][c][0] = mx_re;
+    colmax[kq][c][1] = mx_im;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        mx_re = colmax[w][c][0] > mx_re ? colmax[w][c][0] : mx_re;
+        mx_im = colmax[w][c][1] > mx_im ? colmax[w][c][1] : mx_im;
+    }
+    const int e_re = exponent_of_max(mx_re), e_im = exponent_of_max(mx_im);
+    const int f = c >> 4, r16 = c & 15;
+    if (kq == 0) {
+        E[f * 32 + r16] = e_re;
+        E[f * 32 + 16 + r16] = e_im;
+        E[128 + f * 32 + r16] = e_im;
+        E[128 + f * 32 + 16 + r16] = e_re;
+    }
+    if (kq * 16 >= kSlab * ks) return;
+    const int64_t slice = (int64_t)4 * ks * kFragBytes, tensor = (int64_t)s * slice;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        Fixed xr[4], xi[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            xr[u] = to_fixed<false>(v[4 * w + u].x, e_re);
+            xi[u] = to_fixed<false>(v[4 * w + u].y, e_im);
+        }
+        const SignMask sr = sign_mask(v[4 * w].x, v[4 * w + 1].x, v[4 * w + 2].x, v[4 * w + 3].x);
+        const SignMask si = sign_mask(v[4 * w].y, v[4 * w + 1].y, v[4 * w + 2].y, v[4 * w + 3].y);
+        const int l0 = kq * 16 + w * 4, step = l0 >> 5, ll = l0 & 31;
+        // rows r16 (first plane of the fragment) and 16 + r16 (second): both have the same bit 3, hence the same swap of halves
+        const int64_t lo = (int64_t)(f * ks + step) * kFragBytes + r16 * kSlab + ((((ll >> 4) ^ (r16 >> 3)) & 1) << 4) + (ll & 15);
+        const int64_t hi = lo + 16 * kSlab;
+#pragma unroll
+        for (int p = 1; p <= kBand; ++p) {
+            if (p <= s) {
+                const uint32_t pr = packed_slice<false>(xr, sr, p), pi = packed_slice<false>(xi, si, p);
+                int8_t* d = T + (p - 1) * slice;
+                *reinterpret_cast<uint32_t*>(d + lo) = pr;
+                *reinterpret_cast<uint32_t*>(d + hi) = pi;
+                *reinterpret_cast<uint32_t*>(d + tensor + lo) = pi;
+                *reinterpret_cast<uint32_t*>(d + tensor + hi) = pr;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------- the product
+template <int S, int KS>   // slices; steps of 32 positions of k
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void gate_kernel(const GateArgs g) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int SLICE = KS * 2 * kFragBytes;   // one slice of one plane of the tile's rows: [step][row fragment]
+    constexpr int PLANE = S * SLICE;
+    // behind the two planes: exponents of the 64 rows, [plane][64], then the 256 exponents of the gate's fragments
+    int* ex = reinterpret_cast<int*>(lds + 2 * PLANE);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t row_tile = (int64_t)blockIdx.x * kGateRows;
+
+    // ---- this wavefront's patches: rows 32 wm .. + 31, complex columns 16 f .. 16 f + 15 for f = 2 wn, 2 wn + 1
+    const int wm = wave >> 1, wn = wave & 1;
+    const int rr = lane & 31, half = lane >> 5;
+    // MFMA operand: lane holds row (lane % 32), bytes 16 (lane / 32) .. + 16 of the 32-byte fragment row
+    const unsigned rd_lane = (unsigned)(rr * 32 + ((half ^ ((rr >> 3) & 1)) << 4));
+    const unsigned char* a_rd = lds + wm * kFragBytes + rd_lane;
+    constexpr int BSLICE = 4 * KS * kFragBytes, TENSOR = S * BSLICE;
+    auto read_a = [&](int plane, int p, int step) __attribute__((always_inline)) -> v4i {
+        return *reinterpret_cast<const v4i*>(a_rd + plane * PLANE + p * SLICE + step * 2 * kFragBytes);
+    };
+    auto load_b = [&](int t, int f, int q, int step) __attribute__((always_inline)) -> v4i {
+        return *reinterpret_cast<const v4i*>(g.T + t * TENSOR + q * BSLICE + (f * KS + step) * kFragBytes + rd_lane);
+    };
+    // the gate's fragments of the first walk are requested before anything else: they are on their way while Z is split
+    v4i b[S];
+    static_for<0, S>([&](auto pc) __attribute__((always_inline)) { b[decltype(pc)::value] = load_b(0, 2 * wn, decltype(pc)::value, 0); });
+
+    // ---- the rows of Z -> exponents and slices in LDS. Sixteen lanes work on a row, a lane owns four
+    // consecutive complex elements; a wavefront takes sixteen rows, four at a time.
+    {
+        const int r4 = lane >> 4, c16 = lane & 15;
+        ex[128 + tid] = g.E[tid];
+        ulonglong2 v[4][4];
+#pragma unroll
+        for (int gi = 0; gi < 4; ++gi) {
+            const int64_t row = row_tile + wave * 16 + gi * 4 + r4;
+            const bool live = row < g.m;
+            const ulonglong2* src = reinterpret_cast<const ulonglong2*>(g.Z) + (live ? row : 0) * g.ldz;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int l = c16 * 4 + u;
+                v[gi][u] = ulonglong2{0ull, 0ull};
+                if (live && l < g.k) v[gi][u] = src[l];
+            }
+        }
+#pragma unroll
+        for (int gi = 0; gi < 4; ++gi) {
+            unsigned long long mx_re = 0, mx_im = 0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const unsigned long long a = v[gi][u].x & kAbsMask, b = v[gi][u].y & kAbsMask;
+                mx_re = a > mx_re ? a : mx_re;
+                mx_im = b > mx_im ? b : mx_im;
+            }
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) {
+                const unsigned long long o = __shfl_xor(mx_re, off, 64), q = __shfl_xor(mx_im, off, 64);
+                mx_re = o > mx_re ? o : mx_re;
+                mx_im = q > mx_im ? q : mx_im;
+            }
+            const int e_re = exponent_of_max(mx_re), e_im = exponent_of_max(mx_im);
+            const int lrow = wave * 16 + gi * 4 + r4;
+            if (c16 == 0) {
+                ex[lrow] = e_re;
+                ex[64 + lrow] = e_im;
+            }
+            if (c16 * 4 < kSlab * KS) {   // (a one-step product has no second fragment to fill)
+                Fixed xr[4], xi[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    xr[u] = to_fixed<false>(v[gi][u].x, e_re);
+                    xi[u] = to_fixed<false>(v[gi][u].y, e_im);
+                }
+                const SignMask sr = sign_mask(v[gi][0].x, v[gi][1].x, v[gi][2].x, v[gi][3].x);
+                const SignMask si = sign_mask(v[gi][0].y, v[gi][1].y, v[gi][2].y, v[gi][3].y);
+                // the fragment layout of the slice tensors: rows of 32 bytes, their two halves swapped in rows 8..15 and 24..31
+                const int rr = lrow & 31, l0 = (c16 & 7) * 4;
+                unsigned char* dst = lds + ((c16 >> 3) * 2 + (lrow >> 5)) * kFragBytes + rr * kSlab +
+                                     ((((l0 >> 4) ^ (rr >> 3)) & 1) << 4) + (l0 & 15);
+                static_for<1, S + 1>([&](auto pc) __attribute__((always_inline)) {
+                    constexpr int p = decltype(pc)::value;
+                    *reinterpret_cast<uint32_t*>(dst + (p - 1) * SLICE) = packed_slice<false>(xr, sr, p);
+                    *reinterpret_cast<uint32_t*>(dst + PLANE + (p - 1) * SLICE) = packed_slice<false>(xi, si, p);
+                });
+            }
+            __builtin_amdgcn_sched_barrier(0);   // one group's temporaries at a time
+        }
+    }
+    __syncthreads();
+
+    // ---- the products
+    // accumulator layout of the 32x32 MFMA: lane holds column (lane % 32); register u holds row 8 (u / 4) + 4 (lane / 32) + u % 4
+    const int lrow0 = wm * 32 + 4 * half;
+    // patches of this wavefront that hold a column of C at all (wave-uniform)
+    const int nf = g.n > (2 * wn + 1) * 16 ? 2 : g.n > 2 * wn * 16 ? 1 : 0;
+    if (nf == 0) return;
+
+    v16i acc[S];
+    v4i a[S];
+    double part[16];
+    // iteration it: patch it / 2, pass it % 2 (0: Ar with T1, 1: Ai with T2)
+    for (int it = 0; it < 2 * nf; ++it) {
+        const int pass = it & 1, f = 2 * wn + (it >> 1);
+        const int nit = it + 1 < 2 * nf ? it + 1 : 0;   // (after the last one the first one's fragments again, unused)
+        const int npass = nit & 1, nfr = 2 * wn + (nit >> 1);
+        static_for<0, S>([&](auto pc) __attribute__((always_inline)) { a[decltype(pc)::value] = read_a(pass, decltype(pc)::value, 0); });
+        __builtin_amdgcn_sched_barrier(0);
+        // Group q of a step = the MFMAs of B fragment q with the A fragments S - 1 - q .. 0, each into the sum of
+        // its anti-diagonal p + q: b[q] and a[S - 1 - q] have their last use of the step there and are fetched again,
+        // in place, for the next step. Across the end of a walk only the B fragments are (they come from memory); the
+        // A fragments are read from LDS after the fold, which needs their registers.
+        static_for<0, KS>([&](auto sc) __attribute__((always_inline)) {
+            constexpr int step = decltype(sc)::value;
+            constexpr bool last_step = step == KS - 1;
+            static_for<0, S>([&](auto qc) __attribute__((always_inline)) {
+                constexpr int q = decltype(qc)::value, pmax = S - 1 - q;
+                static_for<0, pmax + 1>([&](auto ic) __attribute__((always_inline)) {
+                    constexpr int p = pmax - decltype(ic)::value;
+                    if constexpr (step == 0 && q == 0) acc[p] = mfma(a[p], b[0], v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0});
+                    else acc[p + q] = mfma(a[p], b[q], acc[p + q]);
+                });
+                if constexpr (last_step) {
+                    b[q] = load_b(npass, nfr, q, 0);
+                } else {
+                    b[q] = load_b(pass, f, q, step + 1);
+                    a[pmax] = read_a(pass, pmax, step + 1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+        // G = the diagonals, least significant first: acc = RN(acc + S_e 2^(-7 (e + 2))) (the product of an integer
+        // below 2^31 and a power of two is exact, so the fused operation rounds like the sum it stands for) ...
+        double sum[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) sum[u] = 0.0;
+#pragma unroll
+        for (int e = S - 1; e >= 0; --e) {
+            const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * (e + 2)) << 52);
+#pragma unroll
+            for (int u = 0; u < 16; ++u) sum[u] = fma((double)acc[e][u], sc, sum[u]);
+            __builtin_amdgcn_sched_barrier(0);   // one diagonal's temporaries at a time
+        }
+        // ... times 2^(EA_i + EB_j)
+        const int* exa = ex + pass * 64 + lrow0;
+        const int eb = ex[128 + pass * 128 + f * 32 + rr];
+#pragma unroll
+        for (int u4 = 0; u4 < 4; ++u4) {
+            const v4i ea = *reinterpret_cast<const v4i*>(exa + 8 * u4);   // four consecutive rows
+#pragma unroll
+            for (int uu = 0; uu < 4; ++uu) sum[4 * u4 + uu] = ldexp(sum[4 * u4 + uu], ea[uu] + eb);
+        }
+        if (pass == 0) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) part[u] = sum[u];
+        } else {
+            // lanes 0..15 of each half: re = G(Ar,Br) - G(Ai,Bi); lanes 16..31: im = G(Ar,Bi) + G(Ai,Br)
+            const bool is_im = (lane & 16) != 0;
+#pragma unroll
+            for (int u = 0; u < 16; ++u) sum[u] = is_im ? part[u] + sum[u] : part[u] - sum[u];
+            // Lanes 16 apart hold the two parts of the same elements. The one with the real parts keeps the first
+            // eight rows and is sent the imaginary parts of those; the other keeps the last eight.
+            const int col = f * 16 + (rr & 15);
+            const int64_t row0 = row_tile + lrow0 + (is_im ? 16 : 0);
+            double* c = g.Cz + 2 * (row0 * g.ldcz + col);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const double keep = is_im ? sum[u + 8] : sum[u];
+                const double recv = __shfl_xor(is_im ? sum[u] : sum[u + 8], 16, 64);
+                const int dr = 8 * (u >> 2) + (u & 3);   // (rows 16 .. of the patch for the second lane: in row0)
+                double2 z;
+                z.x = is_im ? recv : keep;
+                z.y = is_im ? keep : recv;
+                if (row0 + dr < g.m && col < g.n) *reinterpret_cast<double2*>(c + 2 * (int64_t)dr * g.ldcz) = z;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <int S, int KS>
+hipError_t launch_gate(const GateArgs& g, hipStream_t st) {
+    constexpr int lds = 2 * S * KS * 2 * kFragBytes + (2 * 64 + 256) * (int)sizeof(int);
+    static_assert(2 * lds <= 160 * 1024, "two workgroups per compute unit");
+    hipError_t e = allow_dynamic_lds<&gate_kernel<S, KS>>(lds);
+    if (e != hipSuccess) return e;
+    const unsigned grid = (unsigned)((g.m + kGateRows - 1) / kGateRows);
+    gate_kernel<S, KS><<<dim3(grid), dim3(256), lds, st>>>(g);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool gate_product_applies(const double* Z, const double* B, const double* Cz, int64_t n, int64_t k, int s) {
+    return n >= 1 && n <= kGateCols && k >= 1 && k <= kGateCols && s <= kBand && reinterpret_cast<uintptr_t>(Z) % 16 == 0 &&
+           reinterpret_cast<uintptr_t>(B) % 16 == 0 && reinterpret_cast<uintptr_t>(Cz) % 16 == 0;
+}
+
+size_t gate_tensor_bytes(int64_t k, int s) { return (size_t)2 * s * 4 * (k > kSlab ? 2 : 1) * kFragBytes; }
+
+hipError_t launch_gate_split(const double* B, int64_t ldb, int64_t k, int64_t n, int s, int8_t* T, int32_t* E, hipStream_t st) {
+    gate_split_kernel<<<dim3(1), dim3(256), 0, st>>>(B, ldb, (int)k, (int)n, s, k > kSlab ? 2 : 1, T, E);
+    return hipGetLastError();
+}
+
+hipError_t launch_gate_product(const GateArgs& g, int s, hipStream_t st) {
+    if (g.m <= 0) return hipSuccess;
+    if (g.n < 1 || g.n > kGateCols || g.k < 1 || g.k > kGateCols) return hipErrorInvalidValue;
+    const int ks = g.k > kSlab ? 2 : 1;
+    switch (s) {
+#define OZ_CASE(S_) case S_: return ks == 2 ? launch_gate<S_, 2>(g, st) : launch_gate<S_, 1>(g, st);
+        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8)
+#undef OZ_CASE
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace ozimmu

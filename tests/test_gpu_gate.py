@@ -1,0 +1,106 @@
+"""GPU parity of the one-kernel complex product for a small gate on a tall state (Section 4.4: a d-qubit gate on an
+N-qubit state vector is the complex product 2^(N-d) x 2^d x 2^d). ozimmu_zgemm takes that path when k and n are
+at most 64 and at most eight slices are asked for; the state is then split inside the product kernel. Compared bit
+for bit with the oracle, which splits first and multiplies afterwards."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2306_11975_amd import ozimmu
+from paper_2306_11975_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def bits(x):
+    return np.ascontiguousarray(x).view(np.uint64)
+
+
+def gpu_zgemm(A, B, s, lda_extra=0, ldb_extra=0, ldc_extra=0):
+    m, k = A.shape
+    n = B.shape[1]
+    nan = complex(float("nan"), float("nan"))
+    Ad = torch.full((m, k + lda_extra), nan, dtype=torch.complex128, device=DEV)
+    Bd = torch.full((k, n + ldb_extra), nan, dtype=torch.complex128, device=DEV)
+    Cd = torch.full((m, n + ldc_extra), nan, dtype=torch.complex128, device=DEV)
+    Ad[:, :k] = torch.from_numpy(A)
+    Bd[:, :n] = torch.from_numpy(B)
+    ozimmu.zgemm(Ad[:, :k], Bd[:, :n], Cd[:, :n], s, ozimmu.alloc_workspace(m, n, k, s, is_complex=True))
+    torch.cuda.synchronize()
+    out = Cd.cpu().numpy()
+    assert np.all(np.isnan(out[:, n:].real)) and np.all(np.isnan(out[:, n:].imag)), "wrote outside C"
+    return out[:, :n]
+
+
+def assert_same(got, want):
+    assert np.array_equal(bits(got.real.copy()), bits(want.real.copy()))
+    assert np.array_equal(bits(got.imag.copy()), bits(want.imag.copy()))
+
+
+@pytest.mark.parametrize("s", range(1, 9))
+@pytest.mark.parametrize("k", [32, 64])
+def test_gate_every_slice_count(s, k):
+    """Every kernel instantiation (slices x steps), three row tiles with a ragged last one."""
+    m, n = 150, 64
+    A = wl.gaussian_complex(m, k, seed=100 + s)
+    B = wl.unit_column_complex(k, n, seed=200 + s)
+    assert_same(gpu_zgemm(A, B, s), oracle.zgemm(A, B, s))
+
+
+@pytest.mark.parametrize("m,n,k,s", [(1, 1, 1, 3), (64, 64, 64, 8), (65, 63, 33, 7), (63, 17, 31, 5), (130, 16, 64, 8),
+                                     (200, 15, 17, 2), (31, 33, 1, 4), (300, 48, 40, 6), (129, 32, 32, 8), (64, 49, 64, 1)])
+def test_gate_ragged_shapes(m, n, k, s):
+    """Rows, columns and inner dimension on both sides of every boundary the kernel has: 64 rows per workgroup,
+    16 columns per patch (patches past the last column are skipped), 32 positions per step."""
+    A = wl.gaussian_complex(m, k, seed=m + k)
+    B = wl.unit_column_complex(k, n, seed=n + k + 1)
+    assert_same(gpu_zgemm(A, B, s), oracle.zgemm(A, B, s))
+
+
+def test_gate_respects_leading_dimensions():
+    A = wl.gaussian_complex(100, 50, seed=3)
+    B = wl.unit_column_complex(50, 40, seed=4)
+    assert_same(gpu_zgemm(A, B, 7, lda_extra=5, ldb_extra=3, ldc_extra=9), oracle.zgemm(A, B, 7))
+
+
+def test_gate_adversarial_values():
+    """Zero rows and columns, exact powers of two, one huge element per row, subnormals, in both planes."""
+    m, n, k = 96, 64, 64
+    A = wl.adversarial_matrix(m, k, seed=5) + 1j * wl.adversarial_matrix(m, k, seed=6)
+    B = wl.adversarial_matrix(k, n, seed=7) + 1j * wl.adversarial_matrix(k, n, seed=8)
+    for s in (3, 8):
+        assert_same(gpu_zgemm(A, B, s), oracle.zgemm(A, B, s))
+
+
+def test_gate_purely_real_and_purely_imaginary_operands():
+    """Each of the four real products on its own: a part that must come out as an exact zero does."""
+    A = wl.gaussian_complex(70, 64, seed=9)
+    B = wl.unit_column_complex(64, 64, seed=10)
+    for Ax, Bx in ((A.real + 0j, B.real + 0j), (1j * A.imag, 1j * B.imag), (A.real + 0j, 1j * B.imag), (1j * A.imag, B.real + 0j)):
+        got = gpu_zgemm(np.ascontiguousarray(Ax), np.ascontiguousarray(Bx), 6)
+        assert_same(got, oracle.zgemm(Ax, Bx, 6))
+
+
+def test_more_than_eight_slices_take_the_general_path():
+    A = wl.gaussian_complex(70, 64, seed=11)
+    B = wl.unit_column_complex(64, 64, seed=12)
+    assert_same(gpu_zgemm(A, B, 11), oracle.zgemm(A, B, 11))
+
+
+def test_gate_on_a_long_state_sampled_rows():
+    """A 6-qubit gate on 22 qubits (65536 x 64 x 64): rows sampled over the whole state, among them the first and
+    last of the first and last workgroup (separability: an entry of the result depends on one row of the state only)."""
+    m, k, s = 1 << 16, 64, 8
+    A = wl.gaussian_complex_device(m, k, seed=13)
+    A = A / A.abs().pow(2).sum().sqrt()
+    U = wl.haar_unitary_device(k, seed=14).contiguous()
+    C = torch.empty((m, k), dtype=torch.complex128, device=DEV)
+    ozimmu.zgemm(A, U, C, s, ozimmu.alloc_workspace(m, k, k, s, is_complex=True))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(15)
+    rows = np.unique(np.concatenate([[0, 63, 64, m - 64, m - 1], rng.integers(0, m, 200)]))
+    idx = torch.from_numpy(rows).to(DEV)
+    want = oracle.zgemm(A[idx].cpu().numpy(), U.cpu().numpy(), s)
+    assert_same(C[idx].cpu().numpy(), want)
