@@ -559,6 +559,17 @@ ozimmu_status_t ozimmu_zgemm_blas(char transa, char transb, int64_t m, int64_t n
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     unsigned long long* colmax = reinterpret_cast<unsigned long long*>(ws + L.off_colmax);
     hipError_t e = hipSuccess;
+    const bool alpha_one = ar == 1.0 && ai == 0.0;
+    // The product goes straight into C when C's old values are not needed, else beside the slices.
+    double* G = beta_zero ? C : reinterpret_cast<double*>(ws + align_up(L.total));
+    const int64_t ldg = beta_zero ? ldc : m;
+    // Neither operand transposed, a small A on a wide B (a gate on a state vector whose amplitudes are the columns'
+    // entries): the row-major product B^T A^T has the state as its tall operand and takes the one-kernel path.
+    if (!ta && !tb && gate_product_applies(B, A, G, m, k, num_slices)) {
+        e = run_gate_product(L, n, m, k, num_slices, ws, B, ldb, A, lda, G, ldg, st);
+        if (e == hipSuccess && !(beta_zero && alpha_one)) e = launch_zaxpby(G, ldg, C, ldc, n, m, ar, ai, br, bi, st);
+        return hip_status(e);
+    }
     // planes: real, then imaginary (negated while splitting if the operand is conjugated)
     if (!tb) e = split_complex_rows(B, ldb, n, k, num_slices, ws, L.off_sa, L.off_ea, L.m_pad, L.k_pad, st, false);   // op(B)^T: n rows of length k
     else for (int pl = 0; pl < 2 && e == hipSuccess; ++pl)
@@ -570,10 +581,6 @@ ozimmu_status_t ozimmu_zgemm_blas(char transa, char transb, int64_t m, int64_t n
             e = launch_split_cols(A + pl, lda, 2, k, m, num_slices, reinterpret_cast<int8_t*>(ws + L.off_sb[pl]), L.n_pad, L.k_pad,
                                   reinterpret_cast<int32_t*>(ws + L.off_eb[pl]), colmax, st, false);
     }
-    const bool alpha_one = ar == 1.0 && ai == 0.0;
-    // The product goes straight into C when C's old values are not needed, else beside the slices.
-    double* G = beta_zero ? C : reinterpret_cast<double*>(ws + align_up(L.total));
-    const int64_t ldg = beta_zero ? ldc : m;
     if (e == hipSuccess) e = run_complex_products(L, n, m, num_slices, ws, G, ldg, st);
     if (e == hipSuccess && !(beta_zero && alpha_one)) e = launch_zaxpby(G, ldg, C, ldc, n, m, ar, ai, br, bi, st);
     return hip_status(e);

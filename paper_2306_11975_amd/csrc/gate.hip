@@ -33,67 +33,63 @@ constexpr int kGateRows = 64;   // rows of Z per workgroup
 constexpr int kGateCols = 64;   // largest k and n
 
 // ---------------------------------------------------------------------------- the gate -> T1, T2, exponents
-// One workgroup. Thread (c, kq) = (tid % 64, tid / 64) owns column c of B and the positions 16 kq .. 16 kq + 15
-// of k. T: tensor t at t * s * 4 ks KiB, slice q at q * 4 ks KiB, fragment (f, step) at (f ks + step) KiB.
-// E: [t][f][32] exponents of the fragments' rows.
+// One workgroup per fragment f (16 columns of B). Thread (c, w) = (tid % 16, tid / 16) owns column 16 f + c and the
+// four positions 4 w .. 4 w + 3 of k. T: tensor t at t * s * 4 ks KiB, slice q at q * 4 ks KiB, fragment (f, step)
+// at (f ks + step) KiB. E: [t][f][32] exponents of the fragments' rows.
 __global__ __launch_bounds__(256) void gate_split_kernel(const double* __restrict__ B, int64_t ldb, int k, int n, int s,
                                                          int ks, int8_t* __restrict__ T, int32_t* __restrict__ E) {
-    const int tid = threadIdx.x, c = tid & 63, kq = tid >> 6;
+    const int tid = threadIdx.x, r16 = tid & 15, w = tid >> 4, f = blockIdx.x, c = f * 16 + r16;
     const ulonglong2* src = reinterpret_cast<const ulonglong2*>(B);
-    ulonglong2 v[16];
+    ulonglong2 v[4];
     unsigned long long mx_re = 0, mx_im = 0;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int l = kq * 16 + i;
-        v[i] = ulonglong2{0ull, 0ull};
-        if (l < k && c < n) v[i] = src[(int64_t)l * ldb + c];
-        const unsigned long long a = v[i].x & kAbsMask, b = v[i].y & kAbsMask;
+    for (int u = 0; u < 4; ++u) {
+        const int l = 4 * w + u;
+        v[u] = ulonglong2{0ull, 0ull};
+        if (l < k && c < n) v[u] = src[(int64_t)l * ldb + c];
+        const unsigned long long a = v[u].x & kAbsMask, b = v[u].y & kAbsMask;
         mx_re = a > mx_re ? a : mx_re;
         mx_im = b > mx_im ? b : mx_im;
     }
-    __shared__ unsigned long long colmax[4][64][2];
-    colmax[kq][c][0] = mx_re;
-    colmax[kq][c][1] = mx_im;
+    __shared__ unsigned long long colmax[16][16][2];
+    colmax[w][r16][0] = mx_re;
+    colmax[w][r16][1] = mx_im;
     __syncthreads();
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        mx_re = colmax[w][c][0] > mx_re ? colmax[w][c][0] : mx_re;
-        mx_im = colmax[w][c][1] > mx_im ? colmax[w][c][1] : mx_im;
+    for (int i = 0; i < 16; ++i) {
+        mx_re = colmax[i][r16][0] > mx_re ? colmax[i][r16][0] : mx_re;
+        mx_im = colmax[i][r16][1] > mx_im ? colmax[i][r16][1] : mx_im;
     }
     const int e_re = exponent_of_max(mx_re), e_im = exponent_of_max(mx_im);
-    const int f = c >> 4, r16 = c & 15;
-    if (kq == 0) {
+    if (w == 0) {
         E[f * 32 + r16] = e_re;
         E[f * 32 + 16 + r16] = e_im;
         E[128 + f * 32 + r16] = e_im;
         E[128 + f * 32 + 16 + r16] = e_re;
     }
-    if (kq * 16 >= kSlab * ks) return;
+    if (4 * w >= kSlab * ks) return;
     const int64_t slice = (int64_t)4 * ks * kFragBytes, tensor = (int64_t)s * slice;
+    Fixed xr[4], xi[4];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        Fixed xr[4], xi[4];
+    for (int u = 0; u < 4; ++u) {
+        xr[u] = to_fixed<false>(v[u].x, e_re);
+        xi[u] = to_fixed<false>(v[u].y, e_im);
+    }
+    const SignMask sr = sign_mask(v[0].x, v[1].x, v[2].x, v[3].x);
+    const SignMask si = sign_mask(v[0].y, v[1].y, v[2].y, v[3].y);
+    const int l0 = 4 * w, step = l0 >> 5, ll = l0 & 31;
+    // rows r16 (first plane of the fragment) and 16 + r16 (second): both have the same bit 3, hence the same swap of halves
+    const int64_t lo = (int64_t)(f * ks + step) * kFragBytes + r16 * kSlab + ((((ll >> 4) ^ (r16 >> 3)) & 1) << 4) + (ll & 15);
+    const int64_t hi = lo + 16 * kSlab;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            xr[u] = to_fixed<false>(v[4 * w + u].x, e_re);
-            xi[u] = to_fixed<false>(v[4 * w + u].y, e_im);
-        }
-        const SignMask sr = sign_mask(v[4 * w].x, v[4 * w + 1].x, v[4 * w + 2].x, v[4 * w + 3].x);
-        const SignMask si = sign_mask(v[4 * w].y, v[4 * w + 1].y, v[4 * w + 2].y, v[4 * w + 3].y);
-        const int l0 = kq * 16 + w * 4, step = l0 >> 5, ll = l0 & 31;
-        // rows r16 (first plane of the fragment) and 16 + r16 (second): both have the same bit 3, hence the same swap of halves
-        const int64_t lo = (int64_t)(f * ks + step) * kFragBytes + r16 * kSlab + ((((ll >> 4) ^ (r16 >> 3)) & 1) << 4) + (ll & 15);
-        const int64_t hi = lo + 16 * kSlab;
-#pragma unroll
-        for (int p = 1; p <= kBand; ++p) {
-            if (p <= s) {
-                const uint32_t pr = packed_slice<false>(xr, sr, p), pi = packed_slice<false>(xi, si, p);
-                int8_t* d = T + (p - 1) * slice;
-                *reinterpret_cast<uint32_t*>(d + lo) = pr;
-                *reinterpret_cast<uint32_t*>(d + hi) = pi;
-                *reinterpret_cast<uint32_t*>(d + tensor + lo) = pi;
-                *reinterpret_cast<uint32_t*>(d + tensor + hi) = pr;
-            }
+    for (int p = 1; p <= kBand; ++p) {
+        if (p <= s) {
+            const uint32_t pr = packed_slice<false>(xr, sr, p), pi = packed_slice<false>(xi, si, p);
+            int8_t* d = T + (p - 1) * slice;
+            *reinterpret_cast<uint32_t*>(d + lo) = pr;
+            *reinterpret_cast<uint32_t*>(d + hi) = pi;
+            *reinterpret_cast<uint32_t*>(d + tensor + lo) = pi;
+            *reinterpret_cast<uint32_t*>(d + tensor + hi) = pr;
         }
     }
 }
@@ -257,22 +253,27 @@ void gate_kernel(const GateArgs g) {
             for (int u = 0; u < 16; ++u) part[u] = sum[u];
         } else {
             // lanes 0..15 of each half: re = G(Ar,Br) - G(Ai,Bi); lanes 16..31: im = G(Ar,Bi) + G(Ai,Br)
+            // (the subtraction as the addition of the negated term: one flipped sign bit, no selection)
             const bool is_im = (lane & 16) != 0;
+            const long long flip = is_im ? 0ll : (long long)(1ull << 63);
 #pragma unroll
-            for (int u = 0; u < 16; ++u) sum[u] = is_im ? part[u] + sum[u] : part[u] - sum[u];
-            // Lanes 16 apart hold the two parts of the same elements. The one with the real parts keeps the first
-            // eight rows and is sent the imaginary parts of those; the other keeps the last eight.
+            for (int u = 0; u < 16; ++u) sum[u] = part[u] + __longlong_as_double(__double_as_longlong(sum[u]) ^ flip);
+            // Lanes 16 apart hold the two parts of the same elements. Swapping the upper 16 lanes of the register
+            // with rows u against the lower 16 of the one with rows u + 8 leaves (re, im) of row u in the lanes
+            // 0..15 and (re, im) of row u + 8 in the lanes 16..31: whole pairs to store, nothing to select.
             const int col = f * 16 + (rr & 15);
             const int64_t row0 = row_tile + lrow0 + (is_im ? 16 : 0);
             double* c = g.Cz + 2 * (row0 * g.ldcz + col);
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const double keep = is_im ? sum[u + 8] : sum[u];
-                const double recv = __shfl_xor(is_im ? sum[u] : sum[u + 8], 16, 64);
-                const int dr = 8 * (u >> 2) + (u & 3);   // (rows 16 .. of the patch for the second lane: in row0)
+                const unsigned long long x = (unsigned long long)__double_as_longlong(sum[u]);
+                const unsigned long long y = (unsigned long long)__double_as_longlong(sum[u + 8]);
+                const auto lo = __builtin_amdgcn_permlane16_swap((unsigned)x, (unsigned)y, false, false);
+                const auto hi = __builtin_amdgcn_permlane16_swap((unsigned)(x >> 32), (unsigned)(y >> 32), false, false);
+                const int dr = 8 * (u >> 2) + (u & 3);   // (rows 16 .. of the patch for the upper lanes: in row0)
                 double2 z;
-                z.x = is_im ? recv : keep;
-                z.y = is_im ? keep : recv;
+                z.x = __longlong_as_double((long long)(((unsigned long long)hi[0] << 32) | lo[0]));
+                z.y = __longlong_as_double((long long)(((unsigned long long)hi[1] << 32) | lo[1]));
                 if (row0 + dr < g.m && col < g.n) *reinterpret_cast<double2*>(c + 2 * (int64_t)dr * g.ldcz) = z;
             }
         }
@@ -301,7 +302,7 @@ bool gate_product_applies(const double* Z, const double* B, const double* Cz, in
 size_t gate_tensor_bytes(int64_t k, int s) { return (size_t)2 * s * 4 * (k > kSlab ? 2 : 1) * kFragBytes; }
 
 hipError_t launch_gate_split(const double* B, int64_t ldb, int64_t k, int64_t n, int s, int8_t* T, int32_t* E, hipStream_t st) {
-    gate_split_kernel<<<dim3(1), dim3(256), 0, st>>>(B, ldb, (int)k, (int)n, s, k > kSlab ? 2 : 1, T, E);
+    gate_split_kernel<<<dim3(4), dim3(256), 0, st>>>(B, ldb, (int)k, (int)n, s, k > kSlab ? 2 : 1, T, E);
     return hipGetLastError();
 }
 

@@ -116,6 +116,16 @@ def test_complex_blas_shapes_across_the_kernels(m, n, k, s):
     zrun("N", "C", m, n, k, 1.0, 0.0, s, seed=4)
 
 
+@pytest.mark.parametrize("m,n,k,s", [(64, 1000, 64, 8), (32, 300, 32, 5), (17, 129, 40, 7), (64, 200, 64, 9)])
+def test_complex_blas_small_gate_on_a_wide_state(m, n, k, s):
+    """Neither operand transposed, A at most 64 x 64, up to eight slices: the state (B, whose columns are the rows of
+    the row-major product) is split inside the product kernel; with a general alpha and beta the update follows as
+    for every other shape. Nine slices take the general path."""
+    zrun("N", "N", m, n, k, 1.0, 0.0, s, seed=6, c_nan=True)
+    zrun("N", "N", m, n, k, 1.0, 0.0, s, seed=7, pad=(3, 2, 5), c_nan=True)
+    zrun("N", "N", m, n, k, 0.75 - 0.5j, 0.25 + 1.0j, s, seed=8, pad=(0, 1, 2))
+
+
 def test_complex_blas_beta_zero_does_not_read_c_and_degenerate_cases():
     zrun("N", "N", 64, 48, 100, 2.0 - 1j, 0.0, 6, c_nan=True)
     zrun("C", "C", 64, 48, 2000, 1.0, 0.0, 6, c_nan=True)
