@@ -32,7 +32,7 @@ struct Layout {
     size_t sa_bytes, sb_bytes;      // one plane
     size_t off_sa[2], off_sb[2];    // planes (real GEMM uses plane 0)
     size_t off_ea[2], off_eb[2];
-    size_t off_colmax, off_d, off_z;
+    size_t off_colmax, off_d, off_z, off_gate;
     size_t total;
 };
 
@@ -71,6 +71,8 @@ Layout make_layout(int64_t m, int64_t n, int64_t k, int s, bool cplx) {
     if (L.wide) off = align_up(off + (size_t)s * L.tiles_m * L.tiles_n * L.tile_rows * L.tile_cols * sizeof(long long));
     L.off_z = off;   // complex: the real and imaginary parts of the result as two m x n planes
     if (cplx) off = align_up(off + (size_t)2 * m * n * sizeof(double));
+    L.off_gate = off;   // complex with a small B: its slice tensors for the kernel that splits A on the fly
+    if (cplx) off = align_up(off + gate_scratch_bytes(n, k, s));
     L.total = off;
     return L;
 }
@@ -188,28 +190,6 @@ hipError_t run_complex_products(const Layout& L, int64_t m, int64_t n, int s, un
     if (e == hipSuccess) e = run_product(L, m, n, s, ws, 0, 1, Pi, n, 0, st);
     if (e == hipSuccess) e = run_product(L, m, n, s, ws, 1, 0, Pi, n, 4, st, 1.0, 0.0, nullptr, Pr, C, ldc);
     return e;
-}
-
-// The complex product of Z (m x k, split inside the product kernel) with a small B (k x n): see
-// gate_product_applies. The gate's slice tensors take the place of the planes of B's slices in the workspace
-// (the same number of bytes), its exponents that of the first plane's exponents.
-hipError_t run_gate_product(const Layout& L, int64_t m, int64_t n, int64_t k, int s, unsigned char* ws, const double* Z,
-                            int64_t ldz, const double* B, int64_t ldb, double* C, int64_t ldc, hipStream_t st) {
-    int8_t* T = reinterpret_cast<int8_t*>(ws + L.off_sb[0]);
-    int32_t* E = reinterpret_cast<int32_t*>(ws + L.off_eb[0]);
-    hipError_t e = launch_gate_split(B, ldb, k, n, s, T, E, st);
-    if (e != hipSuccess) return e;
-    GateArgs g{};
-    g.Z = Z;
-    g.ldz = ldz;
-    g.m = m;
-    g.k = (int)k;
-    g.n = (int)n;
-    g.T = T;
-    g.E = E;
-    g.Cz = C;
-    g.ldcz = ldc;
-    return launch_gate_product(g, s, st);
 }
 
 // 'N' -> 0, 'T' -> 1, 'C' -> 2, anything else -> -1
@@ -434,7 +414,7 @@ ozimmu_status_t ozimmu_zgemm(int64_t m, int64_t n, int64_t k, const double* A, i
     const int s = num_slices;
     hipError_t e = hipSuccess;
     // a small B on a tall A (a gate on a state vector): one kernel that splits A on the fly and reads it once
-    if (gate_product_applies(A, B, C, n, k, s)) return hip_status(run_gate_product(L, m, n, k, s, ws, A, lda, B, ldb, C, ldc, st));
+    if (gate_product_applies(A, B, C, n, k, s)) return hip_status(launch_gate_product(A, lda, m, k, n, B, ldb, s, ws + L.off_gate, C, ldc, st));
     // the real and imaginary planes are separated while splitting (element stride 2)
     e = split_complex_rows(A, lda, m, k, s, ws, L.off_sa, L.off_ea, L.m_pad, L.k_pad, st, false);
     for (int pl = 0; pl < 2 && e == hipSuccess; ++pl)
@@ -566,7 +546,7 @@ ozimmu_status_t ozimmu_zgemm_blas(char transa, char transb, int64_t m, int64_t n
     // Neither operand transposed, a small A on a wide B (a gate on a state vector whose amplitudes are the columns'
     // entries): the row-major product B^T A^T has the state as its tall operand and takes the one-kernel path.
     if (!ta && !tb && gate_product_applies(B, A, G, m, k, num_slices)) {
-        e = run_gate_product(L, n, m, k, num_slices, ws, B, ldb, A, lda, G, ldg, st);
+        e = launch_gate_product(B, ldb, n, k, m, A, lda, num_slices, ws + L.off_gate, G, ldg, st);
         if (e == hipSuccess && !(beta_zero && alpha_one)) e = launch_zaxpby(G, ldg, C, ldc, n, m, ar, ai, br, bi, st);
         return hip_status(e);
     }

@@ -1,10 +1,11 @@
 // A gate on a state vector (Section 4.4): the complex product of a tall operand Z (m x k, the reshaped state,
-// interleaved re/im) with a small one (B: k x n, the gate), k and n at most 64, up to eight slices, in ONE kernel
+// interleaved re/im) with a small one (B: k x n, the gate), k and n at most 128, up to eight slices, in ONE kernel
 // that reads Z once and writes the result once.
 //
 // With so short an inner dimension the product is bound by the memory traffic of the state and by the vector
 // work around the matrix cores, and splitting the state in a kernel of its own doubles that traffic (slices
-// written, slices read back). Here a workgroup of four wavefronts takes 64 rows of Z: it finds the exponents of
+// written, slices read back). Here a workgroup of four wavefronts takes 64 rows of Z (32 when k or n exceeds 64, so
+// that the slices of a tile still take half the LDS of a compute unit at most): it finds the exponents of
 // their real and imaginary parts and cuts both planes into slices (SplitInt, Section 3.1; the same bit operations as
 // the splitter kernels) straight into LDS, in the fragment layout of the MFMA operand.
 //
@@ -29,16 +30,17 @@
 namespace ozimmu {
 namespace {
 
-constexpr int kGateRows = 64;   // rows of Z per workgroup
-constexpr int kGateCols = 64;   // largest k and n
+constexpr int kGateSmall = 64;    // k and n up to here: tiles of 64 rows, 2 x 2 wavefronts, four fragments of 16 columns of B
+constexpr int kGateLarge = 128;   // beyond, up to here: tiles of 32 rows, 1 x 4 wavefronts, eight fragments, four steps
 
 // ---------------------------------------------------------------------------- the gate -> T1, T2, exponents
 // One workgroup per fragment f (16 columns of B). Thread (c, w) = (tid % 16, tid / 16) owns column 16 f + c and the
-// four positions 4 w .. 4 w + 3 of k. T: tensor t at t * s * 4 ks KiB, slice q at q * 4 ks KiB, fragment (f, step)
-// at (f ks + step) KiB. E: [t][f][32] exponents of the fragments' rows.
-__global__ __launch_bounds__(256) void gate_split_kernel(const double* __restrict__ B, int64_t ldb, int k, int n, int s,
-                                                         int ks, int8_t* __restrict__ T, int32_t* __restrict__ E) {
+// four positions 4 w .. 4 w + 3 of k. T: tensor t at t * s * nfr * ks KiB, slice q at q * nfr * ks KiB, fragment
+// (f, step) at (f ks + step) KiB. E: [t][f][32] exponents of the fragments' rows.
+__global__ __launch_bounds__(512) void gate_split_kernel(const double* __restrict__ B, int64_t ldb, int k, int n, int s,
+                                                         int ks, int nfr, int8_t* __restrict__ T, int32_t* __restrict__ E) {
     const int tid = threadIdx.x, r16 = tid & 15, w = tid >> 4, f = blockIdx.x, c = f * 16 + r16;
+    const int words = blockDim.x >> 4;   // 16 (k <= 64) or 32
     const ulonglong2* src = reinterpret_cast<const ulonglong2*>(B);
     ulonglong2 v[4];
     unsigned long long mx_re = 0, mx_im = 0;
@@ -51,12 +53,11 @@ __global__ __launch_bounds__(256) void gate_split_kernel(const double* __restric
         mx_re = a > mx_re ? a : mx_re;
         mx_im = b > mx_im ? b : mx_im;
     }
-    __shared__ unsigned long long colmax[16][16][2];
+    __shared__ unsigned long long colmax[32][16][2];
     colmax[w][r16][0] = mx_re;
     colmax[w][r16][1] = mx_im;
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < words; ++i) {
         mx_re = colmax[i][r16][0] > mx_re ? colmax[i][r16][0] : mx_re;
         mx_im = colmax[i][r16][1] > mx_im ? colmax[i][r16][1] : mx_im;
     }
@@ -64,11 +65,11 @@ __global__ __launch_bounds__(256) void gate_split_kernel(const double* __restric
     if (w == 0) {
         E[f * 32 + r16] = e_re;
         E[f * 32 + 16 + r16] = e_im;
-        E[128 + f * 32 + r16] = e_im;
-        E[128 + f * 32 + 16 + r16] = e_re;
+        E[nfr * 32 + f * 32 + r16] = e_im;
+        E[nfr * 32 + f * 32 + 16 + r16] = e_re;
     }
     if (4 * w >= kSlab * ks) return;
-    const int64_t slice = (int64_t)4 * ks * kFragBytes, tensor = (int64_t)s * slice;
+    const int64_t slice = (int64_t)nfr * ks * kFragBytes, tensor = (int64_t)s * slice;
     Fixed xr[4], xi[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -95,62 +96,74 @@ __global__ __launch_bounds__(256) void gate_split_kernel(const double* __restric
 }
 
 // ---------------------------------------------------------------------------- the product
-template <int S, int KS>   // slices; steps of 32 positions of k
+// S slices; KS steps of 32 positions of k; RF row fragments per tile: 2 (tiles of 64 rows, wavefronts 2 x 2, four
+// fragments of B) with KS <= 2, or 1 (32 rows, wavefronts 1 x 4, eight fragments of B) with KS = 4.
+template <int S, int KS, int RF>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void gate_kernel(const GateArgs g) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    constexpr int SLICE = KS * 2 * kFragBytes;   // one slice of one plane of the tile's rows: [step][row fragment]
+    constexpr int ROWS = 32 * RF;                 // rows of Z per workgroup
+    constexpr int NFR = RF == 2 ? 4 : 8;          // fragments of 16 columns of B
+    constexpr int SLICE = KS * RF * kFragBytes;   // one slice of one plane of the tile's rows: [step][row fragment]
     constexpr int PLANE = S * SLICE;
-    // behind the two planes: exponents of the 64 rows, [plane][64], then the 256 exponents of the gate's fragments
+    // behind the two planes: exponents of the tile's rows, [plane][ROWS], then those of the gate's fragments, [tensor][NFR][32]
     int* ex = reinterpret_cast<int*>(lds + 2 * PLANE);
+    int* ex_gate = ex + 2 * ROWS;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t row_tile = (int64_t)blockIdx.x * kGateRows;
+    const int64_t row_tile = (int64_t)blockIdx.x * ROWS;
 
-    // ---- this wavefront's patches: rows 32 wm .. + 31, complex columns 16 f .. 16 f + 15 for f = 2 wn, 2 wn + 1
-    const int wm = wave >> 1, wn = wave & 1;
+    // ---- this wavefront's patches: rows 32 wm .. + 31 of the tile, complex columns 16 f .. 16 f + 15 for f = f0, f0 + 1
+    const int wm = RF == 2 ? wave >> 1 : 0, f0 = RF == 2 ? 2 * (wave & 1) : 2 * wave;
     const int rr = lane & 31, half = lane >> 5;
     // MFMA operand: lane holds row (lane % 32), bytes 16 (lane / 32) .. + 16 of the 32-byte fragment row
     const unsigned rd_lane = (unsigned)(rr * 32 + ((half ^ ((rr >> 3) & 1)) << 4));
     const unsigned char* a_rd = lds + wm * kFragBytes + rd_lane;
-    constexpr int BSLICE = 4 * KS * kFragBytes, TENSOR = S * BSLICE;
+    constexpr int BSLICE = NFR * KS * kFragBytes, TENSOR = S * BSLICE;
     auto read_a = [&](int plane, int p, int step) __attribute__((always_inline)) -> v4i {
-        return *reinterpret_cast<const v4i*>(a_rd + plane * PLANE + p * SLICE + step * 2 * kFragBytes);
+        return *reinterpret_cast<const v4i*>(a_rd + plane * PLANE + p * SLICE + step * RF * kFragBytes);
     };
     auto load_b = [&](int t, int f, int q, int step) __attribute__((always_inline)) -> v4i {
         return *reinterpret_cast<const v4i*>(g.T + t * TENSOR + q * BSLICE + (f * KS + step) * kFragBytes + rd_lane);
     };
     // the gate's fragments of the first walk are requested before anything else: they are on their way while Z is split
     v4i b[S];
-    static_for<0, S>([&](auto pc) __attribute__((always_inline)) { b[decltype(pc)::value] = load_b(0, 2 * wn, decltype(pc)::value, 0); });
+    static_for<0, S>([&](auto pc) __attribute__((always_inline)) { b[decltype(pc)::value] = load_b(0, f0, decltype(pc)::value, 0); });
 
-    // ---- the rows of Z -> exponents and slices in LDS. Sixteen lanes work on a row, a lane owns four
-    // consecutive complex elements; a wavefront takes sixteen rows, four at a time.
+    // ---- the rows of Z -> exponents and slices in LDS. Sixteen lanes work on a row; a lane owns W words of four
+    // consecutive complex elements of it (words c16 and, with four steps, 16 + c16); a wavefront takes a quarter of the
+    // tile's rows, four at a time: sixteen complex elements per lane in every shape.
     {
+        constexpr int W = KS > 2 ? 2 : 1, G = ROWS / 16;   // words per lane and row; groups of four rows per wavefront
+        static_assert(G * W == 4, "sixteen complex elements per lane");
         const int r4 = lane >> 4, c16 = lane & 15;
-        ex[128 + tid] = g.E[tid];
-        ulonglong2 v[4][4];
+        for (int i = tid; i < 2 * NFR * 32; i += 256) ex_gate[i] = g.E[i];
+        ulonglong2 v[G][W][4];
 #pragma unroll
-        for (int gi = 0; gi < 4; ++gi) {
-            const int64_t row = row_tile + wave * 16 + gi * 4 + r4;
+        for (int gi = 0; gi < G; ++gi) {
+            const int64_t row = row_tile + wave * (4 * G) + gi * 4 + r4;
             const bool live = row < g.m;
             const ulonglong2* src = reinterpret_cast<const ulonglong2*>(g.Z) + (live ? row : 0) * g.ldz;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int l = c16 * 4 + u;
-                v[gi][u] = ulonglong2{0ull, 0ull};
-                if (live && l < g.k) v[gi][u] = src[l];
-            }
+            for (int j = 0; j < W; ++j)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int l = (c16 + 16 * j) * 4 + u;
+                    v[gi][j][u] = ulonglong2{0ull, 0ull};
+                    if (live && l < g.k) v[gi][j][u] = src[l];
+                }
         }
 #pragma unroll
-        for (int gi = 0; gi < 4; ++gi) {
+        for (int gi = 0; gi < G; ++gi) {
             unsigned long long mx_re = 0, mx_im = 0;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const unsigned long long a = v[gi][u].x & kAbsMask, b = v[gi][u].y & kAbsMask;
-                mx_re = a > mx_re ? a : mx_re;
-                mx_im = b > mx_im ? b : mx_im;
-            }
+            for (int j = 0; j < W; ++j)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const unsigned long long a = v[gi][j][u].x & kAbsMask, b2 = v[gi][j][u].y & kAbsMask;
+                    mx_re = a > mx_re ? a : mx_re;
+                    mx_im = b2 > mx_im ? b2 : mx_im;
+                }
 #pragma unroll
             for (int off = 8; off >= 1; off >>= 1) {
                 const unsigned long long o = __shfl_xor(mx_re, off, 64), q = __shfl_xor(mx_im, off, 64);
@@ -158,31 +171,35 @@ void gate_kernel(const GateArgs g) {
                 mx_im = q > mx_im ? q : mx_im;
             }
             const int e_re = exponent_of_max(mx_re), e_im = exponent_of_max(mx_im);
-            const int lrow = wave * 16 + gi * 4 + r4;
+            const int lrow = wave * (4 * G) + gi * 4 + r4;
             if (c16 == 0) {
                 ex[lrow] = e_re;
-                ex[64 + lrow] = e_im;
+                ex[ROWS + lrow] = e_im;
             }
-            if (c16 * 4 < kSlab * KS) {   // (a one-step product has no second fragment to fill)
-                Fixed xr[4], xi[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    xr[u] = to_fixed<false>(v[gi][u].x, e_re);
-                    xi[u] = to_fixed<false>(v[gi][u].y, e_im);
+            for (int j = 0; j < W; ++j) {
+                const int word = c16 + 16 * j;
+                if (word * 4 < kSlab * KS) {   // (a one-step product has no second fragment to fill)
+                    Fixed xr[4], xi[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        xr[u] = to_fixed<false>(v[gi][j][u].x, e_re);
+                        xi[u] = to_fixed<false>(v[gi][j][u].y, e_im);
+                    }
+                    const SignMask sr = sign_mask(v[gi][j][0].x, v[gi][j][1].x, v[gi][j][2].x, v[gi][j][3].x);
+                    const SignMask si = sign_mask(v[gi][j][0].y, v[gi][j][1].y, v[gi][j][2].y, v[gi][j][3].y);
+                    // the fragment layout of the slice tensors: rows of 32 bytes, their two halves swapped in rows 8..15 and 24..31
+                    const int fr = lrow & 31, l0 = (word & 7) * 4;
+                    unsigned char* dst = lds + ((word >> 3) * RF + (lrow >> 5)) * kFragBytes + fr * kSlab +
+                                         ((((l0 >> 4) ^ (fr >> 3)) & 1) << 4) + (l0 & 15);
+                    static_for<1, S + 1>([&](auto pc) __attribute__((always_inline)) {
+                        constexpr int p = decltype(pc)::value;
+                        *reinterpret_cast<uint32_t*>(dst + (p - 1) * SLICE) = packed_slice<false>(xr, sr, p);
+                        *reinterpret_cast<uint32_t*>(dst + PLANE + (p - 1) * SLICE) = packed_slice<false>(xi, si, p);
+                    });
                 }
-                const SignMask sr = sign_mask(v[gi][0].x, v[gi][1].x, v[gi][2].x, v[gi][3].x);
-                const SignMask si = sign_mask(v[gi][0].y, v[gi][1].y, v[gi][2].y, v[gi][3].y);
-                // the fragment layout of the slice tensors: rows of 32 bytes, their two halves swapped in rows 8..15 and 24..31
-                const int rr = lrow & 31, l0 = (c16 & 7) * 4;
-                unsigned char* dst = lds + ((c16 >> 3) * 2 + (lrow >> 5)) * kFragBytes + rr * kSlab +
-                                     ((((l0 >> 4) ^ (rr >> 3)) & 1) << 4) + (l0 & 15);
-                static_for<1, S + 1>([&](auto pc) __attribute__((always_inline)) {
-                    constexpr int p = decltype(pc)::value;
-                    *reinterpret_cast<uint32_t*>(dst + (p - 1) * SLICE) = packed_slice<false>(xr, sr, p);
-                    *reinterpret_cast<uint32_t*>(dst + PLANE + (p - 1) * SLICE) = packed_slice<false>(xi, si, p);
-                });
+                __builtin_amdgcn_sched_barrier(0);   // one word's temporaries at a time
             }
-            __builtin_amdgcn_sched_barrier(0);   // one group's temporaries at a time
         }
     }
     __syncthreads();
@@ -191,7 +208,7 @@ void gate_kernel(const GateArgs g) {
     // accumulator layout of the 32x32 MFMA: lane holds column (lane % 32); register u holds row 8 (u / 4) + 4 (lane / 32) + u % 4
     const int lrow0 = wm * 32 + 4 * half;
     // patches of this wavefront that hold a column of C at all (wave-uniform)
-    const int nf = g.n > (2 * wn + 1) * 16 ? 2 : g.n > 2 * wn * 16 ? 1 : 0;
+    const int nf = g.n > (f0 + 1) * 16 ? 2 : g.n > f0 * 16 ? 1 : 0;
     if (nf == 0) return;
 
     v16i acc[S];
@@ -199,9 +216,9 @@ void gate_kernel(const GateArgs g) {
     double part[16];
     // iteration it: patch it / 2, pass it % 2 (0: Ar with T1, 1: Ai with T2)
     for (int it = 0; it < 2 * nf; ++it) {
-        const int pass = it & 1, f = 2 * wn + (it >> 1);
+        const int pass = it & 1, f = f0 + (it >> 1);
         const int nit = it + 1 < 2 * nf ? it + 1 : 0;   // (after the last one the first one's fragments again, unused)
-        const int npass = nit & 1, nfr = 2 * wn + (nit >> 1);
+        const int npass = nit & 1, nfr = f0 + (nit >> 1);
         static_for<0, S>([&](auto pc) __attribute__((always_inline)) { a[decltype(pc)::value] = read_a(pass, decltype(pc)::value, 0); });
         __builtin_amdgcn_sched_barrier(0);
         // Group q of a step = the MFMAs of B fragment q with the A fragments S - 1 - q .. 0, each into the sum of
@@ -240,8 +257,8 @@ void gate_kernel(const GateArgs g) {
             __builtin_amdgcn_sched_barrier(0);   // one diagonal's temporaries at a time
         }
         // ... times 2^(EA_i + EB_j)
-        const int* exa = ex + pass * 64 + lrow0;
-        const int eb = ex[128 + pass * 128 + f * 32 + rr];
+        const int* exa = ex + pass * ROWS + lrow0;
+        const int eb = ex_gate[pass * (NFR * 32) + f * 32 + rr];
 #pragma unroll
         for (int u4 = 0; u4 < 4; ++u4) {
             const v4i ea = *reinterpret_cast<const v4i*>(exa + 8 * u4);   // four consecutive rows
@@ -281,37 +298,57 @@ void gate_kernel(const GateArgs g) {
     }
 }
 
-template <int S, int KS>
+template <int S, int KS, int RF>
 hipError_t launch_gate(const GateArgs& g, hipStream_t st) {
-    constexpr int lds = 2 * S * KS * 2 * kFragBytes + (2 * 64 + 256) * (int)sizeof(int);
+    constexpr int rows = 32 * RF, nfr = RF == 2 ? 4 : 8;
+    constexpr int lds = 2 * S * KS * RF * kFragBytes + (2 * rows + 2 * nfr * 32) * (int)sizeof(int);
     static_assert(2 * lds <= 160 * 1024, "two workgroups per compute unit");
-    hipError_t e = allow_dynamic_lds<&gate_kernel<S, KS>>(lds);
+    hipError_t e = allow_dynamic_lds<&gate_kernel<S, KS, RF>>(lds);
     if (e != hipSuccess) return e;
-    const unsigned grid = (unsigned)((g.m + kGateRows - 1) / kGateRows);
-    gate_kernel<S, KS><<<dim3(grid), dim3(256), lds, st>>>(g);
+    const unsigned grid = (unsigned)((g.m + rows - 1) / rows);
+    gate_kernel<S, KS, RF><<<dim3(grid), dim3(256), lds, st>>>(g);
     return hipGetLastError();
 }
+
+// steps and fragments of a gate shape
+inline int gate_steps(int64_t k, int64_t n) { return k > kGateSmall || n > kGateSmall ? 4 : k > kSlab ? 2 : 1; }
+inline int gate_fragments(int64_t k, int64_t n) { return k > kGateSmall || n > kGateSmall ? 8 : 4; }
 
 }  // namespace
 
 bool gate_product_applies(const double* Z, const double* B, const double* Cz, int64_t n, int64_t k, int s) {
-    return n >= 1 && n <= kGateCols && k >= 1 && k <= kGateCols && s <= kBand && reinterpret_cast<uintptr_t>(Z) % 16 == 0 &&
+    return n >= 1 && n <= kGateLarge && k >= 1 && k <= kGateLarge && s <= kBand && reinterpret_cast<uintptr_t>(Z) % 16 == 0 &&
            reinterpret_cast<uintptr_t>(B) % 16 == 0 && reinterpret_cast<uintptr_t>(Cz) % 16 == 0;
 }
 
-size_t gate_tensor_bytes(int64_t k, int s) { return (size_t)2 * s * 4 * (k > kSlab ? 2 : 1) * kFragBytes; }
-
-hipError_t launch_gate_split(const double* B, int64_t ldb, int64_t k, int64_t n, int s, int8_t* T, int32_t* E, hipStream_t st) {
-    gate_split_kernel<<<dim3(4), dim3(256), 0, st>>>(B, ldb, (int)k, (int)n, s, k > kSlab ? 2 : 1, T, E);
-    return hipGetLastError();
+size_t gate_scratch_bytes(int64_t n, int64_t k, int s) {
+    if (n < 1 || n > kGateLarge || k < 1 || k > kGateLarge || s > kBand) return 0;
+    const size_t nfr = (size_t)gate_fragments(k, n);
+    return 2 * nfr * 32 * sizeof(int32_t) + (size_t)2 * s * nfr * gate_steps(k, n) * kFragBytes;
 }
 
-hipError_t launch_gate_product(const GateArgs& g, int s, hipStream_t st) {
-    if (g.m <= 0) return hipSuccess;
-    if (g.n < 1 || g.n > kGateCols || g.k < 1 || g.k > kGateCols) return hipErrorInvalidValue;
-    const int ks = g.k > kSlab ? 2 : 1;
+hipError_t launch_gate_product(const double* Z, int64_t ldz, int64_t m, int64_t k, int64_t n, const double* B, int64_t ldb,
+                               int s, void* scratch, double* Cz, int64_t ldcz, hipStream_t st) {
+    if (m <= 0) return hipSuccess;
+    if (!gate_product_applies(Z, B, Cz, n, k, s) || s < 1) return hipErrorInvalidValue;
+    const int ks = gate_steps(k, n), nfr = gate_fragments(k, n);
+    int32_t* E = static_cast<int32_t*>(scratch);
+    int8_t* T = reinterpret_cast<int8_t*>(E + 2 * nfr * 32);
+    gate_split_kernel<<<dim3(nfr), dim3(ks == 4 ? 512 : 256), 0, st>>>(B, ldb, (int)k, (int)n, s, ks, nfr, T, E);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    GateArgs g{};
+    g.Z = Z;
+    g.ldz = ldz;
+    g.m = m;
+    g.k = (int)k;
+    g.n = (int)n;
+    g.T = T;
+    g.E = E;
+    g.Cz = Cz;
+    g.ldcz = ldcz;
     switch (s) {
-#define OZ_CASE(S_) case S_: return ks == 2 ? launch_gate<S_, 2>(g, st) : launch_gate<S_, 1>(g, st);
+#define OZ_CASE(S_) case S_: return ks == 4 ? launch_gate<S_, 4, 1>(g, st) : ks == 2 ? launch_gate<S_, 2, 2>(g, st) : launch_gate<S_, 1, 2>(g, st);
         OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8)
 #undef OZ_CASE
     }

@@ -68,25 +68,26 @@ struct GemmArgs {
 };
 
 // Arguments of the one-kernel complex product with a short inner dimension and few columns (a gate applied to
-// a state vector, Section 4.4): Z is split inside the kernel, the small operand arrives as the two slice tensors
-// and exponent sets that launch_gate_split makes of it.
+// a state vector, Section 4.4): Z is split inside the kernel, the small operand arrives as two slice tensors
+// and exponent sets (gate.hip).
 struct GateArgs {
     const double* Z;         // m x k complex elements, interleaved (re, im), 16-byte aligned
     int64_t ldz;             // in complex elements
     int64_t m;
-    int k, n;                // 1 .. 64 each
-    const int8_t* T;         // gate_tensor_bytes(k, s) bytes
-    const int32_t* E;        // 256 exponents
+    int k, n;                // 1 .. 128 each
+    const int8_t* T;         // the gate's two slice tensors
+    const int32_t* E;        // and their exponents
     double* Cz;              // m x n complex elements, interleaved, 16-byte aligned
     int64_t ldcz;            // in complex elements
 };
 // Whether that kernel serves a complex product Z (m x k) times B (k x n) -> Cz with s slices.
 bool gate_product_applies(const double* Z, const double* B, const double* Cz, int64_t n, int64_t k, int s);
-size_t gate_tensor_bytes(int64_t k, int s);
-// B: k x n complex elements, leading dimension ldb in complex elements -> T, E (device memory, 16-byte aligned).
-hipError_t launch_gate_split(const double* B, int64_t ldb, int64_t k, int64_t n, int s, int8_t* T, int32_t* E,
-                             hipStream_t st);
-hipError_t launch_gate_product(const GateArgs& args, int s, hipStream_t st);
+// Device scratch it needs for the gate's slices and exponents (0 if the shape is never served).
+size_t gate_scratch_bytes(int64_t n, int64_t k, int s);
+// Cz = Z . B: splits B (k x n complex elements, leading dimension ldb in complex elements) into `scratch`
+// (16-byte aligned, gate_scratch_bytes), then the product kernel. Only where gate_product_applies.
+hipError_t launch_gate_product(const double* Z, int64_t ldz, int64_t m, int64_t k, int64_t n, const double* B, int64_t ldb,
+                               int s, void* scratch, double* Cz, int64_t ldcz, hipStream_t st);
 
 // negate: emit the slices of -A (-B) instead: same exponents, every slice with the opposite sign
 // (how a conjugated operand's imaginary plane is split)

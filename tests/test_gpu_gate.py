@@ -1,7 +1,8 @@
 """GPU parity of the one-kernel complex product for a small gate on a tall state (Section 4.4: a d-qubit gate on an
 N-qubit state vector is the complex product 2^(N-d) x 2^d x 2^d). ozimmu_zgemm takes that path when k and n are
-at most 64 and at most eight slices are asked for; the state is then split inside the product kernel. Compared bit
-for bit with the oracle, which splits first and multiplies afterwards."""
+at most 128 and at most eight slices are asked for; the state is then split inside the product kernel (tiles of 64
+rows and up to two steps while k and n are at most 64, tiles of 32 rows and four steps beyond). Compared bit for bit
+with the oracle, which splits first and multiplies afterwards."""
 import numpy as np
 import pytest
 import torch
@@ -49,6 +50,25 @@ def test_gate_every_slice_count(s, k):
     assert_same(gpu_zgemm(A, B, s), oracle.zgemm(A, B, s))
 
 
+@pytest.mark.parametrize("s", range(1, 9))
+def test_gate_every_slice_count_four_steps(s):
+    """The instantiations for k or n above 64: five row tiles of 32 with a ragged last one, eight fragments of B."""
+    m, n, k = 150, 128, 128
+    A = wl.gaussian_complex(m, k, seed=300 + s)
+    B = wl.unit_column_complex(k, n, seed=400 + s)
+    assert_same(gpu_zgemm(A, B, s), oracle.zgemm(A, B, s))
+
+
+@pytest.mark.parametrize("m,n,k,s", [(33, 128, 65, 8), (100, 65, 64, 7), (31, 70, 20, 3), (97, 113, 127, 6), (64, 128, 1, 2),
+                                     (200, 81, 100, 8)])
+def test_gate_ragged_shapes_four_steps(m, n, k, s):
+    """k or n between 65 and 128 (k short of the four steps is padded with zero slices; fragments past the last
+    column are skipped)."""
+    A = wl.gaussian_complex(m, k, seed=m + k)
+    B = wl.unit_column_complex(k, n, seed=n + k + 1)
+    assert_same(gpu_zgemm(A, B, s, lda_extra=1, ldb_extra=2, ldc_extra=3), oracle.zgemm(A, B, s))
+
+
 @pytest.mark.parametrize("m,n,k,s", [(1, 1, 1, 3), (64, 64, 64, 8), (65, 63, 33, 7), (63, 17, 31, 5), (130, 16, 64, 8),
                                      (200, 15, 17, 2), (31, 33, 1, 4), (300, 48, 40, 6), (129, 32, 32, 8), (64, 49, 64, 1)])
 def test_gate_ragged_shapes(m, n, k, s):
@@ -81,6 +101,21 @@ def test_gate_purely_real_and_purely_imaginary_operands():
     for Ax, Bx in ((A.real + 0j, B.real + 0j), (1j * A.imag, 1j * B.imag), (A.real + 0j, 1j * B.imag), (1j * A.imag, B.real + 0j)):
         got = gpu_zgemm(np.ascontiguousarray(Ax), np.ascontiguousarray(Bx), 6)
         assert_same(got, oracle.zgemm(Ax, Bx, 6))
+
+
+def test_seven_qubit_gate_sampled_rows():
+    """A 7-qubit gate on 20 qubits (8192 x 128 x 128), rows sampled over the whole state."""
+    m, k, s = 1 << 13, 128, 8
+    A = wl.gaussian_complex_device(m, k, seed=16)
+    A = A / A.abs().pow(2).sum().sqrt()
+    U = wl.haar_unitary_device(k, seed=17).contiguous()
+    C = torch.empty((m, k), dtype=torch.complex128, device=DEV)
+    ozimmu.zgemm(A, U, C, s, ozimmu.alloc_workspace(m, k, k, s, is_complex=True))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(18)
+    rows = np.unique(np.concatenate([[0, 31, 32, m - 32, m - 1], rng.integers(0, m, 100)]))
+    idx = torch.from_numpy(rows).to(DEV)
+    assert_same(C[idx].cpu().numpy(), oracle.zgemm(A[idx].cpu().numpy(), U.cpu().numpy(), s))
 
 
 def test_more_than_eight_slices_take_the_general_path():
