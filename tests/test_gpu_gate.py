@@ -1,8 +1,8 @@
 """GPU parity of the one-kernel complex product for a small gate on a tall state (Section 4.4: a d-qubit gate on an
 N-qubit state vector is the complex product 2^(N-d) x 2^d x 2^d). ozimmu_zgemm takes that path when k and n are
-at most 128 and at most eight slices are asked for; the state is then split inside the product kernel (tiles of 64
-rows and up to two steps while k and n are at most 64, tiles of 32 rows and four steps beyond). Compared bit for bit
-with the oracle, which splits first and multiplies afterwards."""
+at most 128 and at most eight slices are asked for; the state is then split inside the product kernel (tiles of 32
+rows; one step of 64 positions and eight fragments of the gate while k and n are at most 64, two steps and sixteen
+fragments beyond). Compared bit for bit with the oracle, which splits first and multiplies afterwards."""
 import numpy as np
 import pytest
 import torch
@@ -43,7 +43,7 @@ def assert_same(got, want):
 @pytest.mark.parametrize("s", range(1, 9))
 @pytest.mark.parametrize("k", [32, 64])
 def test_gate_every_slice_count(s, k):
-    """Every kernel instantiation (slices x steps), three row tiles with a ragged last one."""
+    """Every slice count of the kernel for k, n <= 64, with half a step and a whole one; five row tiles with a ragged last one."""
     m, n = 150, 64
     A = wl.gaussian_complex(m, k, seed=100 + s)
     B = wl.unit_column_complex(k, n, seed=200 + s)
@@ -51,8 +51,8 @@ def test_gate_every_slice_count(s, k):
 
 
 @pytest.mark.parametrize("s", range(1, 9))
-def test_gate_every_slice_count_four_steps(s):
-    """The instantiations for k or n above 64: five row tiles of 32 with a ragged last one, eight fragments of B."""
+def test_gate_every_slice_count_two_steps(s):
+    """The instantiations for k or n above 64: five row tiles of 32 with a ragged last one, sixteen fragments of B."""
     m, n, k = 150, 128, 128
     A = wl.gaussian_complex(m, k, seed=300 + s)
     B = wl.unit_column_complex(k, n, seed=400 + s)
@@ -61,8 +61,8 @@ def test_gate_every_slice_count_four_steps(s):
 
 @pytest.mark.parametrize("m,n,k,s", [(33, 128, 65, 8), (100, 65, 64, 7), (31, 70, 20, 3), (97, 113, 127, 6), (64, 128, 1, 2),
                                      (200, 81, 100, 8)])
-def test_gate_ragged_shapes_four_steps(m, n, k, s):
-    """k or n between 65 and 128 (k short of the four steps is padded with zero slices; fragments past the last
+def test_gate_ragged_shapes_two_steps(m, n, k, s):
+    """k or n between 65 and 128 (k short of the two steps is padded with zero slices; fragments past the last
     column are skipped)."""
     A = wl.gaussian_complex(m, k, seed=m + k)
     B = wl.unit_column_complex(k, n, seed=n + k + 1)
@@ -72,8 +72,8 @@ def test_gate_ragged_shapes_four_steps(m, n, k, s):
 @pytest.mark.parametrize("m,n,k,s", [(1, 1, 1, 3), (64, 64, 64, 8), (65, 63, 33, 7), (63, 17, 31, 5), (130, 16, 64, 8),
                                      (200, 15, 17, 2), (31, 33, 1, 4), (300, 48, 40, 6), (129, 32, 32, 8), (64, 49, 64, 1)])
 def test_gate_ragged_shapes(m, n, k, s):
-    """Rows, columns and inner dimension on both sides of every boundary the kernel has: 64 rows per workgroup,
-    16 columns per patch (patches past the last column are skipped), 32 positions per step."""
+    """Rows, columns and inner dimension on both sides of the boundaries the kernel has: 32 rows per workgroup, 16 per
+    wavefront, 8 columns per patch (patches past the last column are skipped), 64 positions per step."""
     A = wl.gaussian_complex(m, k, seed=m + k)
     B = wl.unit_column_complex(k, n, seed=n + k + 1)
     assert_same(gpu_zgemm(A, B, s), oracle.zgemm(A, B, s))
@@ -135,7 +135,7 @@ def test_gate_on_a_long_state_sampled_rows():
     ozimmu.zgemm(A, U, C, s, ozimmu.alloc_workspace(m, k, k, s, is_complex=True))
     torch.cuda.synchronize()
     rng = np.random.default_rng(15)
-    rows = np.unique(np.concatenate([[0, 63, 64, m - 64, m - 1], rng.integers(0, m, 200)]))
+    rows = np.unique(np.concatenate([[0, 31, 32, 63, 64, m - 32, m - 1], rng.integers(0, m, 200)]))
     idx = torch.from_numpy(rows).to(DEV)
     want = oracle.zgemm(A[idx].cpu().numpy(), U.cpu().numpy(), s)
     assert_same(C[idx].cpu().numpy(), want)
