@@ -117,7 +117,7 @@ def bench_complex(args, m, n, k, s, statevec=None):
                      "achieved": int8_ops / sec / 1e12, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": int8_ops / sec / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": None},
     }
-    if k <= 128 and n <= 128 and s <= 8:
+    if k <= 128 and n <= 128:
         # a small gate on a tall state runs as one kernel that reads the state once and writes the result once
         # (gate_kernel; the gate's own split is a few microseconds): the memory traffic of the state bounds it
         hbm_bytes = 16.0 * m * (k + n)

@@ -136,8 +136,8 @@ ozimmu_status_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_
  * ozimmu_zgemm: A, B, C hold interleaved (re, im) doubles (Section 4.4: the real and
  * imaginary parts are separated while splitting; four real products, each plane with its own
  * exponents; Cr = RN(G(Ar,Br) - G(Ai,Bi)), Ci = RN(G(Ar,Bi) + G(Ai,Br))).
- * With k <= 128, n <= 128 and num_slices <= 8 (a gate of up to seven qubits applied to a state
- * vector) and A, B, C 16-byte aligned, A is split inside the product kernel and read once; the
+ * With k <= 128 and n <= 128 (a gate of up to seven qubits applied to a state vector) and A, B, C
+ * 16-byte aligned, A is split inside the product kernel and read once; the
  * result is the same bit for bit, and of the workspace only the part set aside for B's slices is used.
  */
 ozimmu_status_t ozimmu_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,

@@ -1,5 +1,5 @@
 // A gate on a state vector (Section 4.4): the complex product of a tall operand Z (m x k, the reshaped state,
-// interleaved re/im) with a small one (B: k x n, the gate), k and n at most 128, up to eight slices, in ONE kernel
+// interleaved re/im) with a small one (B: k x n, the gate), k and n at most 128, any slice count, in ONE kernel
 // that reads Z once and writes the result once.
 //
 // With so short an inner dimension the product is bound by the memory traffic of the state and by the vector
@@ -22,7 +22,8 @@
 // Why the small MFMA shape: a wavefront issues vector instructions at half the rate its SIMD can take them, and
 // with the 32 x 32 shape the eight resident diagonals of a patch cost 128 registers, which leaves room for two
 // wavefronts per SIMD only: whenever one of them waited for memory or for the matrix core, the vector pipeline ran
-// at half speed. With 16 x 16 patches (32 registers for the diagonals) four wavefronts fit a SIMD.
+// at half speed. With 16 x 16 patches (32 registers for the diagonals) four wavefronts fit a SIMD; beyond eight
+// slices (up to 64 registers for the diagonals and as many again for the fragments) two.
 // Register allocation is left to the compiler: without accumulation-register operands in inline assembly the MFMA
 // results land in ordinary vector registers, where the FP64 fold reads them directly, and a product's first MFMA
 // per diagonal takes the constant 0 as its addend instead of cleared registers.
@@ -69,6 +70,7 @@ __device__ __forceinline__ v4acc mfma16(const v4i& a, const v4i& b, const v4acc&
 // One workgroup per fragment f (8 columns of B). Thread (c, w) = (tid % 8, tid / 8) owns column 8 f + c and the four
 // positions 4 w .. 4 w + 3 of k. T: tensor t at t * s * nfr * ks KiB, slice q at q * nfr * ks KiB, fragment (f, step)
 // at (f ks + step) KiB. E: [t][f][16] exponents of the fragments' rows.
+template <bool WIDE>   // more than nine slices: the fraction takes both words of the fixed-point value
 __global__ __launch_bounds__(256) void gate_split_kernel(const double* __restrict__ B, int64_t ldb, int k, int n, int s,
                                                          int ks, int nfr, int8_t* __restrict__ T, int32_t* __restrict__ E) {
     const int tid = threadIdx.x, r8 = tid & 7, w = tid >> 3, f = blockIdx.x, c = f * 8 + r8;
@@ -105,8 +107,8 @@ __global__ __launch_bounds__(256) void gate_split_kernel(const double* __restric
     Fixed xr[4], xi[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-        xr[u] = to_fixed<false>(v[u].x, e_re);
-        xi[u] = to_fixed<false>(v[u].y, e_im);
+        xr[u] = to_fixed<WIDE>(v[u].x, e_re);
+        xi[u] = to_fixed<WIDE>(v[u].y, e_im);
     }
     const SignMask sr = sign_mask(v[0].x, v[1].x, v[2].x, v[3].x);
     const SignMask si = sign_mask(v[0].y, v[1].y, v[2].y, v[3].y);
@@ -114,9 +116,9 @@ __global__ __launch_bounds__(256) void gate_split_kernel(const double* __restric
     const int64_t lo = (int64_t)(f * ks + step) * kFragBytes + frag_offset(r8, ll);       // first plane of the fragment
     const int64_t hi = (int64_t)(f * ks + step) * kFragBytes + frag_offset(8 + r8, ll);   // second plane
 #pragma unroll
-    for (int p = 1; p <= kBand; ++p) {
+    for (int p = 1; p <= (WIDE ? OZIMMU_MAX_SLICES : 9); ++p) {
         if (p <= s) {
-            const uint32_t pr = packed_slice<false>(xr, sr, p), pi = packed_slice<false>(xi, si, p);
+            const uint32_t pr = packed_slice<WIDE>(xr, sr, p), pi = packed_slice<WIDE>(xi, si, p);
             int8_t* d = T + (p - 1) * slice;
             *reinterpret_cast<uint32_t*>(d + lo) = pr;
             *reinterpret_cast<uint32_t*>(d + hi) = pi;
@@ -129,8 +131,9 @@ __global__ __launch_bounds__(256) void gate_split_kernel(const double* __restric
 // ---------------------------------------------------------------------------- the product
 // S slices; BIG: k or n above 64 (two steps of 64 positions and sixteen fragments of B instead of one and eight).
 template <int S, bool BIG>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4)))
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(S <= kBand ? 4 : 2, S <= kBand ? 4 : 2)))
 void gate_kernel(const GateArgs g) {
+    constexpr bool WIDE = S > 9;   // the slices beyond the ninth come from the lower word of the fixed-point fraction
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int KS = BIG ? 2 : 1, NFR = BIG ? 16 : 8;
     constexpr int SLICE = KS * 2 * kFragBytes;   // one slice of one plane of the tile's rows: [step][row fragment]
@@ -227,12 +230,12 @@ void gate_kernel(const GateArgs g) {
                 Fixed xr[4], xi[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    if constexpr (decltype(normal_tag)::value) {
+                    if constexpr (decltype(normal_tag)::value && S <= kBand) {
                         xr[u] = to_fixed_upper(v[j][u].x, e_re);
                         xi[u] = to_fixed_upper(v[j][u].y, e_im);
                     } else {
-                        xr[u] = to_fixed<false>(v[j][u].x, e_re);
-                        xi[u] = to_fixed<false>(v[j][u].y, e_im);
+                        xr[u] = to_fixed<WIDE>(v[j][u].x, e_re);
+                        xi[u] = to_fixed<WIDE>(v[j][u].y, e_im);
                     }
                 }
                 const SignMask sr = sign_mask(v[j][0].x, v[j][1].x, v[j][2].x, v[j][3].x);
@@ -240,8 +243,8 @@ void gate_kernel(const GateArgs g) {
                 unsigned char* dst = lds + (j * 2 + (lrow >> 4)) * kFragBytes + frag_offset(lrow & 15, c16 * 4);
                 static_for<1, S + 1>([&](auto pc) __attribute__((always_inline)) {
                     constexpr int p = decltype(pc)::value;
-                    *reinterpret_cast<uint32_t*>(dst + (p - 1) * SLICE) = packed_slice<false>(xr, sr, p);
-                    *reinterpret_cast<uint32_t*>(dst + PLANE + (p - 1) * SLICE) = packed_slice<false>(xi, si, p);
+                    *reinterpret_cast<uint32_t*>(dst + (p - 1) * SLICE) = packed_slice<WIDE>(xr, sr, p);
+                    *reinterpret_cast<uint32_t*>(dst + PLANE + (p - 1) * SLICE) = packed_slice<WIDE>(xi, si, p);
                 });
                 __builtin_amdgcn_sched_barrier(0);   // one word's temporaries at a time
             }
@@ -343,7 +346,7 @@ void gate_kernel(const GateArgs g) {
 template <int S, bool BIG>
 hipError_t launch_gate(const GateArgs& g, hipStream_t st) {
     constexpr int lds = 2 * S * (BIG ? 2 : 1) * 2 * kFragBytes + (2 * kGateRows + 2 * (BIG ? 16 : 8) * 16) * (int)sizeof(int);
-    static_assert(2 * lds <= 160 * 1024, "two workgroups per compute unit");
+    static_assert(lds <= 160 * 1024 && (S > kBand || 2 * lds <= 160 * 1024), "the LDS of a compute unit: two workgroups up to eight slices");
     hipError_t e = allow_dynamic_lds<&gate_kernel<S, BIG>>(lds);
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((g.m + kGateRows - 1) / kGateRows);
@@ -356,12 +359,12 @@ inline bool gate_is_big(int64_t k, int64_t n) { return k > 64 || n > 64; }
 }  // namespace
 
 bool gate_product_applies(const double* Z, const double* B, const double* Cz, int64_t n, int64_t k, int s) {
-    return n >= 1 && n <= kGateMax && k >= 1 && k <= kGateMax && s <= kBand && reinterpret_cast<uintptr_t>(Z) % 16 == 0 &&
+    return n >= 1 && n <= kGateMax && k >= 1 && k <= kGateMax && s <= OZIMMU_MAX_SLICES && reinterpret_cast<uintptr_t>(Z) % 16 == 0 &&
            reinterpret_cast<uintptr_t>(B) % 16 == 0 && reinterpret_cast<uintptr_t>(Cz) % 16 == 0;
 }
 
 size_t gate_scratch_bytes(int64_t n, int64_t k, int s) {
-    if (n < 1 || n > kGateMax || k < 1 || k > kGateMax || s > kBand) return 0;
+    if (n < 1 || n > kGateMax || k < 1 || k > kGateMax || s > OZIMMU_MAX_SLICES) return 0;
     const size_t nfr = gate_is_big(k, n) ? 16 : 8, ks = gate_is_big(k, n) ? 2 : 1;
     return 2 * nfr * 16 * sizeof(int32_t) + (size_t)2 * s * nfr * ks * kFragBytes;
 }
@@ -374,7 +377,8 @@ hipError_t launch_gate_product(const double* Z, int64_t ldz, int64_t m, int64_t 
     const int ks = big ? 2 : 1, nfr = big ? 16 : 8;
     int32_t* E = static_cast<int32_t*>(scratch);
     int8_t* T = reinterpret_cast<int8_t*>(E + 2 * nfr * 16);
-    gate_split_kernel<<<dim3(nfr), dim3(256), 0, st>>>(B, ldb, (int)k, (int)n, s, ks, nfr, T, E);
+    if (s > 9) gate_split_kernel<true><<<dim3(nfr), dim3(256), 0, st>>>(B, ldb, (int)k, (int)n, s, ks, nfr, T, E);
+    else gate_split_kernel<false><<<dim3(nfr), dim3(256), 0, st>>>(B, ldb, (int)k, (int)n, s, ks, nfr, T, E);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     GateArgs g{};
@@ -390,6 +394,7 @@ hipError_t launch_gate_product(const double* Z, int64_t ldz, int64_t m, int64_t 
     switch (s) {
 #define OZ_CASE(S_) case S_: return big ? launch_gate<S_, true>(g, st) : launch_gate<S_, false>(g, st);
         OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8)
+        OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16)
 #undef OZ_CASE
     }
     return hipErrorInvalidValue;

@@ -116,11 +116,12 @@ def test_complex_blas_shapes_across_the_kernels(m, n, k, s):
     zrun("N", "C", m, n, k, 1.0, 0.0, s, seed=4)
 
 
-@pytest.mark.parametrize("m,n,k,s", [(64, 1000, 64, 8), (32, 300, 32, 5), (17, 129, 40, 7), (64, 200, 64, 9)])
+@pytest.mark.parametrize("m,n,k,s", [(64, 1000, 64, 8), (32, 300, 32, 5), (17, 129, 40, 7), (64, 200, 64, 9), (128, 300, 100, 8),
+                                     (100, 150, 128, 12)])
 def test_complex_blas_small_gate_on_a_wide_state(m, n, k, s):
-    """Neither operand transposed, A at most 64 x 64, up to eight slices: the state (B, whose columns are the rows of
-    the row-major product) is split inside the product kernel; with a general alpha and beta the update follows as
-    for every other shape. Nine slices take the general path."""
+    """Neither operand transposed, A at most 128 x 128: the state (B, whose columns are the rows of the row-major
+    product) is split inside the product kernel; with a general alpha and beta the update follows as for every other
+    shape."""
     zrun("N", "N", m, n, k, 1.0, 0.0, s, seed=6, c_nan=True)
     zrun("N", "N", m, n, k, 1.0, 0.0, s, seed=7, pad=(3, 2, 5), c_nan=True)
     zrun("N", "N", m, n, k, 0.75 - 0.5j, 0.25 + 1.0j, s, seed=8, pad=(0, 1, 2))

@@ -1,8 +1,8 @@
 """GPU parity of the one-kernel complex product for a small gate on a tall state (Section 4.4: a d-qubit gate on an
 N-qubit state vector is the complex product 2^(N-d) x 2^d x 2^d). ozimmu_zgemm takes that path when k and n are
-at most 128 and at most eight slices are asked for; the state is then split inside the product kernel (tiles of 32
-rows; one step of 64 positions and eight fragments of the gate while k and n are at most 64, two steps and sixteen
-fragments beyond). Compared bit for bit with the oracle, which splits first and multiplies afterwards."""
+at most 128; the state is then split inside the product kernel (tiles of 32 rows; one step of 64 positions and eight
+fragments of the gate while k and n are at most 64, two steps and sixteen fragments beyond; four wavefronts per SIMD up
+to eight slices, two beyond). Compared bit for bit with the oracle, which splits first and multiplies afterwards."""
 import numpy as np
 import pytest
 import torch
@@ -40,7 +40,7 @@ def assert_same(got, want):
     assert np.array_equal(bits(got.imag.copy()), bits(want.imag.copy()))
 
 
-@pytest.mark.parametrize("s", range(1, 9))
+@pytest.mark.parametrize("s", range(1, 17))
 @pytest.mark.parametrize("k", [32, 64])
 def test_gate_every_slice_count(s, k):
     """Every slice count of the kernel for k, n <= 64, with half a step and a whole one; five row tiles with a ragged last one."""
@@ -50,7 +50,7 @@ def test_gate_every_slice_count(s, k):
     assert_same(gpu_zgemm(A, B, s), oracle.zgemm(A, B, s))
 
 
-@pytest.mark.parametrize("s", range(1, 9))
+@pytest.mark.parametrize("s", range(1, 17))
 def test_gate_every_slice_count_two_steps(s):
     """The instantiations for k or n above 64: five row tiles of 32 with a ragged last one, sixteen fragments of B."""
     m, n, k = 150, 128, 128
@@ -118,10 +118,19 @@ def test_seven_qubit_gate_sampled_rows():
     assert_same(C[idx].cpu().numpy(), oracle.zgemm(A[idx].cpu().numpy(), U.cpu().numpy(), s))
 
 
-def test_more_than_eight_slices_take_the_general_path():
+def test_gate_adversarial_values_many_slices():
+    """The wide fixed-point fraction (more than nine slices) on zero rows, powers of two, huge elements, subnormals."""
+    m, n, k = 70, 100, 90
+    A = wl.adversarial_matrix(m, k, seed=21) + 1j * wl.adversarial_matrix(m, k, seed=22)
+    B = wl.adversarial_matrix(k, n, seed=23) + 1j * wl.adversarial_matrix(k, n, seed=24)
+    for s in (10, 13, 16):
+        assert_same(gpu_zgemm(A, B, s), oracle.zgemm(A, B, s))
+
+
+def test_wider_products_take_the_general_path():
     A = wl.gaussian_complex(70, 64, seed=11)
-    B = wl.unit_column_complex(64, 64, seed=12)
-    assert_same(gpu_zgemm(A, B, 11), oracle.zgemm(A, B, 11))
+    B = wl.unit_column_complex(64, 140, seed=12)
+    assert_same(gpu_zgemm(A, B, 8), oracle.zgemm(A, B, 8))
 
 
 def test_gate_on_a_long_state_sampled_rows():
