@@ -41,13 +41,6 @@ constexpr int kGateStep = 64;    // positions of k per MFMA
 // (both operands alike, which is all a sum over k needs); its 16 bytes sit at byte 16 l.
 __device__ __forceinline__ int frag_offset(int row, int pos) { return ((pos >> 4) * 16 + row) * 16 + (pos & 15); }
 
-// max(x, x of the lane N further round the row of 16 lanes): four of them (N = 8, 4, 2, 1) leave the row's maximum in every lane
-template <int N>
-__device__ __forceinline__ unsigned row_max_step(unsigned x) {
-    const unsigned o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x120 + N, 0xf, 0xf, false);
-    return o > x ? o : x;
-}
-
 // to_fixed for a row whose maximum is a normal number (the shift is then never negative) when only the upper 56 bits
 // of the fraction are wanted (eight slices at most): a shift of 64 or more is cut to 63, which leaves nothing there.
 __device__ __forceinline__ Fixed to_fixed_upper(unsigned long long bits, int E) {

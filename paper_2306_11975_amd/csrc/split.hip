@@ -533,6 +533,90 @@ __global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_complex_kernel(c
     loss_flush(acc_im, lds16, sums_im);
 }
 
+// The same for rows of at most 64 W elements (the state vector under a gate of up to seven qubits, Section 4.4): sixteen
+// lanes per row, four rows per wavefront and pass, nothing shared between wavefronts until the final sums, and the next
+// rows are requested before the current ones are counted. The exponents come from the high words of the bit patterns
+// (rotations inside the row of 16 lanes) unless some row's maximum is zero or subnormal.
+template <int W>
+__global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_complex_short_kernel(const double* __restrict__ Z, int64_t ldz,
+                                                                                     int64_t m, int k,
+                                                                                     unsigned long long* __restrict__ sums_re,
+                                                                                     unsigned long long* __restrict__ sums_im) {
+    const int lane = threadIdx.x & 63, r4 = lane >> 4, c16 = lane & 15;
+    __shared__ unsigned long long lds16[OZIMMU_MAX_SLICES];
+    LossAcc acc_re, acc_im;
+    loss_clear(acc_re);
+    loss_clear(acc_im);
+    const int64_t groups = (m + kRowGroup - 1) / kRowGroup;
+    const int64_t stride = (int64_t)gridDim.x * kLossWavesMax;
+    ulonglong2 cur[W][4], nxt[W][4];
+    auto request = [&](int64_t group, ulonglong2 (&v)[W][4]) __attribute__((always_inline)) {
+        const int64_t row = group * kRowGroup + r4;
+        const bool live = group < groups && row < m;
+        const ulonglong2* src = reinterpret_cast<const ulonglong2*>(Z) + (live ? row : 0) * ldz;
+#pragma unroll
+        for (int j = 0; j < W; ++j)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int l = (c16 + 16 * j) * 4 + u;
+                v[j][u] = ulonglong2{0ull, 0ull};
+                if (live && l < k) v[j][u] = src[l];
+            }
+    };
+    int64_t group = (int64_t)blockIdx.x * kLossWavesMax + (threadIdx.x >> 6);
+    request(group, cur);
+    for (; group < groups; group += stride) {
+        request(group + stride, nxt);
+        unsigned hw_re = 0, hw_im = 0;
+#pragma unroll
+        for (int j = 0; j < W; ++j)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const unsigned a = (unsigned)(cur[j][u].x >> 32) & 0x7fffffffu, b = (unsigned)(cur[j][u].y >> 32) & 0x7fffffffu;
+                hw_re = a > hw_re ? a : hw_re;
+                hw_im = b > hw_im ? b : hw_im;
+            }
+        hw_re = row_max_step<1>(row_max_step<2>(row_max_step<4>(row_max_step<8>(hw_re))));
+        hw_im = row_max_step<1>(row_max_step<2>(row_max_step<4>(row_max_step<8>(hw_im))));
+        int e_re = (int)(hw_re >> 20) - 1022, e_im = (int)(hw_im >> 20) - 1022;   // as exponent_of_max for a normal maximum
+        if (!__all(hw_re >= 0x00100000u && hw_im >= 0x00100000u)) {   // a zero or subnormal maximum somewhere: 64-bit maxima
+            unsigned long long mx_re = 0, mx_im = 0;
+#pragma unroll
+            for (int j = 0; j < W; ++j)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const unsigned long long a = cur[j][u].x & kAbsMask, b = cur[j][u].y & kAbsMask;
+                    mx_re = a > mx_re ? a : mx_re;
+                    mx_im = b > mx_im ? b : mx_im;
+                }
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) {
+                const unsigned long long o = __shfl_xor(mx_re, off, 64), q = __shfl_xor(mx_im, off, 64);
+                mx_re = o > mx_re ? o : mx_re;
+                mx_im = q > mx_im ? q : mx_im;
+            }
+            e_re = exponent_of_max(mx_re);
+            e_im = exponent_of_max(mx_im);
+        }
+#pragma unroll
+        for (int j = 0; j < W; ++j) {
+            if (j * 64 < k) {   // whole words beyond the row are skipped (same for all lanes)
+                const unsigned long long re[4] = {cur[j][0].x, cur[j][1].x, cur[j][2].x, cur[j][3].x};
+                const unsigned long long im[4] = {cur[j][0].y, cur[j][1].y, cur[j][2].y, cur[j][3].y};
+                loss_add4(acc_re, re, e_re);
+                loss_add4(acc_im, im, e_im);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < W; ++j)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) cur[j][u] = nxt[j][u];
+    }
+    loss_flush(acc_re, lds16, sums_re);
+    __syncthreads();   // lds16 is reused
+    loss_flush(acc_im, lds16, sums_im);
+}
+
 // Columns of B: as the column-maximum pass, a lane owns a column and a workgroup a band of rows.
 __global__ __launch_bounds__(256) void loss_cols_kernel(const double* __restrict__ B, int64_t ldb, int inc,
                                                         int64_t k, int64_t n, int band,
@@ -678,6 +762,14 @@ hipError_t launch_loss_scan_rows_complex(const double* Z, int64_t ldz, int64_t m
                                          unsigned long long* sums_re, unsigned long long* sums_im, hipStream_t st) {
     if (m == 0 || k == 0) return hipSuccess;
     if (!complex_scan_in_one_pass(Z, k)) return hipErrorInvalidValue;
+    if (k <= 128) {   // short rows: wavefronts on their own, up to four per SIMD
+        const int64_t row_groups = (m + kRowGroup - 1) / kRowGroup;
+        const int64_t want = (row_groups + kLossWavesMax - 1) / kLossWavesMax;
+        const unsigned grid = (unsigned)(want < 1024 ? want : 1024);
+        if (k <= 64) loss_rows_complex_short_kernel<1><<<dim3(grid), dim3(64 * kLossWavesMax), 0, st>>>(Z, ldz, m, (int)k, sums_re, sums_im);
+        else loss_rows_complex_short_kernel<2><<<dim3(grid), dim3(64 * kLossWavesMax), 0, st>>>(Z, ldz, m, (int)k, sums_re, sums_im);
+        return hipGetLastError();
+    }
     const int wpg = loss_waves_per_group(k, 64 * kZRowCacheWords);
     const int64_t groups = (m + kRowGroup - 1) / kRowGroup;
     loss_rows_complex_kernel<<<dim3(loss_grid(groups, wpg, 512)), dim3(64 * kLossWavesMax), 0, st>>>(Z, ldz, m, k, wpg, sums_re, sums_im);

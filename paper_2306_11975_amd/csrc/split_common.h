@@ -74,5 +74,12 @@ __device__ __forceinline__ uint32_t packed_slice(const Fixed (&x)[4], const Sign
     return apply_sign(c, sm);
 }
 
+// max(x, x of the lane N further round the row of 16 lanes): four of them (N = 8, 4, 2, 1) leave the row's maximum in every lane
+template <int N>
+__device__ __forceinline__ unsigned row_max_step(unsigned x) {
+    const unsigned o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x120 + N, 0xf, 0xf, false);
+    return o > x ? o : x;
+}
+
 }  // namespace
 }  // namespace ozimmu

@@ -89,6 +89,21 @@ def test_auto_complex_rows_beyond_the_one_pass_scan():
     check(wl.gaussian_complex(20000, 70, seed=7), wl.unit_column_complex(70, 9, seed=8), thresholds=(0.0, 1.0))
 
 
+@pytest.mark.parametrize("m,k", [(20000, 64), (4099, 33), (70, 1), (5000, 128), (301, 65), (100000, 16)])
+def test_auto_complex_short_rows(m, k):
+    """Rows of up to 128 interleaved elements (the state vector under a gate of up to seven qubits) have a scan kernel
+    of their own: one and two words per lane, wavefronts that walk several row groups, ragged last groups."""
+    check(wl.gaussian_complex(m, k, seed=m + k), wl.unit_column_complex(k, 9, seed=k + 2), thresholds=(0.0, 1.0))
+
+
+def test_auto_complex_short_rows_adversarial_values():
+    """Zero rows, subnormal rows (the exponents then come from the full bit patterns, not from the high words), exact
+    powers of two and huge elements, in both planes."""
+    for m, k in ((96, 64), (50, 128), (33, 7)):
+        A = wl.adversarial_matrix(m, k, seed=31) + 1j * wl.adversarial_matrix(m, k, seed=32)
+        check(A, wl.unit_column_complex(k, 5, seed=33), thresholds=(0.0, 1.0))
+
+
 @pytest.mark.parametrize("k", [400, 900, 1024])
 def test_auto_complex_rows_shared_by_two_and_four_wavefronts(k):
     """One-pass scan of interleaved rows with two (256 < k <= 512) and four (k <= 1024) wavefronts per row group."""
