@@ -234,6 +234,11 @@ ozimmu_status_t auto_select(const ScanOperand& a, const ScanOperand& b, int64_t 
             if (e == hipSuccess) e = launch_loss_scan_rows_complex(z.ptr, z.ld, z.rows, z.cols, dst, dst + OZIMMU_MAX_SLICES, st);
             continue;
         }
+        if (is_complex && z.by_cols && complex_cols_scan_in_one_launch(z.ptr, z.rows, z.cols)) {   // a small gate: one launch
+            unsigned long long* dst = sums + o * parts * OZIMMU_MAX_SLICES;
+            if (e == hipSuccess) e = launch_loss_scan_cols_complex_small(z.ptr, z.ld, z.rows, z.cols, dst, dst + OZIMMU_MAX_SLICES, st);
+            continue;
+        }
         for (int pl = 0; pl < parts && e == hipSuccess; ++pl) {
             const ScanOperand& x = *ops[o];
             unsigned long long* dst = sums + (o * parts + pl) * OZIMMU_MAX_SLICES;

@@ -107,6 +107,11 @@ hipError_t launch_split_rows_complex(const double* Z, int64_t ldz, int64_t m, in
 bool complex_scan_in_one_pass(const double* Z, int64_t k);
 hipError_t launch_loss_scan_rows_complex(const double* Z, int64_t ldz, int64_t m, int64_t k,
                                          unsigned long long* sums_re, unsigned long long* sums_im, hipStream_t st);
+// Both planes of a small interleaved complex operand scanned by columns (B: k x n complex elements, leading dimension
+// ldb in complex elements, k and n at most 128, 16-byte aligned) in one launch.
+bool complex_cols_scan_in_one_launch(const double* B, int64_t k, int64_t n);
+hipError_t launch_loss_scan_cols_complex_small(const double* B, int64_t ldb, int64_t k, int64_t n,
+                                               unsigned long long* sums_re, unsigned long long* sums_im, hipStream_t st);
 // Slice products of the pairs p + q <= s + 1 with the FP64 sum. mode 0: FP64 sum; 1: double-double sum
 // into C, C_lo; 2: the four real products of a complex one in one launch (no k-blocking: block_steps == 0),
 // real part formed in the plane Zr, imaginary part in the plane C, result interleaved in Cz.

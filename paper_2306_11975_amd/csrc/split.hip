@@ -617,6 +617,46 @@ __global__ __launch_bounds__(64 * kLossWavesMax) void loss_rows_complex_short_ke
     loss_flush(acc_im, lds16, sums_im);
 }
 
+// Both planes of a small interleaved complex operand whose groups are its columns (k x n, both at most 128: a gate),
+// in one launch instead of three per plane: a workgroup per 8 columns, thread (c, w) = (tid % 8, tid / 8) owns four
+// consecutive positions of column c; column maxima through LDS, then the scan.
+__global__ __launch_bounds__(256) void loss_cols_complex_small_kernel(const double* __restrict__ B, int64_t ldb, int k, int n,
+                                                                      unsigned long long* __restrict__ sums_re,
+                                                                      unsigned long long* __restrict__ sums_im) {
+    const int tid = threadIdx.x, r8 = tid & 7, w = tid >> 3, c = blockIdx.x * 8 + r8;
+    const ulonglong2* src = reinterpret_cast<const ulonglong2*>(B);
+    unsigned long long re[4], im[4], mx_re = 0, mx_im = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int l = 4 * w + u;
+        ulonglong2 v = {0ull, 0ull};
+        if (l < k && c < n) v = src[(int64_t)l * ldb + c];
+        re[u] = v.x;
+        im[u] = v.y;
+        const unsigned long long a = v.x & kAbsMask, b = v.y & kAbsMask;
+        mx_re = a > mx_re ? a : mx_re;
+        mx_im = b > mx_im ? b : mx_im;
+    }
+    __shared__ unsigned long long colmax[32][8][2];
+    __shared__ unsigned long long lds16[OZIMMU_MAX_SLICES];
+    colmax[w][r8][0] = mx_re;
+    colmax[w][r8][1] = mx_im;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        mx_re = colmax[i][r8][0] > mx_re ? colmax[i][r8][0] : mx_re;
+        mx_im = colmax[i][r8][1] > mx_im ? colmax[i][r8][1] : mx_im;
+    }
+    LossAcc acc_re, acc_im;
+    loss_clear(acc_re);
+    loss_clear(acc_im);
+    loss_add4(acc_re, re, exponent_of_max(mx_re));
+    loss_add4(acc_im, im, exponent_of_max(mx_im));
+    loss_flush(acc_re, lds16, sums_re);
+    __syncthreads();   // lds16 is reused
+    loss_flush(acc_im, lds16, sums_im);
+}
+
 // Columns of B: as the column-maximum pass, a lane owns a column and a workgroup a band of rows.
 __global__ __launch_bounds__(256) void loss_cols_kernel(const double* __restrict__ B, int64_t ldb, int inc,
                                                         int64_t k, int64_t n, int band,
@@ -773,6 +813,18 @@ hipError_t launch_loss_scan_rows_complex(const double* Z, int64_t ldz, int64_t m
     const int wpg = loss_waves_per_group(k, 64 * kZRowCacheWords);
     const int64_t groups = (m + kRowGroup - 1) / kRowGroup;
     loss_rows_complex_kernel<<<dim3(loss_grid(groups, wpg, 512)), dim3(64 * kLossWavesMax), 0, st>>>(Z, ldz, m, k, wpg, sums_re, sums_im);
+    return hipGetLastError();
+}
+
+bool complex_cols_scan_in_one_launch(const double* B, int64_t k, int64_t n) {
+    return k <= 128 && n <= 128 && reinterpret_cast<uintptr_t>(B) % 16 == 0;
+}
+
+hipError_t launch_loss_scan_cols_complex_small(const double* B, int64_t ldb, int64_t k, int64_t n,
+                                               unsigned long long* sums_re, unsigned long long* sums_im, hipStream_t st) {
+    if (k == 0 || n == 0) return hipSuccess;
+    if (!complex_cols_scan_in_one_launch(B, k, n)) return hipErrorInvalidValue;
+    loss_cols_complex_small_kernel<<<dim3((unsigned)((n + 7) / 8)), dim3(256), 0, st>>>(B, ldb, (int)k, (int)n, sums_re, sums_im);
     return hipGetLastError();
 }
 

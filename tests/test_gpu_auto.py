@@ -99,9 +99,11 @@ def test_auto_complex_short_rows(m, k):
 def test_auto_complex_short_rows_adversarial_values():
     """Zero rows, subnormal rows (the exponents then come from the full bit patterns, not from the high words), exact
     powers of two and huge elements, in both planes."""
-    for m, k in ((96, 64), (50, 128), (33, 7)):
+    for m, k, n in ((96, 64, 64), (50, 128, 128), (33, 7, 100), (70, 100, 3)):
         A = wl.adversarial_matrix(m, k, seed=31) + 1j * wl.adversarial_matrix(m, k, seed=32)
-        check(A, wl.unit_column_complex(k, 5, seed=33), thresholds=(0.0, 1.0))
+        B = wl.adversarial_matrix(k, n, seed=33) + 1j * wl.adversarial_matrix(k, n, seed=34)   # a small operand scanned by columns: one launch for both planes
+        check(A, B, thresholds=(0.0, 1.0))
+        check(A, wl.unit_column_complex(k, n, seed=35), thresholds=(0.0, 1.0))
 
 
 @pytest.mark.parametrize("k", [400, 900, 1024])
