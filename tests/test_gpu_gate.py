@@ -148,3 +148,31 @@ def test_gate_on_a_long_state_sampled_rows():
     idx = torch.from_numpy(rows).to(DEV)
     want = oracle.zgemm(A[idx].cpu().numpy(), U.cpu().numpy(), s)
     assert_same(C[idx].cpu().numpy(), want)
+
+
+def test_gate_call_captured_in_a_graph_replays_correctly():
+    """The gate path only enqueues two kernels on the caller's stream, so a call can be captured and replayed: each
+    replay runs on new data written into the captured buffers, with eager work and synchronisations in between."""
+    m, k, s = 3000, 64, 8
+    A = torch.empty((m, k), dtype=torch.complex128, device=DEV)
+    U = torch.empty((k, k), dtype=torch.complex128, device=DEV)
+    C = torch.empty((m, k), dtype=torch.complex128, device=DEV)
+    ws = ozimmu.alloc_workspace(m, k, k, s, is_complex=True)
+    A.copy_(torch.from_numpy(wl.gaussian_complex(m, k, seed=40)))
+    U.copy_(torch.from_numpy(wl.unit_column_complex(k, k, seed=41)))
+    ozimmu.zgemm(A, U, C, s, ws)            # warm-up outside the capture (one-time kernel attributes)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            ozimmu.zgemm(A, U, C, s, ws, stream=side)
+    for seed in (42, 43, 44):
+        Ah, Uh = wl.gaussian_complex(m, k, seed=seed), wl.unit_column_complex(k, k, seed=seed + 10)
+        A.copy_(torch.from_numpy(Ah))
+        U.copy_(torch.from_numpy(Uh))
+        C.fill_(complex(float("nan"), float("nan")))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_same(C.cpu().numpy(), oracle.zgemm(Ah, Uh, s))
