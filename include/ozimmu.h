@@ -122,7 +122,9 @@ ozimmu_status_t ozimmu_slice_gemm(int64_t m, int64_t n, int64_t k, const int8_t*
  * Workspace size for ozimmu_dgemm / ozimmu_zgemm: slices of A and B, exponents, column maxima, and
  * -- only when num_slices * k_padded > OZIMMU_INT32_BLOCK (k-blocking) -- num_slices INT64 sums per
  * element of C. Otherwise every integer sum stays in registers. A complex product adds two m x n FP64
- * planes in which its real and imaginary parts are formed before C is written, once, interleaved.
+ * planes in which its real and imaginary parts are formed before C is written, once, interleaved,
+ * and, with k and n at most 128, room for B's slices in the form the kernel wants that splits A on
+ * the fly (see ozimmu_zgemm).
  */
 ozimmu_status_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_slices,
                                        int is_complex, size_t* bytes);
