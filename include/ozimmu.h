@@ -123,7 +123,7 @@ ozimmu_status_t ozimmu_slice_gemm(int64_t m, int64_t n, int64_t k, const int8_t*
  * -- only when num_slices * k_padded > OZIMMU_INT32_BLOCK (k-blocking) -- num_slices INT64 sums per
  * element of C. Otherwise every integer sum stays in registers. A complex product adds two m x n FP64
  * planes in which its real and imaginary parts are formed before C is written, once, interleaved,
- * and, with k and n at most 128, room for B's slices in the form the kernel wants that splits A on
+ * and, with k and n small enough, room for B's slices in the form the kernel wants that splits A on
  * the fly (see ozimmu_zgemm).
  */
 ozimmu_status_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_slices,
@@ -138,8 +138,8 @@ ozimmu_status_t ozimmu_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_
  * ozimmu_zgemm: A, B, C hold interleaved (re, im) doubles (Section 4.4: the real and
  * imaginary parts are separated while splitting; four real products, each plane with its own
  * exponents; Cr = RN(G(Ar,Br) - G(Ai,Bi)), Ci = RN(G(Ar,Bi) + G(Ai,Br))).
- * With k <= 128 and n <= 128 (a gate of up to seven qubits applied to a state vector) and A, B, C
- * 16-byte aligned, A is split inside the product kernel and read once; the
+ * With k <= 128 and n <= 128 (256 each with num_slices <= 8: a gate of up to eight qubits applied
+ * to a state vector) and A, B, C 16-byte aligned, A is split inside the product kernel and read once; the
  * result is the same bit for bit, and of the workspace only the part set aside for B's slices is used.
  */
 ozimmu_status_t ozimmu_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,

@@ -1,11 +1,11 @@
 // A gate on a state vector (Section 4.4): the complex product of a tall operand Z (m x k, the reshaped state,
-// interleaved re/im) with a small one (B: k x n, the gate), k and n at most 128, any slice count, in ONE kernel
+// interleaved re/im) with a small one (B: k x n, the gate), k and n at most 128 (256 with up to eight slices), in ONE kernel
 // that reads Z once and writes the result once.
 //
 // With so short an inner dimension the product is bound by the memory traffic of the state and by the vector
 // work around the matrix cores (cutting the state into slices, folding the diagonals in FP64), and splitting the
 // state in a kernel of its own doubles that traffic (slices written, slices read back). Here a workgroup of eight
-// wavefronts takes 32 rows of Z: it finds the exponents of their real and imaginary parts and cuts both planes into
+// wavefronts (sixteen when k or n exceeds 128) takes 32 rows of Z: it finds the exponents of their real and imaginary parts and cuts both planes into
 // slices (SplitInt, Section 3.1; the same bit operations as the splitter kernels) straight into LDS, as operand
 // fragments of v_mfma_i32_16x16x64_i8 (16 rows x 64 positions of k).
 //
@@ -33,7 +33,8 @@
 namespace ozimmu {
 namespace {
 
-constexpr int kGateMax = 128;    // largest k and n
+constexpr int kGateMax = 128;    // largest k and n with more than eight slices
+constexpr int kGateMaxFew = 256; // largest k and n with up to eight slices
 constexpr int kGateRows = 32;    // rows of Z per workgroup: two fragments of 16
 constexpr int kGateStep = 64;    // positions of k per MFMA
 
@@ -64,7 +65,7 @@ __device__ __forceinline__ v4acc mfma16(const v4i& a, const v4i& b, const v4acc&
 // positions 4 w .. 4 w + 3 of k. T: tensor t at t * s * nfr * ks KiB, slice q at q * nfr * ks KiB, fragment (f, step)
 // at (f ks + step) KiB. E: [t][f][16] exponents of the fragments' rows.
 template <bool WIDE>   // more than nine slices: the fraction takes both words of the fixed-point value
-__global__ __launch_bounds__(256) void gate_split_kernel(const double* __restrict__ B, int64_t ldb, int k, int n, int s,
+__global__ __launch_bounds__(512) void gate_split_kernel(const double* __restrict__ B, int64_t ldb, int k, int n, int s,
                                                          int ks, int nfr, int8_t* __restrict__ T, int32_t* __restrict__ E) {
     const int tid = threadIdx.x, r8 = tid & 7, w = tid >> 3, f = blockIdx.x, c = f * 8 + r8;
     const ulonglong2* src = reinterpret_cast<const ulonglong2*>(B);
@@ -79,12 +80,12 @@ __global__ __launch_bounds__(256) void gate_split_kernel(const double* __restric
         mx_re = a > mx_re ? a : mx_re;
         mx_im = b > mx_im ? b : mx_im;
     }
-    __shared__ unsigned long long colmax[32][8][2];
+    __shared__ unsigned long long colmax[64][8][2];
+    const int words = blockDim.x >> 3;   // 32 (k <= 128) or 64
     colmax[w][r8][0] = mx_re;
     colmax[w][r8][1] = mx_im;
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 32; ++i) {
+    for (int i = 0; i < words; ++i) {
         mx_re = colmax[i][r8][0] > mx_re ? colmax[i][r8][0] : mx_re;
         mx_im = colmax[i][r8][1] > mx_im ? colmax[i][r8][1] : mx_im;
     }
@@ -122,13 +123,14 @@ __global__ __launch_bounds__(256) void gate_split_kernel(const double* __restric
 }
 
 // ---------------------------------------------------------------------------- the product
-// S slices; BIG: k or n above 64 (two steps of 64 positions and sixteen fragments of B instead of one and eight).
-template <int S, bool BIG>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(S <= kBand ? 4 : 2, S <= kBand ? 4 : 2)))
+// S slices; CLS, the size class of k and n: 0 up to 64 (one step of 64 positions, eight fragments of B, eight wavefronts),
+// 1 up to 128 (two steps, sixteen fragments), 2 up to 256 (four steps, 32 fragments, sixteen wavefronts; up to eight slices).
+template <int S, int CLS>
+__global__ __launch_bounds__(CLS == 2 ? 1024 : 512) __attribute__((amdgpu_waves_per_eu(S <= kBand ? 4 : 2, S <= kBand ? 4 : 2)))
 void gate_kernel(const GateArgs g) {
     constexpr bool WIDE = S > 9;   // the slices beyond the ninth come from the lower word of the fixed-point fraction
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    constexpr int KS = BIG ? 2 : 1, NFR = BIG ? 16 : 8;
+    constexpr int KS = 1 << CLS, NFR = 8 << CLS, WAVES = CLS == 2 ? 16 : 8, NT = 64 * WAVES;
     constexpr int SLICE = KS * 2 * kFragBytes;   // one slice of one plane of the tile's rows: [step][row fragment]
     constexpr int PLANE = S * SLICE;
     // behind the two planes: exponents of the tile's rows, [plane][32], then those of the gate's fragments, [tensor][NFR][16]
@@ -138,7 +140,7 @@ void gate_kernel(const GateArgs g) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t row_tile = (int64_t)blockIdx.x * kGateRows;
 
-    // ---- this wavefront's patches: rows 16 rf .. + 15 of the tile, complex columns 8 f .. 8 f + 7 for f = cg, cg + 4, ...
+    // ---- this wavefront's patches: rows 16 rf .. + 15 of the tile, complex columns 8 f .. 8 f + 7 for f = cg, cg + WAVES / 2, ...
     const int rf = wave & 1, cg = wave >> 1;
     const unsigned char* a_rd = lds + rf * kFragBytes + 16 * lane;
     constexpr int BSLICE = NFR * KS * kFragBytes, TENSOR = S * BSLICE;
@@ -161,20 +163,21 @@ void gate_kernel(const GateArgs g) {
         static_for<0, S>([&](auto pc) __attribute__((always_inline)) { b[decltype(pc)::value] = load_b(first, decltype(pc)::value, 0); });
     }
 
-    // ---- the rows of Z -> exponents and slices in LDS. Sixteen lanes work on a row; a lane owns KS words of four
-    // consecutive complex elements of it (words c16 and, with two steps, 16 + c16); a wavefront takes four rows.
+    // ---- the rows of Z -> exponents and slices in LDS. LPR lanes work on a row (16, or 32 with sixteen wavefronts); a
+    // lane owns W words of four consecutive complex elements of it (words cl, LPR + cl, ...).
     {
-        const int lrow = tid >> 4, c16 = tid & 15;
-        for (int i = tid; i < 2 * NFR * 16; i += 512) ex_gate[i] = g.E[i];
+        constexpr int LPR = NT / kGateRows, W = KS * 16 / LPR;
+        const int lrow = tid / LPR, cl = tid % LPR;
+        for (int i = tid; i < 2 * NFR * 16; i += NT) ex_gate[i] = g.E[i];
         const int64_t row = row_tile + lrow;
         const bool live = row < g.m;
         const ulonglong2* src = reinterpret_cast<const ulonglong2*>(g.Z) + (live ? row : 0) * g.ldz;
-        ulonglong2 v[KS][4];
+        ulonglong2 v[W][4];
 #pragma unroll
-        for (int j = 0; j < KS; ++j)
+        for (int j = 0; j < W; ++j)
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int l = (c16 + 16 * j) * 4 + u;
+                const int l = (cl + LPR * j) * 4 + u;
                 v[j][u] = ulonglong2{0ull, 0ull};
                 if (live && l < g.k) v[j][u] = src[l];
             }
@@ -182,7 +185,7 @@ void gate_kernel(const GateArgs g) {
         // zero or subnormal: maxima of those over the row's 16 lanes with rotations inside the row, one instruction each.
         unsigned hw_re = 0, hw_im = 0;
 #pragma unroll
-        for (int j = 0; j < KS; ++j)
+        for (int j = 0; j < W; ++j)
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const unsigned a = (unsigned)(v[j][u].x >> 32) & 0x7fffffffu, b2 = (unsigned)(v[j][u].y >> 32) & 0x7fffffffu;
@@ -191,13 +194,18 @@ void gate_kernel(const GateArgs g) {
             }
         hw_re = row_max_step<1>(row_max_step<2>(row_max_step<4>(row_max_step<8>(hw_re))));
         hw_im = row_max_step<1>(row_max_step<2>(row_max_step<4>(row_max_step<8>(hw_im))));
+        if constexpr (LPR == 32) {   // the row's other sixteen lanes
+            const unsigned o = __shfl_xor(hw_re, 16, 64), q = __shfl_xor(hw_im, 16, 64);
+            hw_re = o > hw_re ? o : hw_re;
+            hw_im = q > hw_im ? q : hw_im;
+        }
         int e_re = (int)(hw_re >> 20) - 1022, e_im = (int)(hw_im >> 20) - 1022;   // as exponent_of_max for a normal maximum
         const bool normal = __all(hw_re >= 0x00100000u && hw_im >= 0x00100000u);
         if (!normal) {
             // some row of this wavefront has a zero or subnormal maximum (rows past the end of Z among them): full 64-bit maxima
             unsigned long long mx_re = 0, mx_im = 0;
 #pragma unroll
-            for (int j = 0; j < KS; ++j)
+            for (int j = 0; j < W; ++j)
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const unsigned long long a = v[j][u].x & kAbsMask, b2 = v[j][u].y & kAbsMask;
@@ -205,7 +213,7 @@ void gate_kernel(const GateArgs g) {
                     mx_im = b2 > mx_im ? b2 : mx_im;
                 }
 #pragma unroll
-            for (int off = 8; off >= 1; off >>= 1) {
+            for (int off = LPR / 2; off >= 1; off >>= 1) {
                 const unsigned long long o = __shfl_xor(mx_re, off, 64), q = __shfl_xor(mx_im, off, 64);
                 mx_re = o > mx_re ? o : mx_re;
                 mx_im = q > mx_im ? q : mx_im;
@@ -213,13 +221,13 @@ void gate_kernel(const GateArgs g) {
             e_re = exponent_of_max(mx_re);
             e_im = exponent_of_max(mx_im);
         }
-        if (c16 == 0) {
+        if (cl == 0) {
             ex[lrow] = e_re;
             ex[kGateRows + lrow] = e_im;
         }
         auto emit = [&](auto normal_tag) __attribute__((always_inline)) {
 #pragma unroll
-            for (int j = 0; j < KS; ++j) {
+            for (int j = 0; j < W; ++j) {
                 Fixed xr[4], xi[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -233,7 +241,8 @@ void gate_kernel(const GateArgs g) {
                 }
                 const SignMask sr = sign_mask(v[j][0].x, v[j][1].x, v[j][2].x, v[j][3].x);
                 const SignMask si = sign_mask(v[j][0].y, v[j][1].y, v[j][2].y, v[j][3].y);
-                unsigned char* dst = lds + (j * 2 + (lrow >> 4)) * kFragBytes + frag_offset(lrow & 15, c16 * 4);
+                const int word = cl + LPR * j;   // sixteen words to a step
+                unsigned char* dst = lds + ((word >> 4) * 2 + (lrow >> 4)) * kFragBytes + frag_offset(lrow & 15, (word & 15) * 4);
                 static_for<1, S + 1>([&](auto pc) __attribute__((always_inline)) {
                     constexpr int p = decltype(pc)::value;
                     *reinterpret_cast<uint32_t*>(dst + (p - 1) * SLICE) = packed_slice<WIDE>(xr, sr, p);
@@ -252,7 +261,8 @@ void gate_kernel(const GateArgs g) {
     const int lrow0 = rf * 16 + 4 * (lane >> 4), c8 = lane & 7;
     const bool is_im = (lane & 8) != 0;
     // patches of this wavefront that hold a column of C at all (wave-uniform)
-    const int np = g.n > 8 * cg ? (g.n - 8 * cg - 1) / 32 + 1 : 0;
+    constexpr int CGS = WAVES / 2;   // wavefronts side by side over the fragments of B
+    const int np = g.n > 8 * cg ? (g.n - 8 * cg - 1) / (8 * CGS) + 1 : 0;
     if (np == 0) return;
 
     v4acc acc[S];
@@ -260,9 +270,9 @@ void gate_kernel(const GateArgs g) {
     double part[4];
     // iteration it: patch it / 2, pass it % 2 (0: Ar with T1, 1: Ai with T2)
     for (int it = 0; it < 2 * np; ++it) {
-        const int pass = it & 1, f = cg + 4 * (it >> 1);
+        const int pass = it & 1, f = cg + CGS * (it >> 1);
         const int nit = it + 1 < 2 * np ? it + 1 : 0;   // (after the last one the first one's fragments again, unused)
-        const unsigned b_this = b_base(pass, f), b_next = b_base(nit & 1, cg + 4 * (nit >> 1));
+        const unsigned b_this = b_base(pass, f), b_next = b_base(nit & 1, cg + CGS * (nit >> 1));
         static_for<0, S>([&](auto pc) __attribute__((always_inline)) { a[decltype(pc)::value] = read_a(pass, decltype(pc)::value, 0); });
         __builtin_amdgcn_sched_barrier(0);
         // Group q of a step = the MFMAs of B fragment q with the A fragments S - 1 - q .. 0, each into the sum of
@@ -336,42 +346,44 @@ void gate_kernel(const GateArgs g) {
     }
 }
 
-template <int S, bool BIG>
+template <int S, int CLS>
 hipError_t launch_gate(const GateArgs& g, hipStream_t st) {
-    constexpr int lds = 2 * S * (BIG ? 2 : 1) * 2 * kFragBytes + (2 * kGateRows + 2 * (BIG ? 16 : 8) * 16) * (int)sizeof(int);
-    static_assert(lds <= 160 * 1024 && (S > kBand || 2 * lds <= 160 * 1024), "the LDS of a compute unit: two workgroups up to eight slices");
-    hipError_t e = allow_dynamic_lds<&gate_kernel<S, BIG>>(lds);
+    constexpr int lds = 2 * S * (1 << CLS) * 2 * kFragBytes + (2 * kGateRows + 2 * (8 << CLS) * 16) * (int)sizeof(int);
+    static_assert(lds <= 160 * 1024 && (S > kBand || CLS == 2 || 2 * lds <= 160 * 1024),
+                  "the LDS of a compute unit: two workgroups of eight wavefronts up to eight slices, else one workgroup");
+    hipError_t e = allow_dynamic_lds<&gate_kernel<S, CLS>>(lds);
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((g.m + kGateRows - 1) / kGateRows);
-    gate_kernel<S, BIG><<<dim3(grid), dim3(512), lds, st>>>(g);
+    gate_kernel<S, CLS><<<dim3(grid), dim3(CLS == 2 ? 1024 : 512), lds, st>>>(g);
     return hipGetLastError();
 }
 
-inline bool gate_is_big(int64_t k, int64_t n) { return k > 64 || n > 64; }
+inline int gate_class(int64_t k, int64_t n) { return k > 128 || n > 128 ? 2 : k > 64 || n > 64 ? 1 : 0; }
+inline int64_t gate_limit(int s) { return s <= kBand ? kGateMaxFew : kGateMax; }
 
 }  // namespace
 
 bool gate_product_applies(const double* Z, const double* B, const double* Cz, int64_t n, int64_t k, int s) {
-    return n >= 1 && n <= kGateMax && k >= 1 && k <= kGateMax && s <= OZIMMU_MAX_SLICES && reinterpret_cast<uintptr_t>(Z) % 16 == 0 &&
-           reinterpret_cast<uintptr_t>(B) % 16 == 0 && reinterpret_cast<uintptr_t>(Cz) % 16 == 0;
+    return s >= 1 && s <= OZIMMU_MAX_SLICES && n >= 1 && n <= gate_limit(s) && k >= 1 && k <= gate_limit(s) &&
+           reinterpret_cast<uintptr_t>(Z) % 16 == 0 && reinterpret_cast<uintptr_t>(B) % 16 == 0 && reinterpret_cast<uintptr_t>(Cz) % 16 == 0;
 }
 
 size_t gate_scratch_bytes(int64_t n, int64_t k, int s) {
-    if (n < 1 || n > kGateMax || k < 1 || k > kGateMax || s > OZIMMU_MAX_SLICES) return 0;
-    const size_t nfr = gate_is_big(k, n) ? 16 : 8, ks = gate_is_big(k, n) ? 2 : 1;
+    if (s < 1 || s > OZIMMU_MAX_SLICES || n < 1 || n > gate_limit(s) || k < 1 || k > gate_limit(s)) return 0;
+    const size_t nfr = (size_t)8 << gate_class(k, n), ks = (size_t)1 << gate_class(k, n);
     return 2 * nfr * 16 * sizeof(int32_t) + (size_t)2 * s * nfr * ks * kFragBytes;
 }
 
 hipError_t launch_gate_product(const double* Z, int64_t ldz, int64_t m, int64_t k, int64_t n, const double* B, int64_t ldb,
                                int s, void* scratch, double* Cz, int64_t ldcz, hipStream_t st) {
     if (m <= 0) return hipSuccess;
-    if (!gate_product_applies(Z, B, Cz, n, k, s) || s < 1) return hipErrorInvalidValue;
-    const bool big = gate_is_big(k, n);
-    const int ks = big ? 2 : 1, nfr = big ? 16 : 8;
+    if (!gate_product_applies(Z, B, Cz, n, k, s)) return hipErrorInvalidValue;
+    const int cls = gate_class(k, n), ks = 1 << cls, nfr = 8 << cls;
     int32_t* E = static_cast<int32_t*>(scratch);
     int8_t* T = reinterpret_cast<int8_t*>(E + 2 * nfr * 16);
-    if (s > 9) gate_split_kernel<true><<<dim3(nfr), dim3(256), 0, st>>>(B, ldb, (int)k, (int)n, s, ks, nfr, T, E);
-    else gate_split_kernel<false><<<dim3(nfr), dim3(256), 0, st>>>(B, ldb, (int)k, (int)n, s, ks, nfr, T, E);
+    const unsigned split_threads = cls == 2 ? 512 : 256;   // a thread per word of four positions and column of the fragment
+    if (s > 9) gate_split_kernel<true><<<dim3(nfr), dim3(split_threads), 0, st>>>(B, ldb, (int)k, (int)n, s, ks, nfr, T, E);
+    else gate_split_kernel<false><<<dim3(nfr), dim3(split_threads), 0, st>>>(B, ldb, (int)k, (int)n, s, ks, nfr, T, E);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     GateArgs g{};
@@ -385,8 +397,10 @@ hipError_t launch_gate_product(const double* Z, int64_t ldz, int64_t m, int64_t 
     g.Cz = Cz;
     g.ldcz = ldcz;
     switch (s) {
-#define OZ_CASE(S_) case S_: return big ? launch_gate<S_, true>(g, st) : launch_gate<S_, false>(g, st);
+#define OZ_CASE(S_) case S_: return cls == 2 ? launch_gate<S_, 2>(g, st) : cls == 1 ? launch_gate<S_, 1>(g, st) : launch_gate<S_, 0>(g, st);
         OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8)
+#undef OZ_CASE
+#define OZ_CASE(S_) case S_: return cls == 1 ? launch_gate<S_, 1>(g, st) : launch_gate<S_, 0>(g, st);
         OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16)
 #undef OZ_CASE
     }

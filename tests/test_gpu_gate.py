@@ -1,8 +1,8 @@
 """GPU parity of the one-kernel complex product for a small gate on a tall state (Section 4.4: a d-qubit gate on an
 N-qubit state vector is the complex product 2^(N-d) x 2^d x 2^d). ozimmu_zgemm takes that path when k and n are
-at most 128; the state is then split inside the product kernel (tiles of 32 rows; one step of 64 positions and eight
-fragments of the gate while k and n are at most 64, two steps and sixteen fragments beyond; four wavefronts per SIMD up
-to eight slices, two beyond). Compared bit for bit with the oracle, which splits first and multiplies afterwards."""
+at most 128 (256 with up to eight slices); the state is then split inside the product kernel (tiles of 32 rows; one
+step of 64 positions and eight fragments of the gate while k and n are at most 64, two steps and sixteen fragments up to
+128, four steps, 32 fragments and sixteen wavefronts up to 256; four wavefronts per SIMD up to eight slices, two beyond). Compared bit for bit with the oracle, which splits first and multiplies afterwards."""
 import numpy as np
 import pytest
 import torch
@@ -67,6 +67,41 @@ def test_gate_ragged_shapes_two_steps(m, n, k, s):
     A = wl.gaussian_complex(m, k, seed=m + k)
     B = wl.unit_column_complex(k, n, seed=n + k + 1)
     assert_same(gpu_zgemm(A, B, s, lda_extra=1, ldb_extra=2, ldc_extra=3), oracle.zgemm(A, B, s))
+
+
+@pytest.mark.parametrize("s", range(1, 9))
+def test_gate_every_slice_count_four_steps(s):
+    """k and n up to 256 with up to eight slices: workgroups of sixteen wavefronts, 32 lanes per row, 32 fragments of B."""
+    m, n, k = 70, 256, 256
+    A = wl.gaussian_complex(m, k, seed=500 + s)
+    B = wl.unit_column_complex(k, n, seed=600 + s)
+    assert_same(gpu_zgemm(A, B, s), oracle.zgemm(A, B, s))
+
+
+@pytest.mark.parametrize("m,n,k,s", [(33, 200, 129, 5), (70, 130, 64, 8), (31, 64, 250, 3), (100, 255, 193, 7), (64, 256, 1, 2),
+                                     (40, 129, 129, 9)])
+def test_gate_ragged_shapes_four_steps(m, n, k, s):
+    """k or n between 129 and 256 (zero rows among the adversarial values take the 64-bit maxima over 32 lanes);
+    nine slices at that size take the general path."""
+    A = wl.gaussian_complex(m, k, seed=m + k)
+    A[m // 2, :] = 0.0
+    B = wl.unit_column_complex(k, n, seed=n + k + 1)
+    assert_same(gpu_zgemm(A, B, s, lda_extra=1, ldb_extra=2, ldc_extra=3), oracle.zgemm(A, B, s))
+
+
+def test_eight_qubit_gate_sampled_rows():
+    """An 8-qubit gate on 20 qubits (4096 x 256 x 256), rows sampled over the whole state."""
+    m, k, s = 1 << 12, 256, 8
+    A = wl.gaussian_complex_device(m, k, seed=26)
+    A = A / A.abs().pow(2).sum().sqrt()
+    U = wl.haar_unitary_device(k, seed=27).contiguous()
+    C = torch.empty((m, k), dtype=torch.complex128, device=DEV)
+    ozimmu.zgemm(A, U, C, s, ozimmu.alloc_workspace(m, k, k, s, is_complex=True))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(28)
+    rows = np.unique(np.concatenate([[0, 31, 32, m - 32, m - 1], rng.integers(0, m, 60)]))
+    idx = torch.from_numpy(rows).to(DEV)
+    assert_same(C[idx].cpu().numpy(), oracle.zgemm(A[idx].cpu().numpy(), U.cpu().numpy(), s))
 
 
 @pytest.mark.parametrize("m,n,k,s", [(1, 1, 1, 3), (64, 64, 64, 8), (65, 63, 33, 7), (63, 17, 31, 5), (130, 16, 64, 8),
