@@ -117,6 +117,9 @@ def bench_complex(args, m, n, k, s, statevec=None):
                      "achieved": int8_ops / sec / 1e12, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": int8_ops / sec / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": None},
     }
+    if max(k, n) <= 256 and s <= 8 and max(k, n) > 128:
+        # an 8-qubit gate: the one-kernel path too, but bound by the matrix cores
+        out["roofline"]["kernel"] = "whole ozimmu_zgemm call (gate_split_kernel + gate_kernel)"
     if k <= 128 and n <= 128:
         # a small gate on a tall state runs as one kernel that reads the state once and writes the result once
         # (gate_kernel; the gate's own split is a few microseconds): the memory traffic of the state bounds it
