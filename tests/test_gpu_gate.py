@@ -211,3 +211,25 @@ def test_gate_call_captured_in_a_graph_replays_correctly():
         graph.replay()
         torch.cuda.synchronize()
         assert_same(C.cpu().numpy(), oracle.zgemm(Ah, Uh, s))
+
+
+def test_gate_seeded_random_shapes_and_values():
+    """Forty seeded shapes over the whole range the one-kernel path serves (k, n up to 256 with up to eight slices, up to
+    128 beyond), with Gaussian, wide-exponent and adversarial values in turn."""
+    rng = np.random.default_rng(2024)
+    for it in range(40):
+        s = int(rng.integers(1, 17))
+        lim = 256 if s <= 8 else 128
+        k, n, m = int(rng.integers(1, lim + 1)), int(rng.integers(1, lim + 1)), int(rng.integers(1, 300))
+        if it % 3 == 0:
+            A, B = wl.gaussian_complex(m, k, seed=it), wl.unit_column_complex(k, n, seed=1000 + it)
+        elif it % 3 == 1:
+            A = wl.phi_matrix(m, k, 2.0, seed=it) + 1j * wl.phi_matrix(m, k, 0.5, seed=it + 7)
+            B = wl.phi_matrix(k, n, 1.0, seed=it + 3) + 1j * wl.phi_matrix(k, n, 2.0, seed=it + 5)
+        else:
+            A = wl.adversarial_matrix(m, k, seed=it) + 1j * wl.adversarial_matrix(m, k, seed=it + 1)
+            B = wl.adversarial_matrix(k, n, seed=it + 2) + 1j * wl.adversarial_matrix(k, n, seed=it + 3)
+        got = gpu_zgemm(np.ascontiguousarray(A), np.ascontiguousarray(B), s)
+        want = oracle.zgemm(A, B, s)
+        assert np.array_equal(bits(got.real.copy()), bits(want.real.copy())), (it, m, n, k, s)
+        assert np.array_equal(bits(got.imag.copy()), bits(want.imag.copy())), (it, m, n, k, s)
