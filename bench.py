@@ -130,6 +130,17 @@ def bench_complex(args, m, n, k, s, statevec=None):
                            "int8_mfma_frac": int8_ops / sec / 1e12 / INT8_MFMA_PEAK_TOPS}
     if auto_ms is not None:
         out["auto_num_slices_ms"] = auto_ms
+        # the application's step as the paper runs it (INT8-AUTO per product): count chosen and product formed in one
+        # call, the count of the previous product as the guess
+        ws_auto = torch.empty(max(ozimmu.workspace_bytes(m, n, k, s2, True) for s2 in range(1, 17)), dtype=torch.uint8, device="cuda")
+        scratch = torch.empty(max(ozimmu.auto_scratch_bytes(n), 256), dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            s_auto, confirmed = ozimmu.zgemm_auto(A, B, C, args.threshold, guess=s, workspace=ws_auto, scratch=scratch)
+        t_a = time.perf_counter()
+        for _ in range(10):
+            ozimmu.zgemm_auto(A, B, C, args.threshold, guess=s, workspace=ws_auto, scratch=scratch)
+        out["zgemm_auto_ms"] = (time.perf_counter() - t_a) / 10 * 1e3
+        out["zgemm_auto"] = {"num_slices": s_auto, "guess_confirmed": bool(confirmed)}
     if not args.no_context:
         for _ in range(2):
             torch.matmul(A, B)

@@ -20,7 +20,7 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). All work is
  *     enqueued on it; no entry point synchronises, allocates or frees device memory, or
  *     keeps state between calls (exceptions, stated where they are declared:
- *     ozimmu_auto_num_slices returns a value to the host and waits for the stream;
+ *     ozimmu_auto_num_slices and ozimmu_zgemm_auto return a value to the host and wait for the stream;
  *     ozimmu_dgemm_static uses the library's own scratch array; the library remembers per
  *     device that it has raised a kernel's dynamic LDS limit). Calls that share a workspace must
  *     be stream-ordered.
@@ -275,6 +275,26 @@ ozimmu_status_t ozimmu_auto_num_slices(int64_t m, int64_t n, int64_t k, const do
                                        const double* B, int64_t ldb, int is_complex, double threshold,
                                        int max_slices, void* scratch, size_t scratch_bytes,
                                        int* num_slices, uint64_t* loss_sums, void* stream);
+
+/*
+ * ozimmu_auto_num_slices followed by ozimmu_zgemm with the count it chose, as one call: *num_slices
+ * receives the count, C the product; both are exactly what the two calls give. `guess` is the
+ * caller's expectation of the count (say, the one the previous product of this shape took; 0: none).
+ * Where ozimmu_zgemm runs as the kernel that splits A on the fly (see there) the product is formed
+ * with `guess` at once, and that kernel counts on its way over A what the check of the guess needs;
+ * if the guess was right, A has been read once instead of twice (*guess_confirmed = 1; optional
+ * HOST pointer). Otherwise, and for every other shape, the count is chosen first and the product
+ * formed afterwards. workspace: at least the largest ozimmu_workspace_bytes(m, n, k, s, 1) over
+ * s = 1 .. max_slices; scratch: as for ozimmu_auto_num_slices. Waits for the stream like
+ * ozimmu_auto_num_slices; errors as there and as for ozimmu_zgemm. The first call of a thread
+ * allocates 512 bytes of mapped host memory (where the last kernel leaves the sums the check reads),
+ * kept until the process ends.
+ */
+ozimmu_status_t ozimmu_zgemm_auto(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                                  const double* B, int64_t ldb, double* C, int64_t ldc, double threshold,
+                                  int max_slices, int guess, void* workspace, size_t workspace_bytes,
+                                  void* scratch, size_t scratch_bytes, int* num_slices,
+                                  int* guess_confirmed, void* stream);
 
 /*
  * The same choice for the operands of a BLAS-style call (ozimmu_dgemm_blas / ozimmu_zgemm_blas):

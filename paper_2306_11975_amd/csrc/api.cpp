@@ -210,6 +210,34 @@ struct ScanOperand {
     bool by_cols;
 };
 
+// The slice-count sums of operand o (0: first, 1: second) into sums[(o * parts + plane) * 16 ..].
+hipError_t scan_operand(const ScanOperand& z, int o, int is_complex, unsigned long long* sums, unsigned long long* colmax,
+                        hipStream_t st) {
+    const int parts = is_complex ? 2 : 1, inc = is_complex ? 2 : 1;
+    unsigned long long* dst = sums + o * parts * OZIMMU_MAX_SLICES;
+    if (is_complex && !z.by_cols && complex_scan_in_one_pass(z.ptr, z.cols))   // both planes of short rows at once
+        return launch_loss_scan_rows_complex(z.ptr, z.ld, z.rows, z.cols, dst, dst + OZIMMU_MAX_SLICES, st);
+    if (is_complex && z.by_cols && complex_cols_scan_in_one_launch(z.ptr, z.rows, z.cols))   // a small gate: one launch
+        return launch_loss_scan_cols_complex_small(z.ptr, z.ld, z.rows, z.cols, dst, dst + OZIMMU_MAX_SLICES, st);
+    hipError_t e = hipSuccess;
+    for (int pl = 0; pl < parts && e == hipSuccess; ++pl) {
+        if (z.by_cols) e = launch_loss_scan_cols(z.ptr + pl, z.ld, inc, z.rows, z.cols, colmax, dst + pl * OZIMMU_MAX_SLICES, st);
+        else e = launch_loss_scan_rows(z.ptr + pl, z.ld, inc, z.rows, z.cols, dst + pl * OZIMMU_MAX_SLICES, st);
+    }
+    return e;
+}
+
+// 4 x 16 sums in host memory that kernels can write (one buffer per calling thread, kept until the process ends)
+unsigned long long* mapped_sums() {
+    thread_local unsigned long long* p = nullptr;
+    if (!p) {
+        void* q = nullptr;
+        if (hipHostMalloc(&q, 4 * OZIMMU_MAX_SLICES * sizeof(unsigned long long), hipHostMallocMapped) == hipSuccess)
+            p = static_cast<unsigned long long*>(q);
+    }
+    return p;
+}
+
 ozimmu_status_t auto_select(const ScanOperand& a, const ScanOperand& b, int64_t scratch_cols, int is_complex,
                             double threshold, int max_slices, void* scratch, size_t scratch_bytes, int* num_slices,
                             uint64_t* loss_sums, void* stream) {
@@ -224,28 +252,10 @@ ozimmu_status_t auto_select(const ScanOperand& a, const ScanOperand& b, int64_t 
     hipStream_t st = static_cast<hipStream_t>(stream);
     unsigned long long* sums = static_cast<unsigned long long*>(scratch);          // [4][16]
     unsigned long long* colmax = sums + 4 * OZIMMU_MAX_SLICES;
-    const int parts = is_complex ? 2 : 1, inc = is_complex ? 2 : 1;
+    const int parts = is_complex ? 2 : 1;
     hipError_t e = launch_fill_u64(sums, 4 * OZIMMU_MAX_SLICES, 0ull, st);
-    const ScanOperand* ops[2] = {&a, &b};
-    for (int o = 0; o < 2; ++o) {
-        const ScanOperand& z = *ops[o];
-        if (is_complex && !z.by_cols && complex_scan_in_one_pass(z.ptr, z.cols)) {   // both planes of short rows at once
-            unsigned long long* dst = sums + o * parts * OZIMMU_MAX_SLICES;
-            if (e == hipSuccess) e = launch_loss_scan_rows_complex(z.ptr, z.ld, z.rows, z.cols, dst, dst + OZIMMU_MAX_SLICES, st);
-            continue;
-        }
-        if (is_complex && z.by_cols && complex_cols_scan_in_one_launch(z.ptr, z.rows, z.cols)) {   // a small gate: one launch
-            unsigned long long* dst = sums + o * parts * OZIMMU_MAX_SLICES;
-            if (e == hipSuccess) e = launch_loss_scan_cols_complex_small(z.ptr, z.ld, z.rows, z.cols, dst, dst + OZIMMU_MAX_SLICES, st);
-            continue;
-        }
-        for (int pl = 0; pl < parts && e == hipSuccess; ++pl) {
-            const ScanOperand& x = *ops[o];
-            unsigned long long* dst = sums + (o * parts + pl) * OZIMMU_MAX_SLICES;
-            if (x.by_cols) e = launch_loss_scan_cols(x.ptr + pl, x.ld, inc, x.rows, x.cols, colmax, dst, st);
-            else e = launch_loss_scan_rows(x.ptr + pl, x.ld, inc, x.rows, x.cols, dst, st);
-        }
-    }
+    if (e == hipSuccess) e = scan_operand(a, 0, is_complex, sums, colmax, st);
+    if (e == hipSuccess) e = scan_operand(b, 1, is_complex, sums, colmax, st);
     unsigned long long host[4 * OZIMMU_MAX_SLICES];
     if (e == hipSuccess) e = hipMemcpyAsync(host, sums, sizeof(host), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
@@ -447,6 +457,63 @@ ozimmu_status_t ozimmu_auto_num_slices(int64_t m, int64_t n, int64_t k, const do
     const ScanOperand a{A, lda, m, k, false}, b{B, ldb, k, n, true};
     return auto_select(a, b, n, is_complex, threshold, max_slices, scratch, scratch_bytes, num_slices, loss_sums,
                        stream);
+}
+
+ozimmu_status_t ozimmu_zgemm_auto(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
+                                  int64_t ldb, double* C, int64_t ldc, double threshold, int max_slices, int guess,
+                                  void* workspace, size_t workspace_bytes, void* scratch, size_t scratch_bytes,
+                                  int* num_slices, int* guess_confirmed, void* stream) {
+    if (max_slices < 1 || max_slices > OZIMMU_MAX_SLICES || !(threshold >= 0.0)) return OZIMMU_ERR_BAD_SLICES;
+    if (!num_slices) return OZIMMU_ERR_NULL;
+    if (guess_confirmed) *guess_confirmed = 0;
+    // the workspace must serve whichever slice count comes out
+    Layout L{};
+    size_t need_ws = 0;
+    for (int s = 1; s <= max_slices; ++s) {
+        ozimmu_status_t rc = check_gemm_args(m, n, k, A, lda, B, ldb, C, ldc, s, workspace, workspace_bytes, true, &L);
+        if (rc != OZIMMU_OK) return rc;
+        need_ws = std::max(need_ws, L.total);
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (guess >= 1 && guess <= max_slices && m > 0 && n > 0 && k > 0 && gate_product_applies(A, B, C, n, k, guess)) {
+        size_t need = 0;
+        ozimmu_auto_scratch_bytes(n, &need);
+        if (!scratch || (reinterpret_cast<uintptr_t>(scratch) % OZIMMU_WORKSPACE_ALIGN) != 0 || scratch_bytes < need)
+            return OZIMMU_ERR_WORKSPACE;
+        // Multiply with the guessed count; the kernels that split B and that walk over A count, on their way, what the
+        // check of the guess needs (the bits each plane loses with `guess` and with `guess - 1` slices) and a last small
+        // kernel writes the eight sums into mapped host memory: no pass of its own over A, no copy.
+        L = make_layout(m, n, k, guess, true);
+        if (gate_scan_bytes(m) > L.sa_bytes) return OZIMMU_ERR_WORKSPACE;
+        unsigned char* ws = static_cast<unsigned char*>(workspace);
+        unsigned long long* host = mapped_sums();                                      // [4][16]
+        if (!host) return OZIMMU_ERR_HIP;
+        // the per-tile counters wait where the slices of A would be (that region is not used on this path)
+        hipError_t e = launch_gate_product(A, lda, m, k, n, B, ldb, guess, ws + L.off_gate, C, ldc, st,
+                                           reinterpret_cast<unsigned*>(ws + L.off_sa[0]), host);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return OZIMMU_ERR_HIP;
+        const double count_a = (double)m * (double)k, count_b = (double)k * (double)n;
+        auto within = [&](int s) {   // every plane's loss with s slices within the threshold (the rule of ozimmu_auto_num_slices)
+            bool ok = true;
+            for (int p = 0; p < 4; ++p) ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < 2 ? count_a : count_b);
+            return ok;
+        };
+        // the loss does not grow with the slice count: `guess` is the choice iff it is within the threshold (or the
+        // largest count allowed) and guess - 1 is not
+        if ((within(guess) || guess == max_slices) && (guess == 1 || !within(guess - 1))) {
+            *num_slices = guess;
+            if (guess_confirmed) *guess_confirmed = 1;
+            return OZIMMU_OK;
+        }
+    }
+    int s = 0;
+    ozimmu_status_t rc = ozimmu_auto_num_slices(m, n, k, A, lda, B, ldb, 1, threshold, max_slices, scratch, scratch_bytes, &s,
+                                                nullptr, stream);
+    if (rc != OZIMMU_OK) return rc;
+    rc = ozimmu_zgemm(m, n, k, A, lda, B, ldb, C, ldc, s, workspace, workspace_bytes, stream);
+    if (rc == OZIMMU_OK) *num_slices = s;
+    return rc;
 }
 
 ozimmu_status_t ozimmu_auto_num_slices_blas(char transa, char transb, int64_t m, int64_t n, int64_t k,

@@ -55,6 +55,40 @@ __device__ __forceinline__ Fixed to_fixed_upper(unsigned long long bits, int E) 
     return f;
 }
 
+// What the check of a guessed slice count S needs of a plane (see loss_position): sums of |v - 7 S|, |z - 7 S|, the
+// same for S - 1, and of the stored bits L; the bits lost with s slices are (sum |v - 7 s| - sum |z - 7 s| + sum L) / 2.
+constexpr int kScanCounters = 5;
+struct ScanCount {
+    uint32_t sv_g, sz_g, sv_h, sz_h, bits;
+};
+template <int S>
+__device__ __forceinline__ void scan_count4(ScanCount& a, const unsigned long long (&b)[4], int E) {
+    uint32_t pz = 0, pl = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        uint32_t z, L;
+        loss_position(b[u], E, z, L);
+        pz |= z << (8 * u);
+        pl |= L << (8 * u);
+    }
+    const uint32_t pv = pz + pl;   // bytewise: no byte exceeds 165
+    a.bits = __builtin_amdgcn_sad_u8(pl, 0u, a.bits);
+    constexpr uint32_t edge_g = 0x01010101u * (uint32_t)(OZIMMU_SLICE_BITS * S);
+    a.sv_g = __builtin_amdgcn_sad_u8(pv, edge_g, a.sv_g);
+    a.sz_g = __builtin_amdgcn_sad_u8(pz, edge_g, a.sz_g);
+    if constexpr (S > 1) {
+        constexpr uint32_t edge_h = 0x01010101u * (uint32_t)(OZIMMU_SLICE_BITS * (S - 1));
+        a.sv_h = __builtin_amdgcn_sad_u8(pv, edge_h, a.sv_h);
+        a.sz_h = __builtin_amdgcn_sad_u8(pz, edge_h, a.sz_h);
+    }
+}
+
+// bits an element at (z, L) loses with s slices
+__device__ __forceinline__ unsigned lost_bits(uint32_t z, uint32_t L, int s) {
+    const int edge = OZIMMU_SLICE_BITS * s, below = (int)(z + L) - edge, above = (int)z - edge;
+    return (unsigned)((below > 0 ? below : 0) - (above > 0 ? above : 0));
+}
+
 typedef int v4acc __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ v4acc mfma16(const v4i& a, const v4i& b, const v4acc& c) {
     return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
@@ -66,7 +100,8 @@ __device__ __forceinline__ v4acc mfma16(const v4i& a, const v4i& b, const v4acc&
 // at (f ks + step) KiB. E: [t][f][16] exponents of the fragments' rows.
 template <bool WIDE>   // more than nine slices: the fraction takes both words of the fixed-point value
 __global__ __launch_bounds__(512) void gate_split_kernel(const double* __restrict__ B, int64_t ldb, int k, int n, int s,
-                                                         int ks, int nfr, int8_t* __restrict__ T, int32_t* __restrict__ E) {
+                                                         int ks, int nfr, int8_t* __restrict__ T, int32_t* __restrict__ E,
+                                                         unsigned* __restrict__ scan) {
     const int tid = threadIdx.x, r8 = tid & 7, w = tid >> 3, f = blockIdx.x, c = f * 8 + r8;
     const ulonglong2* src = reinterpret_cast<const ulonglong2*>(B);
     ulonglong2 v[4];
@@ -81,6 +116,8 @@ __global__ __launch_bounds__(512) void gate_split_kernel(const double* __restric
         mx_im = b > mx_im ? b : mx_im;
     }
     __shared__ unsigned long long colmax[64][8][2];
+    __shared__ unsigned lost_lds[4];
+    if (scan && tid < 4) lost_lds[tid] = 0u;
     const int words = blockDim.x >> 3;   // 32 (k <= 128) or 64
     colmax[w][r8][0] = mx_re;
     colmax[w][r8][1] = mx_im;
@@ -95,6 +132,28 @@ __global__ __launch_bounds__(512) void gate_split_kernel(const double* __restric
         E[f * 16 + 8 + r8] = e_im;
         E[nfr * 16 + f * 16 + r8] = e_im;
         E[nfr * 16 + f * 16 + 8 + r8] = e_re;
+    }
+    if (scan) {
+        // the bits the fragment's columns lose with s and with s - 1 slices (Section 4.4): [re s, re s - 1, im s, im s - 1][nfr]
+        unsigned lost[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            uint32_t z, L;
+            loss_position(v[u].x, e_re, z, L);
+            lost[0] += lost_bits(z, L, s);
+            lost[1] += lost_bits(z, L, s - 1);
+            loss_position(v[u].y, e_im, z, L);
+            lost[2] += lost_bits(z, L, s);
+            lost[3] += lost_bits(z, L, s - 1);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) lost[i] += __shfl_xor(lost[i], off, 64);
+            if ((tid & 63) == 0 && lost[i]) atomicAdd(&lost_lds[i], lost[i]);
+        }
+        __syncthreads();
+        if (tid < 4) scan[tid * nfr + f] = lost_lds[tid];
     }
     if (4 * w >= kGateStep * ks) return;
     const int64_t slice = (int64_t)nfr * ks * kFragBytes, tensor = (int64_t)s * slice;
@@ -125,7 +184,10 @@ __global__ __launch_bounds__(512) void gate_split_kernel(const double* __restric
 // ---------------------------------------------------------------------------- the product
 // S slices; CLS, the size class of k and n: 0 up to 64 (one step of 64 positions, eight fragments of B, eight wavefronts),
 // 1 up to 128 (two steps, sixteen fragments), 2 up to 256 (four steps, 32 fragments, sixteen wavefronts; up to eight slices).
-template <int S, int CLS>
+// SCAN: the kernel also counts, for the two planes of Z, what the slice-count choice needs to know about S and S - 1
+// slices (Section 4.4; five counters per plane and tile, added up by gate_scan_reduce_kernel), so that a caller who
+// guessed S can have the guess checked without another pass over Z.
+template <int S, int CLS, bool SCAN>
 __global__ __launch_bounds__(CLS == 2 ? 1024 : 512) __attribute__((amdgpu_waves_per_eu(S <= kBand ? 4 : 2, S <= kBand ? 4 : 2)))
 void gate_kernel(const GateArgs g) {
     constexpr bool WIDE = S > 9;   // the slices beyond the ninth come from the lower word of the fixed-point fraction
@@ -136,6 +198,7 @@ void gate_kernel(const GateArgs g) {
     // behind the two planes: exponents of the tile's rows, [plane][32], then those of the gate's fragments, [tensor][NFR][16]
     int* ex = reinterpret_cast<int*>(lds + 2 * PLANE);
     int* ex_gate = ex + 2 * kGateRows;
+    unsigned* scan_lds = reinterpret_cast<unsigned*>(ex_gate + 2 * NFR * 16);   // SCAN: [plane][5] counters of the tile
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t row_tile = (int64_t)blockIdx.x * kGateRows;
@@ -169,6 +232,10 @@ void gate_kernel(const GateArgs g) {
         constexpr int LPR = NT / kGateRows, W = KS * 16 / LPR;
         const int lrow = tid / LPR, cl = tid % LPR;
         for (int i = tid; i < 2 * NFR * 16; i += NT) ex_gate[i] = g.E[i];
+        if constexpr (SCAN) {
+            if (tid < 2 * kScanCounters) scan_lds[tid] = 0u;
+            __syncthreads();
+        }
         const int64_t row = row_tile + lrow;
         const bool live = row < g.m;
         const ulonglong2* src = reinterpret_cast<const ulonglong2*>(g.Z) + (live ? row : 0) * g.ldz;
@@ -225,6 +292,7 @@ void gate_kernel(const GateArgs g) {
             ex[lrow] = e_re;
             ex[kGateRows + lrow] = e_im;
         }
+        ScanCount cnt_re = {}, cnt_im = {};
         auto emit = [&](auto normal_tag) __attribute__((always_inline)) {
 #pragma unroll
             for (int j = 0; j < W; ++j) {
@@ -241,6 +309,12 @@ void gate_kernel(const GateArgs g) {
                 }
                 const SignMask sr = sign_mask(v[j][0].x, v[j][1].x, v[j][2].x, v[j][3].x);
                 const SignMask si = sign_mask(v[j][0].y, v[j][1].y, v[j][2].y, v[j][3].y);
+                if constexpr (SCAN) {
+                    const unsigned long long re4[4] = {v[j][0].x, v[j][1].x, v[j][2].x, v[j][3].x};
+                    const unsigned long long im4[4] = {v[j][0].y, v[j][1].y, v[j][2].y, v[j][3].y};
+                    scan_count4<S>(cnt_re, re4, e_re);
+                    scan_count4<S>(cnt_im, im4, e_im);
+                }
                 const int word = cl + LPR * j;   // sixteen words to a step
                 unsigned char* dst = lds + ((word >> 4) * 2 + (lrow >> 4)) * kFragBytes + frag_offset(lrow & 15, (word & 15) * 4);
                 static_for<1, S + 1>([&](auto pc) __attribute__((always_inline)) {
@@ -253,8 +327,21 @@ void gate_kernel(const GateArgs g) {
         };
         if (normal) emit(std::true_type{});
         else emit(std::false_type{});
+        if constexpr (SCAN) {
+            // sums over the rows of 16 lanes, then one LDS add per row of lanes and counter
+            unsigned c[2 * kScanCounters] = {cnt_re.sv_g, cnt_re.sz_g, cnt_re.sv_h, cnt_re.sz_h, cnt_re.bits,
+                                             cnt_im.sv_g, cnt_im.sz_g, cnt_im.sv_h, cnt_im.sz_h, cnt_im.bits};
+#pragma unroll
+            for (int i = 0; i < 2 * kScanCounters; ++i) {
+                c[i] = row_sum_step<1>(row_sum_step<2>(row_sum_step<4>(row_sum_step<8>(c[i]))));
+                if ((lane & 15) == 0 && c[i]) atomicAdd(&scan_lds[i], c[i]);
+            }
+        }
     }
     __syncthreads();
+    if constexpr (SCAN) {
+        if (tid < 2 * kScanCounters) g.scan[(int64_t)tid * gridDim.x + blockIdx.x] = scan_lds[tid];   // [counter][tile]
+    }
 
     // ---- the products
     // accumulator layout of the 16x16 MFMA: lane holds column (lane % 16); register u holds row 4 (lane / 16) + u
@@ -346,16 +433,53 @@ void gate_kernel(const GateArgs g) {
     }
 }
 
-template <int S, int CLS>
+// The counters of all tiles ([counter][tile]) and of the gate's fragments (behind them, [4][nfr]) -> the bits the two
+// planes of Z (planes 0, 1) and of B (planes 2, 3) lose with s and with s - 1 slices: out[plane * 16 + s - 1] and
+// out[plane * 16 + s - 2], the layout of the slice-count sums. `out` may be mapped host memory. One workgroup.
+__global__ __launch_bounds__(1024) void gate_scan_reduce_kernel(const unsigned* __restrict__ partials, int64_t tiles, int nfr,
+                                                                int s, unsigned long long* __restrict__ out) {
+    __shared__ unsigned long long sums[2 * kScanCounters + 4];
+    if (threadIdx.x < 2 * kScanCounters + 4) sums[threadIdx.x] = 0ull;
+    __syncthreads();
+    unsigned long long mine[2 * kScanCounters] = {};
+    for (int64_t t = threadIdx.x; t < tiles; t += 1024)
+#pragma unroll
+        for (int i = 0; i < 2 * kScanCounters; ++i) mine[i] += partials[i * tiles + t];
+#pragma unroll
+    for (int i = 0; i < 2 * kScanCounters; ++i) {
+        unsigned long long v = mine[i];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+        if ((threadIdx.x & 63) == 0 && v) atomicAdd(&sums[i], v);
+    }
+    const unsigned* of_gate = partials + 2 * kScanCounters * tiles;
+    if ((int)threadIdx.x < 4 * nfr) atomicAdd(&sums[2 * kScanCounters + threadIdx.x / nfr], (unsigned long long)of_gate[threadIdx.x]);
+    __syncthreads();
+    if (threadIdx.x < 2) {
+        const unsigned long long* c = sums + threadIdx.x * kScanCounters;
+        out[threadIdx.x * OZIMMU_MAX_SLICES + s - 1] = (c[0] - c[1] + c[4]) >> 1;
+        if (s > 1) out[threadIdx.x * OZIMMU_MAX_SLICES + s - 2] = (c[2] - c[3] + c[4]) >> 1;
+    } else if (threadIdx.x < 4) {
+        const unsigned long long* c = sums + 2 * kScanCounters + 2 * (threadIdx.x - 2);
+        out[threadIdx.x * OZIMMU_MAX_SLICES + s - 1] = c[0];
+        if (s > 1) out[threadIdx.x * OZIMMU_MAX_SLICES + s - 2] = c[1];
+    }
+}
+
+template <int S, int CLS, bool SCAN>
 hipError_t launch_gate(const GateArgs& g, hipStream_t st) {
-    constexpr int lds = 2 * S * (1 << CLS) * 2 * kFragBytes + (2 * kGateRows + 2 * (8 << CLS) * 16) * (int)sizeof(int);
+    constexpr int lds = 2 * S * (1 << CLS) * 2 * kFragBytes + (2 * kGateRows + 2 * (8 << CLS) * 16 + 2 * kScanCounters + 2) * (int)sizeof(int);
     static_assert(lds <= 160 * 1024 && (S > kBand || CLS == 2 || 2 * lds <= 160 * 1024),
                   "the LDS of a compute unit: two workgroups of eight wavefronts up to eight slices, else one workgroup");
-    hipError_t e = allow_dynamic_lds<&gate_kernel<S, CLS>>(lds);
+    hipError_t e = allow_dynamic_lds<&gate_kernel<S, CLS, SCAN>>(lds);
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((g.m + kGateRows - 1) / kGateRows);
-    gate_kernel<S, CLS><<<dim3(grid), dim3(CLS == 2 ? 1024 : 512), lds, st>>>(g);
+    gate_kernel<S, CLS, SCAN><<<dim3(grid), dim3(CLS == 2 ? 1024 : 512), lds, st>>>(g);
     return hipGetLastError();
+}
+template <int S, int CLS>
+hipError_t launch_gate(const GateArgs& g, hipStream_t st) {
+    return g.scan ? launch_gate<S, CLS, true>(g, st) : launch_gate<S, CLS, false>(g, st);
 }
 
 inline int gate_class(int64_t k, int64_t n) { return k > 128 || n > 128 ? 2 : k > 64 || n > 64 ? 1 : 0; }
@@ -374,16 +498,23 @@ size_t gate_scratch_bytes(int64_t n, int64_t k, int s) {
     return 2 * nfr * 16 * sizeof(int32_t) + (size_t)2 * s * nfr * ks * kFragBytes;
 }
 
+size_t gate_scan_bytes(int64_t m) {
+    return ((size_t)((m + kGateRows - 1) / kGateRows) * 2 * kScanCounters + 4 * (8 << 2)) * sizeof(unsigned);
+}
+
 hipError_t launch_gate_product(const double* Z, int64_t ldz, int64_t m, int64_t k, int64_t n, const double* B, int64_t ldb,
-                               int s, void* scratch, double* Cz, int64_t ldcz, hipStream_t st) {
+                               int s, void* scratch, double* Cz, int64_t ldcz, hipStream_t st, unsigned* scan_partials,
+                               unsigned long long* scan_sums) {
     if (m <= 0) return hipSuccess;
     if (!gate_product_applies(Z, B, Cz, n, k, s)) return hipErrorInvalidValue;
     const int cls = gate_class(k, n), ks = 1 << cls, nfr = 8 << cls;
     int32_t* E = static_cast<int32_t*>(scratch);
     int8_t* T = reinterpret_cast<int8_t*>(E + 2 * nfr * 16);
     const unsigned split_threads = cls == 2 ? 512 : 256;   // a thread per word of four positions and column of the fragment
-    if (s > 9) gate_split_kernel<true><<<dim3(nfr), dim3(split_threads), 0, st>>>(B, ldb, (int)k, (int)n, s, ks, nfr, T, E);
-    else gate_split_kernel<false><<<dim3(nfr), dim3(split_threads), 0, st>>>(B, ldb, (int)k, (int)n, s, ks, nfr, T, E);
+    const int64_t tiles = (m + kGateRows - 1) / kGateRows;
+    unsigned* scan_gate = scan_partials ? scan_partials + 2 * kScanCounters * tiles : nullptr;
+    if (s > 9) gate_split_kernel<true><<<dim3(nfr), dim3(split_threads), 0, st>>>(B, ldb, (int)k, (int)n, s, ks, nfr, T, E, scan_gate);
+    else gate_split_kernel<false><<<dim3(nfr), dim3(split_threads), 0, st>>>(B, ldb, (int)k, (int)n, s, ks, nfr, T, E, scan_gate);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     GateArgs g{};
@@ -396,15 +527,21 @@ hipError_t launch_gate_product(const double* Z, int64_t ldz, int64_t m, int64_t 
     g.E = E;
     g.Cz = Cz;
     g.ldcz = ldcz;
+    g.scan = scan_partials;
+    e = hipErrorInvalidValue;
     switch (s) {
-#define OZ_CASE(S_) case S_: return cls == 2 ? launch_gate<S_, 2>(g, st) : cls == 1 ? launch_gate<S_, 1>(g, st) : launch_gate<S_, 0>(g, st);
+#define OZ_CASE(S_) case S_: e = cls == 2 ? launch_gate<S_, 2>(g, st) : cls == 1 ? launch_gate<S_, 1>(g, st) : launch_gate<S_, 0>(g, st); break;
         OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8)
 #undef OZ_CASE
-#define OZ_CASE(S_) case S_: return cls == 1 ? launch_gate<S_, 1>(g, st) : launch_gate<S_, 0>(g, st);
+#define OZ_CASE(S_) case S_: e = cls == 1 ? launch_gate<S_, 1>(g, st) : launch_gate<S_, 0>(g, st); break;
         OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16)
 #undef OZ_CASE
     }
-    return hipErrorInvalidValue;
+    if (e == hipSuccess && scan_partials) {
+        gate_scan_reduce_kernel<<<dim3(1), dim3(1024), 0, st>>>(scan_partials, tiles, nfr, s, scan_sums);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 }  // namespace ozimmu

@@ -79,6 +79,7 @@ struct GateArgs {
     const int32_t* E;        // and their exponents
     double* Cz;              // m x n complex elements, interleaved, 16-byte aligned
     int64_t ldcz;            // in complex elements
+    unsigned* scan;          // not null: per tile of 32 rows, ten counters for the check of the slice count (gate.hip)
 };
 // Whether that kernel serves a complex product Z (m x k) times B (k x n) -> Cz with s slices.
 bool gate_product_applies(const double* Z, const double* B, const double* Cz, int64_t n, int64_t k, int s);
@@ -86,8 +87,14 @@ bool gate_product_applies(const double* Z, const double* B, const double* Cz, in
 size_t gate_scratch_bytes(int64_t n, int64_t k, int s);
 // Cz = Z . B: splits B (k x n complex elements, leading dimension ldb in complex elements) into `scratch`
 // (16-byte aligned, gate_scratch_bytes), then the product kernel. Only where gate_product_applies.
+// scan_partials (optional; gate_scan_bytes(m) bytes of device memory): the two kernels also count what the check of s
+// as the automatic slice count needs, and scan_sums[plane * 16 + s - 1], [.. + s - 2] (planes 0, 1: real and imaginary
+// part of Z, 2, 3: of B; the layout of the slice-count sums; device or mapped host memory) receive the bits the planes
+// lose with s and with s - 1 slices.
+size_t gate_scan_bytes(int64_t m);
 hipError_t launch_gate_product(const double* Z, int64_t ldz, int64_t m, int64_t k, int64_t n, const double* B, int64_t ldb,
-                               int s, void* scratch, double* Cz, int64_t ldcz, hipStream_t st);
+                               int s, void* scratch, double* Cz, int64_t ldcz, hipStream_t st,
+                               unsigned* scan_partials = nullptr, unsigned long long* scan_sums = nullptr);
 
 // negate: emit the slices of -A (-B) instead: same exponents, every slice with the opposite sign
 // (how a conjugated operand's imaginary plane is split)

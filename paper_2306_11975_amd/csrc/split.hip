@@ -336,24 +336,6 @@ __device__ __forceinline__ void loss_clear(LossAcc& a) {
     for (int s = 0; s < OZIMMU_MAX_SLICES; ++s) a.sad_v[s] = a.sad_z[s] = 0u;
     a.bits = 0u;
 }
-// z (clamped) and L of one element; both 0 for a zero.
-__device__ __forceinline__ void loss_position(unsigned long long bits, int E, uint32_t& z, uint32_t& L) {
-    const unsigned long long mag = bits & kAbsMask;
-    const int e = (int)(mag >> 52);
-    int zz = E + 1022 - e, LL = 53;
-    if (e == 0) {                       // zero, or subnormal with leading bit b of the stored field
-        if (mag == 0) {
-            zz = 0;
-            LL = 0;
-        } else {
-            const int b = 63 - __clzll((long long)mag);
-            LL = b + 1;
-            zz = E + 1073 - b;
-        }
-    }
-    z = (uint32_t)(zz < 0 ? 0 : zz > OZIMMU_SLICE_BITS * OZIMMU_MAX_SLICES ? OZIMMU_SLICE_BITS * OZIMMU_MAX_SLICES : zz);
-    L = (uint32_t)LL;
-}
 // Four elements that share the exponent E (zeros count nothing: v = z = L = 0).
 __device__ __forceinline__ void loss_add4(LossAcc& a, const unsigned long long b[4], int E) {
     uint32_t pz = 0, pl = 0;

@@ -81,5 +81,33 @@ __device__ __forceinline__ unsigned row_max_step(unsigned x) {
     return o > x ? o : x;
 }
 
+// Slice-count scan (Section 4.4, automatic choice of the number of slices): with the row or column exponent E, z is the
+// distance of an element's leading bit below the binary point (clamped to 7 x 16) and L the number of bits it stores;
+// s slices lose max(0, z + L - 7 s) - max(0, z - 7 s) of them.
+// z (clamped) and L of one element; both 0 for a zero.
+__device__ __forceinline__ void loss_position(unsigned long long bits, int E, uint32_t& z, uint32_t& L) {
+    const unsigned long long mag = bits & kAbsMask;
+    const int e = (int)(mag >> 52);
+    int zz = E + 1022 - e, LL = 53;
+    if (e == 0) {                       // zero, or subnormal with leading bit b of the stored field
+        if (mag == 0) {
+            zz = 0;
+            LL = 0;
+        } else {
+            const int b = 63 - __clzll((long long)mag);
+            LL = b + 1;
+            zz = E + 1073 - b;
+        }
+    }
+    z = (uint32_t)(zz < 0 ? 0 : zz > OZIMMU_SLICE_BITS * OZIMMU_MAX_SLICES ? OZIMMU_SLICE_BITS * OZIMMU_MAX_SLICES : zz);
+    L = (uint32_t)LL;
+}
+
+// sum over the row of 16 lanes, left in every lane of it (rotations by 8, 4, 2, 1)
+template <int N>
+__device__ __forceinline__ unsigned row_sum_step(unsigned x) {
+    return x + (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x120 + N, 0xf, 0xf, false);
+}
+
 }  // namespace
 }  // namespace ozimmu

@@ -25,7 +25,7 @@ EXPORTS = (
     "ozimmu_status_string", "ozimmu_slice_geometry", "ozimmu_slice_offset", "ozimmu_split_rows", "ozimmu_split_cols",
     "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_static", "ozimmu_dgemm_stage",
     "ozimmu_launch_plan", "ozimmu_dgemm_dd", "ozimmu_dgemm_blas", "ozimmu_zgemm_blas_workspace_bytes", "ozimmu_zgemm_blas",
-    "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices", "ozimmu_auto_num_slices_blas",
+    "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices", "ozimmu_auto_num_slices_blas", "ozimmu_zgemm_auto",
 )
 PROBE_EXPORTS = ("ozimmu_probe_int8_mfma",)      # include/ozimmu_probe.h: measurement utility, not the product path
 
@@ -96,6 +96,9 @@ def lib() -> ctypes.CDLL:
         L.ozimmu_auto_num_slices_blas.restype = i32
         L.ozimmu_auto_num_slices_blas.argtypes = [ctypes.c_char, ctypes.c_char, i64, i64, i64, vp, i64, vp, i64, i32,
                                                   ctypes.c_double, i32, vp, sz, ctypes.POINTER(i32), vp, vp]
+        L.ozimmu_zgemm_auto.restype = i32
+        L.ozimmu_zgemm_auto.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, ctypes.c_double, i32, i32, vp, sz, vp, sz,
+                                        ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
         dp = ctypes.POINTER(ctypes.c_double)
         L.ozimmu_probe_int8_mfma.restype = i32
         L.ozimmu_probe_int8_mfma.argtypes = [i32, i32, i32, dp, dp]
@@ -294,6 +297,26 @@ def auto_num_slices(A, B, threshold: float, max_slices: int = MAX_SLICES, scratc
                                         int(max_slices), _ptr(scratch), scratch.numel(), ctypes.byref(s),
                                         sums.ctypes.data, _stream(stream)))
     return s.value, sums
+
+
+def zgemm_auto(A, B, C, threshold: float, guess: int = 0, max_slices: int = MAX_SLICES, workspace=None, scratch=None,
+               stream=None):
+    """C = A . B (complex128 device tensors) with the slice count ozimmu_auto_num_slices would choose, in one call (see
+    ozimmu.h); `guess` is the expected count (0: none). Returns (s, guess_confirmed). Waits for the stream."""
+    import torch
+
+    m, k = A.shape
+    n = B.shape[1]
+    if workspace is None:
+        need = max(workspace_bytes(m, n, k, s, True) for s in range(1, max_slices + 1))
+        workspace = torch.empty(max(need, WORKSPACE_ALIGN), dtype=torch.uint8, device=A.device)
+    if scratch is None:
+        scratch = torch.empty(max(auto_scratch_bytes(n), WORKSPACE_ALIGN), dtype=torch.uint8, device=A.device)
+    s, confirmed = ctypes.c_int(), ctypes.c_int()
+    _check(lib().ozimmu_zgemm_auto(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C), _ld(C, n), float(threshold),
+                                   int(max_slices), int(guess), _ptr(workspace), workspace.numel(), _ptr(scratch),
+                                   scratch.numel(), ctypes.byref(s), ctypes.byref(confirmed), _stream(stream)))
+    return s.value, bool(confirmed.value)
 
 
 def auto_num_slices_blas(transa: str, transb: str, m: int, n: int, k: int, A, lda: int, B, ldb: int, is_complex: bool,

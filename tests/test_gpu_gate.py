@@ -233,3 +233,43 @@ def test_gate_seeded_random_shapes_and_values():
         want = oracle.zgemm(A, B, s)
         assert np.array_equal(bits(got.real.copy()), bits(want.real.copy())), (it, m, n, k, s)
         assert np.array_equal(bits(got.imag.copy()), bits(want.imag.copy())), (it, m, n, k, s)
+
+
+# ------------------------------------------------------------------ slice count chosen and product formed in one call
+def check_zgemm_auto(A, B, threshold, guesses):
+    """ozimmu_zgemm_auto must return the count ozimmu_auto_num_slices chooses (= the oracle's) and the product with that
+    count, whatever the guess; a right guess on a shape of the one-kernel path must be confirmed (A read once)."""
+    s_want, _ = oracle.auto_num_slices(A, B, threshold)
+    want = oracle.zgemm(A, B, s_want)
+    m, k = A.shape
+    n = B.shape[1]
+    dA, dB = torch.from_numpy(np.ascontiguousarray(A)).to(DEV), torch.from_numpy(np.ascontiguousarray(B)).to(DEV)
+    gate_shape = max(k, n) <= (256 if s_want <= 8 else 128)
+    for guess in guesses:
+        guess = s_want + guess[1] if isinstance(guess, tuple) else guess
+        C = torch.full((m, n), complex(float("nan"), float("nan")), dtype=torch.complex128, device=DEV)
+        s_got, confirmed = ozimmu.zgemm_auto(dA, dB, C, threshold, guess=guess)
+        torch.cuda.synchronize()
+        assert s_got == s_want, (guess, s_got, s_want)
+        assert_same(C.cpu().numpy(), want)
+        assert confirmed == (guess == s_want and gate_shape), (guess, s_want, confirmed)
+
+
+@pytest.mark.parametrize("m,n,k", [(3000, 64, 64), (500, 128, 100), (200, 256, 256), (70, 16, 16), (33, 1, 5)])
+@pytest.mark.parametrize("threshold", [0.0, 1.0, 6.0])
+def test_zgemm_auto_with_right_and_wrong_guesses(m, n, k, threshold):
+    A = wl.gaussian_complex(m, k, seed=m + n)
+    A /= np.linalg.norm(A)
+    B = wl.unit_column_complex(k, n, seed=k + 3)
+    check_zgemm_auto(A, B, threshold, guesses=[("rel", 0), ("rel", 1), ("rel", -1), 0, 1, 16])
+
+
+def test_zgemm_auto_adversarial_values_and_other_shapes():
+    """Zero and subnormal rows in the counters of the product kernel; shapes the one-kernel path does not serve."""
+    A = wl.adversarial_matrix(96, 64, seed=51) + 1j * wl.adversarial_matrix(96, 64, seed=52)
+    B = wl.adversarial_matrix(64, 40, seed=53) + 1j * wl.adversarial_matrix(64, 40, seed=54)
+    for threshold in (0.0, 2.0, 30.0):
+        check_zgemm_auto(A, B, threshold, guesses=[("rel", 0), ("rel", -1), 7])
+    A = wl.gaussian_complex(70, 300, seed=55)
+    B = wl.unit_column_complex(300, 50, seed=56)
+    check_zgemm_auto(A, B, 1.0, guesses=[("rel", 0), 0])
