@@ -117,6 +117,24 @@ def test_intercepted_zgemm_is_the_ozaki_result(tmp_path, api):
     assert np.array_equal(bits(got), bits(oracle.zgemm_blas("C", "N", 1.0, A, B, 0.0, C0, s_auto)))
 
 
+@pytest.mark.parametrize("threshold", [0.0, 1.0])
+def test_small_complex_gate_in_automatic_mode_takes_one_call_per_product(tmp_path, threshold):
+    """A gate of 64 x 64 on a wide state, plain product, three times: the count of the call before is the guess of the
+    next (ozimmu_zgemm_auto); count and result stay those of the two-call path, i.e. the oracle's."""
+    rng = np.random.default_rng(23)
+    m, n, k = 64, 2500, 64
+    opA = wl.unit_column_complex(m, k, seed=24)
+    opB = rng.standard_normal((k, n)) + 1j * rng.standard_normal((k, n))
+    opB /= np.linalg.norm(opB)
+    C0 = np.zeros((m, n), dtype=np.complex128)
+    s_auto = oracle.auto_num_slices(opA, opB, threshold)[0]
+    got, log = run_client(tmp_path, 1, "N", "N", 1.0, 0.0, opA, opB, C0, mode="auto", repeats=3,
+                          extra_env={"OZIMMU_THRESHOLD": str(threshold)})
+    assert log.count(f"slices={s_auto} (auto) [one call]") == 1                       # no guess yet
+    assert log.count(f"slices={s_auto} (auto) [one call, guess confirmed]") == 2
+    assert np.array_equal(bits(got), bits(oracle.zgemm_blas("N", "N", 1.0, opA, opB, 0.0, C0, s_auto)))
+
+
 @pytest.mark.parametrize("api,cplx", [(2, False), (2, True), (3, False), (3, True)])
 def test_all_fp64_gemm_ex_calls_are_intercepted_too(tmp_path, api, cplx):
     name = {2: "rocblas_gemm_ex", 3: "hipblasGemmEx"}[api]
@@ -286,6 +304,9 @@ def test_unmodified_simulator_under_the_preload_list(tmp_path):
         got, gates, log = run("auto", threshold)
         picked = [int(x) for x in re.findall(r"hipblasZgemm \S+ m=\d+ n=\d+ k=\d+ slices=(\d+) \(auto\)", log)]
         assert len(picked) == 8, log[-1500:]             # 4 layers of 2 gates
+        # every gate through the one-call path, its guess (the count of the gate before) confirmed whenever it was right
+        assert log.count("[one call") == 8, log[-1500:]
+        assert log.count("guess confirmed") == sum(a == b for a, b in zip(picked, picked[1:])), log[-1500:]
         assert lo <= max(picked) <= hi
         # the oracle's replay of the same circuit: same slice count at every gate, same final state bit for bit
         assert np.array_equal(gates, ref_gates)
