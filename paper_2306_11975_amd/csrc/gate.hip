@@ -441,10 +441,25 @@ __global__ __launch_bounds__(1024) void gate_scan_reduce_kernel(const unsigned* 
     __shared__ unsigned long long sums[2 * kScanCounters + 4];
     if (threadIdx.x < 2 * kScanCounters + 4) sums[threadIdx.x] = 0ull;
     __syncthreads();
+    // eighty loads in flight per thread (the words come from beyond the L2, written by other XCDs); a tile index past
+    // the end reads the last tile and adds nothing
     unsigned long long mine[2 * kScanCounters] = {};
-    for (int64_t t = threadIdx.x; t < tiles; t += 1024)
+    constexpr int U = 8;
+    for (int64_t base = threadIdx.x; base < tiles; base += 1024 * U) {
+        unsigned v[U][2 * kScanCounters];
 #pragma unroll
-        for (int i = 0; i < 2 * kScanCounters; ++i) mine[i] += partials[i * tiles + t];
+        for (int u = 0; u < U; ++u) {
+            const int64_t t = base + 1024 * u, tc = t < tiles ? t : tiles - 1;
+#pragma unroll
+            for (int i = 0; i < 2 * kScanCounters; ++i) v[u][i] = partials[i * tiles + tc];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool in = base + 1024 * u < tiles;
+#pragma unroll
+            for (int i = 0; i < 2 * kScanCounters; ++i) mine[i] += in ? v[u][i] : 0u;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < 2 * kScanCounters; ++i) {
         unsigned long long v = mine[i];
