@@ -32,19 +32,26 @@ def apply_gate(state, U, first_qubit, d, N, product):
     return out.reshape([2] * N).permute(inv).reshape(-1).contiguous()
 
 
+@pytest.mark.parametrize("one_call", [False, True])
 @pytest.mark.parametrize("threshold,max_rel", [(0.0, 5e-14), (1.0, 5e-13)])
-def test_brickwork_random_unitary_circuit(threshold, max_rel):
+def test_brickwork_random_unitary_circuit(threshold, max_rel, one_call):
+    """one_call: count and product by ozimmu_zgemm_auto, the count of the gate before as its guess."""
     N, d, layers = 16, 6, 4
     gen = torch.Generator().manual_seed(11)
-    picked = []
+    picked, confirmed = [], []
 
     def ozaki(M, V):
         m, k = M.shape
         n = V.shape[1]
-        s, _ = ozimmu.auto_num_slices(M, V, threshold)
-        picked.append(s)
         C = torch.empty((m, n), dtype=torch.complex128, device="cuda")
-        ozimmu.zgemm(M, V, C, s, ozimmu.alloc_workspace(m, n, k, s, is_complex=True))
+        if one_call:
+            s, ok = ozimmu.zgemm_auto(M, V, C, threshold, guess=picked[-1] if picked else 0)
+            confirmed.append(ok)
+            assert ok == (bool(picked) and picked[-1] == s)
+        else:
+            s, _ = ozimmu.auto_num_slices(M, V, threshold)
+            ozimmu.zgemm(M, V, C, s, ozimmu.alloc_workspace(m, n, k, s, is_complex=True))
+        picked.append(s)
         # the oracle on the same operands: same slice count, same product, bit for bit
         Mh, Vh = M.cpu().numpy(), V.cpu().numpy()
         assert s == oracle.auto_num_slices(Mh, Vh, threshold)[0]
@@ -74,3 +81,5 @@ def test_brickwork_random_unitary_circuit(threshold, max_rel):
         assert max(picked) >= 9
     else:
         assert max(picked) <= 10
+    if one_call:
+        assert any(confirmed)
