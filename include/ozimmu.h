@@ -20,7 +20,7 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). All work is
  *     enqueued on it; no entry point synchronises, allocates or frees device memory, or
  *     keeps state between calls (exceptions, stated where they are declared:
- *     ozimmu_auto_num_slices and ozimmu_zgemm_auto return a value to the host and wait for the stream;
+ *     ozimmu_auto_num_slices, ozimmu_dgemm_auto and ozimmu_zgemm_auto return a value to the host and wait for the stream;
  *     ozimmu_dgemm_static uses the library's own scratch array; the library remembers per
  *     device that it has raised a kernel's dynamic LDS limit). Calls that share a workspace must
  *     be stream-ordered.
@@ -277,19 +277,28 @@ ozimmu_status_t ozimmu_auto_num_slices(int64_t m, int64_t n, int64_t k, const do
                                        int* num_slices, uint64_t* loss_sums, void* stream);
 
 /*
- * ozimmu_auto_num_slices followed by ozimmu_zgemm with the count it chose, as one call: *num_slices
- * receives the count, C the product; both are exactly what the two calls give. `guess` is the
- * caller's expectation of the count (say, the one the previous product of this shape took; 0: none).
- * Where ozimmu_zgemm runs as the kernel that splits A on the fly (see there) the product is formed
- * with `guess` at once, and that kernel counts on its way over A what the check of the guess needs;
- * if the guess was right, A has been read once instead of twice (*guess_confirmed = 1; optional
- * HOST pointer). Otherwise, and for every other shape, the count is chosen first and the product
- * formed afterwards. workspace: at least the largest ozimmu_workspace_bytes(m, n, k, s, 1) over
+ * ozimmu_auto_num_slices followed by ozimmu_dgemm / ozimmu_zgemm with the count it chose, as one call:
+ * *num_slices receives the count, C the product; both are exactly what the two calls give. `guess` is
+ * the caller's expectation of the count (say, the one the previous product of this shape took; 0: none).
+ * With a guess the product is formed with it at once:
+ *   - where ozimmu_zgemm runs as the kernel that splits A on the fly (see there), that kernel and the
+ *     splitter of B count on their way what the check of the guess needs: a right guess means A has
+ *     been read once instead of twice;
+ *   - for every other shape the scans of ozimmu_auto_num_slices, the copy of their sums and the product
+ *     are queued together and waited for once: a right guess saves the wait between choice and product.
+ * A right guess sets *guess_confirmed = 1 (optional HOST pointer). A wrong one is followed by the
+ * product with the count chosen, so it costs one product; without a guess the count is chosen first.
+ * workspace: at least the largest ozimmu_workspace_bytes(m, n, k, s, is_complex) over
  * s = 1 .. max_slices; scratch: as for ozimmu_auto_num_slices. Waits for the stream like
- * ozimmu_auto_num_slices; errors as there and as for ozimmu_zgemm. The first call of a thread
- * allocates 512 bytes of mapped host memory (where the last kernel leaves the sums the check reads),
- * kept until the process ends.
+ * ozimmu_auto_num_slices; errors as there and as for ozimmu_dgemm. These calls and
+ * ozimmu_auto_num_slices receive their sums in 512 bytes of mapped host memory that the first such
+ * call of a thread allocates and that is kept until the process ends.
  */
+ozimmu_status_t ozimmu_dgemm_auto(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                                  const double* B, int64_t ldb, double* C, int64_t ldc, double threshold,
+                                  int max_slices, int guess, void* workspace, size_t workspace_bytes,
+                                  void* scratch, size_t scratch_bytes, int* num_slices,
+                                  int* guess_confirmed, void* stream);
 ozimmu_status_t ozimmu_zgemm_auto(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
                                   const double* B, int64_t ldb, double* C, int64_t ldc, double threshold,
                                   int max_slices, int guess, void* workspace, size_t workspace_bytes,

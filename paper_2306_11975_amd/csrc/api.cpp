@@ -238,42 +238,133 @@ unsigned long long* mapped_sums() {
     return p;
 }
 
+bool scratch_ok(const void* scratch, size_t scratch_bytes, int64_t scratch_cols) {
+    size_t need = 0;
+    ozimmu_auto_scratch_bytes(scratch_cols, &need);
+    return scratch && (reinterpret_cast<uintptr_t>(scratch) % OZIMMU_WORKSPACE_ALIGN) == 0 && scratch_bytes >= need;
+}
+
+// The scans of both operands and the copy of the 4 x 16 sums to `host`, all on the stream; nothing waits.
+hipError_t enqueue_scans(const ScanOperand& a, const ScanOperand& b, int is_complex, void* scratch, unsigned long long* host,
+                         hipStream_t st) {
+    unsigned long long* sums = static_cast<unsigned long long*>(scratch);          // [4][16]
+    unsigned long long* colmax = sums + 4 * OZIMMU_MAX_SLICES;
+    hipError_t e = launch_fill_u64(sums, 4 * OZIMMU_MAX_SLICES, 0ull, st);
+    if (e == hipSuccess) e = scan_operand(a, 0, is_complex, sums, colmax, st);
+    if (e == hipSuccess) e = scan_operand(b, 1, is_complex, sums, colmax, st);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(host, sums, 4 * OZIMMU_MAX_SLICES * sizeof(unsigned long long), hipMemcpyDeviceToHost, st);
+    return e;
+}
+
+// The smallest count whose sums of lost bits are within the threshold for every plane; max_slices if none.
+int pick_slices(const unsigned long long* host, int is_complex, double count_a, double count_b, double threshold,
+                int max_slices) {
+    const int parts = is_complex ? 2 : 1;
+    for (int s = 1; s <= max_slices; ++s) {
+        bool ok = true;
+        for (int p = 0; p < 2 * parts; ++p)
+            ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < parts ? count_a : count_b);
+        if (ok) return s;
+    }
+    return max_slices;
+}
+
 ozimmu_status_t auto_select(const ScanOperand& a, const ScanOperand& b, int64_t scratch_cols, int is_complex,
                             double threshold, int max_slices, void* scratch, size_t scratch_bytes, int* num_slices,
                             uint64_t* loss_sums, void* stream) {
     if (max_slices < 1 || max_slices > OZIMMU_MAX_SLICES || !(threshold >= 0.0)) return OZIMMU_ERR_BAD_SLICES;
     if (!num_slices) return OZIMMU_ERR_NULL;
     if ((a.rows > 0 && a.cols > 0 && !a.ptr) || (b.rows > 0 && b.cols > 0 && !b.ptr)) return OZIMMU_ERR_NULL;
-    size_t need = 0;
-    ozimmu_auto_scratch_bytes(scratch_cols, &need);
-    if (!scratch || (reinterpret_cast<uintptr_t>(scratch) % OZIMMU_WORKSPACE_ALIGN) != 0 || scratch_bytes < need)
-        return OZIMMU_ERR_WORKSPACE;
+    if (!scratch_ok(scratch, scratch_bytes, scratch_cols)) return OZIMMU_ERR_WORKSPACE;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    unsigned long long* sums = static_cast<unsigned long long*>(scratch);          // [4][16]
-    unsigned long long* colmax = sums + 4 * OZIMMU_MAX_SLICES;
-    const int parts = is_complex ? 2 : 1;
-    hipError_t e = launch_fill_u64(sums, 4 * OZIMMU_MAX_SLICES, 0ull, st);
-    if (e == hipSuccess) e = scan_operand(a, 0, is_complex, sums, colmax, st);
-    if (e == hipSuccess) e = scan_operand(b, 1, is_complex, sums, colmax, st);
-    unsigned long long host[4 * OZIMMU_MAX_SLICES];
-    if (e == hipSuccess) e = hipMemcpyAsync(host, sums, sizeof(host), hipMemcpyDeviceToHost, st);
+    unsigned long long pageable[4 * OZIMMU_MAX_SLICES];
+    unsigned long long* host = mapped_sums();
+    if (!host) host = pageable;
+    hipError_t e = enqueue_scans(a, b, is_complex, scratch, host, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) return OZIMMU_ERR_HIP;
 
-    const int planes = 2 * parts;
-    const double count_a = (double)a.rows * (double)a.cols, count_b = (double)b.rows * (double)b.cols;
-    int pick = max_slices;
-    for (int s = 1; s <= max_slices; ++s) {
-        bool ok = true;
-        for (int p = 0; p < planes; ++p)
-            ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < parts ? count_a : count_b);
-        if (ok) { pick = s; break; }
-    }
-    *num_slices = pick;
+    *num_slices = pick_slices(host, is_complex, (double)a.rows * (double)a.cols, (double)b.rows * (double)b.cols, threshold,
+                              max_slices);
     if (loss_sums)
-        for (int i = 0; i < planes * OZIMMU_MAX_SLICES; ++i) loss_sums[i] = host[i];
+        for (int i = 0; i < (is_complex ? 4 : 2) * OZIMMU_MAX_SLICES; ++i) loss_sums[i] = host[i];
     return OZIMMU_OK;
+}
+
+// Slice count and product in one call (see ozimmu_dgemm_auto / ozimmu_zgemm_auto in ozimmu.h).
+ozimmu_status_t gemm_auto(bool cplx, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
+                          int64_t ldb, double* C, int64_t ldc, double threshold, int max_slices, int guess, void* workspace,
+                          size_t workspace_bytes, void* scratch, size_t scratch_bytes, int* num_slices,
+                          int* guess_confirmed, void* stream) {
+    if (max_slices < 1 || max_slices > OZIMMU_MAX_SLICES || !(threshold >= 0.0)) return OZIMMU_ERR_BAD_SLICES;
+    if (!num_slices) return OZIMMU_ERR_NULL;
+    if (guess_confirmed) *guess_confirmed = 0;
+    // the workspace must serve whichever slice count comes out
+    Layout L{};
+    for (int s = 1; s <= max_slices; ++s) {
+        ozimmu_status_t rc = check_gemm_args(m, n, k, A, lda, B, ldb, C, ldc, s, workspace, workspace_bytes, cplx, &L);
+        if (rc != OZIMMU_OK) return rc;
+    }
+    if (!scratch_ok(scratch, scratch_bytes, n)) return OZIMMU_ERR_WORKSPACE;
+    auto product = [&](int s) {
+        return cplx ? ozimmu_zgemm(m, n, k, A, lda, B, ldb, C, ldc, s, workspace, workspace_bytes, stream)
+                    : ozimmu_dgemm(m, n, k, A, lda, B, ldb, C, ldc, s, workspace, workspace_bytes, stream);
+    };
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool have_guess = guess >= 1 && guess <= max_slices && m > 0 && n > 0 && k > 0;
+    const double count_a = (double)m * (double)k, count_b = (double)k * (double)n;
+    unsigned long long* host = have_guess ? mapped_sums() : nullptr;                   // [4][16]
+    if (host && cplx && gate_product_applies(A, B, C, n, k, guess)) {
+        // Multiply with the guessed count; the kernels that split B and that walk over A count, on their way, what the
+        // check of the guess needs (the bits each plane loses with `guess` and with `guess - 1` slices) and a last small
+        // kernel writes the eight sums into mapped host memory: no pass of its own over A, no copy.
+        L = make_layout(m, n, k, guess, true);
+        if (gate_scan_bytes(m) > L.sa_bytes) return OZIMMU_ERR_WORKSPACE;
+        unsigned char* ws = static_cast<unsigned char*>(workspace);
+        // the per-tile counters wait where the slices of A would be (that region is not used on this path)
+        hipError_t e = launch_gate_product(A, lda, m, k, n, B, ldb, guess, ws + L.off_gate, C, ldc, st,
+                                           reinterpret_cast<unsigned*>(ws + L.off_sa[0]), host);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return OZIMMU_ERR_HIP;
+        auto within = [&](int s) {   // every plane's loss with s slices within the threshold (the rule of ozimmu_auto_num_slices)
+            bool ok = true;
+            for (int p = 0; p < 4; ++p) ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < 2 ? count_a : count_b);
+            return ok;
+        };
+        // the loss does not grow with the slice count: `guess` is the choice iff it is within the threshold (or the
+        // largest count allowed) and guess - 1 is not
+        if ((within(guess) || guess == max_slices) && (guess == 1 || !within(guess - 1))) {
+            *num_slices = guess;
+            if (guess_confirmed) *guess_confirmed = 1;
+            return OZIMMU_OK;
+        }
+    } else if (host) {
+        // Any other shape: the scans, the copy of their sums and the product with the guessed count are queued together
+        // and waited for once; a right guess saves the wait between choice and product, a wrong one costs a product.
+        const ScanOperand a{A, lda, m, k, false}, b{B, ldb, k, n, true};
+        if (enqueue_scans(a, b, cplx, scratch, host, st) != hipSuccess) return OZIMMU_ERR_HIP;
+        ozimmu_status_t rc = product(guess);
+        if (rc != OZIMMU_OK) return rc;
+        if (hipStreamSynchronize(st) != hipSuccess) return OZIMMU_ERR_HIP;
+        const int s = pick_slices(host, cplx, count_a, count_b, threshold, max_slices);
+        if (s != guess) {
+            rc = product(s);
+            if (rc != OZIMMU_OK) return rc;
+        } else if (guess_confirmed) {
+            *guess_confirmed = 1;
+        }
+        *num_slices = s;
+        return OZIMMU_OK;
+    }
+    int s = 0;
+    ozimmu_status_t rc = ozimmu_auto_num_slices(m, n, k, A, lda, B, ldb, cplx, threshold, max_slices, scratch, scratch_bytes,
+                                                &s, nullptr, stream);
+    if (rc != OZIMMU_OK) return rc;
+    rc = product(s);
+    if (rc == OZIMMU_OK) *num_slices = s;
+    return rc;
 }
 
 }  // namespace
@@ -459,61 +550,20 @@ ozimmu_status_t ozimmu_auto_num_slices(int64_t m, int64_t n, int64_t k, const do
                        stream);
 }
 
+ozimmu_status_t ozimmu_dgemm_auto(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
+                                  int64_t ldb, double* C, int64_t ldc, double threshold, int max_slices, int guess,
+                                  void* workspace, size_t workspace_bytes, void* scratch, size_t scratch_bytes,
+                                  int* num_slices, int* guess_confirmed, void* stream) {
+    return gemm_auto(false, m, n, k, A, lda, B, ldb, C, ldc, threshold, max_slices, guess, workspace, workspace_bytes,
+                     scratch, scratch_bytes, num_slices, guess_confirmed, stream);
+}
+
 ozimmu_status_t ozimmu_zgemm_auto(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
                                   int64_t ldb, double* C, int64_t ldc, double threshold, int max_slices, int guess,
                                   void* workspace, size_t workspace_bytes, void* scratch, size_t scratch_bytes,
                                   int* num_slices, int* guess_confirmed, void* stream) {
-    if (max_slices < 1 || max_slices > OZIMMU_MAX_SLICES || !(threshold >= 0.0)) return OZIMMU_ERR_BAD_SLICES;
-    if (!num_slices) return OZIMMU_ERR_NULL;
-    if (guess_confirmed) *guess_confirmed = 0;
-    // the workspace must serve whichever slice count comes out
-    Layout L{};
-    size_t need_ws = 0;
-    for (int s = 1; s <= max_slices; ++s) {
-        ozimmu_status_t rc = check_gemm_args(m, n, k, A, lda, B, ldb, C, ldc, s, workspace, workspace_bytes, true, &L);
-        if (rc != OZIMMU_OK) return rc;
-        need_ws = std::max(need_ws, L.total);
-    }
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (guess >= 1 && guess <= max_slices && m > 0 && n > 0 && k > 0 && gate_product_applies(A, B, C, n, k, guess)) {
-        size_t need = 0;
-        ozimmu_auto_scratch_bytes(n, &need);
-        if (!scratch || (reinterpret_cast<uintptr_t>(scratch) % OZIMMU_WORKSPACE_ALIGN) != 0 || scratch_bytes < need)
-            return OZIMMU_ERR_WORKSPACE;
-        // Multiply with the guessed count; the kernels that split B and that walk over A count, on their way, what the
-        // check of the guess needs (the bits each plane loses with `guess` and with `guess - 1` slices) and a last small
-        // kernel writes the eight sums into mapped host memory: no pass of its own over A, no copy.
-        L = make_layout(m, n, k, guess, true);
-        if (gate_scan_bytes(m) > L.sa_bytes) return OZIMMU_ERR_WORKSPACE;
-        unsigned char* ws = static_cast<unsigned char*>(workspace);
-        unsigned long long* host = mapped_sums();                                      // [4][16]
-        if (!host) return OZIMMU_ERR_HIP;
-        // the per-tile counters wait where the slices of A would be (that region is not used on this path)
-        hipError_t e = launch_gate_product(A, lda, m, k, n, B, ldb, guess, ws + L.off_gate, C, ldc, st,
-                                           reinterpret_cast<unsigned*>(ws + L.off_sa[0]), host);
-        if (e == hipSuccess) e = hipStreamSynchronize(st);
-        if (e != hipSuccess) return OZIMMU_ERR_HIP;
-        const double count_a = (double)m * (double)k, count_b = (double)k * (double)n;
-        auto within = [&](int s) {   // every plane's loss with s slices within the threshold (the rule of ozimmu_auto_num_slices)
-            bool ok = true;
-            for (int p = 0; p < 4; ++p) ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < 2 ? count_a : count_b);
-            return ok;
-        };
-        // the loss does not grow with the slice count: `guess` is the choice iff it is within the threshold (or the
-        // largest count allowed) and guess - 1 is not
-        if ((within(guess) || guess == max_slices) && (guess == 1 || !within(guess - 1))) {
-            *num_slices = guess;
-            if (guess_confirmed) *guess_confirmed = 1;
-            return OZIMMU_OK;
-        }
-    }
-    int s = 0;
-    ozimmu_status_t rc = ozimmu_auto_num_slices(m, n, k, A, lda, B, ldb, 1, threshold, max_slices, scratch, scratch_bytes, &s,
-                                                nullptr, stream);
-    if (rc != OZIMMU_OK) return rc;
-    rc = ozimmu_zgemm(m, n, k, A, lda, B, ldb, C, ldc, s, workspace, workspace_bytes, stream);
-    if (rc == OZIMMU_OK) *num_slices = s;
-    return rc;
+    return gemm_auto(true, m, n, k, A, lda, B, ldb, C, ldc, threshold, max_slices, guess, workspace, workspace_bytes,
+                     scratch, scratch_bytes, num_slices, guess_confirmed, stream);
 }
 
 ozimmu_status_t ozimmu_auto_num_slices_blas(char transa, char transb, int64_t m, int64_t n, int64_t k,

@@ -115,7 +115,7 @@ struct DeviceState {
     hipEvent_t done = nullptr;
     hipStream_t last_stream = nullptr;
     bool used = false;
-    int last_auto_slices = 0;   // what the last automatic choice for a small complex gate came to: the next one's guess
+    int last_auto_slices[2] = {0, 0};   // what the last automatic choice of a plain product came to (real, complex): the next guess
 };
 DeviceState g_state[kMaxDevices];
 std::mutex g_lock;
@@ -175,34 +175,39 @@ bool compute(const Call& c, hipStream_t stream) {
     const bool product = c.k > 0 && !alpha_zero;
     int s = cfg.slices > 0 ? cfg.slices : 1;
     size_t scan_bytes = 0;
-    // A small gate (A, m x k) applied to a tall state (B, k x n), plain product: in row-major terms C^T = B^T A^T, which
-    // ozimmu_zgemm_auto forms in one pass over the state when the slice count of the previous such call still holds.
-    constexpr int64_t kGateMax = 256;
-    if (product && cfg.slices == 0 && c.cplx && c.ta == 'N' && c.tb == 'N' && c.m <= kGateMax && c.k <= kGateMax &&
-        c.alpha[0] == 1.0 && c.alpha[1] == 0.0 && beta_zero) {
-        if (ozimmu_auto_scratch_bytes(c.m, &scan_bytes) != OZIMMU_OK) return false;
-        scan_bytes = align_up(scan_bytes);
+    // A plain product in automatic mode (no transposes, alpha 1, beta 0; in row-major terms C^T = B^T A^T): count and
+    // product in one call, the count of the previous such call as the guess. A small complex gate (A, m x k) on a tall
+    // state (B, k x n) is then formed in one pass over the state; other shapes save the wait between choice and product.
+    const bool alpha_one = c.alpha[0] == 1.0 && (!c.cplx || c.alpha[1] == 0.0);
+    if (product && cfg.slices == 0 && c.ta == 'N' && c.tb == 'N' && alpha_one && beta_zero) {
         size_t ws_bytes = 0;
-        for (int t = 1; t <= OZIMMU_MAX_SLICES; ++t) {
+        bool sized = ozimmu_auto_scratch_bytes(c.m, &scan_bytes) == OZIMMU_OK;
+        scan_bytes = align_up(scan_bytes);
+        for (int t = 1; sized && t <= OZIMMU_MAX_SLICES; ++t) {
             size_t need = 0;
-            if (ozimmu_workspace_bytes(c.n, c.m, c.k, t, 1, &need) != OZIMMU_OK) return false;
+            sized = ozimmu_workspace_bytes(c.n, c.m, c.k, t, c.cplx, &need) == OZIMMU_OK;
             ws_bytes = std::max(ws_bytes, need);
         }
-        unsigned char* buf = static_cast<unsigned char*>(reserve(d, scan_bytes + ws_bytes));
-        if (!buf) return false;
+        // the workspace of the largest slice count may not be available: then the two calls below, sized for the count chosen
+        unsigned char* buf = sized ? static_cast<unsigned char*>(reserve(d, scan_bytes + ws_bytes)) : nullptr;
         int confirmed = 0;
-        if (ozimmu_zgemm_auto(c.n, c.m, c.k, c.B, c.ldb, c.A, c.lda, c.C, c.ldc, cfg.threshold, OZIMMU_MAX_SLICES,
-                              d.last_auto_slices, buf + scan_bytes, ws_bytes, buf, scan_bytes, &s, &confirmed,
-                              stream) != OZIMMU_OK)
-            return false;
-        d.last_auto_slices = s;
-        d.used = true;
-        d.last_stream = stream;
-        (void)hipEventRecord(d.done, stream);
-        if (cfg.verbose)
-            std::fprintf(stderr, "[ozimmu] %s NN m=%lld n=%lld k=%lld slices=%d (auto) [one call%s]\n", c.name, (long long)c.m,
-                         (long long)c.n, (long long)c.k, s, confirmed ? ", guess confirmed" : "");
-        return true;
+        int& last = d.last_auto_slices[c.cplx ? 1 : 0];
+        if (buf) {
+            const ozimmu_status_t rc =
+                c.cplx ? ozimmu_zgemm_auto(c.n, c.m, c.k, c.B, c.ldb, c.A, c.lda, c.C, c.ldc, cfg.threshold, OZIMMU_MAX_SLICES,
+                                           last, buf + scan_bytes, ws_bytes, buf, scan_bytes, &s, &confirmed, stream)
+                       : ozimmu_dgemm_auto(c.n, c.m, c.k, c.B, c.ldb, c.A, c.lda, c.C, c.ldc, cfg.threshold, OZIMMU_MAX_SLICES,
+                                           last, buf + scan_bytes, ws_bytes, buf, scan_bytes, &s, &confirmed, stream);
+            if (rc != OZIMMU_OK) return false;   // beta is 0: whatever C holds now, the vendor routine overwrites it
+            last = s;
+            d.used = true;
+            d.last_stream = stream;
+            (void)hipEventRecord(d.done, stream);
+            if (cfg.verbose)
+                std::fprintf(stderr, "[ozimmu] %s NN m=%lld n=%lld k=%lld slices=%d (auto) [one call%s]\n", c.name,
+                             (long long)c.m, (long long)c.n, (long long)c.k, s, confirmed ? ", guess confirmed" : "");
+            return true;
+        }
     }
     if (product && cfg.slices == 0) {
         if (ozimmu_auto_scratch_bytes(std::max(c.m, c.n), &scan_bytes) != OZIMMU_OK) return false;

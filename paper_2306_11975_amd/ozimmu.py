@@ -26,6 +26,7 @@ EXPORTS = (
     "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_static", "ozimmu_dgemm_stage",
     "ozimmu_launch_plan", "ozimmu_dgemm_dd", "ozimmu_dgemm_blas", "ozimmu_zgemm_blas_workspace_bytes", "ozimmu_zgemm_blas",
     "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices", "ozimmu_auto_num_slices_blas", "ozimmu_zgemm_auto",
+    "ozimmu_dgemm_auto",
 )
 PROBE_EXPORTS = ("ozimmu_probe_int8_mfma",)      # include/ozimmu_probe.h: measurement utility, not the product path
 
@@ -98,6 +99,9 @@ def lib() -> ctypes.CDLL:
                                                   ctypes.c_double, i32, vp, sz, ctypes.POINTER(i32), vp, vp]
         L.ozimmu_zgemm_auto.restype = i32
         L.ozimmu_zgemm_auto.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, ctypes.c_double, i32, i32, vp, sz, vp, sz,
+                                        ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
+        L.ozimmu_dgemm_auto.restype = i32
+        L.ozimmu_dgemm_auto.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, ctypes.c_double, i32, i32, vp, sz, vp, sz,
                                         ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
         dp = ctypes.POINTER(ctypes.c_double)
         L.ozimmu_probe_int8_mfma.restype = i32
@@ -299,24 +303,35 @@ def auto_num_slices(A, B, threshold: float, max_slices: int = MAX_SLICES, scratc
     return s.value, sums
 
 
-def zgemm_auto(A, B, C, threshold: float, guess: int = 0, max_slices: int = MAX_SLICES, workspace=None, scratch=None,
-               stream=None):
-    """C = A . B (complex128 device tensors) with the slice count ozimmu_auto_num_slices would choose, in one call (see
-    ozimmu.h); `guess` is the expected count (0: none). Returns (s, guess_confirmed). Waits for the stream."""
+def _gemm_auto(cplx, A, B, C, threshold, guess, max_slices, workspace, scratch, stream):
     import torch
 
     m, k = A.shape
     n = B.shape[1]
     if workspace is None:
-        need = max(workspace_bytes(m, n, k, s, True) for s in range(1, max_slices + 1))
+        need = max(workspace_bytes(m, n, k, s, cplx) for s in range(1, max_slices + 1))
         workspace = torch.empty(max(need, WORKSPACE_ALIGN), dtype=torch.uint8, device=A.device)
     if scratch is None:
         scratch = torch.empty(max(auto_scratch_bytes(n), WORKSPACE_ALIGN), dtype=torch.uint8, device=A.device)
     s, confirmed = ctypes.c_int(), ctypes.c_int()
-    _check(lib().ozimmu_zgemm_auto(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C), _ld(C, n), float(threshold),
-                                   int(max_slices), int(guess), _ptr(workspace), workspace.numel(), _ptr(scratch),
-                                   scratch.numel(), ctypes.byref(s), ctypes.byref(confirmed), _stream(stream)))
+    f = lib().ozimmu_zgemm_auto if cplx else lib().ozimmu_dgemm_auto
+    _check(f(m, n, k, _ptr(A), _ld(A, k), _ptr(B), _ld(B, n), _ptr(C), _ld(C, n), float(threshold), int(max_slices),
+             int(guess), _ptr(workspace), workspace.numel(), _ptr(scratch), scratch.numel(), ctypes.byref(s),
+             ctypes.byref(confirmed), _stream(stream)))
     return s.value, bool(confirmed.value)
+
+
+def dgemm_auto(A, B, C, threshold: float, guess: int = 0, max_slices: int = MAX_SLICES, workspace=None, scratch=None,
+               stream=None):
+    """C = A . B (float64 device tensors) with the slice count ozimmu_auto_num_slices would choose, in one call (see
+    ozimmu.h); `guess` is the expected count (0: none). Returns (s, guess_confirmed). Waits for the stream."""
+    return _gemm_auto(False, A, B, C, threshold, guess, max_slices, workspace, scratch, stream)
+
+
+def zgemm_auto(A, B, C, threshold: float, guess: int = 0, max_slices: int = MAX_SLICES, workspace=None, scratch=None,
+               stream=None):
+    """The same for complex128 device tensors."""
+    return _gemm_auto(True, A, B, C, threshold, guess, max_slices, workspace, scratch, stream)
 
 
 def auto_num_slices_blas(transa: str, transb: str, m: int, n: int, k: int, A, lda: int, B, ldb: int, is_complex: bool,

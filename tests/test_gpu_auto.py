@@ -146,3 +146,44 @@ def test_auto_for_column_major_operands_with_transposes(ta, tb, cplx):
         s_got, sums_got = ozimmu.auto_num_slices_blas(ta, tb, m, n, k, dA, lda, dB, ldb, cplx, T)
         assert np.array_equal(sums_got, sums_want)
         assert s_got == s_want
+
+
+# ------------------------------------------------------------------ count and product in one call, general shapes
+def bits(x):
+    return np.ascontiguousarray(x).view(np.uint64)
+
+
+@pytest.mark.parametrize("cplx", [False, True])
+@pytest.mark.parametrize("m,n,k,phi,seed", [(300, 270, 517, 2.0, 2), (64, 64, 64, 0.5, 1), (130, 700, 300, 1.0, 3), (1, 1, 1, 1.0, 4)])
+def test_gemm_auto_is_choice_then_product(cplx, m, n, k, phi, seed):
+    """ozimmu_dgemm_auto / ozimmu_zgemm_auto on shapes of the general path: whatever the guess, the count is the oracle's
+    choice and C the oracle's product with it; the guess is confirmed exactly when it was right. (The shapes of the
+    one-kernel complex path are in test_gpu_gate.py.)"""
+    A, B = wl.phi_pair(m, n, k, phi, seed)
+    if cplx:
+        Ai, Bi = wl.phi_pair(m, n, k, phi, seed + 100)
+        A, B = A + 1j * Ai, B + 1j * Bi
+    dA, dB = dev(A), dev(B)
+    gemm_auto = ozimmu.zgemm_auto if cplx else ozimmu.dgemm_auto
+    oracle_gemm = oracle.zgemm if cplx else oracle.dgemm
+    for T in (0.0, 1.0):
+        s_want = oracle.auto_num_slices(A, B, T)[0]
+        want = oracle_gemm(A, B, s_want)
+        for guess in (s_want, s_want - 1, s_want + 1, 0, 16):
+            guess = min(max(guess, 0), 16)
+            C = torch.full((m, n), float("nan"), dtype=dA.dtype, device="cuda")
+            s_got, confirmed = gemm_auto(dA, dB, C, T, guess=guess)
+            assert s_got == s_want, (T, guess)
+            assert confirmed == (guess == s_want), (T, guess)
+            assert np.array_equal(bits(C.cpu().numpy()), bits(want)), (T, guess)
+
+
+def test_gemm_auto_rejects_a_workspace_too_small_for_the_largest_count():
+    A, B = wl.phi_pair(200, 100, 300, 1.0, 7)
+    dA, dB = dev(A), dev(B)
+    C = torch.empty((200, 100), dtype=torch.float64, device="cuda")
+    ws = torch.empty(ozimmu.workspace_bytes(200, 100, 300, 8), dtype=torch.uint8, device="cuda")
+    with pytest.raises(ozimmu.OzimmuError):
+        ozimmu.dgemm_auto(dA, dB, C, 1.0, guess=8, workspace=ws)                      # 16 slices would not fit
+    s, _ = ozimmu.dgemm_auto(dA, dB, C, 1.0, guess=8, max_slices=8, workspace=ws)     # ... 8 do
+    assert s == min(8, oracle.auto_num_slices(A, B, 1.0)[0])
