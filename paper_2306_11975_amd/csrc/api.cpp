@@ -66,7 +66,7 @@ Layout make_layout(int64_t m, int64_t n, int64_t k, int s, bool cplx) {
     for (int p = 0; p < planes; ++p) { L.off_ea[p] = off; off = align_up(off + sizeof(int32_t) * L.m_pad); }
     for (int p = 0; p < planes; ++p) { L.off_eb[p] = off; off = align_up(off + sizeof(int32_t) * L.n_pad); }
     L.off_colmax = off;
-    off = align_up(off + sizeof(unsigned long long) * (L.n_pad > L.m_pad ? L.n_pad : L.m_pad));  // either operand may be split by columns
+    off = align_up(off + sizeof(unsigned long long) * planes * (L.n_pad > L.m_pad ? L.n_pad : L.m_pad));  // either operand may be split by columns (complex: both planes at once)
     L.off_d = off;
     if (L.wide) off = align_up(off + (size_t)s * L.tiles_m * L.tiles_n * L.tile_rows * L.tile_cols * sizeof(long long));
     L.off_z = off;   // complex: the real and imaginary parts of the result as two m x n planes
@@ -523,10 +523,11 @@ ozimmu_status_t ozimmu_zgemm(int64_t m, int64_t n, int64_t k, const double* A, i
     if (gate_product_applies(A, B, C, n, k, s)) return hip_status(launch_gate_product(A, lda, m, k, n, B, ldb, s, ws + L.off_gate, C, ldc, st));
     // the real and imaginary planes are separated while splitting (element stride 2)
     e = split_complex_rows(A, lda, m, k, s, ws, L.off_sa, L.off_ea, L.m_pad, L.k_pad, st, false);
-    for (int pl = 0; pl < 2 && e == hipSuccess; ++pl)
-        e = launch_split_cols(B + pl, ldb, 2, k, n, s, reinterpret_cast<int8_t*>(ws + L.off_sb[pl]), L.n_pad,
-                              L.k_pad, reinterpret_cast<int32_t*>(ws + L.off_eb[pl]),
-                              reinterpret_cast<unsigned long long*>(ws + L.off_colmax), st);
+    if (e == hipSuccess)
+        e = launch_split_cols_complex(B, ldb, k, n, s, reinterpret_cast<int8_t*>(ws + L.off_sb[0]),
+                                      reinterpret_cast<int8_t*>(ws + L.off_sb[1]), L.n_pad, L.k_pad,
+                                      reinterpret_cast<int32_t*>(ws + L.off_eb[0]), reinterpret_cast<int32_t*>(ws + L.off_eb[1]),
+                                      reinterpret_cast<unsigned long long*>(ws + L.off_colmax), st);
     if (e == hipSuccess) e = run_complex_products(L, m, n, s, ws, C, ldc, st);
     return hip_status(e);
 }
@@ -674,14 +675,18 @@ ozimmu_status_t ozimmu_zgemm_blas(char transa, char transb, int64_t m, int64_t n
     }
     // planes: real, then imaginary (negated while splitting if the operand is conjugated)
     if (!tb) e = split_complex_rows(B, ldb, n, k, num_slices, ws, L.off_sa, L.off_ea, L.m_pad, L.k_pad, st, false);   // op(B)^T: n rows of length k
-    else for (int pl = 0; pl < 2 && e == hipSuccess; ++pl)
-        e = launch_split_cols(B + pl, ldb, 2, k, n, num_slices, reinterpret_cast<int8_t*>(ws + L.off_sa[pl]), L.m_pad, L.k_pad,
-                              reinterpret_cast<int32_t*>(ws + L.off_ea[pl]), colmax, st, pl == 1 && tb == 2);
+    else
+        e = launch_split_cols_complex(B, ldb, k, n, num_slices, reinterpret_cast<int8_t*>(ws + L.off_sa[0]),
+                                      reinterpret_cast<int8_t*>(ws + L.off_sa[1]), L.m_pad, L.k_pad,
+                                      reinterpret_cast<int32_t*>(ws + L.off_ea[0]), reinterpret_cast<int32_t*>(ws + L.off_ea[1]),
+                                      colmax, st, tb == 2);
     if (e == hipSuccess) {
         if (ta) e = split_complex_rows(A, lda, m, k, num_slices, ws, L.off_sb, L.off_eb, L.n_pad, L.k_pad, st, ta == 2);   // op(A): m rows of length k
-        else for (int pl = 0; pl < 2 && e == hipSuccess; ++pl)
-            e = launch_split_cols(A + pl, lda, 2, k, m, num_slices, reinterpret_cast<int8_t*>(ws + L.off_sb[pl]), L.n_pad, L.k_pad,
-                                  reinterpret_cast<int32_t*>(ws + L.off_eb[pl]), colmax, st, false);
+        else
+            e = launch_split_cols_complex(A, lda, k, m, num_slices, reinterpret_cast<int8_t*>(ws + L.off_sb[0]),
+                                          reinterpret_cast<int8_t*>(ws + L.off_sb[1]), L.n_pad, L.k_pad,
+                                          reinterpret_cast<int32_t*>(ws + L.off_eb[0]), reinterpret_cast<int32_t*>(ws + L.off_eb[1]),
+                                          colmax, st, false);
     }
     if (e == hipSuccess) e = run_complex_products(L, n, m, num_slices, ws, G, ldg, st);
     if (e == hipSuccess && !(beta_zero && alpha_one)) e = launch_zaxpby(G, ldg, C, ldc, n, m, ar, ai, br, bi, st);

@@ -104,6 +104,11 @@ hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, i
 hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n, int s,
                              int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
                              unsigned long long* colmax, hipStream_t st, bool negate = false);
+// Both planes of an interleaved complex B (k x n complex elements, leading dimension ldb in complex elements) in one
+// set of launches; colmax: 2 n_pad entries. negate_im: the slices of -Im(B) (a conjugated operand).
+hipError_t launch_split_cols_complex(const double* B, int64_t ldb, int64_t k, int64_t n, int s, int8_t* S_re, int8_t* S_im,
+                                     int64_t n_pad, int64_t k_pad, int32_t* E_re, int32_t* E_im,
+                                     unsigned long long* colmax, hipStream_t st, bool negate_im = false);
 // Rows of an interleaved complex operand (Z: m x k complex elements, leading dimension ldz in complex
 // elements), both planes in one pass; only where complex_rows_in_one_pass / complex_scan_in_one_pass say so
 // (short enough rows, 16-byte aligned), otherwise one strided pass per plane with the functions above / below.

@@ -211,14 +211,29 @@ __global__ __launch_bounds__(256) void fill_u64_kernel(unsigned long long* p, in
     if (i < n) p[i] = v;
 }
 
+// The column kernels take a second plane of the same operand in the same launch (the imaginary part of an
+// interleaved complex operand): workgroups with blockIdx.z = 1 work on it, its pointers at these distances
+// from the first plane's.
+struct SecondPlane {
+    int64_t b;        // elements of B
+    int64_t colmax;   // entries
+    int64_t slices;   // bytes
+    int64_t e;        // entries
+    unsigned long long flip;   // its sign flip (0 or the sign bit)
+};
+
 // Column maxima of |B|: a lane owns a column (loads are contiguous across lanes), a workgroup
 // owns a band of rows, bands are combined with a 64-bit atomic maximum on the bit patterns.
 constexpr int kColBand = 256;   // rows per band when the matrix is tall enough to fill the chip
 __global__ __launch_bounds__(256) void col_max_kernel(const double* __restrict__ B, int64_t ldb,
                                                       int inc, int64_t k, int64_t n, int band,
-                                                      unsigned long long* __restrict__ colmax) {
+                                                      unsigned long long* __restrict__ colmax, SecondPlane second = SecondPlane{}) {
     const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= n) return;
+    if (blockIdx.z) {
+        B += second.b;
+        colmax += second.colmax;
+    }
     const int64_t l0 = (int64_t)blockIdx.y * band;
     const int64_t l1 = l0 + band < k ? l0 + band : k;
     const unsigned long long* src = reinterpret_cast<const unsigned long long*>(B);
@@ -252,8 +267,16 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
                                                          int64_t k_pad,
                                                          const unsigned long long* __restrict__ colmax,
                                                          int32_t* __restrict__ Eout, int j_tiles,
-                                                         unsigned long long flip) {   // sign bit, or 0: slices of -B
+                                                         unsigned long long flip,    // sign bit, or 0: slices of -B
+                                                         SecondPlane second = SecondPlane{}) {
     __shared__ uint32_t tile[kColGroup][kColTileJ][kColLdsStride];
+    if (blockIdx.z) {
+        B += second.b;
+        colmax += second.colmax;
+        S += second.slices;
+        Eout += second.e;
+        flip = second.flip;
+    }
     const int tid = threadIdx.x;
     const int jj = tid & 63, lg = tid >> 6;
     const int64_t jt = blockIdx.x % j_tiles, lt = blockIdx.x / j_tiles;
@@ -836,6 +859,39 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
     const dim3 grid((unsigned)(j_tiles * l_tiles));
     if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, E, j_tiles, flip);
     else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, E, j_tiles, flip);
+    return hipGetLastError();
+}
+
+// Both planes of an interleaved complex operand (element stride 2) in three launches: colmax holds 2 n_pad entries.
+hipError_t launch_split_cols_complex(const double* B, int64_t ldb, int64_t k, int64_t n, int s, int8_t* S_re, int8_t* S_im,
+                                     int64_t n_pad, int64_t k_pad, int32_t* E_re, int32_t* E_im,
+                                     unsigned long long* colmax, hipStream_t st, bool negate_im) {
+    if (n_pad == 0) return hipSuccess;
+    fill_u64_kernel<<<dim3((unsigned)((2 * n_pad + 255) / 256)), dim3(256), 0, st>>>(colmax, 2 * n_pad, 0ull);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    SecondPlane second{1, n_pad, S_im - S_re, E_im - E_re, negate_im ? 1ull << 63 : 0ull};
+    if (k > 0 && n > 0) {
+        const int64_t bx = (n + 255) / 256;
+        const int band = column_band(k, n);
+        col_max_kernel<<<dim3((unsigned)bx, (unsigned)((k + band - 1) / band), 2), dim3(256), 0, st>>>(
+            B, ldb, 2, k, n, band, colmax, second);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (k_pad == 0) {   // no slices to write: only the exponents (all zero)
+        if (n > 0) {
+            col_exponent_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(colmax, n, E_re);
+            col_exponent_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(colmax + n_pad, n, E_im);
+        }
+        return hipGetLastError();
+    }
+    const int64_t l_tiles = (k_pad + kColTileL - 1) / kColTileL;
+    const int j_tiles = (int)(n_pad / kColTileJ);
+    if (j_tiles * l_tiles > 0x7fffffffll) return hipErrorInvalidValue;   // beyond any grid (and any memory)
+    const dim3 grid((unsigned)(j_tiles * l_tiles), 1, 2);
+    if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, 2, k, n, s, S_re, n_pad, k_pad, colmax, E_re, j_tiles, 0ull, second);
+    else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, 2, k, n, s, S_re, n_pad, k_pad, colmax, E_re, j_tiles, 0ull, second);
     return hipGetLastError();
 }
 
