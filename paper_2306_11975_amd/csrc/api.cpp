@@ -219,6 +219,8 @@ hipError_t scan_operand(const ScanOperand& z, int o, int is_complex, unsigned lo
         return launch_loss_scan_rows_complex(z.ptr, z.ld, z.rows, z.cols, dst, dst + OZIMMU_MAX_SLICES, st);
     if (is_complex && z.by_cols && complex_cols_scan_in_one_launch(z.ptr, z.rows, z.cols))   // a small gate: one launch
         return launch_loss_scan_cols_complex_small(z.ptr, z.ld, z.rows, z.cols, dst, dst + OZIMMU_MAX_SLICES, st);
+    if (is_complex && z.by_cols)   // both planes in one set of launches
+        return launch_loss_scan_cols_complex(z.ptr, z.ld, z.rows, z.cols, colmax, dst, dst + OZIMMU_MAX_SLICES, st);
     hipError_t e = hipSuccess;
     for (int pl = 0; pl < parts && e == hipSuccess; ++pl) {
         if (z.by_cols) e = launch_loss_scan_cols(z.ptr + pl, z.ld, inc, z.rows, z.cols, colmax, dst + pl * OZIMMU_MAX_SLICES, st);
@@ -535,7 +537,7 @@ ozimmu_status_t ozimmu_zgemm(int64_t m, int64_t n, int64_t k, const double* A, i
 ozimmu_status_t ozimmu_auto_scratch_bytes(int64_t n, size_t* bytes) {
     if (n < 0 || n > kMaxDim) return OZIMMU_ERR_BAD_DIM;
     if (!bytes) return OZIMMU_ERR_NULL;
-    *bytes = 512 + sizeof(unsigned long long) * (size_t)round_up(n, kRowAlign);
+    *bytes = 512 + 2 * sizeof(unsigned long long) * (size_t)round_up(n, kRowAlign);   // the sums, then column maxima of two planes
     return OZIMMU_OK;
 }
 

@@ -133,6 +133,9 @@ hipError_t launch_loss_scan_rows(const double* A, int64_t lda, int inc, int64_t 
                                  unsigned long long* sums, hipStream_t st);
 hipError_t launch_loss_scan_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n,
                                  unsigned long long* colmax, unsigned long long* sums, hipStream_t st);
+// Both planes of an interleaved complex operand (k x n complex elements, ldb in complex elements) by columns; colmax: 2 n entries.
+hipError_t launch_loss_scan_cols_complex(const double* B, int64_t ldb, int64_t k, int64_t n, unsigned long long* colmax,
+                                         unsigned long long* sums_re, unsigned long long* sums_im, hipStream_t st);
 // C = beta C (C = +0 if beta == 0, without reading C) on an m x n row-major array.
 hipError_t launch_scale_f64(double* C, int64_t ldc, int64_t m, int64_t n, double beta, hipStream_t st);
 // Complex update on rows x cols row-major arrays of interleaved (re, im) doubles, leading

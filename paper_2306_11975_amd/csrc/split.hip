@@ -220,6 +220,7 @@ struct SecondPlane {
     int64_t slices;   // bytes
     int64_t e;        // entries
     unsigned long long flip;   // its sign flip (0 or the sign bit)
+    int64_t sums;     // entries (slice-count scan)
 };
 
 // Column maxima of |B|: a lane owns a column (loads are contiguous across lanes), a workgroup
@@ -666,8 +667,13 @@ __global__ __launch_bounds__(256) void loss_cols_complex_small_kernel(const doub
 __global__ __launch_bounds__(256) void loss_cols_kernel(const double* __restrict__ B, int64_t ldb, int inc,
                                                         int64_t k, int64_t n, int band,
                                                         const unsigned long long* __restrict__ colmax,
-                                                        unsigned long long* __restrict__ sums) {
+                                                        unsigned long long* __restrict__ sums, SecondPlane second = SecondPlane{}) {
     __shared__ unsigned long long lds16[OZIMMU_MAX_SLICES];
+    if (blockIdx.z) {
+        B += second.b;
+        colmax += second.colmax;
+        sums += second.sums;
+    }
     const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     LossAcc acc;
     loss_clear(acc);
@@ -870,7 +876,7 @@ hipError_t launch_split_cols_complex(const double* B, int64_t ldb, int64_t k, in
     fill_u64_kernel<<<dim3((unsigned)((2 * n_pad + 255) / 256)), dim3(256), 0, st>>>(colmax, 2 * n_pad, 0ull);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    SecondPlane second{1, n_pad, S_im - S_re, E_im - E_re, negate_im ? 1ull << 63 : 0ull};
+    SecondPlane second{1, n_pad, S_im - S_re, E_im - E_re, negate_im ? 1ull << 63 : 0ull, 0};
     if (k > 0 && n > 0) {
         const int64_t bx = (n + 255) / 256;
         const int band = column_band(k, n);
@@ -935,6 +941,24 @@ hipError_t launch_loss_scan_cols(const double* B, int64_t ldb, int inc, int64_t 
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     loss_cols_kernel<<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, band, colmax, sums);
+    return hipGetLastError();
+}
+
+// Both planes of an interleaved complex operand scanned by columns, in three launches; colmax: 2 n entries.
+hipError_t launch_loss_scan_cols_complex(const double* B, int64_t ldb, int64_t k, int64_t n, unsigned long long* colmax,
+                                         unsigned long long* sums_re, unsigned long long* sums_im, hipStream_t st) {
+    if (k == 0 || n == 0) return hipSuccess;
+    const int64_t bx = (n + 255) / 256;
+    fill_u64_kernel<<<dim3((unsigned)((2 * n + 255) / 256)), dim3(256), 0, st>>>(colmax, 2 * n, 0ull);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int band = column_band(k, n);
+    const dim3 grid((unsigned)bx, (unsigned)((k + band - 1) / band), 2);
+    SecondPlane second{1, n, 0, 0, 0ull, sums_im - sums_re};
+    col_max_kernel<<<grid, dim3(256), 0, st>>>(B, ldb, 2, k, n, band, colmax, second);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    loss_cols_kernel<<<grid, dim3(256), 0, st>>>(B, ldb, 2, k, n, band, colmax, sums_re, second);
     return hipGetLastError();
 }
 

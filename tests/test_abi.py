@@ -159,7 +159,7 @@ def test_blas_call_argument_errors():
 def test_auto_slice_count_argument_errors():
     L = ozimmu.lib()
     out = ctypes.c_size_t()
-    assert L.ozimmu_auto_scratch_bytes(1000, ctypes.byref(out)) == 0 and out.value == 512 + 8 * 1024
+    assert L.ozimmu_auto_scratch_bytes(1000, ctypes.byref(out)) == 0 and out.value == 512 + 2 * 8 * 1024
     assert L.ozimmu_auto_scratch_bytes(-1, ctypes.byref(out)) == 1
     fake = ctypes.c_void_p(256)
     s = ctypes.c_int(-7)
