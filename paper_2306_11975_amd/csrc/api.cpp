@@ -229,12 +229,12 @@ hipError_t scan_operand(const ScanOperand& z, int o, int is_complex, unsigned lo
     return e;
 }
 
-// 4 x 16 sums in host memory that kernels can write (one buffer per calling thread, kept until the process ends)
+// 4 x 16 sums in host memory that kernels of any device can write (one buffer per calling thread, kept until the process ends)
 unsigned long long* mapped_sums() {
     thread_local unsigned long long* p = nullptr;
     if (!p) {
         void* q = nullptr;
-        if (hipHostMalloc(&q, 4 * OZIMMU_MAX_SLICES * sizeof(unsigned long long), hipHostMallocMapped) == hipSuccess)
+        if (hipHostMalloc(&q, 4 * OZIMMU_MAX_SLICES * sizeof(unsigned long long), hipHostMallocMapped | hipHostMallocPortable) == hipSuccess)
             p = static_cast<unsigned long long*>(q);
     }
     return p;
