@@ -284,8 +284,8 @@ ozimmu_status_t ozimmu_auto_num_slices(int64_t m, int64_t n, int64_t k, const do
  *   - where ozimmu_zgemm runs as the kernel that splits A on the fly (see there), that kernel and the
  *     splitter of B count on their way what the check of the guess needs: a right guess means A has
  *     been read once instead of twice;
- *   - for every other shape the scans of ozimmu_auto_num_slices, the copy of their sums and the product
- *     are queued together and waited for once: a right guess saves the wait between choice and product.
+ *   - for every other shape the splitters count the same while they cut the slices, and the product
+ *     follows at once: a right guess means no scan pass over either operand and a single wait.
  * A right guess sets *guess_confirmed = 1 (optional HOST pointer). A wrong one is followed by the
  * product with the count chosen, so it costs one product; without a guess the count is chosen first.
  * workspace: at least the largest ozimmu_workspace_bytes(m, n, k, s, is_complex) over

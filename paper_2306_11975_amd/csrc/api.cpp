@@ -30,6 +30,7 @@ struct Layout {
     int tiles_m, tiles_n, tile_rows, tile_cols;
     bool wide;
     size_t sa_bytes, sb_bytes;      // one plane
+    size_t off_scan;
     size_t off_sa[2], off_sb[2];    // planes (real GEMM uses plane 0)
     size_t off_ea[2], off_eb[2];
     size_t off_colmax, off_d, off_z, off_gate;
@@ -73,6 +74,8 @@ Layout make_layout(int64_t m, int64_t n, int64_t k, int s, bool cplx) {
     if (cplx) off = align_up(off + (size_t)2 * m * n * sizeof(double));
     L.off_gate = off;   // complex with a small B: its slice tensors for the kernel that splits A on the fly
     if (cplx) off = align_up(off + gate_scratch_bytes(n, k, s));
+    L.off_scan = off;   // the counters of splitters that count for the slice-count check: first operand, then second
+    off = align_up(off + 2 * scan_slots_bytes(planes));
     L.total = off;
     return L;
 }
@@ -101,13 +104,15 @@ ozimmu_status_t check_gemm_args(int64_t m, int64_t n, int64_t k, const void* A, 
 // plane. negate_im: the slices of the conjugated operand.
 hipError_t split_complex_rows(const double* Z, int64_t ld, int64_t rows, int64_t k, int s, unsigned char* ws,
                               const size_t (&off_s)[2], const size_t (&off_e)[2], int64_t rows_pad, int64_t k_pad,
-                              hipStream_t st, bool negate_im) {
+                              hipStream_t st, bool negate_im, unsigned long long* scan_slots = nullptr) {
     int8_t* S[2] = {reinterpret_cast<int8_t*>(ws + off_s[0]), reinterpret_cast<int8_t*>(ws + off_s[1])};
     int32_t* E[2] = {reinterpret_cast<int32_t*>(ws + off_e[0]), reinterpret_cast<int32_t*>(ws + off_e[1])};
     if (complex_rows_in_one_pass(Z, k_pad))
-        return launch_split_rows_complex(Z, ld, rows, k, s, S[0], S[1], rows_pad, k_pad, E[0], E[1], st, negate_im);
-    hipError_t e = launch_split_rows(Z, ld, 2, rows, k, s, S[0], rows_pad, k_pad, E[0], st, false);
-    if (e == hipSuccess) e = launch_split_rows(Z + 1, ld, 2, rows, k, s, S[1], rows_pad, k_pad, E[1], st, negate_im);
+        return launch_split_rows_complex(Z, ld, rows, k, s, S[0], S[1], rows_pad, k_pad, E[0], E[1], st, negate_im, scan_slots);
+    hipError_t e = launch_split_rows(Z, ld, 2, rows, k, s, S[0], rows_pad, k_pad, E[0], st, false, scan_slots, 10);
+    if (e == hipSuccess)
+        e = launch_split_rows(Z + 1, ld, 2, rows, k, s, S[1], rows_pad, k_pad, E[1], st, negate_im,
+                              scan_slots ? scan_slots + 5 : nullptr, 10);
     return e;
 }
 
@@ -295,6 +300,36 @@ ozimmu_status_t auto_select(const ScanOperand& a, const ScanOperand& b, int64_t 
     return OZIMMU_OK;
 }
 
+// The splits of a product that also count for the check of num_slices as the automatic slice count (Section 4.4), and
+// the two small kernels that leave the bits lost with num_slices and num_slices - 1 slices in `sums` ([planes][16],
+// device or mapped host memory; first operand's planes first). Arguments already validated.
+hipError_t counting_splits(bool cplx, const Layout& L, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda,
+                           const double* B, int64_t ldb, int s, unsigned char* ws, unsigned long long* sums, hipStream_t st) {
+    const int planes = cplx ? 2 : 1;
+    unsigned long long* slots_a = reinterpret_cast<unsigned long long*>(ws + L.off_scan);
+    unsigned long long* slots_b = slots_a + scan_slots_bytes(planes) / sizeof(unsigned long long);
+    unsigned long long* colmax = reinterpret_cast<unsigned long long*>(ws + L.off_colmax);
+    hipError_t e = launch_fill_u64(slots_a, (int64_t)(2 * scan_slots_bytes(planes) / sizeof(unsigned long long)), 0ull, st);
+    if (e != hipSuccess) return e;
+    if (cplx) {
+        e = split_complex_rows(A, lda, m, k, s, ws, L.off_sa, L.off_ea, L.m_pad, L.k_pad, st, false, slots_a);
+        if (e == hipSuccess)
+            e = launch_split_cols_complex(B, ldb, k, n, s, reinterpret_cast<int8_t*>(ws + L.off_sb[0]),
+                                          reinterpret_cast<int8_t*>(ws + L.off_sb[1]), L.n_pad, L.k_pad,
+                                          reinterpret_cast<int32_t*>(ws + L.off_eb[0]), reinterpret_cast<int32_t*>(ws + L.off_eb[1]),
+                                          colmax, st, false, slots_b);
+    } else {
+        e = launch_split_rows(A, lda, 1, m, k, s, reinterpret_cast<int8_t*>(ws + L.off_sa[0]), L.m_pad, L.k_pad,
+                              reinterpret_cast<int32_t*>(ws + L.off_ea[0]), st, false, slots_a, 5);
+        if (e == hipSuccess)
+            e = launch_split_cols(B, ldb, 1, k, n, s, reinterpret_cast<int8_t*>(ws + L.off_sb[0]), L.n_pad, L.k_pad,
+                                  reinterpret_cast<int32_t*>(ws + L.off_eb[0]), colmax, st, false, slots_b, 5);
+    }
+    if (e == hipSuccess) e = launch_scan_reduce(slots_a, planes, s, sums, st);
+    if (e == hipSuccess) e = launch_scan_reduce(slots_b, planes, s, sums + planes * OZIMMU_MAX_SLICES, st);
+    return e;
+}
+
 // Slice count and product in one call (see ozimmu_dgemm_auto / ozimmu_zgemm_auto in ozimmu.h).
 ozimmu_status_t gemm_auto(bool cplx, int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,
                           int64_t ldb, double* C, int64_t ldc, double threshold, int max_slices, int guess, void* workspace,
@@ -343,22 +378,27 @@ ozimmu_status_t gemm_auto(bool cplx, int64_t m, int64_t n, int64_t k, const doub
             return OZIMMU_OK;
         }
     } else if (host) {
-        // Any other shape: the scans, the copy of their sums and the product with the guessed count are queued together
-        // and waited for once; a right guess saves the wait between choice and product, a wrong one costs a product.
-        const ScanOperand a{A, lda, m, k, false}, b{B, ldb, k, n, true};
-        if (enqueue_scans(a, b, cplx, scratch, host, st) != hipSuccess) return OZIMMU_ERR_HIP;
-        ozimmu_status_t rc = product(guess);
-        if (rc != OZIMMU_OK) return rc;
-        if (hipStreamSynchronize(st) != hipSuccess) return OZIMMU_ERR_HIP;
-        const int s = pick_slices(host, cplx, count_a, count_b, threshold, max_slices);
-        if (s != guess) {
-            rc = product(s);
-            if (rc != OZIMMU_OK) return rc;
-        } else if (guess_confirmed) {
-            *guess_confirmed = 1;
+        // Any other shape: the splitters of the general path count while they split, two small kernels leave the
+        // sums for `guess` and `guess - 1` in the mapped buffer, and the product follows at once; one wait at the end.
+        L = make_layout(m, n, k, guess, cplx);
+        unsigned char* ws = static_cast<unsigned char*>(workspace);
+        hipError_t e = counting_splits(cplx, L, m, n, k, A, lda, B, ldb, guess, ws, host, st);
+        if (e == hipSuccess)
+            e = cplx ? run_complex_products(L, m, n, guess, ws, C, ldc, st) : run_product(L, m, n, guess, ws, 0, 0, C, ldc, 0, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return OZIMMU_ERR_HIP;
+        const int planes = cplx ? 4 : 2;
+        auto within = [&](int s) {
+            bool ok = true;
+            for (int p = 0; p < planes; ++p)
+                ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < planes / 2 ? count_a : count_b);
+            return ok;
+        };
+        if ((within(guess) || guess == max_slices) && (guess == 1 || !within(guess - 1))) {
+            *num_slices = guess;
+            if (guess_confirmed) *guess_confirmed = 1;
+            return OZIMMU_OK;
         }
-        *num_slices = s;
-        return OZIMMU_OK;
     }
     int s = 0;
     ozimmu_status_t rc = ozimmu_auto_num_slices(m, n, k, A, lda, B, ldb, cplx, threshold, max_slices, scratch, scratch_bytes,

@@ -55,32 +55,10 @@ __device__ __forceinline__ Fixed to_fixed_upper(unsigned long long bits, int E) 
     return f;
 }
 
-// What the check of a guessed slice count S needs of a plane (see loss_position): sums of |v - 7 S|, |z - 7 S|, the
-// same for S - 1, and of the stored bits L; the bits lost with s slices are (sum |v - 7 s| - sum |z - 7 s| + sum L) / 2.
-constexpr int kScanCounters = 5;
-struct ScanCount {
-    uint32_t sv_g, sz_g, sv_h, sz_h, bits;
-};
+// scan_count4 with the edges of a compile-time slice count (no counters for S - 1 = 0 slices)
 template <int S>
 __device__ __forceinline__ void scan_count4(ScanCount& a, const unsigned long long (&b)[4], int E) {
-    uint32_t pz = 0, pl = 0;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        uint32_t z, L;
-        loss_position(b[u], E, z, L);
-        pz |= z << (8 * u);
-        pl |= L << (8 * u);
-    }
-    const uint32_t pv = pz + pl;   // bytewise: no byte exceeds 165
-    a.bits = __builtin_amdgcn_sad_u8(pl, 0u, a.bits);
-    constexpr uint32_t edge_g = 0x01010101u * (uint32_t)(OZIMMU_SLICE_BITS * S);
-    a.sv_g = __builtin_amdgcn_sad_u8(pv, edge_g, a.sv_g);
-    a.sz_g = __builtin_amdgcn_sad_u8(pz, edge_g, a.sz_g);
-    if constexpr (S > 1) {
-        constexpr uint32_t edge_h = 0x01010101u * (uint32_t)(OZIMMU_SLICE_BITS * (S - 1));
-        a.sv_h = __builtin_amdgcn_sad_u8(pv, edge_h, a.sv_h);
-        a.sz_h = __builtin_amdgcn_sad_u8(pz, edge_h, a.sz_h);
-    }
+    scan_count4(a, b, E, 0x01010101u * (uint32_t)(OZIMMU_SLICE_BITS * S), 0x01010101u * (uint32_t)(OZIMMU_SLICE_BITS * (S > 1 ? S - 1 : 1)));
 }
 
 // bits an element at (z, L) loses with s slices

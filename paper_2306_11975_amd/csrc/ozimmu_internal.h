@@ -98,24 +98,33 @@ hipError_t launch_gate_product(const double* Z, int64_t ldz, int64_t m, int64_t 
 
 // negate: emit the slices of -A (-B) instead: same exponents, every slice with the opposite sign
 // (how a conjugated operand's imaginary plane is split)
+// Counting while splitting (the check of s as the automatic slice count, Section 4.4): scan_slots, if not null, is a
+// zeroed array of scan_slots_bytes(planes of the operand) bytes; the splitter adds, per plane, five counters into one
+// of its slots (scan_nc counters to a slot: 5 per plane of the operand; a one-plane launcher is handed the pointer to
+// its plane's five), and launch_scan_reduce turns them into the bits lost with s and with s - 1 slices:
+// out[plane * 16 + s - 1], out[plane * 16 + s - 2] (device or mapped host memory).
+size_t scan_slots_bytes(int planes);
+hipError_t launch_scan_reduce(const unsigned long long* slots, int planes, int s, unsigned long long* out, hipStream_t st);
 hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k, int s,
                              int8_t* S, int64_t m_pad, int64_t k_pad, int32_t* E, hipStream_t st,
-                             bool negate = false);
+                             bool negate = false, unsigned long long* scan_slots = nullptr, int scan_nc = 5);
 hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n, int s,
                              int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
-                             unsigned long long* colmax, hipStream_t st, bool negate = false);
+                             unsigned long long* colmax, hipStream_t st, bool negate = false,
+                             unsigned long long* scan_slots = nullptr, int scan_nc = 5);
 // Both planes of an interleaved complex B (k x n complex elements, leading dimension ldb in complex elements) in one
 // set of launches; colmax: 2 n_pad entries. negate_im: the slices of -Im(B) (a conjugated operand).
 hipError_t launch_split_cols_complex(const double* B, int64_t ldb, int64_t k, int64_t n, int s, int8_t* S_re, int8_t* S_im,
                                      int64_t n_pad, int64_t k_pad, int32_t* E_re, int32_t* E_im,
-                                     unsigned long long* colmax, hipStream_t st, bool negate_im = false);
+                                     unsigned long long* colmax, hipStream_t st, bool negate_im = false,
+                                     unsigned long long* scan_slots = nullptr);
 // Rows of an interleaved complex operand (Z: m x k complex elements, leading dimension ldz in complex
 // elements), both planes in one pass; only where complex_rows_in_one_pass / complex_scan_in_one_pass say so
 // (short enough rows, 16-byte aligned), otherwise one strided pass per plane with the functions above / below.
 bool complex_rows_in_one_pass(const double* Z, int64_t k_pad);
 hipError_t launch_split_rows_complex(const double* Z, int64_t ldz, int64_t m, int64_t k, int s, int8_t* S_re,
                                      int8_t* S_im, int64_t m_pad, int64_t k_pad, int32_t* E_re, int32_t* E_im,
-                                     hipStream_t st, bool negate_im = false);
+                                     hipStream_t st, bool negate_im = false, unsigned long long* scan_slots = nullptr);
 bool complex_scan_in_one_pass(const double* Z, int64_t k);
 hipError_t launch_loss_scan_rows_complex(const double* Z, int64_t ldz, int64_t m, int64_t k,
                                          unsigned long long* sums_re, unsigned long long* sums_im, hipStream_t st);

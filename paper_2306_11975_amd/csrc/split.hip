@@ -65,12 +65,16 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_kernel(const dou
                                                                        int inc, int m, int64_t k, int s,
                                                                        int8_t* __restrict__ S, int64_t m_pad,
                                                                        int64_t k_pad, int32_t* __restrict__ Eout,
-                                                                       unsigned long long flip) {   // sign bit, or 0: slices of -A
+                                                                       unsigned long long flip,    // sign bit, or 0: slices of -A
+                                                                       ScanTarget scan) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
     const int r4 = lane >> 4, c16 = lane & 15;
     const int row = blockIdx.x * kRowGroup + r4;
     const bool live = row < m;                       // padding rows: zeros in every slice
+    __shared__ unsigned scan_lds[kScanCounters];
+    if (scan.slots && tid < kScanCounters) scan_lds[tid] = 0u;   // (the barrier after the maxima publishes it)
+    ScanCount cnt = {};
     const int64_t slice_stride = m_pad * k_pad;
     // chunk c of a row = its elements [64 c, 64 c + 64); the wavefronts take the chunks round-robin
     const int64_t chunks = (k_pad + 63) / 64;
@@ -121,6 +125,7 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_kernel(const dou
         for (int j = 0; j < kRowCacheWords; ++j) {
             const int64_t l0 = ((int64_t)(wave + nwaves * j) * 16 + c16) * 4;
             if (l0 < k_pad) emit_word<WIDE>(cache[j], E, s, S + word_offset(row, l0, k_pad), slice_stride, flip);
+            if (scan.slots) scan_count4(cnt, cache[j], E, scan.edge_g, scan.edge_h);
         }
     } else {
         for (int64_t c = wave; c < chunks; c += nwaves) {
@@ -129,9 +134,11 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_kernel(const dou
                 unsigned long long b[4];
                 load_word<VEC>(src, l0, k_live, inc, b);
                 emit_word<WIDE>(b, E, s, S + word_offset(row, l0, k_pad), slice_stride, flip);
+                if (scan.slots) scan_count4(cnt, b, E, scan.edge_g, scan.edge_h);
             }
         }
     }
+    if (scan.slots) scan_flush(cnt, scan_lds, scan);
 }
 
 // Rows of an interleaved complex operand, both planes in one pass: the same mapping as above, a thread's
@@ -144,7 +151,10 @@ template <bool WIDE>
 __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_complex_kernel(
     const double* __restrict__ Z, int64_t ldz, int m, int64_t k, int s, int8_t* __restrict__ S_re,
     int8_t* __restrict__ S_im, int64_t m_pad, int64_t k_pad, int32_t* __restrict__ E_re, int32_t* __restrict__ E_im,
-    unsigned long long flip_re, unsigned long long flip_im) {
+    unsigned long long flip_re, unsigned long long flip_im, ScanTarget scan) {   // scan: the real plane's counters, the imaginary one's five behind
+    __shared__ unsigned scan_lds[2][kScanCounters];
+    if (scan.slots && threadIdx.x < 2 * kScanCounters) (&scan_lds[0][0])[threadIdx.x] = 0u;   // (published by the barrier after the maxima)
+    ScanCount cnt_re = {}, cnt_im = {};
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
     const int r4 = lane >> 4, c16 = lane & 15;
@@ -201,6 +211,16 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_complex_kernel(
             emit_word<WIDE>(re[j], e_re, s, S_re + off, slice_stride, flip_re);
             emit_word<WIDE>(im[j], e_im, s, S_im + off, slice_stride, flip_im);
         }
+        if (scan.slots) {
+            scan_count4(cnt_re, re[j], e_re, scan.edge_g, scan.edge_h);
+            scan_count4(cnt_im, im[j], e_im, scan.edge_g, scan.edge_h);
+        }
+    }
+    if (scan.slots) {
+        scan_flush(cnt_re, scan_lds[0], scan);
+        ScanTarget second = scan;
+        second.slots += kScanCounters;
+        scan_flush(cnt_im, scan_lds[1], second);
     }
 }
 
@@ -269,14 +289,18 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
                                                          const unsigned long long* __restrict__ colmax,
                                                          int32_t* __restrict__ Eout, int j_tiles,
                                                          unsigned long long flip,    // sign bit, or 0: slices of -B
-                                                         SecondPlane second = SecondPlane{}) {
+                                                         SecondPlane second = SecondPlane{}, ScanTarget scan = ScanTarget{}) {
     __shared__ uint32_t tile[kColGroup][kColTileJ][kColLdsStride];
+    __shared__ unsigned scan_lds[kScanCounters];
+    if (scan.slots && threadIdx.x < kScanCounters) scan_lds[threadIdx.x] = 0u;   // (published by the barriers of the write-out)
+    ScanCount cnt = {};
     if (blockIdx.z) {
         B += second.b;
         colmax += second.colmax;
         S += second.slices;
         Eout += second.e;
         flip = second.flip;
+        if (scan.slots) scan.slots += kScanCounters;
     }
     const int tid = threadIdx.x;
     const int jj = tid & 63, lg = tid >> 6;
@@ -301,6 +325,7 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
 #pragma unroll
         for (int u = 0; u < 4; ++u) x[u4][u] = to_fixed<WIDE>(b[u], E);
         sm[u4] = sign_mask(b[0] ^ flip, b[1] ^ flip, b[2] ^ flip, b[3] ^ flip);
+        if (scan.slots) scan_count4(cnt, b, E, scan.edge_g, scan.edge_h);
     }
 #pragma unroll
     for (int p0 = 1; p0 <= (WIDE ? OZIMMU_MAX_SLICES : 9); p0 += kColGroup) {   // unrolled: slice numbers are constants
@@ -333,6 +358,30 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
             }
         }
         __syncthreads();
+    }
+    if (scan.slots) scan_flush(cnt, scan_lds, scan);
+}
+
+// The slots of a counting splitter -> the bits each of the operand's planes loses with s and with s - 1 slices:
+// out[plane * 16 + s - 1] and out[plane * 16 + s - 2] (the layout of the slice-count sums; `out` may be mapped host
+// memory). One workgroup of 256 threads.
+__global__ __launch_bounds__(256) void scan_reduce_kernel(const unsigned long long* __restrict__ slots, int nc, int s,
+                                                          unsigned long long* __restrict__ out) {
+    __shared__ unsigned long long sums[2 * kScanCounters];
+    if (threadIdx.x < 2 * kScanCounters) sums[threadIdx.x] = 0ull;
+    __syncthreads();
+    for (int i = 0; i < nc; ++i) {
+        unsigned long long v = 0;
+        for (int t = threadIdx.x; t < kScanSlots; t += 256) v += slots[(size_t)t * nc + i];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+        if ((threadIdx.x & 63) == 0 && v) atomicAdd(&sums[i], v);
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < nc / kScanCounters) {
+        const unsigned long long* c = sums + threadIdx.x * kScanCounters;
+        out[threadIdx.x * OZIMMU_MAX_SLICES + s - 1] = (c[0] - c[1] + c[4]) >> 1;
+        if (s > 1) out[threadIdx.x * OZIMMU_MAX_SLICES + s - 2] = (c[2] - c[3] + c[4]) >> 1;
     }
 }
 
@@ -752,9 +801,22 @@ static int column_band(int64_t k, int64_t n) {
     return (int)(band < 8 ? 8 : (band > kColBand ? kColBand : band));
 }
 
+static ScanTarget scan_target(unsigned long long* slots, int nc, int s) {
+    return ScanTarget{slots, nc, 0x01010101u * (uint32_t)(OZIMMU_SLICE_BITS * s), 0x01010101u * (uint32_t)(OZIMMU_SLICE_BITS * (s > 1 ? s - 1 : 1))};
+}
+
+size_t scan_slots_bytes(int planes) { return (size_t)kScanSlots * kScanCounters * planes * sizeof(unsigned long long); }
+
+hipError_t launch_scan_reduce(const unsigned long long* slots, int planes, int s, unsigned long long* out, hipStream_t st) {
+    scan_reduce_kernel<<<dim3(1), dim3(256), 0, st>>>(slots, kScanCounters * planes, s, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, int64_t k, int s,
-                             int8_t* S, int64_t m_pad, int64_t k_pad, int32_t* E, hipStream_t st, bool negate) {
+                             int8_t* S, int64_t m_pad, int64_t k_pad, int32_t* E, hipStream_t st, bool negate,
+                             unsigned long long* scan_slots, int scan_nc) {
     if (m_pad == 0 || k_pad == 0) return hipSuccess;
+    const ScanTarget scan = scan_target(scan_slots, scan_nc, s);
     const unsigned long long flip = negate ? 1ull << 63 : 0ull;
     const bool wide = s > 9;
     // a wavefront covers 64 elements of each of its four rows per word it caches
@@ -763,7 +825,7 @@ hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, i
     const bool cached = k_pad <= (int64_t)64 * kRowCacheWords * nwaves;
     const bool vec = inc == 1 && lda % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
     const dim3 grid((unsigned)(m_pad / kRowGroup)), block(64 * nwaves);
-#define OZ_ROWS(W, C, V) split_rows_kernel<W, C, V><<<grid, block, 0, st>>>(A, lda * inc, inc, (int)m, k, s, S, m_pad, k_pad, E, flip)
+#define OZ_ROWS(W, C, V) split_rows_kernel<W, C, V><<<grid, block, 0, st>>>(A, lda * inc, inc, (int)m, k, s, S, m_pad, k_pad, E, flip, scan)
     if (wide) {
         if (cached) { if (vec) OZ_ROWS(true, true, true); else OZ_ROWS(true, true, false); }
         else        { if (vec) OZ_ROWS(true, false, true); else OZ_ROWS(true, false, false); }
@@ -781,15 +843,16 @@ bool complex_rows_in_one_pass(const double* Z, int64_t k_pad) {
 
 hipError_t launch_split_rows_complex(const double* Z, int64_t ldz, int64_t m, int64_t k, int s, int8_t* S_re,
                                      int8_t* S_im, int64_t m_pad, int64_t k_pad, int32_t* E_re, int32_t* E_im,
-                                     hipStream_t st, bool negate_im) {
+                                     hipStream_t st, bool negate_im, unsigned long long* scan_slots) {
     if (m_pad == 0 || k_pad == 0) return hipSuccess;
     if (!complex_rows_in_one_pass(Z, k_pad)) return hipErrorInvalidValue;
+    const ScanTarget scan = scan_target(scan_slots, 2 * kScanCounters, s);
     const int64_t want = (k_pad + 64 * kZRowCacheWords - 1) / (64 * kZRowCacheWords);
     const int nwaves = (int)(want < 1 ? 1 : want);
     const unsigned long long flip_im = negate_im ? 1ull << 63 : 0ull;
     const dim3 grid((unsigned)(m_pad / kRowGroup)), block(64 * nwaves);
-    if (s > 9) split_rows_complex_kernel<true><<<grid, block, 0, st>>>(Z, ldz, (int)m, k, s, S_re, S_im, m_pad, k_pad, E_re, E_im, 0ull, flip_im);
-    else split_rows_complex_kernel<false><<<grid, block, 0, st>>>(Z, ldz, (int)m, k, s, S_re, S_im, m_pad, k_pad, E_re, E_im, 0ull, flip_im);
+    if (s > 9) split_rows_complex_kernel<true><<<grid, block, 0, st>>>(Z, ldz, (int)m, k, s, S_re, S_im, m_pad, k_pad, E_re, E_im, 0ull, flip_im, scan);
+    else split_rows_complex_kernel<false><<<grid, block, 0, st>>>(Z, ldz, (int)m, k, s, S_re, S_im, m_pad, k_pad, E_re, E_im, 0ull, flip_im, scan);
     return hipGetLastError();
 }
 
@@ -841,8 +904,10 @@ hipError_t launch_loss_scan_cols_complex_small(const double* B, int64_t ldb, int
 
 hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, int64_t n, int s,
                              int8_t* S, int64_t n_pad, int64_t k_pad, int32_t* E,
-                             unsigned long long* colmax, hipStream_t st, bool negate) {
+                             unsigned long long* colmax, hipStream_t st, bool negate, unsigned long long* scan_slots,
+                             int scan_nc) {
     if (n_pad == 0) return hipSuccess;
+    const ScanTarget scan = scan_target(scan_slots, scan_nc, s);
     const unsigned long long flip = negate ? 1ull << 63 : 0ull;
     fill_u64_kernel<<<dim3((unsigned)((n_pad + 255) / 256)), dim3(256), 0, st>>>(colmax, n_pad, 0ull);
     hipError_t e = hipGetLastError();
@@ -863,16 +928,18 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
     const int j_tiles = (int)(n_pad / kColTileJ);
     if (j_tiles * l_tiles > 0x7fffffffll) return hipErrorInvalidValue;   // beyond any grid (and any memory)
     const dim3 grid((unsigned)(j_tiles * l_tiles));
-    if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, E, j_tiles, flip);
-    else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, E, j_tiles, flip);
+    if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, E, j_tiles, flip, SecondPlane{}, scan);
+    else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, E, j_tiles, flip, SecondPlane{}, scan);
     return hipGetLastError();
 }
 
 // Both planes of an interleaved complex operand (element stride 2) in three launches: colmax holds 2 n_pad entries.
 hipError_t launch_split_cols_complex(const double* B, int64_t ldb, int64_t k, int64_t n, int s, int8_t* S_re, int8_t* S_im,
                                      int64_t n_pad, int64_t k_pad, int32_t* E_re, int32_t* E_im,
-                                     unsigned long long* colmax, hipStream_t st, bool negate_im) {
+                                     unsigned long long* colmax, hipStream_t st, bool negate_im,
+                                     unsigned long long* scan_slots) {
     if (n_pad == 0) return hipSuccess;
+    const ScanTarget scan = scan_target(scan_slots, 2 * kScanCounters, s);
     fill_u64_kernel<<<dim3((unsigned)((2 * n_pad + 255) / 256)), dim3(256), 0, st>>>(colmax, 2 * n_pad, 0ull);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -896,8 +963,8 @@ hipError_t launch_split_cols_complex(const double* B, int64_t ldb, int64_t k, in
     const int j_tiles = (int)(n_pad / kColTileJ);
     if (j_tiles * l_tiles > 0x7fffffffll) return hipErrorInvalidValue;   // beyond any grid (and any memory)
     const dim3 grid((unsigned)(j_tiles * l_tiles), 1, 2);
-    if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, 2, k, n, s, S_re, n_pad, k_pad, colmax, E_re, j_tiles, 0ull, second);
-    else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, 2, k, n, s, S_re, n_pad, k_pad, colmax, E_re, j_tiles, 0ull, second);
+    if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, 2, k, n, s, S_re, n_pad, k_pad, colmax, E_re, j_tiles, 0ull, second, scan);
+    else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, 2, k, n, s, S_re, n_pad, k_pad, colmax, E_re, j_tiles, 0ull, second, scan);
     return hipGetLastError();
 }
 

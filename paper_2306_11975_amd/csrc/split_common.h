@@ -103,6 +103,50 @@ __device__ __forceinline__ void loss_position(unsigned long long bits, int E, ui
     L = (uint32_t)LL;
 }
 
+// What the check of a guessed slice count g needs of a plane: sums of |v - 7 g|, |z - 7 g|, the same for g - 1, and of
+// the stored bits L (v = z + L); the bits lost with s slices are (sum |v - 7 s| - sum |z - 7 s| + sum L) / 2.
+constexpr int kScanCounters = 5;
+struct ScanCount {
+    uint32_t sv_g, sz_g, sv_h, sz_h, bits;
+};
+// A kernel that counts while it splits: per plane five 64-bit counters in one of kScanSlots slots (a workgroup adds
+// into slot blockIdx.x % kScanSlots: few workgroups meet on an address), nc counters to a slot.
+constexpr int kScanSlots = 2048;
+struct ScanTarget {
+    unsigned long long* slots;   // null: no counting; else zeroed [kScanSlots][nc], this plane's five at + 0 .. 4
+    int nc;                      // counters per slot (5 per plane of the operand)
+    uint32_t edge_g, edge_h;     // 7 g and 7 (g - 1) in every byte
+};
+__device__ __forceinline__ void scan_count4(ScanCount& a, const unsigned long long (&b)[4], int E, uint32_t edge_g, uint32_t edge_h) {
+    uint32_t pz = 0, pl = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        uint32_t z, L;
+        loss_position(b[u], E, z, L);
+        pz |= z << (8 * u);
+        pl |= L << (8 * u);
+    }
+    const uint32_t pv = pz + pl;   // bytewise: no byte exceeds 165
+    a.bits = __builtin_amdgcn_sad_u8(pl, 0u, a.bits);
+    a.sv_g = __builtin_amdgcn_sad_u8(pv, edge_g, a.sv_g);
+    a.sz_g = __builtin_amdgcn_sad_u8(pz, edge_g, a.sz_g);
+    a.sv_h = __builtin_amdgcn_sad_u8(pv, edge_h, a.sv_h);
+    a.sz_h = __builtin_amdgcn_sad_u8(pz, edge_h, a.sz_h);
+}
+// The workgroup's counters -> its slot. lds: five zeroed words; every thread of the workgroup calls this.
+__device__ __forceinline__ void scan_flush(const ScanCount& a, unsigned* lds, const ScanTarget& t) {
+    unsigned c[kScanCounters] = {a.sv_g, a.sz_g, a.sv_h, a.sz_h, a.bits};
+#pragma unroll
+    for (int i = 0; i < kScanCounters; ++i) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) c[i] += __shfl_xor(c[i], off, 64);
+        if ((threadIdx.x & 63) == 0 && c[i]) atomicAdd(&lds[i], c[i]);
+    }
+    __syncthreads();
+    if (threadIdx.x < kScanCounters && lds[threadIdx.x])
+        atomicAdd(&t.slots[(size_t)(blockIdx.x % kScanSlots) * t.nc + threadIdx.x], (unsigned long long)lds[threadIdx.x]);
+}
+
 // sum over the row of 16 lanes, left in every lane of it (rotations by 8, 4, 2, 1)
 template <int N>
 __device__ __forceinline__ unsigned row_sum_step(unsigned x) {

@@ -42,9 +42,10 @@ def test_geometry_and_workspace_size():
     assert ozimmu.slice_geometry(0, 0) == (0, 0)
     s, m, n, k = 8, 8192, 8192, 8192
     ws = ozimmu.workspace_bytes(m, n, k, s)
-    # slices of A and B, exponents and column maxima: every integer sum stays in registers
+    # slices of A and B, exponents, column maxima and the counters of the splitters that count for the slice-count
+    # check (2 operands x 2048 slots x 5 x 8 bytes): every integer sum stays in registers
     lower = s * m * k * 2
-    assert lower <= ws <= lower + 4 * (m + n) + 8 * n + 16 * 256
+    assert lower <= ws <= lower + 4 * (m + n) + 8 * n + 2 * 2048 * 5 * 8 + 16 * 256
     # long k: a diagonal no longer fits one INT32 block, INT64 diagonal sums are kept in the workspace
     ws_wide = ozimmu.workspace_bytes(4096, 4096, 131072, 8)
     assert ws_wide >= 8 * 4096 * 131072 * 2 + 8 * 4096 * 4096 * 8
