@@ -60,7 +60,7 @@ __device__ __forceinline__ void emit_word(const unsigned long long (&b)[4], int 
         if (p <= s) *reinterpret_cast<uint32_t*>(dst + (int64_t)(p - 1) * slice_stride) = packed_slice<WIDE>(x, sm, p);
 }
 
-template <bool WIDE, bool CACHED, bool VEC>
+template <bool WIDE, bool CACHED, bool VEC, bool SCAN>   // SCAN: also count for the slice-count check (scan.slots is set)
 __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_kernel(const double* __restrict__ A, int64_t lda,
                                                                        int inc, int m, int64_t k, int s,
                                                                        int8_t* __restrict__ S, int64_t m_pad,
@@ -72,8 +72,8 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_kernel(const dou
     const int r4 = lane >> 4, c16 = lane & 15;
     const int row = blockIdx.x * kRowGroup + r4;
     const bool live = row < m;                       // padding rows: zeros in every slice
-    __shared__ unsigned scan_lds[kScanCounters];
-    if (scan.slots && tid < kScanCounters) scan_lds[tid] = 0u;   // (the barrier after the maxima publishes it)
+    __shared__ unsigned scan_lds[SCAN ? kScanCounters : 1];
+    if (SCAN && tid < kScanCounters) scan_lds[tid] = 0u;   // (the barrier after the maxima publishes it)
     ScanCount cnt = {};
     const int64_t slice_stride = m_pad * k_pad;
     // chunk c of a row = its elements [64 c, 64 c + 64); the wavefronts take the chunks round-robin
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_kernel(const dou
         for (int j = 0; j < kRowCacheWords; ++j) {
             const int64_t l0 = ((int64_t)(wave + nwaves * j) * 16 + c16) * 4;
             if (l0 < k_pad) emit_word<WIDE>(cache[j], E, s, S + word_offset(row, l0, k_pad), slice_stride, flip);
-            if (scan.slots) scan_count4(cnt, cache[j], E, scan.edge_g, scan.edge_h);
+            if constexpr (SCAN) scan_count4(cnt, cache[j], E, scan.edge_g, scan.edge_h);
         }
     } else {
         for (int64_t c = wave; c < chunks; c += nwaves) {
@@ -134,11 +134,11 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_kernel(const dou
                 unsigned long long b[4];
                 load_word<VEC>(src, l0, k_live, inc, b);
                 emit_word<WIDE>(b, E, s, S + word_offset(row, l0, k_pad), slice_stride, flip);
-                if (scan.slots) scan_count4(cnt, b, E, scan.edge_g, scan.edge_h);
+                if constexpr (SCAN) scan_count4(cnt, b, E, scan.edge_g, scan.edge_h);
             }
         }
     }
-    if (scan.slots) scan_flush(cnt, scan_lds, scan);
+    if constexpr (SCAN) scan_flush(cnt, scan_lds, scan);
 }
 
 // Rows of an interleaved complex operand, both planes in one pass: the same mapping as above, a thread's
@@ -147,13 +147,13 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_kernel(const dou
 // stride 2 fetches every line twice). Rows of up to 4096 elements (they stay in registers); longer
 // ones take the two strided passes.
 constexpr int kZRowCacheWords = 4;
-template <bool WIDE>
+template <bool WIDE, bool SCAN>
 __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_complex_kernel(
     const double* __restrict__ Z, int64_t ldz, int m, int64_t k, int s, int8_t* __restrict__ S_re,
     int8_t* __restrict__ S_im, int64_t m_pad, int64_t k_pad, int32_t* __restrict__ E_re, int32_t* __restrict__ E_im,
     unsigned long long flip_re, unsigned long long flip_im, ScanTarget scan) {   // scan: the real plane's counters, the imaginary one's five behind
-    __shared__ unsigned scan_lds[2][kScanCounters];
-    if (scan.slots && threadIdx.x < 2 * kScanCounters) (&scan_lds[0][0])[threadIdx.x] = 0u;   // (published by the barrier after the maxima)
+    __shared__ unsigned scan_lds[2][SCAN ? kScanCounters : 1];
+    if (SCAN && threadIdx.x < 2 * kScanCounters) (&scan_lds[0][0])[threadIdx.x] = 0u;   // (published by the barrier after the maxima)
     ScanCount cnt_re = {}, cnt_im = {};
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
@@ -211,12 +211,12 @@ __global__ __launch_bounds__(64 * kRowWavesMax) void split_rows_complex_kernel(
             emit_word<WIDE>(re[j], e_re, s, S_re + off, slice_stride, flip_re);
             emit_word<WIDE>(im[j], e_im, s, S_im + off, slice_stride, flip_im);
         }
-        if (scan.slots) {
+        if constexpr (SCAN) {
             scan_count4(cnt_re, re[j], e_re, scan.edge_g, scan.edge_h);
             scan_count4(cnt_im, im[j], e_im, scan.edge_g, scan.edge_h);
         }
     }
-    if (scan.slots) {
+    if constexpr (SCAN) {
         scan_flush(cnt_re, scan_lds[0], scan);
         ScanTarget second = scan;
         second.slots += kScanCounters;
@@ -281,7 +281,7 @@ constexpr int kColTileL = 64, kColTileJ = 64;
 constexpr int kColWords = kColTileL / 4 / 4;   // words of four consecutive l per thread
 constexpr int kColGroup = 4;   // slices transposed through LDS at a time
 constexpr int kColLdsStride = kColTileL / 4 + 1;  // words per LDS row (+1: conflict-free columns)
-template <bool WIDE>
+template <bool WIDE, bool SCAN>
 __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restrict__ B, int64_t ldb,
                                                          int inc, int64_t k, int64_t n, int s,
                                                          int8_t* __restrict__ S, int64_t n_pad,
@@ -291,8 +291,8 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
                                                          unsigned long long flip,    // sign bit, or 0: slices of -B
                                                          SecondPlane second = SecondPlane{}, ScanTarget scan = ScanTarget{}) {
     __shared__ uint32_t tile[kColGroup][kColTileJ][kColLdsStride];
-    __shared__ unsigned scan_lds[kScanCounters];
-    if (scan.slots && threadIdx.x < kScanCounters) scan_lds[threadIdx.x] = 0u;   // (published by the barriers of the write-out)
+    __shared__ unsigned scan_lds[SCAN ? kScanCounters : 1];
+    if (SCAN && threadIdx.x < kScanCounters) scan_lds[threadIdx.x] = 0u;   // (published by the barriers of the write-out)
     ScanCount cnt = {};
     if (blockIdx.z) {
         B += second.b;
@@ -300,7 +300,7 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
         S += second.slices;
         Eout += second.e;
         flip = second.flip;
-        if (scan.slots) scan.slots += kScanCounters;
+        if (SCAN) scan.slots += kScanCounters;
     }
     const int tid = threadIdx.x;
     const int jj = tid & 63, lg = tid >> 6;
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
 #pragma unroll
         for (int u = 0; u < 4; ++u) x[u4][u] = to_fixed<WIDE>(b[u], E);
         sm[u4] = sign_mask(b[0] ^ flip, b[1] ^ flip, b[2] ^ flip, b[3] ^ flip);
-        if (scan.slots) scan_count4(cnt, b, E, scan.edge_g, scan.edge_h);
+        if constexpr (SCAN) scan_count4(cnt, b, E, scan.edge_g, scan.edge_h);
     }
 #pragma unroll
     for (int p0 = 1; p0 <= (WIDE ? OZIMMU_MAX_SLICES : 9); p0 += kColGroup) {   // unrolled: slice numbers are constants
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const double* __restric
         }
         __syncthreads();
     }
-    if (scan.slots) scan_flush(cnt, scan_lds, scan);
+    if constexpr (SCAN) scan_flush(cnt, scan_lds, scan);
 }
 
 // The slots of a counting splitter -> the bits each of the operand's planes loses with s and with s - 1 slices:
@@ -825,7 +825,8 @@ hipError_t launch_split_rows(const double* A, int64_t lda, int inc, int64_t m, i
     const bool cached = k_pad <= (int64_t)64 * kRowCacheWords * nwaves;
     const bool vec = inc == 1 && lda % 2 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0;
     const dim3 grid((unsigned)(m_pad / kRowGroup)), block(64 * nwaves);
-#define OZ_ROWS(W, C, V) split_rows_kernel<W, C, V><<<grid, block, 0, st>>>(A, lda * inc, inc, (int)m, k, s, S, m_pad, k_pad, E, flip, scan)
+#define OZ_ROWS(W, C, V) do { if (scan.slots) split_rows_kernel<W, C, V, true><<<grid, block, 0, st>>>(A, lda * inc, inc, (int)m, k, s, S, m_pad, k_pad, E, flip, scan); \
+                              else split_rows_kernel<W, C, V, false><<<grid, block, 0, st>>>(A, lda * inc, inc, (int)m, k, s, S, m_pad, k_pad, E, flip, scan); } while (0)
     if (wide) {
         if (cached) { if (vec) OZ_ROWS(true, true, true); else OZ_ROWS(true, true, false); }
         else        { if (vec) OZ_ROWS(true, false, true); else OZ_ROWS(true, false, false); }
@@ -851,8 +852,10 @@ hipError_t launch_split_rows_complex(const double* Z, int64_t ldz, int64_t m, in
     const int nwaves = (int)(want < 1 ? 1 : want);
     const unsigned long long flip_im = negate_im ? 1ull << 63 : 0ull;
     const dim3 grid((unsigned)(m_pad / kRowGroup)), block(64 * nwaves);
-    if (s > 9) split_rows_complex_kernel<true><<<grid, block, 0, st>>>(Z, ldz, (int)m, k, s, S_re, S_im, m_pad, k_pad, E_re, E_im, 0ull, flip_im, scan);
-    else split_rows_complex_kernel<false><<<grid, block, 0, st>>>(Z, ldz, (int)m, k, s, S_re, S_im, m_pad, k_pad, E_re, E_im, 0ull, flip_im, scan);
+#define OZ_ZROWS(W, SC) split_rows_complex_kernel<W, SC><<<grid, block, 0, st>>>(Z, ldz, (int)m, k, s, S_re, S_im, m_pad, k_pad, E_re, E_im, 0ull, flip_im, scan)
+    if (s > 9) { if (scan.slots) OZ_ZROWS(true, true); else OZ_ZROWS(true, false); }
+    else       { if (scan.slots) OZ_ZROWS(false, true); else OZ_ZROWS(false, false); }
+#undef OZ_ZROWS
     return hipGetLastError();
 }
 
@@ -928,8 +931,10 @@ hipError_t launch_split_cols(const double* B, int64_t ldb, int inc, int64_t k, i
     const int j_tiles = (int)(n_pad / kColTileJ);
     if (j_tiles * l_tiles > 0x7fffffffll) return hipErrorInvalidValue;   // beyond any grid (and any memory)
     const dim3 grid((unsigned)(j_tiles * l_tiles));
-    if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, E, j_tiles, flip, SecondPlane{}, scan);
-    else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, E, j_tiles, flip, SecondPlane{}, scan);
+#define OZ_COLS(W, SC) split_cols_kernel<W, SC><<<grid, dim3(256), 0, st>>>(B, ldb, inc, k, n, s, S, n_pad, k_pad, colmax, E, j_tiles, flip, SecondPlane{}, scan)
+    if (s > 9) { if (scan.slots) OZ_COLS(true, true); else OZ_COLS(true, false); }
+    else       { if (scan.slots) OZ_COLS(false, true); else OZ_COLS(false, false); }
+#undef OZ_COLS
     return hipGetLastError();
 }
 
@@ -963,8 +968,10 @@ hipError_t launch_split_cols_complex(const double* B, int64_t ldb, int64_t k, in
     const int j_tiles = (int)(n_pad / kColTileJ);
     if (j_tiles * l_tiles > 0x7fffffffll) return hipErrorInvalidValue;   // beyond any grid (and any memory)
     const dim3 grid((unsigned)(j_tiles * l_tiles), 1, 2);
-    if (s > 9) split_cols_kernel<true><<<grid, dim3(256), 0, st>>>(B, ldb, 2, k, n, s, S_re, n_pad, k_pad, colmax, E_re, j_tiles, 0ull, second, scan);
-    else split_cols_kernel<false><<<grid, dim3(256), 0, st>>>(B, ldb, 2, k, n, s, S_re, n_pad, k_pad, colmax, E_re, j_tiles, 0ull, second, scan);
+#define OZ_COLS(W, SC) split_cols_kernel<W, SC><<<grid, dim3(256), 0, st>>>(B, ldb, 2, k, n, s, S_re, n_pad, k_pad, colmax, E_re, j_tiles, 0ull, second, scan)
+    if (s > 9) { if (scan.slots) OZ_COLS(true, true); else OZ_COLS(true, false); }
+    else       { if (scan.slots) OZ_COLS(false, true); else OZ_COLS(false, false); }
+#undef OZ_COLS
     return hipGetLastError();
 }
 
