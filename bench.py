@@ -369,6 +369,25 @@ def main():
                               "mfma_frac": 2.0 * m * n * k * p2 / (gemm2 / reps * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS}
             del ws2, C2
         out["per_slice_count"] = per_s
+        # the automatic mode (Section 4.4, INT8-AUTO) at threshold 1: the choice as a call of its own, and choice and
+        # product as one call with the right guess (the splitters count while they split)
+        ws_auto = torch.empty(max(ozimmu.workspace_bytes(m, n, k, s2) for s2 in range(1, 17)), dtype=torch.uint8, device="cuda")
+        scratch = torch.empty(max(ozimmu.auto_scratch_bytes(n), 256), dtype=torch.uint8, device="cuda")
+        C_auto = torch.empty_like(C)      # (C keeps the product of the timed steps for the parity sample below)
+        s_auto, _ = ozimmu.auto_num_slices(A, B, 1.0, scratch=scratch)
+        t_a = time.perf_counter()
+        for _ in range(3):
+            ozimmu.auto_num_slices(A, B, 1.0, scratch=scratch)
+        choice_ms = (time.perf_counter() - t_a) / 3 * 1e3
+        ozimmu.dgemm_auto(A, B, C_auto, 1.0, guess=s_auto, workspace=ws_auto, scratch=scratch)
+        t_a = time.perf_counter()
+        for _ in range(5):
+            s_got, confirmed = ozimmu.dgemm_auto(A, B, C_auto, 1.0, guess=s_auto, workspace=ws_auto, scratch=scratch)
+        one_call_ms = (time.perf_counter() - t_a) / 5 * 1e3
+        out["automatic_mode"] = {"threshold": 1.0, "num_slices": s_got, "guess_confirmed": bool(confirmed),
+                                 "auto_num_slices_ms": choice_ms, "dgemm_auto_ms": one_call_ms,
+                                 "TFLOPs": 2.0 * m * n * k / (one_call_ms * 1e-3) / 1e12}
+        del ws_auto, C_auto
         # context only: the vendor FP64 GEMM on the same GPU
         for _ in range(2):
             torch.matmul(A, B)
