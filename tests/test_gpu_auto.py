@@ -178,6 +178,24 @@ def test_gemm_auto_is_choice_then_product(cplx, m, n, k, phi, seed):
             assert np.array_equal(bits(C.cpu().numpy()), bits(want)), (T, guess)
 
 
+@pytest.mark.parametrize("cplx,m,n,k", [(False, 6, 33, 8999), (False, 5, 40, 9000), (True, 20, 30, 5000), (True, 9, 70, 4097)])
+def test_gemm_auto_long_rows(cplx, m, n, k):
+    """Rows too long to stay in registers (read twice by the splitter; a complex operand then takes one strided pass
+    per plane), odd leading dimensions: the counting variants of those splitters."""
+    A, B = wl.phi_pair(m, n, k, 1.0, seed=k)
+    if cplx:
+        Ai, Bi = wl.phi_pair(m, n, k, 2.0, seed=k + 1)
+        A, B = A + 1j * Ai, B + 1j * Bi
+    dA, dB = dev(A), dev(B)
+    s_want = oracle.auto_num_slices(A, B, 1.0)[0]
+    want = (oracle.zgemm if cplx else oracle.dgemm)(A, B, s_want)
+    for guess in (s_want, s_want + 1):
+        C = torch.full((m, n), float("nan"), dtype=dA.dtype, device="cuda")
+        s_got, confirmed = (ozimmu.zgemm_auto if cplx else ozimmu.dgemm_auto)(dA, dB, C, 1.0, guess=guess)
+        assert (s_got, confirmed) == (s_want, guess == s_want)
+        assert np.array_equal(bits(C.cpu().numpy()), bits(want))
+
+
 def test_gemm_auto_rejects_a_workspace_too_small_for_the_largest_count():
     A, B = wl.phi_pair(200, 100, 300, 1.0, 7)
     dA, dB = dev(A), dev(B)
