@@ -20,7 +20,7 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). All work is
  *     enqueued on it; no entry point synchronises, allocates or frees device memory, or
  *     keeps state between calls (exceptions, stated where they are declared:
- *     ozimmu_auto_num_slices, ozimmu_dgemm_auto and ozimmu_zgemm_auto return a value to the host and wait for the stream;
+ *     ozimmu_auto_num_slices and the *_auto products return a value to the host and wait for the stream;
  *     ozimmu_dgemm_static uses the library's own scratch array; the library remembers per
  *     device that it has raised a kernel's dynamic LDS limit). Calls that share a workspace must
  *     be stream-ordered.
@@ -316,6 +316,28 @@ ozimmu_status_t ozimmu_auto_num_slices_blas(char transa, char transb, int64_t m,
                                             int is_complex, double threshold, int max_slices, void* scratch,
                                             size_t scratch_bytes, int* num_slices, uint64_t* loss_sums,
                                             void* stream);
+
+/*
+ * ozimmu_auto_num_slices_blas followed by ozimmu_dgemm_blas / ozimmu_zgemm_blas with the count it chose, as
+ * one call, with `guess` as for ozimmu_dgemm_auto. The product is formed on the guess only when it
+ * overwrites C (beta = 0: with another beta a wrong guess would have used up C's old values); then the
+ * splitters count while they split (a small complex gate on a wide state, untransposed, with alpha = 1:
+ * the one-kernel path of ozimmu_zgemm_auto). Otherwise the count is chosen first. workspace: at least
+ * the largest ozimmu_workspace_bytes(n, m, k, s, 0) / ozimmu_zgemm_blas_workspace_bytes(m, n, k, s,
+ * beta == 0) over s = 1 .. max_slices; scratch: at least ozimmu_auto_scratch_bytes(max(m, n)).
+ * Everything else as for the calls it stands for and for ozimmu_dgemm_auto.
+ */
+ozimmu_status_t ozimmu_dgemm_blas_auto(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha,
+                                       const double* A, int64_t lda, const double* B, int64_t ldb, double beta,
+                                       double* C, int64_t ldc, double threshold, int max_slices, int guess,
+                                       void* workspace, size_t workspace_bytes, void* scratch,
+                                       size_t scratch_bytes, int* num_slices, int* guess_confirmed, void* stream);
+ozimmu_status_t ozimmu_zgemm_blas_auto(char transa, char transb, int64_t m, int64_t n, int64_t k,
+                                       const double* alpha, const double* A, int64_t lda, const double* B,
+                                       int64_t ldb, const double* beta, double* C, int64_t ldc, double threshold,
+                                       int max_slices, int guess, void* workspace, size_t workspace_bytes,
+                                       void* scratch, size_t scratch_bytes, int* num_slices,
+                                       int* guess_confirmed, void* stream);
 
 #ifdef __cplusplus
 }

@@ -627,10 +627,12 @@ ozimmu_status_t ozimmu_auto_num_slices_blas(char transa, char transb, int64_t m,
                        loss_sums, stream);
 }
 
-ozimmu_status_t ozimmu_dgemm_blas(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha,
-                                  const double* A, int64_t lda, const double* B, int64_t ldb, double beta, double* C,
-                                  int64_t ldc, int num_slices, void* workspace, size_t workspace_bytes,
-                                  void* stream) {
+// count_sums (device or mapped host memory, [2][16]; or null): the splitters also count for the check of num_slices as
+// the automatic slice count, and the bits op(A) and op(B) lose with num_slices and num_slices - 1 slices arrive there.
+static ozimmu_status_t dgemm_blas_impl(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha,
+                                       const double* A, int64_t lda, const double* B, int64_t ldb, double beta, double* C,
+                                       int64_t ldc, int num_slices, void* workspace, size_t workspace_bytes,
+                                       void* stream, unsigned long long* count_sums) {
     const int pa = parse_trans(transa), pb = parse_trans(transb);
     if (pa < 0 || pb < 0 || !dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
     const bool ta = pa != 0, tb = pb != 0;
@@ -654,15 +656,30 @@ ozimmu_status_t ozimmu_dgemm_blas(char transa, char transb, int64_t m, int64_t n
     int32_t* ER = reinterpret_cast<int32_t*>(ws + L.off_ea[0]);
     int32_t* EC = reinterpret_cast<int32_t*>(ws + L.off_eb[0]);
     unsigned long long* colmax = reinterpret_cast<unsigned long long*>(ws + L.off_colmax);
-    hipError_t e;
-    if (!tb) e = launch_split_rows(B, ldb, 1, n, k, num_slices, SR, L.m_pad, L.k_pad, ER, st);   // B: k x n, column j contiguous
-    else e = launch_split_cols(B, ldb, 1, k, n, num_slices, SR, L.m_pad, L.k_pad, ER, colmax, st);  // B: n x k
+    hipError_t e = hipSuccess;
+    unsigned long long* slots_a = count_sums ? reinterpret_cast<unsigned long long*>(ws + L.off_scan) : nullptr;
+    unsigned long long* slots_b = count_sums ? slots_a + scan_slots_bytes(1) / sizeof(unsigned long long) : nullptr;
+    if (count_sums) e = launch_fill_u64(slots_a, (int64_t)(2 * scan_slots_bytes(1) / sizeof(unsigned long long)), 0ull, st);
     if (e == hipSuccess) {
-        if (!ta) e = launch_split_cols(A, lda, 1, k, m, num_slices, SC, L.n_pad, L.k_pad, EC, colmax, st);  // A: m x k
-        else e = launch_split_rows(A, lda, 1, m, k, num_slices, SC, L.n_pad, L.k_pad, EC, st);              // A: k x m
+        if (!tb) e = launch_split_rows(B, ldb, 1, n, k, num_slices, SR, L.m_pad, L.k_pad, ER, st, false, slots_b, 5);   // B: k x n, column j contiguous
+        else e = launch_split_cols(B, ldb, 1, k, n, num_slices, SR, L.m_pad, L.k_pad, ER, colmax, st, false, slots_b, 5);  // B: n x k
     }
+    if (e == hipSuccess) {
+        if (!ta) e = launch_split_cols(A, lda, 1, k, m, num_slices, SC, L.n_pad, L.k_pad, EC, colmax, st, false, slots_a, 5);  // A: m x k
+        else e = launch_split_rows(A, lda, 1, m, k, num_slices, SC, L.n_pad, L.k_pad, EC, st, false, slots_a, 5);              // A: k x m
+    }
+    if (e == hipSuccess && count_sums) e = launch_scan_reduce(slots_a, 1, num_slices, count_sums, st);
+    if (e == hipSuccess && count_sums) e = launch_scan_reduce(slots_b, 1, num_slices, count_sums + OZIMMU_MAX_SLICES, st);
     if (e == hipSuccess) e = run_product(L, n, m, num_slices, ws, 0, 0, C, ldc, 3, st, alpha, beta);
     return hip_status(e);
+}
+
+ozimmu_status_t ozimmu_dgemm_blas(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha,
+                                  const double* A, int64_t lda, const double* B, int64_t ldb, double beta, double* C,
+                                  int64_t ldc, int num_slices, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+    return dgemm_blas_impl(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_slices, workspace,
+                           workspace_bytes, stream, nullptr);
 }
 
 ozimmu_status_t ozimmu_zgemm_blas_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_slices, int beta_is_zero,
@@ -676,10 +693,12 @@ ozimmu_status_t ozimmu_zgemm_blas_workspace_bytes(int64_t m, int64_t n, int64_t 
     return OZIMMU_OK;
 }
 
-ozimmu_status_t ozimmu_zgemm_blas(char transa, char transb, int64_t m, int64_t n, int64_t k, const double* alpha,
-                                  const double* A, int64_t lda, const double* B, int64_t ldb, const double* beta,
-                                  double* C, int64_t ldc, int num_slices, void* workspace, size_t workspace_bytes,
-                                  void* stream) {
+// count_sums ([4][16]: op(A) re, im, op(B) re, im; or null): as for dgemm_blas_impl; with counting the general path is
+// taken whatever the shape.
+static ozimmu_status_t zgemm_blas_impl(char transa, char transb, int64_t m, int64_t n, int64_t k, const double* alpha,
+                                       const double* A, int64_t lda, const double* B, int64_t ldb, const double* beta,
+                                       double* C, int64_t ldc, int num_slices, void* workspace, size_t workspace_bytes,
+                                       void* stream, unsigned long long* count_sums) {
     const int ta = parse_trans(transa), tb = parse_trans(transb);
     if (ta < 0 || tb < 0 || !dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
     if (num_slices < 1 || num_slices > OZIMMU_MAX_SLICES) return OZIMMU_ERR_BAD_SLICES;
@@ -710,29 +729,125 @@ ozimmu_status_t ozimmu_zgemm_blas(char transa, char transb, int64_t m, int64_t n
     const int64_t ldg = beta_zero ? ldc : m;
     // Neither operand transposed, a small A on a wide B (a gate on a state vector whose amplitudes are the columns'
     // entries): the row-major product B^T A^T has the state as its tall operand and takes the one-kernel path.
-    if (!ta && !tb && gate_product_applies(B, A, G, m, k, num_slices)) {
+    if (!count_sums && !ta && !tb && gate_product_applies(B, A, G, m, k, num_slices)) {
         e = launch_gate_product(B, ldb, n, k, m, A, lda, num_slices, ws + L.off_gate, G, ldg, st);
         if (e == hipSuccess && !(beta_zero && alpha_one)) e = launch_zaxpby(G, ldg, C, ldc, n, m, ar, ai, br, bi, st);
         return hip_status(e);
     }
+    unsigned long long* slots_a = count_sums ? reinterpret_cast<unsigned long long*>(ws + L.off_scan) : nullptr;
+    unsigned long long* slots_b = count_sums ? slots_a + scan_slots_bytes(2) / sizeof(unsigned long long) : nullptr;
+    if (count_sums) e = launch_fill_u64(slots_a, (int64_t)(2 * scan_slots_bytes(2) / sizeof(unsigned long long)), 0ull, st);
     // planes: real, then imaginary (negated while splitting if the operand is conjugated)
-    if (!tb) e = split_complex_rows(B, ldb, n, k, num_slices, ws, L.off_sa, L.off_ea, L.m_pad, L.k_pad, st, false);   // op(B)^T: n rows of length k
-    else
-        e = launch_split_cols_complex(B, ldb, k, n, num_slices, reinterpret_cast<int8_t*>(ws + L.off_sa[0]),
-                                      reinterpret_cast<int8_t*>(ws + L.off_sa[1]), L.m_pad, L.k_pad,
-                                      reinterpret_cast<int32_t*>(ws + L.off_ea[0]), reinterpret_cast<int32_t*>(ws + L.off_ea[1]),
-                                      colmax, st, tb == 2);
     if (e == hipSuccess) {
-        if (ta) e = split_complex_rows(A, lda, m, k, num_slices, ws, L.off_sb, L.off_eb, L.n_pad, L.k_pad, st, ta == 2);   // op(A): m rows of length k
+        if (!tb) e = split_complex_rows(B, ldb, n, k, num_slices, ws, L.off_sa, L.off_ea, L.m_pad, L.k_pad, st, false, slots_b);   // op(B)^T: n rows of length k
+        else
+            e = launch_split_cols_complex(B, ldb, k, n, num_slices, reinterpret_cast<int8_t*>(ws + L.off_sa[0]),
+                                          reinterpret_cast<int8_t*>(ws + L.off_sa[1]), L.m_pad, L.k_pad,
+                                          reinterpret_cast<int32_t*>(ws + L.off_ea[0]), reinterpret_cast<int32_t*>(ws + L.off_ea[1]),
+                                          colmax, st, tb == 2, slots_b);
+    }
+    if (e == hipSuccess) {
+        if (ta) e = split_complex_rows(A, lda, m, k, num_slices, ws, L.off_sb, L.off_eb, L.n_pad, L.k_pad, st, ta == 2, slots_a);   // op(A): m rows of length k
         else
             e = launch_split_cols_complex(A, lda, k, m, num_slices, reinterpret_cast<int8_t*>(ws + L.off_sb[0]),
                                           reinterpret_cast<int8_t*>(ws + L.off_sb[1]), L.n_pad, L.k_pad,
                                           reinterpret_cast<int32_t*>(ws + L.off_eb[0]), reinterpret_cast<int32_t*>(ws + L.off_eb[1]),
-                                          colmax, st, false);
+                                          colmax, st, false, slots_a);
     }
+    if (e == hipSuccess && count_sums) e = launch_scan_reduce(slots_a, 2, num_slices, count_sums, st);
+    if (e == hipSuccess && count_sums) e = launch_scan_reduce(slots_b, 2, num_slices, count_sums + 2 * OZIMMU_MAX_SLICES, st);
     if (e == hipSuccess) e = run_complex_products(L, n, m, num_slices, ws, G, ldg, st);
     if (e == hipSuccess && !(beta_zero && alpha_one)) e = launch_zaxpby(G, ldg, C, ldc, n, m, ar, ai, br, bi, st);
     return hip_status(e);
+}
+
+ozimmu_status_t ozimmu_zgemm_blas(char transa, char transb, int64_t m, int64_t n, int64_t k, const double* alpha,
+                                  const double* A, int64_t lda, const double* B, int64_t ldb, const double* beta,
+                                  double* C, int64_t ldc, int num_slices, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+    return zgemm_blas_impl(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_slices, workspace,
+                           workspace_bytes, stream, nullptr);
+}
+
+// ozimmu_auto_num_slices_blas followed by ozimmu_dgemm_blas / ozimmu_zgemm_blas, as one call (see ozimmu.h).
+static ozimmu_status_t gemm_blas_auto(bool cplx, char transa, char transb, int64_t m, int64_t n, int64_t k,
+                                      const double* alpha, const double* A, int64_t lda, const double* B, int64_t ldb,
+                                      const double* beta, double* C, int64_t ldc, double threshold, int max_slices,
+                                      int guess, void* workspace, size_t workspace_bytes, void* scratch,
+                                      size_t scratch_bytes, int* num_slices, int* guess_confirmed, void* stream) {
+    if (max_slices < 1 || max_slices > OZIMMU_MAX_SLICES || !(threshold >= 0.0)) return OZIMMU_ERR_BAD_SLICES;
+    if (!num_slices || !alpha || !beta) return OZIMMU_ERR_NULL;
+    if (guess_confirmed) *guess_confirmed = 0;
+    if (parse_trans(transa) < 0 || parse_trans(transb) < 0 || !dims_ok(m, n, k)) return OZIMMU_ERR_BAD_DIM;
+    const bool beta_zero = beta[0] == 0.0 && (!cplx || beta[1] == 0.0);
+    const bool alpha_zero = alpha[0] == 0.0 && (!cplx || alpha[1] == 0.0);
+    // the workspace must serve whichever slice count comes out
+    for (int s = 1; s <= max_slices; ++s) {
+        size_t need = 0;
+        const ozimmu_status_t rc = cplx ? ozimmu_zgemm_blas_workspace_bytes(m, n, k, s, beta_zero, &need)
+                                        : ozimmu_workspace_bytes(n, m, k, s, 0, &need);
+        if (rc != OZIMMU_OK) return rc;
+        if (m > 0 && n > 0 && k > 0 && !alpha_zero && workspace_bytes < need) return OZIMMU_ERR_WORKSPACE;
+    }
+    if (!scratch_ok(scratch, scratch_bytes, std::max(m, n))) return OZIMMU_ERR_WORKSPACE;
+    auto product = [&](int s, unsigned long long* count_sums) {
+        return cplx ? zgemm_blas_impl(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, s, workspace,
+                                      workspace_bytes, stream, count_sums)
+                    : dgemm_blas_impl(transa, transb, m, n, k, alpha[0], A, lda, B, ldb, beta[0], C, ldc, s, workspace,
+                                      workspace_bytes, stream, count_sums);
+    };
+    // Only a product that overwrites C can be formed on a guess: with beta != 0 a wrong guess would have used up C's old values.
+    const bool speculate = guess >= 1 && guess <= max_slices && beta_zero && !alpha_zero && m > 0 && n > 0 && k > 0;
+    unsigned long long* host = speculate ? mapped_sums() : nullptr;
+    if (host) {
+        const ozimmu_status_t rc = product(guess, host);
+        if (rc != OZIMMU_OK) return rc;
+        if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return OZIMMU_ERR_HIP;
+        const int planes = cplx ? 4 : 2;
+        const double count_a = (double)m * (double)k, count_b = (double)k * (double)n;
+        auto within = [&](int s) {
+            bool ok = true;
+            for (int p = 0; p < planes; ++p)
+                ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < planes / 2 ? count_a : count_b);
+            return ok;
+        };
+        if ((within(guess) || guess == max_slices) && (guess == 1 || !within(guess - 1))) {
+            *num_slices = guess;
+            if (guess_confirmed) *guess_confirmed = 1;
+            return OZIMMU_OK;
+        }
+    }
+    int s = 0;
+    ozimmu_status_t rc = ozimmu_auto_num_slices_blas(transa, transb, m, n, k, A, lda, B, ldb, cplx, threshold, max_slices,
+                                                     scratch, scratch_bytes, &s, nullptr, stream);
+    if (rc != OZIMMU_OK) return rc;
+    rc = product(s, nullptr);
+    if (rc == OZIMMU_OK) *num_slices = s;
+    return rc;
+}
+
+ozimmu_status_t ozimmu_dgemm_blas_auto(char transa, char transb, int64_t m, int64_t n, int64_t k, double alpha,
+                                       const double* A, int64_t lda, const double* B, int64_t ldb, double beta, double* C,
+                                       int64_t ldc, double threshold, int max_slices, int guess, void* workspace,
+                                       size_t workspace_bytes, void* scratch, size_t scratch_bytes, int* num_slices,
+                                       int* guess_confirmed, void* stream) {
+    return gemm_blas_auto(false, transa, transb, m, n, k, &alpha, A, lda, B, ldb, &beta, C, ldc, threshold, max_slices,
+                          guess, workspace, workspace_bytes, scratch, scratch_bytes, num_slices, guess_confirmed, stream);
+}
+
+ozimmu_status_t ozimmu_zgemm_blas_auto(char transa, char transb, int64_t m, int64_t n, int64_t k, const double* alpha,
+                                       const double* A, int64_t lda, const double* B, int64_t ldb, const double* beta,
+                                       double* C, int64_t ldc, double threshold, int max_slices, int guess,
+                                       void* workspace, size_t workspace_bytes, void* scratch, size_t scratch_bytes,
+                                       int* num_slices, int* guess_confirmed, void* stream) {
+    // a small gate on a wide state, plain product: the one-kernel path, which counts on its way over the state
+    if (alpha && beta && alpha[0] == 1.0 && alpha[1] == 0.0 && beta[0] == 0.0 && beta[1] == 0.0 &&
+        parse_trans(transa) == 0 && parse_trans(transb) == 0 && m > 0 && n > 0 && k > 0 && guess >= 1 &&
+        guess <= OZIMMU_MAX_SLICES && lda >= m && ldb >= k && ldc >= m && gate_product_applies(B, A, C, m, k, guess))
+        return gemm_auto(true, n, m, k, B, ldb, A, lda, C, ldc, threshold, max_slices, guess, workspace, workspace_bytes,
+                         scratch, scratch_bytes, num_slices, guess_confirmed, stream);
+    return gemm_blas_auto(true, transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, threshold, max_slices,
+                          guess, workspace, workspace_bytes, scratch, scratch_bytes, num_slices, guess_confirmed, stream);
 }
 
 ozimmu_status_t ozimmu_dgemm_dd(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B,

@@ -175,17 +175,17 @@ bool compute(const Call& c, hipStream_t stream) {
     const bool product = c.k > 0 && !alpha_zero;
     int s = cfg.slices > 0 ? cfg.slices : 1;
     size_t scan_bytes = 0;
-    // A plain product in automatic mode (no transposes, alpha 1, beta 0; in row-major terms C^T = B^T A^T): count and
-    // product in one call, the count of the previous such call as the guess. A small complex gate (A, m x k) on a tall
-    // state (B, k x n) is then formed in one pass over the state; other shapes save the wait between choice and product.
-    const bool alpha_one = c.alpha[0] == 1.0 && (!c.cplx || c.alpha[1] == 0.0);
-    if (product && cfg.slices == 0 && c.ta == 'N' && c.tb == 'N' && alpha_one && beta_zero) {
+    // A product that overwrites C (beta 0) in automatic mode: count and product in one call, the count of the previous
+    // such call as the guess; the splitters then count while they split (a small complex gate on a wide state is
+    // formed in one pass over the state) and no operand is read just for the choice.
+    if (product && cfg.slices == 0 && beta_zero) {
         size_t ws_bytes = 0;
-        bool sized = ozimmu_auto_scratch_bytes(c.m, &scan_bytes) == OZIMMU_OK;
+        bool sized = ozimmu_auto_scratch_bytes(std::max(c.m, c.n), &scan_bytes) == OZIMMU_OK;
         scan_bytes = align_up(scan_bytes);
         for (int t = 1; sized && t <= OZIMMU_MAX_SLICES; ++t) {
             size_t need = 0;
-            sized = ozimmu_workspace_bytes(c.n, c.m, c.k, t, c.cplx, &need) == OZIMMU_OK;
+            sized = (c.cplx ? ozimmu_zgemm_blas_workspace_bytes(c.m, c.n, c.k, t, 1, &need)
+                            : ozimmu_workspace_bytes(c.n, c.m, c.k, t, 0, &need)) == OZIMMU_OK;
             ws_bytes = std::max(ws_bytes, need);
         }
         // the workspace of the largest slice count may not be available: then the two calls below, sized for the count chosen
@@ -194,18 +194,20 @@ bool compute(const Call& c, hipStream_t stream) {
         int& last = d.last_auto_slices[c.cplx ? 1 : 0];
         if (buf) {
             const ozimmu_status_t rc =
-                c.cplx ? ozimmu_zgemm_auto(c.n, c.m, c.k, c.B, c.ldb, c.A, c.lda, c.C, c.ldc, cfg.threshold, OZIMMU_MAX_SLICES,
-                                           last, buf + scan_bytes, ws_bytes, buf, scan_bytes, &s, &confirmed, stream)
-                       : ozimmu_dgemm_auto(c.n, c.m, c.k, c.B, c.ldb, c.A, c.lda, c.C, c.ldc, cfg.threshold, OZIMMU_MAX_SLICES,
-                                           last, buf + scan_bytes, ws_bytes, buf, scan_bytes, &s, &confirmed, stream);
+                c.cplx ? ozimmu_zgemm_blas_auto(c.ta, c.tb, c.m, c.n, c.k, c.alpha, c.A, c.lda, c.B, c.ldb, c.beta, c.C, c.ldc,
+                                                cfg.threshold, OZIMMU_MAX_SLICES, last, buf + scan_bytes, ws_bytes, buf,
+                                                scan_bytes, &s, &confirmed, stream)
+                       : ozimmu_dgemm_blas_auto(c.ta, c.tb, c.m, c.n, c.k, c.alpha[0], c.A, c.lda, c.B, c.ldb, c.beta[0], c.C,
+                                                c.ldc, cfg.threshold, OZIMMU_MAX_SLICES, last, buf + scan_bytes, ws_bytes,
+                                                buf, scan_bytes, &s, &confirmed, stream);
             if (rc != OZIMMU_OK) return false;   // beta is 0: whatever C holds now, the vendor routine overwrites it
             last = s;
             d.used = true;
             d.last_stream = stream;
             (void)hipEventRecord(d.done, stream);
             if (cfg.verbose)
-                std::fprintf(stderr, "[ozimmu] %s NN m=%lld n=%lld k=%lld slices=%d (auto) [one call%s]\n", c.name,
-                             (long long)c.m, (long long)c.n, (long long)c.k, s, confirmed ? ", guess confirmed" : "");
+                std::fprintf(stderr, "[ozimmu] %s %c%c m=%lld n=%lld k=%lld slices=%d (auto) [one call%s]\n", c.name, c.ta,
+                             c.tb, (long long)c.m, (long long)c.n, (long long)c.k, s, confirmed ? ", guess confirmed" : "");
             return true;
         }
     }

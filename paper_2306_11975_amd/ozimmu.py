@@ -26,7 +26,7 @@ EXPORTS = (
     "ozimmu_slice_gemm", "ozimmu_workspace_bytes", "ozimmu_dgemm", "ozimmu_zgemm", "ozimmu_dgemm_static", "ozimmu_dgemm_stage",
     "ozimmu_launch_plan", "ozimmu_dgemm_dd", "ozimmu_dgemm_blas", "ozimmu_zgemm_blas_workspace_bytes", "ozimmu_zgemm_blas",
     "ozimmu_auto_scratch_bytes", "ozimmu_auto_num_slices", "ozimmu_auto_num_slices_blas", "ozimmu_zgemm_auto",
-    "ozimmu_dgemm_auto",
+    "ozimmu_dgemm_auto", "ozimmu_dgemm_blas_auto", "ozimmu_zgemm_blas_auto",
 )
 PROBE_EXPORTS = ("ozimmu_probe_int8_mfma",)      # include/ozimmu_probe.h: measurement utility, not the product path
 
@@ -103,6 +103,14 @@ def lib() -> ctypes.CDLL:
         L.ozimmu_dgemm_auto.restype = i32
         L.ozimmu_dgemm_auto.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, ctypes.c_double, i32, i32, vp, sz, vp, sz,
                                         ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
+        L.ozimmu_dgemm_blas_auto.restype = i32
+        L.ozimmu_dgemm_blas_auto.argtypes = [ctypes.c_char, ctypes.c_char, i64, i64, i64, ctypes.c_double, vp, i64, vp, i64,
+                                             ctypes.c_double, vp, i64, ctypes.c_double, i32, i32, vp, sz, vp, sz,
+                                             ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
+        L.ozimmu_zgemm_blas_auto.restype = i32
+        L.ozimmu_zgemm_blas_auto.argtypes = [ctypes.c_char, ctypes.c_char, i64, i64, i64, vp, vp, i64, vp, i64, vp, vp, i64,
+                                             ctypes.c_double, i32, i32, vp, sz, vp, sz, ctypes.POINTER(i32),
+                                             ctypes.POINTER(i32), vp]
         dp = ctypes.POINTER(ctypes.c_double)
         L.ozimmu_probe_int8_mfma.restype = i32
         L.ozimmu_probe_int8_mfma.argtypes = [i32, i32, i32, dp, dp]
@@ -332,6 +340,33 @@ def zgemm_auto(A, B, C, threshold: float, guess: int = 0, max_slices: int = MAX_
                stream=None):
     """The same for complex128 device tensors."""
     return _gemm_auto(True, A, B, C, threshold, guess, max_slices, workspace, scratch, stream)
+
+
+def gemm_blas_auto(transa: str, transb: str, m: int, n: int, k: int, alpha, A, lda: int, B, ldb: int, beta, C, ldc: int,
+                   is_complex: bool, threshold: float, guess: int = 0, max_slices: int = MAX_SLICES, stream=None):
+    """The BLAS-style call with the slice count chosen inside it (see ozimmu.h); A, B, C are device tensors used as raw
+    column-major storage. Returns (s, guess_confirmed). Waits for the stream."""
+    import torch
+
+    beta_zero = complex(beta) == 0
+    if is_complex:
+        need = max(zgemm_blas_workspace_bytes(m, n, k, s, beta_zero) for s in range(1, max_slices + 1))
+    else:
+        need = max(workspace_bytes(n, m, k, s) for s in range(1, max_slices + 1))
+    workspace = torch.empty(max(need, WORKSPACE_ALIGN), dtype=torch.uint8, device=C.device)
+    scratch = torch.empty(max(auto_scratch_bytes(max(m, n)), WORKSPACE_ALIGN), dtype=torch.uint8, device=C.device)
+    s, confirmed = ctypes.c_int(), ctypes.c_int()
+    common = (float(threshold), int(max_slices), int(guess), _ptr(workspace), workspace.numel(), _ptr(scratch),
+              scratch.numel(), ctypes.byref(s), ctypes.byref(confirmed), _stream(stream))
+    if is_complex:
+        al = (ctypes.c_double * 2)(complex(alpha).real, complex(alpha).imag)
+        be = (ctypes.c_double * 2)(complex(beta).real, complex(beta).imag)
+        _check(lib().ozimmu_zgemm_blas_auto(transa.encode()[:1], transb.encode()[:1], m, n, k, ctypes.addressof(al), _ptr(A),
+                                            lda, _ptr(B), ldb, ctypes.addressof(be), _ptr(C), ldc, *common))
+    else:
+        _check(lib().ozimmu_dgemm_blas_auto(transa.encode()[:1], transb.encode()[:1], m, n, k, float(alpha), _ptr(A), lda,
+                                            _ptr(B), ldb, float(beta), _ptr(C), ldc, *common))
+    return s.value, bool(confirmed.value)
 
 
 def auto_num_slices_blas(transa: str, transb: str, m: int, n: int, k: int, A, lda: int, B, ldb: int, is_complex: bool,

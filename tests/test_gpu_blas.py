@@ -143,3 +143,59 @@ def test_complex_blas_beta_zero_does_not_read_c_and_degenerate_cases():
             want = oracle.zgemm_blas("N", "N", alpha, np.zeros((m, k), dtype=complex), np.zeros((k, n), dtype=complex),
                                      beta, C0, 4)
             assert np.array_equal(bits(got), bits(want))
+
+
+# ------------------------------------------------------------------ slice count chosen inside the BLAS-style call
+@pytest.mark.parametrize("cplx,ta,tb", [(False, "N", "N"), (False, "T", "N"), (False, "N", "T"), (False, "T", "T"),
+                                        (True, "N", "N"), (True, "T", "N"), (True, "N", "T"), (True, "T", "T"),
+                                        (True, "C", "N"), (True, "N", "C")])
+def test_blas_auto_is_choice_then_product(cplx, ta, tb):
+    """ozimmu_dgemm_blas_auto / ozimmu_zgemm_blas_auto: count = the oracle's choice for op(A), op(B); C = the oracle's
+    update with that count, whatever the guess; a guess can only be confirmed when beta is zero."""
+    m, n, k = 90, 140, 260
+    rng = np.random.default_rng(41)
+    if cplx:
+        opA = rng.standard_normal((m, k)) * np.exp(rng.standard_normal((m, k))) + 1j * rng.standard_normal((m, k))
+        opB = rng.standard_normal((k, n)) + 1j * rng.standard_normal((k, n)) * np.exp(0.5 * rng.standard_normal((k, n)))
+        A = {"N": opA, "T": opA.T.copy(), "C": opA.conj().T.copy()}[ta]
+        B = {"N": opB, "T": opB.T.copy(), "C": opB.conj().T.copy()}[tb]
+        C0 = rng.standard_normal((m, n)) + 1j * rng.standard_normal((m, n))
+        on_device, ref = zcol_major_on_device, lambda al, be, s: oracle.zgemm_blas(ta, tb, al, A, B, be, C0, s)
+        scalars = ((1.0, 0.0), (0.5 - 1.5j, 0.0), (1.0, 0.25j))
+    else:
+        opA, opB = wl.phi_pair(m, n, k, 1.5, 42)
+        A = opA.T.copy() if ta == "T" else opA
+        B = opB.T.copy() if tb == "T" else opB
+        C0 = rng.standard_normal((m, n))
+        on_device, ref = col_major_on_device, lambda al, be, s: oracle.dgemm_blas(ta == "T", tb == "T", al, A, B, be, C0, s)
+        scalars = ((1.0, 0.0), (-1.5, 0.0), (1.0, 0.5))
+    lda, ldb, ldc = A.shape[0] + 3, B.shape[0] + 1, m + 2
+    dA, dB = on_device(A, lda), on_device(B, ldb)
+    for threshold in (0.0, 1.0):
+        s_want = oracle.auto_num_slices(opA, opB, threshold)[0]
+        for alpha, beta in scalars:
+            want = ref(alpha, beta, s_want)
+            for guess in (s_want, s_want - 1, 0):
+                dC = on_device(C0, ldc)
+                s_got, confirmed = ozimmu.gemm_blas_auto(ta, tb, m, n, k, alpha, dA, lda, dB, ldb, beta, dC, ldc, cplx,
+                                                         threshold, guess=guess)
+                assert s_got == s_want
+                assert confirmed == (guess == s_want and beta == 0), (alpha, beta, guess)
+                assert np.array_equal(bits(dC.cpu().numpy()[:n, :m].T), bits(want)), (threshold, alpha, beta, guess)
+
+
+def test_complex_blas_auto_small_gate_on_a_wide_state():
+    """Untransposed plain product with a small first operand: the one-kernel path inside the BLAS-style one-call form."""
+    m, n, k = 64, 700, 64
+    rng = np.random.default_rng(43)
+    opA = wl.unit_column_complex(m, k, seed=44)
+    opB = rng.standard_normal((k, n)) + 1j * rng.standard_normal((k, n))
+    opB /= np.linalg.norm(opB)
+    C0 = np.zeros((m, n), dtype=np.complex128)
+    dA, dB = zcol_major_on_device(opA, m), zcol_major_on_device(opB, k)
+    s_want = oracle.auto_num_slices(opA, opB, 1.0)[0]
+    want = oracle.zgemm_blas("N", "N", 1.0, opA, opB, 0.0, C0, s_want)
+    for guess in (s_want, s_want + 1):
+        dC = zcol_major_on_device(C0, m)
+        assert ozimmu.gemm_blas_auto("N", "N", m, n, k, 1.0, dA, m, dB, k, 0.0, dC, m, True, 1.0, guess=guess) == (s_want, guess == s_want)
+        assert np.array_equal(bits(dC.cpu().numpy()[:n, :m].T), bits(want))
