@@ -205,3 +205,15 @@ def test_gemm_auto_rejects_a_workspace_too_small_for_the_largest_count():
         ozimmu.dgemm_auto(dA, dB, C, 1.0, guess=8, workspace=ws)                      # 16 slices would not fit
     s, _ = ozimmu.dgemm_auto(dA, dB, C, 1.0, guess=8, max_slices=8, workspace=ws)     # ... 8 do
     assert s == min(8, oracle.auto_num_slices(A, B, 1.0)[0])
+
+
+def test_gemm_auto_degenerate_cases():
+    A = torch.zeros((6, 0), dtype=torch.float64, device="cuda")
+    B = torch.zeros((0, 9), dtype=torch.float64, device="cuda")
+    C = torch.full((6, 9), float("nan"), dtype=torch.float64, device="cuda")
+    assert ozimmu.dgemm_auto(A, B, C, 1.0, guess=4) == (1, False)      # k = 0: nothing to inspect, C = 0
+    assert (C.cpu().numpy() == 0.0).all()
+    Z = torch.zeros((40, 30), dtype=torch.float64, device="cuda")       # all-zero operands lose nothing: one slice
+    C = torch.full((40, 50), float("nan"), dtype=torch.float64, device="cuda")
+    assert ozimmu.dgemm_auto(Z, torch.zeros((30, 50), dtype=torch.float64, device="cuda"), C, 0.0, guess=1) == (1, True)
+    assert (C.cpu().numpy() == 0.0).all()

@@ -199,3 +199,22 @@ def test_complex_blas_auto_small_gate_on_a_wide_state():
         dC = zcol_major_on_device(C0, m)
         assert ozimmu.gemm_blas_auto("N", "N", m, n, k, 1.0, dA, m, dB, k, 0.0, dC, m, True, 1.0, guess=guess) == (s_want, guess == s_want)
         assert np.array_equal(bits(dC.cpu().numpy()[:n, :m].T), bits(want))
+
+
+def test_blas_auto_degenerate_cases():
+    """k = 0 (C is only scaled), an empty C, alpha = 0: the one-call forms return what the two calls give."""
+    rng = np.random.default_rng(45)
+    C0 = rng.standard_normal((5, 4))
+    dA, dB = col_major_on_device(np.zeros((5, 1)), 5), col_major_on_device(np.zeros((1, 4)), 1)
+    dC = col_major_on_device(C0, 5)
+    s, confirmed = ozimmu.gemm_blas_auto("N", "N", 5, 4, 0, 1.0, dA, 5, dB, 1, 2.0, dC, 5, False, 1.0, guess=3)
+    assert (s, confirmed) == (1, False)
+    assert np.array_equal(bits(dC.cpu().numpy()[:4, :5].T), bits(2.0 * C0))
+    dC = col_major_on_device(C0, 5)
+    A = rng.standard_normal((5, 7))
+    B = rng.standard_normal((7, 4))
+    s, confirmed = ozimmu.gemm_blas_auto("N", "N", 5, 4, 7, 0.0, col_major_on_device(A, 5), 5, col_major_on_device(B, 7), 7, 0.0,
+                                         dC, 5, False, 1.0, guess=3)
+    assert not confirmed and s == oracle.auto_num_slices(A, B, 1.0)[0]
+    assert (dC.cpu().numpy()[:4, :5] == 0.0).all()
+    assert ozimmu.gemm_blas_auto("N", "N", 0, 4, 7, 1.0, dA, 1, col_major_on_device(B, 7), 7, 0.0, dC, 1, False, 1.0, guess=3)[0] >= 1
