@@ -54,10 +54,11 @@ Layout make_layout(int64_t m, int64_t n, int64_t k, int s, bool cplx) {
     L.n_pad = round_up(n, kRowAlign);
     L.k_pad = round_up(k, kSlab);
     L.wide = needs_wide(s, L.k_pad);
-    // a complex product walks its four real products in one launch of the large-tile kernel from three steps
-    // on; shorter ones take four launches of the real kernel and its tile choice
+    // a complex product walks its four real products in one launch from three steps on (on 64 x 64 tiles only where
+    // the large ones would leave compute units without a tile: measured, a short inner dimension alone does not pay
+    // there); shorter ones take four launches of the real kernel and its tile choice
     const bool one_launch = cplx && !L.wide && L.k_pad / kSlab >= 3;
-    set_tiles(L, m, n, s, !one_launch && use_small_tiles(m, n, L.k_pad, s, L.wide));
+    set_tiles(L, m, n, s, one_launch ? use_small_tiles(m, n, INT64_MAX, s, L.wide) : use_small_tiles(m, n, L.k_pad, s, L.wide));
     L.sa_bytes = (size_t)s * L.m_pad * L.k_pad;
     L.sb_bytes = (size_t)s * L.n_pad * L.k_pad;
     const int planes = cplx ? 2 : 1;

@@ -23,7 +23,8 @@ static inline void tile_waves(int s, bool small, int* wm, int* wn) {
     *wm = 2;
     *wn = (s > 13 || (small && s <= 9)) ? 2 : 4;
 }
-// Whether a real product of this shape runs on 64 x 64 tiles, two workgroups per compute unit: when the inner
+// Whether a product of this shape runs on 64 x 64 tiles, two workgroups per compute unit (a complex product in one
+// launch: asked with k_pad = INT64_MAX, i.e. only for the second reason): when the inner
 // dimension is short (a tile is then mostly start-up, fold and stores, and two independent workgroups overlap
 // one's with the other's matrix-core work) or when the 64 x 128 tiling leaves compute units without a tile.
 // Never with k-blocking, so that the workspace layout does not depend on it.

@@ -731,8 +731,8 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t st) {
 
 template <int MODE>
 hipError_t launch_for(const GemmArgs& g, int s, hipStream_t st) {
-    if (g.tile_cols == 64 && s <= 9) {   // 64 x 64 tiles, two workgroups per compute unit: real products only
-        if constexpr (MODE == kModeReal) {
+    if (g.tile_cols == 64 && s <= 9) {   // 64 x 64 tiles, two workgroups per compute unit: not for the double-double sum
+        if constexpr (MODE == kModeReal || MODE == kModeComplex) {
             switch (s) {
 #define OZ_CASE(S_) case S_: return launch_one<S_, 2, 2, MODE>(g, st);
                 OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
