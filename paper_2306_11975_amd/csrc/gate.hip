@@ -176,7 +176,7 @@ void gate_kernel(const GateArgs g) {
     // behind the two planes: exponents of the tile's rows, [plane][32], then those of the gate's fragments, [tensor][NFR][16]
     int* ex = reinterpret_cast<int*>(lds + 2 * PLANE);
     int* ex_gate = ex + 2 * kGateRows;
-    unsigned* scan_lds = reinterpret_cast<unsigned*>(ex_gate + 2 * NFR * 16);   // SCAN: [plane][5] counters of the tile
+    unsigned* scan_lds = reinterpret_cast<unsigned*>(ex_gate + 2 * NFR * 16);   // SCAN: [wavefront][plane][5] counters
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t row_tile = (int64_t)blockIdx.x * kGateRows;
@@ -210,10 +210,6 @@ void gate_kernel(const GateArgs g) {
         constexpr int LPR = NT / kGateRows, W = KS * 16 / LPR;
         const int lrow = tid / LPR, cl = tid % LPR;
         for (int i = tid; i < 2 * NFR * 16; i += NT) ex_gate[i] = g.E[i];
-        if constexpr (SCAN) {
-            if (tid < 2 * kScanCounters) scan_lds[tid] = 0u;
-            __syncthreads();
-        }
         const int64_t row = row_tile + lrow;
         const bool live = row < g.m;
         const ulonglong2* src = reinterpret_cast<const ulonglong2*>(g.Z) + (live ? row : 0) * g.ldz;
@@ -306,19 +302,29 @@ void gate_kernel(const GateArgs g) {
         if (normal) emit(std::true_type{});
         else emit(std::false_type{});
         if constexpr (SCAN) {
-            // sums over the rows of 16 lanes, then one LDS add per row of lanes and counter
+            // sums over the wavefront (rotations inside the rows of 16 lanes, then the four rows through scalar registers),
+            // one LDS word per wavefront and counter: no atomics, which a tile of few elements would feel
             unsigned c[2 * kScanCounters] = {cnt_re.sv_g, cnt_re.sz_g, cnt_re.sv_h, cnt_re.sz_h, cnt_re.bits,
                                              cnt_im.sv_g, cnt_im.sz_g, cnt_im.sv_h, cnt_im.sz_h, cnt_im.bits};
+            unsigned mine = 0;
 #pragma unroll
             for (int i = 0; i < 2 * kScanCounters; ++i) {
-                c[i] = row_sum_step<1>(row_sum_step<2>(row_sum_step<4>(row_sum_step<8>(c[i]))));
-                if ((lane & 15) == 0 && c[i]) atomicAdd(&scan_lds[i], c[i]);
+                const unsigned r = row_sum_step<1>(row_sum_step<2>(row_sum_step<4>(row_sum_step<8>(c[i]))));
+                const unsigned total = (unsigned)__builtin_amdgcn_readlane((int)r, 0) + (unsigned)__builtin_amdgcn_readlane((int)r, 16) +
+                                       (unsigned)__builtin_amdgcn_readlane((int)r, 32) + (unsigned)__builtin_amdgcn_readlane((int)r, 48);
+                mine = lane == i ? total : mine;
             }
+            if (lane < 2 * kScanCounters) scan_lds[wave * (2 * kScanCounters) + lane] = mine;
         }
     }
     __syncthreads();
     if constexpr (SCAN) {
-        if (tid < 2 * kScanCounters) g.scan[(int64_t)tid * gridDim.x + blockIdx.x] = scan_lds[tid];   // [counter][tile]
+        if (tid < 2 * kScanCounters) {
+            unsigned total = 0;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) total += scan_lds[w * (2 * kScanCounters) + tid];
+            g.scan[(int64_t)tid * gridDim.x + blockIdx.x] = total;   // [counter][tile]
+        }
     }
 
     // ---- the products
@@ -461,7 +467,7 @@ __global__ __launch_bounds__(1024) void gate_scan_reduce_kernel(const unsigned* 
 
 template <int S, int CLS, bool SCAN>
 hipError_t launch_gate(const GateArgs& g, hipStream_t st) {
-    constexpr int lds = 2 * S * (1 << CLS) * 2 * kFragBytes + (2 * kGateRows + 2 * (8 << CLS) * 16 + 2 * kScanCounters + 2) * (int)sizeof(int);
+    constexpr int lds = 2 * S * (1 << CLS) * 2 * kFragBytes + (2 * kGateRows + 2 * (8 << CLS) * 16 + 16 * 2 * kScanCounters) * (int)sizeof(int);
     static_assert(lds <= 160 * 1024 && (S > kBand || CLS == 2 || 2 * lds <= 160 * 1024),
                   "the LDS of a compute unit: two workgroups of eight wavefronts up to eight slices, else one workgroup");
     hipError_t e = allow_dynamic_lds<&gate_kernel<S, CLS, SCAN>>(lds);
