@@ -205,11 +205,15 @@ void gate_kernel(const GateArgs g) {
     }
 
     // ---- the rows of Z -> exponents and slices in LDS. LPR lanes work on a row (16, or 32 with sixteen wavefronts); a
-    // lane owns W words of four consecutive complex elements of it (words cl, LPR + cl, ...).
-    {
-        constexpr int LPR = NT / kGateRows, W = KS * 16 / LPR;
-        const int lrow = tid / LPR, cl = tid % LPR;
-        for (int i = tid; i < 2 * NFR * 16; i += NT) ex_gate[i] = g.E[i];
+    // lane owns W words of four consecutive complex elements of it (words cl, LPR + cl, ...). A narrow gate (k <= 32,
+    // k <= 16) has its rows' live words in 8 or 4 lanes: then half or a quarter of the wavefronts split all 32 rows and
+    // the others skip this part. The positions of a step beyond those words are never written: the gate's fragments
+    // hold zeros there (gate_split_kernel), and an integer times zero is zero whatever the LDS holds.
+    for (int i = tid; i < 2 * NFR * 16; i += NT) ex_gate[i] = g.E[i];
+    constexpr int LPR = NT / kGateRows, W = KS * 16 / LPR;
+    const int lshift = CLS == 0 ? (g.k <= 16 ? 2 : g.k <= 32 ? 3 : 4) : (LPR == 32 ? 5 : 4);   // log2 of the lanes per row
+    if (tid < (kGateRows << lshift)) {   // whole wavefronts
+        const int lrow = tid >> lshift, cl = tid & ((1 << lshift) - 1);
         const int64_t row = row_tile + lrow;
         const bool live = row < g.m;
         const ulonglong2* src = reinterpret_cast<const ulonglong2*>(g.Z) + (live ? row : 0) * g.ldz;
@@ -233,12 +237,20 @@ void gate_kernel(const GateArgs g) {
                 hw_re = a > hw_re ? a : hw_re;
                 hw_im = b2 > hw_im ? b2 : hw_im;
             }
-        hw_re = row_max_step<1>(row_max_step<2>(row_max_step<4>(row_max_step<8>(hw_re))));
-        hw_im = row_max_step<1>(row_max_step<2>(row_max_step<4>(row_max_step<8>(hw_im))));
-        if constexpr (LPR == 32) {   // the row's other sixteen lanes
-            const unsigned o = __shfl_xor(hw_re, 16, 64), q = __shfl_xor(hw_im, 16, 64);
-            hw_re = o > hw_re ? o : hw_re;
-            hw_im = q > hw_im ? q : hw_im;
+        if (CLS != 0 || lshift == 4) {
+            hw_re = row_max_step<1>(row_max_step<2>(row_max_step<4>(row_max_step<8>(hw_re))));
+            hw_im = row_max_step<1>(row_max_step<2>(row_max_step<4>(row_max_step<8>(hw_im))));
+            if constexpr (LPR == 32) {   // the row's other sixteen lanes
+                const unsigned o = __shfl_xor(hw_re, 16, 64), q = __shfl_xor(hw_im, 16, 64);
+                hw_re = o > hw_re ? o : hw_re;
+                hw_im = q > hw_im ? q : hw_im;
+            }
+        } else {   // rows of 4 or 8 lanes
+            for (int off = 1 << (lshift - 1); off >= 1; off >>= 1) {
+                const unsigned o = __shfl_xor(hw_re, off, 64), q = __shfl_xor(hw_im, off, 64);
+                hw_re = o > hw_re ? o : hw_re;
+                hw_im = q > hw_im ? q : hw_im;
+            }
         }
         int e_re = (int)(hw_re >> 20) - 1022, e_im = (int)(hw_im >> 20) - 1022;   // as exponent_of_max for a normal maximum
         const bool normal = __all(hw_re >= 0x00100000u && hw_im >= 0x00100000u);
@@ -253,8 +265,7 @@ void gate_kernel(const GateArgs g) {
                     mx_re = a > mx_re ? a : mx_re;
                     mx_im = b2 > mx_im ? b2 : mx_im;
                 }
-#pragma unroll
-            for (int off = LPR / 2; off >= 1; off >>= 1) {
+            for (int off = 1 << (lshift - 1); off >= 1; off >>= 1) {
                 const unsigned long long o = __shfl_xor(mx_re, off, 64), q = __shfl_xor(mx_im, off, 64);
                 mx_re = o > mx_re ? o : mx_re;
                 mx_im = q > mx_im ? q : mx_im;
@@ -316,6 +327,8 @@ void gate_kernel(const GateArgs g) {
             }
             if (lane < 2 * kScanCounters) scan_lds[wave * (2 * kScanCounters) + lane] = mine;
         }
+    } else if constexpr (SCAN) {
+        if (lane < 2 * kScanCounters) scan_lds[wave * (2 * kScanCounters) + lane] = 0u;
     }
     __syncthreads();
     if constexpr (SCAN) {
