@@ -165,12 +165,16 @@ __global__ __launch_bounds__(512) void gate_split_kernel(const double* __restric
 // SCAN: the kernel also counts, for the two planes of Z, what the slice-count choice needs to know about S and S - 1
 // slices (Section 4.4; five counters per plane and tile, added up by gate_scan_reduce_kernel), so that a caller who
 // guessed S can have the guess checked without another pass over Z.
-template <int S, int CLS, bool SCAN>
-__global__ __launch_bounds__(CLS == 2 ? 1024 : 512) __attribute__((amdgpu_waves_per_eu(S <= kBand ? 4 : 2, S <= kBand ? 4 : 2)))
+// WAVES: wavefronts of the workgroup: 8 (16 for CLS 2); 4 for a gate of at most 32 x 32 (CLS 0), whose tile has work for no
+// more: four such workgroups then share a compute unit, and the latency of a tile's loads hides behind three others.
+constexpr int gate_waves(int cls, bool few) { return cls == 2 ? 16 : few ? 4 : 8; }
+template <int S, int CLS, bool SCAN, bool FEW = false>
+__global__ __launch_bounds__(64 * gate_waves(CLS, FEW)) __attribute__((amdgpu_waves_per_eu(S <= kBand ? 4 : 2, S <= kBand ? 4 : 2)))
 void gate_kernel(const GateArgs g) {
+    static_assert(!FEW || CLS == 0, "four wavefronts: the smallest class only");
     constexpr bool WIDE = S > 9;   // the slices beyond the ninth come from the lower word of the fixed-point fraction
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    constexpr int KS = 1 << CLS, NFR = 8 << CLS, WAVES = CLS == 2 ? 16 : 8, NT = 64 * WAVES;
+    constexpr int KS = 1 << CLS, NFR = 8 << CLS, WAVES = gate_waves(CLS, FEW), NT = 64 * WAVES;
     constexpr int SLICE = KS * 2 * kFragBytes;   // one slice of one plane of the tile's rows: [step][row fragment]
     constexpr int PLANE = S * SLICE;
     // behind the two planes: exponents of the tile's rows, [plane][32], then those of the gate's fragments, [tensor][NFR][16]
@@ -210,7 +214,7 @@ void gate_kernel(const GateArgs g) {
     // the others skip this part. The positions of a step beyond those words are never written: the gate's fragments
     // hold zeros there (gate_split_kernel), and an integer times zero is zero whatever the LDS holds.
     for (int i = tid; i < 2 * NFR * 16; i += NT) ex_gate[i] = g.E[i];
-    constexpr int LPR = NT / kGateRows, W = KS * 16 / LPR;
+    constexpr int LPR = FEW ? 16 : NT / kGateRows, W = KS * 16 / LPR;   // (FEW: k <= 32, never 16 lanes to a row)
     const int lshift = CLS == 0 ? (g.k <= 16 ? 2 : g.k <= 32 ? 3 : 4) : (LPR == 32 ? 5 : 4);   // log2 of the lanes per row
     if (tid < (kGateRows << lshift)) {   // whole wavefronts
         const int lrow = tid >> lshift, cl = tid & ((1 << lshift) - 1);
@@ -478,20 +482,23 @@ __global__ __launch_bounds__(1024) void gate_scan_reduce_kernel(const unsigned* 
     }
 }
 
-template <int S, int CLS, bool SCAN>
+template <int S, int CLS, bool SCAN, bool FEW>
 hipError_t launch_gate(const GateArgs& g, hipStream_t st) {
     constexpr int lds = 2 * S * (1 << CLS) * 2 * kFragBytes + (2 * kGateRows + 2 * (8 << CLS) * 16 + 16 * 2 * kScanCounters) * (int)sizeof(int);
-    static_assert(lds <= 160 * 1024 && (S > kBand || CLS == 2 || 2 * lds <= 160 * 1024),
-                  "the LDS of a compute unit: two workgroups of eight wavefronts up to eight slices, else one workgroup");
-    hipError_t e = allow_dynamic_lds<&gate_kernel<S, CLS, SCAN>>(lds);
+    static_assert(lds <= 160 * 1024 && (S > kBand || CLS == 2 || 2 * lds <= 160 * 1024) && (!FEW || S > kBand || 4 * lds <= 160 * 1024),
+                  "the LDS of a compute unit: two workgroups of eight wavefronts (four of four) up to eight slices, else one workgroup");
+    hipError_t e = allow_dynamic_lds<&gate_kernel<S, CLS, SCAN, FEW>>(lds);
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((g.m + kGateRows - 1) / kGateRows);
-    gate_kernel<S, CLS, SCAN><<<dim3(grid), dim3(CLS == 2 ? 1024 : 512), lds, st>>>(g);
+    gate_kernel<S, CLS, SCAN, FEW><<<dim3(grid), dim3(64 * gate_waves(CLS, FEW)), lds, st>>>(g);
     return hipGetLastError();
 }
 template <int S, int CLS>
 hipError_t launch_gate(const GateArgs& g, hipStream_t st) {
-    return g.scan ? launch_gate<S, CLS, true>(g, st) : launch_gate<S, CLS, false>(g, st);
+    if constexpr (CLS == 0) {
+        if (g.k <= 32 && g.n <= 32) return g.scan ? launch_gate<S, 0, true, true>(g, st) : launch_gate<S, 0, false, true>(g, st);
+    }
+    return g.scan ? launch_gate<S, CLS, true, false>(g, st) : launch_gate<S, CLS, false, false>(g, st);
 }
 
 inline int gate_class(int64_t k, int64_t n) { return k > 128 || n > 128 ? 2 : k > 64 || n > 64 ? 1 : 0; }
