@@ -165,10 +165,12 @@ __global__ __launch_bounds__(512) void gate_split_kernel(const double* __restric
 // SCAN: the kernel also counts, for the two planes of Z, what the slice-count choice needs to know about S and S - 1
 // slices (Section 4.4; five counters per plane and tile, added up by gate_scan_reduce_kernel), so that a caller who
 // guessed S can have the guess checked without another pass over Z.
-// WAVES: wavefronts of the workgroup: 8 (16 for CLS 2); 4 for a gate of at most 32 x 32 (CLS 0), whose tile has work for no
-// more: four such workgroups then share a compute unit, and the latency of a tile's loads hides behind three others.
-constexpr int gate_waves(int cls, bool few) { return cls == 2 ? 16 : few ? 4 : 8; }
-template <int S, int CLS, bool SCAN, bool FEW = false>
+// WAVES: wavefronts of the workgroup: 8 for CLS 1, 16 for CLS 2, 4 for CLS 0 (a gate of at most 32 x 32 has work for no
+// more per tile; up to 64 x 64 a lane takes two words of its row and a wavefront four patches): four such workgroups
+// then share a compute unit up to eight slices, and the latency of a tile's loads and its barrier hide behind three
+// other tiles instead of one.
+constexpr int gate_waves(int cls, int few) { return cls == 2 ? 16 : few ? 4 : 8; }
+template <int S, int CLS, bool SCAN, int FEW = 0>   // FEW: 1 = four wavefronts, k <= 32; 2 = four wavefronts, two words to a lane
 __global__ __launch_bounds__(64 * gate_waves(CLS, FEW)) __attribute__((amdgpu_waves_per_eu(S <= kBand ? 4 : 2, S <= kBand ? 4 : 2)))
 void gate_kernel(const GateArgs g) {
     static_assert(!FEW || CLS == 0, "four wavefronts: the smallest class only");
@@ -214,8 +216,8 @@ void gate_kernel(const GateArgs g) {
     // the others skip this part. The positions of a step beyond those words are never written: the gate's fragments
     // hold zeros there (gate_split_kernel), and an integer times zero is zero whatever the LDS holds.
     for (int i = tid; i < 2 * NFR * 16; i += NT) ex_gate[i] = g.E[i];
-    constexpr int LPR = FEW ? 16 : NT / kGateRows, W = KS * 16 / LPR;   // (FEW: k <= 32, never 16 lanes to a row)
-    const int lshift = CLS == 0 ? (g.k <= 16 ? 2 : g.k <= 32 ? 3 : 4) : (LPR == 32 ? 5 : 4);   // log2 of the lanes per row
+    constexpr int LPR = FEW == 1 ? 16 : NT / kGateRows, W = KS * 16 / LPR;   // (FEW 1: k <= 32, never 16 lanes to a row)
+    const int lshift = FEW == 2 ? 3 : CLS == 0 ? (g.k <= 16 ? 2 : g.k <= 32 ? 3 : 4) : (LPR == 32 ? 5 : 4);   // log2 of the lanes per row
     if (tid < (kGateRows << lshift)) {   // whole wavefronts
         const int lrow = tid >> lshift, cl = tid & ((1 << lshift) - 1);
         const int64_t row = row_tile + lrow;
@@ -482,7 +484,7 @@ __global__ __launch_bounds__(1024) void gate_scan_reduce_kernel(const unsigned* 
     }
 }
 
-template <int S, int CLS, bool SCAN, bool FEW>
+template <int S, int CLS, bool SCAN, int FEW>
 hipError_t launch_gate(const GateArgs& g, hipStream_t st) {
     constexpr int lds = 2 * S * (1 << CLS) * 2 * kFragBytes + (2 * kGateRows + 2 * (8 << CLS) * 16 + 16 * 2 * kScanCounters) * (int)sizeof(int);
     static_assert(lds <= 160 * 1024 && (S > kBand || CLS == 2 || 2 * lds <= 160 * 1024) && (!FEW || S > kBand || 4 * lds <= 160 * 1024),
@@ -496,9 +498,11 @@ hipError_t launch_gate(const GateArgs& g, hipStream_t st) {
 template <int S, int CLS>
 hipError_t launch_gate(const GateArgs& g, hipStream_t st) {
     if constexpr (CLS == 0) {
-        if (g.k <= 32 && g.n <= 32) return g.scan ? launch_gate<S, 0, true, true>(g, st) : launch_gate<S, 0, false, true>(g, st);
+        if (g.k <= 32 && g.n <= 32) return g.scan ? launch_gate<S, 0, true, 1>(g, st) : launch_gate<S, 0, false, 1>(g, st);
+        return g.scan ? launch_gate<S, 0, true, 2>(g, st) : launch_gate<S, 0, false, 2>(g, st);
+    } else {
+        return g.scan ? launch_gate<S, CLS, true, 0>(g, st) : launch_gate<S, CLS, false, 0>(g, st);
     }
-    return g.scan ? launch_gate<S, CLS, true, false>(g, st) : launch_gate<S, CLS, false, false>(g, st);
 }
 
 inline int gate_class(int64_t k, int64_t n) { return k > 128 || n > 128 ? 2 : k > 64 || n > 64 ? 1 : 0; }
