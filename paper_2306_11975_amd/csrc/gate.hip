@@ -4,8 +4,9 @@
 //
 // With so short an inner dimension the product is bound by the memory traffic of the state and by the vector
 // work around the matrix cores (cutting the state into slices, folding the diagonals in FP64), and splitting the
-// state in a kernel of its own doubles that traffic (slices written, slices read back). Here a workgroup of eight
-// wavefronts (sixteen when k or n exceeds 128) takes 32 rows of Z: it finds the exponents of their real and imaginary parts and cuts both planes into
+// state in a kernel of its own doubles that traffic (slices written, slices read back). Here a workgroup of four
+// wavefronts (eight when k or n exceeds 64, sixteen beyond 128) takes 32 rows of Z: it finds the exponents of their
+// real and imaginary parts and cuts both planes into
 // slices (SplitInt, Section 3.1; the same bit operations as the splitter kernels) straight into LDS, as operand
 // fragments of v_mfma_i32_16x16x64_i8 (16 rows x 64 positions of k).
 //
@@ -160,7 +161,7 @@ __global__ __launch_bounds__(512) void gate_split_kernel(const double* __restric
 }
 
 // ---------------------------------------------------------------------------- the product
-// S slices; CLS, the size class of k and n: 0 up to 64 (one step of 64 positions, eight fragments of B, eight wavefronts),
+// S slices; CLS, the size class of k and n: 0 up to 64 (one step of 64 positions, eight fragments of B, four wavefronts),
 // 1 up to 128 (two steps, sixteen fragments), 2 up to 256 (four steps, 32 fragments, sixteen wavefronts; up to eight slices).
 // SCAN: the kernel also counts, for the two planes of Z, what the slice-count choice needs to know about S and S - 1
 // slices (Section 4.4; five counters per plane and tile, added up by gate_scan_reduce_kernel), so that a caller who
