@@ -278,6 +278,20 @@ int pick_slices(const unsigned long long* host, int is_complex, double count_a, 
     return max_slices;
 }
 
+// Whether `guess` is the count pick_slices would return, given only the sums for guess and guess - 1 slices (host: [planes][16],
+// the first operand's planes first): the loss does not grow with the slice count, so guess is the choice iff every plane
+// is within the threshold with it (or it is the largest count allowed) and some plane is not with one slice less.
+bool guess_holds(const unsigned long long* host, int planes, double count_a, double count_b, double threshold, int guess,
+                 int max_slices) {
+    auto within = [&](int s) {
+        bool ok = true;
+        for (int p = 0; p < planes; ++p)
+            ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < planes / 2 ? count_a : count_b);
+        return ok;
+    };
+    return (within(guess) || guess == max_slices) && (guess == 1 || !within(guess - 1));
+}
+
 ozimmu_status_t auto_select(const ScanOperand& a, const ScanOperand& b, int64_t scratch_cols, int is_complex,
                             double threshold, int max_slices, void* scratch, size_t scratch_bytes, int* num_slices,
                             uint64_t* loss_sums, void* stream) {
@@ -366,14 +380,7 @@ ozimmu_status_t gemm_auto(bool cplx, int64_t m, int64_t n, int64_t k, const doub
                                            reinterpret_cast<unsigned*>(ws + L.off_sa[0]), host);
         if (e == hipSuccess) e = hipStreamSynchronize(st);
         if (e != hipSuccess) return OZIMMU_ERR_HIP;
-        auto within = [&](int s) {   // every plane's loss with s slices within the threshold (the rule of ozimmu_auto_num_slices)
-            bool ok = true;
-            for (int p = 0; p < 4; ++p) ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < 2 ? count_a : count_b);
-            return ok;
-        };
-        // the loss does not grow with the slice count: `guess` is the choice iff it is within the threshold (or the
-        // largest count allowed) and guess - 1 is not
-        if ((within(guess) || guess == max_slices) && (guess == 1 || !within(guess - 1))) {
+        if (guess_holds(host, 4, count_a, count_b, threshold, guess, max_slices)) {
             *num_slices = guess;
             if (guess_confirmed) *guess_confirmed = 1;
             return OZIMMU_OK;
@@ -388,14 +395,7 @@ ozimmu_status_t gemm_auto(bool cplx, int64_t m, int64_t n, int64_t k, const doub
             e = cplx ? run_complex_products(L, m, n, guess, ws, C, ldc, st) : run_product(L, m, n, guess, ws, 0, 0, C, ldc, 0, st);
         if (e == hipSuccess) e = hipStreamSynchronize(st);
         if (e != hipSuccess) return OZIMMU_ERR_HIP;
-        const int planes = cplx ? 4 : 2;
-        auto within = [&](int s) {
-            bool ok = true;
-            for (int p = 0; p < planes; ++p)
-                ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < planes / 2 ? count_a : count_b);
-            return ok;
-        };
-        if ((within(guess) || guess == max_slices) && (guess == 1 || !within(guess - 1))) {
+        if (guess_holds(host, cplx ? 4 : 2, count_a, count_b, threshold, guess, max_slices)) {
             *num_slices = guess;
             if (guess_confirmed) *guess_confirmed = 1;
             return OZIMMU_OK;
@@ -804,15 +804,7 @@ static ozimmu_status_t gemm_blas_auto(bool cplx, char transa, char transb, int64
         const ozimmu_status_t rc = product(guess, host);
         if (rc != OZIMMU_OK) return rc;
         if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return OZIMMU_ERR_HIP;
-        const int planes = cplx ? 4 : 2;
-        const double count_a = (double)m * (double)k, count_b = (double)k * (double)n;
-        auto within = [&](int s) {
-            bool ok = true;
-            for (int p = 0; p < planes; ++p)
-                ok = ok && (double)host[p * OZIMMU_MAX_SLICES + (s - 1)] <= threshold * (p < planes / 2 ? count_a : count_b);
-            return ok;
-        };
-        if ((within(guess) || guess == max_slices) && (guess == 1 || !within(guess - 1))) {
+        if (guess_holds(host, cplx ? 4 : 2, (double)m * (double)k, (double)k * (double)n, threshold, guess, max_slices)) {
             *num_slices = guess;
             if (guess_confirmed) *guess_confirmed = 1;
             return OZIMMU_OK;
