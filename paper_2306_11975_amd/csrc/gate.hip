@@ -392,12 +392,31 @@ void gate_kernel(const GateArgs g) {
         // G = the diagonals, least significant first: acc = RN(acc + S_e 2^(-7 (e + 2))) (the product of an integer
         // below 2^31 and a power of two is exact, so the fused operation rounds like the sum it stands for) ...
         // (the first term as a plain product: RN(0 + t) = t, and t is exact)
+        // The four least significant diagonals, two at a time as one integer 2^7 S_(e-1) + S_e: diagonal e sums e + 1 slice
+        // products of at most 64 KS positions and 127^2 each, so while ((S - 1) 2^7 + S) 64 KS 127^2 < 2^31 that integer
+        // fits 32 bits; and the partial sums of those four terms are integers of less than 2^53 units of 2^(-7 (S + 1)),
+        // so no rounding happens among them and any grouping gives the value the one-by-one sequence gives.
+        constexpr bool MERGE = S >= 4 && ((long long)(S - 1) * 128 + S) * (64 * KS) * (127 * 127) < (1ll << 31);
+        constexpr int E_FIRST = MERGE ? S - 5 : S - 2;   // the diagonals from here down are added one by one
+        auto scale_of = [](int e) __attribute__((always_inline)) {
+            return __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * (e + 2)) << 52);
+        };
         double sum[4];
 #pragma unroll
-        for (int e = S - 1; e >= 0; --e) {
-            const double sc = __longlong_as_double((long long)(1023 - OZIMMU_SLICE_BITS * (e + 2)) << 52);
+        for (int u = 0; u < 4; ++u) {
+            if constexpr (MERGE) {
+                const int low = acc[S - 2][u] * (1 << OZIMMU_SLICE_BITS) + acc[S - 1][u];
+                const int next = acc[S - 4][u] * (1 << OZIMMU_SLICE_BITS) + acc[S - 3][u];
+                sum[u] = fma((double)next, scale_of(S - 3), (double)low * scale_of(S - 1));
+            } else {
+                sum[u] = (double)acc[S - 1][u] * scale_of(S - 1);
+            }
+        }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) sum[u] = e == S - 1 ? (double)acc[e][u] * sc : fma((double)acc[e][u], sc, sum[u]);
+        for (int e = E_FIRST; e >= 0; --e) {
+            const double sc = scale_of(e);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) sum[u] = fma((double)acc[e][u], sc, sum[u]);
         }
         // ... times 2^(EA_i + EB_j)
         const v4i ea = *reinterpret_cast<const v4i*>(ex + pass * kGateRows + lrow0);   // four consecutive rows

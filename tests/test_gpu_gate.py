@@ -272,3 +272,19 @@ def test_zgemm_auto_adversarial_values_and_other_shapes():
     A = wl.gaussian_complex(70, 300, seed=55)
     B = wl.unit_column_complex(300, 50, seed=56)
     check_zgemm_auto(A, B, 1.0, guesses=[("rel", 0), 0])
+
+
+@pytest.mark.parametrize("k,s", [(128, 8), (128, 9), (128, 10), (64, 16), (64, 12), (64, 8), (33, 5), (256, 8)])
+@pytest.mark.parametrize("signs", ["same", "mixed"])
+def test_gate_largest_integer_sums(k, s, signs):
+    """Every slice +-127 (elements of magnitude 1 - 2^-53 under a power-of-two maximum): the integer sums of the
+    diagonals take their largest magnitude, which is what the fold's 32-bit merge of neighbouring diagonals must hold."""
+    m, n = 40, min(k, 128)
+    x = 1.0 - 2.0 ** -53
+    rng = np.random.default_rng(k + s)
+    def plane(r, c):
+        sg = np.ones((r, c)) if signs == "same" else rng.choice([-1.0, 1.0], size=(r, c))
+        return sg * x
+    A = plane(m, k) + 1j * plane(m, k)
+    B = plane(k, n) + 1j * plane(k, n)
+    assert_same(gpu_zgemm(A, B, s), oracle.zgemm(A, B, s))
