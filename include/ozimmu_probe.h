@@ -20,7 +20,8 @@ extern "C" {
  *     distribution of the slices); 3: random signed 3-bit magnitudes; 4: random 7-bit magnitudes
  *     without sign; 5: A as 2, every byte of B equal to 1; 6: A as 2, B zero.
  *   shape 0: v_mfma_i32_32x32x32_i8 (the instruction the product kernel uses);
- *         1: v_mfma_i32_16x16x64_i8.
+ *         1: v_mfma_i32_16x16x64_i8 (the kernel for a gate on a state vector uses it);
+ *         2: v_mfma_i32_16x16x32_i8, the older form with half the inner dimension.
  * Errors: OZIMMU_ERR_BAD_DIM for an unknown pattern or shape or iters < 1, OZIMMU_ERR_NULL,
  * OZIMMU_ERR_HIP.
  */

@@ -18,7 +18,8 @@ __device__ __forceinline__ unsigned mix(unsigned x) {
 }
 
 // Register-only issue loop: 16 independent INT8 MFMAs per iteration (SHAPE 0: 32x32x32, 16 result
-// registers each; SHAPE 1: 16x16x64, 4 result registers each; both 32768 multiply-adds), 4 waves per CU.
+// registers each; SHAPE 1: 16x16x64, 4 result registers each; both 32768 multiply-adds; SHAPE 2: the older
+// 16x16x32, 64 instructions of a quarter of the size per iteration), 4 waves per CU.
 // pattern 0: all-zero operands, 1: random bytes, 2: random 7-bit magnitudes with random sign
 // (sign-magnitude values in [-127, 127], the value distribution of Ozaki slices beyond the first),
 // 3: random signed 3-bit magnitudes, 4: random 7-bit magnitudes without sign, 5: A as 2 and every
@@ -66,6 +67,17 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int pattern, int iters, 
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     acc[i * 4 + j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i * 4 + j], 0, 0, 0);
+        } else if (SHAPE == 2) {   // 64 instructions of a quarter of the size, 8 operand bytes per lane
+#pragma unroll
+            for (int h = 0; h < 4; ++h)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const long a8 = (long)(((unsigned long)(unsigned)a[i][1] << 32) | (unsigned)a[i][0]);
+                        const long b8 = (long)(((unsigned long)(unsigned)b[j][1] << 32) | (unsigned)b[j][0]);
+                        acc4[(h & 1) * 16 + i * 4 + j] = __builtin_amdgcn_mfma_i32_16x16x32_i8(a8, b8, acc4[(h & 1) * 16 + i * 4 + j], 0, 0, 0);
+                    }
         } else {   // the same number of multiply-adds per iteration: 32 instructions of half the size
 #pragma unroll
             for (int h = 0; h < 2; ++h)
@@ -102,7 +114,7 @@ extern "C" {
 // Allocates a few KiB of device and pinned host memory for the duration of the call and
 // synchronises the device: a measurement utility, not a building block.
 ozimmu_status_t ozimmu_probe_int8_mfma(int pattern, int shape, int iters, double* tera_ops_per_s, double* shader_mhz) {
-    if (pattern < 0 || pattern > 6 || shape < 0 || shape > 1 || iters < 1) return OZIMMU_ERR_BAD_DIM;
+    if (pattern < 0 || pattern > 6 || shape < 0 || shape > 2 || iters < 1) return OZIMMU_ERR_BAD_DIM;
     if (!tera_ops_per_s || !shader_mhz) return OZIMMU_ERR_NULL;
     int cus = 0, dev = 0;
     int* sink = nullptr;
@@ -115,7 +127,8 @@ ozimmu_status_t ozimmu_probe_int8_mfma(int pattern, int shape, int iters, double
     float ms = 0.f;
     auto launch = [&](int n) {
         if (shape == 0) mfma_rate_kernel<0><<<dim3(cus), dim3(256)>>>(pattern, n, sink, clocks);
-        else mfma_rate_kernel<1><<<dim3(cus), dim3(256)>>>(pattern, n, sink, clocks);
+        else if (shape == 1) mfma_rate_kernel<1><<<dim3(cus), dim3(256)>>>(pattern, n, sink, clocks);
+        else mfma_rate_kernel<2><<<dim3(cus), dim3(256)>>>(pattern, n, sink, clocks);
     };
     if (ok) {
         launch(64);  // warm-up
