@@ -17,27 +17,8 @@ __device__ __forceinline__ unsigned mix(unsigned x) {
     return x;
 }
 
-// Register-only issue loop: 16 independent INT8 MFMAs per iteration (SHAPE 0: 32x32x32, 16 result
-// registers each; SHAPE 1: 16x16x64, 4 result registers each; both 32768 multiply-adds; SHAPE 2: the older
-// 16x16x32, 64 instructions of a quarter of the size per iteration), 4 waves per CU.
-// pattern 0: all-zero operands, 1: random bytes, 2: random 7-bit magnitudes with random sign
-// (sign-magnitude values in [-127, 127], the value distribution of Ozaki slices beyond the first),
-// 3: random signed 3-bit magnitudes, 4: random 7-bit magnitudes without sign, 5: A as 2 and every
-// byte of B equal to 1, 6: A as 2 and B zero.
-template <int SHAPE>
-__global__ __launch_bounds__(256) void mfma_rate_kernel(int pattern, int iters, int* sink, long long* clocks) {
-    const long long c0 = clock64(), w0 = wall_clock64();
-    v16i acc[16];
-    v4i acc4[32];
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
-#pragma unroll
-    for (int i = 0; i < 32; ++i)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc4[i][r] = 0;
-    v4i a[4], b[4];
+// Four operand pairs of a lane for the given pattern.
+__device__ __forceinline__ void probe_operands(int pattern, v4i (&a)[4], v4i (&b)[4]) {
     for (int i = 0; i < 4; ++i)
         for (int c = 0; c < 4; ++c) {
             unsigned ha = mix(threadIdx.x * 64 + i * 8 + c + blockIdx.x * 7919), hb = mix(ha + 12345);
@@ -60,6 +41,55 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int pattern, int iters, 
             a[i][c] = (int)ha;
             b[i][c] = (int)hb;
         }
+}
+
+// The small shape with four wavefronts per SIMD (a workgroup of sixteen wavefronts per CU, at most 128 registers): 16
+// independent v_mfma_i32_16x16x64_i8 per iteration, 4 result registers each.
+__global__ __launch_bounds__(1024) void mfma_rate_small_kernel(int pattern, int iters, int* sink, long long* clocks) {
+    const long long c0 = clock64(), w0 = wall_clock64();
+    v4i acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = v4i{0, 0, 0, 0};
+    v4i a[4], b[4];
+    probe_operands(pattern, a, b);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i * 4 + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[i * 4 + j], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+    if (s == 0x12345678) sink[threadIdx.x] = s;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        clocks[0] = clock64() - c0;
+        clocks[1] = wall_clock64() - w0;
+    }
+}
+
+// Register-only issue loop: 16 independent INT8 MFMAs per iteration (SHAPE 0: 32x32x32, 16 result
+// registers each, 32768 multiply-adds; SHAPE 2: the older 16x16x32, 64 instructions of 8192 multiply-adds
+// per iteration), one workgroup of four wavefronts per CU (one wavefront per SIMD).
+// pattern 0: all-zero operands, 1: random bytes, 2: random 7-bit magnitudes with random sign
+// (sign-magnitude values in [-127, 127], the value distribution of Ozaki slices beyond the first),
+// 3: random signed 3-bit magnitudes, 4: random 7-bit magnitudes without sign, 5: A as 2 and every
+// byte of B equal to 1, 6: A as 2 and B zero.
+template <int SHAPE>
+__global__ __launch_bounds__(256) void mfma_rate_kernel(int pattern, int iters, int* sink, long long* clocks) {
+    const long long c0 = clock64(), w0 = wall_clock64();
+    v16i acc[16];
+    v4i acc4[32];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc4[i][r] = 0;
+    v4i a[4], b[4];
+    probe_operands(pattern, a, b);
     for (int it = 0; it < iters; ++it) {
         if (SHAPE == 0) {
 #pragma unroll
@@ -78,14 +108,6 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int pattern, int iters, 
                         const long b8 = (long)(((unsigned long)(unsigned)b[j][1] << 32) | (unsigned)b[j][0]);
                         acc4[(h & 1) * 16 + i * 4 + j] = __builtin_amdgcn_mfma_i32_16x16x32_i8(a8, b8, acc4[(h & 1) * 16 + i * 4 + j], 0, 0, 0);
                     }
-        } else {   // the same number of multiply-adds per iteration: 32 instructions of half the size
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc4[h * 16 + i * 4 + j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc4[h * 16 + i * 4 + j], 0, 0, 0);
         }
     }
     int s = 0;
@@ -125,9 +147,10 @@ ozimmu_status_t ozimmu_probe_int8_mfma(int pattern, int shape, int iters, double
               hipMalloc(&sink, 4096) == hipSuccess && hipHostMalloc(&clocks, 64) == hipSuccess &&
               hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess;
     float ms = 0.f;
+    const int waves = shape == 1 ? 16 : 4;   // per CU
     auto launch = [&](int n) {
         if (shape == 0) mfma_rate_kernel<0><<<dim3(cus), dim3(256)>>>(pattern, n, sink, clocks);
-        else if (shape == 1) mfma_rate_kernel<1><<<dim3(cus), dim3(256)>>>(pattern, n, sink, clocks);
+        else if (shape == 1) mfma_rate_small_kernel<<<dim3(cus), dim3(1024)>>>(pattern, n, sink, clocks);
         else mfma_rate_kernel<2><<<dim3(cus), dim3(256)>>>(pattern, n, sink, clocks);
     };
     if (ok) {
@@ -138,7 +161,8 @@ ozimmu_status_t ozimmu_probe_int8_mfma(int pattern, int shape, int iters, double
              hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
     }
     if (ok && ms > 0.f) {
-        *tera_ops_per_s = (double)cus * 4.0 * iters * 16.0 * 65536.0 / (ms * 1e-3) / 1e12;
+        const double ops_per_iteration = shape == 1 ? 16.0 * 32768.0 : 16.0 * 65536.0;   // per wavefront
+        *tera_ops_per_s = (double)cus * waves * iters * ops_per_iteration / (ms * 1e-3) / 1e12;
         *shader_mhz = clocks[1] > 0 ? (double)clocks[0] / (double)clocks[1] * 100.0 : 0.0;  // wall clock: 100 MHz
     }
     if (e0) (void)hipEventDestroy(e0);
